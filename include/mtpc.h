@@ -1,0 +1,146 @@
+/* mtpc.h - C ABI of libmtpc: the MtPC head (multi-token-prediction probabilistic
+ * circuit head of a byte-level LLM) on one AMD MI355X (gfx950).
+ *
+ * For every position b the head maps a hidden vector h[b] (e_t in the paper) to
+ * a joint distribution over the next n tokens, encoded by a probabilistic
+ * circuit whose parameters are computed from h[b] (Sec. 3.3):
+ *   input units   phi[b,i,j,:] = softmax(W[i,j] h[b])        W: [n][r][v][d]
+ *   root weights  omega[b,:]   = softmax(Wsum h[b])          Wsum: [r][d]
+ *   r x r sum layers (HMM transitions, binary-tree inner nodes): softmax over
+ *   the last axis of caller-supplied logits (mtpc_sumlayers).
+ * Circuit families (Sec. 2 and 3.2): fully factorised (Eq. FF, r must be 1),
+ * CP mixture (Eq. CP), HMM (Eq. HMM), binary tree (Eq. BTree, n a power of two).
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *    allocates nothing, keeps no state between calls and never synchronises.
+ *    Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream); buffers must stay alive until that work has completed.
+ *  - Row-major, innermost axis contiguous.  h, W, Wsum share `dtype`
+ *    (fp32, or bf16 with fp32 accumulation); all results are fp32 / int32.
+ *  - h, W, Wsum and workspace must be 16-byte aligned; ld_h (row stride of h in
+ *    elements) must keep rows 16-byte aligned.
+ *  - Supported sizes: 1 <= B; d a multiple of 32; 1 <= n <= 64; 1 <= r <= 128;
+ *    1 <= v <= 320.  Anything else returns MTPC_ERR_UNSUPPORTED.
+ *  - On any error nothing is launched and outputs are untouched.  Outputs are
+ *    fully overwritten on success.
+ *  - targets: int32, -1 marks a variable that is summed out (App. B.1: its input
+ *    units integrate to 1); any other id outside [0, v) makes that row's outputs NaN.
+ */
+#ifndef MTPC_H
+#define MTPC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MTPC_OK = 0,
+  MTPC_ERR_NULL = 1,        /* a required pointer is NULL                     */
+  MTPC_ERR_SHAPE = 2,       /* a size is non-positive or inconsistent         */
+  MTPC_ERR_UNSUPPORTED = 3, /* outside the supported ranges listed above      */
+  MTPC_ERR_WORKSPACE = 4,   /* workspace too small or misaligned              */
+  MTPC_ERR_HIP = 5          /* a HIP launch reported an error                 */
+} mtpc_status;
+
+typedef enum { MTPC_F32 = 0, MTPC_BF16 = 1 } mtpc_dtype;
+typedef enum { MTPC_FF = 0, MTPC_CP = 1, MTPC_HMM = 2, MTPC_BTREE = 3 } mtpc_family;
+typedef enum { MTPC_OP_LOGLIK = 0, MTPC_OP_MARGINALS = 1, MTPC_OP_SAMPLE = 2 } mtpc_op;
+typedef enum { MTPC_MARG_PREFIX = 0, MTPC_MARG_UNIVARIATE = 1 } mtpc_marg_mode;
+
+/* Common description of one call (Sec. 3.3). */
+typedef struct {
+  int32_t B, d, n, r, v;  /* positions, hidden size, window, units per layer, vocabulary */
+  int32_t dtype;          /* mtpc_dtype of h, W, Wsum                                     */
+  const void* h;          /* [B][ld_h] hidden states, first d entries of a row are used   */
+  int64_t ld_h;           /* row stride of h in elements, >= d                            */
+  const void* W;          /* [n][r][v][d] unembedding tensor                              */
+  const void* Wsum;       /* [r][d] root mixture (CP, BTree) / initial state (HMM); NULL for FF */
+  void* workspace;        /* device scratch, >= mtpc_workspace_bytes(...)                 */
+  size_t workspace_bytes;
+  void* stream;           /* hipStream_t                                                  */
+} mtpc_head;
+
+/* r x r sum layers as PRE-softmax fp32 logits, normalised over the LAST axis.
+ * HMM (Eq. HMM): L = n-1 transitions, logits[l][j][j'] scores z_{l+2}=j' given
+ * z_{l+1}=j.  BTree (Eq. BTree): L = n-2, layer m-1 belongs to the inner node
+ * with heap index m >= 1 (root 0, children 2m+1 / 2m+2, the leaf of token i at
+ * n-1+i), logits[m-1][k][j] scores z_m=j given the parent's latent k.  A leaf's
+ * r input units are indexed by its parent's latent; the root uses omega.
+ * -inf logits are allowed (zero weight) as long as each row keeps one finite entry. */
+typedef struct {
+  const float* logits;
+  int64_t layer_stride;   /* r*r, or 0: one matrix shared by all L layers (homogeneous)   */
+  int64_t batch_stride;   /* 0: shared by all positions; else elements between positions  */
+} mtpc_sumlayers;
+
+const char* mtpc_status_string(mtpc_status s);
+
+/* Scratch needed by one call.  `layers` may be NULL (FF, CP).  `S` is the number
+ * of drafts per position (sample) and is ignored otherwise; `mode` is the
+ * mtpc_marg_mode for MTPC_OP_MARGINALS.  Returns 0 for invalid arguments. */
+size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
+                            const mtpc_sumlayers* layers, int32_t S, int32_t mode);
+
+/* Exact log-likelihood log q(x_1..x_n | context) of each position's target
+ * window (Eqs. FF / CP / HMM / BTree; the circuit is normalised by
+ * construction, App. B.1).  targets [B][n] int32 -> loglik [B] fp32. */
+mtpc_status mtpc_ff_loglik(const mtpc_head* head, const int32_t* targets, float* loglik);
+mtpc_status mtpc_cp_loglik(const mtpc_head* head, const int32_t* targets, float* loglik);
+mtpc_status mtpc_hmm_loglik(const mtpc_head* head, const mtpc_sumlayers* T,
+                            const int32_t* targets, float* loglik);
+mtpc_status mtpc_btree_loglik(const mtpc_head* head, const mtpc_sumlayers* A,
+                              const int32_t* targets, float* loglik);
+
+/* Marginals (App. B.1: any subset of variables can be summed out exactly).
+ * MTPC_MARG_PREFIX (Alg. 2, prefix marginals used by the accept test):
+ *   out [B][n], out[b][i] = log q(x_1..x_{i+1}); out[b][n-1] is the log-likelihood.
+ * MTPC_MARG_UNIVARIATE: out [B][n][v], out[b][i][a] = log q(x_{i+1} = a);
+ *   targets is ignored and may be NULL. */
+mtpc_status mtpc_ff_marginals(const mtpc_head* head, const int32_t* targets, int32_t mode, float* out);
+mtpc_status mtpc_cp_marginals(const mtpc_head* head, const int32_t* targets, int32_t mode, float* out);
+mtpc_status mtpc_hmm_marginals(const mtpc_head* head, const mtpc_sumlayers* T,
+                               const int32_t* targets, int32_t mode, float* out);
+mtpc_status mtpc_btree_marginals(const mtpc_head* head, const mtpc_sumlayers* A,
+                                 const int32_t* targets, int32_t mode, float* out);
+
+/* Ancestral sampling (Alg. 1): S drafts per position.  Latents are drawn top
+ * down from the sum-unit weights, then token i from the input unit selected by
+ * the latent that indexes leaf i.  Every draw is an inverse-CDF search (smallest
+ * k with u < p_0+..+p_k) on a uniform from Philox4x32-10 with key = (seed low,
+ * seed high) and counter = (slot / 4, b, s, offset), output word slot % 4,
+ * u = (word >> 8) * 2^-24.  Slots: token i -> i; latent l -> n + l with l = 0 for
+ * the CP component, l = i for the HMM state z_{i+1}, l = m for the BTree node m.
+ *   drafts      [B][S][n] int32 (required)
+ *   latents     [B][S][n_lat] int32 or NULL; n_lat = 0 (FF), 1 (CP), n (HMM), n-1 (BTree)
+ *   prefix_logq [B][S][n] fp32 or NULL: prefix marginals of each draft (as
+ *               MTPC_MARG_PREFIX with the draft as target). */
+mtpc_status mtpc_ff_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,
+                           int32_t* drafts, int32_t* latents, float* prefix_logq);
+mtpc_status mtpc_cp_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,
+                           int32_t* drafts, int32_t* latents, float* prefix_logq);
+mtpc_status mtpc_hmm_sample(const mtpc_head* head, const mtpc_sumlayers* T, int32_t S,
+                            uint64_t seed, uint32_t offset,
+                            int32_t* drafts, int32_t* latents, float* prefix_logq);
+mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, int32_t S,
+                              uint64_t seed, uint32_t offset,
+                              int32_t* drafts, int32_t* latents, float* prefix_logq);
+
+/* The uniforms the sampler consumes, out [B][S][slots] fp32 (device), for tests
+ * of the generator and its slot map. */
+mtpc_status mtpc_philox_uniforms(int32_t B, int32_t S, int32_t slots, uint64_t seed,
+                                 uint32_t offset, float* out, void* stream);
+
+/* Profiling aid (the only state the library keeps, per host thread): while both
+ * events (hipEvent_t passed as void*) are non-NULL, every call made by this
+ * thread records `start` right before and `stop` right after its unembedding
+ * kernel launch(es) on the call's stream.  Pass NULLs to switch it off. */
+void mtpc_profile_unembed(void* start_event, void* stop_event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTPC_H */

@@ -1,0 +1,204 @@
+"""Thin ctypes binding of libmtpc (include/mtpc.h): argument marshalling only.
+
+Every step of the head runs in the HIP library; PyTorch is used for device
+buffers and the current stream.  There is no CPU fallback: if the shared library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmtpc.so")
+
+FF, CP, HMM, BTREE = 0, 1, 2, 3
+FAMILY = {"ff": FF, "cp": CP, "hmm": HMM, "btree": BTREE}
+OP_LOGLIK, OP_MARGINALS, OP_SAMPLE = 0, 1, 2
+MARG_PREFIX, MARG_UNIVARIATE = 0, 1
+F32, BF16 = 0, 1
+
+
+class MtpcError(RuntimeError):
+    pass
+
+
+class mtpc_head(C.Structure):
+    _fields_ = [("B", C.c_int32), ("d", C.c_int32), ("n", C.c_int32), ("r", C.c_int32),
+                ("v", C.c_int32), ("dtype", C.c_int32),
+                ("h", C.c_void_p), ("ld_h", C.c_int64), ("W", C.c_void_p), ("Wsum", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
+
+
+class mtpc_sumlayers(C.Structure):
+    _fields_ = [("logits", C.c_void_p), ("layer_stride", C.c_int64), ("batch_stride", C.c_int64)]
+
+
+EXPORTS = [
+    "mtpc_status_string", "mtpc_workspace_bytes",
+    "mtpc_ff_loglik", "mtpc_cp_loglik", "mtpc_hmm_loglik", "mtpc_btree_loglik",
+    "mtpc_ff_marginals", "mtpc_cp_marginals", "mtpc_hmm_marginals", "mtpc_btree_marginals",
+    "mtpc_ff_sample", "mtpc_cp_sample", "mtpc_hmm_sample", "mtpc_btree_sample",
+    "mtpc_philox_uniforms", "mtpc_profile_unembed",
+]
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libmtpc.so (built by __graft_entry__.build()); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise MtpcError(f"{LIB_PATH} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = C.CDLL(LIB_PATH)
+        hp, lp, ip, fp = C.POINTER(mtpc_head), C.POINTER(mtpc_sumlayers), C.c_void_p, C.c_void_p
+        L.mtpc_status_string.restype = C.c_char_p
+        L.mtpc_status_string.argtypes = [C.c_int]
+        L.mtpc_workspace_bytes.restype = C.c_size_t
+        L.mtpc_workspace_bytes.argtypes = [C.c_int32, C.c_int32, hp, lp, C.c_int32, C.c_int32]
+        for fam in ("ff", "cp"):
+            getattr(L, f"mtpc_{fam}_loglik").argtypes = [hp, ip, fp]
+            getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, ip, C.c_int32, fp]
+            getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp]
+        for fam in ("hmm", "btree"):
+            getattr(L, f"mtpc_{fam}_loglik").argtypes = [hp, lp, ip, fp]
+            getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, lp, ip, C.c_int32, fp]
+            getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, lp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp]
+        L.mtpc_philox_uniforms.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
+                                           fp, C.c_void_p]
+        L.mtpc_profile_unembed.argtypes = [C.c_void_p, C.c_void_p]
+        L.mtpc_profile_unembed.restype = None
+        for name in EXPORTS:
+            if name not in ("mtpc_status_string", "mtpc_workspace_bytes", "mtpc_profile_unembed"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise MtpcError(f"libmtpc: {lib().mtpc_status_string(status).decode()} (status {status})")
+
+
+def n_latents(family: str, n: int) -> int:
+    return {"ff": 0, "cp": 1, "hmm": n, "btree": n - 1}[family]
+
+
+class Head:
+    """Device-resident parameters of one head plus a reusable workspace."""
+
+    def __init__(self, family: str, h: torch.Tensor, W: torch.Tensor, Wsum: Optional[torch.Tensor] = None,
+                 layers: Optional[torch.Tensor] = None):
+        assert family in FAMILY
+        assert h.is_cuda and W.is_cuda and h.dim() == 2 and W.dim() == 4
+        assert h.dtype == W.dtype and h.dtype in (torch.float32, torch.bfloat16)
+        assert h.stride(1) == 1 and W.is_contiguous()
+        self.family = family
+        self.h, self.W, self.Wsum = h, W, Wsum
+        self.B, self.d = h.shape
+        self.n, self.r, self.v, d2 = W.shape
+        assert d2 == self.d
+        if Wsum is not None:
+            assert Wsum.is_cuda and Wsum.is_contiguous() and Wsum.dtype == h.dtype and tuple(Wsum.shape) == (self.r, self.d)
+        self.layers = layers
+        self._sl = None
+        if layers is not None:
+            assert layers.is_cuda and layers.dtype == torch.float32 and layers.is_contiguous()
+            need = self.n - 1 if family == "hmm" else self.n - 2
+            if layers.dim() == 3:          # [L, r, r], L == need or 1 (homogeneous)
+                L, bs = layers.shape[0], 0
+            else:                          # [B, L, r, r] contextual
+                assert layers.shape[0] == self.B
+                L, bs = layers.shape[1], layers.shape[1] * self.r * self.r
+            assert L in (need, 1) and tuple(layers.shape[-2:]) == (self.r, self.r)
+            ls = self.r * self.r if (L == need and need > 0) else 0
+            if L == 1 and need > 1:
+                ls = 0
+            self._sl = mtpc_sumlayers(layers.data_ptr(), ls, bs)
+        self._ws = None
+
+    # ---- plumbing --------------------------------------------------------
+    def _head(self, ws_bytes: int) -> mtpc_head:
+        if self._ws is None or self._ws.numel() < ws_bytes:
+            self._ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=self.h.device)
+        hd = mtpc_head()
+        hd.B, hd.d, hd.n, hd.r, hd.v = self.B, self.d, self.n, self.r, self.v
+        hd.dtype = BF16 if self.h.dtype == torch.bfloat16 else F32
+        hd.h, hd.ld_h = self.h.data_ptr(), self.h.stride(0)
+        hd.W = self.W.data_ptr()
+        hd.Wsum = self.Wsum.data_ptr() if self.Wsum is not None else None
+        hd.workspace, hd.workspace_bytes = self._ws.data_ptr(), self._ws.numel()
+        hd.stream = torch.cuda.current_stream(self.h.device).cuda_stream
+        return hd
+
+    def _layers_ref(self):
+        return C.byref(self._sl) if self._sl is not None else None
+
+    def workspace_bytes(self, op: int, S: int = 1, mode: int = 0) -> int:
+        probe = mtpc_head()
+        probe.B, probe.d, probe.n, probe.r, probe.v = self.B, self.d, self.n, self.r, self.v
+        return lib().mtpc_workspace_bytes(FAMILY[self.family], op, C.byref(probe), self._layers_ref(), S, mode)
+
+    def _call(self, name, hd, *args):
+        fn = getattr(lib(), f"mtpc_{self.family}_{name}")
+        if self.family in ("hmm", "btree"):
+            return fn(C.byref(hd), self._layers_ref(), *args)
+        return fn(C.byref(hd), *args)
+
+    # ---- operations ------------------------------------------------------
+    def loglik(self, targets: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        assert targets.is_cuda and targets.dtype == torch.int32 and targets.is_contiguous()
+        assert tuple(targets.shape) == (self.B, self.n)
+        if out is None:
+            out = torch.empty(self.B, dtype=torch.float32, device=self.h.device)
+        hd = self._head(self.workspace_bytes(OP_LOGLIK))
+        _check(self._call("loglik", hd, targets.data_ptr(), out.data_ptr()))
+        return out
+
+    def prefix_marginals(self, targets: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        assert targets.is_cuda and targets.dtype == torch.int32 and targets.is_contiguous()
+        assert tuple(targets.shape) == (self.B, self.n)
+        if out is None:
+            out = torch.empty(self.B, self.n, dtype=torch.float32, device=self.h.device)
+        hd = self._head(self.workspace_bytes(OP_MARGINALS, mode=MARG_PREFIX))
+        _check(self._call("marginals", hd, targets.data_ptr(), MARG_PREFIX, out.data_ptr()))
+        return out
+
+    def univariate_marginals(self, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty(self.B, self.n, self.v, dtype=torch.float32, device=self.h.device)
+        hd = self._head(self.workspace_bytes(OP_MARGINALS, mode=MARG_UNIVARIATE))
+        _check(self._call("marginals", hd, None, MARG_UNIVARIATE, out.data_ptr()))
+        return out
+
+    def sample(self, S: int, seed: int, offset: int = 0, want_latents: bool = True,
+               want_prefix: bool = False, out=None):
+        """Returns (drafts [B,S,n] int32, latents [B,S,n_lat] int32 or None, prefix_logq [B,S,n] or None)."""
+        dev = self.h.device
+        if out is None:
+            drafts = torch.empty(self.B, S, self.n, dtype=torch.int32, device=dev)
+            nl = n_latents(self.family, self.n)
+            lat = torch.empty(self.B, S, nl, dtype=torch.int32, device=dev) if want_latents else None
+            pl = torch.empty(self.B, S, self.n, dtype=torch.float32, device=dev) if want_prefix else None
+        else:
+            drafts, lat, pl = out
+        hd = self._head(self.workspace_bytes(OP_SAMPLE, S=S))
+        _check(self._call("sample", hd, S, seed, offset, drafts.data_ptr(),
+                          lat.data_ptr() if lat is not None and lat.numel() > 0 else None,
+                          pl.data_ptr() if pl is not None else None))
+        return drafts, lat, pl
+
+
+def philox_uniforms(B: int, S: int, slots: int, seed: int, offset: int = 0, device="cuda") -> torch.Tensor:
+    out = torch.empty(B, S, slots, dtype=torch.float32, device=device)
+    st = torch.cuda.current_stream(out.device).cuda_stream
+    _check(lib().mtpc_philox_uniforms(B, S, slots, seed, offset, out.data_ptr(), st))
+    return out
+
+
+def profile_unembed(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    lib().mtpc_profile_unembed(start_event, stop_event)

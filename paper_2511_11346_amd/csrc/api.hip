@@ -1,0 +1,356 @@
+// C ABI of libmtpc (include/mtpc.h): argument validation, workspace carve-up and
+// the launch sequence of each operation.  Host code only.
+#include <cstring>
+
+#include "mtpc_internal.h"
+
+namespace mtpc {
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Events { void* start; void* stop; };
+thread_local Events g_prof = {nullptr, nullptr};
+
+int n_latents(int family, int n) {
+  switch (family) {
+    case MTPC_FF: return 0;
+    case MTPC_CP: return 1;
+    case MTPC_HMM: return n;
+    default: return n - 1;
+  }
+}
+int n_layers(int family, int n) {
+  if (family == MTPC_HMM) return n - 1;
+  if (family == MTPC_BTREE) return n - 2;
+  return 0;
+}
+
+// Drafts are scored by re-reading single rows of W when there are few of them
+// (B*S rows of length d per slab instead of all v), else by a second fused pass.
+bool score_by_gather(const mtpc_head* hd, int S) { return (long long)hd->B * S * 4 <= hd->v; }
+
+struct Plan {           // byte offsets into the workspace
+  size_t logw, lay_nat, lay_circ, e, lse, zleaf, lat, logm, total;
+  int nb, Lst;          // position blocks and stored layers of the normalised copies
+};
+
+mtpc_status check_head(int family, const mtpc_head* hd) {
+  if (!hd) return MTPC_ERR_NULL;
+  if (!hd->h || !hd->W) return MTPC_ERR_NULL;
+  if (family != MTPC_FF && !hd->Wsum) return MTPC_ERR_NULL;
+  if (hd->B < 1 || hd->d < 1 || hd->n < 1 || hd->r < 1 || hd->v < 1) return MTPC_ERR_SHAPE;
+  if (hd->ld_h < hd->d) return MTPC_ERR_SHAPE;
+  if (family == MTPC_FF && hd->r != 1) return MTPC_ERR_SHAPE;
+  if (hd->dtype != MTPC_F32 && hd->dtype != MTPC_BF16) return MTPC_ERR_UNSUPPORTED;
+  if (hd->d % 32 != 0 || hd->n > 64 || hd->r > 128 || hd->v > 320) return MTPC_ERR_UNSUPPORTED;
+  if (family == MTPC_BTREE && (hd->n < 2 || (hd->n & (hd->n - 1)) != 0)) return MTPC_ERR_UNSUPPORTED;
+  const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
+  if (((uintptr_t)hd->h | (uintptr_t)hd->W | (uintptr_t)hd->Wsum) & 15) return MTPC_ERR_UNSUPPORTED;
+  if (((size_t)hd->ld_h * esz) & 15) return MTPC_ERR_UNSUPPORTED;
+  if ((long long)hd->n * hd->r * hd->v > 0x7fffffffLL) return MTPC_ERR_UNSUPPORTED;
+  return MTPC_OK;
+}
+
+mtpc_status check_layers(int family, const mtpc_head* hd, const mtpc_sumlayers* ly) {
+  if (n_layers(family, hd->n) <= 0) return MTPC_OK;
+  if (!ly || !ly->logits) return MTPC_ERR_NULL;
+  const long long rr = (long long)hd->r * hd->r;
+  if (ly->layer_stride != 0 && ly->layer_stride < rr) return MTPC_ERR_SHAPE;
+  if (ly->batch_stride < 0) return MTPC_ERR_SHAPE;
+  return MTPC_OK;
+}
+
+Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly, int S, int mode,
+               bool want_prefix) {
+  Plan p{};
+  const size_t B = hd->B, n = hd->n, r = hd->r;
+  const int L = n_layers(family, hd->n);
+  p.Lst = (L > 0 && ly && ly->layer_stride == 0) ? 1 : L;
+  p.nb = (L > 0 && ly && ly->batch_stride != 0) ? hd->B : 1;
+  const size_t lay_bytes = L > 0 ? up((size_t)p.nb * p.Lst * r * r * 4) : 0;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
+  p.logw = take(B * r * 4);
+  const bool sample = op == MTPC_OP_SAMPLE;
+  const bool uni = op == MTPC_OP_MARGINALS && mode == MTPC_MARG_UNIVARIATE;
+  const bool need_nat = L > 0 && (family == MTPC_HMM || sample || uni);
+  const bool need_tr = L > 0 && family == MTPC_BTREE && (!sample || want_prefix) && !uni;
+  p.lay_nat = need_nat ? take(lay_bytes) : 0;
+  p.lay_circ = need_tr ? take(lay_bytes) : p.lay_nat;
+  const size_t rows = sample ? B * (size_t)S : B;
+  p.e = (uni || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
+  p.lse = (sample && want_prefix) ? take(B * n * r * 4) : 0;
+  p.zleaf = sample ? take(B * (size_t)S * n * 4) : 0;
+  p.lat = sample ? take(B * (size_t)S * (size_t)(n_latents(family, hd->n) + 1) * 4) : 0;
+  p.logm = uni ? take(B * n * r * 4) : 0;
+  p.total = off;
+  return p;
+}
+
+struct ProfScope {
+  hipStream_t st;
+  explicit ProfScope(hipStream_t s) : st(s) {
+    if (g_prof.start && g_prof.stop) (void)hipEventRecord((hipEvent_t)g_prof.start, st);
+  }
+  ~ProfScope() {
+    if (g_prof.start && g_prof.stop) (void)hipEventRecord((hipEvent_t)g_prof.stop, st);
+  }
+};
+
+#define HIP_TRY(x) do { if ((x) != hipSuccess) return MTPC_ERR_HIP; } while (0)
+
+mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly, int S, int mode,
+                    bool want_prefix, Plan& plan) {
+  mtpc_status st = check_head(family, hd);
+  if (st != MTPC_OK) return st;
+  st = check_layers(family, hd, ly);
+  if (st != MTPC_OK) return st;
+  if (op == MTPC_OP_SAMPLE && S < 1) return MTPC_ERR_SHAPE;
+  plan = make_plan(family, op, hd, ly, S, mode, want_prefix);
+  if (!hd->workspace) return MTPC_ERR_NULL;
+  if (((uintptr_t)hd->workspace & 15) || hd->workspace_bytes < plan.total) return MTPC_ERR_WORKSPACE;
+  return MTPC_OK;
+}
+
+// sum-unit parameters shared by all ops
+mtpc_status launch_params(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const Plan& p,
+                          bool nat, bool circ, hipStream_t st) {
+  char* ws = (char*)hd->workspace;
+  if (family != MTPC_FF)
+    HIP_TRY(launch_sumunit(hd->h, hd->ld_h, hd->Wsum, hd->B, hd->d, hd->r, hd->dtype,
+                           (float*)(ws + p.logw), st));
+  const int L = n_layers(family, hd->n);
+  if (L > 0) {
+    if (nat)
+      HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, p.nb, p.Lst,
+                                      hd->r, 0, (float*)(ws + p.lay_nat), st));
+    if (circ && family == MTPC_BTREE)
+      HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, p.nb, p.Lst,
+                                      hd->r, 1, (float*)(ws + p.lay_circ), st));
+  }
+  return MTPC_OK;
+}
+
+CircuitArgs circuit_args(int family, const mtpc_head* hd, const Plan& p, int rows, int T, float* out,
+                         int prefix) {
+  char* ws = (char*)hd->workspace;
+  CircuitArgs c{};
+  c.family = family; c.rows = rows; c.T = T; c.n = hd->n; c.r = hd->r;
+  c.e = (const float*)(ws + p.e);
+  c.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
+  c.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_circ) : nullptr;
+  c.L = p.Lst; c.contextual = p.nb > 1; c.out = out; c.prefix = prefix;
+  return c;
+}
+
+// loglik and prefix marginals: params -> fused unembedding (evidence) -> circuit
+mtpc_status run_evidence_op(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
+                            const int32_t* targets, float* out, int prefix) {
+  if (!targets || !out) return MTPC_ERR_NULL;
+  Plan p;
+  mtpc_status s = prepare(family, prefix ? MTPC_OP_MARGINALS : MTPC_OP_LOGLIK, hd, ly, 1,
+                          MTPC_MARG_PREFIX, false, p);
+  if (s != MTPC_OK) return s;
+  hipStream_t st = (hipStream_t)hd->stream;
+  char* ws = (char*)hd->workspace;
+  s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
+  if (s != MTPC_OK) return s;
+  UnembedArgs u{};
+  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
+  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  u.targets = targets; u.T = 1; u.e = (float*)(ws + p.e);
+  {
+    ProfScope prof(st);
+    HIP_TRY(launch_unembed(u, hd->dtype, st));
+  }
+  HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B, 1, out, prefix), st));
+  return MTPC_OK;
+}
+
+mtpc_status run_univariate(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, float* out) {
+  if (!out) return MTPC_ERR_NULL;
+  Plan p;
+  mtpc_status s = prepare(family, MTPC_OP_MARGINALS, hd, ly, 1, MTPC_MARG_UNIVARIATE, false, p);
+  if (s != MTPC_OK) return s;
+  hipStream_t st = (hipStream_t)hd->stream;
+  char* ws = (char*)hd->workspace;
+  s = launch_params(family, hd, ly, p, true, false, st);
+  if (s != MTPC_OK) return s;
+  UnivariateArgs u{};
+  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
+  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  u.out = out;
+  if (family != MTPC_FF) {
+    LatentMarginalArgs m{};
+    m.family = family; m.B = hd->B; m.n = hd->n; m.r = hd->r;
+    m.logw = (const float*)(ws + p.logw);
+    m.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
+    m.L = p.Lst; m.contextual = p.nb > 1;
+    m.logm = (float*)(ws + p.logm);
+    HIP_TRY(launch_latent_marginals(m, st));
+    u.logm = m.logm;
+  }
+  {
+    ProfScope prof(st);
+    HIP_TRY(launch_univariate(u, hd->dtype, st));
+  }
+  return MTPC_OK;
+}
+
+mtpc_status run_marginals(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
+                          const int32_t* targets, int32_t mode, float* out) {
+  if (mode == MTPC_MARG_PREFIX) return run_evidence_op(family, hd, ly, targets, out, 1);
+  if (mode == MTPC_MARG_UNIVARIATE) return run_univariate(family, hd, ly, out);
+  return MTPC_ERR_UNSUPPORTED;
+}
+
+mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, int32_t S,
+                       uint64_t seed, uint32_t offset, int32_t* drafts, int32_t* latents,
+                       float* prefix_logq) {
+  if (!drafts) return MTPC_ERR_NULL;
+  const bool want_prefix = prefix_logq != nullptr;
+  Plan p;
+  mtpc_status s = prepare(family, MTPC_OP_SAMPLE, hd, ly, S, 0, want_prefix, p);
+  if (s != MTPC_OK) return s;
+  if ((long long)hd->B * S > 0x7fffffffLL / hd->n) return MTPC_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)hd->stream;
+  char* ws = (char*)hd->workspace;
+  s = launch_params(family, hd, ly, p, true, want_prefix, st);
+  if (s != MTPC_OK) return s;
+  const uint32_t seed_lo = (uint32_t)(seed & 0xffffffffu), seed_hi = (uint32_t)(seed >> 32);
+
+  LatentArgs la{};
+  la.family = family; la.B = hd->B; la.S = S; la.n = hd->n; la.r = hd->r;
+  la.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
+  la.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
+  la.L = p.Lst; la.contextual = p.nb > 1;
+  la.seed_lo = seed_lo; la.seed_hi = seed_hi; la.offset = offset;
+  la.zleaf = (int*)(ws + p.zleaf);
+  la.latents = latents ? latents : (int*)(ws + p.lat);
+  HIP_TRY(launch_latents(la, st));
+
+  UnembedArgs u{};
+  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
+  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
+  u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset;
+  const bool gather = want_prefix && score_by_gather(hd, S);
+  if (gather) u.lse = (float*)(ws + p.lse);
+  {
+    ProfScope prof(st);
+    HIP_TRY(launch_unembed(u, hd->dtype, st));
+    if (want_prefix && !gather) {
+      UnembedArgs u2{};
+      u2.h = hd->h; u2.ld_h = hd->ld_h; u2.W = hd->W;
+      u2.B = hd->B; u2.d = hd->d; u2.v = hd->v; u2.n = hd->n; u2.r = hd->r;
+      u2.targets = drafts; u2.T = S; u2.e = (float*)(ws + p.e);
+      HIP_TRY(launch_unembed(u2, hd->dtype, st));
+    }
+  }
+  if (want_prefix) {
+    if (gather) {
+      GatherArgs g{};
+      g.h = hd->h; g.ld_h = hd->ld_h; g.W = hd->W;
+      g.B = hd->B; g.S = S; g.d = hd->d; g.v = hd->v; g.n = hd->n; g.r = hd->r;
+      g.x = drafts; g.lse = (const float*)(ws + p.lse); g.e = (float*)(ws + p.e);
+      HIP_TRY(launch_gather_evidence(g, hd->dtype, st));
+    }
+    HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * S, S, prefix_logq, 1), st));
+  }
+  return MTPC_OK;
+}
+
+}  // namespace
+}  // namespace mtpc
+
+using namespace mtpc;
+
+extern "C" {
+
+const char* mtpc_status_string(mtpc_status s) {
+  switch (s) {
+    case MTPC_OK: return "ok";
+    case MTPC_ERR_NULL: return "a required pointer is NULL";
+    case MTPC_ERR_SHAPE: return "a size is non-positive or inconsistent";
+    case MTPC_ERR_UNSUPPORTED: return "outside the supported sizes, dtypes or alignment";
+    case MTPC_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case MTPC_ERR_HIP: return "a HIP call failed";
+  }
+  return "unknown status";
+}
+
+size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
+                            const mtpc_sumlayers* layers, int32_t S, int32_t mode) {
+  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_SAMPLE) return 0;
+  if (!head || head->B < 1 || head->d < 1 || head->n < 1 || head->r < 1 || head->v < 1) return 0;
+  if (op == MTPC_OP_SAMPLE && S < 1) return 0;
+  // sized for the most demanding variant of the op (sample: with prefix scores)
+  Plan p = make_plan(family, op, head, layers, op == MTPC_OP_SAMPLE ? S : 1, mode, true);
+  return p.total;
+}
+
+mtpc_status mtpc_ff_loglik(const mtpc_head* head, const int32_t* targets, float* loglik) {
+  return run_evidence_op(MTPC_FF, head, nullptr, targets, loglik, 0);
+}
+mtpc_status mtpc_cp_loglik(const mtpc_head* head, const int32_t* targets, float* loglik) {
+  return run_evidence_op(MTPC_CP, head, nullptr, targets, loglik, 0);
+}
+mtpc_status mtpc_hmm_loglik(const mtpc_head* head, const mtpc_sumlayers* T, const int32_t* targets,
+                            float* loglik) {
+  return run_evidence_op(MTPC_HMM, head, T, targets, loglik, 0);
+}
+mtpc_status mtpc_btree_loglik(const mtpc_head* head, const mtpc_sumlayers* A, const int32_t* targets,
+                              float* loglik) {
+  return run_evidence_op(MTPC_BTREE, head, A, targets, loglik, 0);
+}
+
+mtpc_status mtpc_ff_marginals(const mtpc_head* head, const int32_t* targets, int32_t mode, float* out) {
+  return run_marginals(MTPC_FF, head, nullptr, targets, mode, out);
+}
+mtpc_status mtpc_cp_marginals(const mtpc_head* head, const int32_t* targets, int32_t mode, float* out) {
+  return run_marginals(MTPC_CP, head, nullptr, targets, mode, out);
+}
+mtpc_status mtpc_hmm_marginals(const mtpc_head* head, const mtpc_sumlayers* T, const int32_t* targets,
+                               int32_t mode, float* out) {
+  return run_marginals(MTPC_HMM, head, T, targets, mode, out);
+}
+mtpc_status mtpc_btree_marginals(const mtpc_head* head, const mtpc_sumlayers* A, const int32_t* targets,
+                                 int32_t mode, float* out) {
+  return run_marginals(MTPC_BTREE, head, A, targets, mode, out);
+}
+
+mtpc_status mtpc_ff_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,
+                           int32_t* drafts, int32_t* latents, float* prefix_logq) {
+  return run_sample(MTPC_FF, head, nullptr, S, seed, offset, drafts, latents, prefix_logq);
+}
+mtpc_status mtpc_cp_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,
+                           int32_t* drafts, int32_t* latents, float* prefix_logq) {
+  return run_sample(MTPC_CP, head, nullptr, S, seed, offset, drafts, latents, prefix_logq);
+}
+mtpc_status mtpc_hmm_sample(const mtpc_head* head, const mtpc_sumlayers* T, int32_t S, uint64_t seed,
+                            uint32_t offset, int32_t* drafts, int32_t* latents, float* prefix_logq) {
+  return run_sample(MTPC_HMM, head, T, S, seed, offset, drafts, latents, prefix_logq);
+}
+mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, int32_t S, uint64_t seed,
+                              uint32_t offset, int32_t* drafts, int32_t* latents, float* prefix_logq) {
+  return run_sample(MTPC_BTREE, head, A, S, seed, offset, drafts, latents, prefix_logq);
+}
+
+mtpc_status mtpc_philox_uniforms(int32_t B, int32_t S, int32_t slots, uint64_t seed, uint32_t offset,
+                                 float* out, void* stream) {
+  if (!out) return MTPC_ERR_NULL;
+  if (B < 1 || S < 1 || slots < 1) return MTPC_ERR_SHAPE;
+  if (launch_philox_uniforms(B, S, slots, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32),
+                             offset, out, (hipStream_t)stream) != hipSuccess)
+    return MTPC_ERR_HIP;
+  return MTPC_OK;
+}
+
+void mtpc_profile_unembed(void* start_event, void* stop_event) {
+  g_prof.start = start_event;
+  g_prof.stop = stop_event;
+}
+
+}  // extern "C"

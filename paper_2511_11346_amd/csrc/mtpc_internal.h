@@ -1,0 +1,136 @@
+// Internal declarations shared by the HIP translation units of libmtpc.
+// Not part of the public ABI (see include/mtpc.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mtpc.h"
+
+namespace mtpc {
+
+// Arguments of the fused unembedding kernel (Sec. 3.3: phi_ij = softmax(W_ij e_t)).
+// One workgroup owns ALL v logits of one (i, j) slab for a tile of positions, so
+// the softmax over the vocabulary finishes in registers and only O(B n r) values
+// are written.
+struct UnembedArgs {
+  const void* h;        // [B][ld_h]
+  long long ld_h;       // elements
+  const void* W;        // [n*r][v][d]
+  int B, d, v, n, r;
+  // evidence: e[(b*T+t)][i][j] = l[x] - LSE for target window t of position b
+  const int* targets;   // [B][T][n] or nullptr
+  int T;
+  float* e;             // [B*T][n][r]
+  float* lse;           // [B][n][r] or nullptr
+  // sampling: token i of draft (b, s) is drawn from slab (i, zleaf[b][s][i])
+  const int* zleaf;     // [B][S][n] or nullptr
+  int S;
+  int* drafts;          // [B][S][n]
+  uint32_t seed_lo, seed_hi, offset;
+};
+
+// Univariate marginals: M[b][i][a] = log sum_j m[b][i][j] phi[b][i][j][a].
+struct UnivariateArgs {
+  const void* h;
+  long long ld_h;
+  const void* W;
+  int B, d, v, n, r;
+  const float* logm;    // [B][n][r] log marginal of the latent indexing leaf i (nullptr: r == 1)
+  float* out;           // [B][n][v]
+};
+
+hipError_t launch_unembed(const UnembedArgs& a, int dtype, hipStream_t st);
+hipError_t launch_univariate(const UnivariateArgs& a, int dtype, hipStream_t st);
+
+// ---- small kernels (circuits.hip) -----------------------------------------
+// log omega[b][:] = log_softmax(Wsum h[b])
+hipError_t launch_sumunit(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
+                          int dtype, float* logw, hipStream_t st);
+// softmax over the last axis of r x r logits -> linear probabilities.
+// in: logits[(b*bs) + l*ls + k*r + j]; out[((b*L + l)*r + k)*r + j] or transposed [j][k].
+hipError_t launch_normalise_layers(const float* logits, long long layer_stride, long long batch_stride,
+                                   int nb, int L, int r, int transpose, float* out, hipStream_t st);
+
+struct CircuitArgs {
+  int family;           // mtpc_family
+  int rows;             // B*T evidence rows
+  int T;                // rows per position (logw / contextual layers are indexed by row / T)
+  int n, r;
+  const float* e;       // [rows][n][r]
+  const float* logw;    // [B][r] (nullptr for FF)
+  const float* layers;  // normalised linear probabilities, HMM: [nb][L][j][j'], BTree: [nb][L][j][k] (transposed)
+  int L;                // number of stored layers (1 = homogeneous)
+  int contextual;       // 1: layers has a leading position axis
+  float* out;           // prefix ? [rows][n] : [rows]
+  int prefix;
+};
+hipError_t launch_circuit(const CircuitArgs& a, hipStream_t st);
+
+// latent draws of Alg. 1 (top-down over sum units)
+struct LatentArgs {
+  int family, B, S, n, r;
+  const float* logw;    // [B][r]
+  const float* layers;  // normalised linear, natural layout [nb][L][k][j]
+  int L, contextual;
+  uint32_t seed_lo, seed_hi, offset;
+  int* zleaf;           // [B][S][n] state that indexes leaf i
+  int* latents;         // [B][S][n_lat] or nullptr
+};
+hipError_t launch_latents(const LatentArgs& a, hipStream_t st);
+
+// log marginal of the latent that indexes each leaf: logm[b][i][j]
+struct LatentMarginalArgs {
+  int family, B, n, r;
+  const float* logw;
+  const float* layers;  // natural layout
+  int L, contextual;
+  float* logm;          // [B][n][r]
+};
+hipError_t launch_latent_marginals(const LatentMarginalArgs& a, hipStream_t st);
+
+// e[(b*S+s)][i][j] = <W[i][j][x], h[b]> - lse[b][i][j] with x = drafts[b][s][i]
+struct GatherArgs {
+  const void* h; long long ld_h; const void* W;
+  int B, S, d, v, n, r;
+  const int* x;         // [B][S][n]
+  const float* lse;     // [B][n][r]
+  float* e;             // [B*S][n][r]
+};
+hipError_t launch_gather_evidence(const GatherArgs& a, int dtype, hipStream_t st);
+
+hipError_t launch_philox_uniforms(int B, int S, int slots, uint32_t seed_lo, uint32_t seed_hi,
+                                  uint32_t offset, float* out, hipStream_t st);
+
+// ---- device helpers --------------------------------------------------------
+#if defined(__HIPCC__)
+// Philox4x32-10 (Salmon et al., SC'11): 10 rounds of two 32x32->64 multiplies.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4]) {
+  const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int rnd = 0; rnd < 10; ++rnd) {
+    if (rnd > 0) { k0 += W0; k1 += W1; }
+    uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Uniform of (position b, draft s, slot t): counter (t/4, b, s, offset), word t%4,
+// u = (word >> 8) * 2^-24 in [0, 1).
+__device__ __forceinline__ float philox_uniform(uint32_t seed_lo, uint32_t seed_hi, uint32_t offset,
+                                                uint32_t b, uint32_t s, uint32_t slot) {
+  uint32_t w[4];
+  philox4x32_10(slot >> 2, b, s, offset, seed_lo, seed_hi, w);
+  uint32_t sel = slot & 3u;
+  uint32_t word = sel == 0 ? w[0] : sel == 1 ? w[1] : sel == 2 ? w[2] : w[3];
+  return (float)(word >> 8) * 5.9604644775390625e-8f;
+}
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
+#endif
+
+}  // namespace mtpc

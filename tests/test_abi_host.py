@@ -1,0 +1,93 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before launching."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2511_11346_amd", "libmtpc.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libmtpc.so not built")
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mtpc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mtpc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    from paper_2511_11346_amd import binding
+    names = declared_symbols()
+    assert len(names) == 16 and sorted(binding.EXPORTS) == names
+    L = C.CDLL(LIB)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    from paper_2511_11346_amd import binding
+    L = binding.lib()
+    assert L.mtpc_status_string(0) == b"ok"
+    assert len({L.mtpc_status_string(i) for i in range(6)}) == 6
+
+
+def _head(**kw):
+    from paper_2511_11346_amd.binding import mtpc_head
+    hd = mtpc_head()
+    hd.B, hd.d, hd.n, hd.r, hd.v, hd.dtype = 4, 64, 4, 2, 16, 1
+    hd.h, hd.ld_h, hd.W, hd.Wsum = 0x1000, 64, 0x2000, 0x3000
+    hd.workspace, hd.workspace_bytes = 0x10000, 1 << 30
+    for k, v in kw.items():
+        setattr(hd, k, v)
+    return hd
+
+
+def test_argument_errors_are_reported_without_launching():
+    from paper_2511_11346_amd import binding
+    L = binding.lib()
+    tg, out = C.c_void_p(0x4000), C.c_void_p(0x5000)
+    NULL, SHAPE, UNSUP, WS = 1, 2, 3, 4
+    assert L.mtpc_cp_loglik(None, tg, out) == NULL
+    assert L.mtpc_cp_loglik(C.byref(_head()), None, out) == NULL
+    assert L.mtpc_cp_loglik(C.byref(_head(h=None)), tg, out) == NULL
+    assert L.mtpc_cp_loglik(C.byref(_head(Wsum=None)), tg, out) == NULL
+    assert L.mtpc_cp_loglik(C.byref(_head(B=0)), tg, out) == SHAPE
+    assert L.mtpc_cp_loglik(C.byref(_head(ld_h=32)), tg, out) == SHAPE
+    assert L.mtpc_ff_loglik(C.byref(_head(r=2)), tg, out) == SHAPE
+    assert L.mtpc_cp_loglik(C.byref(_head(d=48)), tg, out) == UNSUP
+    assert L.mtpc_cp_loglik(C.byref(_head(v=321)), tg, out) == UNSUP
+    assert L.mtpc_cp_loglik(C.byref(_head(r=129)), tg, out) == UNSUP
+    assert L.mtpc_cp_loglik(C.byref(_head(dtype=7)), tg, out) == UNSUP
+    assert L.mtpc_cp_loglik(C.byref(_head(h=0x1004)), tg, out) == UNSUP
+    assert L.mtpc_cp_loglik(C.byref(_head(workspace_bytes=16)), tg, out) == WS
+    assert L.mtpc_cp_loglik(C.byref(_head(workspace=None)), tg, out) == NULL
+    lay = binding.mtpc_sumlayers(0x6000, 4, 0)
+    assert L.mtpc_btree_loglik(C.byref(_head(n=6)), C.byref(lay), tg, out) == UNSUP
+    assert L.mtpc_hmm_loglik(C.byref(_head()), None, tg, out) == NULL
+    bad = binding.mtpc_sumlayers(0x6000, 3, 0)
+    assert L.mtpc_hmm_loglik(C.byref(_head()), C.byref(bad), tg, out) == SHAPE
+    assert L.mtpc_cp_marginals(C.byref(_head()), tg, 9, out) == UNSUP
+    assert L.mtpc_cp_sample(C.byref(_head()), 0, 1, 0, out, None, None) == SHAPE
+    assert L.mtpc_cp_sample(C.byref(_head()), 2, 1, 0, None, None, None) == NULL
+    assert L.mtpc_philox_uniforms(1, 1, 0, 0, 0, out, None) == SHAPE
+
+
+def test_workspace_query():
+    from paper_2511_11346_amd import binding
+    L = binding.lib()
+    hd = _head()
+    small = L.mtpc_workspace_bytes(binding.CP, binding.OP_LOGLIK, C.byref(hd), None, 1, 0)
+    assert small >= 4 * (hd.B * hd.r + hd.B * hd.n * hd.r)
+    s4 = L.mtpc_workspace_bytes(binding.CP, binding.OP_SAMPLE, C.byref(hd), None, 4, 0)
+    s8 = L.mtpc_workspace_bytes(binding.CP, binding.OP_SAMPLE, C.byref(hd), None, 8, 0)
+    assert s8 > s4 > 0
+    assert L.mtpc_workspace_bytes(9, 0, C.byref(hd), None, 1, 0) == 0
+    assert L.mtpc_workspace_bytes(binding.CP, binding.OP_SAMPLE, C.byref(hd), None, 0, 0) == 0
+    lay = binding.mtpc_sumlayers(0x6000, hd.r * hd.r, 0)
+    hom = binding.mtpc_sumlayers(0x6000, 0, 0)
+    a = L.mtpc_workspace_bytes(binding.HMM, binding.OP_LOGLIK, C.byref(hd), C.byref(lay), 1, 0)
+    b = L.mtpc_workspace_bytes(binding.HMM, binding.OP_LOGLIK, C.byref(hd), C.byref(hom), 1, 0)
+    assert a >= b > small
