@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Throughput of the MtPC head hot path on one MI355X.
+
+Workload: BASELINE configs[1] at full size - CP head, r=16, bf16 inputs with fp32
+accumulation, B=8192 positions, d=4096, n=8, v=320 - on seeded synthetic inputs
+already resident in HBM.  One step = one pass of the whole hot path over the
+batch: sum-unit parameters, fused unembedding + log-softmax + gather, circuit
+layers with prefix marginals (the last one is the log-likelihood), then one
+ancestral draft per position with the prefix marginals of that draft.
+
+Prints ONE JSON line (see the keys below).  `roofline` is for the dominant
+kernel (the fused unembedding kernel of the log-likelihood pass), timed with HIP
+events recorded by the library right around its launch; `cpu_baseline` is the
+float64 NumPy oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+WORKLOAD = dict(family="cp", B=8192, d=4096, n=8, r=16, v=320)
+
+
+class HipEvents:
+    """hipEvent pairs through the HIP runtime (the events are recorded by libmtpc
+    on the stream of the call, see mtpc_profile_unembed)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self):
+        ev = C.c_void_p()
+        assert self.hip.hipEventCreate(C.byref(ev)) == 0
+        return ev
+
+    def elapsed_ms(self, a, b):
+        assert self.hip.hipEventSynchronize(b) == 0
+        ms = C.c_float()
+        assert self.hip.hipEventElapsedTime(C.byref(ms), a, b) == 0
+        return float(ms.value)
+
+
+def cpu_baseline(inp, rows: int, S: int, seed: int):
+    """The oracle, as it stands, on the first `rows` positions of the workload."""
+    import numpy as np
+    from oracle import mtpc_oracle as oc
+    from oracle import philox
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    h = inp.h[:rows]
+    tg = inp.targets[:rows]
+    t0 = time.perf_counter()
+    logphi, logw, _ = oc._params(inp.family, h, inp.W, inp.Wsum, None)
+    P = oc.prefix_marginals_from(inp.family, logphi, logw, None, tg)
+    u = philox.uniforms(rows, S, inp.n + oc.n_latents(inp.family, inp.n), seed)
+    drafts, lat = oc.sample_from(inp.family, logphi, logw, None, u)
+    for s in range(S):
+        oc.prefix_marginals_from(inp.family, logphi, logw, None, drafts[:, s])
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "windows/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {rows} of {inp.B} positions, same W; loglik+prefix marginals+1 draft+draft scores; {dt:.1f} s"}, P
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--cpu-rows", type=int, default=4096)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run a plain 1 GiB device copy (known HBM traffic) to calibrate rocprofv3 counters")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import mtpc_inputs as mi
+    from paper_2511_11346_amd import Head, binding, profile_unembed
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    t_gen = time.perf_counter()
+    inp = mi.config2(r=WORKLOAD["r"], B=WORKLOAD["B"])
+    as_bf16 = lambda bits: torch.from_numpy(bits).view(torch.bfloat16).to(dev)
+    head = Head("cp", as_bf16(inp.h_bits), as_bf16(inp.W_bits), as_bf16(inp.Wsum_bits))
+    tg = torch.from_numpy(inp.targets).to(dev)
+    B, n, S = inp.B, inp.n, 1
+    P = torch.empty(B, n, dtype=torch.float32, device=dev)
+    drafts = torch.empty(B, S, n, dtype=torch.int32, device=dev)
+    lat = torch.empty(B, S, 1, dtype=torch.int32, device=dev)
+    pl = torch.empty(B, S, n, dtype=torch.float32, device=dev)
+    # workspace sized once for the larger of the two ops
+    head._head(max(head.workspace_bytes(binding.OP_MARGINALS), head.workspace_bytes(binding.OP_SAMPLE, S=S)))
+    t_gen = time.perf_counter() - t_gen
+
+    if args.copy_calib:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    ev = HipEvents()
+
+    def step(k, pairs=None):
+        if pairs is not None:
+            profile_unembed(pairs[k][0], pairs[k][1])
+        head.prefix_marginals(tg, out=P)
+        if pairs is not None:
+            profile_unembed(None, None)
+        head.sample(S, seed=0, offset=k, out=(drafts, lat, pl))
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(k, pairs)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt * 1e3 / args.steps
+    k1_ms = sum(ev.elapsed_ms(a, b) for a, b in pairs) / len(pairs)
+
+    # per-op timings (outside the timed region, for the record)
+    def time_op(fn, reps=10):
+        fn(); torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / reps
+    ms_marg = time_op(lambda: head.prefix_marginals(tg, out=P))
+    ms_samp = time_op(lambda: head.sample(S, seed=0, out=(drafts, lat, pl)))
+    ms_samp_only = time_op(lambda: head.sample(S, seed=0, out=(drafts, lat, None)))
+
+    flops = 2.0 * B * inp.n * inp.r * inp.v * inp.d
+    achieved = flops / (k1_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "k_unembed (evidence pass of prefix marginals)",
+                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "avg_launch_ms": k1_ms, "flop_per_launch": flops}
+
+    out = {
+        "metric": "MtPC head windows/sec (loglik + draft sample)",
+        "value": B / (ms_step * 1e-3), "unit": "windows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: CP r=16, B=8192, d=4096, n=8, v=320, bf16 in / fp32 acc; "
+                               "step = prefix marginals (last = loglik) + 1 draft per position with its prefix scores",
+                   **WORKLOAD, "S": S},
+        "roofline": roofline,
+        "ops_ms": {"prefix_marginals": ms_marg, "sample_with_scores": ms_samp, "sample_only": ms_samp_only},
+        "loglik_windows_per_s": B / (ms_marg * 1e-3),
+        "input_generation_s": t_gen,
+    }
+    if not args.no_cpu:
+        base, P_cpu = cpu_baseline(inp, min(args.cpu_rows, B), S, seed=0)
+        out["cpu_baseline"] = base
+        err = float(np.max(np.abs(P[:P_cpu.shape[0]].cpu().numpy() - P_cpu)))
+        out["max_abs_err_vs_oracle_on_sample"] = err
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

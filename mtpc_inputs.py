@@ -14,6 +14,8 @@ of its evaluation data is used or reproduced - the values are i.i.d. Gaussian.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import Optional
 
@@ -63,10 +65,38 @@ class HeadInputs:
     meta: dict = field(default_factory=dict)
 
 
-def _gauss(rng, shape, scale):
-    a = rng.standard_normal(size=shape, dtype=np.float32)
-    a *= np.float32(scale)
-    return a
+_CHUNK = 1 << 22
+
+
+def _gauss(seed, tensor_id, shape, scale, bf16):
+    """N(0, scale^2) of the given shape, drawn chunk by chunk from independent
+    generators seeded (seed, tensor_id, chunk) so that the values do not depend on
+    the number of worker threads.  Returns (fp32 values, bf16 bit patterns or
+    None); with ``bf16`` the fp32 values are the rounded ones."""
+    total = int(np.prod(shape))
+    vals = np.empty(total, dtype=np.float32)
+    bits = np.empty(total, dtype=np.uint16) if bf16 else None
+
+    def work(c):
+        lo, hi = c * _CHUNK, min(total, (c + 1) * _CHUNK)
+        g = np.random.default_rng([seed, tensor_id, c])
+        a = g.standard_normal(size=hi - lo, dtype=np.float32)
+        a *= np.float32(scale)
+        if bf16:
+            b = f32_to_bf16_bits(a)
+            bits[lo:hi] = b
+            vals[lo:hi] = bf16_bits_to_f32(b)
+        else:
+            vals[lo:hi] = a
+
+    nchunk = (total + _CHUNK - 1) // _CHUNK
+    if nchunk <= 1:
+        for c in range(nchunk):
+            work(c)
+    else:
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(work, range(nchunk)))
+    return vals.reshape(shape), (bits.reshape(shape) if bf16 else None)
 
 
 def biased_byte_targets(rng, B: int, n: int) -> np.ndarray:
@@ -96,34 +126,27 @@ def make_inputs(family: str, *, B: int, d: int, n: int, r: int, v: int,
         h_scale = 1.0 if dtype == "f32" else 1.0 / np.sqrt(d)
     if w_scale is None:
         w_scale = 1.0 / np.sqrt(d)
-    h = _gauss(rng, (B, d), h_scale)
-    W = _gauss(rng, (n, r, v, d), w_scale * logit_gain)
-    Wsum = None if family == "ff" else _gauss(rng, (r, d), w_scale * logit_gain)
+    if dtype not in ("f32", "bf16"):
+        raise ValueError(dtype)
+    bf = dtype == "bf16"
+    h, h_bits = _gauss(seed, 1, (B, d), h_scale, bf)
+    W, W_bits = _gauss(seed, 2, (n, r, v, d), w_scale * logit_gain, bf)
+    Wsum, Wsum_bits = (None, None) if family == "ff" else _gauss(seed, 3, (r, d), w_scale * logit_gain, bf)
     layers = None
     if family == "hmm":
         L = (n - 1) if layer_count is None else layer_count
-        layers = _gauss(rng, (L, r, r), 1.0)
+        layers, _ = _gauss(seed, 4, (L, r, r), 1.0, False)
     elif family == "btree":
         L = (n - 2) if layer_count is None else layer_count
-        layers = _gauss(rng, (L, r, r), 1.0)
+        layers, _ = _gauss(seed, 4, (L, r, r), 1.0, False)
     if targets == "uniform":
         tg = rng.integers(0, min(v, 256), size=(B, n), dtype=np.int32)
     elif targets == "biased":
         tg = biased_byte_targets(rng, B, n)
     else:
         raise ValueError(targets)
-    out = HeadInputs(family, dtype, B, d, n, r, v, h, W, Wsum, layers, tg)
-    if dtype == "bf16":
-        out.h_bits = f32_to_bf16_bits(h)
-        out.h = bf16_bits_to_f32(out.h_bits)
-        out.W_bits = f32_to_bf16_bits(W)
-        out.W = bf16_bits_to_f32(out.W_bits)
-        if Wsum is not None:
-            out.Wsum_bits = f32_to_bf16_bits(Wsum)
-            out.Wsum = bf16_bits_to_f32(out.Wsum_bits)
-    elif dtype != "f32":
-        raise ValueError(dtype)
-    return out
+    return HeadInputs(family, dtype, B, d, n, r, v, h, W, Wsum, layers, tg,
+                      h_bits=h_bits, W_bits=W_bits, Wsum_bits=Wsum_bits)
 
 
 # --------------------------------------------------------------------------

@@ -1,0 +1,80 @@
+"""GPU parity at the full sizes of the named workloads, in the launch
+configuration bench.py times.  The oracle evaluates a fixed sample of positions
+(first tile, last tile, random rows); positions are independent, so every sampled
+output is computed by the oracle exactly as in the small tests."""
+import numpy as np
+import pytest
+import torch
+
+import mtpc_inputs as mi
+from oracle import mtpc_oracle as oc
+from oracle import philox
+
+from gpu_util import BOUNDARY, compare_drafts, make_head, tol_check
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(B, k=40, seed=0):
+    rng = np.random.default_rng(seed)
+    rows = set(range(0, 6)) | set(range(B - 6, B)) | set(rng.integers(0, B, size=k).tolist())
+    rows |= {255, 256, 257} & set(range(B))
+    return np.array(sorted(rows))
+
+
+def check_rows(inp, head, rows, S=0, seed=0):
+    tg = torch.from_numpy(inp.targets).cuda()
+    gP = head.prefix_marginals(tg).cpu().numpy()
+    gL = head.loglik(tg).cpu().numpy()
+    lay = inp.layers
+    logphi, logw, loglayers = oc._params(inp.family, inp.h[rows], inp.W,
+                                         inp.Wsum, lay)
+    want = oc.prefix_marginals_from(inp.family, logphi, logw, loglayers, inp.targets[rows])
+    err = tol_check(gP[rows], want, inp.dtype, "prefix marginals")
+    tol_check(gL[rows], want[:, -1], inp.dtype, "loglik")
+    assert np.array_equal(gL, gP[:, -1])
+    assert np.all(np.isfinite(gL)) and np.all(np.diff(gP, axis=1) <= 1e-4)
+    print(f"{inp.family} B={inp.B} r={inp.r}: {len(rows)} rows checked, max abs err {err:.2e}")
+    if S:
+        gd, gl, gp = head.sample(S, seed=seed, want_prefix=True)
+        nl = oc.n_latents(inp.family, inp.n)
+        u_all = philox.uniforms(inp.B, S, inp.n + nl, seed)
+        od, ol, margin = oc.sample_from(inp.family, logphi, logw, loglayers, u_all[rows], with_margin=True)
+        near, bad = compare_drafts(gd[rows], gl[rows] if gl is not None else None, od, ol, margin)
+        print(f"  drafts: {near} of {margin.size} within {BOUNDARY} of a CDF step, {bad} of those differ")
+        gdn = gd.cpu().numpy()
+        for s in range(S):
+            ps = oc.prefix_marginals_from(inp.family, logphi, logw, loglayers, gdn[rows, s])
+            tol_check(gp[rows, s].cpu().numpy(), ps, inp.dtype, "draft scores")
+
+
+def test_config2_ff_and_cp16_full_size():
+    for r in (1, 16):
+        inp = mi.config2(r=r)
+        head = make_head(inp)
+        check_rows(inp, head, sample_rows(inp.B), S=1 if r == 16 else 0)
+        del head
+        torch.cuda.empty_cache()
+
+
+def test_config3_hmm_full_size():
+    inp = mi.config3()
+    head = make_head(inp)
+    check_rows(inp, head, sample_rows(inp.B, k=24))
+    M = head.univariate_marginals()
+    rows = np.array([0, 300, inp.B - 1])
+    want = oc.univariate_marginals("hmm", inp.h[rows], inp.W, inp.Wsum, inp.layers)
+    tol_check(M[rows].cpu().numpy(), want, "bf16", "univariate")
+
+
+def test_config4_btree_full_size():
+    inp = mi.config4()
+    head = make_head(inp)
+    check_rows(inp, head, sample_rows(inp.B, k=12))
+
+
+@pytest.mark.parametrize("B", [1, 8, 64])
+def test_config5_decode_draft_and_score(B):
+    inp = mi.config5(B=B)
+    head = make_head(inp)
+    check_rows(inp, head, np.arange(B), S=1, seed=0)
