@@ -44,41 +44,70 @@ __device__ __forceinline__ float dot_chunk(const i32x4_t& a, const i32x4_t& b) {
 
 // ---------------------------------------------------------------------------
 // log omega[b,:] = log_softmax(Wsum h[b])   (Sec. 3.3, sum unit parameters)
-// one wave per position; r <= 128 scores kept two per lane
+// Few positions: one workgroup per position, its 4 waves split the r rows, the
+// scores meet in LDS.  Many positions go through the MFMA tile kernel instead.
 // ---------------------------------------------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(256) void k_sumunit(const void* h, long long ld_h, const void* Wsum,
                                                  int B, int d, int r, float* logw) {
   constexpr int ESZ = BF16 ? 2 : 4;
   constexpr int EPC = 16 / ESZ;
-  const int lane = threadIdx.x & 63;
-  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (b >= B) return;
+  __shared__ float sc[128];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.x;
   const char* hb = (const char*)h + (long long)b * ld_h * ESZ;
   const int nch = d / EPC;
-  float s0 = neg_inf(), s1 = neg_inf();
-  for (int j = 0; j < r; ++j) {
-    const char* wr = (const char*)Wsum + (long long)j * d * ESZ;
-    float acc = 0.f;
-    for (int c = lane; c < nch; c += 64)
-      acc += dot_chunk<BF16>(*(const i32x4_t*)(wr + c * 16), *(const i32x4_t*)(hb + c * 16));
-    acc = wave_sum(acc);
-    if ((j & 63) == lane) { if (j < 64) s0 = acc; else s1 = acc; }
+  // the position's hidden vector stays in registers: up to 8 chunks of 16 bytes per
+  // lane per pass (d <= 4096 bf16 / 2048 fp32 in one pass), rows four at a time so
+  // that many loads are in flight
+  for (int c0 = 0; c0 < nch; c0 += 512) {
+    i32x4_t hv[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int c = c0 + t * 64 + lane;
+      const i32x4_t x = *(const i32x4_t*)(hb + (long long)min(c, nch - 1) * 16);
+      hv[t] = c < nch ? x : i32x4_t{0, 0, 0, 0};
+    }
+    for (int j0 = wave * 4; j0 < r; j0 += 16) {
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int j = min(j0 + q, r - 1);
+        const char* wr = (const char*)Wsum + (long long)j * d * ESZ;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          // unconditional (clamped) loads so that all of them are in flight together;
+          // chunks beyond d meet a zero hv
+          const int c = min(c0 + t * 64 + lane, nch - 1);
+          acc[q] += dot_chunk<BF16>(*(const i32x4_t*)(wr + (long long)c * 16), hv[t]);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float v = wave_sum(acc[q]);
+        if (lane == 0 && j0 + q < r) { if (c0 == 0) sc[j0 + q] = v; else sc[j0 + q] += v; }
+      }
+    }
   }
-  float m = fmaxf(s0, s1);
-  m = group_max(m, 64);
-  float e = 0.f;
-  if (s0 > neg_inf()) e += __expf(s0 - m);
-  if (s1 > neg_inf()) e += __expf(s1 - m);
-  e = group_sum(e, 64);
-  const float lse = m + __logf(e);
-  if (lane < r) logw[(long long)b * r + lane] = s0 - lse;
-  if (lane + 64 < r) logw[(long long)b * r + lane + 64] = s1 - lse;
+  __syncthreads();
+  if (wave == 0) {
+    const float s0 = lane < r ? sc[lane] : neg_inf();
+    const float s1 = lane + 64 < r ? sc[lane + 64] : neg_inf();
+    const float m = group_max(fmaxf(s0, s1), 64);
+    float e = 0.f;
+    if (s0 > neg_inf()) e += __expf(s0 - m);
+    if (s1 > neg_inf()) e += __expf(s1 - m);
+    e = group_sum(e, 64);
+    const float lse = m + __logf(e);
+    if (lane < r) logw[(long long)b * r + lane] = s0 - lse;
+    if (lane + 64 < r) logw[(long long)b * r + lane + 64] = s1 - lse;
+  }
 }
 
 hipError_t launch_sumunit(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
                           int dtype, float* logw, hipStream_t st) {
-  dim3 grid((B + 3) / 4), block(256);
+  if (B > 128) return launch_sumunit_mfma(h, ld_h, Wsum, B, d, r, dtype, logw, st);
+  dim3 grid(B), block(256);
   if (dtype == MTPC_BF16)
     hipLaunchKernelGGL(k_sumunit<true>, grid, block, 0, st, h, ld_h, Wsum, B, d, r, logw);
   else
@@ -126,9 +155,11 @@ hipError_t launch_normalise_layers(const float* logits, long long layer_stride, 
 
 // ---------------------------------------------------------------------------
 // circuit layers.  A group of G lanes (G = smallest power of two >= min(r, 64))
-// owns one evidence row; lane g holds the units j = g and g + 64 (r <= 128).
-// Sum layers are evaluated in the linear domain after a max shift:
-//   log sum_j w[j] exp(c[j]) = m + log sum_j w[j] exp(c[j] - m).
+// owns RB consecutive evidence rows; lane g holds the units j = g and g + 64
+// (r <= 128) of each.  Sum layers are evaluated in the linear domain after a max
+// shift:  log sum_j w[j] exp(c[j]) = m + log sum_j w[j] exp(c[j] - m),
+// and every weight fetched from the (L2-resident) layer serves all RB rows.
+// Rows that share a batch must share their layers, so contextual layers run RB=1.
 // ---------------------------------------------------------------------------
 struct Pair { float a, b; };   // units g and g+64 of a lane
 
@@ -143,29 +174,6 @@ __device__ __forceinline__ float pair_lse(Pair x, int g, int r, int G) {
   return m + __logf(s);
 }
 
-// out[k] = log sum_j Wl[j][k] exp(c[j]) for the lane's k = g (and g+64); Wl is a
-// normalised layer stored [j][k] (k contiguous).  `sh` is this group's r floats of LDS.
-__device__ __forceinline__ Pair sum_layer(Pair c, const float* __restrict__ Wl, float* sh, int g,
-                                          int r, int G) {
-  const float m = group_max(fmaxf(c.a, c.b), G);
-  Pair o;
-  if (m == neg_inf()) { o.a = o.b = m; return o; }   // uniform inside the group
-  if (g < r) sh[g] = __expf(c.a - m);
-  if (g + 64 < r) sh[g + 64] = __expf(c.b - m);
-  __builtin_amdgcn_wave_barrier();
-  float s0 = 0.f, s1 = 0.f;
-  const bool two = g + 64 < r;
-  for (int j = 0; j < r; ++j) {
-    const float p = sh[j];
-    if (g < r) s0 = fmaf(p, Wl[(long long)j * r + g], s0);
-    if (two) s1 = fmaf(p, Wl[(long long)j * r + g + 64], s1);
-  }
-  __builtin_amdgcn_wave_barrier();
-  o.a = g < r ? m + __logf(s0) : neg_inf();
-  o.b = two ? m + __logf(s1) : neg_inf();
-  return o;
-}
-
 __device__ __forceinline__ Pair load_pair(const float* p, int g, int r, float fill) {
   Pair x;
   x.a = g < r ? p[g] : fill;
@@ -178,55 +186,157 @@ __device__ __forceinline__ void store_pair(float* p, Pair x, int g, int r) {
   if (g + 64 < r) p[g + 64] = x.b;
 }
 
-// dynamic LDS: per group  r floats (exchange) + (n-1)*r floats (BTree node values)
+template <int RB> struct Rows { Pair v[RB]; };
+
+// out[q][k] = log sum_j Wl[j][k] exp(c[q][j]) for the lane's k = g (and g+64); Wl is
+// a normalised layer stored [j][k] (k contiguous).  `sh` holds this group's
+// r * RB floats, laid out [j][q] so that one LDS read serves all RB rows.
+template <int RB>
+__device__ __forceinline__ Rows<RB> sum_layer(const Rows<RB>& c, const float* __restrict__ Wl, float* sh,
+                                              int g, int r, int G) {
+  float m[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) {
+    m[q] = group_max(fmaxf(c.v[q].a, c.v[q].b), G);
+    const float ms = (m[q] == neg_inf()) ? 0.f : m[q];
+    if (g < r) sh[g * RB + q] = __expf(c.v[q].a - ms);             // exp(-inf) = 0
+    if (g + 64 < r) sh[(g + 64) * RB + q] = __expf(c.v[q].b - ms);
+  }
+  __builtin_amdgcn_wave_barrier();
+  float s0[RB], s1[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) s0[q] = s1[q] = 0.f;
+  const bool one = g < r, two = g + 64 < r;
+  const int gc = one ? g : 0;
+  for (int j0 = 0; j0 < r; j0 += 8) {
+    // eight weights per lane in flight at once (clamped rows get weight zero)
+    float w0[8], w1[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = min(j0 + u, r - 1);
+      w0[u] = Wl[(long long)j * r + gc];
+      w1[u] = two ? Wl[(long long)j * r + g + 64] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const bool live = one && j0 + u < r;
+      const float a0 = live ? w0[u] : 0.f, a1 = live ? w1[u] : 0.f;
+      const int j = min(j0 + u, r - 1);
+#pragma unroll
+      for (int q = 0; q < RB; ++q) {
+        const float p = sh[j * RB + q];
+        s0[q] = fmaf(p, a0, s0[q]);
+        s1[q] = fmaf(p, a1, s1[q]);
+      }
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  Rows<RB> o;
+#pragma unroll
+  for (int q = 0; q < RB; ++q) {
+    o.v[q].a = one ? m[q] + __logf(s0[q]) : neg_inf();           // -inf + log 0 = -inf
+    o.v[q].b = two ? m[q] + __logf(s1[q]) : neg_inf();
+  }
+  return o;
+}
+
+// dynamic LDS: per group  RB*r floats (exchange) + (n-1)*RB*r floats (BTree node values)
+template <int RB>
 __global__ __launch_bounds__(256) void k_circuit(const CircuitArgs a, int G, int groups_per_block,
                                                  int sh_per_group) {
   extern __shared__ float csm[];
   const int gl = threadIdx.x / G;           // group inside the block
   const int g = threadIdx.x % G;
-  const long long row = (long long)blockIdx.x * groups_per_block + gl;
+  const long long row0 = ((long long)blockIdx.x * groups_per_block + gl) * RB;
   // whole groups leave together; nothing below synchronises across groups
-  if (gl >= groups_per_block || row >= a.rows) return;
-  const long long rr = row;
+  if (gl >= groups_per_block || row0 >= a.rows) return;
   const int n = a.n, r = a.r;
-  const float* e = a.e + rr * n * r;
-  const long long b = rr / a.T;
   const float ninf = neg_inf();
   float* sh = csm + (size_t)gl * sh_per_group;
-  float* nodes = sh + r;                    // BTree only
-  const float* lay = a.layers;
-  if (a.contextual && lay) lay += b * (long long)a.L * r * r;
+  float* nodes = sh + RB * r;               // BTree only: nodes[(m*RB + q)*r + k]
   const long long lstep = (a.L > 1) ? (long long)r * r : 0;
-  // An id outside [-1, v) leaves NaN in every unit of its window position; max
-  // reductions would drop it, so poison every output that observes that position.
-  int first_bad = n;
-  for (int i = n - 1; i >= 0; --i)
-    if (e[i * r] != e[i * r]) first_bad = i;
-  auto emit = [&](int i, float v) {      // value of the prefix ending at token i
-    if (g != 0) return;
-    if (i >= first_bad) v = __builtin_nanf("");
-    if (a.prefix) a.out[row * n + i] = v;
-    else if (i == n - 1) a.out[row] = v;
+  const float* lay = a.layers;
+  if (a.contextual && lay) lay += (row0 / a.T) * (long long)a.L * r * r;   // RB == 1 here
+
+  // rows beyond the end repeat the last row (loads stay in bounds) and are not stored
+  long long row[RB];
+  const float* e[RB];
+  int first_bad[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) {
+    row[q] = row0 + q;
+    const long long rc = row[q] < a.rows ? row[q] : a.rows - 1;
+    e[q] = a.e + rc * n * r;
+    // An id outside [-1, v) leaves NaN in every unit of its window position; max
+    // reductions would drop it, so poison every output that observes that position.
+    first_bad[q] = n;
+  }
+  if constexpr (RB == 1) {
+    // few rows: the call is latency-bound, so fetch the whole evidence row with all
+    // loads in flight at once and serve the layer-by-layer accesses from LDS
+    float* stage = csm + (size_t)groups_per_block * sh_per_group + (size_t)gl * n * r;
+    const int tot = n * r;
+    for (int t0 = 0; t0 < tot; t0 += 8 * G) {
+      float tmp[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) tmp[u] = e[0][min(t0 + u * G + g, tot - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (t0 + u * G + g < tot) stage[t0 + u * G + g] = tmp[u];
+    }
+    __builtin_amdgcn_wave_barrier();
+    e[0] = stage;
+  }
+#pragma unroll
+  for (int q = 0; q < RB; ++q)
+    for (int i = n - 1; i >= 0; --i)
+      if (e[q][i * r] != e[q][i * r]) first_bad[q] = i;
+  auto emit = [&](int q, int i, float v) {      // value of the prefix ending at token i of row q
+    if (g != 0 || row[q] >= a.rows) return;
+    if (i >= first_bad[q]) v = __builtin_nanf("");
+    if (a.prefix) a.out[row[q] * n + i] = v;
+    else if (i == n - 1) a.out[row[q]] = v;
   };
 
   if (a.family == MTPC_FF) {
-    float acc = 0.f;
-    for (int i = 0; i < n; ++i) {
-      acc += e[i * r];
-      emit(i, acc);
+#pragma unroll
+    for (int q = 0; q < RB; ++q) {
+      float acc = 0.f;
+      for (int i = 0; i < n; ++i) {
+        acc += e[q][i * r];
+        emit(q, i, acc);
+      }
     }
     return;
   }
-  const Pair lw = load_pair(a.logw + b * r, g, r, ninf);
+  Rows<RB> lw;
+#pragma unroll
+  for (int q = 0; q < RB; ++q) {
+    const long long rc = row[q] < a.rows ? row[q] : a.rows - 1;
+    lw.v[q] = load_pair(a.logw + (rc / a.T) * r, g, r, ninf);
+  }
+  auto leaf = [&](int i) {                  // evidence of token i for all rows
+    Rows<RB> x;
+#pragma unroll
+    for (int q = 0; q < RB; ++q) x.v[q] = load_pair(e[q] + i * r, g, r, ninf);
+    return x;
+  };
+  auto add = [&](const Rows<RB>& x, const Rows<RB>& y) {
+    Rows<RB> o;
+#pragma unroll
+    for (int q = 0; q < RB; ++q) o.v[q] = add_pair(x.v[q], y.v[q]);
+    return o;
+  };
+  auto emit_lse = [&](int i, const Rows<RB>& x) {
+#pragma unroll
+    for (int q = 0; q < RB; ++q) emit(q, i, pair_lse(x.v[q], g, r, G));
+  };
 
   if (a.family == MTPC_CP) {
-    Pair acc = lw;
+    Rows<RB> acc = lw;
     for (int i = 0; i < n; ++i) {
-      acc = add_pair(acc, load_pair(e + i * r, g, r, ninf));
-      if (a.prefix || i == n - 1) {
-        const float v = pair_lse(acc, g, r, G);
-        emit(i, v);
-      }
+      acc = add(acc, leaf(i));
+      if (a.prefix || i == n - 1) emit_lse(i, acc);
     }
     return;
   }
@@ -234,44 +344,43 @@ __global__ __launch_bounds__(256) void k_circuit(const CircuitArgs a, int G, int
   if (a.family == MTPC_HMM) {
     // forward messages of Eq. HMM: alpha_0 = log omega + e_0,
     // alpha_i[j'] = e_i[j'] + log sum_j exp(alpha_{i-1}[j]) T_{i-1}[j][j']
-    Pair alpha = add_pair(lw, load_pair(e, g, r, ninf));
+    Rows<RB> alpha = add(lw, leaf(0));
     for (int i = 0; i < n; ++i) {
-      if (i > 0) {
-        const Pair t = sum_layer(alpha, lay + (long long)(i - 1) * lstep, sh, g, r, G);
-        alpha = add_pair(t, load_pair(e + i * r, g, r, ninf));
-      }
-      if (a.prefix || i == n - 1) {
-        const float v = pair_lse(alpha, g, r, G);
-        emit(i, v);
-      }
+      if (i > 0) alpha = add(sum_layer<RB>(alpha, lay + (long long)(i - 1) * lstep, sh, g, r, G), leaf(i));
+      if (a.prefix || i == n - 1) emit_lse(i, alpha);
     }
     return;
   }
 
   // ---- binary tree (Eq. BTree), heap order: inner nodes 0..n-2, leaf i at n-1+i.
-  // nodes[m*r + k] = C_m[k] for inner m >= 1 with every leaf below it observed.
-  auto full_value = [&](int c) -> Pair {   // c: heap index of a child
-    return c >= n - 1 ? load_pair(e + (c - (n - 1)) * r, g, r, ninf)
-                      : load_pair(nodes + (size_t)c * r, g, r, ninf);
+  // nodes[(m*RB+q)*r + k] = C_m[k] of row q for inner m >= 1 with every leaf below it observed.
+  auto full_value = [&](int c) {            // c: heap index of a child
+    if (c >= n - 1) return leaf(c - (n - 1));
+    Rows<RB> x;
+#pragma unroll
+    for (int q = 0; q < RB; ++q) x.v[q] = load_pair(nodes + ((size_t)c * RB + q) * r, g, r, ninf);
+    return x;
   };
   for (int m = n - 2; m >= 1; --m) {
-    const Pair prod = add_pair(full_value(2 * m + 1), full_value(2 * m + 2));
-    const Pair c = sum_layer(prod, lay + (long long)(m - 1) * lstep, sh, g, r, G);
-    store_pair(nodes + (size_t)m * r, c, g, r);
+    const Rows<RB> c = sum_layer<RB>(add(full_value(2 * m + 1), full_value(2 * m + 2)),
+                                     lay + (long long)(m - 1) * lstep, sh, g, r, G);
+#pragma unroll
+    for (int q = 0; q < RB; ++q) store_pair(nodes + ((size_t)m * RB + q) * r, c.v[q], g, r);
     __builtin_amdgcn_wave_barrier();
   }
   if (!a.prefix) {
-    const Pair prod = add_pair(add_pair(full_value(1), full_value(2)), lw);
-    const float v = pair_lse(prod, g, r, G);
-    emit(n - 1, v);
+    emit_lse(n - 1, add(add(full_value(1), full_value(2)), lw));
     return;
   }
   // prefix marginals: tokens 0..i observed, the rest summed out.  A subtree with
   // no observed leaf evaluates to 1 (log 0 = 0 in every unit); a subtree fully
   // observed is the stored value; only the nodes on the path from leaf i to the
   // root whose range straddles the boundary are re-evaluated.
+  Rows<RB> zero;
+#pragma unroll
+  for (int q = 0; q < RB; ++q) zero.v[q] = Pair{0.f, 0.f};
   for (int i = 0; i < n; ++i) {
-    Pair pv = Pair{0.f, 0.f};       // value of the straddling child on the path so far
+    Rows<RB> pv = zero;             // value of the straddling child on the path so far
     int idx = n - 1 + i;            // heap index walking up from leaf i
     int size = 1;                   // leaves under idx
     while (idx > 0) {
@@ -285,66 +394,83 @@ __global__ __launch_bounds__(256) void k_circuit(const CircuitArgs a, int G, int
       const int half = size >> 1;
       const int l_last = first + half - 1, r_first = first + half, r_last = last;
       // left child always starts at or before i
-      const Pair lv = (l_last <= i) ? full_value(cl) : pv;
-      const Pair rv = (r_first > i) ? Pair{0.f, 0.f} : (r_last <= i ? full_value(cr) : pv);
-      const Pair prod = add_pair(lv, rv);
-      if (m > 0) {
-        pv = sum_layer(prod, lay + (long long)(m - 1) * lstep, sh, g, r, G);
-      } else {
-        const float v = pair_lse(add_pair(prod, lw), g, r, G);
-        emit(i, v);
-      }
+      const Rows<RB> lv = (l_last <= i) ? full_value(cl) : pv;
+      const Rows<RB> rv = (r_first > i) ? zero : (r_last <= i ? full_value(cr) : pv);
+      const Rows<RB> prod = add(lv, rv);
+      if (m > 0) pv = sum_layer<RB>(prod, lay + (long long)(m - 1) * lstep, sh, g, r, G);
+      else emit_lse(i, add(prod, lw));
       idx = m;
     }
   }
 }
 
-hipError_t launch_circuit(const CircuitArgs& a, hipStream_t st) {
+template <int RB>
+static hipError_t launch_circuit_rb(const CircuitArgs& a, hipStream_t st) {
   int G = 1;
   while (G < a.r && G < 64) G <<= 1;
-  int sh_per_group = a.r + (a.family == MTPC_BTREE ? (a.n - 1) * a.r : 0);
+  const int sh_per_group = RB * (a.r + (a.family == MTPC_BTREE ? (a.n - 1) * a.r : 0));
   int gpb = 256 / G;
-  while (gpb > 1 && (size_t)gpb * sh_per_group * 4 > 48 * 1024) gpb >>= 1;
-  const size_t smem = (size_t)gpb * sh_per_group * 4;
-  const unsigned grid = (unsigned)((a.rows + gpb - 1) / gpb);
-  hipLaunchKernelGGL(k_circuit, dim3(grid), dim3(256), smem, st, a, G, gpb, sh_per_group);
+  const int stage_per_group = RB == 1 ? a.n * a.r : 0;      // LDS copy of the evidence row
+  while (gpb > 1 && (size_t)gpb * (sh_per_group + stage_per_group) * 4 > 48 * 1024) gpb >>= 1;
+  // one group at the largest sizes (n = 64, r = 128, RB = 1): 32.5 KiB + 32 KiB <= 64 KiB
+  const size_t smem = (size_t)gpb * (sh_per_group + stage_per_group) * 4;
+  const long long ngroups = ((long long)a.rows + RB - 1) / RB;
+  const unsigned grid = (unsigned)((ngroups + gpb - 1) / gpb);
+  hipLaunchKernelGGL(k_circuit<RB>, dim3(grid), dim3(256), smem, st, a, G, gpb, sh_per_group);
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------------------
-// latent draws (Alg. 1): one thread per draft; CDFs accumulated in double
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ int draw_linear(const float* p, int r, float u) {
-  double acc = 0.0;
-  int last = 0;
-  for (int k = 0; k < r; ++k) {
-    const float pk = p[k];
-    acc += (double)pk;
-    if (pk > 0.f) last = k;
-    if ((double)u < acc) return k;
-  }
-  return last;
+hipError_t launch_circuit(const CircuitArgs& a, hipStream_t st) {
+  // batching rows pays when sum layers are shared and there are rows to batch;
+  // the batched BTree node store must still fit one group into 48 KiB of LDS
+  // (measured: the tree's many dependent node evaluations gain from sharing weight
+  // loads; the HMM chain prefers more, narrower groups)
+  const size_t one_group4 = 4ull * 4 * (a.r + (size_t)(a.n - 1) * a.r);
+  if (a.family == MTPC_BTREE && !a.contextual && a.rows >= 1024 && one_group4 <= 48 * 1024)
+    return launch_circuit_rb<4>(a, st);
+  return launch_circuit_rb<1>(a, st);
 }
-__device__ __forceinline__ int draw_log(const float* lp, int r, float u) {
-  double acc = 0.0;
-  int last = 0;
-  for (int k = 0; k < r; ++k) {
-    const float pk = expf(lp[k]);
-    acc += (double)pk;
-    if (pk > 0.f) last = k;
-    if ((double)u < acc) return k;
+
+// ---------------------------------------------------------------------------
+// latent draws (Alg. 1): one wave per draft.  Lane l holds the weights of units l
+// and l+64; the CDF is an inclusive scan in double, the draw the first lane whose
+// partial sum exceeds the uniform (the smallest k with u < p_0+..+p_k), else the
+// last unit with positive weight.  The result is wave-uniform, so the next sum
+// unit's row is again one coalesced load.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double wave_scan_incl(double x, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double t = __shfl_up(x, o);
+    if (lane >= o) x += t;
   }
-  return last;
+  return x;
+}
+__device__ __forceinline__ int wave_draw(float p0, float p1, int r, float u, int lane) {
+  const bool in0 = lane < r, in1 = lane + 64 < r;
+  const double c0 = wave_scan_incl(in0 ? (double)p0 : 0.0, lane);
+  unsigned long long m = __ballot(in0 && (double)u < c0);
+  if (m) return __ffsll((long long)m) - 1;
+  if (r > 64) {
+    const double c1 = __shfl(c0, 63) + wave_scan_incl(in1 ? (double)p1 : 0.0, lane);
+    m = __ballot(in1 && (double)u < c1);
+    if (m) return 64 + __ffsll((long long)m) - 1;
+    m = __ballot(in1 && p1 > 0.f);
+    if (m) return 64 + 63 - __clzll((long long)m);
+  }
+  m = __ballot(in0 && p0 > 0.f);
+  return m ? 63 - __clzll((long long)m) : 0;
 }
 
 __global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
-  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);     // draft index
   if (t >= (long long)a.B * a.S) return;
   const int b = (int)(t / a.S), s = (int)(t % a.S);
   const int n = a.n, r = a.r;
   int* zl = a.zleaf + t * n;
   if (a.family == MTPC_FF) {
-    for (int i = 0; i < n; ++i) zl[i] = 0;
+    for (int i = lane; i < n; i += 64) zl[i] = 0;
     return;
   }
   const float* lay = a.layers;
@@ -353,34 +479,43 @@ __global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
   auto U = [&](int lat) {
     return philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)s, (uint32_t)(n + lat));
   };
-  const int z0 = draw_log(a.logw + (long long)b * r, r, U(0));
+  auto draw_row = [&](const float* row, int lat) {      // row of normalised linear weights
+    const float p0 = lane < r ? row[lane] : 0.f;
+    const float p1 = lane + 64 < r ? row[lane + 64] : 0.f;
+    return wave_draw(p0, p1, r, U(lat), lane);
+  };
+  const float* lw = a.logw + (long long)b * r;
+  const int z0 = wave_draw(lane < r ? expf(lw[lane]) : 0.f, lane + 64 < r ? expf(lw[lane + 64]) : 0.f, r,
+                           U(0), lane);
   if (a.family == MTPC_CP) {
-    for (int i = 0; i < n; ++i) zl[i] = z0;
-    if (a.latents) a.latents[t] = z0;
+    for (int i = lane; i < n; i += 64) zl[i] = z0;
+    if (a.latents && lane == 0) a.latents[t] = z0;
   } else if (a.family == MTPC_HMM) {
     int z = z0;
-    zl[0] = z;
-    if (a.latents) a.latents[t * n] = z;
-    for (int i = 1; i < n; ++i) {
-      z = draw_linear(lay + (long long)(i - 1) * lstep + (long long)z * r, r, U(i));
-      zl[i] = z;
-      if (a.latents) a.latents[t * n + i] = z;
+    for (int i = 0; i < n; ++i) {
+      if (i > 0) z = draw_row(lay + (long long)(i - 1) * lstep + (long long)z * r, i);
+      if (lane == 0) { zl[i] = z; if (a.latents) a.latents[t * n + i] = z; }
     }
   } else {
     // BTree: node m's latent given its parent's (heap order); the state that
     // indexes leaf i is the latent of its parent node (n-2+i)/2.  `latents` is
-    // always a valid buffer here (the caller's or library scratch).
+    // always a valid buffer here (the caller's or library scratch); lane m % 64
+    // keeps node m's latent for its children.
     int* L = a.latents + t * (n - 1);
-    L[0] = z0;
-    for (int m = 1; m < n - 1; ++m)
-      L[m] = draw_linear(lay + (long long)(m - 1) * lstep + (long long)L[(m - 1) >> 1] * r, r, U(m));
-    for (int i = 0; i < n; ++i) zl[i] = L[(n - 2 + i) >> 1];
+    int mine = z0;                                      // latent of node `lane` (n - 1 <= 63 nodes)
+    for (int m = 1; m < n - 1; ++m) {
+      const int zp = __shfl(mine, (m - 1) >> 1);
+      const int z = draw_row(lay + (long long)(m - 1) * lstep + (long long)zp * r, m);
+      if (lane == m) mine = z;
+    }
+    if (lane < n - 1) L[lane] = mine;
+    for (int i = lane; i < n; i += 64) zl[i] = __shfl(mine, (n - 2 + i) >> 1);
   }
 }
 
 hipError_t launch_latents(const LatentArgs& a, hipStream_t st) {
   const long long tot = (long long)a.B * a.S;
-  hipLaunchKernelGGL(k_latents, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(k_latents, dim3((unsigned)((tot + 3) / 4)), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -465,20 +600,51 @@ __global__ __launch_bounds__(256) void k_gather_evidence(const GatherArgs a) {
   const int x = a.x[bsi];
   const char* hb = (const char*)a.h + (long long)b * a.ld_h * ESZ;
   const int nch = a.d / EPC;
+  const bool valid = x >= 0 && x < a.v;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (valid) {
+    // all loads of a pass are issued before the first use (clamped, so unconditional)
+    for (int c0 = 0; c0 < nch; c0 += 512) {
+      i32x4_t hv[8], wv[2][8];
+      const char* wr[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int j = min(q * 4 + jj, a.r - 1);
+        wr[jj] = (const char*)a.W + ((((long long)i * a.r + j) * a.v + x) * (long long)a.d) * ESZ;
+      }
+      int cc[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) cc[t] = min(c0 + t * 64 + lane, nch - 1);
+      // loads first, arithmetic afterwards: two rows of W are in flight at a time
+#pragma unroll
+      for (int t = 0; t < 8; ++t) hv[t] = *(const i32x4_t*)(hb + (long long)cc[t] * 16);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) wv[0][t] = *(const i32x4_t*)(wr[0] + (long long)cc[t] * 16);
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        if (c0 + t * 64 + lane >= nch) hv[t] = i32x4_t{0, 0, 0, 0};
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        if (jj + 1 < 4) {
+#pragma unroll
+          for (int t = 0; t < 8; ++t) wv[(jj + 1) & 1][t] = *(const i32x4_t*)(wr[jj + 1] + (long long)cc[t] * 16);
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[jj] += dot_chunk<BF16>(wv[jj & 1][t], hv[t]);
+      }
+    }
+  }
+#pragma unroll
   for (int jj = 0; jj < 4; ++jj) {
     const int j = q * 4 + jj;
     if (j >= a.r) break;
     float* dst = a.e + (bs * a.n + i) * a.r + j;
-    if (x < 0 || x >= a.v) {
+    if (!valid) {
       if (lane == 0) *dst = (x == -1) ? 0.f : __builtin_nanf("");
       continue;
     }
-    const char* wr = (const char*)a.W + ((((long long)i * a.r + j) * a.v + x) * (long long)a.d) * ESZ;
-    float acc = 0.f;
-    for (int c = lane; c < nch; c += 64)
-      acc += dot_chunk<BF16>(*(const i32x4_t*)(wr + c * 16), *(const i32x4_t*)(hb + c * 16));
-    acc = wave_sum(acc);
-    if (lane == 0) *dst = acc - a.lse[((long long)b * a.n + i) * a.r + j];
+    const float v = wave_sum(acc[jj]);
+    if (lane == 0) *dst = v - a.lse[((long long)b * a.n + i) * a.r + j];
   }
 }
 

@@ -47,6 +47,9 @@ hipError_t launch_univariate(const UnivariateArgs& a, int dtype, hipStream_t st)
 // log omega[b][:] = log_softmax(Wsum h[b])
 hipError_t launch_sumunit(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
                           int dtype, float* logw, hipStream_t st);
+// same result through the MFMA tile kernel (unembed.hip); used when B is large
+hipError_t launch_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
+                               int dtype, float* logw, hipStream_t st);
 // softmax over the last axis of r x r logits -> linear probabilities.
 // in: logits[(b*bs) + l*ls + k*r + j]; out[((b*L + l)*r + k)*r + j] or transposed [j][k].
 hipError_t launch_normalise_layers(const float* logits, long long layer_stride, long long batch_stride,

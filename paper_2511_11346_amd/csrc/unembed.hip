@@ -10,7 +10,7 @@
 // the softmax reduction is almost entirely lane-local.  Wave grid WV (vocab) x WB
 // (positions); a wave owns VB x PB blocks of 32x32.
 // K is consumed in stages of SB bytes per row (SB = 64 or 128).  Both operand
-// tiles go from global memory straight into LDS (global_load_lds_dwordx4) through
+// tiles go from global memory straight into LDS (buffer_load_dwordx4 ... lds) through
 // a ring of NS stages with unpadded, XOR-swizzled rows; fragments are read with
 // conflict-free 16-byte LDS loads one half-step ahead of the MFMAs using them.
 #include "mtpc_internal.h"
@@ -530,6 +530,53 @@ void k_unembed(const UnembedArgs a) {
   }
 }
 
+// Sum-unit parameters for many positions (Sec. 3.3): log omega[b,:] =
+// log_softmax(Wsum h[b]).  Same tile machinery with Wsum as the only "slab" (r rows)
+// and narrow position tiles, so that B/32 workgroups share the work.
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+__global__ __launch_bounds__(WV * WB * 64)
+void k_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int d, int r, float* logw) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wv = wave % WV, wb = wave / WV;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int b0 = blockIdx.x * TL::TP;
+  f32x16_t acc[PB][VB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(Wsum, h, ld_h, B, d, r, 0, b0, smem, acc);
+  float mx[PB], lse[PB];
+  tile_lse<WV, WB, VB, PB, SB, NS>(acc, r, (float2*)(smem + TL::RED_OFF), mx, lse);
+  const int rbase = wv * VB * 32 + 4 * lhalf;
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) {
+    const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+    if (b >= B) continue;
+#pragma unroll
+    for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+        if (row < r) logw[(long long)b * r + row] = acc[pb][vb][i] - lse[pb];
+      }
+  }
+}
+
+template <bool BF16>
+static hipError_t launch_sumunit_mfma_dt(const void* h, long long ld_h, const void* Wsum, int B, int d,
+                                         int r, float* logw, hipStream_t st) {
+  using TL = Tile<2, 1, 2, 1, 64, 4>;      // 128 rows (r <= 128) x 32 positions, 2 waves
+  auto kern = k_sumunit_mfma<2, 1, 2, 1, 64, 4, BF16>;
+  hipLaunchKernelGGL(kern, dim3((B + TL::TP - 1) / TL::TP), dim3(TL::NT), TL::SMEM, st, h, ld_h, Wsum, B,
+                     d, r, logw);
+  return hipGetLastError();
+}
+
+hipError_t launch_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
+                               int dtype, float* logw, hipStream_t st) {
+  return dtype == MTPC_BF16 ? launch_sumunit_mfma_dt<true>(h, ld_h, Wsum, B, d, r, logw, st)
+                            : launch_sumunit_mfma_dt<false>(h, ld_h, Wsum, B, d, r, logw, st);
+}
+
 // Univariate marginals (App. B.1 with every other variable summed out):
 //   M[b,i,a] = log sum_j m[b,i,j] phi[b,i,j,a],  m = marginal of the latent that
 // indexes leaf i.  One workgroup owns window position i for a tile of positions
@@ -637,6 +684,13 @@ static hipError_t launch_cfg(const UnembedArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Ring geometry of the decode-shaped tiles (overridable for experiments)
+#ifndef MTPC_DEC_SB
+#define MTPC_DEC_SB 64
+#endif
+#ifndef MTPC_DEC_NS
+#define MTPC_DEC_NS 4
+#endif
 // Stage geometry of the 320 x 256 training tile (overridable for experiments)
 #ifndef MTPC_TRAIN_SB
 #define MTPC_TRAIN_SB 64
@@ -661,13 +715,13 @@ static hipError_t launch_dt(const UnembedArgs& a, hipStream_t st) {
     return launch_cfg<2, 4, 2, 2, 64, 4, BF16, SAMPLE>(a, st);
   }
   if (a.B > 32) {
-    if (a.v > 256) return launch_cfg<5, 1, 2, 2, 64, 4, BF16, SAMPLE>(a, st);
-    if (a.v > 128) return launch_cfg<4, 1, 2, 2, 64, 4, BF16, SAMPLE>(a, st);
-    return launch_cfg<2, 1, 2, 2, 64, 4, BF16, SAMPLE>(a, st);
+    if (a.v > 256) return launch_cfg<5, 1, 2, 2, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
+    if (a.v > 128) return launch_cfg<4, 1, 2, 2, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
+    return launch_cfg<2, 1, 2, 2, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
   }
-  if (a.v > 256) return launch_cfg<5, 1, 2, 1, 64, 4, BF16, SAMPLE>(a, st);
-  if (a.v > 128) return launch_cfg<4, 1, 2, 1, 64, 4, BF16, SAMPLE>(a, st);
-  return launch_cfg<2, 1, 2, 1, 64, 4, BF16, SAMPLE>(a, st);
+  if (a.v > 256) return launch_cfg<5, 1, 2, 1, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
+  if (a.v > 128) return launch_cfg<4, 1, 2, 1, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
+  return launch_cfg<2, 1, 2, 1, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
 }
 
 hipError_t launch_unembed(const UnembedArgs& a, int dtype, hipStream_t st) {
