@@ -19,6 +19,7 @@ import argparse
 import ctypes as C
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -27,6 +28,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
 WORKLOAD = dict(family="cp", B=8192, d=4096, n=8, r=16, v=320)
 
 
@@ -84,6 +86,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-rows", type=int, default=8192)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-shaped (HBM-bound) side measurement")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) to calibrate rocprofv3 counters")
     args = ap.parse_args()
@@ -178,6 +181,51 @@ def main():
         "loglik_windows_per_s": B / (ms_marg * 1e-3),
         "input_generation_s": t_gen,
     }
+    # context for the roofline fraction: what the matrix pipes sustain on this machine with
+    # register operands only (random data makes the chip hit its power limit)
+    probe = os.path.join(ROOT, "paper_2511_11346_amd", "probes", "mfma_ceiling")
+    if os.path.exists(probe):
+        try:
+            res = subprocess.run([probe], capture_output=True, text=True, timeout=120)
+            roofline["register_only_mfma_ceiling"] = json.loads(res.stdout.strip().splitlines()[-1])
+        except Exception as exc:                                   # the probe is optional context
+            roofline["register_only_mfma_ceiling"] = {"error": str(exc)}
+
+    if not args.no_decode:
+        # side measurement (not part of `value`): the decode-shaped workload of configs[4]
+        # - CP r=32, n=16, d=4096, v=320 - where the unembedding kernel streams the 1.34 GB
+        # of W once and is bound by HBM; one call = 1 draft per position + its prefix scores
+        del head
+        torch.cuda.empty_cache()
+        dec = []
+        inp5 = mi.config5(B=64)
+        W5 = as_bf16(inp5.W_bits)
+        Ws5 = as_bf16(inp5.Wsum_bits)
+        h5 = as_bf16(inp5.h_bits)
+        for Bd in (1, 8, 64):
+            hd = Head("cp", h5[:Bd].contiguous(), W5, Ws5)
+            o = (torch.empty(Bd, 1, inp5.n, dtype=torch.int32, device=dev),
+                 torch.empty(Bd, 1, 1, dtype=torch.int32, device=dev),
+                 torch.empty(Bd, 1, inp5.n, dtype=torch.float32, device=dev))
+            for k in range(3):
+                hd.sample(1, seed=0, offset=k, out=o)
+            torch.cuda.synchronize()
+            reps = 20
+            prs = [(ev.create(), ev.create()) for _ in range(reps)]
+            t = time.perf_counter()
+            for k in range(reps):
+                profile_unembed(prs[k][0], prs[k][1])
+                hd.sample(1, seed=0, offset=k, out=o)
+                profile_unembed(None, None)
+            torch.cuda.synchronize()
+            call_ms = (time.perf_counter() - t) * 1e3 / reps
+            kms = sum(ev.elapsed_ms(a, b) for a, b in prs) / reps
+            byts = inp5.n * inp5.r * inp5.v * inp5.d * 2 + Bd * inp5.d * 2
+            dec.append({"B": Bd, "call_ms": call_ms, "drafts_per_s": Bd / (call_ms * 1e-3),
+                        "k_unembed_ms": kms, "achieved_GBps": byts / (kms * 1e-3) / 1e9,
+                        "frac_of_hbm_peak": byts / (kms * 1e-3) / 1e9 / PEAK_HBM_GBPS})
+        out["decode_cp_r32_n16"] = dec
+
     if not args.no_cpu:
         base, P_cpu = cpu_baseline(inp, min(args.cpu_rows, B), S, seed=0)
         out["cpu_baseline"] = base
