@@ -73,6 +73,23 @@ def sum_layers(layer_logits: np.ndarray) -> np.ndarray:
     return log_softmax(np.asarray(layer_logits, dtype=np.float64), axis=-1)
 
 
+def contextual_layer_logits(h: np.ndarray, R: np.ndarray, bias=None) -> np.ndarray:
+    """Sum-unit parameters computed from the hidden state (Sec. 3.3): the logits
+    of the sum unit (layer l, incoming state k) over its r inputs are R[l,k] e_t,
+    plus an optional input-independent bias (App. HMM setup uses one to start from
+    identity transitions).  R [L,r,r,d], bias [L,r,r] or [r,r] -> logits [B,L,r,r]."""
+    h64 = np.asarray(h, dtype=np.float64)
+    R64 = np.asarray(R, dtype=np.float64)
+    L, r, r2, d = R64.shape
+    out = np.empty((h64.shape[0], L, r, r2), dtype=np.float64)
+    for l in range(L):
+        for k in range(r):
+            out[:, l, k, :] = h64 @ R64[l, k].T
+    if bias is not None:
+        out = out + np.asarray(bias, dtype=np.float64)
+    return out
+
+
 def _layer_view(loglayers: np.ndarray, count: int, B: int) -> np.ndarray:
     """Broadcast log-normalised layers to [B or 1, count, r, r].
 

@@ -254,3 +254,64 @@ def test_logit_memory_matches_the_papers_table(golden_dir):
     for v, r, n, val, u in rows:
         size = oc.logits_bytes(8192, int(n), int(v), int(r)) / unit[u]
         assert abs(size - float(val)) <= 0.051, (v, r, n, size, val)
+
+
+# ------------------------------------------- sum layers computed from the hidden state
+def test_contextual_layer_logits_orientation_and_bias():
+    rng = np.random.default_rng(0)
+    R = rng.standard_normal((3, 2, 2, 5))
+    bias = rng.standard_normal((3, 2, 2))
+    h = np.zeros((2, 5)); h[0, 4] = 1.0; h[1, 1] = 2.0
+    got = oc.contextual_layer_logits(h, R, bias)
+    assert got.shape == (2, 3, 2, 2)
+    assert np.allclose(got[0], R[..., 4] + bias, rtol=0, atol=1e-15)
+    assert np.allclose(got[1], 2.0 * R[..., 1] + bias, rtol=0, atol=1e-15)
+    assert np.array_equal(oc.contextual_layer_logits(h, R), oc.contextual_layer_logits(h, R, np.zeros((2, 2))))
+
+
+@pytest.mark.parametrize("family", ["hmm", "btree"])
+def test_zero_R_with_identity_bias_starts_as_cp(family):
+    """Identity initialisation through a bias makes the deeper circuits equal to CP
+    whatever the hidden state (App. HMM setup)."""
+    n, r, v = 4, 3, 5
+    h, W, Wsum, _ = tiny("cp", n, r, v, B=3, seed=13)
+    L = n - 1 if family == "hmm" else n - 2
+    R = np.zeros((L, r, r, h.shape[1]))
+    bias = np.full((r, r), -np.inf); bias[np.arange(r), np.arange(r)] = 0.0
+    x = np.random.default_rng(5).integers(0, v, size=(3, n))
+    lay = oc.contextual_layer_logits(h, R, bias)
+    assert np.allclose(oc.loglik(family, h, W, Wsum, lay, x), oc.loglik("cp", h, W, Wsum, None, x),
+                       rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("family", ["hmm", "btree"])
+def test_contextual_from_h_equals_enumeration(family):
+    n, r, v = 4, 2, 3
+    h, W, Wsum, _ = tiny("cp", n, r, v, B=3, seed=17)
+    L = n - 1 if family == "hmm" else n - 2
+    rng = np.random.default_rng(2)
+    R = rng.standard_normal((L, r, r, h.shape[1]))
+    bias = rng.standard_normal((L, r, r))
+    lay = oc.contextual_layer_logits(h, R, bias)
+    x = rng.integers(0, v, size=(3, n))
+    ll = oc.loglik(family, h, W, Wsum, lay, x)
+    for b in range(3):
+        phi, omega, _ = tables("cp", h, W, Wsum, None, b)
+        # explicit softmax of this position's own logits R h_b + bias, written out here
+        z = np.einsum("lkjd,d->lkj", R, h[b]) + bias
+        T = np.exp(z - z.max(-1, keepdims=True)); T /= T.sum(-1, keepdims=True)
+        p = bf.prob(family, phi, omega, T, tuple(x[b]))
+        assert abs(ll[b] - np.log(p)) < 1e-12
+
+
+def test_head_parameter_tensors_match_the_papers_head_counts(golden_dir):
+    """With every sum unit parameterised from the hidden state, the head's tensors
+    W [n,r,v,d], Wsum [r,d], R [L,r,r,d] hold the parameter totals the paper prints
+    for d = 4096 (Tab. mtp-circuits-flops, MTP head column)."""
+    rows = [l.split() for l in open(os.path.join(golden_dir, "param_counts.txt"))
+            if l.strip() and not l.startswith("#")]
+    for fam, n, _, head_m in rows:
+        n, r, v, d = int(n), (1 if fam == "ff" else 32), 320, 4096
+        L = {"ff": 0, "cp": 0, "hmm": n - 1, "btree": n - 2}[fam]
+        total = n * r * v * d + (0 if fam == "ff" else r * d) + L * r * r * d
+        assert round(total / 1e6) == int(head_m)
