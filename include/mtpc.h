@@ -64,17 +64,27 @@ typedef struct {
   void* stream;           /* hipStream_t                                                  */
 } mtpc_head;
 
-/* r x r sum layers as PRE-softmax fp32 logits, normalised over the LAST axis.
+/* r x r sum layers, normalised over the LAST axis (softmax), given either as
+ * PRE-softmax fp32 logits or as the contextual parametrisation of Sec. 3.3.
  * HMM (Eq. HMM): L = n-1 transitions, logits[l][j][j'] scores z_{l+2}=j' given
  * z_{l+1}=j.  BTree (Eq. BTree): L = n-2, layer m-1 belongs to the inner node
  * with heap index m >= 1 (root 0, children 2m+1 / 2m+2, the leaf of token i at
  * n-1+i), logits[m-1][k][j] scores z_m=j given the parent's latent k.  A leaf's
  * r input units are indexed by its parent's latent; the root uses omega.
- * -inf logits are allowed (zero weight) as long as each row keeps one finite entry. */
+ * -inf logits are allowed (zero weight) as long as each row keeps one finite entry.
+ *
+ * Contextual layers (Sec. 3.3, sum unit parameters; App. HMM setup): when R is
+ * non-NULL the logits of position b are  R[l][k][j][:] . h[b] + logits[l][k][j],
+ * computed inside the library; `logits` is then the input-independent bias (NULL =
+ * none; an identity bias - 0 on the diagonal, -inf off it - starts the circuit as
+ * CP) and batch_stride must be 0.  R: [L][r][r][d] in the head's dtype, 16-byte
+ * aligned, R_layer_stride = r*r*d, or 0 for one tensor shared by all layers. */
 typedef struct {
   const float* logits;
   int64_t layer_stride;   /* r*r, or 0: one matrix shared by all L layers (homogeneous)   */
   int64_t batch_stride;   /* 0: shared by all positions; else elements between positions  */
+  const void* R;          /* NULL: `logits` are the layer logits themselves               */
+  int64_t R_layer_stride; /* elements between layers of R: r*r*d or 0                      */
 } mtpc_sumlayers;
 
 const char* mtpc_status_string(mtpc_status s);

@@ -62,6 +62,8 @@ class HeadInputs:
     h_bits: Optional[np.ndarray] = None
     W_bits: Optional[np.ndarray] = None
     Wsum_bits: Optional[np.ndarray] = None
+    R: Optional[np.ndarray] = None  # [L, r, r, d]: sum layers computed from h (then `layers` is the bias)
+    R_bits: Optional[np.ndarray] = None
     meta: dict = field(default_factory=dict)
 
 
@@ -111,12 +113,14 @@ def biased_byte_targets(rng, B: int, n: int) -> np.ndarray:
 def make_inputs(family: str, *, B: int, d: int, n: int, r: int, v: int,
                 dtype: str = "bf16", seed: int = 0, h_scale: Optional[float] = None,
                 w_scale: Optional[float] = None, layer_count: Optional[int] = None,
-                targets: str = "uniform", logit_gain: float = 1.0) -> HeadInputs:
+                targets: str = "uniform", logit_gain: float = 1.0,
+                contextual: bool = False) -> HeadInputs:
     """Draw one batch.
 
     h ~ N(0, h_scale^2) (default 1, or 1/sqrt(d) for bf16 workloads as the configs
     state), W, Wsum ~ N(0, 1/d) times ``logit_gain``, static layer logits ~ N(0, 1).
     ``layer_count`` overrides the number of r x r layers (1 = homogeneous HMM).
+    ``contextual`` adds R [L,r,r,d] ~ N(0, 1/d): the layer logits are then R h + layers.
     """
     assert family in FAMILIES
     if family == "ff":
@@ -145,8 +149,11 @@ def make_inputs(family: str, *, B: int, d: int, n: int, r: int, v: int,
         tg = biased_byte_targets(rng, B, n)
     else:
         raise ValueError(targets)
+    R = R_bits = None
+    if contextual and layers is not None:
+        R, R_bits = _gauss(seed, 5, (layers.shape[0], r, r, d), w_scale * logit_gain, bf)
     return HeadInputs(family, dtype, B, d, n, r, v, h, W, Wsum, layers, tg,
-                      h_bits=h_bits, W_bits=W_bits, Wsum_bits=Wsum_bits)
+                      h_bits=h_bits, W_bits=W_bits, Wsum_bits=Wsum_bits, R=R, R_bits=R_bits)
 
 
 # --------------------------------------------------------------------------
@@ -169,6 +176,13 @@ def config3(B: int = 8192, seed: int = 1003) -> HeadInputs:
     """HMM, bf16, d=4096, n=8, r=32, v=320, one shared static 32x32 transition."""
     return make_inputs("hmm", B=B, d=4096, n=8, r=32, v=320, dtype="bf16", seed=seed,
                        targets="biased", layer_count=1)
+
+
+def config3_contextual(B: int = 8192, seed: int = 1013) -> HeadInputs:
+    """The HMM variant the paper trains (App. HMM setup): contextual, inhomogeneous -
+    7 transition layers whose logits are R[l] h + bias[l]; bf16, d=4096, n=8, r=32, v=320."""
+    return make_inputs("hmm", B=B, d=4096, n=8, r=32, v=320, dtype="bf16", seed=seed,
+                       targets="biased", contextual=True)
 
 
 def config4(B: int = 4096, seed: int = 1004) -> HeadInputs:

@@ -34,7 +34,8 @@ class mtpc_head(C.Structure):
 
 
 class mtpc_sumlayers(C.Structure):
-    _fields_ = [("logits", C.c_void_p), ("layer_stride", C.c_int64), ("batch_stride", C.c_int64)]
+    _fields_ = [("logits", C.c_void_p), ("layer_stride", C.c_int64), ("batch_stride", C.c_int64),
+                ("R", C.c_void_p), ("R_layer_stride", C.c_int64)]
 
 
 EXPORTS = [
@@ -92,7 +93,9 @@ class Head:
     """Device-resident parameters of one head plus a reusable workspace."""
 
     def __init__(self, family: str, h: torch.Tensor, W: torch.Tensor, Wsum: Optional[torch.Tensor] = None,
-                 layers: Optional[torch.Tensor] = None):
+                 layers: Optional[torch.Tensor] = None, R: Optional[torch.Tensor] = None):
+        """layers: fp32 logits [L,r,r] / [1,r,r] / [B,L,r,r]; with R ([L,r,r,d] or [1,r,r,d], dtype of h)
+        the layer logits are computed from h inside the library and `layers` (3-dim) is the bias."""
         assert family in FAMILY
         assert h.is_cuda and W.is_cuda and h.dim() == 2 and W.dim() == 4
         assert h.dtype == W.dtype and h.dtype in (torch.float32, torch.bfloat16)
@@ -118,7 +121,18 @@ class Head:
             ls = self.r * self.r if (L == need and need > 0) else 0
             if L == 1 and need > 1:
                 ls = 0
-            self._sl = mtpc_sumlayers(layers.data_ptr(), ls, bs)
+            self._sl = mtpc_sumlayers(layers.data_ptr(), ls, bs, None, 0)
+        self.R = R
+        if R is not None:
+            need = self.n - 1 if family == "hmm" else self.n - 2
+            assert R.is_cuda and R.is_contiguous() and R.dtype == h.dtype and R.dim() == 4
+            assert R.shape[0] in (need, 1) and tuple(R.shape[1:]) == (self.r, self.r, self.d)
+            assert layers is None or layers.dim() == 3
+            rls = self.r * self.r * self.d if (R.shape[0] == need and need > 1) else 0
+            if self._sl is None:
+                self._sl = mtpc_sumlayers(None, 0, 0, R.data_ptr(), rls)
+            else:
+                self._sl.R, self._sl.R_layer_stride = R.data_ptr(), rls
         self._ws = None
 
     # ---- plumbing --------------------------------------------------------

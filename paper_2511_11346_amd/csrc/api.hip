@@ -55,8 +55,16 @@ mtpc_status check_head(int family, const mtpc_head* hd) {
 
 mtpc_status check_layers(int family, const mtpc_head* hd, const mtpc_sumlayers* ly) {
   if (n_layers(family, hd->n) <= 0) return MTPC_OK;
-  if (!ly || !ly->logits) return MTPC_ERR_NULL;
+  if (!ly || (!ly->logits && !ly->R)) return MTPC_ERR_NULL;
   const long long rr = (long long)hd->r * hd->r;
+  if (ly->R != nullptr) {          // contextual: logits (optional) are the bias
+    if (ly->batch_stride != 0) return MTPC_ERR_SHAPE;
+    if (ly->R_layer_stride != 0 && ly->R_layer_stride < rr * hd->d) return MTPC_ERR_SHAPE;
+    if ((uintptr_t)ly->R & 15) return MTPC_ERR_UNSUPPORTED;
+    if (ly->logits && ly->layer_stride != 0 && ly->layer_stride < rr) return MTPC_ERR_SHAPE;
+    return MTPC_OK;
+  }
+  if (!ly->logits) return MTPC_ERR_NULL;
   if (ly->layer_stride != 0 && ly->layer_stride < rr) return MTPC_ERR_SHAPE;
   if (ly->batch_stride < 0) return MTPC_ERR_SHAPE;
   return MTPC_OK;
@@ -67,8 +75,15 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   Plan p{};
   const size_t B = hd->B, n = hd->n, r = hd->r;
   const int L = n_layers(family, hd->n);
-  p.Lst = (L > 0 && ly && ly->layer_stride == 0) ? 1 : L;
-  p.nb = (L > 0 && ly && ly->batch_stride != 0) ? hd->B : 1;
+  const bool ctx = L > 0 && ly && ly->R != nullptr;      // layers computed from h: one set per position
+  if (ctx) {
+    const bool bias_shared = !ly->logits || ly->layer_stride == 0;
+    p.Lst = (ly->R_layer_stride == 0 && bias_shared) ? 1 : L;
+    p.nb = hd->B;
+  } else {
+    p.Lst = (L > 0 && ly && ly->layer_stride == 0) ? 1 : L;
+    p.nb = (L > 0 && ly && ly->batch_stride != 0) ? hd->B : 1;
+  }
   const size_t lay_bytes = L > 0 ? up((size_t)p.nb * p.Lst * r * r * 4) : 0;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
@@ -122,7 +137,16 @@ mtpc_status launch_params(int family, const mtpc_head* hd, const mtpc_sumlayers*
     HIP_TRY(launch_sumunit(hd->h, hd->ld_h, hd->Wsum, hd->B, hd->d, hd->r, hd->dtype,
                            (float*)(ws + p.logw), st));
   const int L = n_layers(family, hd->n);
-  if (L > 0) {
+  if (L > 0 && ly->R != nullptr) {
+    CtxLayerArgs c{};
+    c.h = hd->h; c.ld_h = hd->ld_h; c.R = ly->R; c.R_layer_stride = ly->R_layer_stride;
+    c.bias = ly->logits; c.bias_layer_stride = ly->layer_stride;
+    c.B = hd->B; c.d = hd->d; c.r = hd->r; c.L = p.Lst;
+    // HMM layers are consumed in natural layout everywhere; the BTree contraction wants [j][k]
+    c.out_nat = (nat || (circ && family == MTPC_HMM)) ? (float*)(ws + p.lay_nat) : nullptr;
+    c.out_tr = (circ && family == MTPC_BTREE) ? (float*)(ws + p.lay_circ) : nullptr;
+    if (c.out_nat || c.out_tr) HIP_TRY(launch_ctx_layers(c, hd->dtype, st));
+  } else if (L > 0) {
     if (nat)
       HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, p.nb, p.Lst,
                                       hd->r, 0, (float*)(ws + p.lay_nat), st));

@@ -40,6 +40,21 @@ struct UnivariateArgs {
   float* out;           // [B][n][v]
 };
 
+// Contextual sum layers: P[b][l][k][:] = softmax(R[l][k] h[b] + bias[l][k][:]) as linear
+// probabilities, natural [b][l][k][j] and/or transposed [b][l][j][k] layout.
+struct CtxLayerArgs {
+  const void* h;
+  long long ld_h;
+  const void* R;          // [L][r][r][d]
+  long long R_layer_stride;   // elements, 0 = shared
+  const float* bias;      // [L][r][r] or nullptr
+  long long bias_layer_stride;
+  int B, d, r, L;         // L = layers to produce
+  float* out_nat;         // [B][L][r][r] or nullptr
+  float* out_tr;          // [B][L][r][r] transposed or nullptr
+};
+hipError_t launch_ctx_layers(const CtxLayerArgs& a, int dtype, hipStream_t st);
+
 hipError_t launch_unembed(const UnembedArgs& a, int dtype, hipStream_t st);
 hipError_t launch_univariate(const UnivariateArgs& a, int dtype, hipStream_t st);
 

@@ -103,10 +103,12 @@ __device__ __forceinline__ void load_to_lds(unsigned voff, i32x4_t srd, unsigned
 // Raw buffer resource over [base, base + bytes): reads beyond it return zero.
 __device__ __forceinline__ i32x4_t make_srd(const void* base, unsigned bytes) {
   const unsigned long long a = (unsigned long long)base;
+  // the descriptor must live in scalar registers: base and size are wave-uniform by
+  // construction, readfirstlane makes that visible to the register allocator
   i32x4_t r;
-  r[0] = (int)(unsigned)(a & 0xffffffffull);
-  r[1] = (int)(unsigned)((a >> 32) & 0xffffull);     // stride 0, no swizzle
-  r[2] = (int)bytes;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)(a & 0xffffffffull));
+  r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((a >> 32) & 0xffffull));   // stride 0, no swizzle
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
   r[3] = 0x00020000;                                 // 32-bit data format, raw addressing
   return r;
 }
@@ -575,6 +577,87 @@ hipError_t launch_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, 
                                int dtype, float* logw, hipStream_t st) {
   return dtype == MTPC_BF16 ? launch_sumunit_mfma_dt<true>(h, ld_h, Wsum, B, d, r, logw, st)
                             : launch_sumunit_mfma_dt<false>(h, ld_h, Wsum, B, d, r, logw, st);
+}
+
+// Contextual sum layers (Sec. 3.3, sum unit parameters): every sum unit (layer l,
+// incoming state k) of every position gets its own weights softmax(R[l][k] h[b] +
+// bias[l][k]).  The tile machinery again: a "slab" is one sum unit (r rows of R).
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+__global__ __launch_bounds__(WV * WB * 64)
+void k_ctx_layers(const CtxLayerArgs a) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  constexpr int ESZ = BF16 ? 2 : 4;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wv = wave % WV, wb = wave / WV;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int nslab = a.L * a.r;
+  const int nbt = (a.B + TL::TP - 1) / TL::TP;
+  int slab, bt;
+  tile_of_block(blockIdx.x, nbt, nslab, slab, bt);
+  const int b0 = bt * TL::TP;
+  const int l = slab / a.r, k = slab - l * a.r;
+  const char* Rlk = (const char*)a.R + ((long long)l * a.R_layer_stride + (long long)k * a.r * a.d) * ESZ;
+
+  f32x16_t acc[PB][VB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(Rlk, a.h, a.ld_h, a.B, a.d, a.r, 0, b0, smem, acc);
+  const int rbase = wv * VB * 32 + 4 * lhalf;
+  if (a.bias != nullptr) {
+    const float* bl = a.bias + (long long)l * a.bias_layer_stride + (long long)k * a.r;
+#pragma unroll
+    for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+        const float bv = row < a.r ? bl[row] : 0.f;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) acc[pb][vb][i] += bv;
+      }
+  }
+  float mx[PB], lse[PB];
+  tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.r, (float2*)(smem + TL::RED_OFF), mx, lse);
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) {
+    const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+    if (b >= a.B) continue;
+    const long long base = ((long long)b * a.L + l) * a.r * a.r;
+#pragma unroll
+    for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+        if (row < a.r) {
+          const float p = __expf(acc[pb][vb][i] - lse[pb]);
+          if (a.out_nat) a.out_nat[base + (long long)k * a.r + row] = p;
+          if (a.out_tr) a.out_tr[base + (long long)row * a.r + k] = p;
+        }
+      }
+  }
+}
+
+template <int WV, int WB, int VB, int PB, bool BF16>
+static hipError_t launch_ctx_cfg(const CtxLayerArgs& a, hipStream_t st) {
+  using TL = Tile<WV, WB, VB, PB, 64, 4>;
+  auto kern = k_ctx_layers<WV, WB, VB, PB, 64, 4, BF16>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       TL::SMEM);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int nbt = (a.B + TL::TP - 1) / TL::TP;
+  hipLaunchKernelGGL(kern, dim3(nbt * a.L * a.r), dim3(TL::NT), TL::SMEM, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_ctx_layers(const CtxLayerArgs& a, int dtype, hipStream_t st) {
+  const bool bf = dtype == MTPC_BF16;
+  if (a.B > 64) {     // 64- or 128-row unit tiles x 256 positions
+    if (a.r > 64) return bf ? launch_ctx_cfg<2, 4, 2, 2, true>(a, st) : launch_ctx_cfg<2, 4, 2, 2, false>(a, st);
+    return bf ? launch_ctx_cfg<2, 4, 1, 2, true>(a, st) : launch_ctx_cfg<2, 4, 1, 2, false>(a, st);
+  }
+  return bf ? launch_ctx_cfg<2, 1, 2, 2, true>(a, st) : launch_ctx_cfg<2, 1, 2, 2, false>(a, st);
 }
 
 // Univariate marginals (App. B.1 with every other variable summed out):

@@ -25,7 +25,8 @@ def make_head(inp: mi.HeadInputs, layers=None):
     Wsum = None if inp.Wsum is None else to_dev(inp.Wsum, inp.Wsum_bits if bf else None)
     lay = inp.layers if layers is None else layers
     lay_t = None if lay is None or lay.size == 0 else to_dev(lay.astype(np.float32))
-    return Head(inp.family, h, W, Wsum, lay_t)
+    R = None if inp.R is None else to_dev(inp.R, inp.R_bits if bf else None)
+    return Head(inp.family, h, W, Wsum, lay_t, R=R)
 
 
 def tol_check(got, want, dtype, what=""):

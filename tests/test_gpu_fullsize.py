@@ -27,6 +27,8 @@ def check_rows(inp, head, rows, S=0, seed=0):
     gP = head.prefix_marginals(tg).cpu().numpy()
     gL = head.loglik(tg).cpu().numpy()
     lay = inp.layers
+    if inp.R is not None:            # layers computed from h: R h + bias
+        lay = oc.contextual_layer_logits(inp.h[rows], inp.R, inp.layers)
     logphi, logw, loglayers = oc._params(inp.family, inp.h[rows], inp.W,
                                          inp.Wsum, lay)
     want = oc.prefix_marginals_from(inp.family, logphi, logw, loglayers, inp.targets[rows])
@@ -65,6 +67,13 @@ def test_config3_hmm_full_size():
     rows = np.array([0, 300, inp.B - 1])
     want = oc.univariate_marginals("hmm", inp.h[rows], inp.W, inp.Wsum, inp.layers)
     tol_check(M[rows].cpu().numpy(), want, "bf16", "univariate")
+
+
+def test_config3_contextual_hmm_full_size():
+    """The paper's own HMM variant: every transition computed from the hidden state."""
+    inp = mi.config3_contextual()
+    head = make_head(inp)
+    check_rows(inp, head, sample_rows(inp.B, k=24), S=1, seed=5)
 
 
 def test_config4_btree_full_size():

@@ -197,3 +197,46 @@ def test_strided_hidden_states_and_determinism():
     h2 = Head("cp", wide[:, :64], head.W, head.Wsum)
     assert torch.equal(a, h2.loglik(tg))
     assert torch.equal(a, head.loglik(tg))
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r", [
+    ("hmm", "f32", 70, 64, 4, 5), ("hmm", "bf16", 300, 128, 5, 32), ("btree", "bf16", 130, 64, 8, 16),
+    ("btree", "f32", 33, 32, 4, 70), ("hmm", "bf16", 20, 64, 3, 8),
+])
+def test_sum_layers_computed_from_the_hidden_state(family, dtype, B, d, n, r):
+    """Sec. 3.3 / App. HMM setup: layer logits R[l,k] e_t + bias computed in the library."""
+    from paper_2511_11346_amd import Head
+    v = 64
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=3 * B + r, h_scale=1.0)
+    L = n - 1 if family == "hmm" else n - 2
+    Rv, Rbits = mi._gauss(77, 9, (L, r, r, d), 2.0 / np.sqrt(d), dtype == "bf16")
+    bias = np.random.default_rng(1).standard_normal((L, r, r)).astype(np.float32)
+    bias[:, 0, 1] = -np.inf                       # a forbidden transition through the bias
+    from gpu_util import to_dev
+    base = make_head(inp)
+    head = Head(family, base.h, base.W, base.Wsum, to_dev(bias), R=to_dev(Rv, Rbits))
+    lay = oc.contextual_layer_logits(inp.h, Rv, bias)
+    logphi, logw, loglayers = oc._params(family, inp.h, inp.W, inp.Wsum, lay)
+    tg = torch.from_numpy(inp.targets).cuda()
+    want = oc.prefix_marginals_from(family, logphi, logw, loglayers, inp.targets)
+    tol_check(head.prefix_marginals(tg).cpu().numpy(), want, dtype, "prefix, layers from h")
+    tol_check(head.loglik(tg).cpu().numpy(), want[:, -1], dtype, "loglik, layers from h")
+    S = 2
+    u = philox.uniforms(B, S, n + oc.n_latents(family, n), seed=21)
+    od, ol, margin = oc.sample_from(family, logphi, logw, loglayers, u, with_margin=True)
+    gd, gl, gp = head.sample(S, seed=21, want_prefix=True)
+    near, bad = compare_drafts(gd, gl, od, ol, margin)
+    assert near <= max(4, margin.size // 25)
+    gdn = gd.cpu().numpy()
+    for s in range(S):
+        ps = oc.prefix_marginals_from(family, logphi, logw, loglayers, gdn[:, s])
+        tol_check(gp[:, s].cpu().numpy(), ps, dtype, "draft scores, layers from h")
+    if B <= 70:
+        M = oc.univariate_marginals(family, inp.h, inp.W, inp.Wsum, lay)
+        tol_check(head.univariate_marginals().cpu().numpy(), M, dtype, "univariate, layers from h")
+    # shared R and no bias: one tensor for all layers
+    head2 = Head(family, base.h, base.W, base.Wsum, None, R=to_dev(Rv[:1], None if Rbits is None else Rbits[:1]))
+    lay2 = oc.contextual_layer_logits(inp.h, np.repeat(Rv[:1], L, axis=0))
+    _, _, ll2 = oc._params(family, inp.h, inp.W, inp.Wsum, lay2)
+    tol_check(head2.loglik(tg).cpu().numpy(), oc.joint(family, oc.evidence(logphi, inp.targets), logw, ll2),
+              dtype, "loglik, shared R")
