@@ -185,6 +185,13 @@ def config3_contextual(B: int = 8192, seed: int = 1013) -> HeadInputs:
                        targets="biased", contextual=True)
 
 
+def config_llama_byte(family: str = "cp", n: int = 8, B: int = 2048, seed: int = 1020) -> HeadInputs:
+    """Second model shape of the paper (Tab. model_specs): Llama-3.2-3B-Byte head in
+    fp32, d=3072, v=268 (not a multiple of 32), r=32; B = one 2048-byte context."""
+    return make_inputs(family, B=B, d=3072, n=n, r=32, v=268, dtype="f32", seed=seed,
+                       h_scale=1.0 / np.sqrt(3072), targets="biased")
+
+
 def config4(B: int = 4096, seed: int = 1004) -> HeadInputs:
     """Binary tree, bf16, d=3072, n=16, r=64, v=320, 14 static 64x64 sum layers."""
     return make_inputs("btree", B=B, d=3072, n=16, r=64, v=320, dtype="bf16", seed=seed,

@@ -76,6 +76,14 @@ def test_config3_contextual_hmm_full_size():
     check_rows(inp, head, sample_rows(inp.B, k=24), S=1, seed=5)
 
 
+@pytest.mark.parametrize("family", ["cp", "btree"])
+def test_llama_byte_shape_fp32_ragged_vocabulary(family):
+    """fp32 MFMA path at scale with v = 268 (masked pad rows), d = 3072."""
+    inp = mi.config_llama_byte(family)
+    head = make_head(inp)
+    check_rows(inp, head, sample_rows(inp.B, k=20), S=1, seed=9)
+
+
 def test_config4_btree_full_size():
     inp = mi.config4()
     head = make_head(inp)
