@@ -22,7 +22,27 @@ __device__ __forceinline__ float group_sum(float x, int G) {
   for (int o = G >> 1; o >= 1; o >>= 1) x += __shfl_xor(x, o);
   return x;
 }
+__device__ __forceinline__ int group_min(int x, int G) {
+  for (int o = G >> 1; o >= 1; o >>= 1) x = min(x, __shfl_xor(x, o));
+  return x;
+}
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// First window position of an evidence row e[n][r] whose unit 0 is NaN (n if
+// none).  The lanes of a group probe different positions, eight loads in flight
+// each, so the scan costs one memory round trip instead of n.
+__device__ __forceinline__ int first_nan_position(const float* e, int n, int r, int g, int G) {
+  int fb = n;
+  for (int i0 = 0; i0 < n; i0 += 8 * G) {
+    float t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = e[(long long)min(i0 + u * G + g, n - 1) * r];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (t[u] != t[u]) fb = min(fb, min(i0 + u * G + g, n - 1));
+  }
+  return group_min(fb, G);
+}
 
 // dot of two rows of 8-element (bf16) or 4-element (fp32) 16-byte chunks
 template <bool BF16>
@@ -288,9 +308,7 @@ __global__ __launch_bounds__(256) void k_circuit(const CircuitArgs a, int G, int
     e[0] = stage;
   }
 #pragma unroll
-  for (int q = 0; q < RB; ++q)
-    for (int i = n - 1; i >= 0; --i)
-      if (e[q][i * r] != e[q][i * r]) first_bad[q] = i;
+  for (int q = 0; q < RB; ++q) first_bad[q] = first_nan_position(e[q], n, r, g, G);
   auto emit = [&](int q, int i, float v) {      // value of the prefix ending at token i of row q
     if (g != 0 || row[q] >= a.rows) return;
     if (i >= first_bad[q]) v = __builtin_nanf("");
@@ -420,11 +438,307 @@ static hipError_t launch_circuit_rb(const CircuitArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Binary tree with layers shared by all rows (static A).  The order in which
+// nodes are evaluated does not depend on the data, so a workgroup first writes
+// the evaluation as a short program (one step per sum-layer application) and then
+// all its groups walk that program together: the layer of step t+1 is fetched
+// into LDS while step t is multiplied, and no group waits on global memory for
+// weights.  A group of G lanes owns RB = 4 rows, r <= 64.
+// ---------------------------------------------------------------------------
+struct TreeStep {
+  short m;        // inner node whose layer is applied (0: root, uses log omega instead of a layer)
+  short lsrc;     // left operand: >= 0 heap index of a fully observed child, -1 path value, -2 all-ones
+  short rsrc;     // right operand, same coding
+  short out;      // >= 0: store as full value of node `out`; -1: becomes the path value; -2 - i: emit prefix i
+};
+
+__device__ int build_tree_program(TreeStep* prog, int n, int prefix) {
+  int t = 0;
+  for (int m = n - 2; m >= 1; --m) prog[t++] = TreeStep{(short)m, (short)(2 * m + 1), (short)(2 * m + 2), (short)m};
+  if (!prefix) {
+    prog[t++] = TreeStep{0, 1, 2, (short)(-2 - (n - 1))};
+    return t;
+  }
+  for (int i = 0; i < n; ++i) {
+    int idx = n - 1 + i, size = 1;
+    while (idx > 0) {
+      const int m = (idx - 1) >> 1;
+      size <<= 1;
+      const int first = (m - (n / size - 1)) * size, last = first + size - 1;
+      if (m > 0 && last <= i) { idx = m; continue; }          // fully observed: stored value
+      const int half = size >> 1;
+      const int l_last = first + half - 1, r_first = first + half;
+      const short ls = (l_last <= i) ? (short)(2 * m + 1) : (short)-1;
+      const short rs = (r_first > i) ? (short)-2 : (last <= i ? (short)(2 * m + 2) : (short)-1);
+      prog[t++] = TreeStep{(short)m, ls, rs, (short)(m > 0 ? -1 : -2 - i)};
+      idx = m;
+    }
+  }
+  return t;
+}
+
+// One sum layer for the RB rows of a group with the layer in LDS and one unit per
+// lane (r <= 64):  c[q] <- log sum_j Wl[j][g] exp(c[q][j]).  Lanes g >= r hold -inf.
+template <int RB>
+__device__ __forceinline__ void sum_layer_lds(float (&c)[RB], const float* Wl, float* sh, int g, int r, int G) {
+  float m[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) m[q] = c[q];
+  for (int o = G >> 1; o >= 1; o >>= 1) {        // the RB reductions advance together
+    float t[RB];
+#pragma unroll
+    for (int q = 0; q < RB; ++q) t[q] = __shfl_xor(m[q], o);
+#pragma unroll
+    for (int q = 0; q < RB; ++q) m[q] = fmaxf(m[q], t[q]);
+  }
+  const bool live = g < r;
+  const int gc = live ? g : 0;
+  float ex[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) ex[q] = __expf(c[q] - ((m[q] == neg_inf()) ? 0.f : m[q]));   // exp(-inf) = 0
+  if (live) {
+#pragma unroll
+    for (int q = 0; q < RB; ++q) sh[g * RB + q] = ex[q];
+  }
+  __builtin_amdgcn_wave_barrier();
+  float s[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) s[q] = 0.f;
+  for (int j0 = 0; j0 < r; j0 += 8) {
+    // sixteen LDS reads in flight: eight weights and the eight RB-wide exchange rows
+    float w[8], p[8][RB];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = min(j0 + u, r - 1);
+      w[u] = Wl[j * r + gc];
+#pragma unroll
+      for (int q = 0; q < RB; ++q) p[u][q] = sh[j * RB + q];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float wu = (j0 + u < r) ? w[u] : 0.f;
+#pragma unroll
+      for (int q = 0; q < RB; ++q) s[q] = fmaf(p[u][q], wu, s[q]);
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int q = 0; q < RB; ++q) c[q] = live ? m[q] + __logf(s[q]) : neg_inf();   // -inf + log 0 = -inf
+}
+
+template <int RB>
+__global__ __launch_bounds__(256) void k_btree_static(const CircuitArgs a, int G) {
+  extern __shared__ __align__(16) float bsm[];
+  const int n = a.n, r = a.r;
+  const int groups = 256 / G;
+  const int gl = threadIdx.x / G, g = threadIdx.x % G;
+  const float ninf = neg_inf();
+  const bool live = g < r;
+  const int gc = live ? g : 0;
+  // LDS: [2][r*r] layer ring | per group: RB*r exchange + (n-1)*RB*r node values | program
+  const int rr = r * r;
+  const size_t per_group = (size_t)RB * r * n;
+  float* layer = bsm;
+  float* sh = bsm + 2 * rr + gl * per_group;
+  float* nodes = sh + RB * r;                   // nodes[(m*RB + q)*r + k]
+  TreeStep* prog = (TreeStep*)(bsm + 2 * rr + groups * per_group);
+  __shared__ int s_nsteps;
+  if (threadIdx.x == 0) s_nsteps = build_tree_program(prog, n, a.prefix);
+  __syncthreads();
+  const int nsteps = s_nsteps;
+
+  const long long row0 = ((long long)blockIdx.x * groups + gl) * RB;
+  long long row[RB];
+  const float* e[RB];
+  int first_bad[RB];
+  float lw[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) {
+    row[q] = row0 + q;
+    const long long rc = row[q] < a.rows ? row[q] : a.rows - 1;     // clamped: loads stay in bounds
+    e[q] = a.e + rc * n * r;
+    const float x = a.logw[(rc / a.T) * r + gc];
+    lw[q] = live ? x : ninf;
+    first_bad[q] = first_nan_position(e[q], n, r, g, G);
+  }
+  // leaf operands come from global memory: they are fetched one step ahead
+  float nxl[RB], nxr[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) nxl[q] = nxr[q] = 0.f;
+  auto prefetch = [&](int t) {
+    if (t >= nsteps) return;
+    const TreeStep s = prog[t];
+    if (s.lsrc >= n - 1) {
+#pragma unroll
+      for (int q = 0; q < RB; ++q) nxl[q] = e[q][(s.lsrc - (n - 1)) * r + gc];
+    }
+    if (s.rsrc >= n - 1) {
+#pragma unroll
+      for (int q = 0; q < RB; ++q) nxr[q] = e[q][(s.rsrc - (n - 1)) * r + gc];
+    }
+  };
+  auto operand = [&](int src, const float (&pv)[RB], const float (&pre)[RB], float (&x)[RB]) {
+#pragma unroll
+    for (int q = 0; q < RB; ++q) {
+      float v;
+      if (src == -1) v = pv[q];
+      else if (src == -2) v = 0.f;
+      else if (src >= n - 1) v = pre[q];
+      else v = nodes[((size_t)src * RB + q) * r + gc];
+      x[q] = live ? v : ninf;
+    }
+  };
+  // The layer of step t (transposed layout [j][k], at most 16 floats per thread)
+  // goes to ring slot t & 1 in two halves: loads issued before step t-1 is
+  // evaluated, LDS stores after it, so the loads' latency hides behind that step.
+  const long long lstep = (a.L > 1) ? (long long)rr : 0;
+  float stage[16];
+  auto layer_of = [&](int t) -> const float* {
+    if (t >= nsteps) return nullptr;
+    const int m = prog[t].m;
+    return m == 0 ? nullptr : a.layers + (long long)(m - 1) * lstep;
+  };
+  auto fetch_load = [&](int t) {
+    const float* src = layer_of(t);
+    if (!src) return;
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      if (u * 256 < rr) stage[u] = src[min((int)threadIdx.x + u * 256, rr - 1)];
+  };
+  auto fetch_store = [&](int t) {
+    if (!layer_of(t)) return;
+    float* dst = layer + (t & 1) * rr;
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      if ((int)threadIdx.x + u * 256 < rr) dst[threadIdx.x + u * 256] = stage[u];
+  };
+  fetch_load(0);
+  prefetch(0);
+  fetch_store(0);
+  float pv[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) pv[q] = 0.f;
+  for (int t = 0; t < nsteps; ++t) {
+    __syncthreads();             // layer t is complete in slot t & 1; slot (t+1) & 1 is no longer read
+    const TreeStep st = prog[t];
+    float c[RB];
+    {
+      float lv[RB], rv[RB];
+      operand(st.lsrc, pv, nxl, lv);
+      operand(st.rsrc, pv, nxr, rv);
+#pragma unroll
+      for (int q = 0; q < RB; ++q) c[q] = lv[q] + rv[q];
+    }
+    fetch_load(t + 1);
+    prefetch(t + 1);
+    if (st.m == 0) {             // root: mixture with log omega
+      const int i = -2 - st.out;
+      float x[RB], m[RB], s[RB];
+#pragma unroll
+      for (int q = 0; q < RB; ++q) m[q] = x[q] = c[q] + lw[q];
+      for (int o = G >> 1; o >= 1; o >>= 1) {
+        float tt[RB];
+#pragma unroll
+        for (int q = 0; q < RB; ++q) tt[q] = __shfl_xor(m[q], o);
+#pragma unroll
+        for (int q = 0; q < RB; ++q) m[q] = fmaxf(m[q], tt[q]);
+      }
+#pragma unroll
+      for (int q = 0; q < RB; ++q) s[q] = (live && m[q] != ninf) ? __expf(x[q] - m[q]) : 0.f;
+      for (int o = G >> 1; o >= 1; o >>= 1) {
+        float tt[RB];
+#pragma unroll
+        for (int q = 0; q < RB; ++q) tt[q] = __shfl_xor(s[q], o);
+#pragma unroll
+        for (int q = 0; q < RB; ++q) s[q] += tt[q];
+      }
+#pragma unroll
+      for (int q = 0; q < RB; ++q) {
+        float v = (m[q] == ninf) ? ninf : m[q] + __logf(s[q]);
+        if (g == 0 && row[q] < a.rows) {
+          if (i >= first_bad[q]) v = __builtin_nanf("");
+          if (a.prefix) a.out[row[q] * n + i] = v; else a.out[row[q]] = v;
+        }
+      }
+    } else {
+      sum_layer_lds<RB>(c, layer + (t & 1) * rr, sh, g, r, G);
+      if (st.out >= 0) {
+        if (live) {
+#pragma unroll
+          for (int q = 0; q < RB; ++q) nodes[((size_t)st.out * RB + q) * r + g] = c[q];
+        }
+        __builtin_amdgcn_wave_barrier();
+      } else {
+#pragma unroll
+        for (int q = 0; q < RB; ++q) pv[q] = c[q];
+      }
+    }
+    fetch_store(t + 1);
+  }
+}
+
+static int tree_program_steps(int n, int prefix) {
+  if (!prefix) return n - 2 + 1;
+  int lg = 0;
+  while ((1 << lg) < n) ++lg;
+  return n - 2 + n * lg;          // upper bound: at most log2(n) steps per prefix
+}
+
+#ifndef MTPC_BTREE_RB
+#define MTPC_BTREE_RB 0           // 0: chosen from the row count
+#endif
+
+// rows per group of the program-driven tree kernel: 4 when that still gives every CU
+// two workgroups, else 2 (twice the workgroups, half the LDS each)
+static int btree_static_rb(const CircuitArgs& a) {
+  if (MTPC_BTREE_RB) return MTPC_BTREE_RB;
+  int G = 1;
+  while (G < a.r && G < 64) G <<= 1;
+  return a.rows >= 4ll * (256 / G) * 512 ? 4 : 2;
+}
+
+// LDS the program-driven tree kernel needs (0: shape not supported by it)
+static size_t btree_static_smem(const CircuitArgs& a) {
+  if (a.r > 64) return 0;
+  int G = 1;
+  while (G < a.r && G < 64) G <<= 1;
+  const int groups = 256 / G;
+  return (2ull * a.r * a.r + (size_t)groups * btree_static_rb(a) * a.r * a.n) * 4 +
+         (size_t)tree_program_steps(a.n, a.prefix) * sizeof(TreeStep);
+}
+
+static hipError_t launch_btree_static(const CircuitArgs& a, hipStream_t st) {
+  int G = 1;
+  while (G < a.r && G < 64) G <<= 1;
+  const int groups = 256 / G;
+  const int RB = btree_static_rb(a);
+  const size_t smem = btree_static_smem(a);
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)k_btree_static<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            160 * 1024 - 64) != hipSuccess ||
+        hipFuncSetAttribute((const void*)k_btree_static<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            160 * 1024 - 64) != hipSuccess)
+      return hipErrorInvalidValue;
+    attr_done = true;
+  }
+  const long long ngroups = ((long long)a.rows + RB - 1) / RB;
+  const dim3 grid((unsigned)((ngroups + groups - 1) / groups));
+  if (RB == 4) hipLaunchKernelGGL(k_btree_static<4>, grid, dim3(256), smem, st, a, G);
+  else hipLaunchKernelGGL(k_btree_static<2>, grid, dim3(256), smem, st, a, G);
+  return hipGetLastError();
+}
+
 hipError_t launch_circuit(const CircuitArgs& a, hipStream_t st) {
   // batching rows pays when sum layers are shared and there are rows to batch;
   // the batched BTree node store must still fit one group into 48 KiB of LDS
   // (measured: the tree's many dependent node evaluations gain from sharing weight
   // loads; the HMM chain prefers more, narrower groups)
+  if (a.family == MTPC_BTREE && !a.contextual && a.n > 2 && a.rows >= 256) {
+    const size_t need = btree_static_smem(a);
+    if (need != 0 && need <= 150 * 1024) return launch_btree_static(a, st);
+  }
   const size_t one_group4 = 4ull * 4 * (a.r + (size_t)(a.n - 1) * a.r);
   if (a.family == MTPC_BTREE && !a.contextual && a.rows >= 1024 && one_group4 <= 48 * 1024)
     return launch_circuit_rb<4>(a, st);

@@ -403,8 +403,8 @@ void k_unembed(const UnembedArgs a) {
   float mx[PB], lse[PB];
   tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 
-  // evidence at the target tokens
-  if (a.targets != nullptr) {
+  // evidence at the target tokens (the sampling instantiation never has targets)
+  if constexpr (!SAMPLE) if (a.targets != nullptr) {
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {
       const int b = b0 + wb * PB * 32 + pb * 32 + l31;
