@@ -1,0 +1,108 @@
+"""CPU oracle for the verification half of a speculative-decoding cycle:
+TEST INFRASTRUCTURE, not a product path (same rules as mtpc_oracle.py).
+
+Follows the accept / reject part of Alg. 2 (speculative sampling with a circuit
+as the draft model) step by step in float64, and the greedy variant the paper
+evaluates next to it (Sec. 3.4: a draft token survives iff it is the verifier's
+argmax).  The conditional of the draft model is taken from its definition, a
+ratio of two prefix marginals, for every candidate token: no message passing,
+no reuse of anything the HIP library does.
+
+Random numbers are inputs: ``u`` [B, n+1]; slot s < n is the alpha of the s-th
+acceptance test, slot n drives the single token drawn at the end.
+
+Parity status: pinned by tests/test_oracle_speculative.py (normalisation and
+chain rule of the conditionals, brute-force suffix enumeration, the
+distribution-preservation property of speculative sampling measured on a tiny
+autoregressive verifier, exact acceptance when verifier == draft model, the
+greedy chain).  Nothing here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import mtpc_oracle as oc
+
+
+def conditional_next(family, logphi_b, logw_b, loglayers_b, tokens, j) -> np.ndarray:
+    """log q(X_{j+1} = a | x_1..x_j) for every a (0-based position j), Alg. 2:
+    q(x_1..x_j, a) / q(x_1..x_j), both prefix marginals (later positions summed out).
+
+    logphi_b [n,r,v], logw_b [r] or None, loglayers_b [L,r,r] or None: one position's circuit."""
+    n, r, v = logphi_b.shape
+    e = np.zeros((v, n, r))
+    for i in range(j):
+        e[:, i, :] = logphi_b[i, :, tokens[i]][None, :]
+    e_den = e[:1].copy()                                   # position j summed out as well
+    e[:, j, :] = logphi_b[j].T                             # candidate a at position j
+    lw = None if logw_b is None else np.asarray(logw_b)[None, :]
+    num = oc.joint(family, e, lw, loglayers_b)
+    den = oc.joint(family, e_den, lw, loglayers_b)
+    return num - den[0]
+
+
+def draw_linear(w: np.ndarray, u: float):
+    """Inverse-CDF draw from non-negative weights w / sum(w): smallest k with
+    u < cdf[k] (ascending index order), else the largest k with w[k] > 0.
+    Also returns min_k |u - cdf[k]|."""
+    p = np.asarray(w, dtype=np.float64)
+    p = p / p.sum()
+    cdf = np.cumsum(p)
+    margin = float(np.min(np.abs(cdf - u)))
+    hit = np.nonzero(u < cdf)[0]
+    if hit.size:
+        return int(hit[0]), margin
+    return int(np.nonzero(p > 0)[0][-1]), margin
+
+
+def residual(p_next: np.ndarray, q_next: np.ndarray):
+    """Alg. 2, adjusted distribution after a rejection: max(0, p - q) / Z.
+    Z == 0 only if p == q, where a rejection has probability zero; then p itself."""
+    m = np.maximum(0.0, p_next - q_next)
+    Z = m.sum()
+    return (m / Z) if Z > 0 else p_next
+
+
+def speculative_verify(family, logphi, logw, loglayers, drafts, p, u, mode="sampling"):
+    """One verification per position b (Alg. 2 from the acceptance loop on).
+
+    drafts [B,n] int; p [B,n+1,v] verifier probabilities p(X_{t+i} | x_{<=t+i-1})
+    evaluated along the draft; u [B,n+1] uniforms.
+    Returns accepted [B] (s in 0..n), token [B] (the token emitted after the s
+    accepted ones), and margin [B]: the smallest distance of any decision taken
+    for that row from its boundary (|alpha - p/q| of the tests, |u - cdf| of the
+    final draw; inf in greedy mode)."""
+    B, n, r, v = logphi.shape
+    assert drafts.shape == (B, n) and p.shape == (B, n + 1, v) and u.shape == (B, n + 1)
+    accepted = np.zeros(B, dtype=np.int32)
+    token = np.zeros(B, dtype=np.int32)
+    margin = np.full(B, np.inf)
+    P = oc.prefix_marginals_from(family, logphi, logw, loglayers, drafts)
+    for b in range(B):
+        s = 0
+        if mode == "greedy":
+            while s < n and drafts[b, s] == int(np.argmax(p[b, s])):
+                s += 1
+            accepted[b], token[b] = s, int(np.argmax(p[b, s]))
+            continue
+        while s < n:
+            alpha = u[b, s]
+            logq = P[b, s] - (P[b, s - 1] if s > 0 else 0.0)      # conditional of the drafted token
+            ratio = p[b, s, drafts[b, s]] / np.exp(logq)
+            margin[b] = min(margin[b], abs(alpha - ratio))
+            if alpha > ratio:
+                break
+            s += 1
+        if s < n:
+            lay = None
+            if loglayers is not None:
+                lay = loglayers[b] if loglayers.ndim == 4 else loglayers
+            q_next = np.exp(conditional_next(family, logphi[b], None if logw is None else logw[b],
+                                             lay, drafts[b], s))
+            dist = residual(p[b, s], q_next)
+        else:
+            dist = p[b, n]
+        tok, mg = draw_linear(dist, u[b, n])
+        margin[b] = min(margin[b], mg)
+        accepted[b], token[b] = s, tok
+    return accepted, token, margin

@@ -1,0 +1,155 @@
+"""Pins for the oracle of the verification step (Alg. 2, acceptance loop and the
+adjusted distribution), no GPU.
+
+The conditionals are checked against a dense joint table built by brute-force
+latent enumeration, the accept / reject rule against hand-computed cases, and
+the whole procedure against the property that defines speculative sampling:
+every emitted token is distributed as the autoregressive verifier's conditional
+given the tokens emitted before it."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import bruteforce as bf
+from oracle import mtpc_oracle as oc
+from oracle import speculative as sp
+
+from test_oracle_circuits import tables, tiny
+
+FAMS = ("ff", "cp", "hmm", "btree")
+
+
+def circuit(family, n, r, v, seed):
+    h, W, Wsum, layers = tiny(family, n, r, v, B=1, seed=seed)
+    logphi, logw, loglayers = oc._params(family, h, W, Wsum, layers)
+    return (h, W, Wsum, layers), logphi, logw, loglayers
+
+
+@pytest.mark.parametrize("family", FAMS)
+def test_conditionals_match_the_dense_joint_table(family):
+    n, r, v = 4, 3, 3
+    raw, logphi, logw, loglayers = circuit(family, n, r, v, seed=11)
+    tab = bf.joint_table(family, *tables(family, *raw, 0))
+    rng = np.random.default_rng(0)
+    for _ in range(6):
+        x = rng.integers(0, v, size=n)
+        for j in range(n):
+            sub = tab[tuple(x[:j])]                       # q(x_<j, X_j, ...)
+            num = sub.reshape(v, -1).sum(axis=1) if j < n - 1 else sub
+            want = num / num.sum()
+            got = np.exp(sp.conditional_next(family, logphi[0], None if logw is None else logw[0],
+                                             loglayers, x, j))
+            np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-13)
+
+
+@pytest.mark.parametrize("family", FAMS)
+def test_conditionals_normalise_and_multiply_to_the_joint(family):
+    n, r, v = 8, 4, 5
+    raw, logphi, logw, loglayers = circuit(family, n, r, v, seed=5)
+    x = np.random.default_rng(3).integers(0, v, size=n)
+    total = 0.0
+    for j in range(n):
+        c = sp.conditional_next(family, logphi[0], None if logw is None else logw[0], loglayers, x, j)
+        assert abs(np.exp(c).sum() - 1.0) < 1e-12
+        total += c[x[j]]
+    want = oc.joint(family, oc.evidence(logphi, x[None, :]), logw, loglayers)[0]
+    assert abs(total - want) < 1e-10
+
+
+def one_position_ff(q):
+    """An FF 'circuit' over one token with distribution q (n = 1, r = 1)."""
+    return np.log(np.asarray(q, dtype=np.float64))[None, None, None, :]
+
+
+def test_acceptance_threshold_and_adjusted_distribution_by_hand():
+    q = [0.2, 0.5, 0.3]
+    p = np.array([[[0.5, 0.3, 0.2], [0.1, 0.1, 0.8]]])      # [B=1, n+1=2, v]
+    logphi = one_position_ff(q)
+    # drafted token 1: p/q = 0.6.  alpha = 0.59 accepts and the extra token comes from p[1]
+    acc, tok, _ = sp.speculative_verify("ff", logphi, None, None, np.array([[1]]), p, np.array([[0.59, 0.15]]))
+    assert (acc[0], tok[0]) == (1, 1)            # cdf of p[1] = .1 .2 1. -> u = .15 is token 1
+    # alpha = 0.61 rejects; max(0, p - q) = [.3, 0, 0] -> token 0 whatever u is
+    for u_last in (0.0, 0.5, 0.999):
+        acc, tok, _ = sp.speculative_verify("ff", logphi, None, None, np.array([[1]]), p, np.array([[0.61, u_last]]))
+        assert (acc[0], tok[0]) == (0, 0)
+    # drafted token 0: p/q = 2.5 > 1 is always accepted
+    acc, tok, _ = sp.speculative_verify("ff", logphi, None, None, np.array([[0]]), p, np.array([[0.9999, 0.25]]))
+    assert (acc[0], tok[0]) == (1, 2)
+    # two-token residual: p = [.1,.6,.3], q = [.2,.5,.3] -> m = [0,.1,0] / .1
+    p2 = np.array([[[0.1, 0.6, 0.3], [1 / 3, 1 / 3, 1 / 3]]])
+    acc, tok, _ = sp.speculative_verify("ff", logphi, None, None, np.array([[0]]), p2, np.array([[0.51, 0.7]]))
+    assert (acc[0], tok[0]) == (0, 1)            # p/q = 0.5 < alpha
+    np.testing.assert_allclose(sp.residual(np.array([0.5, 0.3, 0.2]), np.array([0.2, 0.5, 0.3])), [1, 0, 0])
+    np.testing.assert_allclose(sp.residual(np.array([0.6, 0.1, 0.3]), np.array([0.2, 0.2, 0.6])), [1, 0, 0])
+    np.testing.assert_allclose(sp.residual(np.array([0.5, 0.4, 0.1]), np.array([0.3, 0.2, 0.5])), [0.5, 0.5, 0])
+
+
+def ar_tables(n, v, seed):
+    """A tiny autoregressive verifier: T[k][prefix] = p(X_{k+1} | prefix), k = 0..n."""
+    rng = np.random.default_rng(seed)
+    return [rng.dirichlet(np.ones(v) * 1.5, size=(v,) * k) for k in range(n + 1)]
+
+
+@pytest.mark.parametrize("family,n", [("ff", 3), ("cp", 3), ("hmm", 3), ("btree", 4)])
+def test_emitted_tokens_follow_the_verifier(family, n):
+    """Speculative sampling leaves the verifier's distribution unchanged: given
+    the tokens emitted so far in a cycle, the next emitted one (an accepted draft
+    token, the adjusted draw after a rejection, or the bonus draw) is a draw from
+    p(. | those tokens).  Measured over many independent cycles of one circuit."""
+    r, v, N = 3, 3, 24000
+    raw, logphi, logw, loglayers = circuit(family, n, r, v, seed=21)
+    T = ar_tables(n, v, seed=4)
+    rng = np.random.default_rng(99)
+    nl = oc.n_latents(family, n)
+    phiN = np.broadcast_to(logphi, (N,) + logphi.shape[1:])
+    lwN = None if logw is None else np.broadcast_to(logw, (N, logw.shape[1]))
+    drafts = oc.sample_from(family, phiN, lwN, loglayers, rng.random((N, 1, n + nl)))[0][:, 0]
+    p = np.empty((N, n + 1, v))
+    for k in range(n + 1):
+        p[:, k] = T[k][tuple(drafts[:, i] for i in range(k))] if k else T[0]
+    acc, tok, _ = sp.speculative_verify(family, phiN, lwN, loglayers, drafts, p, rng.random((N, n + 1)))
+    assert set(np.unique(acc)) == set(range(n + 1))           # every outcome occurs
+    for k in range(n + 1):
+        rows = np.nonzero(acc >= k)[0]                        # k tokens accepted before this one
+        emitted = np.where(acc[rows] > k, drafts[rows, min(k, n - 1)], tok[rows])
+        cond = T[k][tuple(drafts[rows, i] for i in range(k))] if k else np.broadcast_to(T[0], (len(rows), v))
+        expect = cond.sum(axis=0)
+        counts = np.bincount(emitted, minlength=v)
+        assert np.all(np.abs(counts - expect) <= 4.5 * np.sqrt(0.25 * len(rows)) + 1), (k, counts, expect)
+
+
+@pytest.mark.parametrize("family", FAMS)
+def test_verifier_equal_to_the_draft_model_accepts_every_token(family):
+    n, r, v, B = 4, 3, 4, 5
+    h, W, Wsum, layers = tiny(family, n, r, v, B=B, seed=8)
+    logphi, logw, loglayers = oc._params(family, h, W, Wsum, layers)
+    rng = np.random.default_rng(1)
+    drafts = rng.integers(0, v, size=(B, n))
+    p = np.empty((B, n + 1, v))
+    for b in range(B):
+        for j in range(n):
+            p[b, j] = np.exp(sp.conditional_next(family, logphi[b], None if logw is None else logw[b],
+                                                 loglayers, drafts[b], j))
+        p[b, n] = rng.dirichlet(np.ones(v))
+    u = rng.random((B, n + 1)) * (1 - 1e-9)
+    acc, tok, _ = sp.speculative_verify(family, logphi, logw, loglayers, drafts, p, u)
+    assert np.all(acc == n)
+    for b in range(B):
+        assert tok[b] == int(np.searchsorted(np.cumsum(p[b, n]), u[b, n], side="right"))
+
+
+def test_greedy_mode_keeps_the_longest_argmax_prefix():
+    n, v, B = 4, 5, 4
+    h, W, Wsum, layers = tiny("cp", n, 3, v, B=B, seed=2)
+    logphi, logw, loglayers = oc._params("cp", h, W, Wsum, layers)
+    rng = np.random.default_rng(5)
+    p = rng.dirichlet(np.ones(v), size=(B, n + 1))
+    best = p.argmax(axis=-1)
+    drafts = best[:, :n].copy()
+    drafts[1, 2] = (drafts[1, 2] + 1) % v         # mismatch at position 2
+    drafts[2, 0] = (drafts[2, 0] + 2) % v         # mismatch at once
+    drafts[3, 3] = (drafts[3, 3] + 1) % v
+    acc, tok, _ = sp.speculative_verify("cp", logphi, logw, loglayers, drafts, p, np.zeros((B, n + 1)), mode="greedy")
+    assert list(acc) == [4, 2, 0, 3]
+    assert list(tok) == [best[0, 4], best[1, 2], best[2, 0], best[3, 3]]
