@@ -48,8 +48,9 @@ typedef enum {
 
 typedef enum { MTPC_F32 = 0, MTPC_BF16 = 1 } mtpc_dtype;
 typedef enum { MTPC_FF = 0, MTPC_CP = 1, MTPC_HMM = 2, MTPC_BTREE = 3 } mtpc_family;
-typedef enum { MTPC_OP_LOGLIK = 0, MTPC_OP_MARGINALS = 1, MTPC_OP_SAMPLE = 2 } mtpc_op;
+typedef enum { MTPC_OP_LOGLIK = 0, MTPC_OP_MARGINALS = 1, MTPC_OP_SAMPLE = 2, MTPC_OP_VERIFY = 3 } mtpc_op;
 typedef enum { MTPC_MARG_PREFIX = 0, MTPC_MARG_UNIVARIATE = 1 } mtpc_marg_mode;
+typedef enum { MTPC_VERIFY_SAMPLING = 0, MTPC_VERIFY_GREEDY = 1 } mtpc_verify_mode;
 
 /* Common description of one call (Sec. 3.3). */
 typedef struct {
@@ -127,17 +128,56 @@ mtpc_status mtpc_btree_marginals(const mtpc_head* head, const mtpc_sumlayers* A,
  *   drafts      [B][S][n] int32 (required)
  *   latents     [B][S][n_lat] int32 or NULL; n_lat = 0 (FF), 1 (CP), n (HMM), n-1 (BTree)
  *   prefix_logq [B][S][n] fp32 or NULL: prefix marginals of each draft (as
- *               MTPC_MARG_PREFIX with the draft as target). */
+ *               MTPC_MARG_PREFIX with the draft as target).
+ *   logphi      [B][n][r][v] fp32 or NULL: the normalised input units
+ *               log phi[b,i,j,:] = log softmax(W[i,j] h[b]) of every position, kept
+ *               for the verification step (mtpc_*_verify). */
 mtpc_status mtpc_ff_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,
-                           int32_t* drafts, int32_t* latents, float* prefix_logq);
+                           int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi);
 mtpc_status mtpc_cp_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,
-                           int32_t* drafts, int32_t* latents, float* prefix_logq);
+                           int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi);
 mtpc_status mtpc_hmm_sample(const mtpc_head* head, const mtpc_sumlayers* T, int32_t S,
                             uint64_t seed, uint32_t offset,
-                            int32_t* drafts, int32_t* latents, float* prefix_logq);
+                            int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi);
 mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, int32_t S,
                               uint64_t seed, uint32_t offset,
-                              int32_t* drafts, int32_t* latents, float* prefix_logq);
+                              int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi);
+
+/* Verification step of one speculative-decoding cycle (Alg. 2 from the
+ * acceptance loop on; greedy variant of Sec. 3.4), one draft per position.
+ * Inputs (device): logphi [B][n][r][v] as written by mtpc_*_sample for the same
+ * head; drafts [B][n] int32 in [0, v); prefix_logq [B][n] their prefix
+ * marginals; p [B][n+1][v] fp32 verifier probabilities p(X_{t+i} | x_{<=t+i-1})
+ * evaluated along the draft (rows sum to 1).
+ * MTPC_VERIFY_SAMPLING: token s+1 is accepted unless alpha_s > p(x_{s+1}) /
+ *   q(x_{s+1} | x_{<=s}), the conditional being exp(prefix_logq[s] -
+ *   prefix_logq[s-1]); after the first rejection at position s one token is
+ *   drawn from max(0, p[s] - q(. | x_{<=s})) / Z, where q(. | x_{<=s}) is the
+ *   circuit's exact conditional over the whole vocabulary (if Z == 0, i.e.
+ *   p == q, from p[s]); if all n are accepted the token is drawn from p[n].
+ *   Uniforms: Philox as in mtpc_*_sample with s = 0 and slots 0..n-1 = alpha,
+ *   slot n = the final draw; pass an `offset` (or seed) different from the one
+ *   that drew the draft.
+ * MTPC_VERIFY_GREEDY: token s+1 is accepted iff it is argmax p[s] (ties: the
+ *   smallest id); the emitted token is argmax p[accepted]; seed, offset, logphi
+ *   and prefix_logq are unused and may be 0 / NULL.
+ * Outputs: accepted [B] int32 in 0..n, token [B] int32: the token that follows
+ * the accepted ones.  (A caller that shares the backbone state between draft and
+ * verifier drops `token` whenever accepted > 0, App. speculative decoding.) */
+mtpc_status mtpc_ff_verify(const mtpc_head* head, const float* logphi, const int32_t* drafts,
+                           const float* prefix_logq, const float* p, int32_t mode, uint64_t seed,
+                           uint32_t offset, int32_t* accepted, int32_t* token);
+mtpc_status mtpc_cp_verify(const mtpc_head* head, const float* logphi, const int32_t* drafts,
+                           const float* prefix_logq, const float* p, int32_t mode, uint64_t seed,
+                           uint32_t offset, int32_t* accepted, int32_t* token);
+mtpc_status mtpc_hmm_verify(const mtpc_head* head, const mtpc_sumlayers* T, const float* logphi,
+                            const int32_t* drafts, const float* prefix_logq, const float* p,
+                            int32_t mode, uint64_t seed, uint32_t offset, int32_t* accepted,
+                            int32_t* token);
+mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, const float* logphi,
+                              const int32_t* drafts, const float* prefix_logq, const float* p,
+                              int32_t mode, uint64_t seed, uint32_t offset, int32_t* accepted,
+                              int32_t* token);
 
 /* The uniforms the sampler consumes, out [B][S][slots] fp32 (device), for tests
  * of the generator and its slot map. */

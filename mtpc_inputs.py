@@ -202,3 +202,14 @@ def config5(B: int = 64, seed: int = 1005) -> HeadInputs:
     """Decode-shaped CP, bf16, r=32, d=4096, n=16, v=320, B in {1, 8, 64}."""
     return make_inputs("cp", B=B, d=4096, n=16, r=32, v=320, dtype="bf16", seed=seed,
                        targets="biased")
+
+
+def verifier_noise(B: int, n: int, v: int, seed: int, peak: float = 3.0) -> np.ndarray:
+    """Random categorical tables [B, n+1, v] (float64, rows sum to 1): softmax of
+    peak * N(0,1) logits.  Raw material for synthetic verifier distributions of
+    the speculative-decoding step; the tests and the bench mix it with the draft
+    model's own conditionals to get a spread of acceptance lengths."""
+    g = np.random.default_rng([seed, 77]).standard_normal((B, n + 1, v)) * peak
+    g -= g.max(axis=-1, keepdims=True)
+    p = np.exp(g)
+    return p / p.sum(axis=-1, keepdims=True)

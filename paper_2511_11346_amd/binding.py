@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libmtpc.so")
 
 FF, CP, HMM, BTREE = 0, 1, 2, 3
 FAMILY = {"ff": FF, "cp": CP, "hmm": HMM, "btree": BTREE}
-OP_LOGLIK, OP_MARGINALS, OP_SAMPLE = 0, 1, 2
+OP_LOGLIK, OP_MARGINALS, OP_SAMPLE, OP_VERIFY = 0, 1, 2, 3
+VERIFY_SAMPLING, VERIFY_GREEDY = 0, 1
 MARG_PREFIX, MARG_UNIVARIATE = 0, 1
 F32, BF16 = 0, 1
 
@@ -43,6 +44,7 @@ EXPORTS = [
     "mtpc_ff_loglik", "mtpc_cp_loglik", "mtpc_hmm_loglik", "mtpc_btree_loglik",
     "mtpc_ff_marginals", "mtpc_cp_marginals", "mtpc_hmm_marginals", "mtpc_btree_marginals",
     "mtpc_ff_sample", "mtpc_cp_sample", "mtpc_hmm_sample", "mtpc_btree_sample",
+    "mtpc_ff_verify", "mtpc_cp_verify", "mtpc_hmm_verify", "mtpc_btree_verify",
     "mtpc_philox_uniforms", "mtpc_profile_unembed",
 ]
 
@@ -64,11 +66,13 @@ def lib() -> C.CDLL:
         for fam in ("ff", "cp"):
             getattr(L, f"mtpc_{fam}_loglik").argtypes = [hp, ip, fp]
             getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, ip, C.c_int32, fp]
-            getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp]
+            getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
+            getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
         for fam in ("hmm", "btree"):
             getattr(L, f"mtpc_{fam}_loglik").argtypes = [hp, lp, ip, fp]
             getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, lp, ip, C.c_int32, fp]
-            getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, lp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp]
+            getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, lp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
+            getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, lp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
         L.mtpc_philox_uniforms.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
                                            fp, C.c_void_p]
         L.mtpc_profile_unembed.argtypes = [C.c_void_p, C.c_void_p]
@@ -190,8 +194,9 @@ class Head:
         return out
 
     def sample(self, S: int, seed: int, offset: int = 0, want_latents: bool = True,
-               want_prefix: bool = False, out=None):
-        """Returns (drafts [B,S,n] int32, latents [B,S,n_lat] int32 or None, prefix_logq [B,S,n] or None)."""
+               want_prefix: bool = False, out=None, logphi: Optional[torch.Tensor] = None):
+        """Returns (drafts [B,S,n] int32, latents [B,S,n_lat] int32 or None, prefix_logq [B,S,n] or None).
+        logphi: optional fp32 [B,n,r,v] buffer that receives the normalised input units (for verify)."""
         dev = self.h.device
         if out is None:
             drafts = torch.empty(self.B, S, self.n, dtype=torch.int32, device=dev)
@@ -203,8 +208,37 @@ class Head:
         hd = self._head(self.workspace_bytes(OP_SAMPLE, S=S))
         _check(self._call("sample", hd, S, seed, offset, drafts.data_ptr(),
                           lat.data_ptr() if lat is not None and lat.numel() > 0 else None,
-                          pl.data_ptr() if pl is not None else None))
+                          pl.data_ptr() if pl is not None else None,
+                          self._phi_ptr(logphi)))
         return drafts, lat, pl
+
+    def _phi_ptr(self, logphi):
+        if logphi is None:
+            return None
+        assert logphi.is_cuda and logphi.dtype == torch.float32 and logphi.is_contiguous()
+        assert tuple(logphi.shape) == (self.B, self.n, self.r, self.v)
+        return logphi.data_ptr()
+
+    def verify(self, drafts: torch.Tensor, p: torch.Tensor, prefix_logq: Optional[torch.Tensor] = None,
+               logphi: Optional[torch.Tensor] = None, seed: int = 0, offset: int = 0, mode: str = "sampling"):
+        """One verification per position: drafts [B,n] int32, p [B,n+1,v] fp32 verifier probabilities,
+        prefix_logq [B,n] and logphi [B,n,r,v] from sample().  Returns (accepted [B], token [B]) int32."""
+        dev = self.h.device
+        assert drafts.is_cuda and drafts.dtype == torch.int32 and drafts.is_contiguous()
+        assert tuple(drafts.shape) == (self.B, self.n)
+        assert p.is_cuda and p.dtype == torch.float32 and p.is_contiguous()
+        assert tuple(p.shape) == (self.B, self.n + 1, self.v)
+        if prefix_logq is not None:
+            assert prefix_logq.is_cuda and prefix_logq.dtype == torch.float32 and prefix_logq.is_contiguous()
+            assert tuple(prefix_logq.shape) == (self.B, self.n)
+        accepted = torch.empty(self.B, dtype=torch.int32, device=dev)
+        token = torch.empty(self.B, dtype=torch.int32, device=dev)
+        hd = self._head(self.workspace_bytes(OP_VERIFY))
+        _check(self._call("verify", hd, self._phi_ptr(logphi), drafts.data_ptr(),
+                          prefix_logq.data_ptr() if prefix_logq is not None else None, p.data_ptr(),
+                          {"sampling": VERIFY_SAMPLING, "greedy": VERIFY_GREEDY}[mode], seed, offset,
+                          accepted.data_ptr(), token.data_ptr()))
+        return accepted, token
 
 
 def philox_uniforms(B: int, S: int, slots: int, seed: int, offset: int = 0, device="cuda") -> torch.Tensor:

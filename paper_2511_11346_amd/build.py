@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["unembed.hip", "circuits.hip", "api.hip"]
+SOURCES = ["unembed.hip", "circuits.hip", "speculative.hip", "api.hip"]
 OUT = os.path.join(HERE, "libmtpc.so")
 
 

@@ -90,12 +90,13 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   p.logw = take(B * r * 4);
   const bool sample = op == MTPC_OP_SAMPLE;
   const bool uni = op == MTPC_OP_MARGINALS && mode == MTPC_MARG_UNIVARIATE;
-  const bool need_nat = L > 0 && (family == MTPC_HMM || sample || uni);
+  const bool verify = op == MTPC_OP_VERIFY;
+  const bool need_nat = L > 0 && (family == MTPC_HMM || sample || uni || verify);
   const bool need_tr = L > 0 && family == MTPC_BTREE && (!sample || want_prefix) && !uni;
   p.lay_nat = need_nat ? take(lay_bytes) : 0;
   p.lay_circ = need_tr ? take(lay_bytes) : p.lay_nat;
   const size_t rows = sample ? B * (size_t)S : B;
-  p.e = (uni || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
+  p.e = (uni || verify || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
   p.lse = (sample && want_prefix) ? take(B * n * r * 4) : 0;
   p.zleaf = sample ? take(B * (size_t)S * n * 4) : 0;
   p.lat = sample ? take(B * (size_t)S * (size_t)(n_latents(family, hd->n) + 1) * 4) : 0;
@@ -232,7 +233,7 @@ mtpc_status run_marginals(int family, const mtpc_head* hd, const mtpc_sumlayers*
 
 mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, int32_t S,
                        uint64_t seed, uint32_t offset, int32_t* drafts, int32_t* latents,
-                       float* prefix_logq) {
+                       float* prefix_logq, float* logphi) {
   if (!drafts) return MTPC_ERR_NULL;
   const bool want_prefix = prefix_logq != nullptr;
   Plan p;
@@ -260,6 +261,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
   u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
   u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset;
+  u.logphi = logphi;
   const bool gather = want_prefix && score_by_gather(hd, S);
   if (gather) u.lse = (float*)(ws + p.lse);
   {
@@ -286,6 +288,35 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   return MTPC_OK;
 }
 
+mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const float* logphi,
+                       const int32_t* drafts, const float* prefix_logq, const float* pver, int32_t mode,
+                       uint64_t seed, uint32_t offset, int32_t* accepted, int32_t* token) {
+  if (!drafts || !pver || !accepted || !token) return MTPC_ERR_NULL;
+  if (mode != MTPC_VERIFY_SAMPLING && mode != MTPC_VERIFY_GREEDY) return MTPC_ERR_UNSUPPORTED;
+  if (mode == MTPC_VERIFY_SAMPLING && (!prefix_logq || !logphi)) return MTPC_ERR_NULL;
+  Plan p;
+  mtpc_status s = prepare(family, MTPC_OP_VERIFY, hd, ly, 1, 0, false, p);
+  if (s != MTPC_OK) return s;
+  hipStream_t st = (hipStream_t)hd->stream;
+  char* ws = (char*)hd->workspace;
+  const int L = n_layers(family, hd->n);
+  if (mode == MTPC_VERIFY_SAMPLING) {
+    s = launch_params(family, hd, ly, p, true, family == MTPC_BTREE, st);
+    if (s != MTPC_OK) return s;
+  }
+  VerifyArgs a{};
+  a.family = family; a.B = hd->B; a.n = hd->n; a.r = hd->r; a.v = hd->v; a.mode = mode;
+  a.logphi = logphi; a.drafts = drafts; a.prefix = prefix_logq; a.p = pver;
+  a.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
+  a.lay_nat = L > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
+  a.lay_tr = (L > 0 && family == MTPC_BTREE) ? (const float*)(ws + p.lay_circ) : nullptr;
+  a.L = p.Lst; a.contextual = p.nb > 1;
+  a.seed_lo = (uint32_t)(seed & 0xffffffffu); a.seed_hi = (uint32_t)(seed >> 32); a.offset = offset;
+  a.accepted = accepted; a.token = token;
+  HIP_TRY(launch_verify(a, st));
+  return MTPC_OK;
+}
+
 }  // namespace
 }  // namespace mtpc
 
@@ -307,7 +338,7 @@ const char* mtpc_status_string(mtpc_status s) {
 
 size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
                             const mtpc_sumlayers* layers, int32_t S, int32_t mode) {
-  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_SAMPLE) return 0;
+  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_VERIFY) return 0;
   if (!head || head->B < 1 || head->d < 1 || head->n < 1 || head->r < 1 || head->v < 1) return 0;
   if (op == MTPC_OP_SAMPLE && S < 1) return 0;
   // sized for the most demanding variant of the op (sample: with prefix scores)
@@ -346,20 +377,45 @@ mtpc_status mtpc_btree_marginals(const mtpc_head* head, const mtpc_sumlayers* A,
 }
 
 mtpc_status mtpc_ff_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,
-                           int32_t* drafts, int32_t* latents, float* prefix_logq) {
-  return run_sample(MTPC_FF, head, nullptr, S, seed, offset, drafts, latents, prefix_logq);
+                           int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi) {
+  return run_sample(MTPC_FF, head, nullptr, S, seed, offset, drafts, latents, prefix_logq, logphi);
 }
 mtpc_status mtpc_cp_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,
-                           int32_t* drafts, int32_t* latents, float* prefix_logq) {
-  return run_sample(MTPC_CP, head, nullptr, S, seed, offset, drafts, latents, prefix_logq);
+                           int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi) {
+  return run_sample(MTPC_CP, head, nullptr, S, seed, offset, drafts, latents, prefix_logq, logphi);
 }
 mtpc_status mtpc_hmm_sample(const mtpc_head* head, const mtpc_sumlayers* T, int32_t S, uint64_t seed,
-                            uint32_t offset, int32_t* drafts, int32_t* latents, float* prefix_logq) {
-  return run_sample(MTPC_HMM, head, T, S, seed, offset, drafts, latents, prefix_logq);
+                            uint32_t offset, int32_t* drafts, int32_t* latents, float* prefix_logq,
+                            float* logphi) {
+  return run_sample(MTPC_HMM, head, T, S, seed, offset, drafts, latents, prefix_logq, logphi);
 }
 mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, int32_t S, uint64_t seed,
-                              uint32_t offset, int32_t* drafts, int32_t* latents, float* prefix_logq) {
-  return run_sample(MTPC_BTREE, head, A, S, seed, offset, drafts, latents, prefix_logq);
+                              uint32_t offset, int32_t* drafts, int32_t* latents, float* prefix_logq,
+                              float* logphi) {
+  return run_sample(MTPC_BTREE, head, A, S, seed, offset, drafts, latents, prefix_logq, logphi);
+}
+
+mtpc_status mtpc_ff_verify(const mtpc_head* head, const float* logphi, const int32_t* drafts,
+                           const float* prefix_logq, const float* p, int32_t mode, uint64_t seed,
+                           uint32_t offset, int32_t* accepted, int32_t* token) {
+  return run_verify(MTPC_FF, head, nullptr, logphi, drafts, prefix_logq, p, mode, seed, offset, accepted, token);
+}
+mtpc_status mtpc_cp_verify(const mtpc_head* head, const float* logphi, const int32_t* drafts,
+                           const float* prefix_logq, const float* p, int32_t mode, uint64_t seed,
+                           uint32_t offset, int32_t* accepted, int32_t* token) {
+  return run_verify(MTPC_CP, head, nullptr, logphi, drafts, prefix_logq, p, mode, seed, offset, accepted, token);
+}
+mtpc_status mtpc_hmm_verify(const mtpc_head* head, const mtpc_sumlayers* T, const float* logphi,
+                            const int32_t* drafts, const float* prefix_logq, const float* p,
+                            int32_t mode, uint64_t seed, uint32_t offset, int32_t* accepted,
+                            int32_t* token) {
+  return run_verify(MTPC_HMM, head, T, logphi, drafts, prefix_logq, p, mode, seed, offset, accepted, token);
+}
+mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, const float* logphi,
+                              const int32_t* drafts, const float* prefix_logq, const float* p,
+                              int32_t mode, uint64_t seed, uint32_t offset, int32_t* accepted,
+                              int32_t* token) {
+  return run_verify(MTPC_BTREE, head, A, logphi, drafts, prefix_logq, p, mode, seed, offset, accepted, token);
 }
 
 mtpc_status mtpc_philox_uniforms(int32_t B, int32_t S, int32_t slots, uint64_t seed, uint32_t offset,

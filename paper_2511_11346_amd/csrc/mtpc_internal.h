@@ -28,6 +28,7 @@ struct UnembedArgs {
   int S;
   int* drafts;          // [B][S][n]
   uint32_t seed_lo, seed_hi, offset;
+  float* logphi;        // [B][n][r][v] normalised logits of every slab, or nullptr (sampling kernel only)
 };
 
 // Univariate marginals: M[b][i][a] = log sum_j m[b][i][j] phi[b][i][j][a].
@@ -116,6 +117,23 @@ struct GatherArgs {
   float* e;             // [B*S][n][r]
 };
 hipError_t launch_gather_evidence(const GatherArgs& a, int dtype, hipStream_t st);
+
+// Verification step of a speculative-decoding cycle (Alg. 2, acceptance loop on)
+struct VerifyArgs {
+  int family, B, n, r, v, mode;
+  const float* logphi;  // [B][n][r][v]
+  const int* drafts;    // [B][n]
+  const float* prefix;  // [B][n]
+  const float* p;       // [B][n+1][v]
+  const float* logw;    // [B][r] (nullptr for FF)
+  const float* lay_nat; // normalised linear layers [nb][L][k][j]
+  const float* lay_tr;  // the same transposed [nb][L][j][k] (BTree only)
+  int L, contextual;
+  uint32_t seed_lo, seed_hi, offset;
+  int* accepted;        // [B]
+  int* token;           // [B]
+};
+hipError_t launch_verify(const VerifyArgs& a, hipStream_t st);
 
 hipError_t launch_philox_uniforms(int B, int S, int slots, uint32_t seed_lo, uint32_t seed_hi,
                                   uint32_t offset, float* out, hipStream_t st);

@@ -439,6 +439,38 @@ void k_unembed(const UnembedArgs a) {
   }
 
   if constexpr (SAMPLE) {
+    if (a.logphi != nullptr) {
+      // table log phi[b][wi][wj][:] for the verification step: staged through LDS
+      // (stage buffers are free now) so that the global writes run along v
+      constexpr int STR = TL::VPL * 64 + 1;        // odd stride: positions fall into different banks
+      static_assert(NSLOT * STR * 4 <= NS * TL::STAGE, "table staging must fit in the stage buffers");
+      float* stg = (float*)smem;
+      for (int c0 = 0; c0 < TL::TP; c0 += NSLOT) {
+        __syncthreads();
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+          const int p = wb * PB * 32 + pb * 32 + l31 - c0;
+          if (p >= 0 && p < NSLOT) {
+#pragma unroll
+            for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) {
+                const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+                if (row < a.v) stg[p * STR + row] = acc[pb][vb][i] - lse[pb];
+              }
+          }
+        }
+        __syncthreads();
+        for (int k = wave; k < NSLOT; k += TL::NW) {
+          const int b = b0 + c0 + k;
+          if (b < a.B) {
+            float* dst = a.logphi + (((long long)b * a.n + wi) * a.r + wj) * a.v;
+            for (int row = lane; row < a.v; row += 64) dst[row] = stg[k * STR + row];
+          }
+        }
+      }
+      __syncthreads();
+    }
     if (a.zleaf == nullptr) return;
     // ---- which positions of this tile draw token wi from component wj?
     int* misc = (int*)(smem + TL::MISC_OFF);

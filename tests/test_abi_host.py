@@ -21,7 +21,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported():
     from paper_2511_11346_amd import binding
     names = declared_symbols()
-    assert len(names) == 16 and sorted(binding.EXPORTS) == names
+    assert len(names) == 20 and sorted(binding.EXPORTS) == names
     L = C.CDLL(LIB)
     for n in names:
         assert hasattr(L, n), n
@@ -70,9 +70,16 @@ def test_argument_errors_are_reported_without_launching():
     bad = binding.mtpc_sumlayers(0x6000, 3, 0)
     assert L.mtpc_hmm_loglik(C.byref(_head()), C.byref(bad), tg, out) == SHAPE
     assert L.mtpc_cp_marginals(C.byref(_head()), tg, 9, out) == UNSUP
-    assert L.mtpc_cp_sample(C.byref(_head()), 0, 1, 0, out, None, None) == SHAPE
-    assert L.mtpc_cp_sample(C.byref(_head()), 2, 1, 0, None, None, None) == NULL
+    assert L.mtpc_cp_sample(C.byref(_head()), 0, 1, 0, out, None, None, None) == SHAPE
+    assert L.mtpc_cp_sample(C.byref(_head()), 2, 1, 0, None, None, None, None) == NULL
     assert L.mtpc_philox_uniforms(1, 1, 0, 0, 0, out, None) == SHAPE
+    # verify: required pointers depend on the mode; nothing is launched on error
+    assert L.mtpc_cp_verify(C.byref(_head()), out, tg, out, out, 0, 1, 0, None, tg) == NULL
+    assert L.mtpc_cp_verify(C.byref(_head()), None, tg, out, out, 0, 1, 0, tg, tg) == NULL
+    assert L.mtpc_cp_verify(C.byref(_head()), out, tg, None, out, 0, 1, 0, tg, tg) == NULL
+    assert L.mtpc_cp_verify(C.byref(_head()), out, tg, out, out, 5, 1, 0, tg, tg) == UNSUP
+    assert L.mtpc_cp_verify(C.byref(_head(workspace_bytes=16)), None, tg, None, out, 1, 0, 0, tg, tg) == WS
+    assert L.mtpc_hmm_verify(C.byref(_head()), None, out, tg, out, out, 0, 1, 0, tg, tg) == NULL
 
 
 def test_workspace_query():
