@@ -221,9 +221,25 @@ def main():
             call_ms = (time.perf_counter() - t) * 1e3 / reps
             kms = sum(ev.elapsed_ms(a, b) for a, b in prs) / reps
             byts = inp5.n * inp5.r * inp5.v * inp5.d * 2 + Bd * inp5.d * 2
+            # the verification step of the same cycle (Alg. 2): the sampler also keeps its
+            # table of input units, then accept / reject against a synthetic verifier that is
+            # 90 % the component each draft was drawn from and 10 % random tables
+            table = torch.empty(Bd, inp5.n, inp5.r, inp5.v, dtype=torch.float32, device=dev)
+            hd.sample(1, seed=0, offset=0, out=o, logphi=table)
+            comp = o[1][:, 0, 0].long()
+            q_comp = torch.exp(table[torch.arange(Bd, device=dev), :, comp, :])
+            noise = torch.from_numpy(mi.verifier_noise(Bd, inp5.n, inp5.v, seed=9)).float().to(dev)
+            pver = torch.cat([0.9 * q_comp + 0.1 * noise[:, :inp5.n], noise[:, inp5.n:]], dim=1)
+            pver = (pver / pver.sum(-1, keepdim=True)).contiguous()
+            dr, sc = o[0][:, 0].contiguous(), o[2][:, 0].contiguous()
+            ms_table = time_op(lambda: hd.sample(1, seed=0, offset=0, out=o, logphi=table), reps)
+            ms_verify = time_op(lambda: hd.verify(dr, pver, prefix_logq=sc, logphi=table, seed=1, offset=1), reps)
+            acc, _ = hd.verify(dr, pver, prefix_logq=sc, logphi=table, seed=1, offset=1)
             dec.append({"B": Bd, "call_ms": call_ms, "drafts_per_s": Bd / (call_ms * 1e-3),
                         "k_unembed_ms": kms, "achieved_GBps": byts / (kms * 1e-3) / 1e9,
-                        "frac_of_hbm_peak": byts / (kms * 1e-3) / 1e9 / PEAK_HBM_GBPS})
+                        "frac_of_hbm_peak": byts / (kms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                        "call_ms_keeping_table": ms_table, "verify_call_ms": ms_verify,
+                        "mean_accepted": float(acc.float().mean())})
         out["decode_cp_r32_n16"] = dec
 
     if not args.no_cpu:

@@ -5,6 +5,7 @@ import torch
 
 import mtpc_inputs as mi
 from oracle import mtpc_oracle as oc
+from oracle import speculative as sp
 
 FP32_ABS = 1e-4      # log-likelihood tolerance for fp32 inputs
 BF16_REL = 2e-3      # relative tolerance for bf16 inputs with fp32 accumulation
@@ -59,3 +60,25 @@ def compare_drafts(g_drafts, g_lat, o_drafts, o_lat, margin):
     near = ~safe
     bad = int(np.any(gd[near] != o_drafts[near], axis=-1).sum()) if near.any() else 0
     return int(near.sum()), bad
+
+
+def oracle_params(inp):
+    lay = inp.layers
+    if inp.R is not None:
+        lay = oc.contextual_layer_logits(inp.h, inp.R, inp.layers)
+    return oc._params(inp.family, inp.h, inp.W, inp.Wsum, lay)
+
+
+def synthetic_verifier(inp, logphi, logw, loglayers, drafts, seed):
+    """p[b,i] = (1-eps_b) q(. | x_<i) + eps_b noise, eps_b cycling through the batch."""
+    B, n, r, v = logphi.shape
+    noise = mi.verifier_noise(B, n, v, seed)
+    eps = np.array([0.0, 0.03, 0.08, 0.15, 0.3, 1.0])[np.arange(B) % 6]
+    p = noise.copy()
+    for b in range(B):
+        lay = None if loglayers is None else (loglayers[b] if loglayers.ndim == 4 else loglayers)
+        for i in range(n):
+            q = np.exp(sp.conditional_next(inp.family, logphi[b], None if logw is None else logw[b],
+                                           lay, drafts[b], i))
+            p[b, i] = (1 - eps[b]) * q + eps[b] * noise[b, i]
+    return p / p.sum(axis=-1, keepdims=True)

@@ -10,7 +10,9 @@ import mtpc_inputs as mi
 from oracle import mtpc_oracle as oc
 from oracle import philox
 
-from gpu_util import BOUNDARY, compare_drafts, make_head, tol_check
+from oracle import speculative as sp
+
+from gpu_util import BOUNDARY, compare_drafts, make_head, synthetic_verifier, tol_check
 
 pytestmark = pytest.mark.gpu
 
@@ -95,3 +97,27 @@ def test_config5_decode_draft_and_score(B):
     inp = mi.config5(B=B)
     head = make_head(inp)
     check_rows(inp, head, np.arange(B), S=1, seed=0)
+
+
+def test_config5_decode_cycle_with_verification():
+    """Draft, score, keep the input-unit table, verify (Alg. 2) at the decode shape."""
+    inp = mi.config5(B=64)
+    B, n, r, v = inp.B, inp.n, inp.r, inp.v
+    head = make_head(inp)
+    logphi, logw, loglayers = oc._params(inp.family, inp.h, inp.W, inp.Wsum, inp.layers)
+    table = torch.empty(B, n, r, v, dtype=torch.float32, device="cuda")
+    gd, _, gp = head.sample(1, seed=4, want_prefix=True, logphi=table)
+    tol_check(table.cpu().numpy(), logphi, inp.dtype, "log phi table")
+    od, _ = oc.sample_from(inp.family, logphi, logw, loglayers, philox.uniforms(B, 1, n + 1, 4, 0))
+    drafts = od[:, 0].astype(np.int32)
+    p = synthetic_verifier(inp, logphi, logw, loglayers, drafts, seed=8)
+    u = philox.uniforms(B, 1, n + 1, 21, 1)[:, 0]
+    want_acc, want_tok, margin = sp.speculative_verify(inp.family, logphi, logw, loglayers, drafts, p, u)
+    gdn = gd[:, 0].contiguous()
+    acc, tok = head.verify(gdn, torch.from_numpy(p.astype(np.float32)).cuda(), prefix_logq=gp[:, 0].contiguous(),
+                           logphi=table, seed=21, offset=1)
+    safe = np.all(gdn.cpu().numpy() == drafts, axis=1) & (margin >= 4e-3)
+    assert np.array_equal(acc.cpu().numpy()[safe], want_acc[safe])
+    assert np.array_equal(tok.cpu().numpy()[safe], want_tok[safe])
+    print(f"accepted histogram {np.bincount(want_acc, minlength=n + 1)}; {int((~safe).sum())} of {B} rows near a boundary")
+    assert safe.sum() >= B // 2 and len(np.unique(want_acc)) >= 4
