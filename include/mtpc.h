@@ -48,7 +48,8 @@ typedef enum {
 
 typedef enum { MTPC_F32 = 0, MTPC_BF16 = 1 } mtpc_dtype;
 typedef enum { MTPC_FF = 0, MTPC_CP = 1, MTPC_HMM = 2, MTPC_BTREE = 3 } mtpc_family;
-typedef enum { MTPC_OP_LOGLIK = 0, MTPC_OP_MARGINALS = 1, MTPC_OP_SAMPLE = 2, MTPC_OP_VERIFY = 3 } mtpc_op;
+typedef enum { MTPC_OP_LOGLIK = 0, MTPC_OP_MARGINALS = 1, MTPC_OP_SAMPLE = 2, MTPC_OP_VERIFY = 3,
+               MTPC_OP_BACKWARD = 4 } mtpc_op;
 typedef enum { MTPC_MARG_PREFIX = 0, MTPC_MARG_UNIVARIATE = 1 } mtpc_marg_mode;
 typedef enum { MTPC_VERIFY_SAMPLING = 0, MTPC_VERIFY_GREEDY = 1 } mtpc_verify_mode;
 
@@ -178,6 +179,31 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
                               const int32_t* drafts, const float* prefix_logq, const float* p,
                               int32_t mode, uint64_t seed, uint32_t offset, int32_t* accepted,
                               int32_t* token);
+
+/* Training step (Sec. 4.1): the discounted, locally normalised negative
+ * log-likelihood of overlapping windows and its gradients.  Token j (0-based) of
+ * the window of position b contributes coef[b][j] * (-log q(x_j | x_<j)), the
+ * conditional being a difference of prefix log-marginals:
+ *   loss[b] = sum_j coef[b][j] * (P[b][j-1] - P[b][j]),   P[b][-1] = 0.
+ * The caller folds gamma^j, the validity mask and the 1 / (N * V_ij) normalisation
+ * of Eq. cross-ent-loss into coef [B][n] (fp32, device).  Outputs (device, fp32,
+ * fully overwritten): loss [B]; gradients of sum_b loss[b]: dh [B][d] (row stride
+ * d), dW [n][r][v][d], dWsum [r][d], dlayers = gradient w.r.t. the layer logits.
+ * The logits are recomputed, never stored; the logit gradient is kept in the
+ * dtype of h for the two contractions (bf16 inputs: rounded to nearest even).
+ * targets: ids in [0, v), or -1 (that variable is summed out and receives no
+ * gradient).  Workspace: mtpc_workspace_bytes(family, MTPC_OP_BACKWARD, ...).
+ * Not yet available: HMM and binary tree (MTPC_ERR_UNSUPPORTED). */
+mtpc_status mtpc_ff_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
+                                  float* loss, float* dh, float* dW);
+mtpc_status mtpc_cp_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
+                                  float* loss, float* dh, float* dW, float* dWsum);
+mtpc_status mtpc_hmm_loss_backward(const mtpc_head* head, const mtpc_sumlayers* T, const int32_t* targets,
+                                   const float* coef, float* loss, float* dh, float* dW, float* dWsum,
+                                   float* dlayers);
+mtpc_status mtpc_btree_loss_backward(const mtpc_head* head, const mtpc_sumlayers* A,
+                                     const int32_t* targets, const float* coef, float* loss, float* dh,
+                                     float* dW, float* dWsum, float* dlayers);
 
 /* The uniforms the sampler consumes, out [B][S][slots] fp32 (device), for tests
  * of the generator and its slot map. */

@@ -75,8 +75,10 @@ def prefix_marginals_torch(family, h, W, Wsum, layers, targets):
     B, n = targets.shape
     logits = torch.einsum("nrvd,bd->bnrv", W, h)
     logphi = torch.log_softmax(logits, dim=-1)
-    idx = torch.as_tensor(targets, dtype=torch.int64)[:, :, None, None].expand(B, n, W.shape[1], 1)
+    tt = torch.as_tensor(targets, dtype=torch.int64)
+    idx = tt.clamp(min=0)[:, :, None, None].expand(B, n, W.shape[1], 1)
     e = torch.gather(logphi, 3, idx)[..., 0]                               # [B,n,r]
+    e = e * (tt != -1)[:, :, None]          # a target of -1 is summed out: its input units are 1 (App. B.1)
     logw = None if Wsum is None else torch.log_softmax(h @ Wsum.T, dim=-1)
     loglayers = None if layers is None else torch.log_softmax(layers, dim=-1)
     cols = []

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmtpc.so")
 
 FF, CP, HMM, BTREE = 0, 1, 2, 3
 FAMILY = {"ff": FF, "cp": CP, "hmm": HMM, "btree": BTREE}
-OP_LOGLIK, OP_MARGINALS, OP_SAMPLE, OP_VERIFY = 0, 1, 2, 3
+OP_LOGLIK, OP_MARGINALS, OP_SAMPLE, OP_VERIFY, OP_BACKWARD = 0, 1, 2, 3, 4
 VERIFY_SAMPLING, VERIFY_GREEDY = 0, 1
 MARG_PREFIX, MARG_UNIVARIATE = 0, 1
 F32, BF16 = 0, 1
@@ -45,6 +45,7 @@ EXPORTS = [
     "mtpc_ff_marginals", "mtpc_cp_marginals", "mtpc_hmm_marginals", "mtpc_btree_marginals",
     "mtpc_ff_sample", "mtpc_cp_sample", "mtpc_hmm_sample", "mtpc_btree_sample",
     "mtpc_ff_verify", "mtpc_cp_verify", "mtpc_hmm_verify", "mtpc_btree_verify",
+    "mtpc_ff_loss_backward", "mtpc_cp_loss_backward", "mtpc_hmm_loss_backward", "mtpc_btree_loss_backward",
     "mtpc_philox_uniforms", "mtpc_profile_unembed",
 ]
 
@@ -73,6 +74,10 @@ def lib() -> C.CDLL:
             getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, lp, ip, C.c_int32, fp]
             getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, lp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
             getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, lp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
+        L.mtpc_ff_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp]
+        L.mtpc_cp_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp, fp]
+        L.mtpc_hmm_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp]
+        L.mtpc_btree_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp]
         L.mtpc_philox_uniforms.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
                                            fp, C.c_void_p]
         L.mtpc_profile_unembed.argtypes = [C.c_void_p, C.c_void_p]
@@ -211,6 +216,29 @@ class Head:
                           pl.data_ptr() if pl is not None else None,
                           self._phi_ptr(logphi)))
         return drafts, lat, pl
+
+    def loss_backward(self, targets: torch.Tensor, coef: torch.Tensor, out: Optional[dict] = None) -> dict:
+        """Loss of Sec. 4.1 and its gradients: targets [B,n] int32, coef [B,n] fp32.
+        Returns {"loss" [B], "dh" [B,d], "dW" [n,r,v,d], "dWsum" [r,d] or None, "dlayers" or None}, all fp32."""
+        dev = self.h.device
+        assert targets.is_cuda and targets.dtype == torch.int32 and targets.is_contiguous()
+        assert coef.is_cuda and coef.dtype == torch.float32 and coef.is_contiguous()
+        assert tuple(targets.shape) == (self.B, self.n) and tuple(coef.shape) == (self.B, self.n)
+        f32 = dict(dtype=torch.float32, device=dev)
+        if out is None:
+            out = {"loss": torch.empty(self.B, **f32), "dh": torch.empty(self.B, self.d, **f32),
+                   "dW": torch.empty(self.n, self.r, self.v, self.d, **f32),
+                   "dWsum": None if self.family == "ff" else torch.empty(self.r, self.d, **f32),
+                   "dlayers": None if self.layers is None else torch.empty_like(self.layers)}
+        hd = self._head(self.workspace_bytes(OP_BACKWARD))
+        args = [targets.data_ptr(), coef.data_ptr(), out["loss"].data_ptr(), out["dh"].data_ptr(),
+                out["dW"].data_ptr()]
+        if self.family != "ff":
+            args.append(out["dWsum"].data_ptr())
+        if self.family in ("hmm", "btree"):
+            args.append(out["dlayers"].data_ptr() if out["dlayers"] is not None else None)
+        _check(self._call("loss_backward", hd, *args))
+        return out
 
     def _phi_ptr(self, logphi):
         if logphi is None:

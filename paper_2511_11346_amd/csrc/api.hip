@@ -317,6 +317,111 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   return MTPC_OK;
 }
 
+// Workspace of the training step (byte offsets) and its padded strides.
+struct BwdPlan {
+  Plan fwd;                 // logw, layers, evidence: as for the prefix marginals
+  size_t Ge, dLT, dL, WT, hT, total;
+  long long M, Mx, ldM, ldb;
+};
+
+BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly) {
+  BwdPlan q{};
+  q.fwd = make_plan(family, MTPC_OP_MARGINALS, hd, ly, 1, MTPC_MARG_PREFIX, false);
+  const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
+  q.M = (long long)hd->n * hd->r * hd->v;
+  q.Mx = q.M + (family == MTPC_FF ? 0 : hd->r);      // the sum-unit rows ride along in both contractions
+  q.ldM = (q.Mx + 31) / 32 * 32;
+  q.ldb = ((long long)hd->B + 31) / 32 * 32;
+  size_t off = q.fwd.total;
+  auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
+  q.Ge = take((size_t)hd->B * hd->n * hd->r * 4);
+  q.dLT = take((size_t)q.Mx * q.ldb * esz);
+  q.dL = take((size_t)hd->B * q.ldM * esz);
+  q.WT = take((size_t)hd->d * q.ldM * esz);
+  q.hT = take((size_t)hd->d * q.ldb * esz);
+  q.total = off;
+  return q;
+}
+
+// loss and gradients: forward (evidence) -> circuit reverse pass -> logit gradient by
+// recomputation -> the two contractions
+mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const int32_t* targets,
+                         const float* coef, float* loss, float* dh, float* dW, float* dWsum, float* dlayers) {
+  if (!targets || !coef || !loss || !dh || !dW) return MTPC_ERR_NULL;
+  if (family != MTPC_FF && !dWsum) return MTPC_ERR_NULL;
+  if (family == MTPC_HMM || family == MTPC_BTREE) return MTPC_ERR_UNSUPPORTED;
+  mtpc_status s = check_head(family, hd);
+  if (s != MTPC_OK) return s;
+  s = check_layers(family, hd, ly);
+  if (s != MTPC_OK) return s;
+  const BwdPlan q = make_bwd_plan(family, hd, ly);
+  if (!hd->workspace) return MTPC_ERR_NULL;
+  if (((uintptr_t)hd->workspace & 15) || hd->workspace_bytes < q.total) return MTPC_ERR_WORKSPACE;
+  if (q.ldM * 4 > 0x7fffffffLL / 256 || q.ldb * 4 > 0x7fffffffLL / 256) return MTPC_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)hd->stream;
+  char* ws = (char*)hd->workspace;
+  const Plan& p = q.fwd;
+  const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
+  s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
+  if (s != MTPC_OK) return s;
+  UnembedArgs u{};
+  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
+  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  u.targets = targets; u.T = 1; u.e = (float*)(ws + p.e);
+  HIP_TRY(launch_unembed(u, hd->dtype, st));
+
+  CircuitBwdArgs c{};
+  c.family = family; c.rows = hd->B; c.n = hd->n; c.r = hd->r;
+  c.e = (const float*)(ws + p.e);
+  c.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
+  c.coef = coef; c.Ge = (float*)(ws + q.Ge);
+  c.dslT = family == MTPC_FF ? nullptr : (void*)(ws + q.dLT + (size_t)q.M * q.ldb * esz);
+  c.ldb = q.ldb; c.bf16 = hd->dtype == MTPC_BF16; c.loss = loss;
+  HIP_TRY(launch_circuit_bwd(c, st));
+
+  GradLogitsArgs g{};
+  g.h = hd->h; g.ld_h = hd->ld_h; g.W = hd->W;
+  g.B = hd->B; g.d = hd->d; g.v = hd->v; g.n = hd->n; g.r = hd->r;
+  g.targets = targets; g.Ge = c.Ge; g.dLT = ws + q.dLT; g.ldb = q.ldb;
+  {
+    ProfScope prof(st);
+    HIP_TRY(launch_unembed_grad(g, hd->dtype, st));
+  }
+  // layouts for the two contractions: dL = dLT^T [B][ldM], WT = [W; Wsum]^T [d][ldM], hT = h^T [d][ldb]
+  TransposeArgs t{};
+  t.src = ws + q.dLT; t.ld_src = q.ldb; t.R = (int)q.Mx; t.C = hd->B;
+  t.dst = ws + q.dL; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)q.ldM;
+  HIP_TRY(launch_transpose(t, hd->dtype, st));
+  t.src = hd->W; t.ld_src = hd->d; t.R = (int)q.M; t.C = hd->d;
+  t.dst = ws + q.WT; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)(family == MTPC_FF ? q.ldM : q.M);
+  HIP_TRY(launch_transpose(t, hd->dtype, st));
+  if (family != MTPC_FF) {
+    t.src = hd->Wsum; t.ld_src = hd->d; t.R = hd->r; t.C = hd->d;
+    t.col0 = q.M; t.Rpad = (int)(q.ldM - q.M);
+    HIP_TRY(launch_transpose(t, hd->dtype, st));
+  }
+  t.src = hd->h; t.ld_src = hd->ld_h; t.R = hd->B; t.C = hd->d;
+  t.dst = ws + q.hT; t.ld_dst = q.ldb; t.col0 = 0; t.Rpad = (int)q.ldb;
+  HIP_TRY(launch_transpose(t, hd->dtype, st));
+
+  GemmArgs m{};
+  m.A = ws + q.dL; m.lda = q.ldM; m.M = hd->B;                   // dh[b][k] = sum_m dL[b][m] WT[k][m]
+  m.Bm = ws + q.WT; m.ldb = q.ldM; m.N = hd->d; m.K = (int)q.ldM;
+  m.C = dh; m.ldc = hd->d;
+  HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
+  m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)q.M;               // dW[m][k] = sum_b dLT[m][b] hT[k][b]
+  m.Bm = ws + q.hT; m.ldb = q.ldb; m.N = hd->d; m.K = (int)q.ldb;
+  m.C = dW; m.ldc = hd->d;
+  HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
+  if (family != MTPC_FF) {
+    m.A = ws + q.dLT + (size_t)q.M * q.ldb * esz; m.M = hd->r;
+    m.C = dWsum;
+    HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
+  }
+  (void)dlayers;
+  return MTPC_OK;
+}
+
 }  // namespace
 }  // namespace mtpc
 
@@ -338,8 +443,9 @@ const char* mtpc_status_string(mtpc_status s) {
 
 size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
                             const mtpc_sumlayers* layers, int32_t S, int32_t mode) {
-  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_VERIFY) return 0;
+  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_BACKWARD) return 0;
   if (!head || head->B < 1 || head->d < 1 || head->n < 1 || head->r < 1 || head->v < 1) return 0;
+  if (op == MTPC_OP_BACKWARD) return make_bwd_plan(family, head, layers).total;
   if (op == MTPC_OP_SAMPLE && S < 1) return 0;
   // sized for the most demanding variant of the op (sample: with prefix scores)
   Plan p = make_plan(family, op, head, layers, op == MTPC_OP_SAMPLE ? S : 1, mode, true);
@@ -416,6 +522,25 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
                               int32_t mode, uint64_t seed, uint32_t offset, int32_t* accepted,
                               int32_t* token) {
   return run_verify(MTPC_BTREE, head, A, logphi, drafts, prefix_logq, p, mode, seed, offset, accepted, token);
+}
+
+mtpc_status mtpc_ff_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
+                                  float* loss, float* dh, float* dW) {
+  return run_backward(MTPC_FF, head, nullptr, targets, coef, loss, dh, dW, nullptr, nullptr);
+}
+mtpc_status mtpc_cp_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
+                                  float* loss, float* dh, float* dW, float* dWsum) {
+  return run_backward(MTPC_CP, head, nullptr, targets, coef, loss, dh, dW, dWsum, nullptr);
+}
+mtpc_status mtpc_hmm_loss_backward(const mtpc_head* head, const mtpc_sumlayers* T, const int32_t* targets,
+                                   const float* coef, float* loss, float* dh, float* dW, float* dWsum,
+                                   float* dlayers) {
+  return run_backward(MTPC_HMM, head, T, targets, coef, loss, dh, dW, dWsum, dlayers);
+}
+mtpc_status mtpc_btree_loss_backward(const mtpc_head* head, const mtpc_sumlayers* A, const int32_t* targets,
+                                     const float* coef, float* loss, float* dh, float* dW, float* dWsum,
+                                     float* dlayers) {
+  return run_backward(MTPC_BTREE, head, A, targets, coef, loss, dh, dW, dWsum, dlayers);
 }
 
 mtpc_status mtpc_philox_uniforms(int32_t B, int32_t S, int32_t slots, uint64_t seed, uint32_t offset,

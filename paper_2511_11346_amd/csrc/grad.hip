@@ -1,0 +1,159 @@
+// MFMA kernels of the training step (Sec. 4.1 loss):
+//   k_unembed_grad  recomputes the logits of one (i, j) slab for a tile of positions
+//                   exactly as the forward kernel does, normalises them in registers
+//                   and writes the gradient of the loss w.r.t. the logits,
+//                   Ge[b,i,j] * (onehot(x_bi) - softmax), in the dtype of h; the logits
+//                   themselves are never stored.
+//   k_gemm_tn       C = A B^T with both operands K-contiguous: the two contractions
+//                   that turn the logit gradient into dh (over n*r*v) and dW (over B).
+#include "tile.h"
+
+namespace mtpc {
+
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40);   // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+__global__ __launch_bounds__(WV * WB * 64)
+void k_unembed_grad(const GradLogitsArgs a) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wv = wave % WV, wb = wave / WV;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int nslab = a.n * a.r;
+  const int nbt = (int)((a.ldb + TL::TP - 1) / TL::TP);
+  int slab, bt;
+  tile_of_block(blockIdx.x, nbt, nslab, slab, bt);
+  const int b0 = bt * TL::TP;
+  const int wi = slab / a.r, wj = slab - wi * a.r;
+  if (b0 >= a.B) {
+    // a tile of padding columns only (B is not a multiple of the tile): zeros
+    for (int idx = tid; idx < a.v * TL::TP; idx += TL::NT) {
+      const int row = idx / TL::TP, b = b0 + idx % TL::TP;
+      if (b < a.ldb) {
+        const long long o = ((long long)slab * a.v + row) * a.ldb + b;
+        if constexpr (BF16) ((unsigned short*)a.dLT)[o] = 0; else ((float*)a.dLT)[o] = 0.f;
+      }
+    }
+    return;
+  }
+
+  f32x16_t acc[PB][VB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
+  const int rbase = wv * VB * 32 + 4 * lhalf;
+  float mx[PB], lse[PB];
+  tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
+
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) {
+    const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+    if (b >= a.ldb) continue;
+    float g = 0.f;
+    int x = -1;
+    if (b < a.B) {
+      x = a.targets[(long long)b * a.n + wi];
+      // a summed-out variable (-1) has constant evidence: no gradient reaches its logits
+      g = (x == -1) ? 0.f : a.Ge[((long long)b * a.n + wi) * a.r + wj];
+    }
+#pragma unroll
+    for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+        if (row < a.v) {
+          float val = 0.f;
+          if (b < a.B && x != -1) val = g * ((row == x ? 1.f : 0.f) - __expf(acc[pb][vb][i] - lse[pb]));
+          const long long o = ((long long)slab * a.v + row) * a.ldb + b;
+          if constexpr (BF16) ((unsigned short*)a.dLT)[o] = f32_to_bf16_rne(val);
+          else ((float*)a.dLT)[o] = val;
+        }
+      }
+  }
+}
+
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+static hipError_t launch_grad_cfg(const GradLogitsArgs& a, hipStream_t st) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  auto kern = k_unembed_grad<WV, WB, VB, PB, SB, NS, BF16>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int nbt = (int)((a.ldb + TL::TP - 1) / TL::TP);
+  hipLaunchKernelGGL(kern, dim3(nbt * a.n * a.r), dim3(TL::NT), TL::SMEM, st, a);
+  return hipGetLastError();
+}
+
+template <bool BF16>
+static hipError_t launch_grad_dt(const GradLogitsArgs& a, hipStream_t st) {
+  if (a.v > 256) return launch_grad_cfg<2, 4, 5, 2, 64, 4, BF16>(a, st);
+  if (a.v > 128) return launch_grad_cfg<2, 4, 4, 2, 64, 4, BF16>(a, st);
+  return launch_grad_cfg<2, 4, 2, 2, 64, 4, BF16>(a, st);
+}
+
+hipError_t launch_unembed_grad(const GradLogitsArgs& a, int dtype, hipStream_t st) {
+  return dtype == MTPC_BF16 ? launch_grad_dt<true>(a, st) : launch_grad_dt<false>(a, st);
+}
+
+// ---------------------------------------------------------------------------
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+__global__ __launch_bounds__(WV * WB * 64)
+void k_gemm_tn(const GemmArgs a) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  constexpr int ESZ = BF16 ? 2 : 4;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wv = wave % WV, wb = wave / WV;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int nslab = (a.M + TL::TV - 1) / TL::TV;
+  const int nbt = (a.N + TL::TP - 1) / TL::TP;
+  int slab, bt;
+  tile_of_block(blockIdx.x, nbt, nslab, slab, bt);
+  const int b0 = bt * TL::TP;
+  const int rows = min(TL::TV, a.M - slab * TL::TV);
+  f32x16_t acc[PB][VB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>((const char*)a.A + (long long)slab * TL::TV * a.lda * ESZ, a.lda,
+                                          a.Bm, a.ldb, a.N, a.K, rows, 0, b0, smem, acc);
+  const int rbase = wv * VB * 32 + 4 * lhalf;
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) {
+    const int col = b0 + wb * PB * 32 + pb * 32 + l31;
+    if (col >= a.N) continue;
+#pragma unroll
+    for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+        if (row < rows) a.C[((long long)slab * TL::TV + row) * a.ldc + col] = acc[pb][vb][i];
+      }
+  }
+}
+
+template <bool BF16>
+static hipError_t launch_gemm_dt(const GemmArgs& a, hipStream_t st) {
+  using TL = Tile<2, 4, 4, 2, 64, 4>;          // 256 x 256 workgroup tile
+  auto kern = k_gemm_tn<2, 4, 4, 2, 64, 4, BF16>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int nslab = (a.M + TL::TV - 1) / TL::TV, nbt = (a.N + TL::TP - 1) / TL::TP;
+  hipLaunchKernelGGL(kern, dim3(nslab * nbt), dim3(TL::NT), TL::SMEM, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t st) {
+  if (a.M < 1 || a.N < 1) return hipSuccess;
+  return dtype == MTPC_BF16 ? launch_gemm_dt<true>(a, st) : launch_gemm_dt<false>(a, st);
+}
+
+}  // namespace mtpc

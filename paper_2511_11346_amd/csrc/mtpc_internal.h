@@ -135,6 +135,55 @@ struct VerifyArgs {
 };
 hipError_t launch_verify(const VerifyArgs& a, hipStream_t st);
 
+// ---- training step (grad.hip, backward.hip) ----------------------------------
+// Recompute pass: dLT[(i*r+j)*v + a][b] = Ge[b][i][j] * (1[a == x_bi] - phi[b,i,j,a]) in the
+// dtype of h; columns b in [B, ldb) are written as zero.
+struct GradLogitsArgs {
+  const void* h; long long ld_h; const void* W;
+  int B, d, v, n, r;
+  const int* targets;   // [B][n]
+  const float* Ge;      // [B][n][r] gradient of the loss w.r.t. the evidence
+  void* dLT;            // [n*r*v][ldb]
+  long long ldb;        // >= B, a multiple of 32
+};
+hipError_t launch_unembed_grad(const GradLogitsArgs& a, int dtype, hipStream_t st);
+
+// C[M][N] (fp32, row stride ldc) = A[M][K] * B[N][K]^T, both operands K-contiguous
+// with row strides lda / ldb (elements); K a multiple of 32 (bf16) or 16 (fp32).
+struct GemmArgs {
+  const void* A; long long lda; int M;
+  const void* Bm; long long ldb; int N;
+  int K;
+  float* C; long long ldc;
+};
+hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t st);
+
+// dst[c][col0 + r] = src[r][c] for r < R, c < C; dst[c][col0 + r] = 0 for R <= r < Rpad.
+struct TransposeArgs {
+  const void* src; long long ld_src; int R, C;
+  void* dst; long long ld_dst; long long col0; int Rpad;
+};
+hipError_t launch_transpose(const TransposeArgs& a, int dtype, hipStream_t st);
+
+// Reverse pass through the circuit: from the evidence and the loss coefficients to
+// the gradient w.r.t. the evidence, the sum-unit logits (written transposed, in the
+// dtype of h, as r rows of ldb columns) and the layer logits; also the loss itself.
+struct CircuitBwdArgs {
+  int family, rows, n, r;
+  const float* e;        // [rows][n][r]
+  const float* logw;     // [rows][r] (nullptr for FF)
+  const float* coef;     // [rows][n]
+  const float* lay_nat;  // normalised linear layers [L][k][j] (static only)
+  int L;
+  float* Ge;             // [rows][n][r]
+  void* dslT;            // [r][ldb] or nullptr
+  long long ldb;
+  int bf16;
+  float* loss;           // [rows]
+  float* dlayers;        // [L][r][r] gradient w.r.t. the layer logits (accumulated), or nullptr
+};
+hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st);
+
 hipError_t launch_philox_uniforms(int B, int S, int slots, uint32_t seed_lo, uint32_t seed_hi,
                                   uint32_t offset, float* out, hipStream_t st);
 

@@ -13,373 +13,9 @@
 // tiles go from global memory straight into LDS (buffer_load_dwordx4 ... lds) through
 // a ring of NS stages with unpadded, XOR-swizzled rows; fragments are read with
 // conflict-free 16-byte LDS loads one half-step ahead of the MFMAs using them.
-#include "mtpc_internal.h"
+#include "tile.h"
 
 namespace mtpc {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-typedef __attribute__((ext_vector_type(4))) int i32x4_t;
-
-constexpr int NSLOT = 16;         // positions sampled per pass of the draw loop
-
-#ifndef MTPC_PINGPONG
-#define MTPC_PINGPONG 1
-#endif
-
-template <int WV, int WB, int VB, int PB, int SB, int NS>
-struct Tile {
-  static constexpr int NW = WV * WB;
-  static constexpr int NT = NW * 64;
-  static constexpr int TV = WV * VB * 32;
-  static constexpr int TP = WB * PB * 32;
-  static constexpr int ROWS = TV + TP;
-  static constexpr int CPR = SB / 16;                  // 16-byte chunks per row per stage
-  static constexpr int RPL = 64 / CPR;                 // rows covered by one 1 KiB wave-load
-  static constexpr int NWL = ROWS / RPL;               // wave-loads per stage
-  static constexpr int LPW = (NWL + NW - 1) / NW;      // wave-loads per wave per stage (some waves: LPW-1)
-  static constexpr int PER = (NWL % NW == 0) ? LPW : LPW - 1;   // loads every wave surely issues
-  static constexpr int KS = SB / 32;                   // MFMA k-substeps (2 chunks each) per stage
-  static constexpr int STAGE = ROWS * SB;
-  static constexpr int VPL = (TV + 63) / 64;           // values per lane in the draw scan
-  static constexpr int RED_OFF = NS * STAGE;           // float2 red[WV][TP]
-  static constexpr int MISC_OFF = RED_OFF + WV * TP * 8;   // int cnt, list[TP], slot[TP]
-  static constexpr int SMEM = MISC_OFF + 16 + TP * 8;
-  static_assert(SB == 64 || SB == 128, "stage bytes");
-  static_assert(NS >= 2 && ROWS % RPL == 0, "ring geometry");
-  static_assert(NSLOT * VPL * 64 * 4 <= NS * STAGE, "draw buffer must fit in the stage buffers");
-  static_assert(SMEM <= 160 * 1024, "LDS budget of one CU");
-};
-
-template <bool BF16>
-__device__ __forceinline__ void mma_step(f32x16_t& acc, const i32x4_t& a, const i32x4_t& b) {
-  if constexpr (BF16) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                  __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
-  } else {
-    f32x4_t af = __builtin_bit_cast(f32x4_t, a), bf = __builtin_bit_cast(f32x4_t, b);
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t], bf[t], acc, 0, 0, 0);
-  }
-}
-
-// Map the hardware workgroup id to a (slab, position tile) pair.  Workgroup ids
-// are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a
-// contiguous range of logical ids, and walk logical ids through groups of 4
-// slabs x all position tiles so that concurrently running workgroups of an XCD
-// share a few W slabs and a few h tiles.
-__device__ __forceinline__ void tile_of_block(int w, int nbt, int nslab, int& slab, int& bt) {
-  const int total = nbt * nslab;
-  const int per = total >> 3;
-  int lid = (w < per * 8) ? (w & 7) * per + (w >> 3) : w;
-  constexpr int GS = 4;
-  const int gsz = GS * nbt;
-  const int g = lid / gsz, rem = lid - g * gsz;
-  const int gs = min(GS, nslab - g * GS);
-  bt = rem / gs;
-  slab = g * GS + (rem - bt * gs);
-}
-
-// s_waitcnt that waits only for the vector-memory counter to drop to n
-#define MTPC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-
-// One 16-byte-per-lane load from global memory straight into LDS: lane L's data
-// lands at lds_base + 16*L.  A BUFFER load (resource descriptor + 32-bit lane
-// offset + scalar offset) is used on purpose: its address is formed in the
-// texture-address unit, whereas global/flat loads form theirs on the vector ALU
-// and are starved for as long as another wave keeps the matrix pipe busy
-// (measured on MI355X: buffer loads keep their full rate beside back-to-back
-// MFMAs, global loads make no progress).  Issued as inline assembly so that the
-// compiler's wait-count insertion does not serialise the ring (it cannot tell
-// which stage a later LDS read touches); completion is tracked by hand with
-// vmcnt + barrier.  Nothing else in these kernels uses M0.
-__device__ __forceinline__ void load_to_lds(unsigned voff, i32x4_t srd, unsigned soff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
-               :: "v"(voff), "s"(srd), "s"(soff), "s"(lds_base) : "memory");
-}
-
-// Raw buffer resource over [base, base + bytes): reads beyond it return zero.
-__device__ __forceinline__ i32x4_t make_srd(const void* base, unsigned bytes) {
-  const unsigned long long a = (unsigned long long)base;
-  // the descriptor must live in scalar registers: base and size are wave-uniform by
-  // construction, readfirstlane makes that visible to the register allocator
-  i32x4_t r;
-  r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)(a & 0xffffffffull));
-  r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((a >> 32) & 0xffffull));   // stride 0, no swizzle
-  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
-  r[3] = 0x00020000;                                 // 32-bit data format, raw addressing
-  return r;
-}
-
-// XOR swizzle of the 16-byte chunks of an LDS row, a function of the row's low
-// four bits chosen so that 16 (and any aligned 8) consecutive rows of one logical
-// chunk fall into distinct 16-byte bank groups.
-template <int CPR>
-__device__ __forceinline__ int swz(int row) {
-  if constexpr (CPR == 4)
-    return ((row >> 2) & 1) | ((((row >> 3) ^ (row >> 1)) & 1) << 1);
-  else
-    return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2);
-}
-
-// D = W_slab x h_tile^T for one workgroup; on return every wave holds its VB x PB
-// accumulator blocks and all waves have passed a barrier (the ring is free).
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
-__device__ __forceinline__ void tile_gemm(const void* Wp, const void* hp, long long ld_h, int B, int d,
-                                          int v, int slab, int b0, char* smem,
-                                          f32x16_t (&acc)[PB][VB]) {
-  using TL = Tile<WV, WB, VB, PB, SB, NS>;
-  constexpr int ESZ = BF16 ? 2 : 4;
-  constexpr int CPR = TL::CPR, KS = TL::KS;
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wv = wave % WV, wb = wave / WV;
-  const int l31 = lane & 31, lhalf = lane >> 5;
-
-  // Two resources: this slab of W (v rows of d) and this tile of h (rows b0..).
-  // Lane offsets are relative to them and constant over K; the K advance is the
-  // instruction's scalar offset.  Rows beyond v / B are clamped (in bounds; their
-  // results are masked or never written).
-  const int hrows = min(B - b0, TL::TP);
-  const i32x4_t srdW = make_srd((const char*)Wp + (long long)slab * v * (long long)d * ESZ,
-                                (unsigned)v * (unsigned)d * ESZ);
-  const i32x4_t srdH = make_srd((const char*)hp + (long long)b0 * ld_h * ESZ,
-                                (unsigned)((long long)(hrows - 1) * ld_h * ESZ + (long long)d * ESZ));
-  // wave-load q of this wave covers LDS rows RPL*wl .. RPL*wl+RPL-1 of every stage
-  unsigned voff[TL::LPW];
-#pragma unroll
-  for (int q = 0; q < TL::LPW; ++q) {
-    const int wl = min(wave + q * TL::NW, TL::NWL - 1);
-    const int row = wl * TL::RPL + lane / CPR;
-    const int ch = (lane % CPR) ^ swz<CPR>(row);
-    if (row < TL::TV) voff[q] = (unsigned)min(row, v - 1) * (unsigned)(d * ESZ) + ch * 16;
-    else voff[q] = (unsigned)min(row - TL::TV, hrows - 1) * (unsigned)(ld_h * ESZ) + ch * 16;
-  }
-  const unsigned lds0 = (unsigned)(size_t)smem;
-  unsigned kofs = 0;                                 // byte offset along K of the next stage to issue
-  auto issue_one = [&](int q, int buf) {   // q-th wave-load of this wave for one stage
-    const int wl = wave + q * TL::NW;
-    if (q < TL::PER || wl < TL::NWL) {
-      // a wave-load never straddles the W / h boundary (TV is a multiple of RPL)
-      const bool isW = wl * TL::RPL < TL::TV;
-      load_to_lds(voff[q], isW ? srdW : srdH, kofs, lds0 + buf * TL::STAGE + wl * 1024);
-    }
-  };
-  auto advance = [&]() {
-    kofs += SB;
-  };
-  auto issue = [&](int buf) {
-#pragma unroll
-    for (int q = 0; q < TL::LPW; ++q) issue_one(q, buf);
-    advance();
-  };
-
-#pragma unroll
-  for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[pb][vb][i] = 0.f;
-
-  const int KI = d * ESZ / SB;
-  const int sw = swz<CPR>(l31);
-  const int a_off = (wv * VB * 32 + l31) * SB + ((lhalf ^ sw) << 4);
-  const int b_off = (TL::TV + wb * PB * 32 + l31) * SB + ((lhalf ^ sw) << 4);
-
-  // logical chunk 2*ks + lhalf of a row sits at byte offset base ^ (32*ks)
-  // One k-substep: the PB*VB MFMAs on fragment set `cs`, and interleaved with them
-  // in a fixed order (pinned by scheduling barriers) the LDS reads that fetch
-  // fragment set `ns` (k-substep nks of the stage at nsrc; nullptr: none) and this
-  // substep's share of the direct-to-LDS loads for ring buffer `buf` (< 0: none).
-  // Memory instructions issued back to back keep the wave away from the matrix
-  // pipe; one behind each MFMA disappears in that MFMA's shadow.  Reads are issued
-  // in the order the next substep consumes them.
-  i32x4_t fa[2][VB], fb[2][PB];
-  constexpr int NM = PB * VB;                        // MFMAs per substep
-  constexpr int NR = VB + PB;                        // fragment reads per substep
-  constexpr int LPS = (TL::LPW + KS - 1) / KS;       // direct-to-LDS loads per substep
-  constexpr int NOPS = NR + LPS;
-  auto read_frag = [&](const char* s, int ks, int set, int r) {
-    if (r == 0) fb[set][0] = *(const i32x4_t*)(s + (b_off ^ (ks * 32)));
-    else if (r <= VB) fa[set][r - 1] = *(const i32x4_t*)(s + ((a_off + (r - 1) * 32 * SB) ^ (ks * 32)));
-    else fb[set][r - VB] = *(const i32x4_t*)(s + ((b_off + (r - VB) * 32 * SB) ^ (ks * 32)));
-  };
-  auto load_frags = [&](const char* s, int ks, int set) {
-#pragma unroll
-    for (int r = 0; r < NR; ++r) read_frag(s, ks, set, r);
-  };
-  auto substep = [&](int cs, int ks, const char* nsrc, int nks, int ns, int buf) {
-#pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      mma_step<BF16>(acc[m / VB][m % VB], fa[cs][m % VB], fb[cs][m / VB]);
-#pragma unroll
-      for (int o = 0; o < NOPS; ++o) {
-        if ((o * NM) / NOPS != m) continue;          // op o rides behind MFMA o*NM/NOPS
-        if (o < NR) {
-          if (nsrc != nullptr) read_frag(nsrc, nks, ns, o);
-        } else {
-          const int q = ks * LPS + (o - NR);
-          if (buf >= 0 && q < TL::LPW) {
-            issue_one(q, buf);
-            if (q == TL::LPW - 1) advance();
-          }
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < KI) issue(s);
-
-#if MTPC_PINGPONG
-  if constexpr (NS >= 3 && TL::NW == 8) {
-    // Ping-pong schedule for two waves per SIMD.  When both waves of a SIMD have an
-    // MFMA ready the older one always wins, and a wave that alternates MFMAs with
-    // memory instructions leaves gaps its partner cannot use; so each wave handles
-    // a stage in two clusters separated by workgroup barriers: a memory cluster
-    // (all fragment reads of the stage, the direct-to-LDS loads of stage s+NS-1)
-    // and a compute cluster (all MFMAs of the stage, back to back, at raised
-    // priority).  Waves 0-3 and 4-7 (w and w+4 share a SIMD) run one cluster apart,
-    // so each SIMD always has one wave in its compute cluster.  Every wave executes
-    // 2*KI + 2 barriers.
-    static_assert(KS == 2, "ping-pong is written for two k-substeps per stage");
-    const int group = wave >> 2;
-    if (KI > NS - 2) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-    __syncthreads();                        // stage 0 has landed everywhere
-    if (group == 1) __syncthreads();        // start one cluster late
-    for (int it = 0; it < KI; ++it) {
-      const char* cur = smem + (it % NS) * TL::STAGE;
-      // ---- memory cluster
-      load_frags(cur, 0, 0);
-      load_frags(cur, 1, 1);
-      if (it + NS - 1 < KI) issue((it + NS - 1) % NS);   // buffer of stage it-1: last read one cluster ago
-      if (group == 1) {                     // stage it+1 must be complete before the next barrier
-        if (it + NS - 1 < KI) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      __syncthreads();
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- compute cluster
-      __builtin_amdgcn_s_setprio(1);
-      substep(0, 0, nullptr, 0, 0, -1);
-      substep(1, 1, nullptr, 0, 0, -1);
-      __builtin_amdgcn_s_setprio(0);
-      if (group == 0) {
-        if (it + NS - 1 < KI) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      __syncthreads();
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (group == 0) __syncthreads();        // pairs with the late start of the other group
-  } else
-#endif
-  if constexpr (NS >= 3) {
-    // Waves issue LPW or LPW-1 loads per stage; allowing y*PER loads to stay in
-    // flight guarantees, for either kind, that all but the y youngest stages have
-    // landed (one count for all waves keeps the loop branch-free).  At the barrier
-    // of iteration `it` stage it+1 is already complete, so its first fragments are
-    // read during the last substep of stage `it`: no wave starts an iteration by
-    // waiting on LDS.
-    const int KM = max(KI - (NS - 1), 0);   // iterations whose whole look-ahead exists
-    if (KI > NS - 2) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-    __syncthreads();
-    load_frags(smem, 0, 0);
-    int it = 0;
-    for (; it < KM; ++it) {
-      MTPC_WAIT_VMCNT((NS - 3) * TL::PER);   // stage it+1 landed (stages up to it+NS-2 issued)
-      __syncthreads();                       // ... everywhere; stage it-1 is no longer read
-      const int pbuf = (it + NS - 1) % NS;   // free since the barrier: receives stage it+NS-1
-      const char* cur = smem + (it % NS) * TL::STAGE;
-      const char* nxt = smem + ((it + 1) % NS) * TL::STAGE;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if (ks + 1 < KS) substep(ks & 1, ks, cur, ks + 1, (ks + 1) & 1, pbuf);
-        else substep(ks & 1, ks, nxt, 0, 0, pbuf);
-      }
-    }
-    for (; it < KI; ++it) {
-      MTPC_WAIT_VMCNT(0);
-      __syncthreads();
-      const char* cur = smem + (it % NS) * TL::STAGE;
-      const char* nxt = (it + 1 < KI) ? smem + ((it + 1) % NS) * TL::STAGE : nullptr;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if (ks + 1 < KS) substep(ks & 1, ks, cur, ks + 1, (ks + 1) & 1, -1);
-        else substep(ks & 1, ks, nxt, 0, 0, -1);
-      }
-    }
-  } else {
-    // two stages: the other buffer is being filled while this one is multiplied
-    for (int it = 0; it < KI; ++it) {
-      MTPC_WAIT_VMCNT(0);
-      __syncthreads();                       // stage `it` landed everywhere; stage it-1 no longer read
-      const int pbuf = (it + 1 < KI) ? ((it + 1) & 1) : -1;
-      const char* cur = smem + (it & 1) * TL::STAGE;
-      load_frags(cur, 0, 0);
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        substep(ks & 1, ks, ks + 1 < KS ? cur : nullptr, ks + 1, (ks + 1) & 1, pbuf);
-    }
-  }
-  __syncthreads();     // all waves are done reading the ring
-}
-
-// Softmax statistics of every position column of the tile: max and log-sum-exp
-// over the v vocabulary rows.  Lane (l31, lhalf) of wave (wv, wb) holds, for
-// position column p = wb*PB*32 + pb*32 + l31, the vocabulary rows
-//   row(vb, i) = wv*VB*32 + vb*32 + 8*(i/4) + 4*lhalf + (i%4).
-// Contains one workgroup barrier; `red` must not be reused before the next one.
-template <int WV, int WB, int VB, int PB, int SB, int NS>
-__device__ __forceinline__ void tile_lse(const f32x16_t (&acc)[PB][VB], int v, float2* red,
-                                         float (&mx)[PB], float (&lse)[PB]) {
-  using TL = Tile<WV, WB, VB, PB, SB, NS>;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wv = wave % WV, wb = wave / WV;
-  const int l31 = lane & 31, lhalf = lane >> 5;
-  const int rbase = wv * VB * 32 + 4 * lhalf;
-#pragma unroll
-  for (int pb = 0; pb < PB; ++pb) {
-    float m = neg_inf();
-#pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-        if (row < v) m = fmaxf(m, acc[pb][vb][i]);
-      }
-    m = fmaxf(m, __shfl_xor(m, 32));
-    const float ms = (m == neg_inf()) ? 0.f : m;
-    float s = 0.f;
-#pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-        if (row < v) s += __expf(acc[pb][vb][i] - ms);
-      }
-    s += __shfl_xor(s, 32);
-    if (lhalf == 0) red[wv * TL::TP + wb * PB * 32 + pb * 32 + l31] = make_float2(m, s);
-  }
-  __syncthreads();
-#pragma unroll
-  for (int pb = 0; pb < PB; ++pb) {
-    const int p = wb * PB * 32 + pb * 32 + l31;
-    float M = neg_inf();
-#pragma unroll
-    for (int w = 0; w < WV; ++w) M = fmaxf(M, red[w * TL::TP + p].x);
-    float s = 0.f;
-#pragma unroll
-    for (int w = 0; w < WV; ++w) {
-      const float2 t = red[w * TL::TP + p];
-      if (t.y > 0.f) s += t.y * __expf(t.x - M);
-    }
-    mx[pb] = M;
-    lse[pb] = M + __logf(s);
-  }
-}
 
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE>
 __global__ __launch_bounds__(WV * WB * 64)
@@ -397,7 +33,7 @@ void k_unembed(const UnembedArgs a) {
   const int wi = slab / a.r, wj = slab - wi * a.r;
 
   f32x16_t acc[PB][VB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(a.W, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
 
   const int rbase = wv * VB * 32 + 4 * lhalf;
   float mx[PB], lse[PB];
@@ -577,7 +213,7 @@ void k_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int 
   const int l31 = lane & 31, lhalf = lane >> 5;
   const int b0 = blockIdx.x * TL::TP;
   f32x16_t acc[PB][VB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(Wsum, h, ld_h, B, d, r, 0, b0, smem, acc);
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(Wsum, d, h, ld_h, B, d, r, 0, b0, smem, acc);
   float mx[PB], lse[PB];
   tile_lse<WV, WB, VB, PB, SB, NS>(acc, r, (float2*)(smem + TL::RED_OFF), mx, lse);
   const int rbase = wv * VB * 32 + 4 * lhalf;
@@ -632,7 +268,7 @@ void k_ctx_layers(const CtxLayerArgs a) {
   const char* Rlk = (const char*)a.R + ((long long)l * a.R_layer_stride + (long long)k * a.r * a.d) * ESZ;
 
   f32x16_t acc[PB][VB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(Rlk, a.h, a.ld_h, a.B, a.d, a.r, 0, b0, smem, acc);
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(Rlk, a.d, a.h, a.ld_h, a.B, a.d, a.r, 0, b0, smem, acc);
   const int rbase = wv * VB * 32 + 4 * lhalf;
   if (a.bias != nullptr) {
     const float* bl = a.bias + (long long)l * a.bias_layer_stride + (long long)k * a.r;
@@ -720,7 +356,7 @@ void k_univariate(const UnivariateArgs a) {
 
   for (int j = 0; j < a.r; ++j) {
     f32x16_t acc[PB][VB];
-    tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(a.W, a.h, a.ld_h, a.B, a.d, a.v, wi * a.r + j, b0, smem, acc);
+    tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, wi * a.r + j, b0, smem, acc);
     float mx[PB], lse[PB];
     tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 #pragma unroll

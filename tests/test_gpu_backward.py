@@ -1,0 +1,76 @@
+"""GPU parity of the training step (Sec. 4.1 loss and its gradients) against the
+float64 reverse-mode oracle.
+
+Tolerances.  fp32 inputs: the contractions run on the fp32 matrix pipes, so every
+gradient entry agrees to 2e-5 of the tensor's largest entry.  bf16 inputs: the
+logit gradient is rounded to bf16 (relative 2^-9 per entry, independent signs)
+before the two contractions, so a gradient entry carries a random error of about
+2^-9 / sqrt(3) times the root-sum-square of its terms: the tensors agree to 3e-3
+in the Frobenius norm and every entry to 2e-2 of the largest entry.  The loss is
+a combination of prefix log-marginals and keeps their tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import mtpc_inputs as mi
+from oracle import backward as bw
+
+from gpu_util import make_head
+
+pytestmark = pytest.mark.gpu
+
+
+def check_grad(name, got, want, dtype):
+    got, want = got.cpu().numpy().astype(np.float64), np.asarray(want)
+    assert got.shape == want.shape, (name, got.shape, want.shape)
+    assert np.all(np.isfinite(got)), name
+    err = np.abs(got - want)
+    big = np.abs(want).max()
+    fro = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+    if dtype == "f32":
+        assert err.max() <= 2e-5 * big + 1e-9, f"{name}: max err {err.max():.3e} vs scale {big:.3e}"
+    else:
+        assert fro <= 3e-3, f"{name}: relative Frobenius error {fro:.3e}"
+        assert err.max() <= 2e-2 * big, f"{name}: max err {err.max():.3e} vs scale {big:.3e}"
+    return fro
+
+
+def make_case(family, dtype, B, d, n, r, v, seed):
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=seed, h_scale=1.0)
+    rng = np.random.default_rng(seed + 1)
+    targets = inp.targets.copy()
+    targets[rng.random(targets.shape) < 0.05] = -1               # a few summed-out variables
+    valid = rng.random((B, n)) > 0.15
+    coef = bw.loss_coefficients(0.8, valid, sequence=np.arange(B) // max(B // 3, 1))
+    return inp, targets.astype(np.int32), coef
+
+
+CASES = [
+    ("ff", "f32", 70, 64, 4, 1, 33, 1),
+    ("ff", "bf16", 257, 128, 3, 1, 320, 2),
+    ("cp", "f32", 70, 64, 4, 5, 33, 3),
+    ("cp", "bf16", 300, 128, 8, 16, 320, 4),
+    ("cp", "bf16", 33, 256, 2, 128, 200, 5),
+    ("cp", "f32", 1, 32, 1, 3, 7, 6),
+]
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r,v,seed", CASES)
+def test_loss_and_gradients_match_oracle(family, dtype, B, d, n, r, v, seed):
+    inp, targets, coef = make_case(family, dtype, B, d, n, r, v, seed)
+    head = make_head(inp)
+    out = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda())
+    want = bw.loss_and_gradients(family, inp.h, inp.W, inp.Wsum, inp.layers, targets, coef.astype(np.float32))
+    loss = out["loss"].cpu().numpy()
+    tol = 1e-4 if dtype == "f32" else 2e-3
+    assert np.all(np.abs(loss - want["loss"]) <= tol * np.maximum(np.abs(want["loss"]), 1e-2) + (1e-4 if dtype == "f32" else 0))
+    msg = [f"{family} {dtype} B={B} n={n} r={r} v={v}:"]
+    for name in ("dh", "dW", "dWsum"):
+        if want[name] is None:
+            assert out[name] is None
+            continue
+        msg.append(f"{name} {check_grad(name, out[name], want[name], dtype):.1e}")
+    print(" ".join(msg), "(relative Frobenius error)")
+    # a second call with the same buffers gives the same bits (nothing accumulates across calls)
+    again = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda())
+    assert torch.equal(again["dW"], out["dW"]) and torch.equal(again["dh"], out["dh"])

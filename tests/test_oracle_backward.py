@@ -61,6 +61,27 @@ def test_gradients_equal_finite_differences_of_the_numpy_loss(family):
             assert abs(fd - res[name][idx]) <= 1e-6 * max(1.0, abs(fd)), (name, idx, fd, res[name][idx])
 
 
+@pytest.mark.parametrize("family", FAMS)
+def test_summed_out_targets_follow_the_numpy_oracle(family):
+    h, W, Wsum, layers, targets, coef = setup(family, seed=4)
+    targets[0, 1] = targets[2, 3] = targets[1, 0] = -1
+    res = bw.loss_and_gradients(family, h, W, Wsum, layers, targets, coef)
+    np.testing.assert_allclose(res["P"], oc.prefix_marginals(family, h, W, Wsum, layers, targets), atol=1e-11)
+    eps, rng = 1e-6, np.random.default_rng(2)
+    for _ in range(10):
+        idx = tuple(rng.integers(0, s) for s in W.shape)
+        old = W[idx]
+        W[idx] = old + eps
+        up = numpy_loss(family, h, W, Wsum, layers, targets, coef)
+        W[idx] = old - eps
+        dn = numpy_loss(family, h, W, Wsum, layers, targets, coef)
+        W[idx] = old
+        assert abs((up - dn) / (2 * eps) - res["dW"][idx]) <= 1e-6
+    # no gradient reaches the unembedding rows of a summed-out position of a one-position batch
+    one = bw.loss_and_gradients(family, h[:1], W, Wsum, layers, targets[:1], coef[:1])
+    assert np.abs(one["dW"][1]).max() == 0.0
+
+
 def test_fully_factorised_gradient_is_softmax_minus_one_hot():
     """-log softmax(l)[x] has gradient softmax(l) - onehot(x) in l = W h (textbook)."""
     h, W, _, _, targets, coef = setup("ff", n=3, r=1, v=5, d=4, B=6, seed=9)
