@@ -320,7 +320,7 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
 // Workspace of the training step (byte offsets) and its padded strides.
 struct BwdPlan {
   Plan fwd;                 // logw, layers, evidence: as for the prefix marginals
-  size_t Ge, dLT, dL, WT, hT, total;
+  size_t Ge, dLT, dL, WT, hT, lay_tr, pi, gam, G, total;
   long long M, Mx, ldM, ldb;
 };
 
@@ -339,6 +339,13 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly)
   q.dL = take((size_t)hd->B * q.ldM * esz);
   q.WT = take((size_t)hd->d * q.ldM * esz);
   q.hT = take((size_t)hd->d * q.ldb * esz);
+  const int L = n_layers(family, hd->n);
+  if (family == MTPC_HMM && L > 0) {
+    q.lay_tr = take((size_t)q.fwd.Lst * hd->r * hd->r * 4);
+    q.pi = take((size_t)hd->B * L * hd->r * 4);
+    q.gam = take((size_t)hd->B * L * hd->r * 4);
+    q.G = take((size_t)q.fwd.Lst * hd->r * hd->r * 4);
+  }
   q.total = off;
   return q;
 }
@@ -349,11 +356,17 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
                          const float* coef, float* loss, float* dh, float* dW, float* dWsum, float* dlayers) {
   if (!targets || !coef || !loss || !dh || !dW) return MTPC_ERR_NULL;
   if (family != MTPC_FF && !dWsum) return MTPC_ERR_NULL;
-  if (family == MTPC_HMM || family == MTPC_BTREE) return MTPC_ERR_UNSUPPORTED;
+  if (family == MTPC_BTREE) return MTPC_ERR_UNSUPPORTED;
   mtpc_status s = check_head(family, hd);
   if (s != MTPC_OK) return s;
   s = check_layers(family, hd, ly);
   if (s != MTPC_OK) return s;
+  const int L = n_layers(family, hd->n);
+  if (L > 0) {
+    // layers shared by all positions only; the contextual parametrisation has no reverse pass yet
+    if (ly->R != nullptr || ly->batch_stride != 0) return MTPC_ERR_UNSUPPORTED;
+    if (!dlayers) return MTPC_ERR_NULL;
+  }
   const BwdPlan q = make_bwd_plan(family, hd, ly);
   if (!hd->workspace) return MTPC_ERR_NULL;
   if (((uintptr_t)hd->workspace & 15) || hd->workspace_bytes < q.total) return MTPC_ERR_WORKSPACE;
@@ -377,6 +390,13 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   c.coef = coef; c.Ge = (float*)(ws + q.Ge);
   c.dslT = family == MTPC_FF ? nullptr : (void*)(ws + q.dLT + (size_t)q.M * q.ldb * esz);
   c.ldb = q.ldb; c.bf16 = hd->dtype == MTPC_BF16; c.loss = loss;
+  if (family == MTPC_HMM && L > 0) {
+    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, p.Lst, hd->r, 1,
+                                    (float*)(ws + q.lay_tr), st));
+    c.lay_nat = (const float*)(ws + p.lay_nat); c.lay_tr = (const float*)(ws + q.lay_tr); c.L = p.Lst;
+    c.pi = (float*)(ws + q.pi); c.gam = (float*)(ws + q.gam); c.G = (float*)(ws + q.G);
+    c.dlayers = dlayers;
+  }
   HIP_TRY(launch_circuit_bwd(c, st));
 
   GradLogitsArgs g{};
@@ -407,18 +427,12 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   GemmArgs m{};
   m.A = ws + q.dL; m.lda = q.ldM; m.M = hd->B;                   // dh[b][k] = sum_m dL[b][m] WT[k][m]
   m.Bm = ws + q.WT; m.ldb = q.ldM; m.N = hd->d; m.K = (int)q.ldM;
-  m.C = dh; m.ldc = hd->d;
+  m.C = dh; m.ldc = hd->d; m.split = hd->B; m.C2 = nullptr;
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
-  m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)q.M;               // dW[m][k] = sum_b dLT[m][b] hT[k][b]
+  m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)q.Mx;              // dW[m][k] = sum_b dLT[m][b] hT[k][b]
   m.Bm = ws + q.hT; m.ldb = q.ldb; m.N = hd->d; m.K = (int)q.ldb;
-  m.C = dW; m.ldc = hd->d;
+  m.C = dW; m.ldc = hd->d; m.split = (int)q.M; m.C2 = dWsum;     // the last r rows are dWsum
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
-  if (family != MTPC_FF) {
-    m.A = ws + q.dLT + (size_t)q.M * q.ldb * esz; m.M = hd->r;
-    m.C = dWsum;
-    HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
-  }
-  (void)dlayers;
   return MTPC_OK;
 }
 

@@ -47,9 +47,35 @@ __global__ __launch_bounds__(256) void k_transpose(const TransposeArgs a) {
   }
 }
 
+// acc_u = sum_k sh[k] * M[k*r + unit_u] for the lane's units (lane, lane + 64); M is an
+// r x r matrix in global memory read along its contiguous axis, eight rows in flight.
+__device__ __forceinline__ void wave_matvec(const float* __restrict__ M, const float* sh, int r, int lane,
+                                            float& acc0, float& acc1) {
+  const bool u1 = lane + 64 < r;
+  const int c0 = min(lane, r - 1), c1 = min(lane + 64, r - 1);
+  acc0 = acc1 = 0.f;
+  for (int k0 = 0; k0 < r; k0 += 8) {
+    float w0[8], w1[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const long long k = min(k0 + u, r - 1);
+      w0[u] = M[k * r + c0];
+      w1[u] = u1 ? M[k * r + c1] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (k0 + u < r) {
+        const float x = sh[k0 + u];
+        acc0 = fmaf(x, w0[u], acc0);
+        acc1 = fmaf(x, w1[u], acc1);
+      }
+  }
+}
+
 // One wave per evidence row; lane l holds units l and l + 64.
 __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
   __shared__ float sP[4][64];
+  __shared__ float sX[4][128];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const long long row = (long long)blockIdx.x * 4 + wave;
   const int n = a.n, r = a.r;
@@ -114,6 +140,134 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
     if (lane == 0) a.loss[row] = loss;
     return;
   }
+
+  if (a.family == MTPC_HMM) {
+    // forward messages (Eq. HMM) alpha_j, kept in Ge[j] until the reverse pass replaces them
+    // by their adjoints.  With pi_j = softmax(alpha_j), pred_j = pi_j T_j (predicted next
+    // state) and gam_j = adj(alpha_{j+1}) / pred_j:
+    //   adj(alpha_j) = g_j pi_j + pi_j * (T_j gam_j),   d loss / d log T_j[z][z'] = pi_j[z] T_j[z][z'] gam_j[z'].
+    float* sh = sX[wave];
+    const long long lstep = a.L > 1 ? (long long)r * r : 0;
+    float al0 = w0 + (u0 ? e[lane] : 0.f), al1 = w1 + (u1 ? e[lane + 64] : 0.f);
+    float loss = 0.f;
+    for (int j = 0; j < n; ++j) {
+      if (j > 0) {
+        const float m = wmax(fmaxf(al0, al1));
+        const float ms = m == ninf ? 0.f : m;
+        if (u0) sh[lane] = __expf(al0 - ms);
+        if (u1) sh[lane + 64] = __expf(al1 - ms);
+        __builtin_amdgcn_wave_barrier();
+        float s0, s1;
+        wave_matvec(a.lay_nat + (j - 1) * lstep, sh, r, lane, s0, s1);
+        __builtin_amdgcn_wave_barrier();
+        al0 = u0 ? ms + __logf(s0) + e[j * r + lane] : ninf;
+        al1 = u1 ? ms + __logf(s1) + e[j * r + lane + 64] : ninf;
+      }
+      if (u0) Ge[j * r + lane] = al0;
+      if (u1) Ge[j * r + lane + 64] = al1;
+      const float m = wmax(fmaxf(al0, al1));
+      const float P = m + __logf(wsum((u0 ? __expf(al0 - m) : 0.f) + (u1 ? __expf(al1 - m) : 0.f)));
+      if (lane == 0) sP[wave][j] = P;
+      loss += g_of(j) * P;
+    }
+    __builtin_amdgcn_wave_barrier();
+    float ad0 = 0.f, ad1 = 0.f;                     // adjoint of alpha_{j+1}
+    float nx0 = 0.f, nx1 = 0.f;                     // alpha_{j+1} - e_{j+1}
+    for (int j = n - 1; j >= 0; --j) {
+      const float P = sP[wave][j], g = g_of(j);
+      const float cur0 = u0 ? Ge[j * r + lane] : ninf, cur1 = u1 ? Ge[j * r + lane + 64] : ninf;
+      const float pi0 = u0 ? __expf(cur0 - P) : 0.f, pi1 = u1 ? __expf(cur1 - P) : 0.f;
+      float n0 = g * pi0, n1 = g * pi1;
+      if (j < n - 1) {
+        const float pr0 = __expf(nx0 - P), pr1 = __expf(nx1 - P);          // predicted next state
+        const float gm0 = (u0 && pr0 > 0.f) ? ad0 / pr0 : 0.f, gm1 = (u1 && pr1 > 0.f) ? ad1 / pr1 : 0.f;
+        if (u0) sh[lane] = gm0;
+        if (u1) sh[lane + 64] = gm1;
+        __builtin_amdgcn_wave_barrier();
+        float c0, c1;
+        wave_matvec(a.lay_tr + j * lstep, sh, r, lane, c0, c1);            // (T_j gam)[z] via T_j^T
+        __builtin_amdgcn_wave_barrier();
+        n0 += pi0 * c0;
+        n1 += pi1 * c1;
+        if (a.pi != nullptr) {
+          float* pp = a.pi + (row * (n - 1) + j) * r;
+          float* gp = a.gam + (row * (n - 1) + j) * r;
+          if (u0) { pp[lane] = pi0; gp[lane] = gm0; }
+          if (u1) { pp[lane + 64] = pi1; gp[lane + 64] = gm1; }
+        }
+      }
+      nx0 = u0 ? cur0 - e[j * r + lane] : ninf;
+      nx1 = u1 ? cur1 - e[j * r + lane + 64] : ninf;
+      ad0 = n0; ad1 = n1;
+      if (u0) Ge[j * r + lane] = n0;
+      if (u1) Ge[j * r + lane + 64] = n1;
+    }
+    const float tot = wsum((u0 ? ad0 : 0.f) + (u1 ? ad1 : 0.f));
+    put_dsl(ad0 - __expf(w0) * tot, ad1 - __expf(w1) * tot);
+    if (lane == 0) a.loss[row] = loss;
+    return;
+  }
+}
+
+// G[l][z][z'] += sum over a block of rows of pi[b][j][z] * gam[b][j][z'], l = j (or 0 for a
+// shared layer).  Thread t owns outputs t, t + 256, ...: NO of them.
+template <int NO>
+__global__ __launch_bounds__(256) void k_layer_outer(const float* pi, const float* gam, int rows, int steps,
+                                                     int r, int L, int rows_per_block, float* G) {
+  __shared__ float sp[16][128], sg[16][128];
+  const int j = blockIdx.x, tid = threadIdx.x;
+  const long long b0 = (long long)blockIdx.y * rows_per_block;
+  const long long b1 = min((long long)rows, b0 + rows_per_block);
+  float acc[NO];
+#pragma unroll
+  for (int q = 0; q < NO; ++q) acc[q] = 0.f;
+  for (long long c0 = b0; c0 < b1; c0 += 16) {
+    __syncthreads();
+    for (int idx = tid; idx < 16 * r; idx += 256) {
+      const long long b = c0 + idx / r;
+      const int z = idx % r;
+      const bool ok = b < b1;
+      sp[idx / r][z] = ok ? pi[(b * steps + j) * r + z] : 0.f;
+      sg[idx / r][z] = ok ? gam[(b * steps + j) * r + z] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < NO; ++q) {
+      const int o = tid + q * 256;
+      if (o < r * r) {
+        const int z = o / r, zz = o - z * r;
+        float s = 0.f;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) s = fmaf(sp[t][z], sg[t][zz], s);
+        acc[q] += s;
+      }
+    }
+  }
+  float* dst = G + (L > 1 ? (long long)j * r * r : 0);
+#pragma unroll
+  for (int q = 0; q < NO; ++q) {
+    const int o = tid + q * 256;
+    if (o < r * r) atomicAdd(dst + o, acc[q]);
+  }
+}
+
+// softmax backward of every layer row: dlogit[l][z][:] = T (.) (G - sum_z' T G); one wave per row
+__global__ __launch_bounds__(256) void k_layer_finish(const float* G, const float* T, int nrows, int r,
+                                                      float* dlayers) {
+  const int lane = threadIdx.x & 63;
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= nrows) return;
+  const bool u0 = lane < r, u1 = lane + 64 < r;
+  const float t0 = u0 ? T[row * r + lane] : 0.f, t1 = u1 ? T[row * r + lane + 64] : 0.f;
+  const float g0 = u0 ? G[row * r + lane] : 0.f, g1 = u1 ? G[row * r + lane + 64] : 0.f;
+  const float s = wsum(t0 * g0 + t1 * g1);
+  if (u0) dlayers[row * r + lane] = t0 * (g0 - s);
+  if (u1) dlayers[row * r + lane + 64] = t1 * (g1 - s);
+}
+
+__global__ __launch_bounds__(256) void k_fill_zero(float* p, long long n) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
 }
 
 }  // namespace
@@ -128,7 +282,24 @@ hipError_t launch_transpose(const TransposeArgs& a, int dtype, hipStream_t st) {
 
 hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
   const long long rows = a.dslT ? a.ldb : a.rows;
+  const int r = a.r;
+  const bool layers = a.dlayers != nullptr && a.family == MTPC_HMM && a.n > 1;
+  if (layers) {
+    const long long cnt = (long long)a.L * r * r;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.G, cnt);
+  }
   hipLaunchKernelGGL(k_circuit_bwd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, a);
+  if (layers) {
+    const int steps = a.n - 1, rpb = 256;
+    const dim3 grid(steps, (unsigned)((a.rows + rpb - 1) / rpb));
+    const int no = (r * r + 255) / 256;
+    if (no <= 1) hipLaunchKernelGGL(k_layer_outer<1>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G);
+    else if (no <= 4) hipLaunchKernelGGL(k_layer_outer<4>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G);
+    else if (no <= 16) hipLaunchKernelGGL(k_layer_outer<16>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G);
+    else hipLaunchKernelGGL(k_layer_outer<64>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G);
+    const int nrows = a.L * r;
+    hipLaunchKernelGGL(k_layer_finish, dim3((nrows + 3) / 4), dim3(256), 0, st, a.G, a.lay_nat, nrows, r, a.dlayers);
+  }
   return hipGetLastError();
 }
 

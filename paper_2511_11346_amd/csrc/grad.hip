@@ -131,7 +131,11 @@ void k_gemm_tn(const GemmArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-        if (row < rows) a.C[((long long)slab * TL::TV + row) * a.ldc + col] = acc[pb][vb][i];
+        if (row < rows) {
+          const long long gr = (long long)slab * TL::TV + row;
+          if (gr < a.split) a.C[gr * a.ldc + col] = acc[pb][vb][i];
+          else a.C2[(gr - a.split) * a.ldc + col] = acc[pb][vb][i];
+        }
       }
   }
 }

@@ -148,13 +148,14 @@ struct GradLogitsArgs {
 };
 hipError_t launch_unembed_grad(const GradLogitsArgs& a, int dtype, hipStream_t st);
 
-// C[M][N] (fp32, row stride ldc) = A[M][K] * B[N][K]^T, both operands K-contiguous
+// C[M][N] (fp32, row stride ldc; optionally split by rows over two buffers) = A[M][K] * B[N][K]^T, both operands K-contiguous
 // with row strides lda / ldb (elements); K a multiple of 32 (bf16) or 16 (fp32).
 struct GemmArgs {
   const void* A; long long lda; int M;
   const void* Bm; long long ldb; int N;
   int K;
   float* C; long long ldc;
+  int split; float* C2;   // rows >= split go to C2[(row - split)][ldc] (split >= M: none)
 };
 hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t st);
 
@@ -174,7 +175,11 @@ struct CircuitBwdArgs {
   const float* logw;     // [rows][r] (nullptr for FF)
   const float* coef;     // [rows][n]
   const float* lay_nat;  // normalised linear layers [L][k][j] (static only)
+  const float* lay_tr;   // the same transposed [L][j][k]
   int L;
+  float* pi;             // scratch [rows][n-1][r] (layer gradients only)
+  float* gam;            // scratch [rows][n-1][r]
+  float* G;              // scratch [L][r][r]
   float* Ge;             // [rows][n][r]
   void* dslT;            // [r][ldb] or nullptr
   long long ldb;

@@ -36,7 +36,10 @@ def check_grad(name, got, want, dtype):
 
 
 def make_case(family, dtype, B, d, n, r, v, seed):
-    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=seed, h_scale=1.0)
+    shared = family.endswith("-shared")                          # one transition matrix for all steps
+    family = family.split("-")[0]
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=seed, h_scale=1.0,
+                         layer_count=1 if shared else None)
     rng = np.random.default_rng(seed + 1)
     targets = inp.targets.copy()
     targets[rng.random(targets.shape) < 0.05] = -1               # a few summed-out variables
@@ -52,24 +55,31 @@ CASES = [
     ("cp", "bf16", 300, 128, 8, 16, 320, 4),
     ("cp", "bf16", 33, 256, 2, 128, 200, 5),
     ("cp", "f32", 1, 32, 1, 3, 7, 6),
+    ("hmm", "f32", 70, 64, 4, 5, 33, 7),
+    ("hmm", "bf16", 300, 128, 8, 32, 320, 8),
+    ("hmm", "bf16", 40, 64, 16, 128, 64, 9),
+    ("hmm", "f32", 9, 32, 1, 4, 12, 10),
+    ("hmm-shared", "f32", 50, 64, 6, 8, 40, 11),
 ]
 
 
 @pytest.mark.parametrize("family,dtype,B,d,n,r,v,seed", CASES)
 def test_loss_and_gradients_match_oracle(family, dtype, B, d, n, r, v, seed):
     inp, targets, coef = make_case(family, dtype, B, d, n, r, v, seed)
+    family = inp.family
     head = make_head(inp)
     out = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda())
-    want = bw.loss_and_gradients(family, inp.h, inp.W, inp.Wsum, inp.layers, targets, coef.astype(np.float32))
+    layers = inp.layers if inp.layers is not None and inp.layers.size else None
+    want = bw.loss_and_gradients(family, inp.h, inp.W, inp.Wsum, layers, targets, coef.astype(np.float32))
     loss = out["loss"].cpu().numpy()
     tol = 1e-4 if dtype == "f32" else 2e-3
     assert np.all(np.abs(loss - want["loss"]) <= tol * np.maximum(np.abs(want["loss"]), 1e-2) + (1e-4 if dtype == "f32" else 0))
     msg = [f"{family} {dtype} B={B} n={n} r={r} v={v}:"]
-    for name in ("dh", "dW", "dWsum"):
-        if want[name] is None:
-            assert out[name] is None
+    for name in ("dh", "dW", "dWsum", "dlayers"):
+        if want[name] is None or want[name].size == 0:
             continue
-        msg.append(f"{name} {check_grad(name, out[name], want[name], dtype):.1e}")
+        # layer gradients never pass through the bf16 logit gradient: fp32 accuracy for both dtypes
+        msg.append(f"{name} {check_grad(name, out[name], want[name], 'f32' if name == 'dlayers' else dtype):.1e}")
     print(" ".join(msg), "(relative Frobenius error)")
     # a second call with the same buffers gives the same bits (nothing accumulates across calls)
     again = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda())
