@@ -195,8 +195,8 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
  * gradient).  Workspace: mtpc_workspace_bytes(family, MTPC_OP_BACKWARD, ...).
  * dlayers has the shape of the stored layer logits ([n-1][r][r], or [1][r][r] for a
  * shared matrix, whose gradient is the sum over the steps).
- * Not yet available (MTPC_ERR_UNSUPPORTED): the binary tree, and layers given per
- * position or computed from h (mtpc_sumlayers.R, batch_stride). */
+ * Not yet available (MTPC_ERR_UNSUPPORTED): layers given per position or computed
+ * from h (mtpc_sumlayers.R, batch_stride). */
 mtpc_status mtpc_ff_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
                                   float* loss, float* dh, float* dW);
 mtpc_status mtpc_cp_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,

@@ -320,7 +320,8 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
 // Workspace of the training step (byte offsets) and its padded strides.
 struct BwdPlan {
   Plan fwd;                 // logw, layers, evidence: as for the prefix marginals
-  size_t Ge, dLT, dL, WT, hT, lay_tr, pi, gam, G, total;
+  size_t Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, total;
+  int steps;                // reverse-pass steps with a layer (HMM: n-1; tree: program length)
   long long M, Mx, ldM, ldb;
 };
 
@@ -340,11 +341,17 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly)
   q.WT = take((size_t)hd->d * q.ldM * esz);
   q.hT = take((size_t)hd->d * q.ldb * esz);
   const int L = n_layers(family, hd->n);
-  if (family == MTPC_HMM && L > 0) {
+  q.steps = family == MTPC_BTREE ? tree_program_steps(hd->n, 1) : L;
+  if (L > 0) {
+    q.lay_nat = take((size_t)q.fwd.Lst * hd->r * hd->r * 4);
     q.lay_tr = take((size_t)q.fwd.Lst * hd->r * hd->r * 4);
-    q.pi = take((size_t)hd->B * L * hd->r * 4);
-    q.gam = take((size_t)hd->B * L * hd->r * 4);
+    q.pi = take((size_t)hd->B * q.steps * hd->r * 4);
+    q.gam = take((size_t)hd->B * q.steps * hd->r * 4);
     q.G = take((size_t)q.fwd.Lst * hd->r * hd->r * 4);
+  }
+  if (family == MTPC_BTREE) {
+    q.ct = take((size_t)hd->B * q.steps * hd->r * 4);
+    q.adj = take((size_t)hd->B * (hd->n - 1) * hd->r * 4);
   }
   q.total = off;
   return q;
@@ -356,7 +363,6 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
                          const float* coef, float* loss, float* dh, float* dW, float* dWsum, float* dlayers) {
   if (!targets || !coef || !loss || !dh || !dW) return MTPC_ERR_NULL;
   if (family != MTPC_FF && !dWsum) return MTPC_ERR_NULL;
-  if (family == MTPC_BTREE) return MTPC_ERR_UNSUPPORTED;
   mtpc_status s = check_head(family, hd);
   if (s != MTPC_OK) return s;
   s = check_layers(family, hd, ly);
@@ -390,12 +396,17 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   c.coef = coef; c.Ge = (float*)(ws + q.Ge);
   c.dslT = family == MTPC_FF ? nullptr : (void*)(ws + q.dLT + (size_t)q.M * q.ldb * esz);
   c.ldb = q.ldb; c.bf16 = hd->dtype == MTPC_BF16; c.loss = loss;
-  if (family == MTPC_HMM && L > 0) {
+  if (L > 0) {
+    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, p.Lst, hd->r, 0,
+                                    (float*)(ws + q.lay_nat), st));
     HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, p.Lst, hd->r, 1,
                                     (float*)(ws + q.lay_tr), st));
-    c.lay_nat = (const float*)(ws + p.lay_nat); c.lay_tr = (const float*)(ws + q.lay_tr); c.L = p.Lst;
+    c.lay_nat = (const float*)(ws + q.lay_nat); c.lay_tr = (const float*)(ws + q.lay_tr); c.L = p.Lst;
     c.pi = (float*)(ws + q.pi); c.gam = (float*)(ws + q.gam); c.G = (float*)(ws + q.G);
     c.dlayers = dlayers;
+  }
+  if (family == MTPC_BTREE) {
+    c.ct = (float*)(ws + q.ct); c.adj = (float*)(ws + q.adj);
   }
   HIP_TRY(launch_circuit_bwd(c, st));
 

@@ -209,13 +209,171 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
   }
 }
 
+// Binary tree (Eq. BTree), one wave per evidence row.  The forward pass walks the
+// tree program (full node values bottom-up, then the path of every prefix) and keeps
+// the output of every step; the reverse pass walks it backwards.  For a step
+// c[k] = log sum_j A[k][j] exp(x[j]) with x the sum of its two operands:
+//   xi[j] = exp(x[j] - max x),  delta[k] = adj(c)[k] exp(max x - c[k]),
+//   adj(x)[j] = xi[j] sum_k A[k][j] delta[k],   d loss / d log A[k][j] = delta[k] A[k][j] xi[j],
+// and adj(x) goes to both operands (leaf: evidence gradient; stored node: its
+// adjoint; path value: the adjoint consumed by the previous step of the path).
+__global__ __launch_bounds__(256) void k_btree_bwd(const CircuitBwdArgs a, int nsteps_max) {
+  extern __shared__ TreeStep bprog[];
+  __shared__ float sX[4][128];
+  __shared__ int s_nsteps;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long row = (long long)blockIdx.x * 4 + wave;
+  const int n = a.n, r = a.r;
+  const bool u0 = lane < r, u1 = lane + 64 < r;
+  if (threadIdx.x == 0) s_nsteps = build_tree_program(bprog, n, 1);
+  __syncthreads();
+  const int T = s_nsteps;
+  auto put_dsl = [&](float v0, float v1) {
+    if (a.dslT == nullptr || row >= a.ldb) return;
+    if (a.bf16) {
+      unsigned short* d = (unsigned short*)a.dslT;
+      if (u0) d[(long long)lane * a.ldb + row] = to_bf16_rne(v0);
+      if (u1) d[(long long)(lane + 64) * a.ldb + row] = to_bf16_rne(v1);
+    } else {
+      float* d = (float*)a.dslT;
+      if (u0) d[(long long)lane * a.ldb + row] = v0;
+      if (u1) d[(long long)(lane + 64) * a.ldb + row] = v1;
+    }
+  };
+  if (row >= a.rows) {
+    put_dsl(0.f, 0.f);
+    return;
+  }
+  const float ninf = neg_inf();
+  const float* e = a.e + row * n * r;
+  const float* coef = a.coef + row * n;
+  float* Ge = a.Ge + row * n * r;
+  float* ct = a.ct + row * nsteps_max * r;           // output of every step
+  float* ad = a.adj + row * (long long)(n - 1) * r;   // adjoints of the stored node values
+  float* sh = sX[wave];
+  const float* lw = a.logw + row * r;
+  const float w0 = u0 ? lw[lane] : ninf, w1 = u1 ? lw[lane + 64] : ninf;
+  const long long lstep = a.L > 1 ? (long long)r * r : 0;
+  auto g_of = [&](int j) { return (j + 1 < n ? coef[j + 1] : 0.f) - coef[j]; };
+  // value of an operand for the lane's two units; path values live in ct[t-1]
+  auto operand = [&](int src, int t, float& x0, float& x1) {
+    if (src == -2) { x0 = u0 ? 0.f : ninf; x1 = u1 ? 0.f : ninf; return; }
+    const float* p;
+    if (src == -1) p = ct + (long long)(t - 1) * r;
+    else if (src >= n - 1) p = e + (long long)(src - (n - 1)) * r;
+    else p = ct + (long long)(n - 2 - src) * r;      // node m is the output of up-pass step n-2-m
+    x0 = u0 ? p[lane] : ninf;
+    x1 = u1 ? p[lane + 64] : ninf;
+  };
+
+  // ---- forward
+  float loss = 0.f;
+  for (int t = 0; t < T; ++t) {
+    const TreeStep st = bprog[t];
+    float l0, l1, r0, r1;
+    operand(st.lsrc, t, l0, l1);
+    operand(st.rsrc, t, r0, r1);
+    float x0 = l0 + r0, x1 = l1 + r1;
+    if (st.m == 0) {
+      x0 += w0; x1 += w1;
+      const float m = wmax(fmaxf(x0, x1));
+      const float P = m + __logf(wsum((u0 ? __expf(x0 - m) : 0.f) + (u1 ? __expf(x1 - m) : 0.f)));
+      loss += g_of(-2 - st.out) * P;
+      if (lane == 0) ct[(long long)t * r] = P;       // the root step keeps its scalar
+      continue;
+    }
+    const float m = wmax(fmaxf(x0, x1));
+    const float ms = m == ninf ? 0.f : m;
+    if (u0) sh[lane] = __expf(x0 - ms);
+    if (u1) sh[lane + 64] = __expf(x1 - ms);
+    __builtin_amdgcn_wave_barrier();
+    float s0, s1;
+    wave_matvec(a.lay_tr + (st.m - 1) * lstep, sh, r, lane, s0, s1);       // sum_j A[k][j] xi[j] via A^T
+    __builtin_amdgcn_wave_barrier();
+    if (u0) ct[(long long)t * r + lane] = ms + __logf(s0);
+    if (u1) ct[(long long)t * r + lane + 64] = ms + __logf(s1);
+  }
+  // ---- reverse
+  for (int idx = lane; idx < (n - 1) * r; idx += 64) ad[idx] = 0.f;
+  for (int idx = lane; idx < n * r; idx += 64) Ge[idx] = 0.f;
+  __builtin_amdgcn_wave_barrier();
+  float gw0 = 0.f, gw1 = 0.f;                        // gradient w.r.t. log omega
+  float pv0 = 0.f, pv1 = 0.f;                        // adjoint of the path value of the step above
+  auto scatter = [&](int src, float a0, float a1) {
+    if (src == -2) return;
+    if (src == -1) { pv0 = a0; pv1 = a1; return; }
+    float* p = src >= n - 1 ? Ge + (long long)(src - (n - 1)) * r : ad + (long long)(src - 1) * r;
+    if (u0) p[lane] += a0;
+    if (u1) p[lane + 64] += a1;
+  };
+  for (int t = T - 1; t >= 0; --t) {
+    const TreeStep st = bprog[t];
+    float l0, l1, r0, r1;
+    operand(st.lsrc, t, l0, l1);
+    operand(st.rsrc, t, r0, r1);
+    float x0 = l0 + r0, x1 = l1 + r1;
+    float xb0, xb1;                                  // adjoint of x
+    if (st.m == 0) {
+      const float P = ct[(long long)t * r], g = g_of(-2 - st.out);
+      xb0 = u0 ? g * __expf(x0 + w0 - P) : 0.f;
+      xb1 = u1 ? g * __expf(x1 + w1 - P) : 0.f;
+      gw0 += xb0; gw1 += xb1;
+    } else {
+      float cb0, cb1;                                // adjoint of this step's output
+      if (st.out >= 0) {
+        cb0 = u0 ? ad[(long long)(st.out - 1) * r + lane] : 0.f;
+        cb1 = u1 ? ad[(long long)(st.out - 1) * r + lane + 64] : 0.f;
+      } else {
+        cb0 = pv0; cb1 = pv1;
+      }
+      const float m = wmax(fmaxf(x0, x1));
+      const float ms = m == ninf ? 0.f : m;
+      const float xi0 = u0 ? __expf(x0 - ms) : 0.f, xi1 = u1 ? __expf(x1 - ms) : 0.f;
+      const float c0 = u0 ? ct[(long long)t * r + lane] : 0.f, c1 = u1 ? ct[(long long)t * r + lane + 64] : 0.f;
+      const float d0 = (u0 && cb0 != 0.f) ? cb0 * __expf(ms - c0) : 0.f;
+      const float d1 = (u1 && cb1 != 0.f) ? cb1 * __expf(ms - c1) : 0.f;
+      if (u0) sh[lane] = d0;
+      if (u1) sh[lane + 64] = d1;
+      __builtin_amdgcn_wave_barrier();
+      float s0, s1;
+      wave_matvec(a.lay_nat + (st.m - 1) * lstep, sh, r, lane, s0, s1);     // sum_k A[k][j] delta[k]
+      __builtin_amdgcn_wave_barrier();
+      xb0 = xi0 * s0; xb1 = xi1 * s1;
+      if (a.pi != nullptr) {
+        float* pp = a.pi + (row * nsteps_max + t) * r;
+        float* gp = a.gam + (row * nsteps_max + t) * r;
+        if (u0) { pp[lane] = d0; gp[lane] = xi0; }
+        if (u1) { pp[lane + 64] = d1; gp[lane + 64] = xi1; }
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    scatter(st.lsrc, xb0, xb1);
+    scatter(st.rsrc, xb0, xb1);
+    __builtin_amdgcn_wave_barrier();
+  }
+  const float tot = wsum((u0 ? gw0 : 0.f) + (u1 ? gw1 : 0.f));
+  put_dsl(gw0 - __expf(w0) * tot, gw1 - __expf(w1) * tot);
+  if (lane == 0) a.loss[row] = loss;
+}
+
 // G[l][z][z'] += sum over a block of rows of pi[b][j][z] * gam[b][j][z'], l = j (or 0 for a
 // shared layer).  Thread t owns outputs t, t + 256, ...: NO of them.
+// In tree mode (tree_n > 0) step j applies the layer of node prog[j].m (root steps: none).
 template <int NO>
 __global__ __launch_bounds__(256) void k_layer_outer(const float* pi, const float* gam, int rows, int steps,
-                                                     int r, int L, int rows_per_block, float* G) {
+                                                     int r, int L, int rows_per_block, float* G, int tree_n) {
+  extern __shared__ TreeStep oprog[];
   __shared__ float sp[16][128], sg[16][128];
   const int j = blockIdx.x, tid = threadIdx.x;
+  int layer = j;
+  if (tree_n > 0) {
+    __shared__ int s_cnt;
+    if (tid == 0) s_cnt = build_tree_program(oprog, tree_n, 1);
+    __syncthreads();
+    if (j >= s_cnt) return;                 // the grid is sized by an upper bound of the program length
+    layer = oprog[j].m - 1;
+    if (layer < 0) return;
+  }
   const long long b0 = (long long)blockIdx.y * rows_per_block;
   const long long b1 = min((long long)rows, b0 + rows_per_block);
   float acc[NO];
@@ -243,7 +401,7 @@ __global__ __launch_bounds__(256) void k_layer_outer(const float* pi, const floa
       }
     }
   }
-  float* dst = G + (L > 1 ? (long long)j * r * r : 0);
+  float* dst = G + (L > 1 ? (long long)layer * r * r : 0);
 #pragma unroll
   for (int q = 0; q < NO; ++q) {
     const int o = tid + q * 256;
@@ -283,20 +441,25 @@ hipError_t launch_transpose(const TransposeArgs& a, int dtype, hipStream_t st) {
 hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
   const long long rows = a.dslT ? a.ldb : a.rows;
   const int r = a.r;
-  const bool layers = a.dlayers != nullptr && a.family == MTPC_HMM && a.n > 1;
+  const bool tree = a.family == MTPC_BTREE;
+  const int T = tree ? tree_program_steps(a.n, 1) : a.n - 1;
+  const size_t prog_bytes = tree ? (size_t)T * sizeof(TreeStep) : 0;
+  const bool layers = a.dlayers != nullptr && ((a.family == MTPC_HMM && a.n > 1) || (tree && a.n > 2));
   if (layers) {
     const long long cnt = (long long)a.L * r * r;
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.G, cnt);
   }
-  hipLaunchKernelGGL(k_circuit_bwd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, a);
+  if (tree) hipLaunchKernelGGL(k_btree_bwd, dim3((unsigned)((rows + 3) / 4)), dim3(256), prog_bytes, st, a, T);
+  else hipLaunchKernelGGL(k_circuit_bwd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, a);
   if (layers) {
-    const int steps = a.n - 1, rpb = 256;
+    const int steps = T, rpb = 256;
+    const int tn = tree ? a.n : 0;
     const dim3 grid(steps, (unsigned)((a.rows + rpb - 1) / rpb));
     const int no = (r * r + 255) / 256;
-    if (no <= 1) hipLaunchKernelGGL(k_layer_outer<1>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G);
-    else if (no <= 4) hipLaunchKernelGGL(k_layer_outer<4>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G);
-    else if (no <= 16) hipLaunchKernelGGL(k_layer_outer<16>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G);
-    else hipLaunchKernelGGL(k_layer_outer<64>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G);
+    if (no <= 1) hipLaunchKernelGGL(k_layer_outer<1>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
+    else if (no <= 4) hipLaunchKernelGGL(k_layer_outer<4>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
+    else if (no <= 16) hipLaunchKernelGGL(k_layer_outer<16>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
+    else hipLaunchKernelGGL(k_layer_outer<64>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
     const int nrows = a.L * r;
     hipLaunchKernelGGL(k_layer_finish, dim3((nrows + 3) / 4), dim3(256), 0, st, a.G, a.lay_nat, nrows, r, a.dlayers);
   }

@@ -446,38 +446,6 @@ static hipError_t launch_circuit_rb(const CircuitArgs& a, hipStream_t st) {
 // into LDS while step t is multiplied, and no group waits on global memory for
 // weights.  A group of G lanes owns RB = 4 rows, r <= 64.
 // ---------------------------------------------------------------------------
-struct TreeStep {
-  short m;        // inner node whose layer is applied (0: root, uses log omega instead of a layer)
-  short lsrc;     // left operand: >= 0 heap index of a fully observed child, -1 path value, -2 all-ones
-  short rsrc;     // right operand, same coding
-  short out;      // >= 0: store as full value of node `out`; -1: becomes the path value; -2 - i: emit prefix i
-};
-
-__device__ int build_tree_program(TreeStep* prog, int n, int prefix) {
-  int t = 0;
-  for (int m = n - 2; m >= 1; --m) prog[t++] = TreeStep{(short)m, (short)(2 * m + 1), (short)(2 * m + 2), (short)m};
-  if (!prefix) {
-    prog[t++] = TreeStep{0, 1, 2, (short)(-2 - (n - 1))};
-    return t;
-  }
-  for (int i = 0; i < n; ++i) {
-    int idx = n - 1 + i, size = 1;
-    while (idx > 0) {
-      const int m = (idx - 1) >> 1;
-      size <<= 1;
-      const int first = (m - (n / size - 1)) * size, last = first + size - 1;
-      if (m > 0 && last <= i) { idx = m; continue; }          // fully observed: stored value
-      const int half = size >> 1;
-      const int l_last = first + half - 1, r_first = first + half;
-      const short ls = (l_last <= i) ? (short)(2 * m + 1) : (short)-1;
-      const short rs = (r_first > i) ? (short)-2 : (last <= i ? (short)(2 * m + 2) : (short)-1);
-      prog[t++] = TreeStep{(short)m, ls, rs, (short)(m > 0 ? -1 : -2 - i)};
-      idx = m;
-    }
-  }
-  return t;
-}
-
 // One sum layer for the RB rows of a group with the layer in LDS and one unit per
 // lane (r <= 64):  c[q] <- log sum_j Wl[j][g] exp(c[q][j]).  Lanes g >= r hold -inf.
 template <int RB>
@@ -676,13 +644,6 @@ __global__ __launch_bounds__(256) void k_btree_static(const CircuitArgs a, int G
     }
     fetch_store(t + 1);
   }
-}
-
-static int tree_program_steps(int n, int prefix) {
-  if (!prefix) return n - 2 + 1;
-  int lg = 0;
-  while ((1 << lg) < n) ++lg;
-  return n - 2 + n * lg;          // upper bound: at most log2(n) steps per prefix
 }
 
 #ifndef MTPC_BTREE_RB

@@ -177,9 +177,11 @@ struct CircuitBwdArgs {
   const float* lay_nat;  // normalised linear layers [L][k][j] (static only)
   const float* lay_tr;   // the same transposed [L][j][k]
   int L;
-  float* pi;             // scratch [rows][n-1][r] (layer gradients only)
-  float* gam;            // scratch [rows][n-1][r]
+  float* pi;             // scratch [rows][steps][r] (layer gradients only; steps = n-1 for the HMM)
+  float* gam;            // scratch [rows][steps][r]
   float* G;              // scratch [L][r][r]
+  float* ct;             // binary tree: scratch [rows][steps][r], output of every program step
+  float* adj;            // binary tree: scratch [rows][n-1][r], adjoints of the node values
   float* Ge;             // [rows][n][r]
   void* dslT;            // [r][ldb] or nullptr
   long long ldb;
@@ -221,6 +223,48 @@ __device__ __forceinline__ float philox_uniform(uint32_t seed_lo, uint32_t seed_
 }
 
 __device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
+
+// ---- evaluation order of the binary tree (Eq. BTree) ---------------------------
+// The order in which the tree's nodes are evaluated does not depend on the data: a
+// kernel writes it once as a short program, one step per sum-layer application.
+struct TreeStep {
+  short m;        // inner node whose layer is applied (0: root, uses log omega instead of a layer)
+  short lsrc;     // left operand: >= 0 heap index of a fully observed child, -1 path value, -2 all-ones
+  short rsrc;     // right operand, same coding
+  short out;      // >= 0: store as full value of node `out`; -1: becomes the path value; -2 - i: emit prefix i
+};
+
+__device__ inline int build_tree_program(TreeStep* prog, int n, int prefix) {
+  int t = 0;
+  for (int m = n - 2; m >= 1; --m) prog[t++] = TreeStep{(short)m, (short)(2 * m + 1), (short)(2 * m + 2), (short)m};
+  if (!prefix) {
+    prog[t++] = TreeStep{0, 1, 2, (short)(-2 - (n - 1))};
+    return t;
+  }
+  for (int i = 0; i < n; ++i) {
+    int idx = n - 1 + i, size = 1;
+    while (idx > 0) {
+      const int m = (idx - 1) >> 1;
+      size <<= 1;
+      const int first = (m - (n / size - 1)) * size, last = first + size - 1;
+      if (m > 0 && last <= i) { idx = m; continue; }          // fully observed: stored value
+      const int half = size >> 1;
+      const int l_last = first + half - 1, r_first = first + half;
+      const short ls = (l_last <= i) ? (short)(2 * m + 1) : (short)-1;
+      const short rs = (r_first > i) ? (short)-2 : (last <= i ? (short)(2 * m + 2) : (short)-1);
+      prog[t++] = TreeStep{(short)m, ls, rs, (short)(m > 0 ? -1 : -2 - i)};
+      idx = m;
+    }
+  }
+  return t;
+}
 #endif
+
+inline int tree_program_steps(int n, int prefix) {
+  if (!prefix) return n - 2 + 1;
+  int lg = 0;
+  while ((1 << lg) < n) ++lg;
+  return n - 2 + n * lg;          // upper bound: at most log2(n) steps per prefix
+}
 
 }  // namespace mtpc

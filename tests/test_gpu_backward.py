@@ -60,6 +60,11 @@ CASES = [
     ("hmm", "bf16", 40, 64, 16, 128, 64, 9),
     ("hmm", "f32", 9, 32, 1, 4, 12, 10),
     ("hmm-shared", "f32", 50, 64, 6, 8, 40, 11),
+    ("btree", "f32", 70, 64, 4, 5, 33, 12),
+    ("btree", "bf16", 130, 128, 8, 16, 320, 13),
+    ("btree", "f32", 21, 32, 2, 6, 20, 14),
+    ("btree", "bf16", 37, 64, 16, 128, 40, 15),
+    ("btree-shared", "f32", 45, 64, 8, 8, 40, 16),
 ]
 
 

@@ -10,6 +10,7 @@ import mtpc_inputs as mi
 from oracle import mtpc_oracle as oc
 from oracle import philox
 
+from oracle import backward as bw
 from oracle import speculative as sp
 
 from gpu_util import BOUNDARY, compare_drafts, make_head, synthetic_verifier, tol_check
@@ -121,3 +122,52 @@ def test_config5_decode_cycle_with_verification():
     assert np.array_equal(tok.cpu().numpy()[safe], want_tok[safe])
     print(f"accepted histogram {np.bincount(want_acc, minlength=n + 1)}; {int((~safe).sum())} of {B} rows near a boundary")
     assert safe.sum() >= B // 2 and len(np.unique(want_acc)) >= 4
+
+
+def test_config2_training_step_full_size():
+    """Loss and gradients of configs[1] (CP r=16, B=8192) in the launch configuration the
+    bench times.  dh and the loss are per-position quantities: sampled rows against the
+    oracle.  dW sums over all positions: (1) exact comparison of every entry in a second
+    run whose coefficients are zero outside a few dozen positions (the oracle differentiates
+    those alone), (2) on the dense run the identities sum_a dW[i,j,a,:] = 0 (softmax rows of
+    the logit gradient sum to zero) and <dh,h> = <dW,W> + <dWsum,Wsum> (both sides are the
+    logit gradient contracted with the logits)."""
+    inp = mi.config2(r=16)
+    B, n = inp.B, inp.n
+    head = make_head(inp)
+    rng = np.random.default_rng(12)
+    valid = rng.random((B, n)) > 0.1
+    coef = bw.loss_coefficients(0.8, valid, sequence=np.arange(B) // 1024).astype(np.float32)
+    tg = torch.from_numpy(inp.targets).cuda()
+    out = head.loss_backward(tg, torch.from_numpy(coef).cuda())
+    rows = sample_rows(B, k=12)
+    want = bw.loss_and_gradients("cp", inp.h[rows], inp.W, inp.Wsum, None, inp.targets[rows], coef[rows])
+    dh = out["dh"].cpu().numpy()[rows].astype(np.float64)
+    fro = np.linalg.norm(dh - want["dh"]) / np.linalg.norm(want["dh"])
+    assert fro <= 3e-3 and np.abs(dh - want["dh"]).max() <= 2e-2 * np.abs(want["dh"]).max(), fro
+    loss = out["loss"].cpu().numpy()[rows]
+    assert np.all(np.abs(loss - want["loss"]) <= 2e-3 * np.maximum(np.abs(want["loss"]), 1e-6))
+    dW, dWs = out["dW"].double(), out["dWsum"].double()
+    scale = float(dW.abs().max())
+    # 320 bf16-rounded terms per sum: random error about 2^-9 * sqrt(320) of a typical entry
+    assert float(dW.sum(dim=2).abs().max()) <= 0.1 * scale
+    Wd = torch.from_numpy(inp.W).cuda().double()
+    lhs = float((out["dh"].double() * torch.from_numpy(inp.h).cuda().double()).sum())
+    rhs = float((dW * Wd).sum()) + float((dWs * torch.from_numpy(inp.Wsum).cuda().double()).sum())
+    assert abs(lhs - rhs) <= 3e-3 * max(abs(lhs), float((dW * Wd).abs().sum()) * 1e-3), (lhs, rhs)
+    print(f"dense run: dh rows rel. Frobenius error {fro:.1e}; <dh,h> = {lhs:.6e}, <dW,W>+<dWsum,Wsum> = {rhs:.6e}")
+    del dW, dWs, Wd
+
+    few = np.unique(np.concatenate([sample_rows(B, k=16, seed=3), [4095, 4096, B - 1]]))
+    sparse = np.zeros_like(coef)
+    sparse[few] = coef[few] * 100.0
+    out2 = head.loss_backward(tg, torch.from_numpy(sparse).cuda(), out=out)
+    want2 = bw.loss_and_gradients("cp", inp.h[few], inp.W, inp.Wsum, None, inp.targets[few], sparse[few])
+    for name in ("dW", "dWsum"):
+        got = out2[name].cpu().numpy().astype(np.float64)
+        err = np.abs(got - want2[name])
+        fro2 = np.linalg.norm(got - want2[name]) / np.linalg.norm(want2[name])
+        assert fro2 <= 3e-3 and err.max() <= 2e-2 * np.abs(want2[name]).max(), (name, fro2)
+        print(f"sparse run ({len(few)} positions): {name} rel. Frobenius error {fro2:.1e}")
+    others = np.setdiff1d(np.arange(B), few)
+    assert float(out2["dh"][torch.from_numpy(others).cuda()].abs().max()) == 0.0
