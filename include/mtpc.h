@@ -52,6 +52,7 @@ typedef enum { MTPC_OP_LOGLIK = 0, MTPC_OP_MARGINALS = 1, MTPC_OP_SAMPLE = 2, MT
                MTPC_OP_BACKWARD = 4 } mtpc_op;
 typedef enum { MTPC_MARG_PREFIX = 0, MTPC_MARG_UNIVARIATE = 1 } mtpc_marg_mode;
 typedef enum { MTPC_VERIFY_SAMPLING = 0, MTPC_VERIFY_GREEDY = 1 } mtpc_verify_mode;
+typedef enum { MTPC_BWD_KEEP_PROBS = 0, MTPC_BWD_RECOMPUTE = 1 } mtpc_bwd_mode;
 
 /* Common description of one call (Sec. 3.3). */
 typedef struct {
@@ -93,7 +94,8 @@ const char* mtpc_status_string(mtpc_status s);
 
 /* Scratch needed by one call.  `layers` may be NULL (FF, CP).  `S` is the number
  * of drafts per position (sample) and is ignored otherwise; `mode` is the
- * mtpc_marg_mode for MTPC_OP_MARGINALS.  Returns 0 for invalid arguments. */
+ * mtpc_marg_mode for MTPC_OP_MARGINALS and the mtpc_bwd_mode for MTPC_OP_BACKWARD.
+ * Returns 0 for invalid arguments. */
 size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
                             const mtpc_sumlayers* layers, int32_t S, int32_t mode);
 
@@ -189,10 +191,15 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
  * of Eq. cross-ent-loss into coef [B][n] (fp32, device).  Outputs (device, fp32,
  * fully overwritten): loss [B]; gradients of sum_b loss[b]: dh [B][d] (row stride
  * d), dW [n][r][v][d], dWsum [r][d], dlayers = gradient w.r.t. the layer logits.
- * The logits are recomputed, never stored; the logit gradient is kept in the
- * dtype of h for the two contractions (bf16 inputs: rounded to nearest even).
+ * The logit gradient is kept in the dtype of h for the two contractions (bf16
+ * inputs: rounded to nearest even).  Two plans, chosen by the workspace the call
+ * is given: with mtpc_workspace_bytes(.., MTPC_OP_BACKWARD, .., mode =
+ * MTPC_BWD_KEEP_PROBS) bytes the forward pass keeps its softmax probabilities
+ * (n*r*v*B fp32) and the logit gradient is one elementwise pass; with the
+ * smaller MTPC_BWD_RECOMPUTE size nothing of size n*r*v*B is kept in fp32 and the
+ * logits are recomputed (one more pass of the unembedding product).
  * targets: ids in [0, v), or -1 (that variable is summed out and receives no
- * gradient).  Workspace: mtpc_workspace_bytes(family, MTPC_OP_BACKWARD, ...).
+ * gradient).
  * dlayers has the shape of the stored layer logits ([n-1][r][r], or [1][r][r] for a
  * shared matrix, whose gradient is the sum over the steps).
  * Not yet available (MTPC_ERR_UNSUPPORTED): layers given per position or computed

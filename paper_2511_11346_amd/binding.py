@@ -217,7 +217,8 @@ class Head:
                           self._phi_ptr(logphi)))
         return drafts, lat, pl
 
-    def loss_backward(self, targets: torch.Tensor, coef: torch.Tensor, out: Optional[dict] = None) -> dict:
+    def loss_backward(self, targets: torch.Tensor, coef: torch.Tensor, out: Optional[dict] = None,
+                      recompute: bool = False) -> dict:
         """Loss of Sec. 4.1 and its gradients: targets [B,n] int32, coef [B,n] fp32.
         Returns {"loss" [B], "dh" [B,d], "dW" [n,r,v,d], "dWsum" [r,d] or None, "dlayers" or None}, all fp32."""
         dev = self.h.device
@@ -230,7 +231,11 @@ class Head:
                    "dW": torch.empty(self.n, self.r, self.v, self.d, **f32),
                    "dWsum": None if self.family == "ff" else torch.empty(self.r, self.d, **f32),
                    "dlayers": None if self.layers is None else torch.empty_like(self.layers)}
-        hd = self._head(self.workspace_bytes(OP_BACKWARD))
+        # the library picks its plan from the workspace size it is handed
+        need = self.workspace_bytes(OP_BACKWARD, mode=1 if recompute else 0)
+        hd = self._head(need)
+        if recompute:
+            hd.workspace_bytes = need
         args = [targets.data_ptr(), coef.data_ptr(), out["loss"].data_ptr(), out["dh"].data_ptr(),
                 out["dW"].data_ptr()]
         if self.family != "ff":

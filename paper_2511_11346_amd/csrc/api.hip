@@ -320,13 +320,15 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
 // Workspace of the training step (byte offsets) and its padded strides.
 struct BwdPlan {
   Plan fwd;                 // logw, layers, evidence: as for the prefix marginals
-  size_t Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, total;
+  size_t Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, phi, total;
+  bool keep_phi;            // probabilities kept by the forward pass (else the logits are recomputed)
   int steps;                // reverse-pass steps with a layer (HMM: n-1; tree: program length)
   long long M, Mx, ldM, ldb;
 };
 
-BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly) {
+BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, bool keep_phi) {
   BwdPlan q{};
+  q.keep_phi = keep_phi;
   q.fwd = make_plan(family, MTPC_OP_MARGINALS, hd, ly, 1, MTPC_MARG_PREFIX, false);
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
   q.M = (long long)hd->n * hd->r * hd->v;
@@ -353,6 +355,7 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly)
     q.ct = take((size_t)hd->B * q.steps * hd->r * 4);
     q.adj = take((size_t)hd->B * (hd->n - 1) * hd->r * 4);
   }
+  if (keep_phi) q.phi = take((size_t)q.M * q.ldb * 4);
   q.total = off;
   return q;
 }
@@ -373,9 +376,13 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     if (ly->R != nullptr || ly->batch_stride != 0) return MTPC_ERR_UNSUPPORTED;
     if (!dlayers) return MTPC_ERR_NULL;
   }
-  const BwdPlan q = make_bwd_plan(family, hd, ly);
+  // with the larger workspace the forward pass keeps its probabilities (n*r*v*B fp32) and the
+  // logit gradient is an elementwise pass; with the smaller one the logits are recomputed
+  BwdPlan q = make_bwd_plan(family, hd, ly, true);
   if (!hd->workspace) return MTPC_ERR_NULL;
-  if (((uintptr_t)hd->workspace & 15) || hd->workspace_bytes < q.total) return MTPC_ERR_WORKSPACE;
+  if ((uintptr_t)hd->workspace & 15) return MTPC_ERR_WORKSPACE;
+  if (hd->workspace_bytes < q.total) q = make_bwd_plan(family, hd, ly, false);
+  if (hd->workspace_bytes < q.total) return MTPC_ERR_WORKSPACE;
   if (q.ldM * 4 > 0x7fffffffLL / 256 || q.ldb * 4 > 0x7fffffffLL / 256) return MTPC_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)hd->stream;
   char* ws = (char*)hd->workspace;
@@ -387,6 +394,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
   u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
   u.targets = targets; u.T = 1; u.e = (float*)(ws + p.e);
+  if (q.keep_phi) { u.phiT = (float*)(ws + q.phi); u.ld_phi = q.ldb; }
   HIP_TRY(launch_unembed(u, hd->dtype, st));
 
   CircuitBwdArgs c{};
@@ -410,19 +418,29 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   }
   HIP_TRY(launch_circuit_bwd(c, st));
 
-  GradLogitsArgs g{};
-  g.h = hd->h; g.ld_h = hd->ld_h; g.W = hd->W;
-  g.B = hd->B; g.d = hd->d; g.v = hd->v; g.n = hd->n; g.r = hd->r;
-  g.targets = targets; g.Ge = c.Ge; g.dLT = ws + q.dLT; g.ldb = q.ldb;
-  {
-    ProfScope prof(st);
-    HIP_TRY(launch_unembed_grad(g, hd->dtype, st));
-  }
-  // layouts for the two contractions: dL = dLT^T [B][ldM], WT = [W; Wsum]^T [d][ldM], hT = h^T [d][ldb]
+  // logit gradient in both layouts: dLT [Mx][ldb] and dL = dLT^T [B][ldM]
   TransposeArgs t{};
-  t.src = ws + q.dLT; t.ld_src = q.ldb; t.R = (int)q.Mx; t.C = hd->B;
-  t.dst = ws + q.dL; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)q.ldM;
-  HIP_TRY(launch_transpose(t, hd->dtype, st));
+  if (q.keep_phi) {
+    GradPhiArgs g{};
+    g.phiT = (const float*)(ws + q.phi); g.ld_phi = q.ldb; g.targets = targets; g.Ge = c.Ge;
+    g.B = hd->B; g.n = hd->n; g.r = hd->r; g.v = hd->v;
+    g.M = q.M; g.Mx = q.Mx; g.ldM = q.ldM; g.ldb = q.ldb;
+    g.dLT = ws + q.dLT; g.dL = ws + q.dL;
+    HIP_TRY(launch_grad_from_phi(g, hd->dtype, st));
+  } else {
+    GradLogitsArgs g{};
+    g.h = hd->h; g.ld_h = hd->ld_h; g.W = hd->W;
+    g.B = hd->B; g.d = hd->d; g.v = hd->v; g.n = hd->n; g.r = hd->r;
+    g.targets = targets; g.Ge = c.Ge; g.dLT = ws + q.dLT; g.ldb = q.ldb;
+    {
+      ProfScope prof(st);
+      HIP_TRY(launch_unembed_grad(g, hd->dtype, st));
+    }
+    t.src = ws + q.dLT; t.ld_src = q.ldb; t.R = (int)q.Mx; t.C = hd->B;
+    t.dst = ws + q.dL; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)q.ldM;
+    HIP_TRY(launch_transpose(t, hd->dtype, st));
+  }
+  // WT = [W; Wsum]^T [d][ldM], hT = h^T [d][ldb]
   t.src = hd->W; t.ld_src = hd->d; t.R = (int)q.M; t.C = hd->d;
   t.dst = ws + q.WT; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)(family == MTPC_FF ? q.ldM : q.M);
   HIP_TRY(launch_transpose(t, hd->dtype, st));
@@ -470,7 +488,7 @@ size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
                             const mtpc_sumlayers* layers, int32_t S, int32_t mode) {
   if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_BACKWARD) return 0;
   if (!head || head->B < 1 || head->d < 1 || head->n < 1 || head->r < 1 || head->v < 1) return 0;
-  if (op == MTPC_OP_BACKWARD) return make_bwd_plan(family, head, layers).total;
+  if (op == MTPC_OP_BACKWARD) return make_bwd_plan(family, head, layers, mode != MTPC_BWD_RECOMPUTE).total;
   if (op == MTPC_OP_SAMPLE && S < 1) return 0;
   // sized for the most demanding variant of the op (sample: with prefix scores)
   Plan p = make_plan(family, op, head, layers, op == MTPC_OP_SAMPLE ? S : 1, mode, true);

@@ -47,6 +47,72 @@ __global__ __launch_bounds__(256) void k_transpose(const TransposeArgs a) {
   }
 }
 
+// 64 (m) x 128 (b) tiles: logit gradient from the stored probabilities, written in both
+// layouts (dLT along b straight away, dL along m after a transpose through LDS).  A thread
+// moves four neighbouring elements at a time (16-byte loads, 8- or 16-byte stores).
+template <typename T>
+__global__ __launch_bounds__(256) void k_grad_from_phi(const GradPhiArgs a) {
+  struct alignas(4 * sizeof(T)) Quad { T v[4]; };
+  __shared__ T tile[64][128 + 4];
+  const long long m0 = (long long)blockIdx.y * 64;
+  const int b0 = blockIdx.x * 128;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 column quads x 8 rows per pass
+  const int b = b0 + 4 * tx;                                    // first of the thread's four positions
+  T* dLT = (T*)a.dLT;
+  T* dL = (T*)a.dL;
+  auto conv = [](float x) -> T {
+    if constexpr (sizeof(T) == 2) return to_bf16_rne(x); else return x;
+  };
+  const bool col_ok = b < a.ldb;                                // ldb is a multiple of 4: all four or none
+  int cur_slab = -1, x[4] = {-1, -1, -1, -1};
+  float g[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+  for (int k = 0; k < 8; ++k) {
+    const int ml = ty + 8 * k;
+    const long long m = m0 + ml;
+    Quad out;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) out.v[c] = conv(0.f);
+    if (m < a.M && col_ok) {
+      const int slab = (int)(m / a.v), av = (int)(m - (long long)slab * a.v);
+      if (slab != cur_slab) {                      // rows of a tile mostly share their slab
+        cur_slab = slab;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          x[c] = -1; g[c] = 0.f;
+          if (b + c < a.B) {
+            x[c] = a.targets[(long long)(b + c) * a.n + slab / a.r];
+            g[c] = a.Ge[(long long)(b + c) * a.n * a.r + slab];
+          }
+        }
+      }
+      const float4 ph = *(const float4*)(a.phiT + m * a.ld_phi + b);
+      const float pv[4] = {ph.x, ph.y, ph.z, ph.w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (b + c < a.B && x[c] != -1) out.v[c] = conv(g[c] * ((av == x[c] ? 1.f : 0.f) - pv[c]));
+      *(Quad*)(dLT + m * a.ldb + b) = out;
+    } else if (m < a.Mx && col_ok) {
+      out = *(const Quad*)(dLT + m * a.ldb + b);   // sum-unit rows, written by the reverse pass
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) tile[ml][4 * tx + c] = out.v[c];
+  }
+  __syncthreads();
+  const int mq = threadIdx.x & 15, br = threadIdx.x >> 4;        // 16 row quads x 16 positions per pass
+#pragma unroll 2
+  for (int k = 0; k < 8; ++k) {
+    const int bl = br + 16 * k;
+    const long long m = m0 + 4 * mq;
+    if (b0 + bl < a.B && m < a.ldM) {                           // ldM is a multiple of 4
+      Quad out;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) out.v[c] = tile[4 * mq + c][bl];
+      *(Quad*)(dL + (long long)(b0 + bl) * a.ldM + m) = out;
+    }
+  }
+}
+
 // acc_u = sum_k sh[k] * M[k*r + unit_u] for the lane's units (lane, lane + 64); M is an
 // r x r matrix in global memory read along its contiguous axis, eight rows in flight.
 __device__ __forceinline__ void wave_matvec(const float* __restrict__ M, const float* sh, int r, int lane,
@@ -435,6 +501,13 @@ hipError_t launch_transpose(const TransposeArgs& a, int dtype, hipStream_t st) {
   const dim3 grid((a.C + 63) / 64, (a.Rpad + 63) / 64);
   if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_transpose<unsigned short>, grid, dim3(256), 0, st, a);
   else hipLaunchKernelGGL(k_transpose<float>, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_grad_from_phi(const GradPhiArgs& a, int dtype, hipStream_t st) {
+  const dim3 grid((unsigned)((a.ldb + 127) / 128), (unsigned)((a.ldM + 63) / 64));
+  if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_grad_from_phi<unsigned short>, grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(k_grad_from_phi<float>, grid, dim3(256), 0, st, a);
   return hipGetLastError();
 }
 

@@ -29,6 +29,8 @@ struct UnembedArgs {
   int* drafts;          // [B][S][n]
   uint32_t seed_lo, seed_hi, offset;
   float* logphi;        // [B][n][r][v] normalised logits of every slab, or nullptr (sampling kernel only)
+  float* phiT;          // [n*r*v][ld_phi] softmax probabilities, transposed, or nullptr (evidence kernel only)
+  long long ld_phi;
 };
 
 // Univariate marginals: M[b][i][a] = log sum_j m[b][i][j] phi[b][i][j][a].
@@ -147,6 +149,18 @@ struct GradLogitsArgs {
   long long ldb;        // >= B, a multiple of 32
 };
 hipError_t launch_unembed_grad(const GradLogitsArgs& a, int dtype, hipStream_t st);
+
+// Logit gradient from stored probabilities: for m = (i*r+j)*v + a < M
+//   val = Ge[b][i][j] * (1[a == x_bi] - phiT[m][b]);   rows M <= m < Mx of dLT are passed through.
+// Writes dLT[m][b] (m < M, b < ldb, zero for b >= B) and dL[b][m] (b < B, m < ldM, zero for m >= Mx).
+struct GradPhiArgs {
+  const float* phiT; long long ld_phi;
+  const int* targets; const float* Ge;
+  int B, n, r, v;
+  long long M, Mx, ldM, ldb;
+  void* dLT; void* dL;
+};
+hipError_t launch_grad_from_phi(const GradPhiArgs& a, int dtype, hipStream_t st);
 
 // C[M][N] (fp32, row stride ldc; optionally split by rows over two buffers) = A[M][K] * B[N][K]^T, both operands K-contiguous
 // with row strides lda / ldb (elements); K a multiple of 32 (bf16) or 16 (fp32).

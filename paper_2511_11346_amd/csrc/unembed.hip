@@ -66,6 +66,22 @@ void k_unembed(const UnembedArgs a) {
       }
     }
   }
+  if constexpr (!SAMPLE) if (a.phiT != nullptr) {
+    // keep the normalised probabilities for the training step (transposed: positions contiguous)
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb) {
+      const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+      if (b < a.B) {
+#pragma unroll
+        for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+            if (row < a.v) a.phiT[((long long)slab * a.v + row) * a.ld_phi + b] = __expf(acc[pb][vb][i] - lse[pb]);
+          }
+      }
+    }
+  }
   if (a.lse != nullptr && wv == 0 && lhalf == 0) {
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {

@@ -89,3 +89,9 @@ def test_loss_and_gradients_match_oracle(family, dtype, B, d, n, r, v, seed):
     # a second call with the same buffers gives the same bits (nothing accumulates across calls)
     again = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda())
     assert torch.equal(again["dW"], out["dW"]) and torch.equal(again["dh"], out["dh"])
+    # the lean plan (logits recomputed instead of probabilities kept) meets the same bar
+    lean = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda(),
+                              recompute=True)
+    for name in ("dh", "dW", "dWsum"):
+        if want[name] is not None:
+            check_grad(name + " (recompute)", lean[name], want[name], dtype)
