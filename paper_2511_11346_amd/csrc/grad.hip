@@ -140,10 +140,10 @@ void k_gemm_tn(const GemmArgs a) {
   }
 }
 
-template <bool BF16>
-static hipError_t launch_gemm_dt(const GemmArgs& a, hipStream_t st) {
-  using TL = Tile<2, 4, 4, 2, 64, 4>;          // 256 x 256 workgroup tile
-  auto kern = k_gemm_tn<2, 4, 4, 2, 64, 4, BF16>;
+template <int WV, int WB, int VB, int PB, bool BF16>
+static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t st) {
+  using TL = Tile<WV, WB, VB, PB, 64, 4>;
+  auto kern = k_gemm_tn<WV, WB, VB, PB, 64, 4, BF16>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
@@ -153,6 +153,20 @@ static hipError_t launch_gemm_dt(const GemmArgs& a, hipStream_t st) {
   const int nslab = (a.M + TL::TV - 1) / TL::TV, nbt = (a.N + TL::TP - 1) / TL::TP;
   hipLaunchKernelGGL(kern, dim3(nslab * nbt), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();
+}
+
+template <bool BF16>
+static hipError_t launch_gemm_dt(const GemmArgs& a, hipStream_t st) {
+  // 320 x 256 workgroup tiles (the forward kernel's shape; measured 7 % faster per output
+  // row) or 256 x 256 ones, whichever needs less time by a count of rounds over the 256
+  // CUs: whole rounds while there are few workgroups, fractional once there are many
+  auto cost = [&](int rows, double gain) {
+    const double wgs = (double)((a.M + rows - 1) / rows) * ((a.N + 255) / 256);
+    const double rounds = wgs >= 1024 ? wgs / 256.0 : (double)(long long)((wgs + 255) / 256);
+    return rounds * rows * gain;
+  };
+  if (cost(320, 0.93) < cost(256, 1.0)) return launch_gemm_cfg<2, 4, 5, 2, BF16>(a, st);
+  return launch_gemm_cfg<2, 4, 4, 2, BF16>(a, st);
 }
 
 hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t st) {
