@@ -54,24 +54,32 @@ def _joint(family, e, logw, loglayers):
     if family == "hmm":
         alpha = logw + e[:, 0]
         for i in range(1, n):
-            T = loglayers[i - 1 if loglayers.shape[0] > 1 else 0]          # [prev, next]
-            alpha = e[:, i] + torch.logsumexp(alpha[:, :, None] + T[None], dim=1)
+            if loglayers.dim() == 4:                                       # one set per position [B,L,prev,next]
+                T = loglayers[:, i - 1 if loglayers.shape[1] > 1 else 0]
+            else:
+                T = loglayers[i - 1 if loglayers.shape[0] > 1 else 0][None]    # [prev, next]
+            alpha = e[:, i] + torch.logsumexp(alpha[:, :, None] + T, dim=1)
         return torch.logsumexp(alpha, dim=-1)
     if family == "btree":
         C = [None] * (2 * n - 1)
         for i in range(n):
             C[n - 1 + i] = e[:, i]
         for m in range(n - 2, 0, -1):
-            A = loglayers[m - 1 if loglayers.shape[0] > 1 else 0]          # [parent's latent k, own latent j]
+            if loglayers.dim() == 4:
+                A = loglayers[:, m - 1 if loglayers.shape[1] > 1 else 0]
+            else:
+                A = loglayers[m - 1 if loglayers.shape[0] > 1 else 0][None]    # [parent's latent k, own latent j]
             prod = C[2 * m + 1] + C[2 * m + 2]
-            C[m] = torch.logsumexp(A[None] + prod[:, None, :], dim=-1)
+            C[m] = torch.logsumexp(A + prod[:, None, :], dim=-1)
         return torch.logsumexp(logw + C[1] + C[2], dim=-1)
     raise ValueError(family)
 
 
-def prefix_marginals_torch(family, h, W, Wsum, layers, targets):
+def prefix_marginals_torch(family, h, W, Wsum, layers, targets, R=None):
     """P[b,i] = log q(x_1..x_{i+1}) as a differentiable float64 tensor (Sec. 3.3
-    parameterisation, App. B.1 marginalisation: later input units become 1)."""
+    parameterisation, App. B.1 marginalisation: later input units become 1).
+    With R [L,r,r,d] the layer logits of position b are R h[b] + layers (Sec. 3.3: the
+    sum-unit parameters are computed from the hidden state; ``layers`` is then a bias)."""
     B, n = targets.shape
     logits = torch.einsum("nrvd,bd->bnrv", W, h)
     logphi = torch.log_softmax(logits, dim=-1)
@@ -80,7 +88,13 @@ def prefix_marginals_torch(family, h, W, Wsum, layers, targets):
     e = torch.gather(logphi, 3, idx)[..., 0]                               # [B,n,r]
     e = e * (tt != -1)[:, :, None]          # a target of -1 is summed out: its input units are 1 (App. B.1)
     logw = None if Wsum is None else torch.log_softmax(h @ Wsum.T, dim=-1)
-    loglayers = None if layers is None else torch.log_softmax(layers, dim=-1)
+    if R is not None:
+        lay = torch.einsum("lzyd,bd->blzy", R, h)
+        if layers is not None:
+            lay = lay + layers[None]
+        loglayers = torch.log_softmax(lay, dim=-1)
+    else:
+        loglayers = None if layers is None else torch.log_softmax(layers, dim=-1)
     cols = []
     for i in range(n):
         mask = torch.zeros(n, dtype=torch.float64)
@@ -89,15 +103,16 @@ def prefix_marginals_torch(family, h, W, Wsum, layers, targets):
     return torch.stack(cols, dim=1)
 
 
-def loss_and_gradients(family, h, W, Wsum, layers, targets, coef):
+def loss_and_gradients(family, h, W, Wsum, layers, targets, coef, R=None):
     """Per-position loss  loss[b] = sum_j coef[b,j] * (P[b,j-1] - P[b,j])  (P[b,-1] = 0)
-    and the gradients of sum_b loss[b] with respect to h, W, Wsum and the layer logits."""
+    and the gradients of sum_b loss[b] with respect to h, W, Wsum, the layer logits
+    (or, with R, the bias) and R."""
     t = lambda a: None if a is None else torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
-    h_t, W_t, Ws_t, L_t = t(h), t(W), t(Wsum), t(layers)
-    P = prefix_marginals_torch(family, h_t, W_t, Ws_t, L_t, np.asarray(targets))
+    h_t, W_t, Ws_t, L_t, R_t = t(h), t(W), t(Wsum), t(layers), t(R)
+    P = prefix_marginals_torch(family, h_t, W_t, Ws_t, L_t, np.asarray(targets), R_t)
     prev = torch.cat([torch.zeros(P.shape[0], 1, dtype=torch.float64), P[:, :-1]], dim=1)
     loss_b = (torch.as_tensor(np.asarray(coef, dtype=np.float64)) * (prev - P)).sum(dim=1)
     loss_b.sum().backward()
     g = lambda a: None if a is None else a.grad.numpy()
     return {"loss": loss_b.detach().numpy(), "P": P.detach().numpy(), "dh": g(h_t), "dW": g(W_t),
-            "dWsum": g(Ws_t), "dlayers": g(L_t)}
+            "dWsum": g(Ws_t), "dlayers": g(L_t), "dR": g(R_t)}

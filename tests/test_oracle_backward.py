@@ -82,6 +82,32 @@ def test_summed_out_targets_follow_the_numpy_oracle(family):
     assert np.abs(one["dW"][1]).max() == 0.0
 
 
+def test_layers_computed_from_the_hidden_state_match_finite_differences():
+    """Contextual HMM (Sec. 3.3, App. HMM setup): transition logits R h + bias."""
+    h, W, Wsum, bias, targets, coef = setup("hmm", seed=6)
+    n, r, d = W.shape[0], W.shape[1], h.shape[1]
+    R = np.random.default_rng(8).standard_normal((n - 1, r, r, d)) * 0.7
+    res = bw.loss_and_gradients("hmm", h, W, Wsum, bias, targets, coef, R=R)
+
+    def f():
+        lay = oc.contextual_layer_logits(h, R, bias)
+        return numpy_loss("hmm", h, W, Wsum, lay, targets, coef)
+    np.testing.assert_allclose(res["P"], oc.prefix_marginals("hmm", h, W, Wsum, oc.contextual_layer_logits(h, R, bias),
+                                                             targets), atol=1e-11)
+    eps, rng = 1e-6, np.random.default_rng(3)
+    for name, arr in (("dR", R), ("dlayers", bias), ("dh", h)):
+        for _ in range(12):
+            idx = tuple(rng.integers(0, s) for s in arr.shape)
+            old = arr[idx]
+            arr[idx] = old + eps
+            up = f()
+            arr[idx] = old - eps
+            dn = f()
+            arr[idx] = old
+            fd = (up - dn) / (2 * eps)
+            assert abs(fd - res[name][idx]) <= 1e-6 * max(1.0, abs(fd)), (name, idx)
+
+
 def test_fully_factorised_gradient_is_softmax_minus_one_hot():
     """-log softmax(l)[x] has gradient softmax(l) - onehot(x) in l = W h (textbook)."""
     h, W, _, _, targets, coef = setup("ff", n=3, r=1, v=5, d=4, B=6, seed=9)
