@@ -202,18 +202,22 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
  * gradient).
  * dlayers has the shape of the stored layer logits ([n-1][r][r], or [1][r][r] for a
  * shared matrix, whose gradient is the sum over the steps).
- * Not yet available (MTPC_ERR_UNSUPPORTED): layers given per position or computed
- * from h (mtpc_sumlayers.R, batch_stride). */
+ * Layers computed from h (mtpc_sumlayers.R non-NULL; HMM with one R and, if given, one
+ * bias per step): dR [n-1][r][r][d] receives the gradient w.r.t. R, dlayers the one
+ * w.r.t. the bias (may be NULL when there is no bias), and dh includes the path
+ * through the layers; otherwise dR is ignored and may be NULL.
+ * Not available (MTPC_ERR_UNSUPPORTED): layers given per position (batch_stride),
+ * R for the binary tree, R or its bias shared by several steps. */
 mtpc_status mtpc_ff_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
                                   float* loss, float* dh, float* dW);
 mtpc_status mtpc_cp_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
                                   float* loss, float* dh, float* dW, float* dWsum);
 mtpc_status mtpc_hmm_loss_backward(const mtpc_head* head, const mtpc_sumlayers* T, const int32_t* targets,
                                    const float* coef, float* loss, float* dh, float* dW, float* dWsum,
-                                   float* dlayers);
+                                   float* dlayers, float* dR);
 mtpc_status mtpc_btree_loss_backward(const mtpc_head* head, const mtpc_sumlayers* A,
                                      const int32_t* targets, const float* coef, float* loss, float* dh,
-                                     float* dW, float* dWsum, float* dlayers);
+                                     float* dW, float* dWsum, float* dlayers, float* dR);
 
 /* The uniforms the sampler consumes, out [B][S][slots] fp32 (device), for tests
  * of the generator and its slot map. */

@@ -76,8 +76,8 @@ def lib() -> C.CDLL:
             getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, lp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
         L.mtpc_ff_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp]
         L.mtpc_cp_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp, fp]
-        L.mtpc_hmm_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp]
-        L.mtpc_btree_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp]
+        L.mtpc_hmm_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp, fp]
+        L.mtpc_btree_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp, fp]
         L.mtpc_philox_uniforms.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
                                            fp, C.c_void_p]
         L.mtpc_profile_unembed.argtypes = [C.c_void_p, C.c_void_p]
@@ -220,7 +220,8 @@ class Head:
     def loss_backward(self, targets: torch.Tensor, coef: torch.Tensor, out: Optional[dict] = None,
                       recompute: bool = False) -> dict:
         """Loss of Sec. 4.1 and its gradients: targets [B,n] int32, coef [B,n] fp32.
-        Returns {"loss" [B], "dh" [B,d], "dW" [n,r,v,d], "dWsum" [r,d] or None, "dlayers" or None}, all fp32."""
+        Returns {"loss" [B], "dh" [B,d], "dW" [n,r,v,d], "dWsum" [r,d] or None, "dlayers" or None,
+        "dR" (layers computed from h) or None}, all fp32."""
         dev = self.h.device
         assert targets.is_cuda and targets.dtype == torch.int32 and targets.is_contiguous()
         assert coef.is_cuda and coef.dtype == torch.float32 and coef.is_contiguous()
@@ -230,7 +231,8 @@ class Head:
             out = {"loss": torch.empty(self.B, **f32), "dh": torch.empty(self.B, self.d, **f32),
                    "dW": torch.empty(self.n, self.r, self.v, self.d, **f32),
                    "dWsum": None if self.family == "ff" else torch.empty(self.r, self.d, **f32),
-                   "dlayers": None if self.layers is None else torch.empty_like(self.layers)}
+                   "dlayers": None if self.layers is None else torch.empty_like(self.layers),
+                   "dR": None if self.R is None else torch.empty(self.R.shape, **f32)}
         # the library picks its plan from the workspace size it is handed
         need = self.workspace_bytes(OP_BACKWARD, mode=1 if recompute else 0)
         hd = self._head(need)
@@ -242,6 +244,7 @@ class Head:
             args.append(out["dWsum"].data_ptr())
         if self.family in ("hmm", "btree"):
             args.append(out["dlayers"].data_ptr() if out["dlayers"] is not None else None)
+            args.append(out["dR"].data_ptr() if out.get("dR") is not None else None)
         _check(self._call("loss_backward", hd, *args))
         return out
 

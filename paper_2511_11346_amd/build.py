@@ -24,7 +24,7 @@ def build(verbose: bool = False) -> str:
     def run(cmd):
         res = subprocess.run(cmd, capture_output=True, text=True)
         # the host pass does not know the device-only target feature and says so: harmless
-        err = "\n".join(l for l in res.stderr.splitlines() if "is not a recognized feature" not in l)
+        err = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if "is not a recognized feature" not in l)
         if res.returncode != 0:
             raise RuntimeError("hipcc failed:\n" + err)
         if verbose and err.strip():

@@ -318,52 +318,66 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
 }
 
 // Workspace of the training step (byte offsets) and its padded strides.
+// Rows m of the logit gradient (columns of its transpose): [0, M) unembedding logits,
+// [M, M + r) sum-unit logits, then - only when the layers are computed from h - a gap up
+// to Mlay (a multiple of 64) and L*r*r layer logits; ldM pads the total to a multiple of 32.
 struct BwdPlan {
-  Plan fwd;                 // logw, layers, evidence: as for the prefix marginals
-  size_t Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, phi, total;
+  size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, phi, total;
   bool keep_phi;            // probabilities kept by the forward pass (else the logits are recomputed)
+  bool ctx;                 // layers computed from h, one set per position
+  int Lst;                  // stored layers (1: one matrix shared by all steps)
   int steps;                // reverse-pass steps with a layer (HMM: n-1; tree: program length)
-  long long M, Mx, ldM, ldb;
+  long long M, Mx, Mlay, Mtot, ldM, ldb;
 };
 
 BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, bool keep_phi) {
   BwdPlan q{};
   q.keep_phi = keep_phi;
-  q.fwd = make_plan(family, MTPC_OP_MARGINALS, hd, ly, 1, MTPC_MARG_PREFIX, false);
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
+  const size_t B = hd->B, n = hd->n, r = hd->r;
+  const int L = n_layers(family, hd->n);
+  q.ctx = L > 0 && ly && ly->R != nullptr;
+  q.Lst = (L > 0 && ly && !q.ctx && ly->layer_stride == 0) ? 1 : L;
   q.M = (long long)hd->n * hd->r * hd->v;
   q.Mx = q.M + (family == MTPC_FF ? 0 : hd->r);      // the sum-unit rows ride along in both contractions
-  q.ldM = (q.Mx + 31) / 32 * 32;
+  q.Mlay = q.ctx ? (q.Mx + 63) / 64 * 64 : q.Mx;
+  q.Mtot = q.ctx ? q.Mlay + (long long)L * hd->r * hd->r : q.Mx;
+  q.ldM = (q.Mtot + 31) / 32 * 32;
   q.ldb = ((long long)hd->B + 31) / 32 * 32;
-  size_t off = q.fwd.total;
+  size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
-  q.Ge = take((size_t)hd->B * hd->n * hd->r * 4);
-  q.dLT = take((size_t)q.Mx * q.ldb * esz);
-  q.dL = take((size_t)hd->B * q.ldM * esz);
+  q.logw = take(B * r * 4);
+  q.e = take(B * n * r * 4);
+  q.Ge = take(B * n * r * 4);
+  q.dLT = take((size_t)(q.ctx ? q.ldM : q.Mx) * q.ldb * esz);
+  q.dL = take(B * q.ldM * esz);
   q.WT = take((size_t)hd->d * q.ldM * esz);
   q.hT = take((size_t)hd->d * q.ldb * esz);
-  const int L = n_layers(family, hd->n);
   q.steps = family == MTPC_BTREE ? tree_program_steps(hd->n, 1) : L;
   if (L > 0) {
-    q.lay_nat = take((size_t)q.fwd.Lst * hd->r * hd->r * 4);
-    q.lay_tr = take((size_t)q.fwd.Lst * hd->r * hd->r * 4);
-    q.pi = take((size_t)hd->B * q.steps * hd->r * 4);
-    q.gam = take((size_t)hd->B * q.steps * hd->r * 4);
-    q.G = take((size_t)q.fwd.Lst * hd->r * hd->r * 4);
+    const size_t lay = (q.ctx ? B : 1) * (size_t)q.Lst * r * r * 4;
+    q.lay_nat = take(lay);
+    q.lay_tr = take(lay);
+    if (!q.ctx) {
+      q.pi = take(B * q.steps * r * 4);
+      q.gam = take(B * q.steps * r * 4);
+      q.G = take((size_t)q.Lst * r * r * 4);
+    }
   }
   if (family == MTPC_BTREE) {
-    q.ct = take((size_t)hd->B * q.steps * hd->r * 4);
-    q.adj = take((size_t)hd->B * (hd->n - 1) * hd->r * 4);
+    q.ct = take(B * q.steps * r * 4);
+    q.adj = take(B * (n - 1) * r * 4);
   }
   if (keep_phi) q.phi = take((size_t)q.M * q.ldb * 4);
   q.total = off;
   return q;
 }
 
-// loss and gradients: forward (evidence) -> circuit reverse pass -> logit gradient by
-// recomputation -> the two contractions
+// loss and gradients: forward (evidence, probabilities) -> circuit reverse pass -> logit
+// gradient in both layouts -> the two contractions
 mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const int32_t* targets,
-                         const float* coef, float* loss, float* dh, float* dW, float* dWsum, float* dlayers) {
+                         const float* coef, float* loss, float* dh, float* dW, float* dWsum, float* dlayers,
+                         float* dR) {
   if (!targets || !coef || !loss || !dh || !dW) return MTPC_ERR_NULL;
   if (family != MTPC_FF && !dWsum) return MTPC_ERR_NULL;
   mtpc_status s = check_head(family, hd);
@@ -371,10 +385,19 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   s = check_layers(family, hd, ly);
   if (s != MTPC_OK) return s;
   const int L = n_layers(family, hd->n);
+  const bool ctx = L > 0 && ly->R != nullptr;
   if (L > 0) {
-    // layers shared by all positions only; the contextual parametrisation has no reverse pass yet
-    if (ly->R != nullptr || ly->batch_stride != 0) return MTPC_ERR_UNSUPPORTED;
-    if (!dlayers) return MTPC_ERR_NULL;
+    if (ly->batch_stride != 0) return MTPC_ERR_UNSUPPORTED;       // layers given per position: no reverse pass
+    if (ctx) {
+      // layers computed from h: HMM with one R (and bias) per step
+      if (family != MTPC_HMM) return MTPC_ERR_UNSUPPORTED;
+      if (L > 1 && (ly->R_layer_stride != (long long)hd->r * hd->r * hd->d ||
+                    (ly->logits && ly->layer_stride != (long long)hd->r * hd->r)))
+        return MTPC_ERR_UNSUPPORTED;
+      if (!dR || (ly->logits && !dlayers)) return MTPC_ERR_NULL;
+    } else if (!dlayers) {
+      return MTPC_ERR_NULL;
+    }
   }
   // with the larger workspace the forward pass keeps its probabilities (n*r*v*B fp32) and the
   // logit gradient is an elementwise pass; with the smaller one the logits are recomputed
@@ -383,48 +406,66 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   if ((uintptr_t)hd->workspace & 15) return MTPC_ERR_WORKSPACE;
   if (hd->workspace_bytes < q.total) q = make_bwd_plan(family, hd, ly, false);
   if (hd->workspace_bytes < q.total) return MTPC_ERR_WORKSPACE;
-  if (q.ldM * 4 > 0x7fffffffLL / 256 || q.ldb * 4 > 0x7fffffffLL / 256) return MTPC_ERR_UNSUPPORTED;
+  if (q.ldM * 4 > 0x7fffffffLL / 320 || q.ldb * 4 > 0x7fffffffLL / 320) return MTPC_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)hd->stream;
   char* ws = (char*)hd->workspace;
-  const Plan& p = q.fwd;
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
-  s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
-  if (s != MTPC_OK) return s;
+  const long long rr = (long long)hd->r * hd->r;
+
+  // ---- parameters and forward pass
+  if (family != MTPC_FF)
+    HIP_TRY(launch_sumunit(hd->h, hd->ld_h, hd->Wsum, hd->B, hd->d, hd->r, hd->dtype, (float*)(ws + q.logw), st));
+  if (ctx) {
+    CtxLayerArgs cl{};
+    cl.h = hd->h; cl.ld_h = hd->ld_h; cl.R = ly->R; cl.R_layer_stride = ly->R_layer_stride;
+    cl.bias = ly->logits; cl.bias_layer_stride = ly->layer_stride;
+    cl.B = hd->B; cl.d = hd->d; cl.r = hd->r; cl.L = q.Lst;
+    cl.out_nat = (float*)(ws + q.lay_nat); cl.out_tr = (float*)(ws + q.lay_tr);
+    HIP_TRY(launch_ctx_layers(cl, hd->dtype, st));
+  } else if (L > 0) {
+    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, q.Lst, hd->r, 0,
+                                    (float*)(ws + q.lay_nat), st));
+    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, q.Lst, hd->r, 1,
+                                    (float*)(ws + q.lay_tr), st));
+  }
   UnembedArgs u{};
   u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
   u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
-  u.targets = targets; u.T = 1; u.e = (float*)(ws + p.e);
+  u.targets = targets; u.T = 1; u.e = (float*)(ws + q.e);
   if (q.keep_phi) { u.phiT = (float*)(ws + q.phi); u.ld_phi = q.ldb; }
   HIP_TRY(launch_unembed(u, hd->dtype, st));
 
+  // ---- reverse pass through the circuit
   CircuitBwdArgs c{};
   c.family = family; c.rows = hd->B; c.n = hd->n; c.r = hd->r;
-  c.e = (const float*)(ws + p.e);
-  c.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
+  c.e = (const float*)(ws + q.e);
+  c.logw = family == MTPC_FF ? nullptr : (const float*)(ws + q.logw);
   c.coef = coef; c.Ge = (float*)(ws + q.Ge);
   c.dslT = family == MTPC_FF ? nullptr : (void*)(ws + q.dLT + (size_t)q.M * q.ldb * esz);
   c.ldb = q.ldb; c.bf16 = hd->dtype == MTPC_BF16; c.loss = loss;
   if (L > 0) {
-    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, p.Lst, hd->r, 0,
-                                    (float*)(ws + q.lay_nat), st));
-    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, p.Lst, hd->r, 1,
-                                    (float*)(ws + q.lay_tr), st));
-    c.lay_nat = (const float*)(ws + q.lay_nat); c.lay_tr = (const float*)(ws + q.lay_tr); c.L = p.Lst;
-    c.pi = (float*)(ws + q.pi); c.gam = (float*)(ws + q.gam); c.G = (float*)(ws + q.G);
+    c.lay_nat = (const float*)(ws + q.lay_nat); c.lay_tr = (const float*)(ws + q.lay_tr); c.L = q.Lst;
     c.dlayers = dlayers;
+    if (ctx) {
+      c.contextual = 1;
+      c.dlog = ws + q.dL + (size_t)q.Mlay * esz; c.ld_dlog = q.ldM; c.dlog_cols = (int)(q.ldM - q.Mlay);
+    } else {
+      c.pi = (float*)(ws + q.pi); c.gam = (float*)(ws + q.gam); c.G = (float*)(ws + q.G);
+    }
   }
   if (family == MTPC_BTREE) {
     c.ct = (float*)(ws + q.ct); c.adj = (float*)(ws + q.adj);
   }
   HIP_TRY(launch_circuit_bwd(c, st));
 
-  // logit gradient in both layouts: dLT [Mx][ldb] and dL = dLT^T [B][ldM]
+  // ---- logit gradient in both layouts: dLT [.][ldb] and dL = dLT^T [B][ldM]
   TransposeArgs t{};
   if (q.keep_phi) {
     GradPhiArgs g{};
     g.phiT = (const float*)(ws + q.phi); g.ld_phi = q.ldb; g.targets = targets; g.Ge = c.Ge;
     g.B = hd->B; g.n = hd->n; g.r = hd->r; g.v = hd->v;
     g.M = q.M; g.Mx = q.Mx; g.ldM = q.ldM; g.ldb = q.ldb;
+    g.dl_end = ctx ? q.Mlay : q.ldM;           // the layer-logit columns are written by the reverse pass
     g.dLT = ws + q.dLT; g.dL = ws + q.dL;
     HIP_TRY(launch_grad_from_phi(g, hd->dtype, st));
   } else {
@@ -437,30 +478,43 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
       HIP_TRY(launch_unembed_grad(g, hd->dtype, st));
     }
     t.src = ws + q.dLT; t.ld_src = q.ldb; t.R = (int)q.Mx; t.C = hd->B;
-    t.dst = ws + q.dL; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)q.ldM;
+    t.dst = ws + q.dL; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)(ctx ? q.Mlay : q.ldM);
     HIP_TRY(launch_transpose(t, hd->dtype, st));
   }
-  // WT = [W; Wsum]^T [d][ldM], hT = h^T [d][ldb]
+  if (ctx) {                                 // layer-logit block: written per position, transposed here
+    t.src = ws + q.dL + (size_t)q.Mlay * esz; t.ld_src = q.ldM; t.R = hd->B; t.C = (int)(q.ldM - q.Mlay);
+    t.dst = ws + q.dLT + (size_t)q.Mlay * q.ldb * esz; t.ld_dst = q.ldb; t.col0 = 0; t.Rpad = (int)q.ldb;
+    HIP_TRY(launch_transpose(t, hd->dtype, st));
+  }
+  // ---- WT = [W; Wsum; (gap); R]^T [d][ldM], hT = h^T [d][ldb]
   t.src = hd->W; t.ld_src = hd->d; t.R = (int)q.M; t.C = hd->d;
   t.dst = ws + q.WT; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)(family == MTPC_FF ? q.ldM : q.M);
   HIP_TRY(launch_transpose(t, hd->dtype, st));
   if (family != MTPC_FF) {
     t.src = hd->Wsum; t.ld_src = hd->d; t.R = hd->r; t.C = hd->d;
-    t.col0 = q.M; t.Rpad = (int)(q.ldM - q.M);
+    t.col0 = q.M; t.Rpad = (int)((ctx ? q.Mlay : q.ldM) - q.M);
+    HIP_TRY(launch_transpose(t, hd->dtype, st));
+  }
+  if (ctx) {
+    t.src = ly->R; t.ld_src = hd->d; t.R = (int)(L * rr); t.C = hd->d;
+    t.col0 = q.Mlay; t.Rpad = (int)(q.ldM - q.Mlay);
     HIP_TRY(launch_transpose(t, hd->dtype, st));
   }
   t.src = hd->h; t.ld_src = hd->ld_h; t.R = hd->B; t.C = hd->d;
   t.dst = ws + q.hT; t.ld_dst = q.ldb; t.col0 = 0; t.Rpad = (int)q.ldb;
   HIP_TRY(launch_transpose(t, hd->dtype, st));
 
+  // ---- the two contractions
   GemmArgs m{};
   m.A = ws + q.dL; m.lda = q.ldM; m.M = hd->B;                   // dh[b][k] = sum_m dL[b][m] WT[k][m]
   m.Bm = ws + q.WT; m.ldb = q.ldM; m.N = hd->d; m.K = (int)q.ldM;
-  m.C = dh; m.ldc = hd->d; m.split = hd->B; m.C2 = nullptr;
+  m.C = dh; m.ldc = hd->d; m.split = hd->B; m.n2 = 0; m.C2 = nullptr; m.split3 = 0x7fffffff; m.C3 = nullptr;
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
-  m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)q.Mx;              // dW[m][k] = sum_b dLT[m][b] hT[k][b]
+  m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)q.Mtot;            // dW[m][k] = sum_b dLT[m][b] hT[k][b]
   m.Bm = ws + q.hT; m.ldb = q.ldb; m.N = hd->d; m.K = (int)q.ldb;
-  m.C = dW; m.ldc = hd->d; m.split = (int)q.M; m.C2 = dWsum;     // the last r rows are dWsum
+  m.C = dW; m.ldc = hd->d;
+  m.split = (int)q.M; m.n2 = family == MTPC_FF ? 0 : hd->r; m.C2 = dWsum;   // then the r rows of dWsum
+  m.split3 = ctx ? (int)q.Mlay : 0x7fffffff; m.C3 = dR;                     // and, after the gap, dR
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
   return MTPC_OK;
 }
@@ -569,21 +623,21 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
 
 mtpc_status mtpc_ff_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
                                   float* loss, float* dh, float* dW) {
-  return run_backward(MTPC_FF, head, nullptr, targets, coef, loss, dh, dW, nullptr, nullptr);
+  return run_backward(MTPC_FF, head, nullptr, targets, coef, loss, dh, dW, nullptr, nullptr, nullptr);
 }
 mtpc_status mtpc_cp_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
                                   float* loss, float* dh, float* dW, float* dWsum) {
-  return run_backward(MTPC_CP, head, nullptr, targets, coef, loss, dh, dW, dWsum, nullptr);
+  return run_backward(MTPC_CP, head, nullptr, targets, coef, loss, dh, dW, dWsum, nullptr, nullptr);
 }
 mtpc_status mtpc_hmm_loss_backward(const mtpc_head* head, const mtpc_sumlayers* T, const int32_t* targets,
                                    const float* coef, float* loss, float* dh, float* dW, float* dWsum,
-                                   float* dlayers) {
-  return run_backward(MTPC_HMM, head, T, targets, coef, loss, dh, dW, dWsum, dlayers);
+                                   float* dlayers, float* dR) {
+  return run_backward(MTPC_HMM, head, T, targets, coef, loss, dh, dW, dWsum, dlayers, dR);
 }
 mtpc_status mtpc_btree_loss_backward(const mtpc_head* head, const mtpc_sumlayers* A, const int32_t* targets,
                                      const float* coef, float* loss, float* dh, float* dW, float* dWsum,
-                                     float* dlayers) {
-  return run_backward(MTPC_BTREE, head, A, targets, coef, loss, dh, dW, dWsum, dlayers);
+                                     float* dlayers, float* dR) {
+  return run_backward(MTPC_BTREE, head, A, targets, coef, loss, dh, dW, dWsum, dlayers, dR);
 }
 
 mtpc_status mtpc_philox_uniforms(int32_t B, int32_t S, int32_t slots, uint64_t seed, uint32_t offset,

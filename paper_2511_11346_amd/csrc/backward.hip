@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void k_grad_from_phi(const GradPhiArgs a) {
   for (int k = 0; k < 8; ++k) {
     const int bl = br + 16 * k;
     const long long m = m0 + 4 * mq;
-    if (b0 + bl < a.B && m < a.ldM) {                           // ldM is a multiple of 4
+    if (b0 + bl < a.B && m < a.dl_end) {                        // dl_end is a multiple of 4
       Quad out;
 #pragma unroll
       for (int c = 0; c < 4; ++c) out.v[c] = tile[4 * mq + c][bl];
@@ -142,6 +142,7 @@ __device__ __forceinline__ void wave_matvec(const float* __restrict__ M, const f
 __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
   __shared__ float sP[4][64];
   __shared__ float sX[4][128];
+  __shared__ float sPi[4][128], sC[4][128];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const long long row = (long long)blockIdx.x * 4 + wave;
   const int n = a.n, r = a.r;
@@ -214,6 +215,9 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
     //   adj(alpha_j) = g_j pi_j + pi_j * (T_j gam_j),   d loss / d log T_j[z][z'] = pi_j[z] T_j[z][z'] gam_j[z'].
     float* sh = sX[wave];
     const long long lstep = a.L > 1 ? (long long)r * r : 0;
+    const long long lrow = a.contextual ? row * a.L * r * r : 0;       // this position's own layers
+    const float* lay_nat = a.lay_nat + lrow;
+    const float* lay_tr = a.lay_tr + lrow;
     float al0 = w0 + (u0 ? e[lane] : 0.f), al1 = w1 + (u1 ? e[lane + 64] : 0.f);
     float loss = 0.f;
     for (int j = 0; j < n; ++j) {
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
         if (u1) sh[lane + 64] = __expf(al1 - ms);
         __builtin_amdgcn_wave_barrier();
         float s0, s1;
-        wave_matvec(a.lay_nat + (j - 1) * lstep, sh, r, lane, s0, s1);
+        wave_matvec(lay_nat + (j - 1) * lstep, sh, r, lane, s0, s1);
         __builtin_amdgcn_wave_barrier();
         al0 = u0 ? ms + __logf(s0) + e[j * r + lane] : ninf;
         al1 = u1 ? ms + __logf(s1) + e[j * r + lane + 64] : ninf;
@@ -251,7 +255,7 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
         if (u1) sh[lane + 64] = gm1;
         __builtin_amdgcn_wave_barrier();
         float c0, c1;
-        wave_matvec(a.lay_tr + j * lstep, sh, r, lane, c0, c1);            // (T_j gam)[z] via T_j^T
+        wave_matvec(lay_tr + j * lstep, sh, r, lane, c0, c1);              // (T_j gam)[z] via T_j^T
         __builtin_amdgcn_wave_barrier();
         n0 += pi0 * c0;
         n1 += pi1 * c1;
@@ -261,6 +265,29 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
           if (u0) { pp[lane] = pi0; gp[lane] = gm0; }
           if (u1) { pp[lane + 64] = pi1; gp[lane + 64] = gm1; }
         }
+        if (a.dlog != nullptr) {
+          // this position's own transition matrix: softmax backward of pi_z T[z][z'] gam_z' is
+          // pi_z T[z][z'] (gam_z' - (T gam)_z); lanes run over z', the loop over z
+          if (u0) { sPi[wave][lane] = pi0; sC[wave][lane] = c0; }
+          if (u1) { sPi[wave][lane + 64] = pi1; sC[wave][lane + 64] = c1; }
+          __builtin_amdgcn_wave_barrier();
+          const float* Tj = lay_nat + j * lstep;
+          const long long o = row * a.ld_dlog + (long long)j * r * r;
+          for (int z = 0; z < r; ++z) {
+            const float pz = sPi[wave][z], cz = sC[wave][z];
+            if (u0) {
+              const float val = pz * Tj[z * r + lane] * (gm0 - cz);
+              if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane] = to_bf16_rne(val);
+              else ((float*)a.dlog)[o + z * r + lane] = val;
+            }
+            if (u1) {
+              const float val = pz * Tj[z * r + lane + 64] * (gm1 - cz);
+              if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane + 64] = to_bf16_rne(val);
+              else ((float*)a.dlog)[o + z * r + lane + 64] = val;
+            }
+          }
+          __builtin_amdgcn_wave_barrier();
+        }
       }
       nx0 = u0 ? cur0 - e[j * r + lane] : ninf;
       nx1 = u1 ? cur1 - e[j * r + lane + 64] : ninf;
@@ -268,6 +295,11 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
       if (u0) Ge[j * r + lane] = n0;
       if (u1) Ge[j * r + lane + 64] = n1;
     }
+    if (a.dlog != nullptr)                          // padding columns of the block
+      for (int c = (n - 1) * r * r + lane; c < a.dlog_cols; c += 64) {
+        if (a.bf16) ((unsigned short*)a.dlog)[row * a.ld_dlog + c] = 0;
+        else ((float*)a.dlog)[row * a.ld_dlog + c] = 0.f;
+      }
     const float tot = wsum((u0 ? ad0 : 0.f) + (u1 ? ad1 : 0.f));
     put_dsl(ad0 - __expf(w0) * tot, ad1 - __expf(w1) * tot);
     if (lane == 0) a.loss[row] = loss;
@@ -489,6 +521,24 @@ __global__ __launch_bounds__(256) void k_layer_finish(const float* G, const floa
   if (u1) dlayers[row * r + lane + 64] = t1 * (g1 - s);
 }
 
+// out[c] += sum_b src[b][c] over a block of rows (src in the dtype of h, out fp32)
+template <typename T>
+__global__ __launch_bounds__(256) void k_colsum(const T* src, long long ld, int rows, int cols, float* out) {
+  __shared__ float part[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), ty = threadIdx.x >> 6;
+  const int b0 = blockIdx.y * 256;
+  float s = 0.f;
+  if (c < cols)
+    for (int b = b0 + ty; b < min(rows, b0 + 256); b += 4) {
+      if constexpr (sizeof(T) == 2) s += __uint_as_float(((unsigned)src[(long long)b * ld + c]) << 16);
+      else s += src[(long long)b * ld + c];
+    }
+  part[ty][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (ty == 0 && c < cols)
+    atomicAdd(out + c, (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]));
+}
+
 __global__ __launch_bounds__(256) void k_fill_zero(float* p, long long n) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0.f;
@@ -517,7 +567,12 @@ hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
   const bool tree = a.family == MTPC_BTREE;
   const int T = tree ? tree_program_steps(a.n, 1) : a.n - 1;
   const size_t prog_bytes = tree ? (size_t)T * sizeof(TreeStep) : 0;
-  const bool layers = a.dlayers != nullptr && ((a.family == MTPC_HMM && a.n > 1) || (tree && a.n > 2));
+  const bool ctx = a.contextual && a.dlog != nullptr;
+  const bool layers = !ctx && a.dlayers != nullptr && ((a.family == MTPC_HMM && a.n > 1) || (tree && a.n > 2));
+  if (ctx && a.dlayers != nullptr) {               // bias gradient = column sums of the logit gradients
+    const long long cnt = (long long)a.L * r * r;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.dlayers, cnt);
+  }
   if (layers) {
     const long long cnt = (long long)a.L * r * r;
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.G, cnt);
@@ -535,6 +590,14 @@ hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
     else hipLaunchKernelGGL(k_layer_outer<64>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
     const int nrows = a.L * r;
     hipLaunchKernelGGL(k_layer_finish, dim3((nrows + 3) / 4), dim3(256), 0, st, a.G, a.lay_nat, nrows, r, a.dlayers);
+  }
+  if (ctx && a.dlayers != nullptr) {
+    const int cols = a.L * r * r;
+    const dim3 grid((cols + 63) / 64, (a.rows + 255) / 256);
+    if (a.bf16) hipLaunchKernelGGL(k_colsum<unsigned short>, grid, dim3(256), 0, st, (const unsigned short*)a.dlog,
+                                   a.ld_dlog, a.rows, cols, a.dlayers);
+    else hipLaunchKernelGGL(k_colsum<float>, grid, dim3(256), 0, st, (const float*)a.dlog, a.ld_dlog, a.rows, cols,
+                            a.dlayers);
   }
   return hipGetLastError();
 }

@@ -134,7 +134,8 @@ void k_gemm_tn(const GemmArgs a) {
         if (row < rows) {
           const long long gr = (long long)slab * TL::TV + row;
           if (gr < a.split) a.C[gr * a.ldc + col] = acc[pb][vb][i];
-          else a.C2[(gr - a.split) * a.ldc + col] = acc[pb][vb][i];
+          else if (gr < a.split + a.n2) a.C2[(gr - a.split) * a.ldc + col] = acc[pb][vb][i];
+          else if (gr >= a.split3) a.C3[(gr - a.split3) * a.ldc + col] = acc[pb][vb][i];
         }
       }
   }

@@ -158,6 +158,7 @@ struct GradPhiArgs {
   const int* targets; const float* Ge;
   int B, n, r, v;
   long long M, Mx, ldM, ldb;
+  long long dl_end;     // dL is written for m < dl_end (a multiple of 4); columns beyond belong to others
   void* dLT; void* dL;
 };
 hipError_t launch_grad_from_phi(const GradPhiArgs& a, int dtype, hipStream_t st);
@@ -169,7 +170,10 @@ struct GemmArgs {
   const void* Bm; long long ldb; int N;
   int K;
   float* C; long long ldc;
-  int split; float* C2;   // rows >= split go to C2[(row - split)][ldc] (split >= M: none)
+  // output rows are dealt to up to three buffers: [0, split) -> C, [split, split + n2) -> C2,
+  // [split3, M) -> C3; rows in between are computed and dropped
+  int split; int n2; float* C2;
+  int split3; float* C3;
 };
 hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t st);
 
@@ -194,6 +198,11 @@ struct CircuitBwdArgs {
   float* pi;             // scratch [rows][steps][r] (layer gradients only; steps = n-1 for the HMM)
   float* gam;            // scratch [rows][steps][r]
   float* G;              // scratch [L][r][r]
+  // layers of every position (computed from h): lay_nat / lay_tr hold [rows][L][r][r] and the
+  // gradient w.r.t. the logits of position b goes to dlog[b*ld_dlog + (l*r + z)*r + z'] in the
+  // dtype of h (dlog_cols columns, zero beyond L*r*r); dlayers then receives the column sums
+  int contextual;
+  void* dlog; long long ld_dlog; int dlog_cols;
   float* ct;             // binary tree: scratch [rows][steps][r], output of every program step
   float* adj;            // binary tree: scratch [rows][n-1][r], adjoints of the node values
   float* Ge;             // [rows][n][r]

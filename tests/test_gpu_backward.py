@@ -37,9 +37,10 @@ def check_grad(name, got, want, dtype):
 
 def make_case(family, dtype, B, d, n, r, v, seed):
     shared = family.endswith("-shared")                          # one transition matrix for all steps
+    ctx = family.endswith("-ctx")                                # transition logits R h + bias (Sec. 3.3)
     family = family.split("-")[0]
     inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=seed, h_scale=1.0,
-                         layer_count=1 if shared else None)
+                         layer_count=1 if shared else None, contextual=ctx)
     rng = np.random.default_rng(seed + 1)
     targets = inp.targets.copy()
     targets[rng.random(targets.shape) < 0.05] = -1               # a few summed-out variables
@@ -65,6 +66,9 @@ CASES = [
     ("btree", "f32", 21, 32, 2, 6, 20, 14),
     ("btree", "bf16", 37, 64, 16, 128, 40, 15),
     ("btree-shared", "f32", 45, 64, 8, 8, 40, 16),
+    ("hmm-ctx", "f32", 70, 64, 4, 5, 33, 17),
+    ("hmm-ctx", "bf16", 200, 128, 8, 16, 320, 18),
+    ("hmm-ctx", "bf16", 37, 64, 3, 128, 40, 19),
 ]
 
 
@@ -75,16 +79,18 @@ def test_loss_and_gradients_match_oracle(family, dtype, B, d, n, r, v, seed):
     head = make_head(inp)
     out = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda())
     layers = inp.layers if inp.layers is not None and inp.layers.size else None
-    want = bw.loss_and_gradients(family, inp.h, inp.W, inp.Wsum, layers, targets, coef.astype(np.float32))
+    want = bw.loss_and_gradients(family, inp.h, inp.W, inp.Wsum, layers, targets, coef.astype(np.float32), R=inp.R)
     loss = out["loss"].cpu().numpy()
     tol = 1e-4 if dtype == "f32" else 2e-3
     assert np.all(np.abs(loss - want["loss"]) <= tol * np.maximum(np.abs(want["loss"]), 1e-2) + (1e-4 if dtype == "f32" else 0))
     msg = [f"{family} {dtype} B={B} n={n} r={r} v={v}:"]
-    for name in ("dh", "dW", "dWsum", "dlayers"):
+    for name in ("dh", "dW", "dWsum", "dlayers", "dR"):
         if want[name] is None or want[name].size == 0:
             continue
-        # layer gradients never pass through the bf16 logit gradient: fp32 accuracy for both dtypes
-        msg.append(f"{name} {check_grad(name, out[name], want[name], 'f32' if name == 'dlayers' else dtype):.1e}")
+        # gradients of layers shared by all positions never pass through the bf16 logit gradient:
+        # fp32 accuracy for both dtypes; with R they do (bias = column sums of rounded values)
+        crit = "f32" if (name == "dlayers" and inp.R is None) else dtype
+        msg.append(f"{name} {check_grad(name, out[name], want[name], crit):.1e}")
     print(" ".join(msg), "(relative Frobenius error)")
     # a second call with the same buffers gives the same bits (nothing accumulates across calls)
     again = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda())
@@ -92,6 +98,6 @@ def test_loss_and_gradients_match_oracle(family, dtype, B, d, n, r, v, seed):
     # the lean plan (logits recomputed instead of probabilities kept) meets the same bar
     lean = head.loss_backward(torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda(),
                               recompute=True)
-    for name in ("dh", "dW", "dWsum"):
+    for name in ("dh", "dW", "dWsum", "dR"):
         if want[name] is not None:
             check_grad(name + " (recompute)", lean[name], want[name], dtype)
