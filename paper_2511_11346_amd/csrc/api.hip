@@ -357,8 +357,8 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
   if (L > 0) {
     const size_t lay = (q.ctx ? B : 1) * (size_t)q.Lst * r * r * 4;
     q.lay_nat = take(lay);
-    q.lay_tr = take(lay);
     if (!q.ctx) {
+      q.lay_tr = take(lay);
       q.pi = take(B * q.steps * r * 4);
       q.gam = take(B * q.steps * r * 4);
       q.G = take((size_t)q.Lst * r * r * 4);
@@ -420,7 +420,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     cl.h = hd->h; cl.ld_h = hd->ld_h; cl.R = ly->R; cl.R_layer_stride = ly->R_layer_stride;
     cl.bias = ly->logits; cl.bias_layer_stride = ly->layer_stride;
     cl.B = hd->B; cl.d = hd->d; cl.r = hd->r; cl.L = q.Lst;
-    cl.out_nat = (float*)(ws + q.lay_nat); cl.out_tr = (float*)(ws + q.lay_tr);
+    cl.out_nat = (float*)(ws + q.lay_nat); cl.out_tr = nullptr;
     HIP_TRY(launch_ctx_layers(cl, hd->dtype, st));
   } else if (L > 0) {
     HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, q.Lst, hd->r, 0,
@@ -444,7 +444,8 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   c.dslT = family == MTPC_FF ? nullptr : (void*)(ws + q.dLT + (size_t)q.M * q.ldb * esz);
   c.ldb = q.ldb; c.bf16 = hd->dtype == MTPC_BF16; c.loss = loss;
   if (L > 0) {
-    c.lay_nat = (const float*)(ws + q.lay_nat); c.lay_tr = (const float*)(ws + q.lay_tr); c.L = q.Lst;
+    c.lay_nat = (const float*)(ws + q.lay_nat); c.lay_tr = ctx ? nullptr : (const float*)(ws + q.lay_tr);
+    c.L = q.Lst;
     c.dlayers = dlayers;
     if (ctx) {
       c.contextual = 1;

@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
     const long long lstep = a.L > 1 ? (long long)r * r : 0;
     const long long lrow = a.contextual ? row * a.L * r * r : 0;       // this position's own layers
     const float* lay_nat = a.lay_nat + lrow;
-    const float* lay_tr = a.lay_tr + lrow;
+    const float* lay_tr = a.lay_tr ? a.lay_tr + lrow : nullptr;   // shared layers only
     float al0 = w0 + (u0 ? e[lane] : 0.f), al1 = w1 + (u1 ? e[lane + 64] : 0.f);
     float loss = 0.f;
     for (int j = 0; j < n; ++j) {
@@ -255,7 +255,37 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
         if (u1) sh[lane + 64] = gm1;
         __builtin_amdgcn_wave_barrier();
         float c0, c1;
-        wave_matvec(lay_tr + j * lstep, sh, r, lane, c0, c1);              // (T_j gam)[z] via T_j^T
+        if (a.dlog == nullptr) {
+          wave_matvec(lay_tr + j * lstep, sh, r, lane, c0, c1);            // (T_j gam)[z] via T_j^T
+        } else {
+          // this position's own transition matrix (natural layout only): lanes run over z',
+          // the loop over z; (T gam)_z is a wave reduction, and the softmax backward of
+          // pi_z T[z][z'] gam_z' is pi_z T[z][z'] (gam_z' - (T gam)_z), written along z'
+          if (u0) sPi[wave][lane] = pi0;
+          if (u1) sPi[wave][lane + 64] = pi1;
+          __builtin_amdgcn_wave_barrier();
+          const float* Tj = lay_nat + j * lstep;
+          const long long o = row * a.ld_dlog + (long long)j * r * r;
+          for (int z = 0; z < r; ++z) {
+            const float t0 = u0 ? Tj[z * r + lane] : 0.f, t1 = u1 ? Tj[z * r + lane + 64] : 0.f;
+            const float cz = wsum(t0 * gm0 + t1 * gm1);
+            const float pz = sPi[wave][z];
+            if (lane == 0) sC[wave][z] = cz;
+            if (u0) {
+              const float val = pz * t0 * (gm0 - cz);
+              if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane] = to_bf16_rne(val);
+              else ((float*)a.dlog)[o + z * r + lane] = val;
+            }
+            if (u1) {
+              const float val = pz * t1 * (gm1 - cz);
+              if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane + 64] = to_bf16_rne(val);
+              else ((float*)a.dlog)[o + z * r + lane + 64] = val;
+            }
+          }
+          __builtin_amdgcn_wave_barrier();
+          c0 = u0 ? sC[wave][lane] : 0.f;
+          c1 = u1 ? sC[wave][lane + 64] : 0.f;
+        }
         __builtin_amdgcn_wave_barrier();
         n0 += pi0 * c0;
         n1 += pi1 * c1;
@@ -264,29 +294,6 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
           float* gp = a.gam + (row * (n - 1) + j) * r;
           if (u0) { pp[lane] = pi0; gp[lane] = gm0; }
           if (u1) { pp[lane + 64] = pi1; gp[lane + 64] = gm1; }
-        }
-        if (a.dlog != nullptr) {
-          // this position's own transition matrix: softmax backward of pi_z T[z][z'] gam_z' is
-          // pi_z T[z][z'] (gam_z' - (T gam)_z); lanes run over z', the loop over z
-          if (u0) { sPi[wave][lane] = pi0; sC[wave][lane] = c0; }
-          if (u1) { sPi[wave][lane + 64] = pi1; sC[wave][lane + 64] = c1; }
-          __builtin_amdgcn_wave_barrier();
-          const float* Tj = lay_nat + j * lstep;
-          const long long o = row * a.ld_dlog + (long long)j * r * r;
-          for (int z = 0; z < r; ++z) {
-            const float pz = sPi[wave][z], cz = sC[wave][z];
-            if (u0) {
-              const float val = pz * Tj[z * r + lane] * (gm0 - cz);
-              if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane] = to_bf16_rne(val);
-              else ((float*)a.dlog)[o + z * r + lane] = val;
-            }
-            if (u1) {
-              const float val = pz * Tj[z * r + lane + 64] * (gm1 - cz);
-              if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane + 64] = to_bf16_rne(val);
-              else ((float*)a.dlog)[o + z * r + lane + 64] = val;
-            }
-          }
-          __builtin_amdgcn_wave_barrier();
         }
       }
       nx0 = u0 ? cur0 - e[j * r + lane] : ninf;

@@ -319,6 +319,115 @@ void k_ctx_layers(const CtxLayerArgs a) {
   }
 }
 
+// The same for r a power of two in 8..128 and natural layout only: R is taken as one
+// dense [L*r*r][d] matrix cut into 256-row slabs, so no matrix-pipe row is wasted on
+// padding.  A sum unit is an aligned run of r rows; in the accumulator layout those are
+// whole 32-row blocks of one wave (r >= 32) or register groups of a block (r < 32) plus
+// the partner lane 32 away, so its softmax needs one cross-lane exchange and no LDS.
+template <int R, bool BF16>
+__global__ __launch_bounds__(512)
+void k_ctx_layers_dense(const CtxLayerArgs a) {
+  constexpr int WV = 2, WB = 4, VB = 4, PB = 2, SB = 64, NS = 4;
+  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  constexpr int ESZ = BF16 ? 2 : 4;
+  constexpr int UB = R >= 32 ? R / 32 : 1;          // blocks per unit
+  constexpr int RG = R >= 32 ? 16 : R / 2;          // registers per unit within a block
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wv = wave % WV, wb = wave / WV;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int Mr = a.L * a.r * a.r;
+  const int nslab = (Mr + TL::TV - 1) / TL::TV;
+  const int nbt = (a.B + TL::TP - 1) / TL::TP;
+  int slab, bt;
+  tile_of_block(blockIdx.x, nbt, nslab, slab, bt);
+  const int b0 = bt * TL::TP;
+  const int rows = min(TL::TV, Mr - slab * TL::TV);
+  f32x16_t acc[PB][VB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>((const char*)a.R + (long long)slab * TL::TV * a.d * ESZ, a.d, a.h,
+                                          a.ld_h, a.B, a.d, rows, 0, b0, smem, acc);
+  const int rbase = wv * VB * 32 + 4 * lhalf;
+  if (a.bias != nullptr) {
+#pragma unroll
+    for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+        const float bv = row < rows ? a.bias[(long long)slab * TL::TV + row] : 0.f;
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) acc[pb][vb][i] += bv;
+      }
+  }
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) {
+    const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+#pragma unroll
+    for (int vb0 = 0; vb0 < VB; vb0 += UB)
+#pragma unroll
+      for (int i0 = 0; i0 < 16; i0 += RG) {
+        float m = neg_inf();
+#pragma unroll
+        for (int vb = vb0; vb < vb0 + UB; ++vb)
+#pragma unroll
+          for (int i = i0; i < i0 + RG; ++i) m = fmaxf(m, acc[pb][vb][i]);
+        m = fmaxf(m, __shfl_xor(m, 32));
+        float s = 0.f;
+#pragma unroll
+        for (int vb = vb0; vb < vb0 + UB; ++vb)
+#pragma unroll
+          for (int i = i0; i < i0 + RG; ++i) {
+            acc[pb][vb][i] = __expf(acc[pb][vb][i] - m);
+            s += acc[pb][vb][i];
+          }
+        s += __shfl_xor(s, 32);
+        const float inv = 1.f / s;
+#pragma unroll
+        for (int vb = vb0; vb < vb0 + UB; ++vb)
+#pragma unroll
+          for (int i = i0; i < i0 + RG; ++i) acc[pb][vb][i] *= inv;
+      }
+    if (b < a.B) {
+      float* dst = a.out_nat + (long long)b * Mr + (long long)slab * TL::TV;
+#pragma unroll
+      for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row = rbase + vb * 32 + 8 * q;
+          if (row < rows)
+            *(f32x4_t*)(dst + row) = f32x4_t{acc[pb][vb][4 * q], acc[pb][vb][4 * q + 1], acc[pb][vb][4 * q + 2],
+                                             acc[pb][vb][4 * q + 3]};
+        }
+    }
+  }
+}
+
+template <int R, bool BF16>
+static hipError_t launch_ctx_dense(const CtxLayerArgs& a, hipStream_t st) {
+  using TL = Tile<2, 4, 4, 2, 64, 4>;
+  auto kern = k_ctx_layers_dense<R, BF16>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int Mr = a.L * a.r * a.r;
+  const int nbt = (a.B + TL::TP - 1) / TL::TP, nslab = (Mr + TL::TV - 1) / TL::TV;
+  hipLaunchKernelGGL(kern, dim3(nbt * nslab), dim3(TL::NT), TL::SMEM, st, a);
+  return hipGetLastError();
+}
+
+template <bool BF16>
+static hipError_t launch_ctx_dense_dt(const CtxLayerArgs& a, hipStream_t st) {
+  switch (a.r) {
+    case 8: return launch_ctx_dense<8, BF16>(a, st);
+    case 16: return launch_ctx_dense<16, BF16>(a, st);
+    case 32: return launch_ctx_dense<32, BF16>(a, st);
+    case 64: return launch_ctx_dense<64, BF16>(a, st);
+    default: return launch_ctx_dense<128, BF16>(a, st);
+  }
+}
+
 template <int WV, int WB, int VB, int PB, bool BF16>
 static hipError_t launch_ctx_cfg(const CtxLayerArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, 64, 4>;
@@ -337,6 +446,12 @@ static hipError_t launch_ctx_cfg(const CtxLayerArgs& a, hipStream_t st) {
 
 hipError_t launch_ctx_layers(const CtxLayerArgs& a, int dtype, hipStream_t st) {
   const bool bf = dtype == MTPC_BF16;
+  const long long rr = (long long)a.r * a.r;
+  const bool pow2 = a.r >= 8 && a.r <= 128 && (a.r & (a.r - 1)) == 0;
+  const bool dense_R = a.L == 1 || a.R_layer_stride == rr * a.d;
+  const bool dense_bias = a.bias == nullptr || a.L == 1 || a.bias_layer_stride == rr;
+  if (a.B > 64 && pow2 && dense_R && dense_bias && a.out_nat != nullptr && a.out_tr == nullptr)
+    return bf ? launch_ctx_dense_dt<true>(a, st) : launch_ctx_dense_dt<false>(a, st);
   if (a.B > 64) {     // 64- or 128-row unit tiles x 256 positions
     if (a.r > 64) return bf ? launch_ctx_cfg<2, 4, 2, 2, true>(a, st) : launch_ctx_cfg<2, 4, 2, 2, false>(a, st);
     return bf ? launch_ctx_cfg<2, 4, 1, 2, true>(a, st) : launch_ctx_cfg<2, 4, 1, 2, false>(a, st);

@@ -202,6 +202,9 @@ def test_strided_hidden_states_and_determinism():
 @pytest.mark.parametrize("family,dtype,B,d,n,r", [
     ("hmm", "f32", 70, 64, 4, 5), ("hmm", "bf16", 300, 128, 5, 32), ("btree", "bf16", 130, 64, 8, 16),
     ("btree", "f32", 33, 32, 4, 70), ("hmm", "bf16", 20, 64, 3, 8),
+    # r a power of two and more than 64 positions: the dense-slab kernel, every unit size
+    ("hmm", "f32", 100, 64, 3, 8), ("hmm", "bf16", 97, 64, 4, 16), ("hmm", "bf16", 130, 64, 3, 64),
+    ("hmm", "f32", 70, 32, 2, 128),
 ])
 def test_sum_layers_computed_from_the_hidden_state(family, dtype, B, d, n, r):
     """Sec. 3.3 / App. HMM setup: layer logits R[l,k] e_t + bias computed in the library."""
