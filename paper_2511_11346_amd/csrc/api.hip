@@ -27,12 +27,12 @@ int n_layers(int family, int n) {
   return 0;
 }
 
-// Drafts are scored by re-reading single rows of W when there are few of them
-// (B*S rows of length d per slab instead of all v), else by a second fused pass.
+// Few drafts are scored from the table of normalised input units that the sampling pass
+// then writes (B*n*r*v floats), many by a second fused pass with the drafts as targets.
 bool score_by_gather(const mtpc_head* hd, int S) { return (long long)hd->B * S * 4 <= hd->v; }
 
 struct Plan {           // byte offsets into the workspace
-  size_t logw, lay_nat, lay_circ, e, lse, zleaf, lat, logm, total;
+  size_t logw, lay_nat, lay_circ, e, zleaf, lat, logm, table, total;
   int nb, Lst;          // position blocks and stored layers of the normalised copies
 };
 
@@ -97,7 +97,8 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   p.lay_circ = need_tr ? take(lay_bytes) : p.lay_nat;
   const size_t rows = sample ? B * (size_t)S : B;
   p.e = (uni || verify || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
-  p.lse = (sample && want_prefix) ? take(B * n * r * 4) : 0;
+  // few drafts: they are scored from the table of input units the sampling pass leaves behind
+  p.table = (sample && want_prefix && score_by_gather(hd, S)) ? take(B * n * r * (size_t)hd->v * 4) : 0;
   p.zleaf = sample ? take(B * (size_t)S * n * 4) : 0;
   p.lat = sample ? take(B * (size_t)S * (size_t)(n_latents(family, hd->n) + 1) * 4) : 0;
   p.logm = uni ? take(B * n * r * 4) : 0;
@@ -261,9 +262,8 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
   u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
   u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset;
-  u.logphi = logphi;
   const bool gather = want_prefix && score_by_gather(hd, S);
-  if (gather) u.lse = (float*)(ws + p.lse);
+  u.logphi = logphi ? logphi : (gather ? (float*)(ws + p.table) : nullptr);
   {
     ProfScope prof(st);
     HIP_TRY(launch_unembed(u, hd->dtype, st));
@@ -278,10 +278,9 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   if (want_prefix) {
     if (gather) {
       GatherArgs g{};
-      g.h = hd->h; g.ld_h = hd->ld_h; g.W = hd->W;
-      g.B = hd->B; g.S = S; g.d = hd->d; g.v = hd->v; g.n = hd->n; g.r = hd->r;
-      g.x = drafts; g.lse = (const float*)(ws + p.lse); g.e = (float*)(ws + p.e);
-      HIP_TRY(launch_gather_evidence(g, hd->dtype, st));
+      g.B = hd->B; g.S = S; g.v = hd->v; g.n = hd->n; g.r = hd->r;
+      g.x = drafts; g.e = (float*)(ws + p.e);
+      HIP_TRY(launch_gather_table(g, u.logphi, st));
     }
     HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * S, S, prefix_logq, 1), st));
   }

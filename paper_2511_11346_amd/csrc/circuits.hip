@@ -855,79 +855,26 @@ hipError_t launch_latent_marginals(const LatentMarginalArgs& a, hipStream_t st) 
 }
 
 // ---------------------------------------------------------------------------
-// gather evidence: e[(b,s)][i][j] = <W[i][j][x_bsi], h[b]> - lse[b][i][j]
-// one wave per (b, s, i, group of 4 components)
-// ---------------------------------------------------------------------------
-template <bool BF16>
-__global__ __launch_bounds__(256) void k_gather_evidence(const GatherArgs a) {
-  constexpr int ESZ = BF16 ? 2 : 4;
-  constexpr int EPC = 16 / ESZ;
-  const int lane = threadIdx.x & 63;
-  const int jg = (a.r + 3) / 4;
-  const long long wid = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const long long total = (long long)a.B * a.S * a.n * jg;
-  if (wid >= total) return;
-  const int q = (int)(wid % jg);
-  const long long bsi = wid / jg;
+// evidence of drafted tokens read from the table of normalised input units the sampling
+// pass wrote: e[(b*S+s)][i][j] = logphi[b][i][j][x]
+__global__ __launch_bounds__(256) void k_gather_table(const GatherArgs a, const float* logphi) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long total = (long long)a.B * a.S * a.n * a.r;
+  if (t >= total) return;
+  const int j = (int)(t % a.r);
+  const long long bsi = t / a.r;
   const int i = (int)(bsi % a.n);
-  const long long bs = bsi / a.n;
-  const int b = (int)(bs / a.S);
+  const long long b = bsi / a.n / a.S;
   const int x = a.x[bsi];
-  const char* hb = (const char*)a.h + (long long)b * a.ld_h * ESZ;
-  const int nch = a.d / EPC;
-  const bool valid = x >= 0 && x < a.v;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  if (valid) {
-    // all loads of a pass are issued before the first use (clamped, so unconditional)
-    for (int c0 = 0; c0 < nch; c0 += 512) {
-      i32x4_t hv[8], wv[2][8];
-      const char* wr[4];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int j = min(q * 4 + jj, a.r - 1);
-        wr[jj] = (const char*)a.W + ((((long long)i * a.r + j) * a.v + x) * (long long)a.d) * ESZ;
-      }
-      int cc[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) cc[t] = min(c0 + t * 64 + lane, nch - 1);
-      // loads first, arithmetic afterwards: two rows of W are in flight at a time
-#pragma unroll
-      for (int t = 0; t < 8; ++t) hv[t] = *(const i32x4_t*)(hb + (long long)cc[t] * 16);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) wv[0][t] = *(const i32x4_t*)(wr[0] + (long long)cc[t] * 16);
-#pragma unroll
-      for (int t = 0; t < 8; ++t)
-        if (c0 + t * 64 + lane >= nch) hv[t] = i32x4_t{0, 0, 0, 0};
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        if (jj + 1 < 4) {
-#pragma unroll
-          for (int t = 0; t < 8; ++t) wv[(jj + 1) & 1][t] = *(const i32x4_t*)(wr[jj + 1] + (long long)cc[t] * 16);
-        }
-#pragma unroll
-        for (int t = 0; t < 8; ++t) acc[jj] += dot_chunk<BF16>(wv[jj & 1][t], hv[t]);
-      }
-    }
-  }
-#pragma unroll
-  for (int jj = 0; jj < 4; ++jj) {
-    const int j = q * 4 + jj;
-    if (j >= a.r) break;
-    float* dst = a.e + (bs * a.n + i) * a.r + j;
-    if (!valid) {
-      if (lane == 0) *dst = (x == -1) ? 0.f : __builtin_nanf("");
-      continue;
-    }
-    const float v = wave_sum(acc[jj]);
-    if (lane == 0) *dst = v - a.lse[((long long)b * a.n + i) * a.r + j];
-  }
+  float v;
+  if (x >= 0 && x < a.v) v = logphi[((b * a.n + i) * a.r + j) * a.v + x];
+  else v = (x == -1) ? 0.f : __builtin_nanf("");
+  a.e[t] = v;
 }
 
-hipError_t launch_gather_evidence(const GatherArgs& a, int dtype, hipStream_t st) {
-  const long long total = (long long)a.B * a.S * a.n * ((a.r + 3) / 4);
-  dim3 grid((unsigned)((total + 3) / 4)), block(256);
-  if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_gather_evidence<true>, grid, block, 0, st, a);
-  else hipLaunchKernelGGL(k_gather_evidence<false>, grid, block, 0, st, a);
+hipError_t launch_gather_table(const GatherArgs& a, const float* logphi, hipStream_t st) {
+  const long long total = (long long)a.B * a.S * a.n * a.r;
+  hipLaunchKernelGGL(k_gather_table, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, logphi);
   return hipGetLastError();
 }
 

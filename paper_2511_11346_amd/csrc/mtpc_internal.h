@@ -110,15 +110,14 @@ struct LatentMarginalArgs {
 };
 hipError_t launch_latent_marginals(const LatentMarginalArgs& a, hipStream_t st);
 
-// e[(b*S+s)][i][j] = <W[i][j][x], h[b]> - lse[b][i][j] with x = drafts[b][s][i]
+// evidence of drafted tokens from the table the sampling pass wrote:
+// e[(b*S+s)][i][j] = logphi[b][i][j][x] with x = drafts[b][s][i]
 struct GatherArgs {
-  const void* h; long long ld_h; const void* W;
-  int B, S, d, v, n, r;
+  int B, S, v, n, r;
   const int* x;         // [B][S][n]
-  const float* lse;     // [B][n][r]
   float* e;             // [B*S][n][r]
 };
-hipError_t launch_gather_evidence(const GatherArgs& a, int dtype, hipStream_t st);
+hipError_t launch_gather_table(const GatherArgs& a, const float* logphi, hipStream_t st);
 
 // Verification step of a speculative-decoding cycle (Alg. 2, acceptance loop on)
 struct VerifyArgs {

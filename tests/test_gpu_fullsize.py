@@ -171,3 +171,33 @@ def test_config2_training_step_full_size():
         print(f"sparse run ({len(few)} positions): {name} rel. Frobenius error {fro2:.1e}")
     others = np.setdiff1d(np.arange(B), few)
     assert float(out2["dh"][torch.from_numpy(others).cuda()].abs().max()) == 0.0
+
+
+def test_config3_contextual_training_step_full_size():
+    """The HMM the paper trains (transition logits R h + bias), B = 8192: loss and dh on
+    sampled positions against the oracle; dW, dWsum, dR and the bias gradient exactly in a
+    run whose coefficients vanish outside a couple of dozen positions."""
+    inp = mi.config3_contextual()
+    B, n = inp.B, inp.n
+    head = make_head(inp)
+    coef = bw.loss_coefficients(0.8, np.ones((B, n), bool), sequence=np.arange(B) // 2048).astype(np.float32)
+    tg = torch.from_numpy(inp.targets).cuda()
+    out = head.loss_backward(tg, torch.from_numpy(coef).cuda())
+    rows = sample_rows(B, k=6)
+    want = bw.loss_and_gradients("hmm", inp.h[rows], inp.W, inp.Wsum, inp.layers, inp.targets[rows], coef[rows], R=inp.R)
+    dh = out["dh"].cpu().numpy()[rows].astype(np.float64)
+    fro = np.linalg.norm(dh - want["dh"]) / np.linalg.norm(want["dh"])
+    assert fro <= 3e-3, fro
+    assert np.all(np.abs(out["loss"].cpu().numpy()[rows] - want["loss"]) <= 2e-3 * np.maximum(np.abs(want["loss"]), 1e-6))
+    few = np.unique(np.concatenate([sample_rows(B, k=6, seed=5), [4095, 4096]]))
+    sparse = np.zeros_like(coef)
+    sparse[few] = coef[few] * 100.0
+    out2 = head.loss_backward(tg, torch.from_numpy(sparse).cuda(), out=out)
+    want2 = bw.loss_and_gradients("hmm", inp.h[few], inp.W, inp.Wsum, inp.layers, inp.targets[few], sparse[few], R=inp.R)
+    msg = [f"dh rows {fro:.1e}"]
+    for name in ("dW", "dWsum", "dR", "dlayers"):
+        got = out2[name].cpu().numpy().astype(np.float64)
+        f2 = np.linalg.norm(got - want2[name]) / np.linalg.norm(want2[name])
+        assert f2 <= 3e-3 and np.abs(got - want2[name]).max() <= 2e-2 * np.abs(want2[name]).max(), (name, f2)
+        msg.append(f"{name} {f2:.1e}")
+    print("relative Frobenius errors:", " ".join(msg))
