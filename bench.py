@@ -229,7 +229,8 @@ def main():
             torch.cuda.synchronize()
             call_ms = (time.perf_counter() - t) * 1e3 / reps
             kms = sum(ev.elapsed_ms(a, b) for a, b in prs) / reps
-            byts = inp5.n * inp5.r * inp5.v * inp5.d * 2 + Bd * inp5.d * 2
+            # W streamed once, h, and the table of input units the sampling pass writes
+            byts = inp5.n * inp5.r * inp5.v * inp5.d * 2 + Bd * inp5.d * 2 + Bd * inp5.n * inp5.r * inp5.v * 4
             # the verification step of the same cycle (Alg. 2): the sampler also keeps its
             # table of input units, then accept / reject against a synthetic verifier that is
             # 90 % the component each draft was drawn from and 10 % random tables
@@ -244,10 +245,26 @@ def main():
             ms_table = time_op(lambda: hd.sample(1, seed=0, offset=0, out=o, logphi=table), reps)
             ms_verify = time_op(lambda: hd.verify(dr, pver, prefix_logq=sc, logphi=table, seed=1, offset=1), reps)
             acc, _ = hd.verify(dr, pver, prefix_logq=sc, logphi=table, seed=1, offset=1)
+            # the same cycle (draft + scores + table, verification) replayed from a HIP graph
+            def cycle():
+                hd.sample(1, seed=0, offset=0, out=o, logphi=table)
+                return hd.verify(o[0][:, 0], pver, prefix_logq=o[2][:, 0], logphi=table, seed=1, offset=1)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                cycle()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                cycle()
+            ms_graph = time_op(graph.replay, reps)
+            del graph
             dec.append({"B": Bd, "call_ms": call_ms, "drafts_per_s": Bd / (call_ms * 1e-3),
                         "k_unembed_ms": kms, "achieved_GBps": byts / (kms * 1e-3) / 1e9,
                         "frac_of_hbm_peak": byts / (kms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
                         "call_ms_keeping_table": ms_table, "verify_call_ms": ms_verify,
+                        "cycle_ms_from_graph": ms_graph,
                         "mean_accepted": float(acc.float().mean())})
         out["decode_cp_r32_n16"] = dec
 

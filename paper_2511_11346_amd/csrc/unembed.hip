@@ -92,36 +92,32 @@ void k_unembed(const UnembedArgs a) {
 
   if constexpr (SAMPLE) {
     if (a.logphi != nullptr) {
-      // table log phi[b][wi][wj][:] for the verification step: staged through LDS
-      // (stage buffers are free now) so that the global writes run along v
-      constexpr int STR = TL::VPL * 64 + 1;        // odd stride: positions fall into different banks
-      static_assert(NSLOT * STR * 4 <= NS * TL::STAGE, "table staging must fit in the stage buffers");
-      float* stg = (float*)smem;
-      for (int c0 = 0; c0 < TL::TP; c0 += NSLOT) {
-        __syncthreads();
+      // table log phi[b][wi][wj][:] for the scoring and verification steps.  Registers
+      // 4q..4q+3 of a block hold four consecutive vocabulary rows of one position: one
+      // 16-byte store each (the row of a position is 4v bytes long and 16-byte aligned
+      // when v is a multiple of 4; otherwise element by element)
+      const bool vec = (a.v & 3) == 0;
 #pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-          const int p = wb * PB * 32 + pb * 32 + l31 - c0;
-          if (p >= 0 && p < NSLOT) {
+      for (int pb = 0; pb < PB; ++pb) {
+        const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+        if (b >= a.B) continue;
+        float* dst = a.logphi + (((long long)b * a.n + wi) * a.r + wj) * a.v;
 #pragma unroll
-            for (int vb = 0; vb < VB; ++vb)
+        for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-                if (row < a.v) stg[p * STR + row] = acc[pb][vb][i] - lse[pb];
-              }
+          for (int q = 0; q < 4; ++q) {
+            const int row = rbase + vb * 32 + 8 * q;
+            if (vec) {
+              if (row < a.v)
+                *(f32x4_t*)(dst + row) = f32x4_t{acc[pb][vb][4 * q] - lse[pb], acc[pb][vb][4 * q + 1] - lse[pb],
+                                                 acc[pb][vb][4 * q + 2] - lse[pb], acc[pb][vb][4 * q + 3] - lse[pb]};
+            } else {
+#pragma unroll
+              for (int t = 0; t < 4; ++t)
+                if (row + t < a.v) dst[row + t] = acc[pb][vb][4 * q + t] - lse[pb];
+            }
           }
-        }
-        __syncthreads();
-        for (int k = wave; k < NSLOT; k += TL::NW) {
-          const int b = b0 + c0 + k;
-          if (b < a.B) {
-            float* dst = a.logphi + (((long long)b * a.n + wi) * a.r + wj) * a.v;
-            for (int row = lane; row < a.v; row += 64) dst[row] = stg[k * STR + row];
-          }
-        }
       }
-      __syncthreads();
     }
     if (a.zleaf == nullptr) return;
     // ---- which positions of this tile draw token wi from component wj?
