@@ -171,7 +171,12 @@ def main():
     achieved = flops / (k1_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "k_unembed (evidence pass of prefix marginals)",
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": achieved / PEAK_BF16_TFLOPS,
+                # L2 <-> fabric bytes per launch of this kernel on this workload, from two rocprofv3
+                # --pmc runs of this script (FETCH_SIZE 1,709,069 x 2 KiB, WRITE_SIZE 8,192 x 1 KiB,
+                # factors calibrated on a 1 GiB device copy); reads served by the Infinity Cache count
+                "traffic": 1709069 * 2048 + 8192 * 1024, "traffic_unit": "bytes/launch",
+                "algorithmic_bytes": (B * inp.d + inp.n * inp.r * inp.v * inp.d) * 2 + B * inp.n * inp.r * 4,
                 "avg_launch_ms": k1_ms, "flop_per_launch": flops}
 
     out = {
