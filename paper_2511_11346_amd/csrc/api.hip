@@ -321,7 +321,8 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
 // [M, M + r) sum-unit logits, then - only when the layers are computed from h - a gap up
 // to Mlay (a multiple of 64) and L*r*r layer logits; ldM pads the total to a multiple of 32.
 struct BwdPlan {
-  size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, phi, total;
+  size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, phi, partial, total;
+  int ksplit, kchunk;       // split of the dh contraction over K (few output tiles)
   bool keep_phi;            // probabilities kept by the forward pass (else the logits are recomputed)
   bool ctx;                 // layers computed from h, one set per position
   int Lst;                  // stored layers (1: one matrix shared by all steps)
@@ -368,6 +369,13 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
     q.adj = take(B * (n - 1) * r * 4);
   }
   if (keep_phi) q.phi = take((size_t)q.M * q.ldb * 4);
+  q.ksplit = gemm_ksplit(hd->B, hd->d, (int)q.ldM);
+  q.kchunk = (int)q.ldM;
+  if (q.ksplit > 1) {
+    q.kchunk = (int)(((q.ldM + q.ksplit - 1) / q.ksplit + 63) / 64 * 64);
+    q.ksplit = (int)((q.ldM + q.kchunk - 1) / q.kchunk);
+    q.partial = take((size_t)q.ksplit * B * hd->d * 4);
+  }
   q.total = off;
   return q;
 }
@@ -509,7 +517,9 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   m.A = ws + q.dL; m.lda = q.ldM; m.M = hd->B;                   // dh[b][k] = sum_m dL[b][m] WT[k][m]
   m.Bm = ws + q.WT; m.ldb = q.ldM; m.N = hd->d; m.K = (int)q.ldM;
   m.C = dh; m.ldc = hd->d; m.split = hd->B; m.n2 = 0; m.C2 = nullptr; m.split3 = 0x7fffffff; m.C3 = nullptr;
+  m.ksplit = q.ksplit; m.kchunk = q.kchunk; m.partial = q.ksplit > 1 ? (float*)(ws + q.partial) : nullptr;
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
+  m.ksplit = 1; m.partial = nullptr;
   m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)q.Mtot;            // dW[m][k] = sum_b dLT[m][b] hT[k][b]
   m.Bm = ws + q.hT; m.ldb = q.ldb; m.N = hd->d; m.K = (int)q.ldb;
   m.C = dW; m.ldc = hd->d;

@@ -115,30 +115,37 @@ void k_gemm_tn(const GemmArgs a) {
   const int nslab = (a.M + TL::TV - 1) / TL::TV;
   const int nbt = (a.N + TL::TP - 1) / TL::TP;
   int slab, bt;
-  tile_of_block(blockIdx.x, nbt, nslab, slab, bt);
+  const int tiles = nbt * nslab;
+  const int ks = blockIdx.x / tiles;                 // K split handled by this workgroup
+  tile_of_block(blockIdx.x - ks * tiles, nbt, nslab, slab, bt);
   const int b0 = bt * TL::TP;
   const int rows = min(TL::TV, a.M - slab * TL::TV);
+  const int k0 = ks * a.kchunk, klen = min(a.kchunk, a.K - k0);
   f32x16_t acc[PB][VB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>((const char*)a.A + (long long)slab * TL::TV * a.lda * ESZ, a.lda,
-                                          a.Bm, a.ldb, a.N, a.K, rows, 0, b0, smem, acc);
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>((const char*)a.A + ((long long)slab * TL::TV * a.lda + k0) * ESZ, a.lda,
+                                          (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0, b0,
+                                          smem, acc);
   const int rbase = wv * VB * 32 + 4 * lhalf;
+  // one destination row at a time (keeps the address arithmetic out of the 160 live accumulators)
 #pragma unroll
-  for (int pb = 0; pb < PB; ++pb) {
-    const int col = b0 + wb * PB * 32 + pb * 32 + l31;
-    if (col >= a.N) continue;
+  for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
+    for (int i = 0; i < 16; ++i) {
+      const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+      if (row >= rows) continue;
+      const long long gr = (long long)slab * TL::TV + row;
+      float* rp = nullptr;
+      if (a.ksplit > 1) rp = a.partial + ((long long)ks * a.M + gr) * a.ldc;
+      else if (gr < a.split) rp = a.C + gr * a.ldc;
+      else if (gr < a.split + a.n2) rp = a.C2 + (gr - a.split) * a.ldc;
+      else if (gr >= a.split3) rp = a.C3 + (gr - a.split3) * a.ldc;
+      if (rp == nullptr) continue;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-        if (row < rows) {
-          const long long gr = (long long)slab * TL::TV + row;
-          if (gr < a.split) a.C[gr * a.ldc + col] = acc[pb][vb][i];
-          else if (gr < a.split + a.n2) a.C2[(gr - a.split) * a.ldc + col] = acc[pb][vb][i];
-          else if (gr >= a.split3) a.C3[(gr - a.split3) * a.ldc + col] = acc[pb][vb][i];
-        }
+      for (int pb = 0; pb < PB; ++pb) {
+        const int col = b0 + wb * PB * 32 + pb * 32 + l31;
+        if (col < a.N) rp[col] = acc[pb][vb][i];
       }
-  }
+    }
 }
 
 template <int WV, int WB, int VB, int PB, bool BF16>
@@ -152,8 +159,35 @@ static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t st) {
     attr_done = true;
   }
   const int nslab = (a.M + TL::TV - 1) / TL::TV, nbt = (a.N + TL::TP - 1) / TL::TP;
-  hipLaunchKernelGGL(kern, dim3(nslab * nbt), dim3(TL::NT), TL::SMEM, st, a);
+  hipLaunchKernelGGL(kern, dim3(nslab * nbt * max(a.ksplit, 1)), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();
+}
+
+// C[i] = sum over the K splits of partial[ks][i], in the order ks = 0, 1, ...
+__global__ __launch_bounds__(256) void k_reduce_splits(const float* partial, long long count, int ksplit, float* C) {
+  const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= count) return;
+  f32x4_t s = *(const f32x4_t*)(partial + i);
+  for (int ks = 1; ks < ksplit; ++ks) {
+    const f32x4_t p = *(const f32x4_t*)(partial + (long long)ks * count + i);
+    s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
+  }
+  *(f32x4_t*)(C + i) = s;
+}
+
+int gemm_ksplit(int M, int N, int K) {
+  const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+  if (tiles >= 384) return 1;
+  const int cand[] = {1, 2, 3, 4, 6, 8, 12, 16};
+  int best = 1;
+  double best_cost = 1e30;
+  for (int ks : cand) {
+    if (ks > 1 && K / ks < 2048) break;
+    // rounds over the CUs, each 1/ks long, plus a little for writing and adding the partials
+    const double cost = (double)((tiles * ks + 255) / 256) / ks + 0.02 * ks;
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = ks; }
+  }
+  return best;
 }
 
 template <bool BF16>
@@ -166,13 +200,20 @@ static hipError_t launch_gemm_dt(const GemmArgs& a, hipStream_t st) {
     const double rounds = wgs >= 1024 ? wgs / 256.0 : (double)(long long)((wgs + 255) / 256);
     return rounds * rows * gain;
   };
-  if (cost(320, 0.93) < cost(256, 1.0)) return launch_gemm_cfg<2, 4, 5, 2, BF16>(a, st);
+  if (a.ksplit == 1 && cost(320, 0.93) < cost(256, 1.0)) return launch_gemm_cfg<2, 4, 5, 2, BF16>(a, st);
   return launch_gemm_cfg<2, 4, 4, 2, BF16>(a, st);
 }
 
-hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t st) {
-  if (a.M < 1 || a.N < 1) return hipSuccess;
-  return dtype == MTPC_BF16 ? launch_gemm_dt<true>(a, st) : launch_gemm_dt<false>(a, st);
+hipError_t launch_gemm_tn(const GemmArgs& a0, int dtype, hipStream_t st) {
+  if (a0.M < 1 || a0.N < 1) return hipSuccess;
+  GemmArgs a = a0;
+  if (a.ksplit <= 1 || a.partial == nullptr) { a.ksplit = 1; a.kchunk = a.K; }
+  const hipError_t e = dtype == MTPC_BF16 ? launch_gemm_dt<true>(a, st) : launch_gemm_dt<false>(a, st);
+  if (e != hipSuccess || a.ksplit == 1) return e;
+  const long long count = (long long)a.M * a.ldc;     // ldc a multiple of 4 (d is a multiple of 32)
+  hipLaunchKernelGGL(k_reduce_splits, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, st, a.partial, count,
+                     a.ksplit, a.C);
+  return hipGetLastError();
 }
 
 }  // namespace mtpc

@@ -173,8 +173,14 @@ struct GemmArgs {
   // [split3, M) -> C3; rows in between are computed and dropped
   int split; int n2; float* C2;
   int split3; float* C3;
+  // split over K (few output tiles, long K): ksplit > 1 workgroups per tile each take kchunk
+  // columns and write their partial tile to partial[ks][M][ldc]; a second kernel adds the
+  // partials in a fixed order into C (single output buffer only)
+  int ksplit; int kchunk; float* partial;
 };
 hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t st);
+// number of K splits that fills the 256 CUs best for an M x N output (1: none)
+int gemm_ksplit(int M, int N, int K);
 
 // dst[c][col0 + r] = src[r][c] for r < R, c < C; dst[c][col0 + r] = 0 for R <= r < Rpad.
 struct TransposeArgs {
