@@ -146,6 +146,23 @@ mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, in
                               uint64_t seed, uint32_t offset,
                               int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi);
 
+/* Greedy draft for greedy speculative decoding (Sec. 3.4): the top-down traversal
+ * of Alg. 1 with every draw replaced by the most likely outcome - each sum unit
+ * takes its largest weight, each selected input unit its most likely token (ties:
+ * the smallest index).  For the fully factorised head this is the exact mode of q;
+ * for the other circuits it is a heuristic draft, which the greedy verification
+ * corrects.  One draft per position: drafts [B][n]; latents, prefix_logq, logphi as
+ * for mtpc_*_sample with S = 1 (any of them may be NULL).  Workspace: as for
+ * MTPC_OP_SAMPLE with S = 1. */
+mtpc_status mtpc_ff_greedy_draft(const mtpc_head* head, int32_t* drafts, int32_t* latents,
+                                 float* prefix_logq, float* logphi);
+mtpc_status mtpc_cp_greedy_draft(const mtpc_head* head, int32_t* drafts, int32_t* latents,
+                                 float* prefix_logq, float* logphi);
+mtpc_status mtpc_hmm_greedy_draft(const mtpc_head* head, const mtpc_sumlayers* T, int32_t* drafts,
+                                  int32_t* latents, float* prefix_logq, float* logphi);
+mtpc_status mtpc_btree_greedy_draft(const mtpc_head* head, const mtpc_sumlayers* A, int32_t* drafts,
+                                    int32_t* latents, float* prefix_logq, float* logphi);
+
 /* Verification step of one speculative-decoding cycle (Alg. 2 from the
  * acceptance loop on; greedy variant of Sec. 3.4), one draft per position.
  * Inputs (device): logphi [B][n][r][v] as written by mtpc_*_sample for the same

@@ -106,3 +106,51 @@ def speculative_verify(family, logphi, logw, loglayers, drafts, p, u, mode="samp
         margin[b] = min(margin[b], mg)
         accepted[b], token[b] = s, tok
     return accepted, token, margin
+
+
+def greedy_draft(family, logphi, logw, loglayers):
+    """Draft for greedy speculative decoding (Sec. 3.4): the top-down traversal of Alg. 1
+    with every draw replaced by the most likely outcome (first index on ties) - each sum
+    unit takes its largest weight, each selected input unit its most likely token.
+    Returns drafts [B,n], latents [B,n_lat] and, per position, the smallest gap between
+    the two largest probabilities met at any of its decisions."""
+    B, n, r, v = logphi.shape
+    nl = oc.n_latents(family, n)
+    drafts = np.zeros((B, n), dtype=np.int32)
+    lat = np.zeros((B, nl), dtype=np.int32)
+    gap = np.full(B, np.inf)
+    if family == "hmm" and n > 1:
+        T = oc._layer_view(loglayers, n - 1, B)
+    if family == "btree" and n > 2:
+        A = oc._layer_view(loglayers, n - 2, B)
+
+    def pick(logp, b):
+        p = np.exp(np.asarray(logp, dtype=np.float64))
+        k = int(np.argmax(p))
+        if p.size > 1:
+            top = np.sort(p)[-2:]
+            gap[b] = min(gap[b], top[1] - top[0])
+        return k
+
+    for b in range(B):
+        leaf_state = [0] * n
+        if family == "cp":
+            lat[b, 0] = pick(logw[b], b)
+            leaf_state = [int(lat[b, 0])] * n
+        elif family == "hmm":
+            z = pick(logw[b], b)
+            lat[b, 0] = leaf_state[0] = z
+            for i in range(1, n):
+                z = pick(T[b if T.shape[0] > 1 else 0, i - 1][z], b)
+                lat[b, i] = leaf_state[i] = z
+        elif family == "btree":
+            zs = [0] * (n - 1)
+            zs[0] = pick(logw[b], b)
+            for m in range(1, n - 1):
+                zs[m] = pick(A[b if A.shape[0] > 1 else 0, m - 1][zs[(m - 1) // 2]], b)
+            lat[b] = zs
+            leaf_state = [zs[(n - 1 + i - 1) // 2] for i in range(n)]
+        for i in range(n):
+            drafts[b, i] = pick(logphi[b, i, leaf_state[i]], b)
+    return drafts, lat, gap
+

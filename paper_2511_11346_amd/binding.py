@@ -45,6 +45,7 @@ EXPORTS = [
     "mtpc_ff_marginals", "mtpc_cp_marginals", "mtpc_hmm_marginals", "mtpc_btree_marginals",
     "mtpc_ff_sample", "mtpc_cp_sample", "mtpc_hmm_sample", "mtpc_btree_sample",
     "mtpc_ff_verify", "mtpc_cp_verify", "mtpc_hmm_verify", "mtpc_btree_verify",
+    "mtpc_ff_greedy_draft", "mtpc_cp_greedy_draft", "mtpc_hmm_greedy_draft", "mtpc_btree_greedy_draft",
     "mtpc_ff_loss_backward", "mtpc_cp_loss_backward", "mtpc_hmm_loss_backward", "mtpc_btree_loss_backward",
     "mtpc_philox_uniforms", "mtpc_profile_unembed",
 ]
@@ -69,11 +70,13 @@ def lib() -> C.CDLL:
             getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, ip, C.c_int32, fp]
             getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
             getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
+            getattr(L, f"mtpc_{fam}_greedy_draft").argtypes = [hp, ip, ip, fp, fp]
         for fam in ("hmm", "btree"):
             getattr(L, f"mtpc_{fam}_loglik").argtypes = [hp, lp, ip, fp]
             getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, lp, ip, C.c_int32, fp]
             getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, lp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
             getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, lp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
+            getattr(L, f"mtpc_{fam}_greedy_draft").argtypes = [hp, lp, ip, ip, fp, fp]
         L.mtpc_ff_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp]
         L.mtpc_cp_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp, fp]
         L.mtpc_hmm_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp, fp]
@@ -247,6 +250,20 @@ class Head:
             args.append(out["dR"].data_ptr() if out.get("dR") is not None else None)
         _check(self._call("loss_backward", hd, *args))
         return out
+
+    def greedy_draft(self, want_latents: bool = True, want_prefix: bool = False,
+                     logphi: Optional[torch.Tensor] = None):
+        """The argmax traversal: returns (drafts [B,n] int32, latents [B,n_lat] or None, prefix_logq [B,n] or None)."""
+        dev = self.h.device
+        drafts = torch.empty(self.B, self.n, dtype=torch.int32, device=dev)
+        nl = n_latents(self.family, self.n)
+        lat = torch.empty(self.B, nl, dtype=torch.int32, device=dev) if want_latents else None
+        pl = torch.empty(self.B, self.n, dtype=torch.float32, device=dev) if want_prefix else None
+        hd = self._head(self.workspace_bytes(OP_SAMPLE, S=1))
+        _check(self._call("greedy_draft", hd, drafts.data_ptr(),
+                          lat.data_ptr() if lat is not None and lat.numel() > 0 else None,
+                          pl.data_ptr() if pl is not None else None, self._phi_ptr(logphi)))
+        return drafts, lat, pl
 
     def _phi_ptr(self, logphi):
         if logphi is None:

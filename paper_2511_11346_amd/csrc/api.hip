@@ -234,7 +234,7 @@ mtpc_status run_marginals(int family, const mtpc_head* hd, const mtpc_sumlayers*
 
 mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, int32_t S,
                        uint64_t seed, uint32_t offset, int32_t* drafts, int32_t* latents,
-                       float* prefix_logq, float* logphi) {
+                       float* prefix_logq, float* logphi, bool greedy = false) {
   if (!drafts) return MTPC_ERR_NULL;
   const bool want_prefix = prefix_logq != nullptr;
   Plan p;
@@ -252,7 +252,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   la.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
   la.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
   la.L = p.Lst; la.contextual = p.nb > 1;
-  la.seed_lo = seed_lo; la.seed_hi = seed_hi; la.offset = offset;
+  la.seed_lo = seed_lo; la.seed_hi = seed_hi; la.offset = offset; la.greedy = greedy;
   la.zleaf = (int*)(ws + p.zleaf);
   la.latents = latents ? latents : (int*)(ws + p.lat);
   HIP_TRY(launch_latents(la, st));
@@ -261,7 +261,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
   u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
   u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
-  u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset;
+  u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset; u.greedy = greedy;
   const bool gather = want_prefix && score_by_gather(hd, S);
   u.logphi = logphi ? logphi : (gather ? (float*)(ws + p.table) : nullptr);
   {
@@ -606,6 +606,23 @@ mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, in
                               uint32_t offset, int32_t* drafts, int32_t* latents, float* prefix_logq,
                               float* logphi) {
   return run_sample(MTPC_BTREE, head, A, S, seed, offset, drafts, latents, prefix_logq, logphi);
+}
+
+mtpc_status mtpc_ff_greedy_draft(const mtpc_head* head, int32_t* drafts, int32_t* latents, float* prefix_logq,
+                                 float* logphi) {
+  return run_sample(MTPC_FF, head, nullptr, 1, 0, 0, drafts, latents, prefix_logq, logphi, true);
+}
+mtpc_status mtpc_cp_greedy_draft(const mtpc_head* head, int32_t* drafts, int32_t* latents, float* prefix_logq,
+                                 float* logphi) {
+  return run_sample(MTPC_CP, head, nullptr, 1, 0, 0, drafts, latents, prefix_logq, logphi, true);
+}
+mtpc_status mtpc_hmm_greedy_draft(const mtpc_head* head, const mtpc_sumlayers* T, int32_t* drafts,
+                                  int32_t* latents, float* prefix_logq, float* logphi) {
+  return run_sample(MTPC_HMM, head, T, 1, 0, 0, drafts, latents, prefix_logq, logphi, true);
+}
+mtpc_status mtpc_btree_greedy_draft(const mtpc_head* head, const mtpc_sumlayers* A, int32_t* drafts,
+                                    int32_t* latents, float* prefix_logq, float* logphi) {
+  return run_sample(MTPC_BTREE, head, A, 1, 0, 0, drafts, latents, prefix_logq, logphi, true);
 }
 
 mtpc_status mtpc_ff_verify(const mtpc_head* head, const float* logphi, const int32_t* drafts,

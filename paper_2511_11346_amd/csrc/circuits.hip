@@ -737,6 +737,20 @@ __device__ __forceinline__ int wave_draw(float p0, float p1, int r, float u, int
   return m ? 63 - __clzll((long long)m) : 0;
 }
 
+// index of the largest of the r weights (lane holds units lane and lane + 64); ties: smallest index
+__device__ __forceinline__ int wave_argmax(float p0, float p1, int r, int lane) {
+  float best = lane < r ? p0 : -1.f;
+  int arg = lane;
+  if (lane + 64 < r && p1 > best) { best = p1; arg = lane + 64; }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const float ob = __shfl_xor(best, o);
+    const int oa = __shfl_xor(arg, o);
+    if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+  }
+  return arg;
+}
+
 __global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
   const int lane = threadIdx.x & 63;
   const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);     // draft index
@@ -757,11 +771,11 @@ __global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
   auto draw_row = [&](const float* row, int lat) {      // row of normalised linear weights
     const float p0 = lane < r ? row[lane] : 0.f;
     const float p1 = lane + 64 < r ? row[lane + 64] : 0.f;
-    return wave_draw(p0, p1, r, U(lat), lane);
+    return a.greedy ? wave_argmax(p0, p1, r, lane) : wave_draw(p0, p1, r, U(lat), lane);
   };
   const float* lw = a.logw + (long long)b * r;
-  const int z0 = wave_draw(lane < r ? expf(lw[lane]) : 0.f, lane + 64 < r ? expf(lw[lane + 64]) : 0.f, r,
-                           U(0), lane);
+  const float q0 = lane < r ? expf(lw[lane]) : 0.f, q1 = lane + 64 < r ? expf(lw[lane + 64]) : 0.f;
+  const int z0 = a.greedy ? wave_argmax(q0, q1, r, lane) : wave_draw(q0, q1, r, U(0), lane);
   if (a.family == MTPC_CP) {
     for (int i = lane; i < n; i += 64) zl[i] = z0;
     if (a.latents && lane == 0) a.latents[t] = z0;

@@ -28,6 +28,7 @@ struct UnembedArgs {
   int S;
   int* drafts;          // [B][S][n]
   uint32_t seed_lo, seed_hi, offset;
+  int greedy;           // 1: every draw is replaced by the most likely outcome (no random numbers)
   float* logphi;        // [B][n][r][v] normalised logits of every slab, or nullptr (sampling kernel only)
   float* phiT;          // [n*r*v][ld_phi] softmax probabilities, transposed, or nullptr (evidence kernel only)
   long long ld_phi;
@@ -95,6 +96,7 @@ struct LatentArgs {
   const float* layers;  // normalised linear, natural layout [nb][L][k][j]
   int L, contextual;
   uint32_t seed_lo, seed_hi, offset;
+  int greedy;           // 1: every sum unit takes its largest weight
   int* zleaf;           // [B][S][n] state that indexes leaf i
   int* latents;         // [B][S][n_lat] or nullptr
 };

@@ -179,6 +179,22 @@ void k_unembed(const UnembedArgs a) {
         for (int s = 0; s < a.S; ++s) {
           const long long di = ((long long)b * a.S + s) * a.n + wi;
           if (a.zleaf[di] != wj) continue;
+          if (a.greedy) {
+            // the most likely token of this input unit; ties: the smallest id
+            float best = -1.f;
+            int arg = 0;
+#pragma unroll
+            for (int q = 0; q < TL::VPL; ++q)
+              if (vals[q] > best) { best = vals[q]; arg = lane * TL::VPL + q; }
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) {
+              const float ob = __shfl_xor(best, o);
+              const int oa = __shfl_xor(arg, o);
+              if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+            }
+            if (lane == 0) a.drafts[di] = arg;
+            continue;
+          }
           const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)s,
                                          (uint32_t)wi);
           const float tgt = u * Z;

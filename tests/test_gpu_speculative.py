@@ -92,3 +92,28 @@ def test_verify_matches_oracle(family, dtype, B, d, n, r, v, ctx):
     assert np.array_equal(acc2.cpu().numpy()[safe], w_acc[safe])
     assert np.array_equal(tok2.cpu().numpy()[safe], w_tok[safe])
     assert safe.sum() >= B // 2
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r,v,ctx", CASES)
+def test_greedy_draft_matches_oracle(family, dtype, B, d, n, r, v, ctx):
+    """The argmax traversal (Sec. 3.4): bit-exact for every position none of whose decisions
+    has its two largest probabilities closer than 1e-6; its prefix scores to tolerance; and
+    drafting greedily against a verifier equal to the draft accepts everything."""
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=500 + n + r, h_scale=1.0,
+                         contextual=ctx)
+    head = make_head(inp)
+    logphi, logw, loglayers = oracle_params(inp)
+    want_d, want_l, gap = sp.greedy_draft(family, logphi, logw, loglayers)
+    gd, gl, gp = head.greedy_draft(want_prefix=True)
+    safe = gap >= 1e-6
+    assert np.array_equal(gd.cpu().numpy()[safe], want_d[safe])
+    if gl is not None and want_l.shape[1]:
+        assert np.array_equal(gl.cpu().numpy()[safe], want_l[safe])
+    P = oc.prefix_marginals_from(family, logphi, logw, loglayers, gd.cpu().numpy())
+    tol_check(gp.cpu().numpy(), P, dtype, "scores of the greedy draft")
+    onehot = torch.zeros(B, n + 1, v, device="cuda")
+    onehot[:, :n].scatter_(2, gd.long()[:, :, None], 1.0)
+    onehot[:, n, 0] = 1.0
+    acc, tok = head.verify(gd, onehot, mode="greedy")
+    assert torch.all(acc == n) and torch.all(tok == 0)
+    print(f"{family} {dtype}: {int((~safe).sum())} of {B} positions have a near-tie")

@@ -153,3 +153,51 @@ def test_greedy_mode_keeps_the_longest_argmax_prefix():
     acc, tok, _ = sp.speculative_verify("cp", logphi, logw, loglayers, drafts, p, np.zeros((B, n + 1)), mode="greedy")
     assert list(acc) == [4, 2, 0, 3]
     assert list(tok) == [best[0, 4], best[1, 2], best[2, 0], best[3, 3]]
+
+
+def test_greedy_draft_of_the_factorised_head_is_the_mode_of_the_joint():
+    n, v = 4, 3
+    raw, logphi, logw, loglayers = circuit("ff", n, 1, v, seed=31)
+    tab = bf.joint_table("ff", *tables("ff", *raw, 0))
+    drafts, lat, _ = sp.greedy_draft("ff", logphi, logw, loglayers)
+    assert tuple(drafts[0]) == np.unravel_index(np.argmax(tab), tab.shape) and lat.shape == (1, 0)
+
+
+@pytest.mark.parametrize("family,n", [("cp", 4), ("hmm", 4), ("btree", 4), ("btree", 8)])
+def test_greedy_draft_is_ancestral_sampling_with_the_uniforms_at_the_mode(family, n):
+    """Replacing a draw by its most likely outcome is the same as handing the sampler a
+    uniform that falls inside that outcome's CDF interval: build those uniforms by hand,
+    decision by decision, and let the (separately pinned) sampler reproduce the draft."""
+    r, v = 3, 4
+    raw, logphi, logw, loglayers = circuit(family, n, r, v, seed=17)
+    drafts, lat, _ = sp.greedy_draft(family, logphi, logw, loglayers)
+    nl = oc.n_latents(family, n)
+    u = np.zeros((1, 1, n + nl))
+
+    def mid(logp):                       # midpoint of the CDF interval of the arg max
+        p = np.exp(logp)
+        k = int(np.argmax(p))
+        c = np.concatenate([[0.0], np.cumsum(p)])
+        return k, 0.5 * (c[k] + c[k + 1])
+
+    lay = None if loglayers is None else np.asarray(loglayers)
+    if family == "cp":
+        z, u[0, 0, n] = mid(logw[0])
+        leaf = [z] * n
+    elif family == "hmm":
+        z, u[0, 0, n] = mid(logw[0])
+        leaf = [z]
+        for i in range(1, n):
+            z, u[0, 0, n + i] = mid(lay[i - 1][z])
+            leaf.append(z)
+    else:
+        zs = [0] * (n - 1)
+        zs[0], u[0, 0, n] = mid(logw[0])
+        for m in range(1, n - 1):
+            zs[m], u[0, 0, n + m] = mid(lay[m - 1][zs[(m - 1) // 2]])
+        leaf = [zs[(n - 1 + i - 1) // 2] for i in range(n)]
+    for i in range(n):
+        _, u[0, 0, i] = mid(logphi[0, i, leaf[i]])
+    d2, l2 = oc.sample_from(family, logphi, logw, loglayers, u)
+    assert np.array_equal(d2[0, 0], drafts[0]) and np.array_equal(l2[0, 0], lat[0])
+
