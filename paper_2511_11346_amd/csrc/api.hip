@@ -27,9 +27,13 @@ int n_layers(int family, int n) {
   return 0;
 }
 
-// Few drafts are scored from the table of normalised input units that the sampling pass
-// then writes (B*n*r*v floats), many by a second fused pass with the drafts as targets.
-bool score_by_gather(const mtpc_head* hd, int S) { return (long long)hd->B * S * 4 <= hd->v; }
+// Drafts are scored from the table of normalised input units that the sampling pass then
+// writes (B*n*r*v floats: one extra write of the tile instead of a second pass over W and h),
+// unless that table would exceed 8 GiB; then by a second fused pass with the drafts as targets.
+bool score_by_gather(const mtpc_head* hd, int S) {
+  (void)S;
+  return (unsigned long long)hd->B * hd->n * hd->r * hd->v * 4ull <= (8ull << 30);
+}
 
 struct Plan {           // byte offsets into the workspace
   size_t logw, lay_nat, lay_circ, e, zleaf, lat, logm, table, total;
