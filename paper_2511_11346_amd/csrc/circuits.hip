@@ -1,6 +1,6 @@
 // Small kernels of the MtPC head: sum-unit parameters, the circuit's sum/product
 // layers on the evidence e[rows][n][r], latent draws of the ancestral sampler,
-// latent marginals, and the gather-style evidence used to score a few drafts.
+// latent marginals, and the table lookup that scores drafts.
 // All of them touch O(B n r) or O(L r^2) data; none is a roofline concern.
 #include "mtpc_internal.h"
 

@@ -22,7 +22,6 @@ struct UnembedArgs {
   const int* targets;   // [B][T][n] or nullptr
   int T;
   float* e;             // [B*T][n][r]
-  float* lse;           // [B][n][r] or nullptr
   // sampling: token i of draft (b, s) is drawn from slab (i, zleaf[b][s][i])
   const int* zleaf;     // [B][S][n] or nullptr
   int S;

@@ -82,14 +82,6 @@ void k_unembed(const UnembedArgs a) {
       }
     }
   }
-  if (a.lse != nullptr && wv == 0 && lhalf == 0) {
-#pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      const int b = b0 + wb * PB * 32 + pb * 32 + l31;
-      if (b < a.B) a.lse[((long long)b * a.n + wi) * a.r + wj] = lse[pb];
-    }
-  }
-
   if constexpr (SAMPLE) {
     if (a.logphi != nullptr) {
       // table log phi[b][wi][wj][:] for the scoring and verification steps.  Registers

@@ -80,6 +80,19 @@ def test_argument_errors_are_reported_without_launching():
     assert L.mtpc_cp_verify(C.byref(_head()), out, tg, out, out, 5, 1, 0, tg, tg) == UNSUP
     assert L.mtpc_cp_verify(C.byref(_head(workspace_bytes=16)), None, tg, None, out, 1, 0, 0, tg, tg) == WS
     assert L.mtpc_hmm_verify(C.byref(_head()), None, out, tg, out, out, 0, 1, 0, tg, tg) == NULL
+    # greedy draft and training step
+    assert L.mtpc_cp_greedy_draft(C.byref(_head()), None, None, None, None) == NULL
+    assert L.mtpc_cp_greedy_draft(C.byref(_head(workspace_bytes=16)), tg, None, None, None) == WS
+    assert L.mtpc_cp_loss_backward(C.byref(_head()), tg, out, out, out, out, None) == NULL
+    assert L.mtpc_cp_loss_backward(C.byref(_head()), tg, None, out, out, out, out) == NULL
+    assert L.mtpc_cp_loss_backward(C.byref(_head(workspace_bytes=16)), tg, out, out, out, out, out) == WS
+    assert L.mtpc_ff_loss_backward(C.byref(_head(r=2)), tg, out, out, out, out) == SHAPE
+    assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(lay), tg, out, out, out, out, out, None, None) == NULL
+    per_pos = binding.mtpc_sumlayers(0x6000, 4, 12)
+    assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(per_pos), tg, out, out, out, out, out, out, None) == UNSUP
+    ctx = binding.mtpc_sumlayers(None, 0, 0, 0x7000, 4 * 64)
+    assert L.mtpc_btree_loss_backward(C.byref(_head()), C.byref(ctx), tg, out, out, out, out, out, out, out) == UNSUP
+    assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(ctx), tg, out, out, out, out, out, None, None) == NULL
 
 
 def test_workspace_query():
