@@ -101,3 +101,23 @@ def test_loss_and_gradients_match_oracle(family, dtype, B, d, n, r, v, seed):
     for name in ("dh", "dW", "dWsum", "dR"):
         if want[name] is not None:
             check_grad(name + " (recompute)", lean[name], want[name], dtype)
+
+
+def test_strided_hidden_states_and_preallocated_outputs():
+    """h rows may be a slice of a wider buffer (ld_h > d); outputs may be reused across calls."""
+    from paper_2511_11346_amd import Head
+    inp, targets, coef = make_case("cp", "bf16", 90, 64, 4, 8, 100, 23)
+    base = make_head(inp)
+    wide = torch.zeros(90, 192, dtype=torch.bfloat16, device="cuda")
+    wide[:, :64] = base.h
+    wide[:, 64:] = 7.0                                   # must never be read
+    head = Head("cp", wide[:, :64], base.W, base.Wsum)
+    tg, cf = torch.from_numpy(targets).cuda(), torch.from_numpy(coef.astype(np.float32)).cuda()
+    ref = base.loss_backward(tg, cf)
+    out = head.loss_backward(tg, cf)
+    for k in ("loss", "dh", "dW", "dWsum"):
+        assert torch.equal(out[k], ref[k]), k
+    out["dW"].fill_(3.0)
+    again = head.loss_backward(tg, cf, out=out)
+    assert torch.equal(again["dW"], ref["dW"])
+

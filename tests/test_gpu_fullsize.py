@@ -201,3 +201,30 @@ def test_config3_contextual_training_step_full_size():
         assert f2 <= 3e-3 and np.abs(got - want2[name]).max() <= 2e-2 * np.abs(want2[name]).max(), (name, f2)
         msg.append(f"{name} {f2:.1e}")
     print("relative Frobenius errors:", " ".join(msg))
+
+
+def test_llama_byte_training_step_fp32_split_k():
+    """fp32 training step at the second model shape (d = 3072, v = 268, r = 32, B = 2048): the dh
+    contraction has 96 output tiles and runs split over K; vocabulary rows 268..319 of the tile
+    are padding.  Sampled rows for dh and the loss, a sparse-coefficient run for dW and dWsum."""
+    inp = mi.config_llama_byte("cp")
+    B, n = inp.B, inp.n
+    head = make_head(inp)
+    coef = bw.loss_coefficients(0.9, np.ones((B, n), bool)).astype(np.float32)
+    tg = torch.from_numpy(inp.targets).cuda()
+    out = head.loss_backward(tg, torch.from_numpy(coef).cuda())
+    rows = sample_rows(B, k=6)
+    want = bw.loss_and_gradients("cp", inp.h[rows], inp.W, inp.Wsum, None, inp.targets[rows], coef[rows])
+    dh = out["dh"].cpu().numpy()[rows].astype(np.float64)
+    assert np.abs(dh - want["dh"]).max() <= 2e-5 * np.abs(want["dh"]).max()
+    assert np.all(np.abs(out["loss"].cpu().numpy()[rows] - want["loss"]) <= 1e-4 * np.maximum(1.0, np.abs(want["loss"])))
+    few = np.unique(np.concatenate([sample_rows(B, k=4, seed=2), [1023, 1024]]))
+    sparse = np.zeros_like(coef)
+    sparse[few] = coef[few] * 50.0
+    out2 = head.loss_backward(tg, torch.from_numpy(sparse).cuda(), out=out)
+    want2 = bw.loss_and_gradients("cp", inp.h[few], inp.W, inp.Wsum, None, inp.targets[few], sparse[few])
+    for name, tol in (("dW", 2e-5), ("dWsum", 1e-4)):
+        # the sum-unit gradient G_z - omega_z sum G is a difference of nearly equal fp32 terms
+        got = out2[name].cpu().numpy().astype(np.float64)
+        assert np.abs(got - want2[name]).max() <= tol * np.abs(want2[name]).max(), name
+    print("fp32 training step: dh rows, loss, dW within 2e-5 and dWsum within 1e-4 of the largest entry")
