@@ -1,0 +1,84 @@
+"""A seeded sweep over legal shapes (every family, both dtypes, windows from 1 to 64,
+1 to 128 units, ragged vocabularies and batches): every operation of the library against
+the oracle on each.  The shapes are drawn once from a fixed seed, so the sweep is the
+same on every run; the oracle's cost per case is bounded."""
+import numpy as np
+import pytest
+import torch
+
+import mtpc_inputs as mi
+from oracle import backward as bw
+from oracle import mtpc_oracle as oc
+from oracle import philox
+from oracle import speculative as sp
+
+from gpu_util import compare_drafts, make_head, synthetic_verifier, tol_check
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_cases(count=24, seed=20251127):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        family = ["ff", "cp", "hmm", "btree"][rng.integers(0, 4)]
+        n = int(rng.choice([2, 4, 8, 16, 32, 64] if family == "btree" else [1, 2, 3, 5, 8, 16, 33, 64]))
+        r = 1 if family == "ff" else int(rng.choice([1, 2, 3, 7, 8, 16, 31, 32, 64, 100, 128]))
+        v = int(rng.choice([1, 2, 5, 33, 64, 100, 129, 256, 257, 268, 319, 320]))
+        d = int(rng.choice([32, 64, 96, 160]))
+        B = int(rng.choice([1, 2, 31, 33, 64, 65, 130, 257]))
+        dtype = ["f32", "bf16"][rng.integers(0, 2)]
+        if n * r * v * B > 6_000_000 or n * r * r > 300_000:      # keep the oracle to seconds
+            continue
+        cases.append((family, dtype, B, d, n, r, v))
+    return cases
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r,v", draw_cases())
+def test_every_operation_on_a_drawn_shape(family, dtype, B, d, n, r, v):
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=n * 1000 + r * 7 + v, h_scale=1.0)
+    inp.targets[:] = np.random.default_rng(1).integers(0, v, size=inp.targets.shape)
+    head = make_head(inp)
+    layers = inp.layers if inp.layers is not None and inp.layers.size else None
+    logphi, logw, loglayers = oc._params(family, inp.h, inp.W, inp.Wsum, layers)
+    tg = torch.from_numpy(inp.targets).cuda()
+    # likelihoods and prefix marginals
+    want = oc.prefix_marginals_from(family, logphi, logw, loglayers, inp.targets)
+    tol_check(head.prefix_marginals(tg).cpu().numpy(), want, dtype, "prefix marginals")
+    tol_check(head.loglik(tg).cpu().numpy(), want[:, -1], dtype, "loglik")
+    # drafts, their scores, the table
+    S = 2
+    nl = oc.n_latents(family, n)
+    u = philox.uniforms(B, S, n + nl, seed=9)
+    od, ol, margin = oc.sample_from(family, logphi, logw, loglayers, u, with_margin=True)
+    table = torch.empty(B, n, r, v, dtype=torch.float32, device="cuda")
+    gd, gl, gp = head.sample(S, seed=9, want_prefix=True, logphi=table)
+    compare_drafts(gd, gl, od, ol, margin)
+    tol_check(table.cpu().numpy(), logphi, dtype, "table")
+    scores = oc.prefix_marginals_from(family, logphi, logw, loglayers, gd[:, 0].cpu().numpy())
+    tol_check(gp[:, 0].cpu().numpy(), scores, dtype, "draft scores")
+    # verification on oracle-built inputs
+    drafts = od[:, 0].astype(np.int32)
+    P = oc.prefix_marginals_from(family, logphi, logw, loglayers, drafts)
+    p = synthetic_verifier(inp, logphi, logw, loglayers, drafts, seed=4)
+    uv = philox.uniforms(B, 1, n + 1, 10, 1)[:, 0]
+    w_acc, w_tok, mg = sp.speculative_verify(family, logphi, logw, loglayers, drafts, p, uv)
+    acc, tok = head.verify(torch.from_numpy(drafts).cuda(), torch.from_numpy(p.astype(np.float32)).cuda(),
+                           prefix_logq=torch.from_numpy(P.astype(np.float32)).cuda(),
+                           logphi=torch.from_numpy(logphi.astype(np.float32)).cuda(), seed=10, offset=1)
+    safe = mg >= 2e-5
+    assert np.array_equal(acc.cpu().numpy()[safe], w_acc[safe]) and np.array_equal(tok.cpu().numpy()[safe], w_tok[safe])
+    # training step
+    coef = bw.loss_coefficients(0.9, np.random.default_rng(2).random((B, n)) > 0.1).astype(np.float32)
+    out = head.loss_backward(tg, torch.from_numpy(coef).cuda())
+    ref = bw.loss_and_gradients(family, inp.h, inp.W, inp.Wsum, layers, inp.targets, coef)
+    for name in ("dh", "dW", "dWsum", "dlayers"):
+        if ref[name] is None:
+            continue
+        got = out[name].cpu().numpy().astype(np.float64)
+        scale = max(np.abs(ref[name]).max(), 1e-30)
+        # fp32 paths: 1e-4 of the largest entry; the softmax-backward differences G - omega sum(G)
+        # behind dWsum and dlayers cancel after reverse chains of up to 446 steps (n = 64): 5e-4
+        lim = (5e-4 if name in ("dWsum", "dlayers") else 1e-4) if (dtype == "f32" or name == "dlayers") else 2e-2
+        # 1e-8: with a one-token vocabulary every gradient is exactly zero and only rounding is left
+        assert np.abs(got - ref[name]).max() <= lim * scale + 1e-8, (name, np.abs(got - ref[name]).max() / scale)
