@@ -47,6 +47,47 @@ __global__ __launch_bounds__(256) void k_transpose(const TransposeArgs a) {
   }
 }
 
+// The same with 16-byte accesses on both sides (VE = 16 / sizeof(T) elements per thread);
+// needs 16-byte aligned rows on both sides (checked by the launcher).
+template <typename T>
+__global__ __launch_bounds__(256) void k_transpose_vec(const TransposeArgs a) {
+  constexpr int VE = 16 / sizeof(T);
+  constexpr int TPR = 64 / VE;                       // threads per tile row
+  struct alignas(16) Vec { T v[VE]; };
+  __shared__ T tile[64][64 + VE + (sizeof(T) == 2 ? 2 : 1)];
+  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  const int tx = threadIdx.x % TPR, ty = threadIdx.x / TPR;
+  const T* src = (const T*)a.src;
+  T* dst = (T*)a.dst;
+  for (int rr = ty; rr < 64; rr += 256 / TPR) {
+    const int r = r0 + rr, c = c0 + tx * VE;
+    Vec x;
+#pragma unroll
+    for (int t = 0; t < VE; ++t) x.v[t] = 0;
+    if (r < a.R) {
+      if (c + VE <= a.C) x = *(const Vec*)(src + (long long)r * a.ld_src + c);
+      else
+        for (int t = 0; t < VE; ++t)
+          if (c + t < a.C) x.v[t] = src[(long long)r * a.ld_src + c + t];
+    }
+#pragma unroll
+    for (int t = 0; t < VE; ++t) tile[rr][tx * VE + t] = x.v[t];
+  }
+  __syncthreads();
+  for (int cc = ty; cc < 64; cc += 256 / TPR) {
+    const int c = c0 + cc, r = r0 + tx * VE;
+    if (c >= a.C) continue;
+    Vec x;
+#pragma unroll
+    for (int t = 0; t < VE; ++t) x.v[t] = tile[tx * VE + t][cc];
+    T* o = dst + (long long)c * a.ld_dst + a.col0 + r;
+    if (r + VE <= a.Rpad) *(Vec*)o = x;
+    else
+      for (int t = 0; t < VE; ++t)
+        if (r + t < a.Rpad) o[t] = x.v[t];
+  }
+}
+
 // 64 (m) x 128 (b) tiles: logit gradient from the stored probabilities, written in both
 // layouts (dLT along b straight away, dL along m after a transpose through LDS).  A thread
 // moves four neighbouring elements at a time (16-byte loads, 8- or 16-byte stores).
@@ -556,8 +597,16 @@ __global__ __launch_bounds__(256) void k_fill_zero(float* p, long long n) {
 hipError_t launch_transpose(const TransposeArgs& a, int dtype, hipStream_t st) {
   if (a.C < 1 || a.Rpad < 1) return hipSuccess;
   const dim3 grid((a.C + 63) / 64, (a.Rpad + 63) / 64);
-  if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_transpose<unsigned short>, grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL(k_transpose<float>, grid, dim3(256), 0, st, a);
+  const int esz = dtype == MTPC_BF16 ? 2 : 4, ve = 16 / esz;
+  const bool vec = a.ld_src % ve == 0 && a.ld_dst % ve == 0 && a.col0 % ve == 0 &&
+                   (((uintptr_t)a.src | (uintptr_t)a.dst) & 15) == 0;
+  if (vec) {
+    if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_transpose_vec<unsigned short>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(k_transpose_vec<float>, grid, dim3(256), 0, st, a);
+  } else {
+    if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_transpose<unsigned short>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(k_transpose<float>, grid, dim3(256), 0, st, a);
+  }
   return hipGetLastError();
 }
 
