@@ -325,7 +325,7 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
 // [M, M + r) sum-unit logits, then - only when the layers are computed from h - a gap up
 // to Mlay (a multiple of 64) and L*r*r layer logits; ldM pads the total to a multiple of 32.
 struct BwdPlan {
-  size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, phi, partial, total;
+  size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, phi, partial, dlog32, total;
   int ksplit, kchunk;       // split of the dh contraction over K (few output tiles)
   bool keep_phi;            // probabilities kept by the forward pass (else the logits are recomputed)
   bool ctx;                 // layers computed from h, one set per position
@@ -371,6 +371,7 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
   if (family == MTPC_BTREE) {
     q.ct = take(B * q.steps * r * 4);
     q.adj = take(B * (n - 1) * r * 4);
+    if (q.ctx) q.dlog32 = take(B * (size_t)L * r * r * 4);
   }
   if (keep_phi) q.phi = take((size_t)q.M * q.ldb * 4);
   q.ksplit = gemm_ksplit(hd->B, hd->d, (int)q.ldM);
@@ -400,8 +401,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   if (L > 0) {
     if (ly->batch_stride != 0) return MTPC_ERR_UNSUPPORTED;       // layers given per position: no reverse pass
     if (ctx) {
-      // layers computed from h: HMM with one R (and bias) per step
-      if (family != MTPC_HMM) return MTPC_ERR_UNSUPPORTED;
+      // layers computed from h: one R (and bias) per step / inner node
       if (L > 1 && (ly->R_layer_stride != (long long)hd->r * hd->r * hd->d ||
                     (ly->logits && ly->layer_stride != (long long)hd->r * hd->r)))
         return MTPC_ERR_UNSUPPORTED;
@@ -461,6 +461,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     if (ctx) {
       c.contextual = 1;
       c.dlog = ws + q.dL + (size_t)q.Mlay * esz; c.ld_dlog = q.ldM; c.dlog_cols = (int)(q.ldM - q.Mlay);
+      if (family == MTPC_BTREE) c.dlog32 = (float*)(ws + q.dlog32);
     } else {
       c.pi = (float*)(ws + q.pi); c.gam = (float*)(ws + q.gam); c.G = (float*)(ws + q.G);
     }

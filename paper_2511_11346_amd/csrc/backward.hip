@@ -366,6 +366,7 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
 __global__ __launch_bounds__(256) void k_btree_bwd(const CircuitBwdArgs a, int nsteps_max) {
   extern __shared__ TreeStep bprog[];
   __shared__ float sX[4][128];
+  __shared__ float sPi[4][128];
   __shared__ int s_nsteps;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const long long row = (long long)blockIdx.x * 4 + wave;
@@ -400,6 +401,7 @@ __global__ __launch_bounds__(256) void k_btree_bwd(const CircuitBwdArgs a, int n
   const float* lw = a.logw + row * r;
   const float w0 = u0 ? lw[lane] : ninf, w1 = u1 ? lw[lane + 64] : ninf;
   const long long lstep = a.L > 1 ? (long long)r * r : 0;
+  const long long lrow = a.contextual ? row * a.L * r * r : 0;        // this position's own layers
   auto g_of = [&](int j) { return (j + 1 < n ? coef[j + 1] : 0.f) - coef[j]; };
   // value of an operand for the lane's two units; path values live in ct[t-1]
   auto operand = [&](int src, int t, float& x0, float& x1) {
@@ -434,7 +436,19 @@ __global__ __launch_bounds__(256) void k_btree_bwd(const CircuitBwdArgs a, int n
     if (u1) sh[lane + 64] = __expf(x1 - ms);
     __builtin_amdgcn_wave_barrier();
     float s0, s1;
-    wave_matvec(a.lay_tr + (st.m - 1) * lstep, sh, r, lane, s0, s1);       // sum_j A[k][j] xi[j] via A^T
+    if (!a.contextual) {
+      wave_matvec(a.lay_tr + (st.m - 1) * lstep, sh, r, lane, s0, s1);     // sum_j A[k][j] xi[j] via A^T
+    } else {
+      // this position's own layer, natural layout only: lanes run over j, one wave reduction per k
+      const float* A = a.lay_nat + lrow + (st.m - 1) * lstep;
+      const float xa = u0 ? sh[lane] : 0.f, xb = u1 ? sh[lane + 64] : 0.f;
+      s0 = s1 = 0.f;
+      for (int k = 0; k < r; ++k) {
+        const float v = wsum((u0 ? A[k * r + lane] * xa : 0.f) + (u1 ? A[k * r + lane + 64] * xb : 0.f));
+        if (k == lane) s0 = v;
+        if (k == lane + 64) s1 = v;
+      }
+    }
     __builtin_amdgcn_wave_barrier();
     if (u0) ct[(long long)t * r + lane] = ms + __logf(s0);
     if (u1) ct[(long long)t * r + lane + 64] = ms + __logf(s1);
@@ -482,7 +496,32 @@ __global__ __launch_bounds__(256) void k_btree_bwd(const CircuitBwdArgs a, int n
       if (u1) sh[lane + 64] = d1;
       __builtin_amdgcn_wave_barrier();
       float s0, s1;
-      wave_matvec(a.lay_nat + (st.m - 1) * lstep, sh, r, lane, s0, s1);     // sum_k A[k][j] delta[k]
+      if (!a.contextual) {
+        wave_matvec(a.lay_nat + (st.m - 1) * lstep, sh, r, lane, s0, s1);   // sum_k A[k][j] delta[k]
+      } else {
+        // one pass over this position's layer gives both sum_k A[k][j] delta[k] and the softmax
+        // backward of its logits, delta_k A[k][j] (xi_j - (A xi)_k) with (A xi)_k = exp(c_k - max x),
+        // accumulated in fp32 per position (a layer is applied by several steps)
+        if (u0) sPi[wave][lane] = c0 == ninf ? 0.f : __expf(c0 - ms);
+        if (u1) sPi[wave][lane + 64] = c1 == ninf ? 0.f : __expf(c1 - ms);
+        __builtin_amdgcn_wave_barrier();
+        const float* A = a.lay_nat + lrow + (st.m - 1) * lstep;
+        float* dl = a.dlog32 + row * (long long)a.L * r * r + (long long)(st.m - 1) * r * r;
+        s0 = s1 = 0.f;
+        for (int k = 0; k < r; ++k) {
+          const float dk = sh[k], sk = sPi[wave][k];
+          if (u0) {
+            const float w = A[k * r + lane];
+            s0 = fmaf(w, dk, s0);
+            dl[k * r + lane] += dk * w * (xi0 - sk);
+          }
+          if (u1) {
+            const float w = A[k * r + lane + 64];
+            s1 = fmaf(w, dk, s1);
+            dl[k * r + lane + 64] += dk * w * (xi1 - sk);
+          }
+        }
+      }
       __builtin_amdgcn_wave_barrier();
       xb0 = xi0 * s0; xb1 = xi1 * s1;
       if (a.pi != nullptr) {
@@ -587,6 +626,18 @@ __global__ __launch_bounds__(256) void k_colsum(const T* src, long long ld, int 
     atomicAdd(out + c, (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]));
 }
 
+// dst[b][c] (dtype of h, row stride ld) = src[b][c] for c < cols, 0 for cols <= c < cols_pad
+template <typename T>
+__global__ __launch_bounds__(256) void k_convert_block(const float* src, int rows, int cols, int cols_pad, T* dst,
+                                                       long long ld) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (long long)rows * cols_pad) return;
+  const long long b = t / cols_pad;
+  const int c = (int)(t - b * cols_pad);
+  const float v = c < cols ? src[b * cols + c] : 0.f;
+  if constexpr (sizeof(T) == 2) dst[b * ld + c] = to_bf16_rne(v); else dst[b * ld + c] = v;
+}
+
 __global__ __launch_bounds__(256) void k_fill_zero(float* p, long long n) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0.f;
@@ -629,6 +680,10 @@ hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
     const long long cnt = (long long)a.L * r * r;
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.dlayers, cnt);
   }
+  if (ctx && tree) {                               // per-position fp32 accumulators of the tree
+    const long long cnt = (long long)a.rows * a.L * r * r;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.dlog32, cnt);
+  }
   if (layers) {
     const long long cnt = (long long)a.L * r * r;
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.G, cnt);
@@ -646,6 +701,15 @@ hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
     else hipLaunchKernelGGL(k_layer_outer<64>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
     const int nrows = a.L * r;
     hipLaunchKernelGGL(k_layer_finish, dim3((nrows + 3) / 4), dim3(256), 0, st, a.G, a.lay_nat, nrows, r, a.dlayers);
+  }
+  if (ctx && tree) {
+    const int cols = a.L * r * r;
+    const long long cnt = (long long)a.rows * a.dlog_cols;
+    const dim3 g((unsigned)((cnt + 255) / 256));
+    if (a.bf16) hipLaunchKernelGGL(k_convert_block<unsigned short>, g, dim3(256), 0, st, a.dlog32, a.rows, cols,
+                                   a.dlog_cols, (unsigned short*)a.dlog, a.ld_dlog);
+    else hipLaunchKernelGGL(k_convert_block<float>, g, dim3(256), 0, st, a.dlog32, a.rows, cols, a.dlog_cols,
+                            (float*)a.dlog, a.ld_dlog);
   }
   if (ctx && a.dlayers != nullptr) {
     const int cols = a.L * r * r;

@@ -91,7 +91,8 @@ def test_argument_errors_are_reported_without_launching():
     per_pos = binding.mtpc_sumlayers(0x6000, 4, 12)
     assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(per_pos), tg, out, out, out, out, out, out, None) == UNSUP
     ctx = binding.mtpc_sumlayers(None, 0, 0, 0x7000, 4 * 64)
-    assert L.mtpc_btree_loss_backward(C.byref(_head()), C.byref(ctx), tg, out, out, out, out, out, out, out) == UNSUP
+    shared_R = binding.mtpc_sumlayers(None, 0, 0, 0x7000, 0)
+    assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(shared_R), tg, out, out, out, out, out, out, out) == UNSUP
     assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(ctx), tg, out, out, out, out, out, None, None) == NULL
 
 

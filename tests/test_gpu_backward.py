@@ -69,6 +69,9 @@ CASES = [
     ("hmm-ctx", "f32", 70, 64, 4, 5, 33, 17),
     ("hmm-ctx", "bf16", 200, 128, 8, 16, 320, 18),
     ("hmm-ctx", "bf16", 37, 64, 3, 128, 40, 19),
+    ("btree-ctx", "f32", 70, 64, 4, 5, 33, 20),
+    ("btree-ctx", "bf16", 150, 128, 8, 16, 320, 21),
+    ("btree-ctx", "bf16", 20, 64, 16, 128, 24, 22),
 ]
 
 
