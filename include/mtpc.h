@@ -219,12 +219,13 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
  * gradient).
  * dlayers has the shape of the stored layer logits ([n-1][r][r], or [1][r][r] for a
  * shared matrix, whose gradient is the sum over the steps).
- * Layers computed from h (mtpc_sumlayers.R non-NULL, with one R and, if given, one bias
- * per step / inner node): dR [L][r][r][d] receives the gradient w.r.t. R, dlayers the one
- * w.r.t. the bias (may be NULL when there is no bias), and dh includes the path
- * through the layers; otherwise dR is ignored and may be NULL.
- * Not available (MTPC_ERR_UNSUPPORTED): layers given per position (batch_stride),
- * an R or bias shared by several steps. */
+ * Layers given per position (batch_stride != 0; dense [B][L or 1][r][r]): dlayers has
+ * that shape too, the gradient w.r.t. each position's own logits.
+ * Layers computed from h (mtpc_sumlayers.R non-NULL; R and bias either both one per
+ * step / inner node, contiguous, or both shared by all of them): dR [L or 1][r][r][d]
+ * receives the gradient w.r.t. R, dlayers the one w.r.t. the bias (may be NULL when
+ * there is no bias), and dh includes the path through the layers; otherwise dR is
+ * ignored and may be NULL.  Other stride combinations: MTPC_ERR_UNSUPPORTED. */
 mtpc_status mtpc_ff_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
                                   float* loss, float* dh, float* dW);
 mtpc_status mtpc_cp_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,

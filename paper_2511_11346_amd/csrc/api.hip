@@ -329,6 +329,7 @@ struct BwdPlan {
   int ksplit, kchunk;       // split of the dh contraction over K (few output tiles)
   bool keep_phi;            // probabilities kept by the forward pass (else the logits are recomputed)
   bool ctx;                 // layers computed from h, one set per position
+  bool perpos;              // layer logits given per position by the caller
   int Lst;                  // stored layers (1: one matrix shared by all steps)
   int steps;                // reverse-pass steps with a layer (HMM: n-1; tree: program length)
   long long M, Mx, Mlay, Mtot, ldM, ldb;
@@ -341,11 +342,13 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
   const size_t B = hd->B, n = hd->n, r = hd->r;
   const int L = n_layers(family, hd->n);
   q.ctx = L > 0 && ly && ly->R != nullptr;
-  q.Lst = (L > 0 && ly && !q.ctx && ly->layer_stride == 0) ? 1 : L;
+  q.perpos = L > 0 && ly && !q.ctx && ly->batch_stride != 0;
+  if (q.ctx) q.Lst = (ly->R_layer_stride == 0 && (!ly->logits || ly->layer_stride == 0)) ? 1 : L;
+  else q.Lst = (L > 0 && ly && ly->layer_stride == 0) ? 1 : L;
   q.M = (long long)hd->n * hd->r * hd->v;
   q.Mx = q.M + (family == MTPC_FF ? 0 : hd->r);      // the sum-unit rows ride along in both contractions
   q.Mlay = q.ctx ? (q.Mx + 63) / 64 * 64 : q.Mx;
-  q.Mtot = q.ctx ? q.Mlay + (long long)L * hd->r * hd->r : q.Mx;
+  q.Mtot = q.ctx ? q.Mlay + (long long)q.Lst * hd->r * hd->r : q.Mx;
   q.ldM = (q.Mtot + 31) / 32 * 32;
   q.ldb = ((long long)hd->B + 31) / 32 * 32;
   size_t off = 0;
@@ -359,9 +362,9 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
   q.hT = take((size_t)hd->d * q.ldb * esz);
   q.steps = family == MTPC_BTREE ? tree_program_steps(hd->n, 1) : L;
   if (L > 0) {
-    const size_t lay = (q.ctx ? B : 1) * (size_t)q.Lst * r * r * 4;
+    const size_t lay = ((q.ctx || q.perpos) ? B : 1) * (size_t)q.Lst * r * r * 4;
     q.lay_nat = take(lay);
-    if (!q.ctx) {
+    if (!q.ctx && !q.perpos) {
       q.lay_tr = take(lay);
       q.pi = take(B * q.steps * r * 4);
       q.gam = take(B * q.steps * r * 4);
@@ -371,8 +374,9 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
   if (family == MTPC_BTREE) {
     q.ct = take(B * q.steps * r * 4);
     q.adj = take(B * (n - 1) * r * 4);
-    if (q.ctx) q.dlog32 = take(B * (size_t)L * r * r * 4);
   }
+  // fp32 accumulation of per-position layer-logit gradients: the tree, or one R for all steps
+  if (q.ctx && (family == MTPC_BTREE || (q.Lst == 1 && L > 1))) q.dlog32 = take(B * (size_t)q.Lst * r * r * 4);
   if (keep_phi) q.phi = take((size_t)q.M * q.ldb * 4);
   q.ksplit = gemm_ksplit(hd->B, hd->d, (int)q.ldM);
   q.kchunk = (int)q.ldM;
@@ -399,15 +403,23 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   const int L = n_layers(family, hd->n);
   const bool ctx = L > 0 && ly->R != nullptr;
   if (L > 0) {
-    if (ly->batch_stride != 0) return MTPC_ERR_UNSUPPORTED;       // layers given per position: no reverse pass
     if (ctx) {
-      // layers computed from h: one R (and bias) per step / inner node
-      if (L > 1 && (ly->R_layer_stride != (long long)hd->r * hd->r * hd->d ||
-                    (ly->logits && ly->layer_stride != (long long)hd->r * hd->r)))
-        return MTPC_ERR_UNSUPPORTED;
+      // layers computed from h: R and bias either both one per step / inner node (contiguous)
+      // or both shared by all of them
+      const long long rr = (long long)hd->r * hd->r;
+      const bool per_layer = ly->R_layer_stride == rr * hd->d && (!ly->logits || ly->layer_stride == rr);
+      const bool shared = ly->R_layer_stride == 0 && (!ly->logits || ly->layer_stride == 0);
+      if (L > 1 && !per_layer && !shared) return MTPC_ERR_UNSUPPORTED;
+      if (ly->batch_stride != 0) return MTPC_ERR_SHAPE;
       if (!dR || (ly->logits && !dlayers)) return MTPC_ERR_NULL;
-    } else if (!dlayers) {
-      return MTPC_ERR_NULL;
+    } else {
+      if (!dlayers) return MTPC_ERR_NULL;
+      // per position: dense [B][Lst][r][r] logits only
+      if (ly->batch_stride != 0) {
+        const long long rr = (long long)hd->r * hd->r;
+        const long long per = (ly->layer_stride == 0 ? 1 : L) * rr;
+        if (ly->batch_stride != per || (ly->layer_stride != 0 && ly->layer_stride != rr)) return MTPC_ERR_UNSUPPORTED;
+      }
     }
   }
   // with the larger workspace the forward pass keeps its probabilities (n*r*v*B fp32) and the
@@ -433,6 +445,9 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     cl.B = hd->B; cl.d = hd->d; cl.r = hd->r; cl.L = q.Lst;
     cl.out_nat = (float*)(ws + q.lay_nat); cl.out_tr = nullptr;
     HIP_TRY(launch_ctx_layers(cl, hd->dtype, st));
+  } else if (q.perpos) {
+    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, hd->B, q.Lst, hd->r, 0,
+                                    (float*)(ws + q.lay_nat), st));
   } else if (L > 0) {
     HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, q.Lst, hd->r, 0,
                                     (float*)(ws + q.lay_nat), st));
@@ -455,13 +470,17 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   c.dslT = family == MTPC_FF ? nullptr : (void*)(ws + q.dLT + (size_t)q.M * q.ldb * esz);
   c.ldb = q.ldb; c.bf16 = hd->dtype == MTPC_BF16; c.loss = loss;
   if (L > 0) {
-    c.lay_nat = (const float*)(ws + q.lay_nat); c.lay_tr = ctx ? nullptr : (const float*)(ws + q.lay_tr);
+    c.lay_nat = (const float*)(ws + q.lay_nat);
+    c.lay_tr = (ctx || q.perpos) ? nullptr : (const float*)(ws + q.lay_tr);
     c.L = q.Lst;
     c.dlayers = dlayers;
     if (ctx) {
       c.contextual = 1;
       c.dlog = ws + q.dL + (size_t)q.Mlay * esz; c.ld_dlog = q.ldM; c.dlog_cols = (int)(q.ldM - q.Mlay);
-      if (family == MTPC_BTREE) c.dlog32 = (float*)(ws + q.dlog32);
+      if (q.dlog32) c.dlog32 = (float*)(ws + q.dlog32);
+    } else if (q.perpos) {
+      // the caller's [B][Lst][r][r] gradient buffer is the accumulator itself
+      c.contextual = 1; c.dlog = nullptr; c.dlog32 = dlayers; c.dlayers = nullptr;
     } else {
       c.pi = (float*)(ws + q.pi); c.gam = (float*)(ws + q.gam); c.G = (float*)(ws + q.G);
     }
@@ -509,7 +528,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     HIP_TRY(launch_transpose(t, hd->dtype, st));
   }
   if (ctx) {
-    t.src = ly->R; t.ld_src = hd->d; t.R = (int)(L * rr); t.C = hd->d;
+    t.src = ly->R; t.ld_src = hd->d; t.R = (int)(q.Lst * rr); t.C = hd->d;
     t.col0 = q.Mlay; t.Rpad = (int)(q.ldM - q.Mlay);
     HIP_TRY(launch_transpose(t, hd->dtype, st));
   }

@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
         if (u1) sh[lane + 64] = gm1;
         __builtin_amdgcn_wave_barrier();
         float c0, c1;
-        if (a.dlog == nullptr) {
+        if (!a.contextual) {
           wave_matvec(lay_tr + j * lstep, sh, r, lane, c0, c1);            // (T_j gam)[z] via T_j^T
         } else {
           // this position's own transition matrix (natural layout only): lanes run over z',
@@ -306,7 +306,10 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
           if (u1) sPi[wave][lane + 64] = pi1;
           __builtin_amdgcn_wave_barrier();
           const float* Tj = lay_nat + j * lstep;
+          // one matrix per step: written once, in the dtype of h, straight into the logit-gradient
+          // block; a matrix shared by the steps (or a caller's per-position buffer): fp32 accumulation
           const long long o = row * a.ld_dlog + (long long)j * r * r;
+          float* acc32 = a.dlog32 ? a.dlog32 + row * (long long)a.L * r * r + j * lstep : nullptr;
           for (int z = 0; z < r; ++z) {
             const float t0 = u0 ? Tj[z * r + lane] : 0.f, t1 = u1 ? Tj[z * r + lane + 64] : 0.f;
             const float cz = wsum(t0 * gm0 + t1 * gm1);
@@ -314,12 +317,14 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
             if (lane == 0) sC[wave][z] = cz;
             if (u0) {
               const float val = pz * t0 * (gm0 - cz);
-              if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane] = to_bf16_rne(val);
+              if (acc32) acc32[z * r + lane] += val;
+              else if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane] = to_bf16_rne(val);
               else ((float*)a.dlog)[o + z * r + lane] = val;
             }
             if (u1) {
               const float val = pz * t1 * (gm1 - cz);
-              if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane + 64] = to_bf16_rne(val);
+              if (acc32) acc32[z * r + lane + 64] += val;
+              else if (a.bf16) ((unsigned short*)a.dlog)[o + z * r + lane + 64] = to_bf16_rne(val);
               else ((float*)a.dlog)[o + z * r + lane + 64] = val;
             }
           }
@@ -343,7 +348,7 @@ __global__ __launch_bounds__(256) void k_circuit_bwd(const CircuitBwdArgs a) {
       if (u0) Ge[j * r + lane] = n0;
       if (u1) Ge[j * r + lane + 64] = n1;
     }
-    if (a.dlog != nullptr)                          // padding columns of the block
+    if (a.dlog != nullptr && a.dlog32 == nullptr)   // padding columns of the block
       for (int c = (n - 1) * r * r + lane; c < a.dlog_cols; c += 64) {
         if (a.bf16) ((unsigned short*)a.dlog)[row * a.ld_dlog + c] = 0;
         else ((float*)a.dlog)[row * a.ld_dlog + c] = 0.f;
@@ -506,7 +511,7 @@ __global__ __launch_bounds__(256) void k_btree_bwd(const CircuitBwdArgs a, int n
         if (u1) sPi[wave][lane + 64] = c1 == ninf ? 0.f : __expf(c1 - ms);
         __builtin_amdgcn_wave_barrier();
         const float* A = a.lay_nat + lrow + (st.m - 1) * lstep;
-        float* dl = a.dlog32 + row * (long long)a.L * r * r + (long long)(st.m - 1) * r * r;
+        float* dl = a.dlog32 + row * (long long)a.L * r * r + (st.m - 1) * lstep;
         s0 = s1 = 0.f;
         for (int k = 0; k < r; ++k) {
           const float dk = sh[k], sk = sPi[wave][k];
@@ -674,13 +679,13 @@ hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
   const bool tree = a.family == MTPC_BTREE;
   const int T = tree ? tree_program_steps(a.n, 1) : a.n - 1;
   const size_t prog_bytes = tree ? (size_t)T * sizeof(TreeStep) : 0;
-  const bool ctx = a.contextual && a.dlog != nullptr;
-  const bool layers = !ctx && a.dlayers != nullptr && ((a.family == MTPC_HMM && a.n > 1) || (tree && a.n > 2));
+  const bool ctx = a.contextual && a.dlog != nullptr;        // layers computed from h (R): bias gradient = column sums
+  const bool layers = !a.contextual && a.dlayers != nullptr && ((a.family == MTPC_HMM && a.n > 1) || (tree && a.n > 2));
   if (ctx && a.dlayers != nullptr) {               // bias gradient = column sums of the logit gradients
     const long long cnt = (long long)a.L * r * r;
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.dlayers, cnt);
   }
-  if (ctx && tree) {                               // per-position fp32 accumulators of the tree
+  if (a.contextual && a.dlog32 != nullptr) {       // per-position fp32 accumulators
     const long long cnt = (long long)a.rows * a.L * r * r;
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.dlog32, cnt);
   }
@@ -702,7 +707,7 @@ hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
     const int nrows = a.L * r;
     hipLaunchKernelGGL(k_layer_finish, dim3((nrows + 3) / 4), dim3(256), 0, st, a.G, a.lay_nat, nrows, r, a.dlayers);
   }
-  if (ctx && tree) {
+  if (ctx && a.dlog32 != nullptr) {
     const int cols = a.L * r * r;
     const long long cnt = (long long)a.rows * a.dlog_cols;
     const dim3 g((unsigned)((cnt + 255) / 256));

@@ -209,7 +209,8 @@ struct CircuitBwdArgs {
   // dtype of h (dlog_cols columns, zero beyond L*r*r); dlayers then receives the column sums
   int contextual;
   void* dlog; long long ld_dlog; int dlog_cols;
-  float* dlog32;         // binary tree only: fp32 accumulators [rows][L*r*r], converted into dlog at the end
+  float* dlog32;         // fp32 accumulators [rows][L*r*r] (tree; a matrix shared by all steps; a caller's
+                         // per-position gradient buffer), converted into dlog at the end when dlog is set
   float* ct;             // binary tree: scratch [rows][steps][r], output of every program step
   float* adj;            // binary tree: scratch [rows][n-1][r], adjoints of the node values
   float* Ge;             // [rows][n][r]

@@ -88,11 +88,11 @@ def test_argument_errors_are_reported_without_launching():
     assert L.mtpc_cp_loss_backward(C.byref(_head(workspace_bytes=16)), tg, out, out, out, out, out) == WS
     assert L.mtpc_ff_loss_backward(C.byref(_head(r=2)), tg, out, out, out, out) == SHAPE
     assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(lay), tg, out, out, out, out, out, None, None) == NULL
-    per_pos = binding.mtpc_sumlayers(0x6000, 4, 12)
-    assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(per_pos), tg, out, out, out, out, out, out, None) == UNSUP
+    gappy = binding.mtpc_sumlayers(0x6000, 4, 13)         # per-position logits that are not dense
+    assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(gappy), tg, out, out, out, out, out, out, None) == UNSUP
     ctx = binding.mtpc_sumlayers(None, 0, 0, 0x7000, 4 * 64)
-    shared_R = binding.mtpc_sumlayers(None, 0, 0, 0x7000, 0)
-    assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(shared_R), tg, out, out, out, out, out, out, out) == UNSUP
+    mixed = binding.mtpc_sumlayers(0x6000, 0, 0, 0x7000, 4 * 64)   # one R per step but a shared bias
+    assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(mixed), tg, out, out, out, out, out, out, out) == UNSUP
     assert L.mtpc_hmm_loss_backward(C.byref(_head()), C.byref(ctx), tg, out, out, out, out, out, None, None) == NULL
 
 

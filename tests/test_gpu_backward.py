@@ -37,10 +37,13 @@ def check_grad(name, got, want, dtype):
 
 def make_case(family, dtype, B, d, n, r, v, seed):
     shared = family.endswith("-shared")                          # one transition matrix for all steps
-    ctx = family.endswith("-ctx")                                # transition logits R h + bias (Sec. 3.3)
+    ctx = "-ctx" in family                                       # transition logits R h + bias (Sec. 3.3)
+    perpos = "-perpos" in family                                 # logits of every position supplied by the caller
     family = family.split("-")[0]
     inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=seed, h_scale=1.0,
                          layer_count=1 if shared else None, contextual=ctx)
+    if perpos:
+        inp.layers = np.random.default_rng(seed + 7).standard_normal((B,) + inp.layers.shape).astype(np.float32)
     rng = np.random.default_rng(seed + 1)
     targets = inp.targets.copy()
     targets[rng.random(targets.shape) < 0.05] = -1               # a few summed-out variables
@@ -72,6 +75,13 @@ CASES = [
     ("btree-ctx", "f32", 70, 64, 4, 5, 33, 20),
     ("btree-ctx", "bf16", 150, 128, 8, 16, 320, 21),
     ("btree-ctx", "bf16", 20, 64, 16, 128, 24, 22),
+    # one R (and bias) shared by all steps / inner nodes
+    ("hmm-ctx-shared", "f32", 60, 64, 5, 8, 33, 24),
+    ("btree-ctx-shared", "bf16", 90, 64, 8, 16, 100, 25),
+    # layer logits given per position by the caller: the gradient has their shape
+    ("hmm-perpos", "f32", 50, 64, 4, 6, 33, 26),
+    ("btree-perpos", "bf16", 70, 64, 8, 16, 64, 27),
+    ("hmm-perpos-shared", "f32", 33, 32, 6, 5, 20, 28),
 ]
 
 
