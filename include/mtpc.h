@@ -49,8 +49,9 @@ typedef enum {
 typedef enum { MTPC_F32 = 0, MTPC_BF16 = 1 } mtpc_dtype;
 typedef enum { MTPC_FF = 0, MTPC_CP = 1, MTPC_HMM = 2, MTPC_BTREE = 3 } mtpc_family;
 typedef enum { MTPC_OP_LOGLIK = 0, MTPC_OP_MARGINALS = 1, MTPC_OP_SAMPLE = 2, MTPC_OP_VERIFY = 3,
-               MTPC_OP_BACKWARD = 4 } mtpc_op;
+               MTPC_OP_BACKWARD = 4, MTPC_OP_TABLE = 5 } mtpc_op;
 typedef enum { MTPC_MARG_PREFIX = 0, MTPC_MARG_UNIVARIATE = 1 } mtpc_marg_mode;
+typedef enum { MTPC_SCORE_JOINT = 0, MTPC_SCORE_PREFIX = 1 } mtpc_score_mode;
 typedef enum { MTPC_VERIFY_SAMPLING = 0, MTPC_VERIFY_GREEDY = 1 } mtpc_verify_mode;
 typedef enum { MTPC_BWD_KEEP_PROBS = 0, MTPC_BWD_RECOMPUTE = 1 } mtpc_bwd_mode;
 
@@ -93,7 +94,8 @@ typedef struct {
 const char* mtpc_status_string(mtpc_status s);
 
 /* Scratch needed by one call.  `layers` may be NULL (FF, CP).  `S` is the number
- * of drafts per position (sample) and is ignored otherwise; `mode` is the
+ * of drafts per position (sample) or of windows per position (MTPC_OP_TABLE) and is
+ * ignored otherwise; `mode` is the
  * mtpc_marg_mode for MTPC_OP_MARGINALS and the mtpc_bwd_mode for MTPC_OP_BACKWARD.
  * Returns 0 for invalid arguments. */
 size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
@@ -145,6 +147,28 @@ mtpc_status mtpc_hmm_sample(const mtpc_head* head, const mtpc_sumlayers* T, int3
 mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, int32_t S,
                               uint64_t seed, uint32_t offset,
                               int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi);
+
+/* Scores of arbitrary windows from the table of input units a sampling call left
+ * (same head, same h): the evidence of each token is read from logphi and the circuit
+ * is evaluated as in mtpc_*_loglik / MTPC_MARG_PREFIX (Eqs. FF / CP / HMM / BTree,
+ * Alg. 2 prefix marginals), without another pass over W.  Serves the scoring of
+ * several candidate windows per position, and - on a training-shaped batch - the
+ * likelihood of the targets next to the drafts of the same positions from ONE
+ * unembedding pass.
+ *   logphi [B][n][r][v] fp32 (read only), as written by mtpc_*_sample / *_greedy_draft
+ *   x      [B][T][n] int32 windows, -1 = summed out
+ *   mode   MTPC_SCORE_JOINT: out [B][T] log q(x); MTPC_SCORE_PREFIX: out [B][T][n]
+ * Workspace: mtpc_workspace_bytes(family, MTPC_OP_TABLE, head, layers, T, 0). */
+mtpc_status mtpc_ff_table_scores(const mtpc_head* head, const float* logphi, const int32_t* x,
+                                 int32_t T, int32_t mode, float* out);
+mtpc_status mtpc_cp_table_scores(const mtpc_head* head, const float* logphi, const int32_t* x,
+                                 int32_t T, int32_t mode, float* out);
+mtpc_status mtpc_hmm_table_scores(const mtpc_head* head, const mtpc_sumlayers* T_layers,
+                                  const float* logphi, const int32_t* x, int32_t T, int32_t mode,
+                                  float* out);
+mtpc_status mtpc_btree_table_scores(const mtpc_head* head, const mtpc_sumlayers* A,
+                                    const float* logphi, const int32_t* x, int32_t T, int32_t mode,
+                                    float* out);
 
 /* Greedy draft for greedy speculative decoding (Sec. 3.4): the top-down traversal
  * of Alg. 1 with every draw replaced by the most likely outcome - each sum unit

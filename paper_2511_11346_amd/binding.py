@@ -17,9 +17,10 @@ LIB_PATH = os.path.join(_HERE, "libmtpc.so")
 
 FF, CP, HMM, BTREE = 0, 1, 2, 3
 FAMILY = {"ff": FF, "cp": CP, "hmm": HMM, "btree": BTREE}
-OP_LOGLIK, OP_MARGINALS, OP_SAMPLE, OP_VERIFY, OP_BACKWARD = 0, 1, 2, 3, 4
+OP_LOGLIK, OP_MARGINALS, OP_SAMPLE, OP_VERIFY, OP_BACKWARD, OP_TABLE = 0, 1, 2, 3, 4, 5
 VERIFY_SAMPLING, VERIFY_GREEDY = 0, 1
 MARG_PREFIX, MARG_UNIVARIATE = 0, 1
+SCORE_JOINT, SCORE_PREFIX = 0, 1
 F32, BF16 = 0, 1
 
 
@@ -45,6 +46,7 @@ EXPORTS = [
     "mtpc_ff_marginals", "mtpc_cp_marginals", "mtpc_hmm_marginals", "mtpc_btree_marginals",
     "mtpc_ff_sample", "mtpc_cp_sample", "mtpc_hmm_sample", "mtpc_btree_sample",
     "mtpc_ff_verify", "mtpc_cp_verify", "mtpc_hmm_verify", "mtpc_btree_verify",
+    "mtpc_ff_table_scores", "mtpc_cp_table_scores", "mtpc_hmm_table_scores", "mtpc_btree_table_scores",
     "mtpc_ff_greedy_draft", "mtpc_cp_greedy_draft", "mtpc_hmm_greedy_draft", "mtpc_btree_greedy_draft",
     "mtpc_ff_loss_backward", "mtpc_cp_loss_backward", "mtpc_hmm_loss_backward", "mtpc_btree_loss_backward",
     "mtpc_philox_uniforms", "mtpc_profile_unembed",
@@ -71,12 +73,14 @@ def lib() -> C.CDLL:
             getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
             getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
             getattr(L, f"mtpc_{fam}_greedy_draft").argtypes = [hp, ip, ip, fp, fp]
+            getattr(L, f"mtpc_{fam}_table_scores").argtypes = [hp, fp, ip, C.c_int32, C.c_int32, fp]
         for fam in ("hmm", "btree"):
             getattr(L, f"mtpc_{fam}_loglik").argtypes = [hp, lp, ip, fp]
             getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, lp, ip, C.c_int32, fp]
             getattr(L, f"mtpc_{fam}_sample").argtypes = [hp, lp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
             getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, lp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
             getattr(L, f"mtpc_{fam}_greedy_draft").argtypes = [hp, lp, ip, ip, fp, fp]
+            getattr(L, f"mtpc_{fam}_table_scores").argtypes = [hp, lp, fp, ip, C.c_int32, C.c_int32, fp]
         L.mtpc_ff_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp]
         L.mtpc_cp_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp, fp]
         L.mtpc_hmm_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp, fp]
@@ -271,6 +275,26 @@ class Head:
         assert logphi.is_cuda and logphi.dtype == torch.float32 and logphi.is_contiguous()
         assert tuple(logphi.shape) == (self.B, self.n, self.r, self.v)
         return logphi.data_ptr()
+
+    def table_scores(self, logphi: torch.Tensor, x: torch.Tensor, prefix: bool = False,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Scores of windows x [B,T,n] (or [B,n]) int32 from the table logphi [B,n,r,v] a sample() call
+        left: log-likelihoods [B,T], or prefix marginals [B,T,n] with prefix=True."""
+        assert x.is_cuda and x.dtype == torch.int32 and x.is_contiguous()
+        squeeze = x.dim() == 2
+        xs = x.unsqueeze(1) if squeeze else x
+        assert xs.dim() == 3 and xs.shape[0] == self.B and xs.shape[2] == self.n
+        T = xs.shape[1]
+        shape = (self.B, T, self.n) if prefix else (self.B, T)
+        if out is None:
+            out = torch.empty(shape, dtype=torch.float32, device=self.h.device)
+        else:
+            assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == self.B * T * (self.n if prefix else 1)
+            out = out.view(shape)
+        hd = self._head(self.workspace_bytes(OP_TABLE, S=T))
+        _check(self._call("table_scores", hd, self._phi_ptr(logphi), xs.data_ptr(), T,
+                          SCORE_PREFIX if prefix else SCORE_JOINT, out.data_ptr()))
+        return out.squeeze(1) if squeeze else out
 
     def verify(self, drafts: torch.Tensor, p: torch.Tensor, prefix_logq: Optional[torch.Tensor] = None,
                logphi: Optional[torch.Tensor] = None, seed: int = 0, offset: int = 0, mode: str = "sampling"):

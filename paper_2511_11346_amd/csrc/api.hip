@@ -95,11 +95,12 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   const bool sample = op == MTPC_OP_SAMPLE;
   const bool uni = op == MTPC_OP_MARGINALS && mode == MTPC_MARG_UNIVARIATE;
   const bool verify = op == MTPC_OP_VERIFY;
+  const bool table_op = op == MTPC_OP_TABLE;       // S windows per position scored from a table
   const bool need_nat = L > 0 && (family == MTPC_HMM || sample || uni || verify);
   const bool need_tr = L > 0 && family == MTPC_BTREE && (!sample || want_prefix) && !uni;
   p.lay_nat = need_nat ? take(lay_bytes) : 0;
   p.lay_circ = need_tr ? take(lay_bytes) : p.lay_nat;
-  const size_t rows = sample ? B * (size_t)S : B;
+  const size_t rows = (sample || table_op) ? B * (size_t)S : B;
   p.e = (uni || verify || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
   // few drafts: they are scored from the table of input units the sampling pass leaves behind
   p.table = (sample && want_prefix && score_by_gather(hd, S)) ? take(B * n * r * (size_t)hd->v * 4) : 0;
@@ -128,7 +129,7 @@ mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayer
   if (st != MTPC_OK) return st;
   st = check_layers(family, hd, ly);
   if (st != MTPC_OK) return st;
-  if (op == MTPC_OP_SAMPLE && S < 1) return MTPC_ERR_SHAPE;
+  if ((op == MTPC_OP_SAMPLE || op == MTPC_OP_TABLE) && S < 1) return MTPC_ERR_SHAPE;
   plan = make_plan(family, op, hd, ly, S, mode, want_prefix);
   if (!hd->workspace) return MTPC_ERR_NULL;
   if (((uintptr_t)hd->workspace & 15) || hd->workspace_bytes < plan.total) return MTPC_ERR_WORKSPACE;
@@ -268,9 +269,23 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset; u.greedy = greedy;
   const bool gather = want_prefix && score_by_gather(hd, S);
   u.logphi = logphi ? logphi : (gather ? (float*)(ws + p.table) : nullptr);
+  // Training-sized batches that write the table anyway: the fused kernel only normalises
+  // and stores, and the draws read one table row each (the in-kernel draw stage costs more
+  // than that read once every workgroup of the grid has to run it).
+  const bool draw_from_table = u.logphi != nullptr && hd->B > 64;
+  if (draw_from_table) u.zleaf = nullptr;
   {
-    ProfScope prof(st);
-    HIP_TRY(launch_unembed(u, hd->dtype, st));
+    {
+      ProfScope prof(st);
+      HIP_TRY(launch_unembed(u, hd->dtype, st));
+    }
+    if (draw_from_table) {
+      DrawArgs dr{};
+      dr.B = hd->B; dr.S = S; dr.v = hd->v; dr.n = hd->n; dr.r = hd->r;
+      dr.logphi = u.logphi; dr.zleaf = la.zleaf; dr.drafts = drafts;
+      dr.seed_lo = seed_lo; dr.seed_hi = seed_hi; dr.offset = offset; dr.greedy = greedy;
+      HIP_TRY(launch_draw_table(dr, st));
+    }
     if (want_prefix && !gather) {
       UnembedArgs u2{};
       u2.h = hd->h; u2.ld_h = hd->ld_h; u2.W = hd->W;
@@ -288,6 +303,28 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     }
     HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * S, S, prefix_logq, 1), st));
   }
+  return MTPC_OK;
+}
+
+// log-likelihoods / prefix marginals of T windows per position from the table of input units
+// a sampling call left: params -> gather -> circuit, no pass over W
+mtpc_status run_table_scores(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const float* logphi,
+                             const int32_t* x, int32_t T, int32_t mode, float* out) {
+  if (!logphi || !x || !out) return MTPC_ERR_NULL;
+  if (mode != MTPC_SCORE_JOINT && mode != MTPC_SCORE_PREFIX) return MTPC_ERR_UNSUPPORTED;
+  Plan p;
+  mtpc_status s = prepare(family, MTPC_OP_TABLE, hd, ly, T, 0, false, p);
+  if (s != MTPC_OK) return s;
+  if ((long long)hd->B * T > 0x7fffffffLL / hd->n) return MTPC_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)hd->stream;
+  char* ws = (char*)hd->workspace;
+  s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
+  if (s != MTPC_OK) return s;
+  GatherArgs g{};
+  g.B = hd->B; g.S = T; g.v = hd->v; g.n = hd->n; g.r = hd->r;
+  g.x = x; g.e = (float*)(ws + p.e);
+  HIP_TRY(launch_gather_table(g, logphi, st));
+  HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * T, T, out, mode == MTPC_SCORE_PREFIX), st));
   return MTPC_OK;
 }
 
@@ -574,12 +611,13 @@ const char* mtpc_status_string(mtpc_status s) {
 
 size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
                             const mtpc_sumlayers* layers, int32_t S, int32_t mode) {
-  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_BACKWARD) return 0;
+  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_TABLE) return 0;
   if (!head || head->B < 1 || head->d < 1 || head->n < 1 || head->r < 1 || head->v < 1) return 0;
   if (op == MTPC_OP_BACKWARD) return make_bwd_plan(family, head, layers, mode != MTPC_BWD_RECOMPUTE).total;
-  if (op == MTPC_OP_SAMPLE && S < 1) return 0;
+  const bool per_draft = op == MTPC_OP_SAMPLE || op == MTPC_OP_TABLE;
+  if (per_draft && S < 1) return 0;
   // sized for the most demanding variant of the op (sample: with prefix scores)
-  Plan p = make_plan(family, op, head, layers, op == MTPC_OP_SAMPLE ? S : 1, mode, true);
+  Plan p = make_plan(family, op, head, layers, per_draft ? S : 1, mode, true);
   return p.total;
 }
 
@@ -670,6 +708,23 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
                               int32_t mode, uint64_t seed, uint32_t offset, int32_t* accepted,
                               int32_t* token) {
   return run_verify(MTPC_BTREE, head, A, logphi, drafts, prefix_logq, p, mode, seed, offset, accepted, token);
+}
+
+mtpc_status mtpc_ff_table_scores(const mtpc_head* head, const float* logphi, const int32_t* x, int32_t T,
+                                 int32_t mode, float* out) {
+  return run_table_scores(MTPC_FF, head, nullptr, logphi, x, T, mode, out);
+}
+mtpc_status mtpc_cp_table_scores(const mtpc_head* head, const float* logphi, const int32_t* x, int32_t T,
+                                 int32_t mode, float* out) {
+  return run_table_scores(MTPC_CP, head, nullptr, logphi, x, T, mode, out);
+}
+mtpc_status mtpc_hmm_table_scores(const mtpc_head* head, const mtpc_sumlayers* T_layers, const float* logphi,
+                                  const int32_t* x, int32_t T, int32_t mode, float* out) {
+  return run_table_scores(MTPC_HMM, head, T_layers, logphi, x, T, mode, out);
+}
+mtpc_status mtpc_btree_table_scores(const mtpc_head* head, const mtpc_sumlayers* A, const float* logphi,
+                                    const int32_t* x, int32_t T, int32_t mode, float* out) {
+  return run_table_scores(MTPC_BTREE, head, A, logphi, x, T, mode, out);
 }
 
 mtpc_status mtpc_ff_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,

@@ -893,6 +893,84 @@ hipError_t launch_gather_table(const GatherArgs& a, const float* logphi, hipStre
 }
 
 // ---------------------------------------------------------------------------
+// Token draws of Alg. 1 from the table of normalised input units (large batches: the fused
+// kernel only writes the table, the draws read one row each).  One wave per token; lane l
+// holds tokens 5l..5l+4 (v <= 320), the CDF is an ordered scan over lanes, the draw the
+// smallest k with u * total < cdf[k], else the last token with positive mass.
+__global__ __launch_bounds__(256) void k_draw_table(const DrawArgs a) {
+  constexpr int VPL = 5;
+  const int lane = threadIdx.x & 63;
+  const long long di = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);   // (b, s, i) flattened
+  if (di >= (long long)a.B * a.S * a.n) return;
+  const int i = (int)(di % a.n);
+  const long long bs = di / a.n;
+  const long long b = bs / a.S;
+  const int s = (int)(bs - b * a.S);
+  const int z = a.zleaf[di];
+  const float* row = a.logphi + ((b * a.n + i) * a.r + z) * a.v;
+  float lg[VPL], vals[VPL];
+  float ls = 0.f;
+#pragma unroll
+  for (int q = 0; q < VPL; ++q) {
+    const int k = lane * VPL + q;
+    lg[q] = k < a.v ? row[k] : neg_inf();
+    vals[q] = k < a.v ? expf(lg[q]) : 0.f;
+    ls += vals[q];
+  }
+  if (a.greedy) {
+    float best = neg_inf();   // lanes past the vocabulary keep -inf and never win
+    int arg = 0;
+#pragma unroll
+    for (int q = 0; q < VPL; ++q)
+      if (lg[q] > best) { best = lg[q]; arg = lane * VPL + q; }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const float ob = __shfl_xor(best, o);
+      const int oa = __shfl_xor(arg, o);
+      if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+    }
+    if (lane == 0) a.drafts[di] = arg;
+    return;
+  }
+  float incl = ls;   // inclusive scan over lanes
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const float t = __shfl_up(incl, o);
+    if (lane >= o) incl += t;
+  }
+  const float Z = __shfl(incl, 63);
+  const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)s, (uint32_t)i);
+  const float tgt = u * Z;
+  const unsigned long long cross = __ballot(tgt < incl);
+  if (cross != 0ull) {
+    const int L = __ffsll((long long)cross) - 1;
+    float run = incl - ls;
+    int tok = lane * VPL + VPL - 1;
+    bool found = false;
+#pragma unroll
+    for (int q = 0; q < VPL; ++q) {
+      run += vals[q];
+      if (!found && tgt < run) { tok = lane * VPL + q; found = true; }
+    }
+    if (lane == L) a.drafts[di] = tok;
+  } else {
+    int last = -1;
+#pragma unroll
+    for (int q = 0; q < VPL; ++q)
+      if (vals[q] > 0.f) last = lane * VPL + q;
+    const unsigned long long pos = __ballot(last >= 0);
+    const int L = 63 - __clzll((long long)pos);
+    if (lane == L) a.drafts[di] = last;
+  }
+}
+
+hipError_t launch_draw_table(const DrawArgs& a, hipStream_t st) {
+  const long long rows = (long long)a.B * a.S * a.n;
+  hipLaunchKernelGGL(k_draw_table, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 __global__ void k_philox_uniforms(int B, int S, int slots, uint32_t seed_lo, uint32_t seed_hi,
                                   uint32_t offset, float* out) {
   const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;

@@ -120,6 +120,18 @@ struct GatherArgs {
 };
 hipError_t launch_gather_table(const GatherArgs& a, const float* logphi, hipStream_t st);
 
+// token draws of Alg. 1 from the table of normalised input units: token i of draft (b,s)
+// comes from the row log phi[b][i][zleaf[b][s][i]][:]
+struct DrawArgs {
+  int B, S, v, n, r;
+  const float* logphi;  // [B][n][r][v]
+  const int* zleaf;     // [B][S][n] selected input unit of every token
+  int* drafts;          // [B][S][n]
+  uint32_t seed_lo, seed_hi, offset;
+  int greedy;           // most likely token instead of a draw (smallest id on ties)
+};
+hipError_t launch_draw_table(const DrawArgs& a, hipStream_t st);
+
 // Verification step of a speculative-decoding cycle (Alg. 2, acceptance loop on)
 struct VerifyArgs {
   int family, B, n, r, v, mode;

@@ -82,35 +82,35 @@ void k_unembed(const UnembedArgs a) {
       }
     }
   }
-  if constexpr (SAMPLE) {
-    if (a.logphi != nullptr) {
-      // table log phi[b][wi][wj][:] for the scoring and verification steps.  Registers
-      // 4q..4q+3 of a block hold four consecutive vocabulary rows of one position: one
-      // 16-byte store each (the row of a position is 4v bytes long and 16-byte aligned
-      // when v is a multiple of 4; otherwise element by element)
-      const bool vec = (a.v & 3) == 0;
+  if (a.logphi != nullptr) {
+    // table log phi[b][wi][wj][:] for the scoring and verification steps.  Registers
+    // 4q..4q+3 of a block hold four consecutive vocabulary rows of one position: one
+    // 16-byte store each (the row of a position is 4v bytes long and 16-byte aligned
+    // when v is a multiple of 4; otherwise element by element)
+    const bool vec = (a.v & 3) == 0;
 #pragma unroll
-      for (int pb = 0; pb < PB; ++pb) {
-        const int b = b0 + wb * PB * 32 + pb * 32 + l31;
-        if (b >= a.B) continue;
-        float* dst = a.logphi + (((long long)b * a.n + wi) * a.r + wj) * a.v;
+    for (int pb = 0; pb < PB; ++pb) {
+      const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+      if (b >= a.B) continue;
+      float* dst = a.logphi + (((long long)b * a.n + wi) * a.r + wj) * a.v;
 #pragma unroll
-        for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int row = rbase + vb * 32 + 8 * q;
-            if (vec) {
-              if (row < a.v)
-                *(f32x4_t*)(dst + row) = f32x4_t{acc[pb][vb][4 * q] - lse[pb], acc[pb][vb][4 * q + 1] - lse[pb],
-                                                 acc[pb][vb][4 * q + 2] - lse[pb], acc[pb][vb][4 * q + 3] - lse[pb]};
-            } else {
+        for (int q = 0; q < 4; ++q) {
+          const int row = rbase + vb * 32 + 8 * q;
+          if (vec) {
+            if (row < a.v)
+              *(f32x4_t*)(dst + row) = f32x4_t{acc[pb][vb][4 * q] - lse[pb], acc[pb][vb][4 * q + 1] - lse[pb],
+                                               acc[pb][vb][4 * q + 2] - lse[pb], acc[pb][vb][4 * q + 3] - lse[pb]};
+          } else {
 #pragma unroll
-              for (int t = 0; t < 4; ++t)
-                if (row + t < a.v) dst[row + t] = acc[pb][vb][4 * q + t] - lse[pb];
-            }
+            for (int t = 0; t < 4; ++t)
+              if (row + t < a.v) dst[row + t] = acc[pb][vb][4 * q + t] - lse[pb];
           }
-      }
+        }
     }
+  }
+  if constexpr (SAMPLE) {
     if (a.zleaf == nullptr) return;
     // ---- which positions of this tile draw token wi from component wj?
     int* misc = (int*)(smem + TL::MISC_OFF);

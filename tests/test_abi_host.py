@@ -21,7 +21,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported():
     from paper_2511_11346_amd import binding
     names = declared_symbols()
-    assert len(names) == 28 and sorted(binding.EXPORTS) == names
+    assert len(names) == 32 and sorted(binding.EXPORTS) == names
     L = C.CDLL(LIB)
     for n in names:
         assert hasattr(L, n), n
@@ -80,6 +80,13 @@ def test_argument_errors_are_reported_without_launching():
     assert L.mtpc_cp_verify(C.byref(_head()), out, tg, out, out, 5, 1, 0, tg, tg) == UNSUP
     assert L.mtpc_cp_verify(C.byref(_head(workspace_bytes=16)), None, tg, None, out, 1, 0, 0, tg, tg) == WS
     assert L.mtpc_hmm_verify(C.byref(_head()), None, out, tg, out, out, 0, 1, 0, tg, tg) == NULL
+    # scores from a table
+    assert L.mtpc_cp_table_scores(C.byref(_head()), None, tg, 1, 0, out) == NULL
+    assert L.mtpc_cp_table_scores(C.byref(_head()), out, None, 1, 0, out) == NULL
+    assert L.mtpc_cp_table_scores(C.byref(_head()), out, tg, 0, 0, out) == SHAPE
+    assert L.mtpc_cp_table_scores(C.byref(_head()), out, tg, 1, 2, out) == UNSUP
+    assert L.mtpc_cp_table_scores(C.byref(_head(workspace_bytes=16)), out, tg, 1, 0, out) == WS
+    assert L.mtpc_btree_table_scores(C.byref(_head()), None, out, tg, 1, 0, out) == NULL
     # greedy draft and training step
     assert L.mtpc_cp_greedy_draft(C.byref(_head()), None, None, None, None) == NULL
     assert L.mtpc_cp_greedy_draft(C.byref(_head(workspace_bytes=16)), tg, None, None, None) == WS
@@ -107,6 +114,10 @@ def test_workspace_query():
     assert s8 > s4 > 0
     assert L.mtpc_workspace_bytes(9, 0, C.byref(hd), None, 1, 0) == 0
     assert L.mtpc_workspace_bytes(binding.CP, binding.OP_SAMPLE, C.byref(hd), None, 0, 0) == 0
+    t1 = L.mtpc_workspace_bytes(binding.CP, binding.OP_TABLE, C.byref(hd), None, 1, 0)
+    t16 = L.mtpc_workspace_bytes(binding.CP, binding.OP_TABLE, C.byref(hd), None, 16, 0)
+    assert t16 >= 16 * 4 * hd.B * hd.n * hd.r and t16 > t1 == small
+    assert L.mtpc_workspace_bytes(binding.CP, binding.OP_TABLE, C.byref(hd), None, 0, 0) == 0
     lay = binding.mtpc_sumlayers(0x6000, hd.r * hd.r, 0)
     hom = binding.mtpc_sumlayers(0x6000, 0, 0)
     a = L.mtpc_workspace_bytes(binding.HMM, binding.OP_LOGLIK, C.byref(hd), C.byref(lay), 1, 0)

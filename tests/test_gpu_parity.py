@@ -120,9 +120,12 @@ def test_sampling_matches_the_oracle(family, dtype, B, d, n, r, v, S):
     for s in range(S):
         ps = oc.prefix_marginals_from(family, logphi, logw, loglayers, gdn[:, s])
         tol_check(gp[:, s].cpu().numpy(), ps, dtype, "draft prefix scores")
-    # without the optional outputs the drafts are the same
+    # without the optional outputs the drafts are the same (large batches then draw inside the
+    # fused kernel instead of from the table: same rule, so only boundary draws may differ)
     gd2, _, _ = head.sample(S, seed=seed, offset=off, want_latents=False, want_prefix=False)
-    assert torch.equal(gd, gd2)
+    near2, _ = compare_drafts(gd2, None, od, ol, margin)
+    assert near2 == near
+    assert torch.equal(gd, gd2) or B > 64
 
 
 def test_peaked_logits_and_forbidden_transitions():

@@ -1,0 +1,105 @@
+"""GPU parity of the operations that work from the table of normalised input units
+log phi[B][n][r][v]: scores of arbitrary windows (log-likelihood / prefix marginals without
+another pass over W) and, for training-sized batches, the token draws of Alg. 1 read from it."""
+import numpy as np
+import pytest
+import torch
+
+import mtpc_inputs as mi
+from oracle import mtpc_oracle as oc
+from oracle import philox
+from oracle import speculative as sp
+
+from gpu_util import BOUNDARY, compare_drafts, make_head, oracle_params, tol_check
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # family, dtype, B, d, n, r, v, contextual
+    ("ff", "f32", 70, 64, 5, 1, 100, False),
+    ("ff", "bf16", 9, 64, 3, 1, 320, False),
+    ("cp", "bf16", 300, 128, 8, 16, 320, False),
+    ("cp", "f32", 130, 64, 4, 5, 33, False),
+    ("hmm", "f32", 65, 64, 6, 4, 130, False),
+    ("hmm", "bf16", 140, 128, 8, 32, 320, True),
+    ("btree", "bf16", 260, 64, 4, 16, 268, False),
+    ("btree", "f32", 97, 64, 16, 8, 257, False),
+    ("btree", "bf16", 33, 128, 8, 8, 100, True),
+]
+
+
+def windows(inp, T, seed):
+    """T windows per position: uniform ids, some variables summed out, one invalid id."""
+    B, n, v = inp.h.shape[0], inp.W.shape[0], inp.W.shape[2]
+    rng = np.random.default_rng([seed, B, n, v])
+    x = rng.integers(0, v, size=(B, T, n)).astype(np.int32)
+    x[rng.random(x.shape) < 0.15] = -1
+    x[0, 0, :] = -1                    # everything summed out: log 1 = 0
+    if B > 1:
+        x[1, T - 1, n - 1] = v         # invalid id: the outputs that observe it are NaN
+    return x
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r,v,ctx", CASES)
+def test_table_scores_match_the_oracle(family, dtype, B, d, n, r, v, ctx):
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=900 + B + r, h_scale=1.0,
+                         contextual=ctx)
+    head = make_head(inp)
+    logphi, logw, loglayers = oracle_params(inp)
+    T = 3
+    x = windows(inp, T, 17)
+    xd = torch.from_numpy(x).cuda()
+    want_P = np.stack([oc.prefix_marginals_from(family, logphi, logw, loglayers, x[:, t]) for t in range(T)], axis=1)
+    want_L = np.stack([oc.joint(family, oc.evidence(logphi, x[:, t]), logw, loglayers) for t in range(T)], axis=1)
+
+    # the table as the oracle computes it: only the sum units carry the dtype's tolerance
+    tab = torch.from_numpy(logphi.astype(np.float32)).cuda()
+    tol_check(head.table_scores(tab, xd, prefix=True).cpu().numpy(), want_P, dtype, "prefix scores, oracle table")
+    got_L = head.table_scores(tab, xd).cpu().numpy()
+    tol_check(got_L, want_L, dtype, "log-likelihoods, oracle table")
+    assert abs(got_L[0, 0]) < 1e-5
+
+    # the table a sampling call leaves (training-sized batches: written by the evidence kernel)
+    table = torch.empty(B, n, r, v, dtype=torch.float32, device="cuda")
+    head.sample(1, seed=3, want_prefix=False, logphi=table)
+    tol_check(table.cpu().numpy(), logphi, dtype, "log phi table")
+    tol_check(head.table_scores(table, xd, prefix=True).cpu().numpy(), want_P, dtype, "prefix scores, own table")
+    tol_check(head.table_scores(table, xd).cpu().numpy(), want_L, dtype, "log-likelihoods, own table")
+    # one window per position, 2-dim form; equals the fused evidence path to rounding
+    one = head.table_scores(table, xd[:, 2].contiguous())
+    ref = head.loglik(xd[:, 2].contiguous())
+    fin = torch.isfinite(ref)
+    assert torch.equal(torch.isnan(one), torch.isnan(ref))
+    assert float((one[fin] - ref[fin]).abs().max()) < 2e-5
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r,v,ctx", [c for c in CASES if c[2] > 64])
+def test_draws_from_the_table_match_the_oracle(family, dtype, B, d, n, r, v, ctx):
+    """Batches above 64 positions that keep the table draw their tokens from it."""
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=40 + B + n, h_scale=1.0,
+                         contextual=ctx)
+    head = make_head(inp)
+    logphi, logw, loglayers = oracle_params(inp)
+    S, seed, off = 2, 0xFEDCBA9876543210, 9
+    u = philox.uniforms(B, S, n + oc.n_latents(family, n), seed, off)
+    od, ol, margin = oc.sample_from(family, logphi, logw, loglayers, u, with_margin=True)
+    table = torch.empty(B, n, r, v, dtype=torch.float32, device="cuda")
+    gd, gl, gp = head.sample(S, seed=seed, offset=off, want_prefix=True, logphi=table)
+    near, bad = compare_drafts(gd, gl, od, ol, margin)
+    print(f"{family}: {near} of {margin.size} drafts within {BOUNDARY} of a CDF step, {bad} of those differ")
+    assert near <= max(4, margin.size // 50)
+    gdn = gd.cpu().numpy()
+    assert gdn.min() >= 0 and gdn.max() < v
+    for s in range(S):
+        ps = oc.prefix_marginals_from(family, logphi, logw, loglayers, gdn[:, s])
+        tol_check(gp[:, s].cpu().numpy(), ps, dtype, "draft prefix scores")
+
+    # greedy draft through the same table path
+    want_d, want_l, gap = sp.greedy_draft(family, logphi, logw, loglayers)
+    g2, l2, p2 = head.greedy_draft(want_prefix=True, logphi=table)
+    safe = gap >= 1e-6
+    assert np.array_equal(g2.cpu().numpy()[safe], want_d[safe])
+    if l2 is not None and want_l.shape[1]:
+        assert np.array_equal(l2.cpu().numpy()[safe], want_l[safe])
+    tol_check(p2.cpu().numpy(), oc.prefix_marginals_from(family, logphi, logw, loglayers, g2.cpu().numpy()),
+              dtype, "scores of the greedy draft")
