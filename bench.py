@@ -113,12 +113,11 @@ def main():
     drafts = torch.empty(B, S, n, dtype=torch.int32, device=dev)
     lat = torch.empty(B, S, 1, dtype=torch.int32, device=dev)
     pl = torch.empty(B, S, n, dtype=torch.float32, device=dev)
-    # normalised input units log phi[B][n][r][v] (1.34 GB): written by the one unembedding pass of
-    # a step, read by the draws, the draft scores and the scores of the targets
-    table = torch.empty(B, n, inp.r, inp.v, dtype=torch.float32, device=dev)
+    tg3 = tg.view(B, 1, n)
+    P2 = torch.empty(B, 1 + S, n, dtype=torch.float32, device=dev)
     # workspace sized once for the largest of the ops
     head._head(max(head.workspace_bytes(binding.OP_MARGINALS), head.workspace_bytes(binding.OP_SAMPLE, S=S),
-                   head.workspace_bytes(binding.OP_TABLE, S=1)))
+                   head.workspace_bytes(binding.OP_WINDOWS, S=1 + S)))
     t_gen = time.perf_counter() - t_gen
 
     if args.copy_calib:
@@ -132,14 +131,15 @@ def main():
     ev = HipEvents()
 
     def step(k, pairs=None):
-        # one pass over W and h: drafts, their prefix scores and the table; then the prefix
-        # marginals (last = log-likelihood) of the targets from the table
+        # drafts: latents, then each token from the one input unit it is drawn from (1/r of a pass
+        # over W); then ONE fused pass scores the targets and the drafts of every position
+        # (prefix marginals, the last of which is the log-likelihood)
+        head.sample(S, seed=0, offset=k, out=(drafts, lat, None))
         if pairs is not None:
             profile_unembed(pairs[k][0], pairs[k][1])
-        head.sample(S, seed=0, offset=k, out=(drafts, lat, pl), logphi=table)
+        head.window_scores(tg3, drafts, prefix=True, out=P2)
         if pairs is not None:
             profile_unembed(None, None)
-        head.table_scores(table, tg, prefix=True, out=P)
 
     for k in range(args.warmup):
         step(k)
@@ -163,16 +163,14 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / reps
     ms_marg = time_op(lambda: head.prefix_marginals(tg, out=P))
-    ms_samp = time_op(lambda: head.sample(S, seed=0, out=(drafts, lat, pl), logphi=table))
+    ms_samp = time_op(lambda: head.sample(S, seed=0, out=(drafts, lat, pl)))
+    ms_win = time_op(lambda: head.window_scores(tg3, drafts, prefix=True, out=P2))
+    # the other route to the same results: one pass that leaves the table of normalised input
+    # units log phi[B][n][r][v] (1.34 GB), from which tokens are drawn and windows scored
+    table = torch.empty(B, n, inp.r, inp.v, dtype=torch.float32, device=dev)
+    ms_samp_tab = time_op(lambda: head.sample(S, seed=0, out=(drafts, lat, pl), logphi=table))
     ms_tab = time_op(lambda: head.table_scores(table, tg, prefix=True, out=P))
-    # the evidence kernel of a loglik-only call (nothing but e[B][n][r] leaves the registers)
-    ev_pairs = [(ev.create(), ev.create()) for _ in range(5)]
-    for a, b in ev_pairs:
-        profile_unembed(a, b)
-        head.prefix_marginals(tg, out=P)
-    profile_unembed(None, None)
-    torch.cuda.synchronize()
-    k1_ev_ms = sum(ev.elapsed_ms(a, b) for a, b in ev_pairs) / len(ev_pairs)
+    del table
     ms_samp_only = time_op(lambda: head.sample(S, seed=0, out=(drafts, lat, None)))
 
     flops = 2.0 * B * inp.n * inp.r * inp.v * inp.d
@@ -184,18 +182,15 @@ def main():
     del grads
     torch.cuda.empty_cache()
     achieved = flops / (k1_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_unembed (the step's one pass: normalise and store the table of input units)",
+    roofline = {"bound": "mfma", "kernel": "k_unembed (evidence of targets and drafts, the step's one pass over all of W)",
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS,
                 # L2 <-> fabric bytes per launch of this kernel on this workload, from two rocprofv3
                 # --pmc runs of this script (FETCH_SIZE 1,709,069 x 2 KiB, WRITE_SIZE 8,192 x 1 KiB,
                 # factors calibrated on a 1 GiB device copy); reads served by the Infinity Cache count
                 "traffic": 1709069 * 2048 + 8192 * 1024, "traffic_unit": "bytes/launch",
-                "algorithmic_bytes": (B * inp.d + inp.n * inp.r * inp.v * inp.d) * 2 + B * inp.n * inp.r * 4,
-                "avg_launch_ms": k1_ms, "flop_per_launch": flops,
-                # the same kernel in a loglik-only call, which stores no table
-                "evidence_only": {"avg_launch_ms": k1_ev_ms, "achieved": flops / (k1_ev_ms * 1e-3) / 1e12,
-                                  "frac": flops / (k1_ev_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}}
+                "algorithmic_bytes": (B * inp.d + inp.n * inp.r * inp.v * inp.d) * 2 + (1 + S) * B * inp.n * inp.r * 4,
+                "avg_launch_ms": k1_ms, "flop_per_launch": flops}
 
     out = {
         "metric": "MtPC head windows/sec (loglik + draft sample)",
@@ -204,12 +199,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: CP r=16, B=8192, d=4096, n=8, v=320, bf16 in / fp32 acc; "
-                               "step = 1 draft per position with its prefix scores + prefix marginals (last = loglik) "
-                               "of the targets, all from one unembedding pass that leaves the table of input units",
+                               "step = 1 draft per position (tokens drawn through buckets of their input unit) + prefix "
+                               "marginals (last = loglik) of the targets and of the draft in one fused unembedding pass",
                    **WORKLOAD, "S": S},
         "roofline": roofline,
-        "ops_ms": {"sample_with_scores_and_table": ms_samp, "table_scores_of_targets": ms_tab,
-                   "prefix_marginals_call": ms_marg, "sample_only": ms_samp_only},
+        "ops_ms": {"sample_only": ms_samp_only, "window_scores_targets_and_drafts": ms_win,
+                   "prefix_marginals_call": ms_marg, "sample_with_scores": ms_samp,
+                   "sample_with_scores_and_table": ms_samp_tab, "table_scores_of_targets": ms_tab},
         "loglik_windows_per_s": B / (ms_marg * 1e-3),
         "train_step": {"loss_backward_ms": ms_train, "windows_per_s": B / (ms_train * 1e-3),
                        "matrix_passes": 3, "TFLOPs": 3 * flops / (ms_train * 1e-3) / 1e12},

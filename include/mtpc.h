@@ -49,7 +49,7 @@ typedef enum {
 typedef enum { MTPC_F32 = 0, MTPC_BF16 = 1 } mtpc_dtype;
 typedef enum { MTPC_FF = 0, MTPC_CP = 1, MTPC_HMM = 2, MTPC_BTREE = 3 } mtpc_family;
 typedef enum { MTPC_OP_LOGLIK = 0, MTPC_OP_MARGINALS = 1, MTPC_OP_SAMPLE = 2, MTPC_OP_VERIFY = 3,
-               MTPC_OP_BACKWARD = 4, MTPC_OP_TABLE = 5 } mtpc_op;
+               MTPC_OP_BACKWARD = 4, MTPC_OP_TABLE = 5, MTPC_OP_WINDOWS = 6 } mtpc_op;
 typedef enum { MTPC_MARG_PREFIX = 0, MTPC_MARG_UNIVARIATE = 1 } mtpc_marg_mode;
 typedef enum { MTPC_SCORE_JOINT = 0, MTPC_SCORE_PREFIX = 1 } mtpc_score_mode;
 typedef enum { MTPC_VERIFY_SAMPLING = 0, MTPC_VERIFY_GREEDY = 1 } mtpc_verify_mode;
@@ -94,8 +94,8 @@ typedef struct {
 const char* mtpc_status_string(mtpc_status s);
 
 /* Scratch needed by one call.  `layers` may be NULL (FF, CP).  `S` is the number
- * of drafts per position (sample) or of windows per position (MTPC_OP_TABLE) and is
- * ignored otherwise; `mode` is the
+ * of drafts per position (sample) or of windows per position (MTPC_OP_TABLE,
+ * MTPC_OP_WINDOWS: T + T2) and is ignored otherwise; `mode` is the
  * mtpc_marg_mode for MTPC_OP_MARGINALS and the mtpc_bwd_mode for MTPC_OP_BACKWARD.
  * Returns 0 for invalid arguments. */
 size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
@@ -147,6 +147,27 @@ mtpc_status mtpc_hmm_sample(const mtpc_head* head, const mtpc_sumlayers* T, int3
 mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, int32_t S,
                               uint64_t seed, uint32_t offset,
                               int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi);
+
+/* Scores of several windows per position in ONE unembedding pass: the log-likelihood
+ * (Eqs. FF / CP / HMM / BTree) or the prefix marginals (Alg. 2) of every window, as
+ * mtpc_*_loglik / MTPC_MARG_PREFIX compute them for one.  The windows come as two sets so
+ * that, e.g., the targets and the drafts of the same positions are scored together
+ * without copying them into one buffer:
+ *   x  [B][T][n]  int32, T >= 1;   x2 [B][T2][n] int32 or NULL with T2 = 0;  -1 = summed out
+ *   mode MTPC_SCORE_JOINT:  out [B][T+T2]     log q(window)
+ *        MTPC_SCORE_PREFIX: out [B][T+T2][n]  prefix marginals
+ *   (per position the T windows of x come first, then the T2 windows of x2)
+ * Workspace: mtpc_workspace_bytes(family, MTPC_OP_WINDOWS, head, layers, T + T2, 0). */
+mtpc_status mtpc_ff_window_scores(const mtpc_head* head, const int32_t* x, int32_t T,
+                                  const int32_t* x2, int32_t T2, int32_t mode, float* out);
+mtpc_status mtpc_cp_window_scores(const mtpc_head* head, const int32_t* x, int32_t T,
+                                  const int32_t* x2, int32_t T2, int32_t mode, float* out);
+mtpc_status mtpc_hmm_window_scores(const mtpc_head* head, const mtpc_sumlayers* T_layers,
+                                   const int32_t* x, int32_t T, const int32_t* x2, int32_t T2,
+                                   int32_t mode, float* out);
+mtpc_status mtpc_btree_window_scores(const mtpc_head* head, const mtpc_sumlayers* A,
+                                     const int32_t* x, int32_t T, const int32_t* x2, int32_t T2,
+                                     int32_t mode, float* out);
 
 /* Scores of arbitrary windows from the table of input units a sampling call left
  * (same head, same h): the evidence of each token is read from logphi and the circuit

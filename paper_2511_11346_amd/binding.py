@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmtpc.so")
 
 FF, CP, HMM, BTREE = 0, 1, 2, 3
 FAMILY = {"ff": FF, "cp": CP, "hmm": HMM, "btree": BTREE}
-OP_LOGLIK, OP_MARGINALS, OP_SAMPLE, OP_VERIFY, OP_BACKWARD, OP_TABLE = 0, 1, 2, 3, 4, 5
+OP_LOGLIK, OP_MARGINALS, OP_SAMPLE, OP_VERIFY, OP_BACKWARD, OP_TABLE, OP_WINDOWS = 0, 1, 2, 3, 4, 5, 6
 VERIFY_SAMPLING, VERIFY_GREEDY = 0, 1
 MARG_PREFIX, MARG_UNIVARIATE = 0, 1
 SCORE_JOINT, SCORE_PREFIX = 0, 1
@@ -46,6 +46,7 @@ EXPORTS = [
     "mtpc_ff_marginals", "mtpc_cp_marginals", "mtpc_hmm_marginals", "mtpc_btree_marginals",
     "mtpc_ff_sample", "mtpc_cp_sample", "mtpc_hmm_sample", "mtpc_btree_sample",
     "mtpc_ff_verify", "mtpc_cp_verify", "mtpc_hmm_verify", "mtpc_btree_verify",
+    "mtpc_ff_window_scores", "mtpc_cp_window_scores", "mtpc_hmm_window_scores", "mtpc_btree_window_scores",
     "mtpc_ff_table_scores", "mtpc_cp_table_scores", "mtpc_hmm_table_scores", "mtpc_btree_table_scores",
     "mtpc_ff_greedy_draft", "mtpc_cp_greedy_draft", "mtpc_hmm_greedy_draft", "mtpc_btree_greedy_draft",
     "mtpc_ff_loss_backward", "mtpc_cp_loss_backward", "mtpc_hmm_loss_backward", "mtpc_btree_loss_backward",
@@ -74,6 +75,7 @@ def lib() -> C.CDLL:
             getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
             getattr(L, f"mtpc_{fam}_greedy_draft").argtypes = [hp, ip, ip, fp, fp]
             getattr(L, f"mtpc_{fam}_table_scores").argtypes = [hp, fp, ip, C.c_int32, C.c_int32, fp]
+            getattr(L, f"mtpc_{fam}_window_scores").argtypes = [hp, ip, C.c_int32, ip, C.c_int32, C.c_int32, fp]
         for fam in ("hmm", "btree"):
             getattr(L, f"mtpc_{fam}_loglik").argtypes = [hp, lp, ip, fp]
             getattr(L, f"mtpc_{fam}_marginals").argtypes = [hp, lp, ip, C.c_int32, fp]
@@ -81,6 +83,7 @@ def lib() -> C.CDLL:
             getattr(L, f"mtpc_{fam}_verify").argtypes = [hp, lp, fp, ip, fp, fp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip]
             getattr(L, f"mtpc_{fam}_greedy_draft").argtypes = [hp, lp, ip, ip, fp, fp]
             getattr(L, f"mtpc_{fam}_table_scores").argtypes = [hp, lp, fp, ip, C.c_int32, C.c_int32, fp]
+            getattr(L, f"mtpc_{fam}_window_scores").argtypes = [hp, lp, ip, C.c_int32, ip, C.c_int32, C.c_int32, fp]
         L.mtpc_ff_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp]
         L.mtpc_cp_loss_backward.argtypes = [hp, ip, fp, fp, fp, fp, fp]
         L.mtpc_hmm_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp, fp]
@@ -275,6 +278,26 @@ class Head:
         assert logphi.is_cuda and logphi.dtype == torch.float32 and logphi.is_contiguous()
         assert tuple(logphi.shape) == (self.B, self.n, self.r, self.v)
         return logphi.data_ptr()
+
+    def window_scores(self, x: torch.Tensor, x2: Optional[torch.Tensor] = None, prefix: bool = False,
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Scores of the windows x [B,T,n] and (optionally) x2 [B,T2,n], int32, in one unembedding pass:
+        log-likelihoods [B,T+T2], or prefix marginals [B,T+T2,n] with prefix=True (x's windows first)."""
+        def chk(t):
+            assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
+            assert t.dim() == 3 and t.shape[0] == self.B and t.shape[2] == self.n
+            return t.shape[1]
+        T = chk(x)
+        T2 = chk(x2) if x2 is not None else 0
+        shape = (self.B, T + T2, self.n) if prefix else (self.B, T + T2)
+        if out is None:
+            out = torch.empty(shape, dtype=torch.float32, device=self.h.device)
+        else:
+            assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == shape
+        hd = self._head(self.workspace_bytes(OP_WINDOWS, S=T + T2))
+        _check(self._call("window_scores", hd, x.data_ptr(), T, x2.data_ptr() if x2 is not None else None, T2,
+                          SCORE_PREFIX if prefix else SCORE_JOINT, out.data_ptr()))
+        return out
 
     def table_scores(self, logphi: torch.Tensor, x: torch.Tensor, prefix: bool = False,
                      out: Optional[torch.Tensor] = None) -> torch.Tensor:

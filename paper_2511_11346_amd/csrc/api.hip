@@ -27,16 +27,21 @@ int n_layers(int family, int n) {
   return 0;
 }
 
-// Drafts are scored from the table of normalised input units that the sampling pass then
-// writes (B*n*r*v floats: one extra write of the tile instead of a second pass over W and h),
-// unless that table would exceed 8 GiB; then by a second fused pass with the drafts as targets.
-bool score_by_gather(const mtpc_head* hd, int S) {
-  (void)S;
-  return (unsigned long long)hd->B * hd->n * hd->r * hd->v * 4ull <= (8ull << 30);
+// Decode-sized batches (B <= 64, bound by the one read of W): the sampling pass also writes
+// the table of normalised input units (B*n*r*v floats) and the drafts are scored from it,
+// instead of a second pass over W.  Larger batches draw through buckets (1/r of a pass) and
+// score their drafts with one evidence pass, unless the caller asks for the table.
+bool decode_sized(const mtpc_head* hd) { return hd->B <= 64; }
+
+// most windows per position whose rows B*T*n still index with an int
+long long hd_rows_limit(const mtpc_head* hd) {
+  if (!hd || hd->B < 1 || hd->n < 1) return 0x7fffffffLL;      // rejected later by check_head
+  return 0x7fffffffLL / hd->n / hd->B;
 }
 
 struct Plan {           // byte offsets into the workspace
   size_t logw, lay_nat, lay_circ, e, zleaf, lat, logm, table, total;
+  size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_list;   // buckets of the token draws (large batches)
   int nb, Lst;          // position blocks and stored layers of the normalised copies
 };
 
@@ -95,15 +100,21 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   const bool sample = op == MTPC_OP_SAMPLE;
   const bool uni = op == MTPC_OP_MARGINALS && mode == MTPC_MARG_UNIVARIATE;
   const bool verify = op == MTPC_OP_VERIFY;
-  const bool table_op = op == MTPC_OP_TABLE;       // S windows per position scored from a table
+  const bool table_op = op == MTPC_OP_TABLE || op == MTPC_OP_WINDOWS;   // S windows per position
   const bool need_nat = L > 0 && (family == MTPC_HMM || sample || uni || verify);
   const bool need_tr = L > 0 && family == MTPC_BTREE && (!sample || want_prefix) && !uni;
   p.lay_nat = need_nat ? take(lay_bytes) : 0;
   p.lay_circ = need_tr ? take(lay_bytes) : p.lay_nat;
   const size_t rows = (sample || table_op) ? B * (size_t)S : B;
   p.e = (uni || verify || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
-  // few drafts: they are scored from the table of input units the sampling pass leaves behind
-  p.table = (sample && want_prefix && score_by_gather(hd, S)) ? take(B * n * r * (size_t)hd->v * 4) : 0;
+  p.table = (sample && want_prefix && decode_sized(hd)) ? take(B * n * r * (size_t)hd->v * 4) : 0;
+  if (sample && !decode_sized(hd)) {
+    p.bk_count = take(n * r * 4);
+    p.bk_rowoff = take((n * r + 1) * 4);
+    p.bk_tileoff = take((n * r + 1) * 4);
+    p.bk_slot = take(B * (size_t)S * n * 4);
+    p.bk_list = take(B * (size_t)S * n * 4);
+  }
   p.zleaf = sample ? take(B * (size_t)S * n * 4) : 0;
   p.lat = sample ? take(B * (size_t)S * (size_t)(n_latents(family, hd->n) + 1) * 4) : 0;
   p.logm = uni ? take(B * n * r * 4) : 0;
@@ -129,7 +140,7 @@ mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayer
   if (st != MTPC_OK) return st;
   st = check_layers(family, hd, ly);
   if (st != MTPC_OK) return st;
-  if ((op == MTPC_OP_SAMPLE || op == MTPC_OP_TABLE) && S < 1) return MTPC_ERR_SHAPE;
+  if ((op == MTPC_OP_SAMPLE || op == MTPC_OP_TABLE || op == MTPC_OP_WINDOWS) && S < 1) return MTPC_ERR_SHAPE;
   plan = make_plan(family, op, hd, ly, S, mode, want_prefix);
   if (!hd->workspace) return MTPC_ERR_NULL;
   if (((uintptr_t)hd->workspace & 15) || hd->workspace_bytes < plan.total) return MTPC_ERR_WORKSPACE;
@@ -267,15 +278,35 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
   u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
   u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset; u.greedy = greedy;
-  const bool gather = want_prefix && score_by_gather(hd, S);
+  // how the tokens are drawn and the drafts scored (see decode_sized)
+  const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
+  const bool big = !decode_sized(hd);
+  const bool span_ok = (unsigned long long)hd->B * (unsigned long long)hd->ld_h * esz <= 0xffffffffull;
+  const bool use_buckets = big && !logphi && span_ok;
+  const bool gather = want_prefix && (logphi != nullptr || !big);      // scores read from the table
   u.logphi = logphi ? logphi : (gather ? (float*)(ws + p.table) : nullptr);
-  // Training-sized batches that write the table anyway: the fused kernel only normalises
-  // and stores, and the draws read one table row each (the in-kernel draw stage costs more
-  // than that read once every workgroup of the grid has to run it).
-  const bool draw_from_table = u.logphi != nullptr && hd->B > 64;
-  if (draw_from_table) u.zleaf = nullptr;
+  const bool draw_from_table = big && logphi != nullptr;
+  if (use_buckets) {
+    BucketArgs bk{};
+    bk.B = hd->B; bk.S = S; bk.n = hd->n; bk.r = hd->r; bk.tile = DRAW_GATHER_TILE;
+    bk.zleaf = la.zleaf;
+    bk.count = (int*)(ws + p.bk_count); bk.slot = (int*)(ws + p.bk_slot);
+    bk.row_off = (int*)(ws + p.bk_rowoff); bk.tile_off = (int*)(ws + p.bk_tileoff);
+    bk.list = (int*)(ws + p.bk_list);
+    HIP_TRY(launch_buckets(bk, st));
+    DrawGatherArgs dg{};
+    dg.h = hd->h; dg.ld_h = hd->ld_h; dg.W = hd->W;
+    dg.B = hd->B; dg.S = S; dg.d = hd->d; dg.v = hd->v; dg.n = hd->n; dg.r = hd->r;
+    dg.row_off = bk.row_off; dg.tile_off = bk.tile_off; dg.list = bk.list; dg.drafts = drafts;
+    dg.seed_lo = seed_lo; dg.seed_hi = seed_hi; dg.offset = offset; dg.greedy = greedy;
+    HIP_TRY(launch_draw_gather(dg, hd->dtype, st));
+  } else if (draw_from_table) {
+    // the caller keeps the table: the fused kernel only normalises and stores, and the
+    // draws read one table row each
+    u.zleaf = nullptr;
+  }
   {
-    {
+    if (!use_buckets) {
       ProfScope prof(st);
       HIP_TRY(launch_unembed(u, hd->dtype, st));
     }
@@ -291,6 +322,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
       u2.h = hd->h; u2.ld_h = hd->ld_h; u2.W = hd->W;
       u2.B = hd->B; u2.d = hd->d; u2.v = hd->v; u2.n = hd->n; u2.r = hd->r;
       u2.targets = drafts; u2.T = S; u2.e = (float*)(ws + p.e);
+      ProfScope prof(st);
       HIP_TRY(launch_unembed(u2, hd->dtype, st));
     }
   }
@@ -303,6 +335,34 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     }
     HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * S, S, prefix_logq, 1), st));
   }
+  return MTPC_OK;
+}
+
+// log-likelihoods / prefix marginals of several windows per position, given as two sets
+// (say targets and drafts): params -> ONE fused unembedding pass -> circuit
+mtpc_status run_window_scores(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const int32_t* x,
+                              int32_t T, const int32_t* x2, int32_t T2, int32_t mode, float* out) {
+  if (!x || !out || (T2 > 0 && !x2)) return MTPC_ERR_NULL;
+  if (T < 1 || T2 < 0) return MTPC_ERR_SHAPE;
+  if (mode != MTPC_SCORE_JOINT && mode != MTPC_SCORE_PREFIX) return MTPC_ERR_UNSUPPORTED;
+  const long long TT = (long long)T + T2;
+  if (TT > 0x7fffffffLL || (long long)hd_rows_limit(hd) < TT) return MTPC_ERR_UNSUPPORTED;
+  Plan p;
+  mtpc_status s = prepare(family, MTPC_OP_WINDOWS, hd, ly, (int)TT, 0, false, p);
+  if (s != MTPC_OK) return s;
+  hipStream_t st = (hipStream_t)hd->stream;
+  char* ws = (char*)hd->workspace;
+  s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
+  if (s != MTPC_OK) return s;
+  UnembedArgs u{};
+  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
+  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  u.targets = x; u.T = T; u.targets2 = x2; u.T2 = T2; u.e = (float*)(ws + p.e);
+  {
+    ProfScope prof(st);
+    HIP_TRY(launch_unembed(u, hd->dtype, st));
+  }
+  HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * (int)TT, (int)TT, out, mode == MTPC_SCORE_PREFIX), st));
   return MTPC_OK;
 }
 
@@ -611,10 +671,10 @@ const char* mtpc_status_string(mtpc_status s) {
 
 size_t mtpc_workspace_bytes(int32_t family, int32_t op, const mtpc_head* head,
                             const mtpc_sumlayers* layers, int32_t S, int32_t mode) {
-  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_TABLE) return 0;
+  if (family < MTPC_FF || family > MTPC_BTREE || op < MTPC_OP_LOGLIK || op > MTPC_OP_WINDOWS) return 0;
   if (!head || head->B < 1 || head->d < 1 || head->n < 1 || head->r < 1 || head->v < 1) return 0;
   if (op == MTPC_OP_BACKWARD) return make_bwd_plan(family, head, layers, mode != MTPC_BWD_RECOMPUTE).total;
-  const bool per_draft = op == MTPC_OP_SAMPLE || op == MTPC_OP_TABLE;
+  const bool per_draft = op == MTPC_OP_SAMPLE || op == MTPC_OP_TABLE || op == MTPC_OP_WINDOWS;
   if (per_draft && S < 1) return 0;
   // sized for the most demanding variant of the op (sample: with prefix scores)
   Plan p = make_plan(family, op, head, layers, per_draft ? S : 1, mode, true);
@@ -708,6 +768,23 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
                               int32_t mode, uint64_t seed, uint32_t offset, int32_t* accepted,
                               int32_t* token) {
   return run_verify(MTPC_BTREE, head, A, logphi, drafts, prefix_logq, p, mode, seed, offset, accepted, token);
+}
+
+mtpc_status mtpc_ff_window_scores(const mtpc_head* head, const int32_t* x, int32_t T, const int32_t* x2,
+                                  int32_t T2, int32_t mode, float* out) {
+  return run_window_scores(MTPC_FF, head, nullptr, x, T, x2, T2, mode, out);
+}
+mtpc_status mtpc_cp_window_scores(const mtpc_head* head, const int32_t* x, int32_t T, const int32_t* x2,
+                                  int32_t T2, int32_t mode, float* out) {
+  return run_window_scores(MTPC_CP, head, nullptr, x, T, x2, T2, mode, out);
+}
+mtpc_status mtpc_hmm_window_scores(const mtpc_head* head, const mtpc_sumlayers* T_layers, const int32_t* x,
+                                   int32_t T, const int32_t* x2, int32_t T2, int32_t mode, float* out) {
+  return run_window_scores(MTPC_HMM, head, T_layers, x, T, x2, T2, mode, out);
+}
+mtpc_status mtpc_btree_window_scores(const mtpc_head* head, const mtpc_sumlayers* A, const int32_t* x,
+                                     int32_t T, const int32_t* x2, int32_t T2, int32_t mode, float* out) {
+  return run_window_scores(MTPC_BTREE, head, A, x, T, x2, T2, mode, out);
 }
 
 mtpc_status mtpc_ff_table_scores(const mtpc_head* head, const float* logphi, const int32_t* x, int32_t T,

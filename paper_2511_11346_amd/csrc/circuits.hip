@@ -971,6 +971,94 @@ hipError_t launch_draw_table(const DrawArgs& a, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------
+// Bucketing of the token draws by (token index, selected input unit).  Three small kernels:
+// clear the counters; count (the value an atomic returns is the triple's rank in its
+// bucket); one workgroup turns the counts into row and tile offsets; fill the lists.
+__global__ __launch_bounds__(256) void k_bucket_clear(int* count, int ng) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t < ng) count[t] = 0;
+}
+
+// Ranks are taken inside a workgroup first (LDS counters), then every non-empty bucket of
+// the workgroup reserves its range with one global atomic: B*S*n / 1024 * (buckets hit)
+// global atomics instead of B*S*n on n*r addresses.
+__global__ __launch_bounds__(1024) void k_bucket_count(const BucketArgs a) {
+  extern __shared__ int s_count[];                   // [n*r]
+  const int ng = a.n * a.r;
+  for (int g = threadIdx.x; g < ng; g += 1024) s_count[g] = 0;
+  __syncthreads();
+  const long long t = (long long)blockIdx.x * 1024 + threadIdx.x;
+  const bool live = t < (long long)a.B * a.S * a.n;
+  int g = 0, rank = 0;
+  if (live) {
+    const int i = (int)(t % a.n);
+    g = i * a.r + min(max(a.zleaf[t], 0), a.r - 1);
+    rank = atomicAdd(&s_count[g], 1);
+  }
+  __syncthreads();
+  for (int k = threadIdx.x; k < ng; k += 1024) {
+    const int c = s_count[k];
+    if (c > 0) s_count[k] = atomicAdd(&a.count[k], c);
+  }
+  __syncthreads();
+  if (live) a.slot[t] = s_count[g] + rank;
+}
+
+__global__ __launch_bounds__(256) void k_bucket_offsets(const BucketArgs a) {
+  __shared__ int s_rows[256], s_tiles[256];
+  const int ng = a.n * a.r, tid = threadIdx.x;
+  const int per = (ng + 255) / 256;                  // consecutive buckets per thread
+  const int g0 = tid * per, g1 = min(g0 + per, ng);
+  int rows = 0, tiles = 0;
+  for (int g = g0; g < g1; ++g) {
+    const int c = a.count[g];
+    rows += c;
+    tiles += (c + a.tile - 1) / a.tile;
+  }
+  s_rows[tid] = rows;
+  s_tiles[tid] = tiles;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {                // inclusive scan
+    const int r2 = tid >= o ? s_rows[tid - o] : 0, t2 = tid >= o ? s_tiles[tid - o] : 0;
+    __syncthreads();
+    s_rows[tid] += r2;
+    s_tiles[tid] += t2;
+    __syncthreads();
+  }
+  int ro = s_rows[tid] - rows, to = s_tiles[tid] - tiles;
+  for (int g = g0; g < g1; ++g) {
+    const int c = a.count[g];
+    a.row_off[g] = ro;
+    a.tile_off[g] = to;
+    ro += c;
+    to += (c + a.tile - 1) / a.tile;
+  }
+  if (tid == 255) {
+    a.row_off[ng] = s_rows[255];
+    a.tile_off[ng] = s_tiles[255];
+  }
+}
+
+__global__ __launch_bounds__(256) void k_bucket_fill(const BucketArgs a) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (long long)a.B * a.S * a.n) return;
+  const int i = (int)(t % a.n);
+  const int z = min(max(a.zleaf[t], 0), a.r - 1);
+  a.list[a.row_off[i * a.r + z] + a.slot[t]] = (int)(t / a.n);
+}
+
+hipError_t launch_buckets(const BucketArgs& a, hipStream_t st) {
+  const int ng = a.n * a.r;
+  const long long rows = (long long)a.B * a.S * a.n;
+  const unsigned gb = (unsigned)((rows + 255) / 256);
+  hipLaunchKernelGGL(k_bucket_clear, dim3((ng + 255) / 256), dim3(256), 0, st, a.count, ng);
+  hipLaunchKernelGGL(k_bucket_count, dim3((unsigned)((rows + 1023) / 1024)), dim3(1024), (size_t)ng * 4, st, a);
+  hipLaunchKernelGGL(k_bucket_offsets, dim3(1), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(k_bucket_fill, dim3(gb), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 __global__ void k_philox_uniforms(int B, int S, int slots, uint32_t seed_lo, uint32_t seed_hi,
                                   uint32_t offset, float* out) {
   const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;

@@ -21,14 +21,16 @@ struct UnembedArgs {
   // evidence: e[(b*T+t)][i][j] = l[x] - LSE for target window t of position b
   const int* targets;   // [B][T][n] or nullptr
   int T;
-  float* e;             // [B*T][n][r]
+  const int* targets2;  // [B][T2][n]: a second set of windows per position (rows T..T+T2-1 of a position), or nullptr
+  int T2;
+  float* e;             // [B*(T+T2)][n][r]
   // sampling: token i of draft (b, s) is drawn from slab (i, zleaf[b][s][i])
   const int* zleaf;     // [B][S][n] or nullptr
   int S;
   int* drafts;          // [B][S][n]
   uint32_t seed_lo, seed_hi, offset;
   int greedy;           // 1: every draw is replaced by the most likely outcome (no random numbers)
-  float* logphi;        // [B][n][r][v] normalised logits of every slab, or nullptr (sampling kernel only)
+  float* logphi;        // [B][n][r][v] normalised logits of every slab, or nullptr
   float* phiT;          // [n*r*v][ld_phi] softmax probabilities, transposed, or nullptr (evidence kernel only)
   long long ld_phi;
 };
@@ -131,6 +133,40 @@ struct DrawArgs {
   int greedy;           // most likely token instead of a draw (smallest id on ties)
 };
 hipError_t launch_draw_table(const DrawArgs& a, hipStream_t st);
+
+// Buckets of the (b, s, i) triples by (i, selected input unit): bucket g = i*r + z holds
+// list[row_off[g] .. row_off[g+1]) = the draft rows b*S+s whose token i comes from unit z
+// (in no particular order), and is covered by tiles tile_off[g] .. tile_off[g+1]-1 of
+// `tile` rows each.
+struct BucketArgs {
+  int B, S, n, r, tile;
+  const int* zleaf;     // [B][S][n]
+  int* count;           // [n*r] scratch
+  int* slot;            // [B*S*n] scratch: rank of a triple inside its bucket
+  int* row_off;         // [n*r + 1]
+  int* tile_off;        // [n*r + 1]
+  int* list;            // [B*S*n]
+};
+hipError_t launch_buckets(const BucketArgs& a, hipStream_t st);
+
+// token draws through the buckets: one slab per tile, h rows gathered
+struct DrawGatherArgs {
+  const void* h;
+  long long ld_h;
+  const void* W;
+  int B, S, d, v, n, r;
+  const int* row_off;
+  const int* tile_off;
+  const int* list;
+  int* drafts;          // [B][S][n]
+  uint32_t seed_lo, seed_hi, offset;
+  int greedy;
+};
+hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t st);
+#ifndef MTPC_GATHER_TILE
+#define MTPC_GATHER_TILE 128
+#endif
+constexpr int DRAW_GATHER_TILE = MTPC_GATHER_TILE;   // rows per tile of the gathered draw kernel
 
 // Verification step of a speculative-decoding cycle (Alg. 2, acceptance loop on)
 struct VerifyArgs {

@@ -116,10 +116,15 @@ __device__ __forceinline__ int swz(int row) {
 
 // D = W_slab x h_tile^T for one workgroup; on return every wave holds its VB x PB
 // accumulator blocks and all waves have passed a barrier (the ring is free).
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+// GATHER: the tile's position rows are not consecutive: row p of the tile is row
+// rows[p] / rdiv of h (p < nrows <= TP, nrows >= 1; b0 is ignored and the whole of h,
+// which must span less than 4 GiB, is one resource).  32-row position blocks past nrows
+// are not multiplied (their accumulators stay zero), so a nearly empty tile is cheap.
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false>
 __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const void* hp, long long ld_h,
                                           int B, int d, int v, int slab, int b0, char* smem,
-                                          f32x16_t (&acc)[PB][VB]) {
+                                          f32x16_t (&acc)[PB][VB], const int* rows = nullptr, int nrows = 0,
+                                          int rdiv = 1) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
   constexpr int ESZ = BF16 ? 2 : 4;
   constexpr int CPR = TL::CPR, KS = TL::KS;
@@ -131,11 +136,13 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   // Lane offsets are relative to them and constant over K; the K advance is the
   // instruction's scalar offset.  Rows beyond v / B are clamped (in bounds; their
   // results are masked or never written).
-  const int hrows = min(B - b0, TL::TP);
+  const int hrows = GATHER ? nrows : min(B - b0, TL::TP);
+  const int hbase = GATHER ? 0 : b0;
+  const int hspan = GATHER ? B : hrows;
   const i32x4_t srdW = make_srd((const char*)Wp + (long long)slab * v * ld_w * ESZ,
                                 (unsigned)((long long)(v - 1) * ld_w * ESZ + (long long)d * ESZ));
-  const i32x4_t srdH = make_srd((const char*)hp + (long long)b0 * ld_h * ESZ,
-                                (unsigned)((long long)(hrows - 1) * ld_h * ESZ + (long long)d * ESZ));
+  const i32x4_t srdH = make_srd((const char*)hp + (long long)hbase * ld_h * ESZ,
+                                (unsigned)((long long)(hspan - 1) * ld_h * ESZ + (long long)d * ESZ));
   // wave-load q of this wave covers LDS rows RPL*wl .. RPL*wl+RPL-1 of every stage
   unsigned voff[TL::LPW];
 #pragma unroll
@@ -144,7 +151,11 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     const int row = wl * TL::RPL + lane / CPR;
     const int ch = (lane % CPR) ^ swz<CPR>(row);
     if (row < TL::TV) voff[q] = (unsigned)min(row, v - 1) * (unsigned)(ld_w * ESZ) + ch * 16;
-    else voff[q] = (unsigned)min(row - TL::TV, hrows - 1) * (unsigned)(ld_h * ESZ) + ch * 16;
+    else {
+      int hr = min(row - TL::TV, hrows - 1);
+      if constexpr (GATHER) hr = min(max(rows[hr] / rdiv, 0), B - 1);
+      voff[q] = (unsigned)hr * (unsigned)(ld_h * ESZ) + ch * 16;
+    }
   }
   const unsigned lds0 = (unsigned)(size_t)smem;
   unsigned kofs = 0;                                 // byte offset along K of the next stage to issue
@@ -186,6 +197,9 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   // pipe; one behind each MFMA disappears in that MFMA's shadow.  Reads are issued
   // in the order the next substep consumes them.
   i32x4_t fa[2][VB], fb[2][PB];
+  bool act[PB];                                      // wave-uniform: position block holds rows
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) act[pb] = !GATHER || (wb * PB + pb) * 32 < hrows;
   constexpr int NM = PB * VB;                        // MFMAs per substep
   constexpr int NR = VB + PB;                        // fragment reads per substep
   constexpr int LPS = (TL::LPW + KS - 1) / KS;       // direct-to-LDS loads per substep
@@ -202,7 +216,7 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   auto substep = [&](int cs, int ks, const char* nsrc, int nks, int ns, int buf) {
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      mma_step<BF16>(acc[m / VB][m % VB], fa[cs][m % VB], fb[cs][m / VB]);
+      if (!GATHER || act[m / VB]) mma_step<BF16>(acc[m / VB][m % VB], fa[cs][m % VB], fb[cs][m / VB]);
 #pragma unroll
       for (int o = 0; o < NOPS; ++o) {
         if ((o * NM) / NOPS != m) continue;          // op o rides behind MFMA o*NM/NOPS

@@ -17,6 +17,112 @@
 
 namespace mtpc {
 
+// ---- token draws on a finished tile -------------------------------------------------------
+// A wave holds exp(l - max) of one position in vocabulary order, VPL consecutive tokens per
+// lane (`vals`), `ls` their sum, `incl` the inclusive scan of ls over lanes, Z the total.
+// Inverse CDF (Alg. 1): the smallest k with u * Z < cdf[k]; if rounding leaves u * Z >= Z,
+// the last token with positive mass.  Returns the token in the lane for which `writer` is set.
+template <int VPL>
+__device__ __forceinline__ int wave_draw_token(const float (&vals)[VPL], float ls, float incl, float Z, float u,
+                                               int lane, bool& writer) {
+  const float tgt = u * Z;
+  const unsigned long long cross = __ballot(tgt < incl);
+  if (cross != 0ull) {
+    const int L = __ffsll((long long)cross) - 1;
+    float run = incl - ls;
+    int tok = lane * VPL + VPL - 1;
+    bool found = false;
+#pragma unroll
+    for (int q = 0; q < VPL; ++q) {
+      run += vals[q];
+      if (!found && tgt < run) { tok = lane * VPL + q; found = true; }
+    }
+    writer = lane == L;
+    return tok;
+  }
+  int last = -1;
+#pragma unroll
+  for (int q = 0; q < VPL; ++q)
+    if (vals[q] > 0.f) last = lane * VPL + q;
+  const unsigned long long pos = __ballot(last >= 0);
+  writer = lane == 63 - __clzll((long long)pos);
+  return last;
+}
+
+// the most likely token of the position a wave holds (ties: the smallest id); all lanes get it
+template <int VPL>
+__device__ __forceinline__ int wave_argmax_token(const float (&vals)[VPL], int lane) {
+  float best = -1.f;
+  int arg = 0;
+#pragma unroll
+  for (int q = 0; q < VPL; ++q)
+    if (vals[q] > best) { best = vals[q]; arg = lane * VPL + q; }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const float ob = __shfl_xor(best, o);
+    const int oa = __shfl_xor(arg, o);
+    if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+  }
+  return arg;
+}
+
+// Draw stage of a tile whose LSE statistics are known.  The tile-local positions that draw
+// are listed in LDS (s_list[0..cnt), written before the preceding barrier).  NSL positions
+// at a time: their accumulator columns are dumped as exp(l - max) in vocabulary order into
+// the (now free) stage buffers, then one wave per position scans its row and calls
+// body(p, vals, ls, incl, Z).
+template <class TL, int VB, int PB, int NSL, class Body>
+__device__ __forceinline__ void tile_draws(const f32x16_t (&acc)[PB][VB], const float (&mx)[PB], int v, char* smem,
+                                           int cnt, Body body) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wv = wave % (TL::TV / (VB * 32)), wb = wave / (TL::TV / (VB * 32));
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int rbase = wv * VB * 32 + 4 * lhalf;
+  int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
+  int* s_slot = s_list + TL::TP;
+  float* probs = (float*)smem;
+  static_assert(NSL * TL::VPL * 64 * 4 <= TL::RED_OFF, "draw buffer must fit in the stage buffers");
+  for (int c0 = 0; c0 < cnt; c0 += NSL) {
+    const int nsl = min(NSL, cnt - c0);
+    for (int p = tid; p < TL::TP; p += TL::NT) s_slot[p] = -1;
+    __syncthreads();
+    if (tid < nsl) s_slot[s_list[c0 + tid]] = tid;
+    __syncthreads();
+#pragma unroll
+    for (int pb = 0; pb < PB; ++pb) {
+      const int sl = s_slot[wb * PB * 32 + pb * 32 + l31];
+      if (sl >= 0) {
+#pragma unroll
+        for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+            probs[sl * (TL::VPL * 64) + row] = (row < v) ? expf(acc[pb][vb][i] - mx[pb]) : 0.f;
+          }
+      }
+    }
+    __syncthreads();
+    for (int k = wave; k < nsl; k += TL::NW) {
+      float vals[TL::VPL];
+      float ls = 0.f;
+#pragma unroll
+      for (int q = 0; q < TL::VPL; ++q) {
+        vals[q] = probs[k * (TL::VPL * 64) + lane * TL::VPL + q];
+        ls += vals[q];
+      }
+      float incl = ls;   // inclusive scan over lanes
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const float t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+      }
+      const float Z = __shfl(incl, 63);
+      body(s_list[c0 + k], vals, ls, incl, Z);
+    }
+    __syncthreads();
+  }
+}
+
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_unembed(const UnembedArgs a) {
@@ -45,9 +151,11 @@ void k_unembed(const UnembedArgs a) {
     for (int pb = 0; pb < PB; ++pb) {
       const int b = b0 + wb * PB * 32 + pb * 32 + l31;
       if (b < a.B) {
-        for (int t = 0; t < a.T; ++t) {
-          const long long rowid = (long long)b * a.T + t;
-          const int x = a.targets[rowid * a.n + wi];
+        const int TT = a.T + a.T2;
+        for (int t = 0; t < TT; ++t) {
+          const long long rowid = (long long)b * TT + t;
+          const int x = t < a.T ? a.targets[((long long)b * a.T + t) * a.n + wi]
+                                : a.targets2[((long long)b * a.T2 + (t - a.T)) * a.n + wi];
           float* dst = a.e + (rowid * a.n + wi) * a.r + wj;
           if (x < 0 || x >= a.v) {
             if (wv == 0 && lhalf == 0) *dst = (x == -1) ? 0.f : __builtin_nanf("");
@@ -116,8 +224,6 @@ void k_unembed(const UnembedArgs a) {
     int* misc = (int*)(smem + TL::MISC_OFF);
     int* s_cnt = misc;
     int* s_list = misc + 4;
-    int* s_slot = s_list + TL::TP;
-    float* probs = (float*)smem;   // stage buffers are free now
     if (tid == 0) *s_cnt = 0;
     __syncthreads();
     for (int p = tid; p < TL::TP; p += TL::NT) {
@@ -130,96 +236,119 @@ void k_unembed(const UnembedArgs a) {
     }
     __syncthreads();
     const int cnt = *s_cnt;
-    for (int c0 = 0; c0 < cnt; c0 += NSLOT) {
-      const int nsl = min(NSLOT, cnt - c0);
-      for (int p = tid; p < TL::TP; p += TL::NT) s_slot[p] = -1;
-      __syncthreads();
-      if (tid < nsl) s_slot[s_list[c0 + tid]] = tid;
-      __syncthreads();
-      // dump exp(l - max) of the selected positions in vocabulary order
-#pragma unroll
-      for (int pb = 0; pb < PB; ++pb) {
-        const int sl = s_slot[wb * PB * 32 + pb * 32 + l31];
-        if (sl >= 0) {
-#pragma unroll
-          for (int vb = 0; vb < VB; ++vb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-              probs[sl * (TL::VPL * 64) + row] = (row < a.v) ? expf(acc[pb][vb][i] - mx[pb]) : 0.f;
-            }
+    tile_draws<TL, VB, PB, NSLOT>(acc, mx, a.v, smem, cnt, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
+                                                        float Z) {
+      const int b = b0 + p;
+      for (int s = 0; s < a.S; ++s) {
+        const long long di = ((long long)b * a.S + s) * a.n + wi;
+        if (a.zleaf[di] != wj) continue;
+        int tok;
+        bool writer;
+        if (a.greedy) {
+          tok = wave_argmax_token<TL::VPL>(vals, lane);
+          writer = lane == 0;
+        } else {
+          const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)s, (uint32_t)wi);
+          tok = wave_draw_token<TL::VPL>(vals, ls, incl, Z, u, lane, writer);
         }
+        if (writer) a.drafts[di] = tok;
       }
-      __syncthreads();
-      for (int k = wave; k < nsl; k += TL::NW) {
-        const int p = s_list[c0 + k];
-        const int b = b0 + p;
-        float vals[TL::VPL];
-        float ls = 0.f;
-#pragma unroll
-        for (int q = 0; q < TL::VPL; ++q) {
-          vals[q] = probs[k * (TL::VPL * 64) + lane * TL::VPL + q];
-          ls += vals[q];
-        }
-        float incl = ls;   // inclusive scan over lanes
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const float t = __shfl_up(incl, o);
-          if (lane >= o) incl += t;
-        }
-        const float Z = __shfl(incl, 63);
-        for (int s = 0; s < a.S; ++s) {
-          const long long di = ((long long)b * a.S + s) * a.n + wi;
-          if (a.zleaf[di] != wj) continue;
-          if (a.greedy) {
-            // the most likely token of this input unit; ties: the smallest id
-            float best = -1.f;
-            int arg = 0;
-#pragma unroll
-            for (int q = 0; q < TL::VPL; ++q)
-              if (vals[q] > best) { best = vals[q]; arg = lane * TL::VPL + q; }
-#pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) {
-              const float ob = __shfl_xor(best, o);
-              const int oa = __shfl_xor(arg, o);
-              if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
-            }
-            if (lane == 0) a.drafts[di] = arg;
-            continue;
-          }
-          const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)s,
-                                         (uint32_t)wi);
-          const float tgt = u * Z;
-          const unsigned long long cross = __ballot(tgt < incl);
-          int tok;
-          if (cross != 0ull) {
-            const int L = __ffsll((long long)cross) - 1;
-            float run = incl - ls;
-            tok = lane * TL::VPL + TL::VPL - 1;
-            bool found = false;
-#pragma unroll
-            for (int q = 0; q < TL::VPL; ++q) {
-              run += vals[q];
-              if (!found && tgt < run) { tok = lane * TL::VPL + q; found = true; }
-            }
-            if (lane == L) a.drafts[di] = tok;
-          } else {
-            // rounding left u*Z >= total: the last token with positive mass
-            int last = -1;
-#pragma unroll
-            for (int q = 0; q < TL::VPL; ++q)
-              if (vals[q] > 0.f) last = lane * TL::VPL + q;
-            const unsigned long long pos = __ballot(last >= 0);
-            const int L = 63 - __clzll((long long)pos);
-            if (lane == L) a.drafts[di] = last;
-          }
-        }
-      }
-      __syncthreads();
-    }
+    });
   }
 }
 
+#ifndef MTPC_GATHER_NSL
+#define MTPC_GATHER_NSL 16
+#endif
+#ifndef MTPC_GATHER_NS
+#define MTPC_GATHER_NS 4
+#endif
+// Token draws of Alg. 1 for training-sized batches: only the input unit a token is drawn
+// from is evaluated.  The (b, s, i) triples were bucketed by (i, z) = (token, selected
+// unit); a workgroup takes up to TP rows of one bucket, gathers their h rows, multiplies
+// them with the one slab W[i][z] and draws every row's token - 1/r of the products a
+// pass over all slabs needs.
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+__global__ __launch_bounds__(WV * WB * 64)
+void k_draw_gather(const DrawGatherArgs a) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  // each XCD owns a contiguous range of logical tiles, so that the tiles of a bucket
+  // (which share a W slab) run under one L2
+  const int per = (int)gridDim.x >> 3;
+  const int w = blockIdx.x;
+  const int lid = (w < per * 8) ? (w & 7) * per + (w >> 3) : w;
+  const int ngroups = a.n * a.r;
+  if (lid >= a.tile_off[ngroups]) return;            // the grid is an upper bound
+  int lo = 0, hi = ngroups - 1;                      // the bucket g with tile_off[g] <= lid < tile_off[g+1]
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (a.tile_off[mid] <= lid) lo = mid; else hi = mid - 1;
+  }
+  const int g = lo;
+  const int first = a.row_off[g] + (lid - a.tile_off[g]) * TL::TP;
+  const int nrows = min(a.row_off[g + 1] - first, TL::TP);     // >= 1 by construction of tile_off
+  const int* rows = a.list + first;
+  const int wi = g / a.r;
+
+  f32x16_t acc[PB][VB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, true>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, g, 0, smem, acc, rows, nrows, a.S);
+  float mx[PB], lse[PB];
+  tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
+
+  int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
+  for (int p = tid; p < nrows; p += TL::NT) s_list[p] = p;
+  __syncthreads();
+  tile_draws<TL, VB, PB, MTPC_GATHER_NSL>(acc, mx, a.v, smem, nrows, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
+                                                        float Z) {
+    const int rid = rows[p];                         // b * S + s
+    const int b = rid / a.S, s = rid - b * a.S;
+    int tok;
+    bool writer;
+    if (a.greedy) {
+      tok = wave_argmax_token<TL::VPL>(vals, lane);
+      writer = lane == 0;
+    } else {
+      const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)s, (uint32_t)wi);
+      tok = wave_draw_token<TL::VPL>(vals, ls, incl, Z, u, lane, writer);
+    }
+    if (writer) a.drafts[(long long)rid * a.n + wi] = tok;
+  });
+}
+
+template <int WV, int WB, int VB, int PB, bool BF16>
+static hipError_t launch_draw_gather_cfg(const DrawGatherArgs& a, hipStream_t st) {
+  using TL = Tile<WV, WB, VB, PB, 64, MTPC_GATHER_NS>;
+  static_assert(TL::TP == DRAW_GATHER_TILE, "the bucketing kernels count tiles of this many rows");
+  auto kern = k_draw_gather<WV, WB, VB, PB, 64, MTPC_GATHER_NS, BF16>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const long long rows = (long long)a.B * a.S * a.n;
+  const int grid = (int)(rows / TL::TP) + a.n * a.r;             // >= sum over buckets of ceil(rows_g / TP)
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(TL::NT), TL::SMEM, st, a);
+  return hipGetLastError();
+}
+
+template <bool BF16>
+static hipError_t launch_draw_gather_dt(const DrawGatherArgs& a, hipStream_t st) {
+  constexpr int PB = DRAW_GATHER_TILE / 128;
+  if (a.v > 256) return launch_draw_gather_cfg<2, 4, 5, PB, BF16>(a, st);
+  if (a.v > 128) return launch_draw_gather_cfg<2, 4, 4, PB, BF16>(a, st);
+  return launch_draw_gather_cfg<2, 4, 2, PB, BF16>(a, st);
+}
+
+hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t st) {
+  return dtype == MTPC_BF16 ? launch_draw_gather_dt<true>(a, st) : launch_draw_gather_dt<false>(a, st);
+}
+
+#ifndef MTPC_SUMUNIT_SB
+#define MTPC_SUMUNIT_SB 128
+#endif
 // Sum-unit parameters for many positions (Sec. 3.3): log omega[b,:] =
 // log_softmax(Wsum h[b]).  Same tile machinery with Wsum as the only "slab" (r rows)
 // and narrow position tiles, so that B/32 workgroups share the work.
@@ -251,14 +380,30 @@ void k_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int 
   }
 }
 
-template <bool BF16>
-static hipError_t launch_sumunit_mfma_dt(const void* h, long long ld_h, const void* Wsum, int B, int d,
-                                         int r, float* logw, hipStream_t st) {
-  using TL = Tile<2, 1, 2, 1, 64, 4>;      // 128 rows (r <= 128) x 32 positions, 2 waves
-  auto kern = k_sumunit_mfma<2, 1, 2, 1, 64, 4, BF16>;
+template <int SB, bool BF16>
+static hipError_t launch_sumunit_mfma_cfg(const void* h, long long ld_h, const void* Wsum, int B, int d,
+                                          int r, float* logw, hipStream_t st) {
+  using TL = Tile<2, 1, 2, 1, SB, 4>;      // 128 rows (r <= 128) x 32 positions, 2 waves
+  auto kern = k_sumunit_mfma<2, 1, 2, 1, SB, 4, BF16>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
   hipLaunchKernelGGL(kern, dim3((B + TL::TP - 1) / TL::TP), dim3(TL::NT), TL::SMEM, st, h, ld_h, Wsum, B,
                      d, r, logw);
   return hipGetLastError();
+}
+
+// The kernel streams h once with one small workgroup per 32 positions, so what limits it is
+// the number of bytes it keeps in flight: 128-byte stages when the rows allow it.
+template <bool BF16>
+static hipError_t launch_sumunit_mfma_dt(const void* h, long long ld_h, const void* Wsum, int B, int d,
+                                         int r, float* logw, hipStream_t st) {
+  if ((d * (BF16 ? 2 : 4)) % MTPC_SUMUNIT_SB == 0)
+    return launch_sumunit_mfma_cfg<MTPC_SUMUNIT_SB, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
+  return launch_sumunit_mfma_cfg<64, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
 }
 
 hipError_t launch_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,

@@ -21,7 +21,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported():
     from paper_2511_11346_amd import binding
     names = declared_symbols()
-    assert len(names) == 32 and sorted(binding.EXPORTS) == names
+    assert len(names) == 36 and sorted(binding.EXPORTS) == names
     L = C.CDLL(LIB)
     for n in names:
         assert hasattr(L, n), n
@@ -87,6 +87,14 @@ def test_argument_errors_are_reported_without_launching():
     assert L.mtpc_cp_table_scores(C.byref(_head()), out, tg, 1, 2, out) == UNSUP
     assert L.mtpc_cp_table_scores(C.byref(_head(workspace_bytes=16)), out, tg, 1, 0, out) == WS
     assert L.mtpc_btree_table_scores(C.byref(_head()), None, out, tg, 1, 0, out) == NULL
+    # several windows per position in one pass
+    assert L.mtpc_cp_window_scores(C.byref(_head()), None, 1, None, 0, 0, out) == NULL
+    assert L.mtpc_cp_window_scores(C.byref(_head()), tg, 1, None, 2, 0, out) == NULL
+    assert L.mtpc_cp_window_scores(C.byref(_head()), tg, 0, None, 0, 0, out) == SHAPE
+    assert L.mtpc_cp_window_scores(C.byref(_head()), tg, 1, tg, -1, 0, out) == SHAPE
+    assert L.mtpc_cp_window_scores(C.byref(_head()), tg, 1, None, 0, 3, out) == UNSUP
+    assert L.mtpc_cp_window_scores(C.byref(_head(workspace_bytes=16)), tg, 1, tg, 1, 1, out) == WS
+    assert L.mtpc_hmm_window_scores(C.byref(_head()), None, tg, 1, None, 0, 0, out) == NULL
     # greedy draft and training step
     assert L.mtpc_cp_greedy_draft(C.byref(_head()), None, None, None, None) == NULL
     assert L.mtpc_cp_greedy_draft(C.byref(_head(workspace_bytes=16)), tg, None, None, None) == WS

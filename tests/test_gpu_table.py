@@ -1,6 +1,8 @@
-"""GPU parity of the operations that work from the table of normalised input units
-log phi[B][n][r][v]: scores of arbitrary windows (log-likelihood / prefix marginals without
-another pass over W) and, for training-sized batches, the token draws of Alg. 1 read from it."""
+"""GPU parity of the operations on several windows per position and on the table of
+normalised input units log phi[B][n][r][v]: scores of arbitrary windows from the table
+(log-likelihood / prefix marginals without another pass over W) or from W in one pass, and
+the two ways training-sized batches draw their tokens (Alg. 1): from the table when the
+caller keeps it, else through buckets of (token, selected input unit)."""
 import numpy as np
 import pytest
 import torch
@@ -94,12 +96,40 @@ def test_draws_from_the_table_match_the_oracle(family, dtype, B, d, n, r, v, ctx
         ps = oc.prefix_marginals_from(family, logphi, logw, loglayers, gdn[:, s])
         tol_check(gp[:, s].cpu().numpy(), ps, dtype, "draft prefix scores")
 
-    # greedy draft through the same table path
+    # without the table the same draws go through the buckets
+    gd3, gl3, gp3 = head.sample(S, seed=seed, offset=off, want_prefix=True)
+    near3, _ = compare_drafts(gd3, gl3, od, ol, margin)
+    assert near3 == near
+    for s in range(S):
+        ps = oc.prefix_marginals_from(family, logphi, logw, loglayers, gd3.cpu().numpy()[:, s])
+        tol_check(gp3[:, s].cpu().numpy(), ps, dtype, "draft prefix scores (bucket path)")
+
+    # greedy draft through both paths
     want_d, want_l, gap = sp.greedy_draft(family, logphi, logw, loglayers)
-    g2, l2, p2 = head.greedy_draft(want_prefix=True, logphi=table)
     safe = gap >= 1e-6
-    assert np.array_equal(g2.cpu().numpy()[safe], want_d[safe])
-    if l2 is not None and want_l.shape[1]:
-        assert np.array_equal(l2.cpu().numpy()[safe], want_l[safe])
-    tol_check(p2.cpu().numpy(), oc.prefix_marginals_from(family, logphi, logw, loglayers, g2.cpu().numpy()),
-              dtype, "scores of the greedy draft")
+    for tab in (table, None):
+        g2, l2, p2 = head.greedy_draft(want_prefix=True, logphi=tab)
+        assert np.array_equal(g2.cpu().numpy()[safe], want_d[safe])
+        if l2 is not None and want_l.shape[1]:
+            assert np.array_equal(l2.cpu().numpy()[safe], want_l[safe])
+        tol_check(p2.cpu().numpy(), oc.prefix_marginals_from(family, logphi, logw, loglayers, g2.cpu().numpy()),
+                  dtype, "scores of the greedy draft")
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r,v,ctx", CASES)
+def test_window_scores_match_the_oracle(family, dtype, B, d, n, r, v, ctx):
+    """Two sets of windows per position scored in one unembedding pass."""
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=700 + B + r, h_scale=1.0,
+                         contextual=ctx)
+    head = make_head(inp)
+    logphi, logw, loglayers = oracle_params(inp)
+    x = windows(inp, 3, 23)
+    xa = torch.from_numpy(np.ascontiguousarray(x[:, :2])).cuda()
+    xb = torch.from_numpy(np.ascontiguousarray(x[:, 2:])).cuda()
+    want_P = np.stack([oc.prefix_marginals_from(family, logphi, logw, loglayers, x[:, t]) for t in range(3)], axis=1)
+    want_L = np.stack([oc.joint(family, oc.evidence(logphi, x[:, t]), logw, loglayers) for t in range(3)], axis=1)
+    tol_check(head.window_scores(xa, xb, prefix=True).cpu().numpy(), want_P, dtype, "prefix scores of two window sets")
+    tol_check(head.window_scores(xa, xb).cpu().numpy(), want_L, dtype, "log-likelihoods of two window sets")
+    tol_check(head.window_scores(xb).cpu().numpy(), want_L[:, 2:], dtype, "log-likelihoods of one window set")
+    # one window per position: the very numbers of the loglik call
+    assert torch.equal(head.window_scores(xb)[:, 0].nan_to_num(7.0), head.loglik(xb[:, 0].contiguous()).nan_to_num(7.0))
