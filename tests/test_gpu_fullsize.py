@@ -51,6 +51,14 @@ def check_rows(inp, head, rows, S=0, seed=0):
         for s in range(S):
             ps = oc.prefix_marginals_from(inp.family, logphi, logw, loglayers, gdn[rows, s])
             tol_check(gp[rows, s].cpu().numpy(), ps, inp.dtype, "draft scores")
+        # the step bench.py times: drafts alone, then targets and drafts scored in one fused pass
+        gd2, _, _ = head.sample(S, seed=seed)
+        assert torch.equal(gd2, gd)
+        both = head.window_scores(tg.view(inp.B, 1, inp.n), gd2, prefix=True).cpu().numpy()
+        tol_check(both[rows, 0], want, inp.dtype, "prefix marginals of the targets (fused with the drafts)")
+        for s in range(S):
+            ps = oc.prefix_marginals_from(inp.family, logphi, logw, loglayers, gdn[rows, s])
+            tol_check(both[rows, 1 + s], ps, inp.dtype, "draft scores (fused with the targets)")
 
 
 def test_config2_ff_and_cp16_full_size():
