@@ -273,20 +273,23 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   la.latents = latents ? latents : (int*)(ws + p.lat);
   HIP_TRY(launch_latents(la, st));
 
-  UnembedArgs u{};
-  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
-  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
-  u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
-  u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset; u.greedy = greedy;
-  // how the tokens are drawn and the drafts scored (see decode_sized)
+  // Where the tokens are drawn (see decode_sized):
+  //   InKernel  - in the epilogue of the fused kernel, which evaluates every slab
+  //   Buckets   - k_draw_gather on the one slab each token needs
+  //   FromTable - the fused kernel only writes the caller's table, k_draw_table reads it
+  // and how the drafts are scored: from the table when there is one, else by one more
+  // fused pass with the drafts as targets.
+  enum class Draw { InKernel, Buckets, FromTable };
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
-  const bool big = !decode_sized(hd);
   const bool span_ok = (unsigned long long)hd->B * (unsigned long long)hd->ld_h * esz <= 0xffffffffull;
-  const bool use_buckets = big && !logphi && span_ok;
-  const bool gather = want_prefix && (logphi != nullptr || !big);      // scores read from the table
-  u.logphi = logphi ? logphi : (gather ? (float*)(ws + p.table) : nullptr);
-  const bool draw_from_table = big && logphi != nullptr;
-  if (use_buckets) {
+  const Draw draw = decode_sized(hd) ? Draw::InKernel
+                    : logphi         ? Draw::FromTable
+                    : span_ok        ? Draw::Buckets      // the gather addresses h through one 4 GiB resource
+                                     : Draw::InKernel;
+  const bool table_scores = want_prefix && (logphi != nullptr || decode_sized(hd));
+  float* table = logphi ? logphi : (table_scores ? (float*)(ws + p.table) : nullptr);
+
+  if (draw == Draw::Buckets) {
     BucketArgs bk{};
     bk.B = hd->B; bk.S = S; bk.n = hd->n; bk.r = hd->r; bk.tile = DRAW_GATHER_TILE;
     bk.zleaf = la.zleaf;
@@ -300,38 +303,41 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     dg.row_off = bk.row_off; dg.tile_off = bk.tile_off; dg.list = bk.list; dg.drafts = drafts;
     dg.seed_lo = seed_lo; dg.seed_hi = seed_hi; dg.offset = offset; dg.greedy = greedy;
     HIP_TRY(launch_draw_gather(dg, hd->dtype, st));
-  } else if (draw_from_table) {
-    // the caller keeps the table: the fused kernel only normalises and stores, and the
-    // draws read one table row each
-    u.zleaf = nullptr;
-  }
-  {
-    if (!use_buckets) {
+  } else {
+    UnembedArgs u{};
+    u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
+    u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+    u.logphi = table;
+    if (draw == Draw::InKernel) {
+      u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
+      u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset; u.greedy = greedy;
+    }
+    {
       ProfScope prof(st);
       HIP_TRY(launch_unembed(u, hd->dtype, st));
     }
-    if (draw_from_table) {
+    if (draw == Draw::FromTable) {
       DrawArgs dr{};
       dr.B = hd->B; dr.S = S; dr.v = hd->v; dr.n = hd->n; dr.r = hd->r;
-      dr.logphi = u.logphi; dr.zleaf = la.zleaf; dr.drafts = drafts;
+      dr.logphi = table; dr.zleaf = la.zleaf; dr.drafts = drafts;
       dr.seed_lo = seed_lo; dr.seed_hi = seed_hi; dr.offset = offset; dr.greedy = greedy;
       HIP_TRY(launch_draw_table(dr, st));
     }
-    if (want_prefix && !gather) {
-      UnembedArgs u2{};
-      u2.h = hd->h; u2.ld_h = hd->ld_h; u2.W = hd->W;
-      u2.B = hd->B; u2.d = hd->d; u2.v = hd->v; u2.n = hd->n; u2.r = hd->r;
-      u2.targets = drafts; u2.T = S; u2.e = (float*)(ws + p.e);
-      ProfScope prof(st);
-      HIP_TRY(launch_unembed(u2, hd->dtype, st));
-    }
+  }
+  if (want_prefix && !table_scores) {
+    UnembedArgs u2{};
+    u2.h = hd->h; u2.ld_h = hd->ld_h; u2.W = hd->W;
+    u2.B = hd->B; u2.d = hd->d; u2.v = hd->v; u2.n = hd->n; u2.r = hd->r;
+    u2.targets = drafts; u2.T = S; u2.e = (float*)(ws + p.e);
+    ProfScope prof(st);
+    HIP_TRY(launch_unembed(u2, hd->dtype, st));
   }
   if (want_prefix) {
-    if (gather) {
+    if (table_scores) {
       GatherArgs g{};
       g.B = hd->B; g.S = S; g.v = hd->v; g.n = hd->n; g.r = hd->r;
       g.x = drafts; g.e = (float*)(ws + p.e);
-      HIP_TRY(launch_gather_table(g, u.logphi, st));
+      HIP_TRY(launch_gather_table(g, table, st));
     }
     HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * S, S, prefix_logq, 1), st));
   }
