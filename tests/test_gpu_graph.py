@@ -56,3 +56,46 @@ def test_decode_cycle_replays_from_a_graph(family):
         assert torch.equal(table_g, table), k
         head.loglik(tg)                                    # eager work on the same head and workspace
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("family", ["cp", "hmm"])
+def test_training_sized_step_replays_from_a_graph(family):
+    """Drafts through the buckets (their counters are cleared by a kernel, atomics decide only
+    the order inside a bucket) and the fused scoring of targets and drafts."""
+    B, n, r, v = 300, 4, 8, 268
+    inp = mi.make_inputs(family, B=B, d=256, n=n, r=r, v=v, dtype="bf16", seed=43, h_scale=1.0)
+    head = make_head(inp)
+    dev = "cuda"
+    tg = torch.from_numpy(inp.targets).cuda().view(B, 1, n)
+    nl = {"cp": 1, "hmm": n}[family]
+
+    def buffers():
+        return ((torch.empty(B, 2, n, dtype=torch.int32, device=dev), torch.empty(B, 2, nl, dtype=torch.int32, device=dev), None),
+                torch.empty(B, 3, n, dtype=torch.float32, device=dev))
+
+    def step(out, P):
+        d, _, _ = head.sample(2, seed=8, offset=1, out=out)
+        head.window_scores(tg, d, prefix=True, out=P)
+
+    out_e, P_e = buffers()
+    step(out_e, P_e)
+    torch.cuda.synchronize()
+    out_g, P_g = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(out_g, P_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(out_g, P_g)
+    for k in range(4):
+        out_g[0].zero_()
+        P_g.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g[0], out_e[0]) and torch.equal(out_g[1], out_e[1]), k
+        assert torch.equal(P_g, P_e), k
+        head.loglik(tg[:, 0].contiguous())                 # eager work on the same head and workspace
+        torch.cuda.synchronize()
