@@ -266,6 +266,14 @@ def main():
             ms_table = time_op(lambda: hd.sample(1, seed=0, offset=0, out=o, logphi=table), reps)
             ms_verify = time_op(lambda: hd.verify(dr, pver, prefix_logq=sc, logphi=table, seed=1, offset=1), reps)
             acc, _ = hd.verify(dr, pver, prefix_logq=sc, logphi=table, seed=1, offset=1)
+            # the workload's other reading of "16 verified prefixes per draft": 16 prefixes of random
+            # length of each draft (later variables summed out), scored from the table
+            gen = torch.Generator().manual_seed(16)
+            lens = torch.randint(1, inp5.n + 1, (Bd, 16), generator=gen).to(dev)
+            x16 = dr[:, None, :].repeat(1, 16, 1)
+            x16[torch.arange(inp5.n, device=dev)[None, None, :] >= lens[:, :, None]] = -1
+            x16 = x16.contiguous()
+            ms_16 = time_op(lambda: hd.table_scores(table, x16), reps)
             # the same cycle (draft + scores + table, verification) replayed from a HIP graph
             def cycle():
                 hd.sample(1, seed=0, offset=0, out=o, logphi=table)
@@ -285,7 +293,7 @@ def main():
                         "k_unembed_ms": kms, "achieved_GBps": byts / (kms * 1e-3) / 1e9,
                         "frac_of_hbm_peak": byts / (kms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
                         "call_ms_keeping_table": ms_table, "verify_call_ms": ms_verify,
-                        "cycle_ms_from_graph": ms_graph,
+                        "cycle_ms_from_graph": ms_graph, "score_16_prefixes_per_draft_ms": ms_16,
                         "mean_accepted": float(acc.float().mean())})
         out["decode_cp_r32_n16"] = dec
 

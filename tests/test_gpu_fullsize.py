@@ -106,6 +106,16 @@ def test_config5_decode_draft_and_score(B):
     inp = mi.config5(B=B)
     head = make_head(inp)
     check_rows(inp, head, np.arange(B), S=1, seed=0)
+    # 16 prefixes of random length per draft, scored from the table the sampling call keeps
+    table = torch.empty(B, inp.n, inp.r, inp.v, dtype=torch.float32, device="cuda")
+    gd, _, gp = head.sample(1, seed=0, want_prefix=True, logphi=table)
+    lens = np.random.default_rng(B).integers(1, inp.n + 1, size=(B, 16))
+    x16 = np.repeat(gd.cpu().numpy()[:, :1, :], 16, axis=1)
+    x16[np.arange(inp.n)[None, None, :] >= lens[:, :, None]] = -1
+    got = head.table_scores(table, torch.from_numpy(x16).cuda()).cpu().numpy()
+    logphi, logw, loglayers = oc._params(inp.family, inp.h, inp.W, inp.Wsum, inp.layers)
+    P = oc.prefix_marginals_from(inp.family, logphi, logw, loglayers, gd.cpu().numpy()[:, 0])
+    tol_check(got, np.take_along_axis(P, lens - 1, axis=1), inp.dtype, "16 prefixes per draft")
 
 
 def test_config5_decode_cycle_with_verification():
