@@ -1008,7 +1008,7 @@ __global__ __launch_bounds__(256) void k_bucket_offsets(const BucketArgs a) {
   __shared__ int s_rows[256], s_tiles[256];
   const int ng = a.n * a.r, tid = threadIdx.x;
   const int per = (ng + 255) / 256;                  // consecutive buckets per thread
-  const int g0 = tid * per, g1 = min(g0 + per, ng);
+  const int g0 = min(tid * per, ng), g1 = min(g0 + per, ng);
   int rows = 0, tiles = 0;
   for (int g = g0; g < g1; ++g) {
     const int c = a.count[g];
