@@ -19,7 +19,8 @@
  *  - Row-major, innermost axis contiguous.  h, W, Wsum share `dtype`
  *    (fp32, or bf16 with fp32 accumulation); all results are fp32 / int32.
  *  - h, W, Wsum and workspace must be 16-byte aligned; ld_h (row stride of h in
- *    elements) must keep rows 16-byte aligned.
+ *    elements) must keep rows 16-byte aligned and span at most 16 MiB; a row of W
+ *    (d elements) at most 8 MiB.
  *  - Supported sizes: 1 <= B; d a multiple of 32; 1 <= n <= 64; 1 <= r <= 128;
  *    1 <= v <= 320.  Anything else returns MTPC_ERR_UNSUPPORTED.
  *  - On any error nothing is launched and outputs are untouched.  Outputs are

@@ -59,6 +59,9 @@ mtpc_status check_head(int family, const mtpc_head* hd) {
   if (((uintptr_t)hd->h | (uintptr_t)hd->W | (uintptr_t)hd->Wsum) & 15) return MTPC_ERR_UNSUPPORTED;
   if (((size_t)hd->ld_h * esz) & 15) return MTPC_ERR_UNSUPPORTED;
   if ((long long)hd->n * hd->r * hd->v > 0x7fffffffLL) return MTPC_ERR_UNSUPPORTED;
+  // a tile (up to 256 rows of h, 320 of W) is addressed through one 32-bit buffer resource
+  if ((unsigned long long)hd->ld_h * esz > (1ull << 24) || (unsigned long long)hd->d * esz > (1ull << 23))
+    return MTPC_ERR_UNSUPPORTED;
   return MTPC_OK;
 }
 

@@ -62,6 +62,7 @@ def test_argument_errors_are_reported_without_launching():
     assert L.mtpc_cp_loglik(C.byref(_head(r=129)), tg, out) == UNSUP
     assert L.mtpc_cp_loglik(C.byref(_head(dtype=7)), tg, out) == UNSUP
     assert L.mtpc_cp_loglik(C.byref(_head(h=0x1004)), tg, out) == UNSUP
+    assert L.mtpc_cp_loglik(C.byref(_head(ld_h=(1 << 23) + 8)), tg, out) == UNSUP     # rows of h further apart than 16 MiB
     assert L.mtpc_cp_loglik(C.byref(_head(workspace_bytes=16)), tg, out) == WS
     assert L.mtpc_cp_loglik(C.byref(_head(workspace=None)), tg, out) == NULL
     lay = binding.mtpc_sumlayers(0x6000, 4, 0)

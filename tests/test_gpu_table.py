@@ -133,3 +133,30 @@ def test_window_scores_match_the_oracle(family, dtype, B, d, n, r, v, ctx):
     tol_check(head.window_scores(xb).cpu().numpy(), want_L[:, 2:], dtype, "log-likelihoods of one window set")
     # one window per position: the very numbers of the loglik call
     assert torch.equal(head.window_scores(xb)[:, 0].nan_to_num(7.0), head.loglik(xb[:, 0].contiguous()).nan_to_num(7.0))
+
+
+def test_rows_of_h_spread_over_more_than_4_gib():
+    """h as a strided view whose rows lie 16 MiB apart: the gathered draw kernel addresses h
+    through one 32-bit resource and must not be used; the in-kernel draws take over."""
+    from paper_2511_11346_amd import Head
+    B, d, n, r, v = 300, 64, 4, 8, 268
+    inp = mi.make_inputs("hmm", B=B, d=d, n=n, r=r, v=v, dtype="bf16", seed=77, h_scale=1.0)
+    ld = 1 << 23                                               # elements: 16 MiB per row, 4.7 GiB in all
+    big = torch.zeros(B, ld, dtype=torch.bfloat16, device="cuda")
+    big[:, :d] = torch.from_numpy(inp.h_bits.copy()).view(torch.bfloat16).cuda()
+    as_dev = lambda bits: torch.from_numpy(bits.copy()).view(torch.bfloat16).cuda()
+    head = Head("hmm", big[:, :d], as_dev(inp.W_bits), as_dev(inp.Wsum_bits),
+                torch.from_numpy(inp.layers.astype(np.float32)).cuda())
+    logphi, logw, loglayers = oracle_params(inp)
+    S, seed = 2, 31
+    u = philox.uniforms(B, S, n + oc.n_latents("hmm", n), seed, 0)
+    od, ol, margin = oc.sample_from("hmm", logphi, logw, loglayers, u, with_margin=True)
+    gd, gl, gp = head.sample(S, seed=seed, want_prefix=True)
+    near, _ = compare_drafts(gd, gl, od, ol, margin)
+    assert near <= max(4, margin.size // 50)
+    for s in range(S):
+        ps = oc.prefix_marginals_from("hmm", logphi, logw, loglayers, gd.cpu().numpy()[:, s])
+        tol_check(gp[:, s].cpu().numpy(), ps, "bf16", "draft prefix scores")
+    tg = torch.from_numpy(inp.targets).cuda()
+    want = oc.joint("hmm", oc.evidence(logphi, inp.targets), logw, loglayers)
+    tol_check(head.loglik(tg).cpu().numpy(), want, "bf16", "loglik")
