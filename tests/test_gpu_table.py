@@ -160,3 +160,33 @@ def test_rows_of_h_spread_over_more_than_4_gib():
     tg = torch.from_numpy(inp.targets).cuda()
     want = oc.joint("hmm", oc.evidence(logphi, inp.targets), logw, loglayers)
     tol_check(head.loglik(tg).cpu().numpy(), want, "bf16", "loglik")
+
+
+@pytest.mark.parametrize("family,B,n,r,v,flat", [
+    ("cp", 300, 4, 8, 100, True),        # greedy with a flat mixture: every draft in bucket 0
+    ("hmm", 70, 3, 128, 64, False),      # far more buckets than rows: most are empty
+    ("btree", 513, 4, 2, 320, False),    # two units: buckets of a few hundred rows, ragged last tiles
+])
+def test_bucket_extremes(family, B, n, r, v, flat):
+    inp = mi.make_inputs(family, B=B, d=64, n=n, r=r, v=v, dtype="f32", seed=5 + B, h_scale=1.0)
+    if flat:
+        inp.Wsum[...] = 0.0
+    head = make_head(inp)
+    logphi, logw, loglayers = oracle_params(inp)
+    S, seed = 2, 99
+    u = philox.uniforms(B, S, n + oc.n_latents(family, n), seed, 0)
+    od, ol, margin = oc.sample_from(family, logphi, logw, loglayers, u, with_margin=True)
+    gd, gl, _ = head.sample(S, seed=seed)
+    near, _ = compare_drafts(gd, gl, od, ol, margin)
+    assert near <= max(4, margin.size // 50)
+    want_d, want_l, gap = sp.greedy_draft(family, logphi, logw, loglayers)
+    g2, l2, _ = head.greedy_draft()
+    if flat:
+        # the mixture is an exact tie (first index wins on both sides): only the token decisions count
+        assert np.all(l2.cpu().numpy() == 0) and np.all(want_l == 0)
+        top2 = np.sort(np.exp(logphi[:, :, 0, :]), axis=-1)[..., -2:]
+        safe = (top2[..., 1] - top2[..., 0]).min(axis=1) >= 1e-6
+        assert safe.sum() >= B // 2
+    else:
+        safe = gap >= 1e-6
+    assert np.array_equal(g2.cpu().numpy()[safe], want_d[safe])
