@@ -691,7 +691,171 @@ static hipError_t launch_btree_static(const CircuitArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Few rows (decode-sized calls): the HMM chain and the binary tree are chains of
+// dependent r x r products, and with one group per row every product waits for its
+// layer to come from L2.  Here ONE WORKGROUP owns a row: all layers of the row, its
+// evidence and log omega are fetched into LDS with every load in flight at once, then
+//  - binary tree: the nodes of a level are evaluated side by side by the workgroup's
+//    groups (one barrier per level), and the n prefix marginals - each a walk from a
+//    leaf to the root of at most log2 n products - are dealt to the groups;
+//  - HMM: one group runs the forward recursion out of LDS.
+// One unit per lane (r <= 64).  LDS: layers L*r*r + evidence n*r + nodes (n-1)*r +
+// log omega r + one exchange row of r floats per group.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_circuit_row(const CircuitArgs a, int G) {
+  extern __shared__ __align__(16) float rsm[];
+  const int n = a.n, r = a.r, tid = threadIdx.x;
+  const int NG = 256 / G, gi = tid / G, g = tid % G;
+  const long long row = blockIdx.x;
+  const long long pos = row / a.T;
+  const int Lst = a.L;                                   // stored layers (1: shared by all steps / nodes)
+  const int lstep = Lst > 1 ? r * r : 0;
+  float* s_lay = rsm;                                    // [Lst][j][k]
+  float* s_ev = s_lay + (size_t)Lst * r * r;             // [n][r]
+  float* s_nodes = s_ev + (size_t)n * r;                 // [n-1][r] (binary tree)
+  float* s_lw = s_nodes + (size_t)(n - 1) * r;           // [r]
+  float* s_sh = s_lw + r + (size_t)gi * r;               // this group's exchange row
+  int* s_bad = (int*)(s_lw + r + (size_t)NG * r);
+
+  const float* lay = a.layers;
+  if (a.contextual && lay) lay += pos * (long long)Lst * r * r;
+  const float* ev = a.e + row * (long long)n * r;
+  const int nlay = lay ? Lst * r * r : 0;
+  if ((nlay & 3) == 0 && (((size_t)lay) & 15) == 0) {
+    // 16-byte loads, four per thread in flight
+    const float4* src = (const float4*)lay;
+    float4* dst = (float4*)s_lay;
+    const int nq = nlay >> 2;
+    for (int t0 = 0; t0 < nq; t0 += 4 * 256) {
+      float4 tmp[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) tmp[u] = src[min(t0 + u * 256 + tid, nq - 1)];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (t0 + u * 256 + tid < nq) dst[t0 + u * 256 + tid] = tmp[u];
+    }
+  } else {
+    for (int t0 = 0; t0 < nlay; t0 += 8 * 256) {         // eight loads per thread in flight
+      float tmp[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) tmp[u] = lay[min(t0 + u * 256 + tid, nlay - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (t0 + u * 256 + tid < nlay) s_lay[t0 + u * 256 + tid] = tmp[u];
+    }
+  }
+  for (int t = tid; t < n * r; t += 256) s_ev[t] = ev[t];
+  if (tid < r) s_lw[tid] = a.logw[pos * r + tid];
+  __syncthreads();
+  // an id outside [-1, v) left NaN in every unit of its window position: poison what observes it
+  if (gi == 0) {
+    const int fb = first_nan_position(s_ev, n, r, g, G);
+    if (g == 0) *s_bad = fb;
+  }
+  __syncthreads();
+  const int first_bad = *s_bad;
+  const float ninf = neg_inf();
+  auto emit = [&](int i, float v) {
+    if (g != 0) return;
+    if (i >= first_bad) v = __builtin_nanf("");
+    if (a.prefix) a.out[row * n + i] = v;
+    else if (i == n - 1) a.out[row] = v;
+  };
+  auto lse = [&](float x) {
+    const float m = group_max(x, G);
+    if (m == ninf) return m;
+    return m + __logf(group_sum(g < r ? __expf(x - m) : 0.f, G));
+  };
+  auto leaf = [&](int i) { return g < r ? s_ev[i * r + g] : ninf; };
+  const float lw = g < r ? s_lw[g] : ninf;
+
+  if (a.family == MTPC_HMM) {
+    if (gi != 0) return;                                 // (no workgroup barrier below)
+    float alpha[1] = {lw + leaf(0)};
+    for (int i = 0; i < n; ++i) {
+      if (i > 0) {
+        sum_layer_lds<1>(alpha, s_lay + (size_t)(i - 1) * lstep, s_sh, g, r, G);
+        alpha[0] += leaf(i);
+      }
+      if (a.prefix || i == n - 1) emit(i, lse(alpha[0]));
+    }
+    return;
+  }
+
+  // ---- binary tree, heap order: inner nodes 0..n-2, leaf i at n-1+i
+  auto full_value = [&](int c) {                         // child fully observed
+    if (c >= n - 1) return leaf(c - (n - 1));
+    return g < r ? s_nodes[c * r + g] : ninf;
+  };
+  for (int lo = (n >> 1) - 1; lo >= 1; lo = (lo - 1) >> 1) {   // levels bottom-up: nodes lo .. 2*lo
+    for (int m = lo + gi; m <= 2 * lo; m += NG) {
+      float c[1] = {full_value(2 * m + 1) + full_value(2 * m + 2)};
+      sum_layer_lds<1>(c, s_lay + (size_t)(m - 1) * lstep, s_sh, g, r, G);
+      if (g < r) s_nodes[m * r + g] = c[0];
+    }
+    __syncthreads();
+  }
+  if (!a.prefix) {
+    if (gi == 0) emit(n - 1, lse(full_value(1) + full_value(2) + lw));
+    return;
+  }
+  // prefix i: a subtree without observed leaf is 1, a fully observed one its stored value;
+  // only the nodes whose leaf range straddles the boundary are evaluated again
+  for (int i = gi; i < n; i += NG) {
+    float pv = 0.f;                 // value of the straddling child on the path so far
+    int idx = n - 1 + i, size = 1;
+    while (idx > 0) {
+      const int m = (idx - 1) >> 1;
+      size <<= 1;
+      const int first = (m - (n / size - 1)) * size, last = first + size - 1;
+      if (m > 0 && last <= i) { idx = m; continue; }
+      const int cl = 2 * m + 1, cr = cl + 1, half = size >> 1;
+      const int l_last = first + half - 1, r_first = first + half;
+      const float lv = (l_last <= i) ? full_value(cl) : pv;
+      const float rv = (r_first > i) ? (g < r ? 0.f : ninf) : (last <= i ? full_value(cr) : pv);
+      float c[1] = {lv + rv};
+      if (m > 0) {
+        sum_layer_lds<1>(c, s_lay + (size_t)(m - 1) * lstep, s_sh, g, r, G);
+        pv = c[0];
+      } else {
+        emit(i, lse(c[0] + lw));
+      }
+      idx = m;
+    }
+  }
+}
+
+// LDS of k_circuit_row in bytes (0: the shape is not served)
+static size_t circuit_row_smem(const CircuitArgs& a, int G) {
+  if (a.r > 64 || (a.family != MTPC_HMM && a.family != MTPC_BTREE)) return 0;
+  const int L = a.family == MTPC_HMM ? a.n - 1 : a.n - 2;
+  if (L > 0 && !a.layers) return 0;
+  const size_t fl = (size_t)(L > 0 ? a.L : 0) * a.r * a.r + (size_t)a.n * a.r + (size_t)(a.n - 1) * a.r + a.r +
+                    (size_t)(256 / G) * a.r + 4;
+  return fl * 4;
+}
+
+static hipError_t launch_circuit_row(const CircuitArgs& a, int G, size_t smem, hipStream_t st) {
+  static size_t attr = 0;                                // largest dynamic LDS size granted so far
+  if (smem > attr) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_circuit_row, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)smem);
+    if (e != hipSuccess) return e;
+    attr = smem;
+  }
+  hipLaunchKernelGGL(k_circuit_row, dim3((unsigned)a.rows), dim3(256), smem, st, a, G);
+  return hipGetLastError();
+}
+
 hipError_t launch_circuit(const CircuitArgs& a, hipStream_t st) {
+  // decode-sized calls of the families with r x r layers: one workgroup per row
+  if (a.rows <= 2048 && (a.family == MTPC_HMM || a.family == MTPC_BTREE)) {
+    int G = 1;
+    while (G < a.r && G < 64) G <<= 1;
+    const size_t need = circuit_row_smem(a, G);
+    if (need != 0 && need <= 144 * 1024) return launch_circuit_row(a, G, need, st);
+  }
   // batching rows pays when sum layers are shared and there are rows to batch;
   // the batched BTree node store must still fit one group into 48 KiB of LDS
   // (measured: the tree's many dependent node evaluations gain from sharing weight
