@@ -150,6 +150,14 @@ mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayer
   return MTPC_OK;
 }
 
+// the operands every launch of the fused kernel shares
+UnembedArgs unembed_args(const mtpc_head* hd) {
+  UnembedArgs u{};
+  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
+  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  return u;
+}
+
 // sum-unit parameters shared by all ops
 mtpc_status launch_params(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const Plan& p,
                           bool nat, bool circ, hipStream_t st) {
@@ -202,9 +210,7 @@ mtpc_status run_evidence_op(int family, const mtpc_head* hd, const mtpc_sumlayer
   char* ws = (char*)hd->workspace;
   s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
   if (s != MTPC_OK) return s;
-  UnembedArgs u{};
-  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
-  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  UnembedArgs u = unembed_args(hd);
   u.targets = targets; u.T = 1; u.e = (float*)(ws + p.e);
   {
     ProfScope prof(st);
@@ -307,9 +313,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     dg.seed_lo = seed_lo; dg.seed_hi = seed_hi; dg.offset = offset; dg.greedy = greedy;
     HIP_TRY(launch_draw_gather(dg, hd->dtype, st));
   } else {
-    UnembedArgs u{};
-    u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
-    u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+    UnembedArgs u = unembed_args(hd);
     u.logphi = table;
     if (draw == Draw::InKernel) {
       u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
@@ -328,9 +332,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     }
   }
   if (want_prefix && !table_scores) {
-    UnembedArgs u2{};
-    u2.h = hd->h; u2.ld_h = hd->ld_h; u2.W = hd->W;
-    u2.B = hd->B; u2.d = hd->d; u2.v = hd->v; u2.n = hd->n; u2.r = hd->r;
+    UnembedArgs u2 = unembed_args(hd);
     u2.targets = drafts; u2.T = S; u2.e = (float*)(ws + p.e);
     ProfScope prof(st);
     HIP_TRY(launch_unembed(u2, hd->dtype, st));
@@ -363,9 +365,7 @@ mtpc_status run_window_scores(int family, const mtpc_head* hd, const mtpc_sumlay
   char* ws = (char*)hd->workspace;
   s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
   if (s != MTPC_OK) return s;
-  UnembedArgs u{};
-  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
-  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  UnembedArgs u = unembed_args(hd);
   u.targets = x; u.T = T; u.targets2 = x2; u.T2 = T2; u.e = (float*)(ws + p.e);
   {
     ProfScope prof(st);
@@ -560,9 +560,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, q.Lst, hd->r, 1,
                                     (float*)(ws + q.lay_tr), st));
   }
-  UnembedArgs u{};
-  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
-  u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
+  UnembedArgs u = unembed_args(hd);
   u.targets = targets; u.T = 1; u.e = (float*)(ws + q.e);
   if (q.keep_phi) { u.phiT = (float*)(ws + q.phi); u.ld_phi = q.ldb; }
   HIP_TRY(launch_unembed(u, hd->dtype, st));
