@@ -176,12 +176,10 @@ mtpc_status launch_params(int family, const mtpc_head* hd, const mtpc_sumlayers*
     c.out_tr = (circ && family == MTPC_BTREE) ? (float*)(ws + p.lay_circ) : nullptr;
     if (c.out_nat || c.out_tr) HIP_TRY(launch_ctx_layers(c, hd->dtype, st));
   } else if (L > 0) {
-    if (nat)
-      HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, p.nb, p.Lst,
-                                      hd->r, 0, (float*)(ws + p.lay_nat), st));
-    if (circ && family == MTPC_BTREE)
-      HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, p.nb, p.Lst,
-                                      hd->r, 1, (float*)(ws + p.lay_circ), st));
+    float* out_nat = nat ? (float*)(ws + p.lay_nat) : nullptr;
+    float* out_tr = (circ && family == MTPC_BTREE) ? (float*)(ws + p.lay_circ) : nullptr;
+    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, p.nb, p.Lst, hd->r,
+                                    out_nat, out_tr, st));
   }
   return MTPC_OK;
 }
@@ -552,13 +550,11 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     cl.out_nat = (float*)(ws + q.lay_nat); cl.out_tr = nullptr;
     HIP_TRY(launch_ctx_layers(cl, hd->dtype, st));
   } else if (q.perpos) {
-    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, hd->B, q.Lst, hd->r, 0,
-                                    (float*)(ws + q.lay_nat), st));
+    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, hd->B, q.Lst, hd->r,
+                                    (float*)(ws + q.lay_nat), nullptr, st));
   } else if (L > 0) {
-    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, q.Lst, hd->r, 0,
-                                    (float*)(ws + q.lay_nat), st));
-    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, q.Lst, hd->r, 1,
-                                    (float*)(ws + q.lay_tr), st));
+    HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, 0, 1, q.Lst, hd->r,
+                                    (float*)(ws + q.lay_nat), (float*)(ws + q.lay_tr), st));
   }
   UnembedArgs u = unembed_args(hd);
   u.targets = targets; u.T = 1; u.e = (float*)(ws + q.e);

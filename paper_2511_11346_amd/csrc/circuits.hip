@@ -137,11 +137,12 @@ hipError_t launch_sumunit(const void* h, long long ld_h, const void* Wsum, int B
 
 // ---------------------------------------------------------------------------
 // softmax over the last axis of every r x r sum layer -> linear probabilities
-// one wave per sum unit (row k of layer l of position-block b)
+// one wave per sum unit (row k of layer l of position-block b); the natural copy
+// [k][j], the transposed one [j][k], or both from one launch
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_normalise_layers(const float* logits, long long ls,
                                                           long long bs, int nb, int L, int r,
-                                                          int transpose, float* out) {
+                                                          float* out_nat, float* out_tr) {
   const int lane = threadIdx.x & 63;
   const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const long long nrows = (long long)nb * L * r;
@@ -158,18 +159,23 @@ __global__ __launch_bounds__(256) void k_normalise_layers(const float* logits, l
   const float e1 = x1 > neg_inf() ? expf(x1 - ms) : 0.f;
   const float tot = group_sum(e0 + e1, 64);
   const float inv = tot > 0.f ? 1.f / tot : 0.f;
-  float* dst = out + (b * L + l) * (long long)r * r;
-  if (lane < r) dst[transpose ? (long long)lane * r + k : (long long)k * r + lane] = e0 * inv;
-  if (lane + 64 < r)
-    dst[transpose ? (long long)(lane + 64) * r + k : (long long)k * r + lane + 64] = e1 * inv;
+  const long long base = (b * L + l) * (long long)r * r;
+  if (out_nat) {
+    if (lane < r) out_nat[base + (long long)k * r + lane] = e0 * inv;
+    if (lane + 64 < r) out_nat[base + (long long)k * r + lane + 64] = e1 * inv;
+  }
+  if (out_tr) {
+    if (lane < r) out_tr[base + (long long)lane * r + k] = e0 * inv;
+    if (lane + 64 < r) out_tr[base + (long long)(lane + 64) * r + k] = e1 * inv;
+  }
 }
 
 hipError_t launch_normalise_layers(const float* logits, long long layer_stride, long long batch_stride,
-                                   int nb, int L, int r, int transpose, float* out, hipStream_t st) {
+                                   int nb, int L, int r, float* out_nat, float* out_tr, hipStream_t st) {
   const long long nrows = (long long)nb * L * r;
-  if (nrows == 0) return hipSuccess;
+  if (nrows == 0 || (!out_nat && !out_tr)) return hipSuccess;
   hipLaunchKernelGGL(k_normalise_layers, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, st, logits,
-                     layer_stride, batch_stride, nb, L, r, transpose, out);
+                     layer_stride, batch_stride, nb, L, r, out_nat, out_tr);
   return hipGetLastError();
 }
 

@@ -71,9 +71,10 @@ hipError_t launch_sumunit(const void* h, long long ld_h, const void* Wsum, int B
 hipError_t launch_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
                                int dtype, float* logw, hipStream_t st);
 // softmax over the last axis of r x r logits -> linear probabilities.
-// in: logits[(b*bs) + l*ls + k*r + j]; out[((b*L + l)*r + k)*r + j] or transposed [j][k].
+// in: logits[(b*bs) + l*ls + k*r + j]; out_nat[((b*L + l)*r + k)*r + j] and / or the same
+// transposed, out_tr[((b*L + l)*r + j)*r + k] (either may be nullptr).
 hipError_t launch_normalise_layers(const float* logits, long long layer_stride, long long batch_stride,
-                                   int nb, int L, int r, int transpose, float* out, hipStream_t st);
+                                   int nb, int L, int r, float* out_nat, float* out_tr, hipStream_t st);
 
 struct CircuitArgs {
   int family;           // mtpc_family
