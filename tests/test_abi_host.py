@@ -132,3 +132,27 @@ def test_workspace_query():
     a = L.mtpc_workspace_bytes(binding.HMM, binding.OP_LOGLIK, C.byref(hd), C.byref(lay), 1, 0)
     b = L.mtpc_workspace_bytes(binding.HMM, binding.OP_LOGLIK, C.byref(hd), C.byref(hom), 1, 0)
     assert a >= b > small
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 and a C program that only
+    includes it links against libmtpc.so and reads its status strings (no GPU call)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include "mtpc.h"\n#include <stdio.h>\n#include <string.h>\n'
+        "int main(void) {\n"
+        "  mtpc_head hd; memset(&hd, 0, sizeof hd);\n"
+        "  if (mtpc_cp_loglik(&hd, 0, 0) == MTPC_OK) return 2;\n"          # rejected on the host
+        "  if (mtpc_workspace_bytes(MTPC_CP, MTPC_OP_LOGLIK, &hd, 0, 1, 0) != 0) return 3;\n"
+        '  printf("%s\\n", mtpc_status_string(MTPC_ERR_WORKSPACE));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "abi"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), LIB, "-Wl,-rpath," + os.path.dirname(LIB)], check=True)
+    res = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert res.returncode == 0 and res.stdout.strip() != ""
