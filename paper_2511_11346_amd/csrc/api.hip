@@ -29,9 +29,17 @@ int n_layers(int family, int n) {
 
 // Decode-sized batches (B <= 64, bound by the one read of W): the sampling pass also writes
 // the table of normalised input units (B*n*r*v floats) and the drafts are scored from it,
-// instead of a second pass over W.  Larger batches draw through buckets (1/r of a pass) and
-// score their drafts with one evidence pass, unless the caller asks for the table.
+// instead of a second pass over W.  Larger batches draw through buckets of (token, selected
+// unit) - 1/r of a pass when the buckets are full - and score their drafts with one evidence
+// pass, unless the caller asks for the table.  In between (buckets of fewer than 64 rows on
+// average) a bucket tile costs as much as a slab of the full pass: when scores are wanted too,
+// the one sampling pass that also leaves the table is cheaper than buckets plus a second pass.
 bool decode_sized(const mtpc_head* hd) { return hd->B <= 64; }
+bool buckets_filled(const mtpc_head* hd, int S) { return (long long)hd->B * S >= 64LL * hd->r; }
+bool table_in_workspace(const mtpc_head* hd, int S) {
+  if (!decode_sized(hd) && buckets_filled(hd, S)) return false;
+  return (unsigned long long)hd->B * hd->n * hd->r * hd->v * 4ull <= (8ull << 30);   // else a second pass
+}
 
 // most windows per position whose rows B*T*n still index with an int
 long long hd_rows_limit(const mtpc_head* hd) {
@@ -43,6 +51,7 @@ struct Plan {           // byte offsets into the workspace
   size_t logw, lay_nat, lay_circ, e, zleaf, lat, logm, table, total;
   size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_list;   // buckets of the token draws (large batches)
   int nb, Lst;          // position blocks and stored layers of the normalised copies
+  bool has_table;       // room for the table of input units (sampling with scores, see decode_sized)
 };
 
 mtpc_status check_head(int family, const mtpc_head* hd) {
@@ -110,7 +119,8 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   p.lay_circ = need_tr ? take(lay_bytes) : p.lay_nat;
   const size_t rows = (sample || table_op) ? B * (size_t)S : B;
   p.e = (uni || verify || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
-  p.table = (sample && want_prefix && decode_sized(hd)) ? take(B * n * r * (size_t)hd->v * 4) : 0;
+  p.has_table = sample && want_prefix && table_in_workspace(hd, S);
+  p.table = p.has_table ? take(B * n * r * (size_t)hd->v * 4) : 0;
   if (sample && !decode_sized(hd)) {
     p.bk_count = take(n * r * 4);
     p.bk_rowoff = take((n * r + 1) * 4);
@@ -289,11 +299,12 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   enum class Draw { InKernel, Buckets, FromTable };
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
   const bool span_ok = (unsigned long long)hd->B * (unsigned long long)hd->ld_h * esz <= 0xffffffffull;
-  const Draw draw = decode_sized(hd) ? Draw::InKernel
-                    : logphi         ? Draw::FromTable
-                    : span_ok        ? Draw::Buckets      // the gather addresses h through one 4 GiB resource
-                                     : Draw::InKernel;
-  const bool table_scores = want_prefix && (logphi != nullptr || decode_sized(hd));
+  const bool buckets_pay = !want_prefix || buckets_filled(hd, S);
+  const Draw draw = decode_sized(hd)       ? Draw::InKernel
+                    : logphi               ? Draw::FromTable
+                    : span_ok && buckets_pay ? Draw::Buckets   // the gather addresses h through one 4 GiB resource
+                                           : Draw::InKernel;
+  const bool table_scores = want_prefix && draw != Draw::Buckets && (logphi != nullptr || p.has_table);
   float* table = logphi ? logphi : (table_scores ? (float*)(ws + p.table) : nullptr);
 
   if (draw == Draw::Buckets) {
