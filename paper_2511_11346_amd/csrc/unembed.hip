@@ -160,15 +160,24 @@ void k_unembed(const UnembedArgs a) {
           if (x < 0 || x >= a.v) {
             if (wv == 0 && lhalf == 0) *dst = (x == -1) ? 0.f : __builtin_nanf("");
           } else {
+            // the lane holds rows rbase + 32 vb + 8 q + t (q, t in 0..3): first the block vb of
+            // the target row, then its register by the bits of the offset (about 80 selects
+            // instead of a compare and a select for each of the 16 VB registers)
             const int xr = x - rbase;
-            float val = 0.f;
-            bool hit = false;
+            if (xr >= 0 && xr < VB * 32 && (xr & 4) == 0) {
+              const int xvb = xr >> 5;
+              f32x16_t blk = acc[pb][0];
 #pragma unroll
-            for (int vb = 0; vb < VB; ++vb)
-#pragma unroll
-              for (int i = 0; i < 16; ++i)
-                if (xr == vb * 32 + 8 * (i >> 2) + (i & 3)) { val = acc[pb][vb][i]; hit = true; }
-            if (hit) *dst = val - lse[pb];
+              for (int vb = 1; vb < VB; ++vb) blk = (xvb == vb) ? acc[pb][vb] : blk;
+              const bool t0 = xr & 1, t1 = xr & 2, q0 = xr & 8, q1 = xr & 16;
+              const float b0 = t0 ? blk[1] : blk[0], b1 = t0 ? blk[3] : blk[2];
+              const float b2 = t0 ? blk[5] : blk[4], b3 = t0 ? blk[7] : blk[6];
+              const float b4 = t0 ? blk[9] : blk[8], b5 = t0 ? blk[11] : blk[10];
+              const float b6 = t0 ? blk[13] : blk[12], b7 = t0 ? blk[15] : blk[14];
+              const float c0 = t1 ? b1 : b0, c1 = t1 ? b3 : b2, c2 = t1 ? b5 : b4, c3 = t1 ? b7 : b6;
+              const float lo = q0 ? c1 : c0, hi = q0 ? c3 : c2;
+              *dst = (q1 ? hi : lo) - lse[pb];
+            }
           }
         }
       }
