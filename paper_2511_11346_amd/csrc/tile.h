@@ -344,26 +344,45 @@ __device__ __forceinline__ void tile_lse(const f32x16_t (&acc)[PB][VB], int v, f
   const int wv = wave % WV, wb = wave / WV;
   const int l31 = lane & 31, lhalf = lane >> 5;
   const int rbase = wv * VB * 32 + 4 * lhalf;
+  // exp(l - m) = 2^(l * log2(e) - m * log2(e)): one fused multiply-add and one v_exp per logit.
+  // A tile whose v fills all TV rows (v = 320 on the 320-row tiles) needs no row masks.
+  constexpr float LOG2E = 1.4426950408889634f;
+  const bool full = v == TL::TV;
 #pragma unroll
   for (int pb = 0; pb < PB; ++pb) {
     float m = neg_inf();
+    if (full) {
 #pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-        if (row < v) m = fmaxf(m, acc[pb][vb][i]);
-      }
+        for (int i = 0; i < 16; ++i) m = fmaxf(m, acc[pb][vb][i]);
+    } else {
+#pragma unroll
+      for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+          if (row < v) m = fmaxf(m, acc[pb][vb][i]);
+        }
+    }
     m = fmaxf(m, __shfl_xor(m, 32));
     const float ms = (m == neg_inf()) ? 0.f : m;
+    const float ms2 = -ms * LOG2E;
     float s = 0.f;
+    if (full) {
 #pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-        if (row < v) s += __expf(acc[pb][vb][i] - ms);
-      }
+        for (int i = 0; i < 16; ++i) s += __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, ms2));
+    } else {
+#pragma unroll
+      for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+          if (row < v) s += __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, ms2));
+        }
+    }
     s += __shfl_xor(s, 32);
     if (lhalf == 0) red[wv * TL::TP + wb * PB * 32 + pb * 32 + l31] = make_float2(m, s);
   }
