@@ -189,12 +189,16 @@ void k_unembed(const UnembedArgs a) {
     for (int pb = 0; pb < PB; ++pb) {
       const int b = b0 + wb * PB * 32 + pb * 32 + l31;
       if (b < a.B) {
+        // phi = 2^((l - lse) log2 e): one fused multiply-add and one v_exp per probability
+        constexpr float LOG2E = 1.4426950408889634f;
+        const float shift = -lse[pb] * LOG2E;
+        float* col = a.phiT + ((long long)slab * a.v + rbase) * a.ld_phi + b;
 #pragma unroll
         for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-            if (row < a.v) a.phiT[((long long)slab * a.v + row) * a.ld_phi + b] = __expf(acc[pb][vb][i] - lse[pb]);
+            const int off = vb * 32 + 8 * (i >> 2) + (i & 3);
+            if (rbase + off < a.v) col[off * a.ld_phi] = __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, shift));
           }
       }
     }
