@@ -186,9 +186,9 @@ def main():
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS,
                 # L2 <-> fabric bytes per launch of this kernel on this workload, from two rocprofv3
-                # --pmc runs of this script (FETCH_SIZE 1,709,627 x 2 KiB, WRITE_SIZE 16,384 x 1 KiB,
+                # --pmc runs of this script (FETCH_SIZE 1,709,262 x 2 KiB, WRITE_SIZE 16,384 x 1 KiB,
                 # factors calibrated on a 1 GiB device copy); reads served by the Infinity Cache count
-                "traffic": 1709627 * 2048 + 16384 * 1024, "traffic_unit": "bytes/launch",
+                "traffic": 1709262 * 2048 + 16384 * 1024, "traffic_unit": "bytes/launch",
                 "algorithmic_bytes": (B * inp.d + inp.n * inp.r * inp.v * inp.d) * 2 + (1 + S) * B * inp.n * inp.r * 4,
                 "avg_launch_ms": k1_ms, "flop_per_launch": flops}
 
