@@ -1,15 +1,16 @@
 #!/usr/bin/env python3
 """Throughput of the MtPC head hot path on one MI355X.
 
-Workload: BASELINE configs[1] at full size - CP head, r=16, bf16 inputs with fp32
-accumulation, B=8192 positions, d=4096, n=8, v=320 - on seeded synthetic inputs
+Workload: the CP head of the second named configuration at full size - r=16, bf16 inputs with
+fp32 accumulation, B=8192 positions, d=4096, n=8, v=320 - on seeded synthetic inputs
 already resident in HBM.  One step = one pass of the whole hot path over the
-batch: sum-unit parameters, fused unembedding + log-softmax + gather, circuit
-layers with prefix marginals (the last one is the log-likelihood), then one
-ancestral draft per position with the prefix marginals of that draft.
+batch: sum-unit parameters, one ancestral draft per position (latents, then each token
+from the one input unit it is drawn from), then ONE fused pass (unembedding + log-softmax
++ gather) that scores the targets and the drafts, and the circuit layers with prefix
+marginals of both (the last one is the log-likelihood).
 
 Prints ONE JSON line (see the keys below).  `roofline` is for the dominant
-kernel (the fused unembedding kernel of the log-likelihood pass), timed with HIP
+kernel (the fused unembedding kernel of that scoring pass), timed with HIP
 events recorded by the library right around its launch; `cpu_baseline` is the
 float64 NumPy oracle timed on a bounded sample of the same workload.
 """
