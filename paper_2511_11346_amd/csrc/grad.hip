@@ -126,6 +126,29 @@ void k_gemm_tn(const GemmArgs a) {
                                           (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0, b0,
                                           smem, acc);
   const int rbase = wv * VB * 32 + 4 * lhalf;
+  // A full tile that lies inside one destination (the common case): one base pointer per
+  // column, rows at constant multiples of ldc.
+  {
+    const long long gr0 = (long long)slab * TL::TV;
+    float* base = nullptr;
+    if (rows == TL::TV) {
+      if (a.ksplit > 1) base = a.partial + ((long long)ks * a.M + gr0) * a.ldc;
+      else if (gr0 + TL::TV <= a.split) base = a.C + gr0 * a.ldc;
+    }
+    if (base != nullptr) {
+#pragma unroll
+      for (int pb = 0; pb < PB; ++pb) {
+        const int col = b0 + wb * PB * 32 + pb * 32 + l31;
+        if (col >= a.N) continue;
+        float* cp = base + (long long)rbase * a.ldc + col;
+#pragma unroll
+        for (int vb = 0; vb < VB; ++vb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) cp[(long long)(vb * 32 + 8 * (i >> 2) + (i & 3)) * a.ldc] = acc[pb][vb][i];
+      }
+      return;
+    }
+  }
   // one destination row at a time (keeps the address arithmetic out of the 160 live accumulators)
 #pragma unroll
   for (int vb = 0; vb < VB; ++vb)
