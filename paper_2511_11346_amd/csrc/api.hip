@@ -49,7 +49,7 @@ long long hd_rows_limit(const mtpc_head* hd) {
 
 struct Plan {           // byte offsets into the workspace
   size_t logw, lay_nat, lay_circ, e, zleaf, lat, logm, table, total;
-  size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_list;   // buckets of the token draws (large batches)
+  size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_tilebucket, bk_list;   // buckets of the token draws (large batches)
   int nb, Lst;          // position blocks and stored layers of the normalised copies
   bool has_table;       // room for the table of input units (sampling with scores, see decode_sized)
 };
@@ -125,6 +125,7 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
     p.bk_count = take(n * r * 4);
     p.bk_rowoff = take((n * r + 1) * 4);
     p.bk_tileoff = take((n * r + 1) * 4);
+    p.bk_tilebucket = take((B * (size_t)S * n / DRAW_GATHER_TILE + n * r) * 4);
     p.bk_slot = take(B * (size_t)S * n * 4);
     p.bk_list = take(B * (size_t)S * n * 4);
   }
@@ -313,12 +314,14 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     bk.zleaf = la.zleaf;
     bk.count = (int*)(ws + p.bk_count); bk.slot = (int*)(ws + p.bk_slot);
     bk.row_off = (int*)(ws + p.bk_rowoff); bk.tile_off = (int*)(ws + p.bk_tileoff);
+    bk.tile_bucket = (int*)(ws + p.bk_tilebucket);
     bk.list = (int*)(ws + p.bk_list);
     HIP_TRY(launch_buckets(bk, st));
     DrawGatherArgs dg{};
     dg.h = hd->h; dg.ld_h = hd->ld_h; dg.W = hd->W;
     dg.B = hd->B; dg.S = S; dg.d = hd->d; dg.v = hd->v; dg.n = hd->n; dg.r = hd->r;
-    dg.row_off = bk.row_off; dg.tile_off = bk.tile_off; dg.list = bk.list; dg.drafts = drafts;
+    dg.row_off = bk.row_off; dg.tile_off = bk.tile_off; dg.tile_bucket = bk.tile_bucket; dg.list = bk.list;
+    dg.drafts = drafts;
     dg.seed_lo = seed_lo; dg.seed_hi = seed_hi; dg.offset = offset; dg.greedy = greedy;
     HIP_TRY(launch_draw_gather(dg, hd->dtype, st));
   } else {

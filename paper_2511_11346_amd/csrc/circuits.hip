@@ -1200,8 +1200,10 @@ __global__ __launch_bounds__(256) void k_bucket_offsets(const BucketArgs a) {
     const int c = a.count[g];
     a.row_off[g] = ro;
     a.tile_off[g] = to;
+    const int nt = (c + a.tile - 1) / a.tile;
+    for (int t = 0; t < nt; ++t) a.tile_bucket[to + t] = g;
     ro += c;
-    to += (c + a.tile - 1) / a.tile;
+    to += nt;
   }
   if (tid == 255) {
     a.row_off[ng] = s_rows[255];

@@ -146,6 +146,7 @@ struct BucketArgs {
   int* slot;            // [B*S*n] scratch: rank of a triple inside its bucket
   int* row_off;         // [n*r + 1]
   int* tile_off;        // [n*r + 1]
+  int* tile_bucket;     // [B*S*n / tile + n*r] bucket of every tile
   int* list;            // [B*S*n]
 };
 hipError_t launch_buckets(const BucketArgs& a, hipStream_t st);
@@ -158,6 +159,7 @@ struct DrawGatherArgs {
   int B, S, d, v, n, r;
   const int* row_off;
   const int* tile_off;
+  const int* tile_bucket;
   const int* list;
   int* drafts;          // [B][S][n]
   uint32_t seed_lo, seed_hi, offset;

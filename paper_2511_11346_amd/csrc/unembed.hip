@@ -81,7 +81,8 @@ __device__ __forceinline__ void tile_draws(const f32x16_t (&acc)[PB][VB], const 
   int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
   int* s_slot = s_list + TL::TP;
   float* probs = (float*)smem;
-  static_assert(NSL * TL::VPL * 64 * 4 <= TL::RED_OFF, "draw buffer must fit in the stage buffers");
+  constexpr int SLOT = TL::VPL * 64 + 1;     // odd stride: the lanes of a wave dump different slots into different banks
+  static_assert(NSL * SLOT * 4 <= TL::RED_OFF, "draw buffer must fit in the stage buffers");
   for (int c0 = 0; c0 < cnt; c0 += NSL) {
     const int nsl = min(NSL, cnt - c0);
     for (int p = tid; p < TL::TP; p += TL::NT) s_slot[p] = -1;
@@ -97,7 +98,7 @@ __device__ __forceinline__ void tile_draws(const f32x16_t (&acc)[PB][VB], const 
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-            probs[sl * (TL::VPL * 64) + row] = (row < v) ? expf(acc[pb][vb][i] - mx[pb]) : 0.f;
+            probs[sl * SLOT + row] = (row < v) ? expf(acc[pb][vb][i] - mx[pb]) : 0.f;
           }
       }
     }
@@ -107,7 +108,7 @@ __device__ __forceinline__ void tile_draws(const f32x16_t (&acc)[PB][VB], const 
       float ls = 0.f;
 #pragma unroll
       for (int q = 0; q < TL::VPL; ++q) {
-        vals[q] = probs[k * (TL::VPL * 64) + lane * TL::VPL + q];
+        vals[q] = probs[k * SLOT + lane * TL::VPL + q];
         ls += vals[q];
       }
       float incl = ls;   // inclusive scan over lanes
@@ -294,12 +295,7 @@ void k_draw_gather(const DrawGatherArgs a) {
   const int lid = (w < per * 8) ? (w & 7) * per + (w >> 3) : w;
   const int ngroups = a.n * a.r;
   if (lid >= a.tile_off[ngroups]) return;            // the grid is an upper bound
-  int lo = 0, hi = ngroups - 1;                      // the bucket g with tile_off[g] <= lid < tile_off[g+1]
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (a.tile_off[mid] <= lid) lo = mid; else hi = mid - 1;
-  }
-  const int g = lo;
+  const int g = a.tile_bucket[lid];                  // tile_off[g] <= lid < tile_off[g+1]
   const int first = a.row_off[g] + (lid - a.tile_off[g]) * TL::TP;
   const int nrows = min(a.row_off[g + 1] - first, TL::TP);     // >= 1 by construction of tile_off
   const int* rows = a.list + first;
