@@ -1200,10 +1200,8 @@ __global__ __launch_bounds__(256) void k_bucket_offsets(const BucketArgs a) {
     const int c = a.count[g];
     a.row_off[g] = ro;
     a.tile_off[g] = to;
-    const int nt = (c + a.tile - 1) / a.tile;
-    for (int t = 0; t < nt; ++t) a.tile_bucket[to + t] = g;
     ro += c;
-    to += nt;
+    to += (c + a.tile - 1) / a.tile;
   }
   if (tid == 255) {
     a.row_off[ng] = s_rows[255];
@@ -1216,7 +1214,9 @@ __global__ __launch_bounds__(256) void k_bucket_fill(const BucketArgs a) {
   if (t >= (long long)a.B * a.S * a.n) return;
   const int i = (int)(t % a.n);
   const int z = min(max(a.zleaf[t], 0), a.r - 1);
-  a.list[a.row_off[i * a.r + z] + a.slot[t]] = (int)(t / a.n);
+  const int g = i * a.r + z, slot = a.slot[t];
+  a.list[a.row_off[g] + slot] = (int)(t / a.n);
+  if (slot % a.tile == 0) a.tile_bucket[a.tile_off[g] + slot / a.tile] = g;   // the first row of a tile names its bucket
 }
 
 hipError_t launch_buckets(const BucketArgs& a, hipStream_t st) {
