@@ -34,10 +34,15 @@ int n_layers(int family, int n) {
 // pass, unless the caller asks for the table.  In between (buckets of fewer than 64 rows on
 // average) a bucket tile costs as much as a slab of the full pass: when scores are wanted too,
 // the one sampling pass that also leaves the table is cheaper than buckets plus a second pass.
+// With one unit per layer (r = 1, the fully factorised head) there is nothing to skip and the
+// narrower bucket tiles only cost: it always takes the one sampling pass.
 bool decode_sized(const mtpc_head* hd) { return hd->B <= 64; }
-bool buckets_filled(const mtpc_head* hd, int S) { return (long long)hd->B * S >= 64LL * hd->r; }
-bool table_in_workspace(const mtpc_head* hd, int S) {
-  if (!decode_sized(hd) && buckets_filled(hd, S)) return false;
+bool buckets_pay(const mtpc_head* hd, int S, bool want_scores) {
+  if (decode_sized(hd) || hd->r < 2) return false;
+  return !want_scores || (long long)hd->B * S >= 64LL * hd->r;
+}
+bool table_in_workspace(const mtpc_head* hd, int S) {      // for a sampling call that wants scores
+  if (buckets_pay(hd, S, true)) return false;
   return (unsigned long long)hd->B * hd->n * hd->r * hd->v * 4ull <= (8ull << 30);   // else a second pass
 }
 
@@ -300,11 +305,10 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   enum class Draw { InKernel, Buckets, FromTable };
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
   const bool span_ok = (unsigned long long)hd->B * (unsigned long long)hd->ld_h * esz <= 0xffffffffull;
-  const bool buckets_pay = !want_prefix || buckets_filled(hd, S);
-  const Draw draw = decode_sized(hd)       ? Draw::InKernel
-                    : logphi               ? Draw::FromTable
-                    : span_ok && buckets_pay ? Draw::Buckets   // the gather addresses h through one 4 GiB resource
-                                           : Draw::InKernel;
+  const Draw draw = decode_sized(hd) ? Draw::InKernel
+                    : logphi         ? Draw::FromTable
+                    : span_ok && buckets_pay(hd, S, want_prefix) ? Draw::Buckets   // (h through one 4 GiB resource)
+                                     : Draw::InKernel;
   const bool table_scores = want_prefix && draw != Draw::Buckets && (logphi != nullptr || p.has_table);
   float* table = logphi ? logphi : (table_scores ? (float*)(ws + p.table) : nullptr);
 
