@@ -652,11 +652,13 @@ void k_univariate(const UnivariateArgs a) {
     for (int pb = 0; pb < PB; ++pb) {
       const int b = min(b0 + wb * PB * 32 + pb * 32 + l31, a.B - 1);
       const float lm = a.logm ? a.logm[((long long)b * a.n + wi) * a.r + j] : 0.f;
-      const float shift = lm - lse[pb];
+      // m_j phi_j = 2^((l - lse_j + log m_j) log2 e): one fused multiply-add and one v_exp per logit
+      constexpr float LOG2E = 1.4426950408889634f;
+      const float shift = (lm - lse[pb]) * LOG2E;
 #pragma unroll
       for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) run[pb][vb][i] += __expf(acc[pb][vb][i] + shift);
+        for (int i = 0; i < 16; ++i) run[pb][vb][i] += __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, shift));
     }
     __syncthreads();   // `red` is rewritten by the next slab
   }
