@@ -76,6 +76,40 @@ __device__ float matvec_log(const float* c, const float* __restrict__ M, int r, 
   return tid < r ? ms + __logf(s) : neg_inf();          // log 0 = -inf
 }
 
+// The same product in two halves, for chains of products whose layers are known in advance:
+// mv_load fetches this thread's 16 weights of a layer (its column t, its part of the k range;
+// needs ceil(r / (256 / G)) <= 16), mv_apply multiplies.  Loading the next layer before
+// applying the current one takes the L2 round trip out of the chain.
+struct MvWeights { float w[16]; };
+
+__device__ __forceinline__ void mv_load(const float* __restrict__ M, int r, int G, MvWeights& o) {
+  const int tid = threadIdx.x, parts = 256 / G, t = tid % G, pt = tid / G;
+  const int per = (r + parts - 1) / parts, k0 = pt * per, tc = min(t, r - 1);
+#pragma unroll
+  for (int u = 0; u < 16; ++u) o.w[u] = M[(long long)min(k0 + u, r - 1) * r + tc];
+}
+
+__device__ float mv_apply(const float* c, const MvWeights& wt, int r, int G, float* x, float* part, float* red) {
+  const int tid = threadIdx.x;
+  const float mx = block_max(tid < r ? c[tid] : neg_inf(), red);
+  const float ms = (mx == neg_inf()) ? 0.f : mx;
+  if (tid < r) x[tid] = __expf(c[tid] - ms);
+  __syncthreads();
+  const int parts = 256 / G, pt = tid / G;
+  const int per = (r + parts - 1) / parts;
+  const int k0 = pt * per, k1 = min(r, k0 + per);
+  float acc = 0.f;
+#pragma unroll
+  for (int u = 0; u < 16; ++u)
+    if (k0 + u < k1) acc = fmaf(x[k0 + u], wt.w[u], acc);
+  part[tid] = acc;
+  __syncthreads();
+  float s = 0.f;
+  if (tid < r)
+    for (int q = 0; q < parts; ++q) s += part[q * G + tid];
+  return tid < r ? ms + __logf(s) : neg_inf();          // log 0 = -inf
+}
+
 __global__ __launch_bounds__(256) void k_verify(const VerifyArgs a, int G) {
   extern __shared__ float vsm[];
   __shared__ float s_red[4], s_x[128], s_c[128], s_part[256], s_ratio[64], s_alpha[64];
@@ -151,6 +185,7 @@ __global__ __launch_bounds__(256) void k_verify(const VerifyArgs a, int G) {
     const float* lw = a.logw ? a.logw + (long long)b * r : nullptr;
     const long long lstep = a.L > 1 ? (long long)r * r : 0;
     const long long lbase = a.contextual ? (long long)b * a.L * r * r : 0;
+    const bool ahead = (r + 256 / G - 1) / (256 / G) <= 16;     // a thread's share of a layer fits mv_load
     // log-domain message into leaf j -> s_c
     if (a.family == MTPC_FF) {
       if (tid < r) s_c[tid] = 0.f;
@@ -163,8 +198,17 @@ __global__ __launch_bounds__(256) void k_verify(const VerifyArgs a, int G) {
     } else if (a.family == MTPC_HMM) {
       if (tid < r) s_c[tid] = lw[tid] + (j > 0 ? s_e[tid] : 0.f);
       __syncthreads();
+      MvWeights cur, nxt;
+      if (ahead && j >= 1) mv_load(a.lay_nat + lbase, r, G, cur);
       for (int i = 1; i <= j; ++i) {                         // predict state i from state i-1
-        float o = matvec_log(s_c, a.lay_nat + lbase + (i - 1) * lstep, r, G, s_x, s_part, s_red);
+        float o;
+        if (ahead) {
+          if (i < j) mv_load(a.lay_nat + lbase + i * lstep, r, G, nxt);
+          o = mv_apply(s_c, cur, r, G, s_x, s_part, s_red);
+          cur = nxt;
+        } else {
+          o = matvec_log(s_c, a.lay_nat + lbase + (i - 1) * lstep, r, G, s_x, s_part, s_red);
+        }
         if (i < j && tid < r) o += s_e[i * r + tid];         // ... and observe token i if accepted
         if (tid < r) s_c[tid] = o;
         __syncthreads();
@@ -176,25 +220,41 @@ __global__ __launch_bounds__(256) void k_verify(const VerifyArgs a, int G) {
       };
       int lg = 0;
       while ((1 << lg) < n) ++lg;
-      for (int m = n - 2; m >= 1; --m) {                     // bottom-up over subtrees left of leaf j
-        const int lev = 31 - __clz(m + 1);
-        const int span = n >> lev;
-        const int last = (m + 1 - (1 << lev)) * span + span - 1;
-        if (last >= j) continue;
+      auto next_left = [&](int m) {                          // next inner node below m whose leaves all lie left of leaf j
+        for (--m; m >= 1; --m) {
+          const int lev = 31 - __clz(m + 1);
+          const int span = n >> lev;
+          if ((m + 1 - (1 << lev)) * span + span - 1 < j) return m;
+        }
+        return 0;
+      };
+      MvWeights cur, nxt;
+      int m = next_left(n - 1);
+      if (ahead && m) mv_load(a.lay_tr + lbase + (m - 1) * lstep, r, G, cur);
+      while (m) {                                            // bottom-up over those subtrees
+        const int mn = next_left(m);
+        if (ahead && mn) mv_load(a.lay_tr + lbase + (mn - 1) * lstep, r, G, nxt);
         if (tid < r) s_c[tid] = value(2 * m + 1, tid) + value(2 * m + 2, tid);
         __syncthreads();
-        const float o = matvec_log(s_c, a.lay_tr + lbase + (m - 1) * lstep, r, G, s_x, s_part, s_red);
+        const float o = ahead ? mv_apply(s_c, cur, r, G, s_x, s_part, s_red)
+                              : matvec_log(s_c, a.lay_tr + lbase + (m - 1) * lstep, r, G, s_x, s_part, s_red);
         if (tid < r) s_nodes[m * r + tid] = o;
         __syncthreads();
+        cur = nxt;
+        m = mn;
       }
       // top-down along the path: D_child[t] = (sum_k D_node[k] A_node[k][t]) * sibling[t]
       for (int lev = 0; lev < lg; ++lev) {
         // child of the path node at this level: the node (or leaf) one level down that covers leaf j
         const int c = lev + 1 < lg ? (1 << (lev + 1)) - 1 + (j >> (lg - lev - 1)) : n - 1 + j;
         const int node = (c - 1) >> 1;
+        // the node of the next level is this level's child c: its layer can be fetched now
+        if (ahead && lev + 1 < lg) mv_load(a.lay_nat + lbase + (c - 1) * lstep, r, G, nxt);
         float o;
         if (node == 0) o = tid < r ? lw[tid] : neg_inf();
+        else if (ahead) o = mv_apply(s_c, cur, r, G, s_x, s_part, s_red);
         else o = matvec_log(s_c, a.lay_nat + lbase + (node - 1) * lstep, r, G, s_x, s_part, s_red);
+        cur = nxt;
         if ((c & 1) == 0 && tid < r) o += value(c - 1, tid);  // left sibling: leaves < j, observed
         __syncthreads();
         if (tid < r) s_c[tid] = o;                            // right sibling: nothing observed, = 1
