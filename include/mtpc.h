@@ -139,7 +139,9 @@ mtpc_status mtpc_btree_marginals(const mtpc_head* head, const mtpc_sumlayers* A,
  *               log phi[b,i,j,:] = log softmax(W[i,j] h[b]) of every position, kept
  *               for the verification step (mtpc_*_verify) and mtpc_*_table_scores.
  * Batches of more than 64 positions evaluate only the input unit each token is drawn
- * from, unless logphi is requested or scores are wanted for fewer than 64 r drafts; a
+ * from, unless logphi is requested or scores are wanted for fewer than 64 r drafts; so
+ * do calls for a handful of drafts (2 B S <= r) that ask for neither scores nor logphi
+ * (n B S rows of W are read instead of all n r v of them); a
  * draw whose uniform lies within rounding of a CDF step may then differ between calls
  * that ask for different outputs (the rule is the same, the fp32 partial sums are not). */
 mtpc_status mtpc_ff_sample(const mtpc_head* head, int32_t S, uint64_t seed, uint32_t offset,

@@ -41,6 +41,9 @@ bool buckets_pay(const mtpc_head* hd, int S, bool want_scores) {
   if (decode_sized(hd) || hd->r < 2) return false;
   return !want_scores || (long long)hd->B * S >= 64LL * hd->r;
 }
+// A handful of drafts without scores (2 B S <= r, say batch-1 greedy speculative decoding): only
+// the n slabs a draft's tokens are drawn from are read, as plain dot products.
+bool few_drafts(const mtpc_head* hd, int S) { return 2LL * hd->B * S <= hd->r; }
 bool table_in_workspace(const mtpc_head* hd, int S) {      // for a sampling call that wants scores
   if (buckets_pay(hd, S, true)) return false;
   return (unsigned long long)hd->B * hd->n * hd->r * hd->v * 4ull <= (8ull << 30);   // else a second pass
@@ -54,7 +57,8 @@ long long hd_rows_limit(const mtpc_head* hd) {
 
 struct Plan {           // byte offsets into the workspace
   size_t logw, lay_nat, lay_circ, e, zleaf, lat, logm, table, total;
-  size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_tilebucket, bk_list;   // buckets of the token draws (large batches)
+  size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_tilebucket, bk_list;
+  size_t rowlogits;     // compact table of the few-drafts path   // buckets of the token draws (large batches)
   int nb, Lst;          // position blocks and stored layers of the normalised copies
   bool has_table;       // room for the table of input units (sampling with scores, see decode_sized)
 };
@@ -126,6 +130,7 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   p.e = (uni || verify || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
   p.has_table = sample && want_prefix && table_in_workspace(hd, S);
   p.table = p.has_table ? take(B * n * r * (size_t)hd->v * 4) : 0;
+  p.rowlogits = (sample && few_drafts(hd, S)) ? take(B * (size_t)S * n * hd->v * 4) : 0;
   if (sample && !decode_sized(hd)) {
     p.bk_count = take(n * r * 4);
     p.bk_rowoff = take((n * r + 1) * 4);
@@ -302,17 +307,30 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   //   FromTable - the fused kernel only writes the caller's table, k_draw_table reads it
   // and how the drafts are scored: from the table when there is one, else by one more
   // fused pass with the drafts as targets.
-  enum class Draw { InKernel, Buckets, FromTable };
+  //   Rows      - k_rows_logits on the n slabs a draft needs, k_draw_table on the compact result
+  enum class Draw { InKernel, Buckets, FromTable, Rows };
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
   const bool span_ok = (unsigned long long)hd->B * (unsigned long long)hd->ld_h * esz <= 0xffffffffull;
-  const Draw draw = decode_sized(hd) ? Draw::InKernel
+  const Draw draw = (!want_prefix && !logphi && few_drafts(hd, S)) ? Draw::Rows
+                    : decode_sized(hd) ? Draw::InKernel
                     : logphi         ? Draw::FromTable
                     : span_ok && buckets_pay(hd, S, want_prefix) ? Draw::Buckets   // (h through one 4 GiB resource)
                                      : Draw::InKernel;
   const bool table_scores = want_prefix && draw != Draw::Buckets && (logphi != nullptr || p.has_table);
   float* table = logphi ? logphi : (table_scores ? (float*)(ws + p.table) : nullptr);
 
-  if (draw == Draw::Buckets) {
+  if (draw == Draw::Rows) {
+    RowLogitArgs rl{};
+    rl.h = hd->h; rl.ld_h = hd->ld_h; rl.W = hd->W;
+    rl.B = hd->B; rl.S = S; rl.d = hd->d; rl.v = hd->v; rl.n = hd->n; rl.r = hd->r;
+    rl.zleaf = la.zleaf; rl.out = (float*)(ws + p.rowlogits);
+    HIP_TRY(launch_rows_logits(rl, hd->dtype, st));
+    DrawArgs dr{};
+    dr.B = hd->B; dr.S = S; dr.v = hd->v; dr.n = hd->n; dr.r = hd->r;
+    dr.logphi = rl.out; dr.zleaf = la.zleaf; dr.drafts = drafts; dr.compact = 1;
+    dr.seed_lo = seed_lo; dr.seed_hi = seed_hi; dr.offset = offset; dr.greedy = greedy;
+    HIP_TRY(launch_draw_table(dr, st));
+  } else if (draw == Draw::Buckets) {
     BucketArgs bk{};
     bk.B = hd->B; bk.S = S; bk.n = hd->n; bk.r = hd->r; bk.tile = DRAW_GATHER_TILE;
     bk.zleaf = la.zleaf;

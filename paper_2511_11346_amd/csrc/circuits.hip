@@ -1077,14 +1077,23 @@ __global__ __launch_bounds__(256) void k_draw_table(const DrawArgs a) {
   const long long b = bs / a.S;
   const int s = (int)(bs - b * a.S);
   const int z = a.zleaf[di];
-  const float* row = a.logphi + ((b * a.n + i) * a.r + z) * a.v;
+  // rows of the full table, or (compact) one row of unnormalised logits per token
+  const float* row = a.compact ? a.logphi + di * a.v : a.logphi + ((b * a.n + i) * a.r + z) * a.v;
   float lg[VPL], vals[VPL];
-  float ls = 0.f;
+  float mx = neg_inf();
 #pragma unroll
   for (int q = 0; q < VPL; ++q) {
     const int k = lane * VPL + q;
     lg[q] = k < a.v ? row[k] : neg_inf();
-    vals[q] = k < a.v ? expf(lg[q]) : 0.f;
+    mx = fmaxf(mx, lg[q]);
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if (!a.compact) mx = 0.f;   // rows of the table are normalised (and may be all -inf)
+  float ls = 0.f;
+#pragma unroll
+  for (int q = 0; q < VPL; ++q) {
+    vals[q] = lane * VPL + q < a.v ? expf(lg[q] - mx) : 0.f;
     ls += vals[q];
   }
   if (a.greedy) {
@@ -1132,6 +1141,61 @@ __global__ __launch_bounds__(256) void k_draw_table(const DrawArgs a) {
     const int L = 63 - __clzll((long long)pos);
     if (lane == L) a.drafts[di] = last;
   }
+}
+
+// ---------------------------------------------------------------------------
+// Very few drafts (2 B S <= r): a draft only needs the logits of the one input unit each of
+// its tokens is drawn from, n of the n*r slabs of W.  One workgroup computes 16 logits of one
+// token, W[i][z][16 rows] . h[b], as plain dot products (its 4 waves take 4 rows each, the
+// hidden vector stays in registers); the rows go to a compact table [B*S*n][v] that
+// k_draw_table reads.  B*S*n*v*d products and as many bytes of W instead of a pass over all of it.
+// ---------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_rows_logits(const RowLogitArgs a) {
+  constexpr int ESZ = BF16 ? 2 : 4;
+  constexpr int EPC = 16 / ESZ;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long di = blockIdx.x;                       // (b, s, i) flattened
+  const int i = (int)(di % a.n);
+  const long long b = di / a.n / a.S;
+  const int z = min(max(a.zleaf[di], 0), a.r - 1);
+  const char* hb = (const char*)a.h + b * a.ld_h * ESZ;
+  const char* Wz = (const char*)a.W + ((long long)(i * a.r + z) * a.v) * a.d * ESZ;
+  const int row0 = blockIdx.y * 16 + wave * 4;
+  const int nch = a.d / EPC;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int c0 = 0; c0 < nch; c0 += 512) {
+    i32x4_t hv[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int c = c0 + t * 64 + lane;
+      const i32x4_t x = *(const i32x4_t*)(hb + (long long)min(c, nch - 1) * 16);
+      hv[t] = c < nch ? x : i32x4_t{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const char* wr = Wz + (long long)min(row0 + q, a.v - 1) * a.d * ESZ;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        // unconditional (clamped) loads so that all of them are in flight together;
+        // chunks beyond d meet a zero hv
+        const int c = min(c0 + t * 64 + lane, nch - 1);
+        acc[q] += dot_chunk<BF16>(*(const i32x4_t*)(wr + (long long)c * 16), hv[t]);
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const float val = wave_sum(acc[q]);
+    if (lane == 0 && row0 + q < a.v) a.out[di * a.v + row0 + q] = val;
+  }
+}
+
+hipError_t launch_rows_logits(const RowLogitArgs& a, int dtype, hipStream_t st) {
+  const dim3 grid((unsigned)((long long)a.B * a.S * a.n), (unsigned)((a.v + 15) / 16));
+  if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_rows_logits<true>, grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(k_rows_logits<false>, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_draw_table(const DrawArgs& a, hipStream_t st) {

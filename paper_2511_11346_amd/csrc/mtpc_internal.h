@@ -132,8 +132,20 @@ struct DrawArgs {
   int* drafts;          // [B][S][n]
   uint32_t seed_lo, seed_hi, offset;
   int greedy;           // most likely token instead of a draw (smallest id on ties)
+  int compact;          // logphi is [B*S*n][v]: one row of (unnormalised) logits per token
 };
 hipError_t launch_draw_table(const DrawArgs& a, hipStream_t st);
+
+// logits of the selected input unit of every token: out[(b,s,i)][:] = W[i][zleaf[b][s][i]] h[b]
+struct RowLogitArgs {
+  const void* h;
+  long long ld_h;
+  const void* W;
+  int B, S, d, v, n, r;
+  const int* zleaf;     // [B][S][n]
+  float* out;           // [B*S*n][v]
+};
+hipError_t launch_rows_logits(const RowLogitArgs& a, int dtype, hipStream_t st);
 
 // Buckets of the (b, s, i) triples by (i, selected input unit): bucket g = i*r + z holds
 // list[row_off[g] .. row_off[g+1]) = the draft rows b*S+s whose token i comes from unit z

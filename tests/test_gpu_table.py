@@ -190,3 +190,43 @@ def test_bucket_extremes(family, B, n, r, v, flat):
     else:
         safe = gap >= 1e-6
     assert np.array_equal(g2.cpu().numpy()[safe], want_d[safe])
+
+
+@pytest.mark.parametrize("family,dtype,B,S,d,n,r,v,ctx", [
+    ("cp", "bf16", 1, 1, 4096, 16, 32, 320, False),     # batch-1 decoding at the full head width
+    ("cp", "f32", 2, 2, 96, 4, 8, 33, False),           # exactly 2 B S = r
+    ("hmm", "bf16", 3, 2, 160, 6, 16, 257, True),       # d with a ragged last group of chunks
+    ("btree", "f32", 1, 3, 64, 8, 6, 100, False),
+    ("btree", "f32", 4, 1, 2080, 4, 128, 40, False),    # d beyond one register-resident piece of h
+])
+def test_a_handful_of_drafts_without_scores(family, dtype, B, S, d, n, r, v, ctx):
+    """With 2 B S <= r and no scores asked for, only the input unit each token is drawn from
+    is evaluated (dot products instead of the pass over W): same draws, same greedy draft."""
+    assert 2 * B * S <= r
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=17 + d + n, h_scale=1.0,
+                         contextual=ctx)
+    head = make_head(inp)
+    logphi, logw, loglayers = oracle_params(inp)
+    seed, off = 0x0123456789ABCDEF, 4
+    near_sum = 0
+    for k in range(4):                                   # few tokens a call: several calls
+        u = philox.uniforms(B, S, n + oc.n_latents(family, n), seed, off + k)
+        od, ol, margin = oc.sample_from(family, logphi, logw, loglayers, u, with_margin=True)
+        gd, gl, gp = head.sample(S, seed=seed, offset=off + k)
+        assert gp is None
+        gdn = gd.cpu().numpy()
+        assert gdn.min() >= 0 and gdn.max() < v
+        near, _ = compare_drafts(gd, gl, od, ol, margin)
+        near_sum += near
+        # the pass over all of W (scores asked for) draws the same tokens
+        gd2, gl2, _ = head.sample(S, seed=seed, offset=off + k, want_prefix=True)
+        same = (gd2 == gd).all(dim=-1).cpu().numpy()
+        assert np.all(same | (margin.reshape(same.shape) < BOUNDARY))
+    assert near_sum <= 2
+    if 2 * B <= r:
+        want_d, want_l, gap = sp.greedy_draft(family, logphi, logw, loglayers)
+        safe = gap >= 1e-6
+        g2, l2, _ = head.greedy_draft()
+        assert np.array_equal(g2.cpu().numpy()[safe], want_d[safe])
+        if l2 is not None and want_l.shape[1]:
+            assert np.array_equal(l2.cpu().numpy()[safe], want_l[safe])
