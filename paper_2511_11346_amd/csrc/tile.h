@@ -5,6 +5,8 @@
 
 #include "mtpc_internal.h"
 
+#include <type_traits>
+
 namespace mtpc {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -41,6 +43,38 @@ struct Tile {
   static_assert(NSLOT * VPL * 64 * 4 <= NS * STAGE, "draw buffer must fit in the stage buffers");
   static_assert(SMEM <= 160 * 1024, "LDS budget of one CU");
 };
+
+// How the accumulators of a wave are laid out.  The tile geometry counts in blocks of 32 rows
+// (VB) x 32 positions (PB) per wave; the MFMA that fills them is either 32x32 (one block each,
+// 16 registers: lane (l % 32, l / 32) holds position column l % 32 and rows 8q + 4 (l / 32) + t,
+// register 4q + t) or 16x16 (M16: four blocks per 32 x 32, 4 registers each: lane (l % 16, l / 16)
+// holds column l % 16 and rows 4 (l / 16) + t).  bf16 kernels with two waves per SIMD take the
+// 16x16x32 instruction: with real operands the chip is power limited, and the same products cost
+// less through it (register operands only: 1.93 against 1.76 PFLOP/s on the same board).
+template <bool M16>
+struct Frag {
+  static constexpr int BR = M16 ? 16 : 32;             // rows and columns of a block
+  static constexpr int NI = M16 ? 4 : 16;              // accumulator registers of a block
+  static constexpr int SUB = 32 / BR;                  // blocks per 32 rows (or columns)
+  using blk_t = typename std::conditional<M16, f32x4_t, f32x16_t>::type;
+  static __device__ __forceinline__ int lcol(int lane) { return lane & (BR - 1); }   // column inside a block
+  static __device__ __forceinline__ int lgrp(int lane) { return lane / BR; }         // this lane's rows start at 4 * lgrp
+  static __device__ __forceinline__ constexpr int roff(int i) { return M16 ? i : 8 * (i >> 2) + (i & 3); }
+  // combine the values the lanes that share a column hold
+  template <class F>
+  static __device__ __forceinline__ float across(float x, F f) {
+    x = f(x, __shfl_xor(x, 32));
+    if constexpr (M16) x = f(x, __shfl_xor(x, 16));
+    return x;
+  }
+};
+
+template <bool BF16>
+__device__ __forceinline__ void mma_step(f32x4_t& acc, const i32x4_t& a, const i32x4_t& b) {
+  static_assert(BF16, "the 16x16 blocks are used by the bf16 kernels only");
+  acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                acc, 0, 0, 0);
+}
 
 template <bool BF16>
 __device__ __forceinline__ void mma_step(f32x16_t& acc, const i32x4_t& a, const i32x4_t& b) {
@@ -120,12 +154,15 @@ __device__ __forceinline__ int swz(int row) {
 // rows[p] / rdiv of h (p < nrows <= TP, nrows >= 1; b0 is ignored and the whole of h,
 // which must span less than 4 GiB, is one resource).  32-row position blocks past nrows
 // are not multiplied (their accumulators stay zero), so a nearly empty tile is cheap.
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false>
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false>
 __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const void* hp, long long ld_h,
                                           int B, int d, int v, int slab, int b0, char* smem,
-                                          f32x16_t (&acc)[PB][VB], const int* rows = nullptr, int nrows = 0,
-                                          int rdiv = 1) {
+                                          typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
+                                          const int* rows = nullptr, int nrows = 0, int rdiv = 1) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  using FR = Frag<M16>;
+  static_assert(!M16 || (BF16 && MTPC_PINGPONG && NS >= 3 && TL::NW == 8 && SB == 64),
+                "16x16 blocks: bf16, two waves per SIMD, one MFMA k-step per 64-byte stage");
   constexpr int ESZ = BF16 ? 2 : 4;
   constexpr int CPR = TL::CPR, KS = TL::KS;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -177,11 +214,11 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   };
 
 #pragma unroll
-  for (int pb = 0; pb < PB; ++pb)
+  for (int pb = 0; pb < PB * FR::SUB; ++pb)
 #pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
+    for (int vb = 0; vb < VB * FR::SUB; ++vb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[pb][vb][i] = 0.f;
+      for (int i = 0; i < FR::NI; ++i) acc[pb][vb][i] = 0.f;
 
   const int KI = d * ESZ / SB;
   const int sw = swz<CPR>(l31);
@@ -216,7 +253,8 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   auto substep = [&](int cs, int ks, const char* nsrc, int nks, int ns, int buf) {
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      if (!GATHER || act[m / VB]) mma_step<BF16>(acc[m / VB][m % VB], fa[cs][m % VB], fb[cs][m / VB]);
+      if constexpr (!M16)
+        if (!GATHER || act[m / VB]) mma_step<BF16>(acc[m / VB][m % VB], fa[cs][m % VB], fb[cs][m / VB]);
 #pragma unroll
       for (int o = 0; o < NOPS; ++o) {
         if ((o * NM) / NOPS != m) continue;          // op o rides behind MFMA o*NM/NOPS
@@ -250,14 +288,31 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     // 2*KI + 2 barriers.
     static_assert(KS == 2, "ping-pong is written for two k-substeps per stage");
     const int group = wave >> 2;
+    // 16x16 blocks: lane (l15, lq) reads chunk lq of row l15 of every 16-row block, the
+    // whole 64-byte stage is one k-step of 2 VB x 2 PB MFMAs
+    const int l15 = lane & 15, lq = lane >> 4;
+    const int sw16 = swz<CPR>(l15);
+    const int a16 = (wv * VB * 32 + l15) * SB + ((lq ^ sw16) << 4);
+    const int b16 = (TL::TV + wb * PB * 32 + l15) * SB + ((lq ^ sw16) << 4);
+    i32x4_t ga[2 * VB], gb[2 * PB];
+    bool act16[2 * PB];
+#pragma unroll
+    for (int pb = 0; pb < 2 * PB; ++pb) act16[pb] = !GATHER || wb * PB * 32 + pb * 16 < hrows;
     if (KI > NS - 2) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
     __syncthreads();                        // stage 0 has landed everywhere
     if (group == 1) __syncthreads();        // start one cluster late
     for (int it = 0; it < KI; ++it) {
       const char* cur = smem + (it % NS) * TL::STAGE;
       // ---- memory cluster
-      load_frags(cur, 0, 0);
-      load_frags(cur, 1, 1);
+      if constexpr (M16) {
+#pragma unroll
+        for (int pb = 0; pb < 2 * PB; ++pb) gb[pb] = *(const i32x4_t*)(cur + b16 + pb * 16 * SB);
+#pragma unroll
+        for (int vb = 0; vb < 2 * VB; ++vb) ga[vb] = *(const i32x4_t*)(cur + a16 + vb * 16 * SB);
+      } else {
+        load_frags(cur, 0, 0);
+        load_frags(cur, 1, 1);
+      }
       if (it + NS - 1 < KI) issue((it + NS - 1) % NS);   // buffer of stage it-1: last read one cluster ago
       if (group == 1) {                     // stage it+1 must be complete before the next barrier
         if (it + NS - 1 < KI) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
@@ -267,8 +322,18 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
       __builtin_amdgcn_sched_barrier(0);
       // ---- compute cluster
       __builtin_amdgcn_s_setprio(1);
-      substep(0, 0, nullptr, 0, 0, -1);
-      substep(1, 1, nullptr, 0, 0, -1);
+      if constexpr (M16) {
+#pragma unroll
+        for (int pb = 0; pb < 2 * PB; ++pb)
+#pragma unroll
+          for (int vb = 0; vb < 2 * VB; ++vb) {
+            if (!GATHER || act16[pb]) mma_step<BF16>(acc[pb][vb], ga[vb], gb[pb]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      } else {
+        substep(0, 0, nullptr, 0, 0, -1);
+        substep(1, 1, nullptr, 0, 0, -1);
+      }
       __builtin_amdgcn_s_setprio(0);
       if (group == 0) {
         if (it + NS - 1 < KI) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
@@ -332,64 +397,67 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
 }
 
 // Softmax statistics of every position column of the tile: max and log-sum-exp
-// over the v vocabulary rows.  Lane (l31, lhalf) of wave (wv, wb) holds, for
-// position column p = wb*PB*32 + pb*32 + l31, the vocabulary rows
-//   row(vb, i) = wv*VB*32 + vb*32 + 8*(i/4) + 4*lhalf + (i%4).
+// over the v vocabulary rows.  With FR = Frag<M16>, lane (lcol, lgrp) of wave (wv, wb) holds, for
+// position column p = wb*PB*32 + pb*FR::BR + lcol, the vocabulary rows
+//   row(vb, i) = wv*VB*32 + vb*FR::BR + 4*lgrp + FR::roff(i).
 // Contains one workgroup barrier; `red` must not be reused before the next one.
-template <int WV, int WB, int VB, int PB, int SB, int NS>
-__device__ __forceinline__ void tile_lse(const f32x16_t (&acc)[PB][VB], int v, float2* red,
-                                         float (&mx)[PB], float (&lse)[PB]) {
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool M16 = false>
+__device__ __forceinline__ void tile_lse(const typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
+                                         int v, float2* red, float (&mx)[PB * Frag<M16>::SUB],
+                                         float (&lse)[PB * Frag<M16>::SUB]) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  using FR = Frag<M16>;
+  constexpr int NPB = PB * FR::SUB, NVB = VB * FR::SUB;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wv = wave % WV, wb = wave / WV;
-  const int l31 = lane & 31, lhalf = lane >> 5;
-  const int rbase = wv * VB * 32 + 4 * lhalf;
+  const int lcol = FR::lcol(lane), lgrp = FR::lgrp(lane);
+  const int rbase = wv * VB * 32 + 4 * lgrp;
   // exp(l - m) = 2^(l * log2(e) - m * log2(e)): one fused multiply-add and one v_exp per logit.
   // A tile whose v fills all TV rows (v = 320 on the 320-row tiles) needs no row masks.
   constexpr float LOG2E = 1.4426950408889634f;
   const bool full = v == TL::TV;
 #pragma unroll
-  for (int pb = 0; pb < PB; ++pb) {
+  for (int pb = 0; pb < NPB; ++pb) {
     float m = neg_inf();
     if (full) {
 #pragma unroll
-      for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) m = fmaxf(m, acc[pb][vb][i]);
+        for (int i = 0; i < FR::NI; ++i) m = fmaxf(m, acc[pb][vb][i]);
     } else {
 #pragma unroll
-      for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+        for (int i = 0; i < FR::NI; ++i) {
+          const int row = rbase + vb * FR::BR + FR::roff(i);
           if (row < v) m = fmaxf(m, acc[pb][vb][i]);
         }
     }
-    m = fmaxf(m, __shfl_xor(m, 32));
+    m = FR::across(m, [](float x, float y) { return fmaxf(x, y); });
     const float ms = (m == neg_inf()) ? 0.f : m;
     const float ms2 = -ms * LOG2E;
     float s = 0.f;
     if (full) {
 #pragma unroll
-      for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s += __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, ms2));
+        for (int i = 0; i < FR::NI; ++i) s += __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, ms2));
     } else {
 #pragma unroll
-      for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+        for (int i = 0; i < FR::NI; ++i) {
+          const int row = rbase + vb * FR::BR + FR::roff(i);
           if (row < v) s += __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, ms2));
         }
     }
-    s += __shfl_xor(s, 32);
-    if (lhalf == 0) red[wv * TL::TP + wb * PB * 32 + pb * 32 + l31] = make_float2(m, s);
+    s = FR::across(s, [](float x, float y) { return x + y; });
+    if (lgrp == 0) red[wv * TL::TP + wb * PB * 32 + pb * FR::BR + lcol] = make_float2(m, s);
   }
   __syncthreads();
 #pragma unroll
-  for (int pb = 0; pb < PB; ++pb) {
-    const int p = wb * PB * 32 + pb * 32 + l31;
+  for (int pb = 0; pb < NPB; ++pb) {
+    const int p = wb * PB * 32 + pb * FR::BR + lcol;
     float M = neg_inf();
 #pragma unroll
     for (int w = 0; w < WV; ++w) M = fmaxf(M, red[w * TL::TP + p].x);

@@ -6,9 +6,9 @@
 //
 // Tiling.  One workgroup computes D = W_slab (v rows) x h_tile^T (TP positions):
 // the vocabulary is the MFMA M dimension, positions the N dimension, so that the
-// 32x32 accumulator block of a lane holds 16 vocabulary rows of ONE position and
-// the softmax reduction is almost entirely lane-local.  Wave grid WV (vocab) x WB
-// (positions); a wave owns VB x PB blocks of 32x32.
+// accumulator block of a lane holds 16 (32x32 MFMA) or 4 (16x16) vocabulary rows of ONE
+// position and the softmax reduction is almost entirely lane-local.  Wave grid WV (vocab)
+// x WB (positions); a wave owns VB x PB blocks of 32x32 (see Frag for the two layouts).
 // K is consumed in stages of SB bytes per row (SB = 64 or 128).  Both operand
 // tiles go from global memory straight into LDS (buffer_load_dwordx4 ... lds) through
 // a ring of NS stages with unpadded, XOR-swizzled rows; fragments are read with
@@ -71,13 +71,14 @@ __device__ __forceinline__ int wave_argmax_token(const float (&vals)[VPL], int l
 // at a time: their accumulator columns are dumped as exp(l - max) in vocabulary order into
 // the (now free) stage buffers, then one wave per position scans its row and calls
 // body(p, vals, ls, incl, Z).
-template <class TL, int VB, int PB, int NSL, class Body>
-__device__ __forceinline__ void tile_draws(const f32x16_t (&acc)[PB][VB], const float (&mx)[PB], int v, char* smem,
-                                           int cnt, Body body) {
+template <class TL, int VB, int PB, int NSL, bool M16, class Body>
+__device__ __forceinline__ void tile_draws(const typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
+                                           const float (&mx)[PB * Frag<M16>::SUB], int v, char* smem, int cnt, Body body) {
+  using FR = Frag<M16>;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wv = wave % (TL::TV / (VB * 32)), wb = wave / (TL::TV / (VB * 32));
-  const int l31 = lane & 31, lhalf = lane >> 5;
-  const int rbase = wv * VB * 32 + 4 * lhalf;
+  const int lcol = FR::lcol(lane);
+  const int rbase = wv * VB * 32 + 4 * FR::lgrp(lane);
   int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
   int* s_slot = s_list + TL::TP;
   float* probs = (float*)smem;
@@ -90,14 +91,14 @@ __device__ __forceinline__ void tile_draws(const f32x16_t (&acc)[PB][VB], const 
     if (tid < nsl) s_slot[s_list[c0 + tid]] = tid;
     __syncthreads();
 #pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      const int sl = s_slot[wb * PB * 32 + pb * 32 + l31];
+    for (int pb = 0; pb < PB * FR::SUB; ++pb) {
+      const int sl = s_slot[wb * PB * 32 + pb * FR::BR + lcol];
       if (sl >= 0) {
 #pragma unroll
-        for (int vb = 0; vb < VB; ++vb)
+        for (int vb = 0; vb < VB * FR::SUB; ++vb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+          for (int i = 0; i < FR::NI; ++i) {
+            const int row = rbase + vb * FR::BR + FR::roff(i);
             probs[sl * SLOT + row] = (row < v) ? expf(acc[pb][vb][i] - mx[pb]) : 0.f;
           }
       }
@@ -124,14 +125,21 @@ __device__ __forceinline__ void tile_draws(const f32x16_t (&acc)[PB][VB], const 
   }
 }
 
+// bf16 tiles of 8 waves (two per SIMD, ping-pong schedule) multiply through 16x16x32 MFMAs
+template <int WV, int WB, int SB, int NS, bool BF16>
+constexpr bool use_m16() { return BF16 && MTPC_PINGPONG && WV * WB == 8 && SB == 64 && NS >= 3; }
+
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_unembed(const UnembedArgs a) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  constexpr bool M16 = use_m16<WV, WB, SB, NS, BF16>();
+  using FR = Frag<M16>;
+  constexpr int NPB = PB * FR::SUB, NVB = VB * FR::SUB;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wv = wave % WV, wb = wave / WV;
-  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int lcol = FR::lcol(lane), lgrp = FR::lgrp(lane);
   const int nslab = a.n * a.r;
   const int nbt = (a.B + TL::TP - 1) / TL::TP;
   int slab, bt;
@@ -139,18 +147,19 @@ void k_unembed(const UnembedArgs a) {
   const int b0 = bt * TL::TP;
   const int wi = slab / a.r, wj = slab - wi * a.r;
 
-  f32x16_t acc[PB][VB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
+  typename FR::blk_t acc[NPB][NVB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
 
-  const int rbase = wv * VB * 32 + 4 * lhalf;
-  float mx[PB], lse[PB];
-  tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
+  // this lane holds, of position column wb*PB*32 + pb*BR + lcol, rows rbase + vb*BR + roff(i)
+  const int rbase = wv * VB * 32 + 4 * lgrp;
+  float mx[NPB], lse[NPB];
+  tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 
   // evidence at the target tokens (the sampling instantiation never has targets)
   if constexpr (!SAMPLE) if (a.targets != nullptr) {
 #pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+    for (int pb = 0; pb < NPB; ++pb) {
+      const int b = b0 + wb * PB * 32 + pb * FR::BR + lcol;
       if (b < a.B) {
         const int TT = a.T + a.T2;
         for (int t = 0; t < TT; ++t) {
@@ -159,25 +168,38 @@ void k_unembed(const UnembedArgs a) {
                                 : a.targets2[((long long)b * a.T2 + (t - a.T)) * a.n + wi];
           float* dst = a.e + (rowid * a.n + wi) * a.r + wj;
           if (x < 0 || x >= a.v) {
-            if (wv == 0 && lhalf == 0) *dst = (x == -1) ? 0.f : __builtin_nanf("");
+            if (wv == 0 && lgrp == 0) *dst = (x == -1) ? 0.f : __builtin_nanf("");
           } else {
-            // the lane holds rows rbase + 32 vb + 8 q + t (q, t in 0..3): first the block vb of
-            // the target row, then its register by the bits of the offset (about 80 selects
-            // instead of a compare and a select for each of the 16 VB registers)
+            // first the block of the target row, then its register by the bits of the offset
+            // (a few dozen selects instead of a compare and a select for every register)
             const int xr = x - rbase;
-            if (xr >= 0 && xr < VB * 32 && (xr & 4) == 0) {
-              const int xvb = xr >> 5;
-              f32x16_t blk = acc[pb][0];
+            if constexpr (M16) {
+              // rows rbase + 16 vb + t (t in 0..3)
+              if (xr >= 0 && xr < VB * 32 && (xr & 12) == 0) {
+                const int xvb = xr >> 4;
+                f32x4_t blk = acc[pb][0];
 #pragma unroll
-              for (int vb = 1; vb < VB; ++vb) blk = (xvb == vb) ? acc[pb][vb] : blk;
-              const bool t0 = xr & 1, t1 = xr & 2, q0 = xr & 8, q1 = xr & 16;
-              const float b0 = t0 ? blk[1] : blk[0], b1 = t0 ? blk[3] : blk[2];
-              const float b2 = t0 ? blk[5] : blk[4], b3 = t0 ? blk[7] : blk[6];
-              const float b4 = t0 ? blk[9] : blk[8], b5 = t0 ? blk[11] : blk[10];
-              const float b6 = t0 ? blk[13] : blk[12], b7 = t0 ? blk[15] : blk[14];
-              const float c0 = t1 ? b1 : b0, c1 = t1 ? b3 : b2, c2 = t1 ? b5 : b4, c3 = t1 ? b7 : b6;
-              const float lo = q0 ? c1 : c0, hi = q0 ? c3 : c2;
-              *dst = (q1 ? hi : lo) - lse[pb];
+                for (int vb = 1; vb < NVB; ++vb) blk = (xvb == vb) ? acc[pb][vb] : blk;
+                const bool t0 = xr & 1, t1 = xr & 2;
+                const float c0 = t0 ? blk[1] : blk[0], c1 = t0 ? blk[3] : blk[2];
+                *dst = (t1 ? c1 : c0) - lse[pb];
+              }
+            } else {
+              // rows rbase + 32 vb + 8 q + t (q, t in 0..3)
+              if (xr >= 0 && xr < VB * 32 && (xr & 4) == 0) {
+                const int xvb = xr >> 5;
+                f32x16_t blk = acc[pb][0];
+#pragma unroll
+                for (int vb = 1; vb < VB; ++vb) blk = (xvb == vb) ? acc[pb][vb] : blk;
+                const bool t0 = xr & 1, t1 = xr & 2, q0 = xr & 8, q1 = xr & 16;
+                const float b0 = t0 ? blk[1] : blk[0], b1 = t0 ? blk[3] : blk[2];
+                const float b2 = t0 ? blk[5] : blk[4], b3 = t0 ? blk[7] : blk[6];
+                const float b4 = t0 ? blk[9] : blk[8], b5 = t0 ? blk[11] : blk[10];
+                const float b6 = t0 ? blk[13] : blk[12], b7 = t0 ? blk[15] : blk[14];
+                const float c0 = t1 ? b1 : b0, c1 = t1 ? b3 : b2, c2 = t1 ? b5 : b4, c3 = t1 ? b7 : b6;
+                const float lo = q0 ? c1 : c0, hi = q0 ? c3 : c2;
+                *dst = (q1 ? hi : lo) - lse[pb];
+              }
             }
           }
         }
@@ -187,18 +209,18 @@ void k_unembed(const UnembedArgs a) {
   if constexpr (!SAMPLE) if (a.phiT != nullptr) {
     // keep the normalised probabilities for the training step (transposed: positions contiguous)
 #pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+    for (int pb = 0; pb < NPB; ++pb) {
+      const int b = b0 + wb * PB * 32 + pb * FR::BR + lcol;
       if (b < a.B) {
         // phi = 2^((l - lse) log2 e): one fused multiply-add and one v_exp per probability
         constexpr float LOG2E = 1.4426950408889634f;
         const float shift = -lse[pb] * LOG2E;
         float* col = a.phiT + ((long long)slab * a.v + rbase) * a.ld_phi + b;
 #pragma unroll
-        for (int vb = 0; vb < VB; ++vb)
+        for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int off = vb * 32 + 8 * (i >> 2) + (i & 3);
+          for (int i = 0; i < FR::NI; ++i) {
+            const int off = vb * FR::BR + FR::roff(i);
             if (rbase + off < a.v) col[off * a.ld_phi] = __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, shift));
           }
       }
@@ -211,15 +233,15 @@ void k_unembed(const UnembedArgs a) {
     // when v is a multiple of 4; otherwise element by element)
     const bool vec = (a.v & 3) == 0;
 #pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+    for (int pb = 0; pb < NPB; ++pb) {
+      const int b = b0 + wb * PB * 32 + pb * FR::BR + lcol;
       if (b >= a.B) continue;
       float* dst = a.logphi + (((long long)b * a.n + wi) * a.r + wj) * a.v;
 #pragma unroll
-      for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int row = rbase + vb * 32 + 8 * q;
+        for (int q = 0; q < FR::NI / 4; ++q) {
+          const int row = rbase + vb * FR::BR + FR::roff(4 * q);
           if (vec) {
             if (row < a.v)
               *(f32x4_t*)(dst + row) = f32x4_t{acc[pb][vb][4 * q] - lse[pb], acc[pb][vb][4 * q + 1] - lse[pb],
@@ -250,7 +272,7 @@ void k_unembed(const UnembedArgs a) {
     }
     __syncthreads();
     const int cnt = *s_cnt;
-    tile_draws<TL, VB, PB, NSLOT>(acc, mx, a.v, smem, cnt, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
+    tile_draws<TL, VB, PB, NSLOT, M16>(acc, mx, a.v, smem, cnt, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
                                                         float Z) {
       const int b = b0 + p;
       for (int s = 0; s < a.S; ++s) {
@@ -301,15 +323,16 @@ void k_draw_gather(const DrawGatherArgs a) {
   const int* rows = a.list + first;
   const int wi = g / a.r;
 
-  f32x16_t acc[PB][VB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, true>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, g, 0, smem, acc, rows, nrows, a.S);
-  float mx[PB], lse[PB];
-  tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
+  constexpr bool M16 = use_m16<WV, WB, SB, NS, BF16>();
+  typename Frag<M16>::blk_t acc[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, true, M16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, g, 0, smem, acc, rows, nrows, a.S);
+  float mx[PB * Frag<M16>::SUB], lse[PB * Frag<M16>::SUB];
+  tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 
   int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
   for (int p = tid; p < nrows; p += TL::NT) s_list[p] = p;
   __syncthreads();
-  tile_draws<TL, VB, PB, MTPC_GATHER_NSL>(acc, mx, a.v, smem, nrows, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
+  tile_draws<TL, VB, PB, MTPC_GATHER_NSL, M16>(acc, mx, a.v, smem, nrows, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
                                                         float Z) {
     const int rid = rows[p];                         // b * S + s
     const int b = rid / a.S, s = rid - b * a.S;
