@@ -21,10 +21,13 @@ template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_unembed_grad(const GradLogitsArgs a) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  constexpr bool M16 = use_m16<WV, WB, SB, NS, BF16>();
+  using FR = Frag<M16>;
+  constexpr int NPB = PB * FR::SUB, NVB = VB * FR::SUB;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wv = wave % WV, wb = wave / WV;
-  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int lcol = FR::lcol(lane), lgrp = FR::lgrp(lane);
   const int nslab = a.n * a.r;
   const int nbt = (int)((a.ldb + TL::TP - 1) / TL::TP);
   int slab, bt;
@@ -43,37 +46,43 @@ void k_unembed_grad(const GradLogitsArgs a) {
     return;
   }
 
-  f32x16_t acc[PB][VB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
-  const int rbase = wv * VB * 32 + 4 * lhalf;
-  float mx[PB], lse[PB];
-  tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
+  typename FR::blk_t acc[NPB][NVB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
+  const int rbase = wv * VB * 32 + 4 * lgrp;
+  float mx[NPB], lse[NPB];
+  tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 
+  float g[NPB];
+  int x[NPB];
 #pragma unroll
-  for (int pb = 0; pb < PB; ++pb) {
-    const int b = b0 + wb * PB * 32 + pb * 32 + l31;
-    if (b >= a.ldb) continue;
-    float g = 0.f;
-    int x = -1;
+  for (int pb = 0; pb < NPB; ++pb) {
+    const int b = b0 + wb * PB * 32 + pb * FR::BR + lcol;
+    g[pb] = 0.f;
+    x[pb] = -1;
     if (b < a.B) {
-      x = a.targets[(long long)b * a.n + wi];
+      x[pb] = a.targets[(long long)b * a.n + wi];
       // a summed-out variable (-1) has constant evidence: no gradient reaches its logits
-      g = (x == -1) ? 0.f : a.Ge[((long long)b * a.n + wi) * a.r + wj];
+      g[pb] = (x[pb] == -1) ? 0.f : a.Ge[((long long)b * a.n + wi) * a.r + wj];
     }
-#pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
-        if (row < a.v) {
-          float val = 0.f;
-          if (b < a.B && x != -1) val = g * ((row == x ? 1.f : 0.f) - __expf(acc[pb][vb][i] - lse[pb]));
-          const long long o = ((long long)slab * a.v + row) * a.ldb + b;
-          if constexpr (BF16) ((unsigned short*)a.dLT)[o] = f32_to_bf16_rne(val);
-          else ((float*)a.dLT)[o] = val;
-        }
-      }
   }
+  // the column blocks of a row back to back: together they fill whole lines
+#pragma unroll
+  for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+    for (int i = 0; i < FR::NI; ++i) {
+      const int row = rbase + vb * FR::BR + FR::roff(i);
+      if (row >= a.v) continue;
+#pragma unroll
+      for (int pb = 0; pb < NPB; ++pb) {
+        const int b = b0 + wb * PB * 32 + pb * FR::BR + lcol;
+        if (b >= a.ldb) continue;
+        float val = 0.f;
+        if (b < a.B && x[pb] != -1) val = g[pb] * ((row == x[pb] ? 1.f : 0.f) - __expf(acc[pb][vb][i] - lse[pb]));
+        const long long o = ((long long)slab * a.v + row) * a.ldb + b;
+        if constexpr (BF16) ((unsigned short*)a.dLT)[o] = f32_to_bf16_rne(val);
+        else ((float*)a.dLT)[o] = val;
+      }
+    }
 }
 
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
@@ -107,11 +116,14 @@ template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_gemm_tn(const GemmArgs a) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  constexpr bool M16 = use_m16<WV, WB, SB, NS, BF16>();
+  using FR = Frag<M16>;
+  constexpr int NPB = PB * FR::SUB, NVB = VB * FR::SUB;
   constexpr int ESZ = BF16 ? 2 : 4;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wv = wave % WV, wb = wave / WV;
-  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int lcol = FR::lcol(lane), lgrp = FR::lgrp(lane);
   const int nslab = (a.M + TL::TV - 1) / TL::TV;
   const int nbt = (a.N + TL::TP - 1) / TL::TP;
   int slab, bt;
@@ -121,11 +133,11 @@ void k_gemm_tn(const GemmArgs a) {
   const int b0 = bt * TL::TP;
   const int rows = min(TL::TV, a.M - slab * TL::TV);
   const int k0 = ks * a.kchunk, klen = min(a.kchunk, a.K - k0);
-  f32x16_t acc[PB][VB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16>((const char*)a.A + ((long long)slab * TL::TV * a.lda + k0) * ESZ, a.lda,
-                                          (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0, b0,
-                                          smem, acc);
-  const int rbase = wv * VB * 32 + 4 * lhalf;
+  typename FR::blk_t acc[NPB][NVB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>((const char*)a.A + ((long long)slab * TL::TV * a.lda + k0) * ESZ, a.lda,
+                                                      (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0,
+                                                      b0, smem, acc);
+  const int rbase = wv * VB * 32 + 4 * lgrp;
   // A full tile that lies inside one destination (the common case): one base pointer per
   // column, rows at constant multiples of ldc.
   {
@@ -136,25 +148,26 @@ void k_gemm_tn(const GemmArgs a) {
       else if (gr0 + TL::TV <= a.split) base = a.C + gr0 * a.ldc;
     }
     if (base != nullptr) {
+      // the column blocks of a row back to back: together they fill whole lines
+      const int col0 = b0 + wb * PB * 32 + lcol;
+      float* cp = base + (long long)rbase * a.ldc + col0;
 #pragma unroll
-      for (int pb = 0; pb < PB; ++pb) {
-        const int col = b0 + wb * PB * 32 + pb * 32 + l31;
-        if (col >= a.N) continue;
-        float* cp = base + (long long)rbase * a.ldc + col;
+      for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int vb = 0; vb < VB; ++vb)
+        for (int i = 0; i < FR::NI; ++i)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) cp[(long long)(vb * 32 + 8 * (i >> 2) + (i & 3)) * a.ldc] = acc[pb][vb][i];
-      }
+          for (int pb = 0; pb < NPB; ++pb)
+            if (col0 + pb * FR::BR < a.N)
+              cp[(long long)(vb * FR::BR + FR::roff(i)) * a.ldc + pb * FR::BR] = acc[pb][vb][i];
       return;
     }
   }
   // one destination row at a time (keeps the address arithmetic out of the 160 live accumulators)
 #pragma unroll
-  for (int vb = 0; vb < VB; ++vb)
+  for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+    for (int i = 0; i < FR::NI; ++i) {
+      const int row = rbase + vb * FR::BR + FR::roff(i);
       if (row >= rows) continue;
       const long long gr = (long long)slab * TL::TV + row;
       float* rp = nullptr;
@@ -164,8 +177,8 @@ void k_gemm_tn(const GemmArgs a) {
       else if (gr >= a.split3) rp = a.C3 + (gr - a.split3) * a.ldc;
       if (rp == nullptr) continue;
 #pragma unroll
-      for (int pb = 0; pb < PB; ++pb) {
-        const int col = b0 + wb * PB * 32 + pb * 32 + l31;
+      for (int pb = 0; pb < NPB; ++pb) {
+        const int col = b0 + wb * PB * 32 + pb * FR::BR + lcol;
         if (col < a.N) rp[col] = acc[pb][vb][i];
       }
     }

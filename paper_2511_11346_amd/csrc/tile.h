@@ -69,6 +69,10 @@ struct Frag {
   }
 };
 
+// bf16 tiles of 8 waves (two per SIMD, ping-pong schedule) multiply through 16x16x32 MFMAs
+template <int WV, int WB, int SB, int NS, bool BF16>
+constexpr bool use_m16() { return BF16 && MTPC_PINGPONG && WV * WB == 8 && SB == 64 && NS >= 3; }
+
 template <bool BF16>
 __device__ __forceinline__ void mma_step(f32x4_t& acc, const i32x4_t& a, const i32x4_t& b) {
   static_assert(BF16, "the 16x16 blocks are used by the bf16 kernels only");

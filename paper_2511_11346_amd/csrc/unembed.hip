@@ -125,10 +125,6 @@ __device__ __forceinline__ void tile_draws(const typename Frag<M16>::blk_t (&acc
   }
 }
 
-// bf16 tiles of 8 waves (two per SIMD, ping-pong schedule) multiply through 16x16x32 MFMAs
-template <int WV, int WB, int SB, int NS, bool BF16>
-constexpr bool use_m16() { return BF16 && MTPC_PINGPONG && WV * WB == 8 && SB == 64 && NS >= 3; }
-
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_unembed(const UnembedArgs a) {
@@ -207,24 +203,26 @@ void k_unembed(const UnembedArgs a) {
     }
   }
   if constexpr (!SAMPLE) if (a.phiT != nullptr) {
-    // keep the normalised probabilities for the training step (transposed: positions contiguous)
+    // keep the normalised probabilities for the training step (transposed: positions contiguous;
+    // the column blocks of a row are stored back to back, together they fill whole lines).
+    // phi = 2^((l - lse) log2 e): one fused multiply-add and one v_exp per probability
+    constexpr float LOG2E = 1.4426950408889634f;
+    const int bl = b0 + wb * PB * 32 + lcol;
+    float* col = a.phiT + ((long long)slab * a.v + rbase) * a.ld_phi + bl;
+    float shift[NPB];
 #pragma unroll
-    for (int pb = 0; pb < NPB; ++pb) {
-      const int b = b0 + wb * PB * 32 + pb * FR::BR + lcol;
-      if (b < a.B) {
-        // phi = 2^((l - lse) log2 e): one fused multiply-add and one v_exp per probability
-        constexpr float LOG2E = 1.4426950408889634f;
-        const float shift = -lse[pb] * LOG2E;
-        float* col = a.phiT + ((long long)slab * a.v + rbase) * a.ld_phi + b;
+    for (int pb = 0; pb < NPB; ++pb) shift[pb] = -lse[pb] * LOG2E;
 #pragma unroll
-        for (int vb = 0; vb < NVB; ++vb)
+    for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-          for (int i = 0; i < FR::NI; ++i) {
-            const int off = vb * FR::BR + FR::roff(i);
-            if (rbase + off < a.v) col[off * a.ld_phi] = __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, shift));
-          }
+      for (int i = 0; i < FR::NI; ++i) {
+        const int off = vb * FR::BR + FR::roff(i);
+        if (rbase + off >= a.v) continue;
+#pragma unroll
+        for (int pb = 0; pb < NPB; ++pb)
+          if (bl + pb * FR::BR < a.B)
+            col[off * a.ld_phi + pb * FR::BR] = __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, shift[pb]));
       }
-    }
   }
   if (a.logphi != nullptr) {
     // table log phi[b][wi][wj][:] for the scoring and verification steps.  Registers
