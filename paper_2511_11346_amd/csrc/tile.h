@@ -312,12 +312,10 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     bool act16[2 * PB];
 #pragma unroll
     for (int pb = 0; pb < 2 * PB; ++pb) act16[pb] = !GATHER || wb * PB * 32 + pb * 16 < hrows;
-    if (KI > NS - 2) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-    __syncthreads();                        // stage 0 has landed everywhere
-    if (group == 1) __syncthreads();        // start one cluster late
-    for (int it = 0; it < KI; ++it) {
+    // memory cluster of stage `it`: its fragments, and the loads of stage it+NS-1 into the
+    // buffer of stage it-1 (last read before the previous barrier)
+    auto mem_cluster = [&](int it) {
       const char* cur = smem + (it % NS) * TL::STAGE;
-      // ---- memory cluster
       if constexpr (M16) {
 #pragma unroll
         for (int pb = 0; pb < 2 * PB; ++pb) gb[pb] = *(const i32x4_t*)(cur + b16 + pb * 16 * SB);
@@ -327,14 +325,11 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
         load_frags(cur, 0, 0);
         load_frags(cur, 1, 1);
       }
-      if (it + NS - 1 < KI) issue((it + NS - 1) % NS);   // buffer of stage it-1: last read one cluster ago
-      if (group == 1) {                     // stage it+1 must be complete before the next barrier
-        if (it + NS - 1 < KI) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-      }
+      if (it + NS - 1 < KI) issue((it + NS - 1) % NS);
       __builtin_amdgcn_sched_barrier(0);
-      __syncthreads();
+    };
+    auto compute_cluster = [&]() {
       __builtin_amdgcn_sched_barrier(0);
-      // ---- compute cluster
       __builtin_amdgcn_s_setprio(1);
       if constexpr (M16) {
 #pragma unroll
@@ -349,12 +344,27 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
         substep(1, 1, nullptr, 0, 0, -1);
       }
       __builtin_amdgcn_s_setprio(0);
-      if (group == 0) {
-        if (it + NS - 1 < KI) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // own loads of stage it+1 have landed (stages up to it+NS-1 are issued)
+    auto wait_next = [&](int it) {
+      if (it + NS - 1 < KI) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
+    };
+    auto barrier = [&]() {
       __builtin_amdgcn_sched_barrier(0);
       __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
+    };
+    if (KI > NS - 2) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
+    __syncthreads();                        // stage 0 has landed everywhere
+    if (group == 1) __syncthreads();        // start one cluster late
+    for (int it = 0; it < KI; ++it) {
+      mem_cluster(it);
+      if (group == 1) wait_next(it);        // stage it+1 must be complete before the next barrier
+      barrier();
+      compute_cluster();
+      if (group == 0) wait_next(it);
+      barrier();
     }
     if (group == 0) __syncthreads();        // pairs with the late start of the other group
   } else
