@@ -294,6 +294,9 @@ void k_unembed(const UnembedArgs a) {
 #ifndef MTPC_GATHER_NSL
 #define MTPC_GATHER_NSL 16
 #endif
+#ifndef MTPC_GATHER_SB
+#define MTPC_GATHER_SB 64
+#endif
 #ifndef MTPC_GATHER_NS
 #define MTPC_GATHER_NS 4
 #endif
@@ -349,9 +352,9 @@ void k_draw_gather(const DrawGatherArgs a) {
 
 template <int WV, int WB, int VB, int PB, bool BF16>
 static hipError_t launch_draw_gather_cfg(const DrawGatherArgs& a, hipStream_t st) {
-  using TL = Tile<WV, WB, VB, PB, 64, MTPC_GATHER_NS>;
+  using TL = Tile<WV, WB, VB, PB, MTPC_GATHER_SB, MTPC_GATHER_NS>;
   static_assert(TL::TP == DRAW_GATHER_TILE, "the bucketing kernels count tiles of this many rows");
-  auto kern = k_draw_gather<WV, WB, VB, PB, 64, MTPC_GATHER_NS, BF16>;
+  auto kern = k_draw_gather<WV, WB, VB, PB, MTPC_GATHER_SB, MTPC_GATHER_NS, BF16>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);

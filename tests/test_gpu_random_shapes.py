@@ -98,6 +98,8 @@ def test_every_operation_on_a_drawn_shape(family, dtype, B, d, n, r, v):
         steps = {"btree": 7 * n, "hmm": n}.get(family, 1)
         lim_sum = max(5e-4, 6e-5 * np.sqrt(steps))
         lim = (lim_sum if name in ("dWsum", "dlayers") else 1e-4) if (dtype == "f32" or name == "dlayers") else 2e-2
-        # 1e-7: with a one-token vocabulary every gradient is exactly zero and only rounding is left
-        # (a few 1e-8 after the sums over positions and reverse steps)
-        assert np.abs(got - ref[name]).max() <= lim * scale + 1e-7, (name, np.abs(got - ref[name]).max() / scale)
+        # floor: with a one-token vocabulary every gradient is exactly zero and only the rounding of
+        # the fp32 sums is left, one unit in the last place of their largest summands: the coefficients
+        # of all windows times the largest |h| (1.9e-7 seen for a tree over 16 tokens at B = 1)
+        floor = max(1e-7, 2.0 ** -23 * float(coef.sum()) * float(np.abs(inp.h.astype(np.float64)).max()))
+        assert np.abs(got - ref[name]).max() <= lim * scale + floor, (name, np.abs(got - ref[name]).max() / scale)
