@@ -325,10 +325,12 @@ __global__ __launch_bounds__(256) void k_circuit(const CircuitArgs a, int G, int
   if (a.family == MTPC_FF) {
 #pragma unroll
     for (int q = 0; q < RB; ++q) {
-      float acc = 0.f;
+      // a running sum of up to 64 terms near -6 each: kept in double, so that the fp32 result
+      // carries one rounding instead of one per token (an ulp is 3e-5 at 400)
+      double acc = 0.0;
       for (int i = 0; i < n; ++i) {
-        acc += e[q][i * r];
-        emit(q, i, acc);
+        acc += (double)e[q][i * r];
+        emit(q, i, (float)acc);
       }
     }
     return;
