@@ -290,12 +290,42 @@ def main():
                 cycle()
             ms_graph = time_op(graph.replay, reps)
             del graph
+            # greedy speculative decoding (Sec. 3.4): the draft is the argmax traversal, a token
+            # survives iff it is the verifier's argmax - no scores and no table are needed, so for
+            # a handful of positions only the n slabs the draft selects are read
+            # (synthetic verifier: the drafted component, with half of the mass moved onto the drafted
+            # token at 9 of 10 places and onto a random token at the others)
+            gdr, glat, _ = hd.greedy_draft()
+            qg = torch.exp(table[torch.arange(Bd, device=dev), :, glat[:, 0].long(), :])
+            gen = torch.Generator().manual_seed(17)
+            agree = (torch.rand(Bd, inp5.n, generator=gen) < 0.9).to(dev)
+            other = torch.randint(0, inp5.v, (Bd, inp5.n), generator=gen).to(dev)
+            peak = torch.where(agree, gdr.long(), other)
+            pverg = torch.cat([0.5 * qg + 0.5 * torch.nn.functional.one_hot(peak, inp5.v).float(), noise[:, inp5.n:]], dim=1)
+            pverg = (pverg / pverg.sum(-1, keepdim=True)).contiguous()
+            def greedy_cycle():
+                g, _, _ = hd.greedy_draft(want_latents=False)
+                return hd.verify(g, pverg, mode="greedy")
+            ms_gdraft = time_op(lambda: hd.greedy_draft(want_latents=False), reps)
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                greedy_cycle()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            ggraph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(ggraph):
+                gacc, _ = greedy_cycle()
+            ms_ggraph = time_op(ggraph.replay, reps)
+            mean_gacc = float(gacc.float().mean())
+            del ggraph
             dec.append({"B": Bd, "call_ms": call_ms, "drafts_per_s": Bd / (call_ms * 1e-3),
                         "k_unembed_ms": kms, "achieved_GBps": byts / (kms * 1e-3) / 1e9,
                         "frac_of_hbm_peak": byts / (kms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
                         "call_ms_keeping_table": ms_table, "verify_call_ms": ms_verify,
                         "cycle_ms_from_graph": ms_graph, "score_16_prefixes_per_draft_ms": ms_16,
-                        "mean_accepted": float(acc.float().mean())})
+                        "mean_accepted": float(acc.float().mean()),
+                        "greedy_draft_call_ms": ms_gdraft, "greedy_cycle_ms_from_graph": ms_ggraph,
+                        "greedy_mean_accepted": mean_gacc})
         out["decode_cp_r32_n16"] = dec
 
     if not args.no_cpu:

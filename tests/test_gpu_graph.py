@@ -99,3 +99,39 @@ def test_training_sized_step_replays_from_a_graph(family):
         assert torch.equal(P_g, P_e), k
         head.loglik(tg[:, 0].contiguous())                 # eager work on the same head and workspace
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("family", ["cp", "btree"])
+def test_greedy_cycle_of_a_few_positions_replays_from_a_graph(family):
+    """Greedy draft without scores (only the slabs the draft selects are read) + greedy verification."""
+    B, n, r, v = 2, 8, 16, 300
+    inp = mi.make_inputs(family, B=B, d=256, n=n, r=r, v=v, dtype="bf16", seed=47, h_scale=1.0)
+    head = make_head(inp)
+    dev = "cuda"
+    pver = torch.from_numpy(mi.verifier_noise(B, n, v, seed=3, peak=1.0).astype(np.float32)).to(dev)
+
+    def cycle():
+        g, _, _ = head.greedy_draft(want_latents=False)
+        acc, tok = head.verify(g, pver, mode="greedy")
+        return g, acc, tok
+
+    g_e, acc_e, tok_e = cycle()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        cycle()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g_g, acc_g, tok_g = cycle()
+    tg = torch.from_numpy(inp.targets).cuda()
+    for k in range(4):
+        g_g.zero_()
+        acc_g.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g_g, g_e) and torch.equal(acc_g, acc_e) and torch.equal(tok_g, tok_e), k
+        head.loglik(tg)                                    # eager work on the same head and workspace
+        torch.cuda.synchronize()
