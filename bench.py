@@ -173,6 +173,9 @@ def main():
     ms_tab = time_op(lambda: head.table_scores(table, tg, prefix=True, out=P))
     del table
     ms_samp_only = time_op(lambda: head.sample(S, seed=0, out=(drafts, lat, None)))
+    uni = torch.empty(B, n, inp.v, dtype=torch.float32, device=dev)
+    ms_uni = time_op(lambda: head.univariate_marginals(out=uni), 5)
+    del uni
 
     flops = 2.0 * B * inp.n * inp.r * inp.v * inp.d
     # training step of the same workload (Sec. 4.1 loss + gradients w.r.t. h, W, Wsum): the forward
@@ -206,7 +209,8 @@ def main():
         "roofline": roofline,
         "ops_ms": {"sample_only": ms_samp_only, "window_scores_targets_and_drafts": ms_win,
                    "prefix_marginals_call": ms_marg, "sample_with_scores": ms_samp,
-                   "sample_with_scores_and_table": ms_samp_tab, "table_scores_of_targets": ms_tab},
+                   "sample_with_scores_and_table": ms_samp_tab, "table_scores_of_targets": ms_tab,
+                   "univariate_marginals_call": ms_uni},
         "loglik_windows_per_s": B / (ms_marg * 1e-3),
         "train_step": {"loss_backward_ms": ms_train, "windows_per_s": B / (ms_train * 1e-3),
                        "matrix_passes": 3, "TFLOPs": 3 * flops / (ms_train * 1e-3) / 1e12},

@@ -116,7 +116,11 @@ mtpc_status mtpc_btree_loglik(const mtpc_head* head, const mtpc_sumlayers* A,
  * MTPC_MARG_PREFIX (Alg. 2, prefix marginals used by the accept test):
  *   out [B][n], out[b][i] = log q(x_1..x_{i+1}); out[b][n-1] is the log-likelihood.
  * MTPC_MARG_UNIVARIATE: out [B][n][v], out[b][i][a] = log q(x_{i+1} = a);
- *   targets is ignored and may be NULL. */
+ *   targets is ignored and may be NULL.  The size mtpc_workspace_bytes returns has room for
+ *   the input units of all positions (B n r v floats, when that is at most 8 GiB and r > 1):
+ *   one pass writes them, a second kernel mixes them.  A workspace smaller by that many bytes
+ *   is accepted too; the r units of a token are then mixed in registers (slower, above all
+ *   for a few positions). */
 mtpc_status mtpc_ff_marginals(const mtpc_head* head, const int32_t* targets, int32_t mode, float* out);
 mtpc_status mtpc_cp_marginals(const mtpc_head* head, const int32_t* targets, int32_t mode, float* out);
 mtpc_status mtpc_hmm_marginals(const mtpc_head* head, const mtpc_sumlayers* T,

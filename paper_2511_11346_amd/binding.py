@@ -201,10 +201,15 @@ class Head:
         _check(self._call("marginals", hd, targets.data_ptr(), MARG_PREFIX, out.data_ptr()))
         return out
 
-    def univariate_marginals(self, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    def univariate_marginals(self, out: Optional[torch.Tensor] = None, keep_table: bool = True) -> torch.Tensor:
+        """[B,n,v] log marginal of every token.  keep_table=False hands the library a workspace without
+        room for the table of input units (B n r v floats): the mixture is then formed in registers."""
         if out is None:
             out = torch.empty(self.B, self.n, self.v, dtype=torch.float32, device=self.h.device)
-        hd = self._head(self.workspace_bytes(OP_MARGINALS, mode=MARG_UNIVARIATE))
+        need = self.workspace_bytes(OP_MARGINALS, mode=MARG_UNIVARIATE)
+        hd = self._head(need)
+        if not keep_table and self.r > 1:
+            hd.workspace_bytes = max(need - 4 * self.B * self.n * self.r * self.v, 16)
         _check(self._call("marginals", hd, None, MARG_UNIVARIATE, out.data_ptr()))
         return out
 

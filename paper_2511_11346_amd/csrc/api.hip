@@ -44,9 +44,12 @@ bool buckets_pay(const mtpc_head* hd, int S, bool want_scores) {
 // A handful of drafts without scores (2 B S <= r, say batch-1 greedy speculative decoding): only
 // the n slabs a draft's tokens are drawn from are read, as plain dot products.
 bool few_drafts(const mtpc_head* hd, int S) { return 2LL * hd->B * S <= hd->r; }
+bool table_fits(const mtpc_head* hd) {
+  return (unsigned long long)hd->B * hd->n * hd->r * hd->v * 4ull <= (8ull << 30);
+}
 bool table_in_workspace(const mtpc_head* hd, int S) {      // for a sampling call that wants scores
   if (buckets_pay(hd, S, true)) return false;
-  return (unsigned long long)hd->B * hd->n * hd->r * hd->v * 4ull <= (8ull << 30);   // else a second pass
+  return table_fits(hd);                                   // else a second pass
 }
 
 // most windows per position whose rows B*T*n still index with an int
@@ -57,10 +60,12 @@ long long hd_rows_limit(const mtpc_head* hd) {
 
 struct Plan {           // byte offsets into the workspace
   size_t logw, lay_nat, lay_circ, e, zleaf, lat, logm, table, total;
+  size_t lean_total;    // univariate marginals: the plan without the table
   size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_tilebucket, bk_list;
   size_t rowlogits;     // compact table of the few-drafts path   // buckets of the token draws (large batches)
   int nb, Lst;          // position blocks and stored layers of the normalised copies
-  bool has_table;       // room for the table of input units (sampling with scores, see decode_sized)
+  bool has_table;       // room for the table of input units (sampling with scores, see decode_sized;
+                        // univariate marginals of a head with sum units whose table is at most 8 GiB)
 };
 
 mtpc_status check_head(int family, const mtpc_head* hd) {
@@ -142,6 +147,11 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   p.zleaf = sample ? take(B * (size_t)S * n * 4) : 0;
   p.lat = sample ? take(B * (size_t)S * (size_t)(n_latents(family, hd->n) + 1) * 4) : 0;
   p.logm = uni ? take(B * n * r * 4) : 0;
+  p.lean_total = off;
+  if (uni && r > 1 && table_fits(hd)) {       // last, so that a caller may leave it out (see prepare)
+    p.has_table = true;
+    p.table = take(B * n * r * (size_t)hd->v * 4);
+  }
   p.total = off;
   return p;
 }
@@ -167,7 +177,14 @@ mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayer
   if ((op == MTPC_OP_SAMPLE || op == MTPC_OP_TABLE || op == MTPC_OP_WINDOWS) && S < 1) return MTPC_ERR_SHAPE;
   plan = make_plan(family, op, hd, ly, S, mode, want_prefix);
   if (!hd->workspace) return MTPC_ERR_NULL;
-  if (((uintptr_t)hd->workspace & 15) || hd->workspace_bytes < plan.total) return MTPC_ERR_WORKSPACE;
+  if ((uintptr_t)hd->workspace & 15) return MTPC_ERR_WORKSPACE;
+  if (hd->workspace_bytes < plan.total) {
+    // univariate marginals run without the table when the workspace has no room for it
+    const bool uni = op == MTPC_OP_MARGINALS && mode == MTPC_MARG_UNIVARIATE;
+    if (!uni || !plan.has_table || hd->workspace_bytes < plan.lean_total) return MTPC_ERR_WORKSPACE;
+    plan.has_table = false;
+    plan.total = plan.lean_total;
+  }
   return MTPC_OK;
 }
 
@@ -261,6 +278,19 @@ mtpc_status run_univariate(int family, const mtpc_head* hd, const mtpc_sumlayers
     m.logm = (float*)(ws + p.logm);
     HIP_TRY(launch_latent_marginals(m, st));
     u.logm = m.logm;
+  }
+  // One pass of the evidence kernel that only writes log phi (the head without sum units: straight
+  // into `out`, which is that table), then the mixture over the r units per token.  A table
+  // above 8 GiB is not kept: the slabs of a token are then mixed in registers, on smaller tiles.
+  if (family == MTPC_FF || p.has_table) {
+    UnembedArgs t = unembed_args(hd);
+    t.logphi = family == MTPC_FF ? out : (float*)(ws + p.table);
+    {
+      ProfScope prof(st);
+      HIP_TRY(launch_unembed(t, hd->dtype, st));
+    }
+    if (family != MTPC_FF) HIP_TRY(launch_univariate_table(u, t.logphi, st));
+    return MTPC_OK;
   }
   {
     ProfScope prof(st);

@@ -1200,6 +1200,61 @@ hipError_t launch_rows_logits(const RowLogitArgs& a, int dtype, hipStream_t st) 
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Univariate marginals (App. B.1) from the table of normalised input units:
+//   M[b][i][a] = log sum_j exp(logm[b][i][j] + log phi[b][i][j][a]).
+// One wave per (b, i); lane l holds tokens l, l + 64, ...; the r rows of the table are read
+// once, front to back (whole 256-byte segments), into a running maximum and a sum relative to it.
+__global__ __launch_bounds__(256) void k_univariate_table(const float* logphi, const float* logm, float* out,
+                                                          long long tokens, int r, int v) {
+  constexpr int VPL = 5;                      // v <= 320
+  const int lane = threadIdx.x & 63;
+  const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);       // (b, i) flattened
+  if (t >= tokens) return;
+  const float* rows = logphi + t * r * v;
+  float m[VPL], s[VPL];
+#pragma unroll
+  for (int q = 0; q < VPL; ++q) { m[q] = neg_inf(); s[q] = 0.f; }
+  constexpr int JB = 4;                       // rows fetched together
+  for (int j0 = 0; j0 < r; j0 += JB) {
+    float x[JB][VPL];
+#pragma unroll
+    for (int u = 0; u < JB; ++u) {
+      const int j = min(j0 + u, r - 1);
+      const float lm = (j0 + u < r) ? (logm ? logm[t * r + j] : 0.f) : neg_inf();
+#pragma unroll
+      for (int q = 0; q < VPL; ++q) {
+        const int k = lane + 64 * q;
+        x[u][q] = lm + rows[(long long)j * v + min(k, v - 1)];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < VPL; ++q) {
+      float mm = m[q];
+#pragma unroll
+      for (int u = 0; u < JB; ++u) mm = fmaxf(mm, x[u][q]);
+      if (mm == neg_inf()) continue;          // only terms of probability zero so far
+      float ss = s[q] * __expf(m[q] - mm);    // (m = -inf: s = 0, exp(-inf) = 0)
+#pragma unroll
+      for (int u = 0; u < JB; ++u) ss += __expf(x[u][q] - mm);
+      m[q] = mm;
+      s[q] = ss;
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < VPL; ++q) {
+    const int k = lane + 64 * q;
+    if (k < v) out[t * v + k] = s[q] > 0.f ? m[q] + __logf(s[q]) : neg_inf();
+  }
+}
+
+hipError_t launch_univariate_table(const UnivariateArgs& a, const float* logphi, hipStream_t st) {
+  const long long tokens = (long long)a.B * a.n;
+  hipLaunchKernelGGL(k_univariate_table, dim3((unsigned)((tokens + 3) / 4)), dim3(256), 0, st, logphi, a.logm, a.out,
+                     tokens, a.r, a.v);
+  return hipGetLastError();
+}
+
 hipError_t launch_draw_table(const DrawArgs& a, hipStream_t st) {
   const long long rows = (long long)a.B * a.S * a.n;
   hipLaunchKernelGGL(k_draw_table, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, a);

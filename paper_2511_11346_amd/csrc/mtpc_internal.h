@@ -45,6 +45,10 @@ struct UnivariateArgs {
   float* out;           // [B][n][v]
 };
 
+// The same from the table of normalised input units log phi[B][n][r][v] (a.h, a.W unused):
+// M[b][i][a] = log sum_j exp(logm[b][i][j] + logphi[b][i][j][a]).
+hipError_t launch_univariate_table(const UnivariateArgs& a, const float* logphi, hipStream_t st);
+
 // Contextual sum layers: P[b][l][k][:] = softmax(R[l][k] h[b] + bias[l][k][:]) as linear
 // probabilities, natural [b][l][k][j] and/or transposed [b][l][j][k] layout.
 struct CtxLayerArgs {

@@ -650,52 +650,55 @@ template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_univariate(const UnivariateArgs a) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  constexpr bool M16 = use_m16<WV, WB, SB, NS, BF16>();
+  using FR = Frag<M16>;
+  constexpr int NPB = PB * FR::SUB, NVB = VB * FR::SUB;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wv = wave % WV, wb = wave / WV;
-  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int lcol = FR::lcol(lane);
   const int nbt = (a.B + TL::TP - 1) / TL::TP;
   const int wi = blockIdx.x / nbt, bt = blockIdx.x - wi * nbt;
   const int b0 = bt * TL::TP;
-  const int rbase = wv * VB * 32 + 4 * lhalf;
+  const int rbase = wv * VB * 32 + 4 * FR::lgrp(lane);
 
-  f32x16_t run[PB][VB];
+  typename FR::blk_t run[NPB][NVB];
 #pragma unroll
-  for (int pb = 0; pb < PB; ++pb)
+  for (int pb = 0; pb < NPB; ++pb)
 #pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
+    for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) run[pb][vb][i] = 0.f;
+      for (int i = 0; i < FR::NI; ++i) run[pb][vb][i] = 0.f;
 
   for (int j = 0; j < a.r; ++j) {
-    f32x16_t acc[PB][VB];
-    tile_gemm<WV, WB, VB, PB, SB, NS, BF16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, wi * a.r + j, b0, smem, acc);
-    float mx[PB], lse[PB];
-    tile_lse<WV, WB, VB, PB, SB, NS>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
+    typename FR::blk_t acc[NPB][NVB];
+    tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, wi * a.r + j, b0, smem, acc);
+    float mx[NPB], lse[NPB];
+    tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 #pragma unroll
-    for (int pb = 0; pb < PB; ++pb) {
-      const int b = min(b0 + wb * PB * 32 + pb * 32 + l31, a.B - 1);
+    for (int pb = 0; pb < NPB; ++pb) {
+      const int b = min(b0 + wb * PB * 32 + pb * FR::BR + lcol, a.B - 1);
       const float lm = a.logm ? a.logm[((long long)b * a.n + wi) * a.r + j] : 0.f;
       // m_j phi_j = 2^((l - lse_j + log m_j) log2 e): one fused multiply-add and one v_exp per logit
       constexpr float LOG2E = 1.4426950408889634f;
       const float shift = (lm - lse[pb]) * LOG2E;
 #pragma unroll
-      for (int vb = 0; vb < VB; ++vb)
+      for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) run[pb][vb][i] += __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, shift));
+        for (int i = 0; i < FR::NI; ++i) run[pb][vb][i] += __builtin_amdgcn_exp2f(fmaf(acc[pb][vb][i], LOG2E, shift));
     }
     __syncthreads();   // `red` is rewritten by the next slab
   }
 #pragma unroll
-  for (int pb = 0; pb < PB; ++pb) {
-    const int b = b0 + wb * PB * 32 + pb * 32 + l31;
+  for (int pb = 0; pb < NPB; ++pb) {
+    const int b = b0 + wb * PB * 32 + pb * FR::BR + lcol;
     if (b >= a.B) continue;
     float* dst = a.out + ((long long)b * a.n + wi) * a.v;
 #pragma unroll
-    for (int vb = 0; vb < VB; ++vb)
+    for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = rbase + vb * 32 + 8 * (i >> 2) + (i & 3);
+      for (int i = 0; i < FR::NI; ++i) {
+        const int row = rbase + vb * FR::BR + FR::roff(i);
         if (row < a.v) dst[row] = __logf(run[pb][vb][i]);
       }
   }

@@ -78,6 +78,8 @@ def test_config3_hmm_full_size():
     rows = np.array([0, 300, inp.B - 1])
     want = oc.univariate_marginals("hmm", inp.h[rows], inp.W, inp.Wsum, inp.layers)
     tol_check(M[rows].cpu().numpy(), want, "bf16", "univariate")
+    M2 = head.univariate_marginals(keep_table=False)          # no 2.7 GB table: the slabs mixed in registers
+    tol_check(M2[rows].cpu().numpy(), want, "bf16", "univariate, mixed in registers")
 
 
 def test_config3_contextual_hmm_full_size():

@@ -94,6 +94,7 @@ def test_loglik_and_marginals(family, dtype, B, d, n, r, v):
         lay = inp.layers if (inp.layers is not None and inp.layers.size) else None
         M = oc.univariate_marginals(family, inp.h, inp.W, inp.Wsum, lay)
         tol_check(head.univariate_marginals().cpu().numpy(), M, dtype, "univariate")
+        tol_check(head.univariate_marginals(keep_table=False).cpu().numpy(), M, dtype, "univariate, mixed in registers")
 
 
 @pytest.mark.parametrize("family,dtype,B,d,n,r,v,S", [
@@ -240,6 +241,8 @@ def test_sum_layers_computed_from_the_hidden_state(family, dtype, B, d, n, r):
     if B <= 70:
         M = oc.univariate_marginals(family, inp.h, inp.W, inp.Wsum, lay)
         tol_check(head.univariate_marginals().cpu().numpy(), M, dtype, "univariate, layers from h")
+        tol_check(head.univariate_marginals(keep_table=False).cpu().numpy(), M, dtype,
+                  "univariate, layers from h, mixed in registers")
     # shared R and no bias: one tensor for all layers
     head2 = Head(family, base.h, base.W, base.Wsum, None, R=to_dev(Rv[:1], None if Rbits is None else Rbits[:1]))
     lay2 = oc.contextual_layer_logits(inp.h, np.repeat(Rv[:1], L, axis=0))
