@@ -710,12 +710,19 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   m.ksplit = q.ksplit; m.kchunk = q.kchunk; m.partial = q.ksplit > 1 ? (float*)(ws + q.partial) : nullptr;
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
   m.ksplit = 1; m.partial = nullptr;
-  m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)q.Mtot;            // dW[m][k] = sum_b dLT[m][b] hT[k][b]
+  // dW[m][k] = sum_b dLT[m][b] hT[k][b].  With layers computed from h the r rows of dWsum and,
+  // after a gap, those of dR ride along; otherwise the r rows would add one nearly empty row of
+  // tiles (n r v is a multiple of the tile height for the 320-token vocabulary: one more round over
+  // the CUs), so they get a small kernel of their own.
+  const bool own_dwsum = family != MTPC_FF && !ctx;
+  m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)(own_dwsum ? q.M : q.Mtot);
   m.Bm = ws + q.hT; m.ldb = q.ldb; m.N = hd->d; m.K = (int)q.ldb;
   m.C = dW; m.ldc = hd->d;
-  m.split = (int)q.M; m.n2 = family == MTPC_FF ? 0 : hd->r; m.C2 = dWsum;   // then the r rows of dWsum
-  m.split3 = ctx ? (int)q.Mlay : 0x7fffffff; m.C3 = dR;                     // and, after the gap, dR
+  m.split = (int)q.M; m.n2 = (family == MTPC_FF || own_dwsum) ? 0 : hd->r; m.C2 = dWsum;
+  m.split3 = ctx ? (int)q.Mlay : 0x7fffffff; m.C3 = dR;
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
+  if (own_dwsum)
+    HIP_TRY(launch_dwsum(ws + q.dLT + (size_t)q.M * q.ldb * esz, ws + q.hT, q.ldb, hd->r, hd->d, hd->dtype, dWsum, st));
   return MTPC_OK;
 }
 

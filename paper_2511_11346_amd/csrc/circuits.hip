@@ -1201,6 +1201,55 @@ hipError_t launch_rows_logits(const RowLogitArgs& a, int dtype, hipStream_t st) 
 }
 
 // ---------------------------------------------------------------------------
+// Gradient of the sum-unit matrix (Sec. 4.1 loss): dWsum[j][c] = sum_b g[j][b] hT[c][b], with the
+// gradient of the sum-unit logits g [r][ldb] and the transposed hidden states hT [d][ldb] both
+// contiguous over the (zero-padded) positions.  r*d dot products of length B: a workgroup takes
+// 8 columns c, each of its waves 4 rows j at a time; sums in a fixed order.
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_dwsum(const void* gT, const void* hT, long long ldb, int r, int d,
+                                               float* out) {
+  constexpr int ESZ = BF16 ? 2 : 4;
+  constexpr int CT = 8;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c0 = blockIdx.x * CT;
+  const long long pitch = ldb * ESZ;
+  const int nch = (int)(pitch / 16);
+  for (int j0 = wave * 4; j0 < r; j0 += 16) {
+    float acc[4][CT];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int q = 0; q < CT; ++q) acc[u][q] = 0.f;
+    for (int t = lane; t < nch; t += 64) {
+      i32x4_t hv[CT];
+#pragma unroll
+      for (int q = 0; q < CT; ++q) hv[q] = *(const i32x4_t*)((const char*)hT + (long long)min(c0 + q, d - 1) * pitch + (long long)t * 16);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const i32x4_t gv = *(const i32x4_t*)((const char*)gT + (long long)min(j0 + u, r - 1) * pitch + (long long)t * 16);
+#pragma unroll
+        for (int q = 0; q < CT; ++q) acc[u][q] += dot_chunk<BF16>(gv, hv[q]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int q = 0; q < CT; ++q) {
+        const float val = wave_sum(acc[u][q]);
+        if (lane == 0 && j0 + u < r && c0 + q < d) out[(long long)(j0 + u) * d + c0 + q] = val;
+      }
+  }
+}
+
+hipError_t launch_dwsum(const void* gT, const void* hT, long long ldb, int r, int d, int dtype, float* out,
+                        hipStream_t st) {
+  const dim3 grid((unsigned)((d + 7) / 8));
+  if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_dwsum<true>, grid, dim3(256), 0, st, gT, hT, ldb, r, d, out);
+  else hipLaunchKernelGGL(k_dwsum<false>, grid, dim3(256), 0, st, gT, hT, ldb, r, d, out);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Univariate marginals (App. B.1) from the table of normalised input units:
 //   M[b][i][a] = log sum_j exp(logm[b][i][j] + log phi[b][i][j][a]).
 // One wave per (b, i); lane l holds tokens l, l + 64, ...; the r rows of the table are read

@@ -45,6 +45,9 @@ struct UnivariateArgs {
   float* out;           // [B][n][v]
 };
 
+// dWsum[j][c] = sum_b gT[j][b] hT[c][b]; gT [r][ldb], hT [d][ldb] in the dtype of h, ldb a multiple of 32
+hipError_t launch_dwsum(const void* gT, const void* hT, long long ldb, int r, int d, int dtype, float* out,
+                        hipStream_t st);
 // The same from the table of normalised input units log phi[B][n][r][v] (a.h, a.W unused):
 // M[b][i][a] = log sum_j exp(logm[b][i][j] + logphi[b][i][j][a]).
 hipError_t launch_univariate_table(const UnivariateArgs& a, const float* logphi, hipStream_t st);
