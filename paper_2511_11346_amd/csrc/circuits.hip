@@ -1204,12 +1204,12 @@ hipError_t launch_rows_logits(const RowLogitArgs& a, int dtype, hipStream_t st) 
 // Gradient of the sum-unit matrix (Sec. 4.1 loss): dWsum[j][c] = sum_b g[j][b] hT[c][b], with the
 // gradient of the sum-unit logits g [r][ldb] and the transposed hidden states hT [d][ldb] both
 // contiguous over the (zero-padded) positions.  r*d dot products of length B: a workgroup takes
-// 8 columns c, each of its waves 4 rows j at a time; sums in a fixed order.
+// 4 columns c, each of its waves 4 rows j at a time; sums in a fixed order.
 template <bool BF16>
 __global__ __launch_bounds__(256) void k_dwsum(const void* gT, const void* hT, long long ldb, int r, int d,
                                                float* out) {
   constexpr int ESZ = BF16 ? 2 : 4;
-  constexpr int CT = 8;
+  constexpr int CT = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c0 = blockIdx.x * CT;
   const long long pitch = ldb * ESZ;
@@ -1220,6 +1220,7 @@ __global__ __launch_bounds__(256) void k_dwsum(const void* gT, const void* hT, l
     for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int q = 0; q < CT; ++q) acc[u][q] = 0.f;
+#pragma unroll 2
     for (int t = lane; t < nch; t += 64) {
       i32x4_t hv[CT];
 #pragma unroll
@@ -1243,7 +1244,7 @@ __global__ __launch_bounds__(256) void k_dwsum(const void* gT, const void* hT, l
 
 hipError_t launch_dwsum(const void* gT, const void* hT, long long ldb, int r, int d, int dtype, float* out,
                         hipStream_t st) {
-  const dim3 grid((unsigned)((d + 7) / 8));
+  const dim3 grid((unsigned)((d + 3) / 4));
   if (dtype == MTPC_BF16) hipLaunchKernelGGL(k_dwsum<true>, grid, dim3(256), 0, st, gT, hT, ldb, r, d, out);
   else hipLaunchKernelGGL(k_dwsum<false>, grid, dim3(256), 0, st, gT, hT, ldb, r, d, out);
   return hipGetLastError();
