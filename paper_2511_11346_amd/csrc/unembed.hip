@@ -753,13 +753,6 @@ static hipError_t launch_cfg(const UnembedArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-// Ring geometry of the decode-shaped tiles (overridable for experiments)
-#ifndef MTPC_DEC_SB
-#define MTPC_DEC_SB 64
-#endif
-#ifndef MTPC_DEC_NS
-#define MTPC_DEC_NS 4
-#endif
 // Stage geometry of the 320 x 256 training tile (overridable for experiments)
 #ifndef MTPC_TRAIN_SB
 #define MTPC_TRAIN_SB 64
@@ -767,6 +760,15 @@ static hipError_t launch_cfg(const UnembedArgs& a, hipStream_t st) {
 #ifndef MTPC_TRAIN_NS
 #define MTPC_TRAIN_NS 4
 #endif
+
+// Decode-shaped tiles (B <= 64: WV waves over the vocabulary, W streamed once) are bound by HBM:
+// 128-byte stages in a 3-stage ring when the rows allow it (whole cache lines per row and stage,
+// 90 KB in flight per CU; 1.5-2.5 % faster than 64-byte stages in a 4-stage ring).
+template <int WV, int PB, bool BF16, bool SAMPLE>
+static hipError_t launch_dec(const UnembedArgs& a, int row_bytes, hipStream_t st) {
+  if (row_bytes % 128 == 0) return launch_cfg<WV, 1, 2, PB, 128, 3, BF16, SAMPLE>(a, st);
+  return launch_cfg<WV, 1, 2, PB, 64, 4, BF16, SAMPLE>(a, st);
+}
 
 template <bool BF16, bool SAMPLE>
 static hipError_t launch_dt(const UnembedArgs& a, hipStream_t st) {
@@ -784,13 +786,13 @@ static hipError_t launch_dt(const UnembedArgs& a, hipStream_t st) {
     return launch_cfg<2, 4, 2, 2, 64, 4, BF16, SAMPLE>(a, st);
   }
   if (a.B > 32) {
-    if (a.v > 256) return launch_cfg<5, 1, 2, 2, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
-    if (a.v > 128) return launch_cfg<4, 1, 2, 2, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
-    return launch_cfg<2, 1, 2, 2, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
+    if (a.v > 256) return launch_dec<5, 2, BF16, SAMPLE>(a, row_bytes, st);
+    if (a.v > 128) return launch_dec<4, 2, BF16, SAMPLE>(a, row_bytes, st);
+    return launch_dec<2, 2, BF16, SAMPLE>(a, row_bytes, st);
   }
-  if (a.v > 256) return launch_cfg<5, 1, 2, 1, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
-  if (a.v > 128) return launch_cfg<4, 1, 2, 1, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
-  return launch_cfg<2, 1, 2, 1, MTPC_DEC_SB, MTPC_DEC_NS, BF16, SAMPLE>(a, st);
+  if (a.v > 256) return launch_dec<5, 1, BF16, SAMPLE>(a, row_bytes, st);
+  if (a.v > 128) return launch_dec<4, 1, BF16, SAMPLE>(a, row_bytes, st);
+  return launch_dec<2, 1, BF16, SAMPLE>(a, row_bytes, st);
 }
 
 hipError_t launch_unembed(const UnembedArgs& a, int dtype, hipStream_t st) {
