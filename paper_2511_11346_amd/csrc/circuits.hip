@@ -357,12 +357,33 @@ __global__ __launch_bounds__(256) void k_circuit(const CircuitArgs a, int G, int
 #pragma unroll
     for (int q = 0; q < RB; ++q) emit(q, i, pair_lse(x.v[q], g, r, G));
   };
+  // The chains (CP, HMM) take one step per token.  Their messages are kept relative to their
+  // largest unit and the magnitude taken out is summed in double, so that the fp32 result carries
+  // the rounding of one step, not of n (an ulp is 3e-5 at the |log q| = 350 of a 64-token window).
+  double scale[RB];
+#pragma unroll
+  for (int q = 0; q < RB; ++q) scale[q] = 0.0;
+  auto renorm = [&](Rows<RB>& x) {
+#pragma unroll
+    for (int q = 0; q < RB; ++q) {
+      const float m = group_max(fmaxf(x.v[q].a, x.v[q].b), G);
+      if (m == ninf) continue;                           // probability zero so far: nothing to take out
+      x.v[q].a -= m;
+      x.v[q].b -= m;
+      scale[q] += (double)m;
+    }
+  };
+  auto emit_scaled = [&](int i, const Rows<RB>& x) {
+#pragma unroll
+    for (int q = 0; q < RB; ++q) emit(q, i, (float)(scale[q] + (double)pair_lse(x.v[q], g, r, G)));
+  };
 
   if (a.family == MTPC_CP) {
     Rows<RB> acc = lw;
     for (int i = 0; i < n; ++i) {
       acc = add(acc, leaf(i));
-      if (a.prefix || i == n - 1) emit_lse(i, acc);
+      renorm(acc);
+      if (a.prefix || i == n - 1) emit_scaled(i, acc);
     }
     return;
   }
@@ -373,7 +394,8 @@ __global__ __launch_bounds__(256) void k_circuit(const CircuitArgs a, int G, int
     Rows<RB> alpha = add(lw, leaf(0));
     for (int i = 0; i < n; ++i) {
       if (i > 0) alpha = add(sum_layer<RB>(alpha, lay + (long long)(i - 1) * lstep, sh, g, r, G), leaf(i));
-      if (a.prefix || i == n - 1) emit_lse(i, alpha);
+      renorm(alpha);
+      if (a.prefix || i == n - 1) emit_scaled(i, alpha);
     }
     return;
   }
@@ -780,13 +802,17 @@ __global__ __launch_bounds__(256) void k_circuit_row(const CircuitArgs a, int G)
 
   if (a.family == MTPC_HMM) {
     if (gi != 0) return;                                 // (no workgroup barrier below)
+    // the message stays relative to its largest unit, the magnitude taken out is summed in double
     float alpha[1] = {lw + leaf(0)};
+    double scale = 0.0;
     for (int i = 0; i < n; ++i) {
       if (i > 0) {
         sum_layer_lds<1>(alpha, s_lay + (size_t)(i - 1) * lstep, s_sh, g, r, G);
         alpha[0] += leaf(i);
       }
-      if (a.prefix || i == n - 1) emit(i, lse(alpha[0]));
+      const float m = group_max(alpha[0], G);
+      if (m != ninf) { alpha[0] -= m; scale += (double)m; }
+      if (a.prefix || i == n - 1) emit(i, (float)(scale + (double)lse(alpha[0])));
     }
     return;
   }

@@ -8,7 +8,6 @@ from oracle import mtpc_oracle as oc
 from oracle import speculative as sp
 
 FP32_ABS = 1e-4      # log-likelihood tolerance for fp32 inputs
-FP32_ULPS = 13       # ... or this many fp32 units in the last place of the reference, if that is more
 BF16_REL = 2e-3      # relative tolerance for bf16 inputs with fp32 accumulation
 BOUNDARY = 1e-6      # uniforms closer than this to a CDF step are not compared
 
@@ -42,13 +41,9 @@ def tol_check(got, want, dtype, what=""):
     fin = ~ok_special
     err = np.abs(got[fin] - want[fin])
     if dtype == "f32":
-        # 1e-4 is 13 units in the last place of an fp32 number in [64, 128), the size of the
-        # log-probabilities of the paper's windows (up to 16 tokens).  A window of 64 tokens reaches
-        # |log q| = 350, where one unit is 3e-5 and a chain of 64 dependent fp32 steps drifts by
-        # sqrt(64) / 2 = 4 of them (1.7e-4 and 1.8e-4 seen): beyond 128 the bar is the same 13 units.
-        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want[fin]), 1.0))) - 23)
-        lim = np.maximum(FP32_ABS, FP32_ULPS * ulp)
-        assert err.size == 0 or np.all(err <= lim), f"{what}: max abs err {err.max():.3e}"
+        # also for windows of 64 tokens (|log q| up to 350, where an fp32 unit is 3e-5): the chains
+        # keep their messages relative to the largest unit and sum the magnitude in double
+        assert err.size == 0 or err.max() <= FP32_ABS, f"{what}: max abs err {err.max():.3e}"
     else:
         lim = BF16_REL * np.maximum(np.abs(want[fin]), 1e-2)
         assert err.size == 0 or np.all(err <= lim), f"{what}: max err {err.max():.3e}"
