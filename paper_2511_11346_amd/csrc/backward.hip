@@ -13,16 +13,8 @@ __device__ __forceinline__ unsigned short to_bf16_rne(float x) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (unsigned short)(u >> 16);
 }
-__device__ __forceinline__ float wsum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-  return x;
-}
-__device__ __forceinline__ float wmax(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-  return x;
-}
+__device__ __forceinline__ float wsum(float x) { return group_sum(x, 64); }
+__device__ __forceinline__ float wmax(float x) { return group_max(x, 64); }
 
 // 64 x 64 element tiles through LDS; T is the 2- or 4-byte element type.
 template <typename T>

@@ -8,24 +8,7 @@ namespace mtpc {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4_t;
 
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-  return x;
-}
-// reductions inside aligned groups of G lanes (G a power of two <= 64)
-__device__ __forceinline__ float group_max(float x, int G) {
-  for (int o = G >> 1; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-  return x;
-}
-__device__ __forceinline__ float group_sum(float x, int G) {
-  for (int o = G >> 1; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-  return x;
-}
-__device__ __forceinline__ int group_min(int x, int G) {
-  for (int o = G >> 1; o >= 1; o >>= 1) x = min(x, __shfl_xor(x, o));
-  return x;
-}
+__device__ __forceinline__ float wave_sum(float x) { return group_sum(x, 64); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 // First window position of an evidence row e[n][r] whose unit 0 is NaN (n if
@@ -373,17 +356,23 @@ __global__ __launch_bounds__(256) void k_circuit(const CircuitArgs a, int G, int
       scale[q] += (double)m;
     }
   };
-  auto emit_scaled = [&](int i, const Rows<RB>& x) {
+  auto emit_scaled = [&](int i, const Rows<RB>& x) {     // x fresh from renorm: its largest unit is 0
 #pragma unroll
-    for (int q = 0; q < RB; ++q) emit(q, i, (float)(scale[q] + (double)pair_lse(x.v[q], g, r, G)));
+    for (int q = 0; q < RB; ++q) {
+      float s = 0.f;
+      if (g < r) s += __expf(x.v[q].a);
+      if (g + 64 < r) s += __expf(x.v[q].b);
+      s = group_sum(s, G);                               // all units -inf: log 0 = -inf
+      emit(q, i, (float)(scale[q] + (double)__logf(s)));
+    }
   };
 
   if (a.family == MTPC_CP) {
     Rows<RB> acc = lw;
     for (int i = 0; i < n; ++i) {
       acc = add(acc, leaf(i));
-      renorm(acc);
-      if (a.prefix || i == n - 1) emit_scaled(i, acc);
+      renorm(acc);                                      // every step, so that the log-likelihood call
+      if (a.prefix || i == n - 1) emit_scaled(i, acc);  // returns the bits of the last prefix marginal
     }
     return;
   }
@@ -812,7 +801,8 @@ __global__ __launch_bounds__(256) void k_circuit_row(const CircuitArgs a, int G)
       }
       const float m = group_max(alpha[0], G);
       if (m != ninf) { alpha[0] -= m; scale += (double)m; }
-      if (a.prefix || i == n - 1) emit(i, (float)(scale + (double)lse(alpha[0])));
+      if (a.prefix || i == n - 1)                        // largest unit 0 (or all -inf: log 0)
+        emit(i, (float)(scale + (double)__logf(group_sum(g < r ? __expf(alpha[0]) : 0.f, G))));
     }
     return;
   }

@@ -325,6 +325,43 @@ __device__ __forceinline__ float philox_uniform(uint32_t seed_lo, uint32_t seed_
 
 __device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
 
+// Reductions inside aligned groups of G lanes (G a power of two <= 64); every lane of the group
+// gets the result.  The steps inside a row of 16 lanes are data-parallel-primitive moves on the
+// operand path (swap neighbours, swap pairs, mirror 8, mirror 16: once the smaller blocks agree, a
+// mirror pairs each block with the other one), only the steps across rows go through the LDS
+// crossbar - a chain of circuit steps is a chain of these reductions, and a crossbar step costs
+// about ten times a move.  All source lanes lie inside the group, so groups that have left do not
+// matter.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int x) {
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, true);
+}
+template <class Op>
+__device__ __forceinline__ float group_reduce(float x, int G, Op op) {
+  if (G >= 2) x = op(x, __int_as_float(dpp_move<0xB1>(__float_as_int(x))));     // quad_perm [1,0,3,2]
+  if (G >= 4) x = op(x, __int_as_float(dpp_move<0x4E>(__float_as_int(x))));     // quad_perm [2,3,0,1]
+  if (G >= 8) x = op(x, __int_as_float(dpp_move<0x141>(__float_as_int(x))));    // row_half_mirror
+  if (G >= 16) x = op(x, __int_as_float(dpp_move<0x140>(__float_as_int(x))));   // row_mirror
+  if (G >= 32) x = op(x, __shfl_xor(x, 16));
+  if (G >= 64) x = op(x, __shfl_xor(x, 32));
+  return x;
+}
+__device__ __forceinline__ float group_max(float x, int G) {
+  return group_reduce(x, G, [](float a, float b) { return fmaxf(a, b); });
+}
+__device__ __forceinline__ float group_sum(float x, int G) {
+  return group_reduce(x, G, [](float a, float b) { return a + b; });
+}
+__device__ __forceinline__ int group_min(int x, int G) {
+  if (G >= 2) x = min(x, dpp_move<0xB1>(x));
+  if (G >= 4) x = min(x, dpp_move<0x4E>(x));
+  if (G >= 8) x = min(x, dpp_move<0x141>(x));
+  if (G >= 16) x = min(x, dpp_move<0x140>(x));
+  if (G >= 32) x = min(x, __shfl_xor(x, 16));
+  if (G >= 64) x = min(x, __shfl_xor(x, 32));
+  return x;
+}
+
 // ---- evaluation order of the binary tree (Eq. BTree) ---------------------------
 // The order in which the tree's nodes are evaluated does not depend on the data: a
 // kernel writes it once as a short program, one step per sum-layer application.

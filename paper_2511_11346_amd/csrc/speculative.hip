@@ -18,16 +18,8 @@
 namespace mtpc {
 namespace {
 
-__device__ __forceinline__ float wmax(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-  return x;
-}
-__device__ __forceinline__ float wsum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-  return x;
-}
+__device__ __forceinline__ float wmax(float x) { return group_max(x, 64); }
+__device__ __forceinline__ float wsum(float x) { return group_sum(x, 64); }
 // block-wide reductions of 256 threads; `red` holds 4 floats
 __device__ __forceinline__ float block_max(float x, float* red) {
   x = wmax(x);
