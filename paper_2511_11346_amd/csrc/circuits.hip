@@ -901,12 +901,27 @@ hipError_t launch_circuit(const CircuitArgs& a, hipStream_t st) {
 // last unit with positive weight.  The result is wave-uniform, so the next sum
 // unit's row is again one coalesced load.
 // ---------------------------------------------------------------------------
+// Inclusive scan over the 64 lanes in double.  Inside a row of 16 lanes the four steps are DPP
+// row shifts (lanes without a source read zero), then the row totals travel over the LDS crossbar:
+// the last lane of the previous row, and after that the last lane of the row before it, which by
+// then holds the total of two rows.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_f64(double x) {
+  const long long v = __double_as_longlong(x);
+  const unsigned lo = (unsigned)dpp_move<CTRL>((int)(unsigned)(v & 0xffffffffll));
+  const unsigned hi = (unsigned)dpp_move<CTRL>((int)(unsigned)((unsigned long long)v >> 32));
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
 __device__ __forceinline__ double wave_scan_incl(double x, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const double t = __shfl_up(x, o);
-    if (lane >= o) x += t;
-  }
+  x += dpp_move_f64<0x111>(x);      // row_shr:1
+  x += dpp_move_f64<0x112>(x);      // row_shr:2
+  x += dpp_move_f64<0x114>(x);      // row_shr:4
+  x += dpp_move_f64<0x118>(x);      // row_shr:8
+  const int row = lane >> 4;
+  const double t1 = __shfl(x, max(16 * row - 1, 0));
+  if (row >= 1) x += t1;
+  const double t2 = __shfl(x, max(16 * row - 17, 0));
+  if (row >= 2) x += t2;
   return x;
 }
 __device__ __forceinline__ int wave_draw(float p0, float p1, int r, float u, int lane) {
