@@ -471,14 +471,7 @@ template <int RB>
 __device__ __forceinline__ void sum_layer_lds(float (&c)[RB], const float* Wl, float* sh, int g, int r, int G) {
   float m[RB];
 #pragma unroll
-  for (int q = 0; q < RB; ++q) m[q] = c[q];
-  for (int o = G >> 1; o >= 1; o >>= 1) {        // the RB reductions advance together
-    float t[RB];
-#pragma unroll
-    for (int q = 0; q < RB; ++q) t[q] = __shfl_xor(m[q], o);
-#pragma unroll
-    for (int q = 0; q < RB; ++q) m[q] = fmaxf(m[q], t[q]);
-  }
+  for (int q = 0; q < RB; ++q) m[q] = group_max(c[q], G);
   const bool live = g < r;
   const int gc = live ? g : 0;
   float ex[RB];
@@ -623,23 +616,9 @@ __global__ __launch_bounds__(256) void k_btree_static(const CircuitArgs a, int G
       const int i = -2 - st.out;
       float x[RB], m[RB], s[RB];
 #pragma unroll
-      for (int q = 0; q < RB; ++q) m[q] = x[q] = c[q] + lw[q];
-      for (int o = G >> 1; o >= 1; o >>= 1) {
-        float tt[RB];
+      for (int q = 0; q < RB; ++q) { x[q] = c[q] + lw[q]; m[q] = group_max(x[q], G); }
 #pragma unroll
-        for (int q = 0; q < RB; ++q) tt[q] = __shfl_xor(m[q], o);
-#pragma unroll
-        for (int q = 0; q < RB; ++q) m[q] = fmaxf(m[q], tt[q]);
-      }
-#pragma unroll
-      for (int q = 0; q < RB; ++q) s[q] = (live && m[q] != ninf) ? __expf(x[q] - m[q]) : 0.f;
-      for (int o = G >> 1; o >= 1; o >>= 1) {
-        float tt[RB];
-#pragma unroll
-        for (int q = 0; q < RB; ++q) tt[q] = __shfl_xor(s[q], o);
-#pragma unroll
-        for (int q = 0; q < RB; ++q) s[q] += tt[q];
-      }
+      for (int q = 0; q < RB; ++q) s[q] = group_sum((live && m[q] != ninf) ? __expf(x[q] - m[q]) : 0.f, G);
 #pragma unroll
       for (int q = 0; q < RB; ++q) {
         float v = (m[q] == ninf) ? ninf : m[q] + __logf(s[q]);
