@@ -13,7 +13,9 @@
  *
  * Conventions
  *  - Every data pointer is a DEVICE pointer owned by the caller; the library
- *    allocates nothing, keeps no state between calls and never synchronises.
+ *    allocates nothing, never synchronises and keeps nothing between calls that a
+ *    result depends on (it remembers, per kernel and device, that the kernel's LDS
+ *    limit has been raised; and the optional profiling events of a thread).
  *    Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *    default stream); buffers must stay alive until that work has completed.
  *  - Row-major, innermost axis contiguous.  h, W, Wsum share `dtype`
@@ -23,8 +25,11 @@
  *    (d elements) at most 8 MiB.
  *  - Supported sizes: 1 <= B; d a multiple of 32; 1 <= n <= 64; 1 <= r <= 128;
  *    1 <= v <= 320.  Anything else returns MTPC_ERR_UNSUPPORTED.
- *  - On any error nothing is launched and outputs are untouched.  Outputs are
- *    fully overwritten on success.
+ *  - Arguments are checked before the first launch: on MTPC_ERR_NULL, _SHAPE,
+ *    _UNSUPPORTED and _WORKSPACE nothing has been enqueued and outputs are untouched.
+ *    MTPC_ERR_HIP means the runtime refused a launch in the middle of a call: what
+ *    was enqueued before it still runs, the outputs and the workspace are then
+ *    unspecified.  Outputs are fully overwritten on success.
  *  - targets: int32, -1 marks a variable that is summed out (App. B.1: its input
  *    units integrate to 1); any other id outside [0, v) makes that row's outputs NaN.
  */
@@ -231,9 +236,9 @@ mtpc_status mtpc_btree_greedy_draft(const mtpc_head* head, const mtpc_sumlayers*
  *   drawn from max(0, p[s] - q(. | x_{<=s})) / Z, where q(. | x_{<=s}) is the
  *   circuit's exact conditional over the whole vocabulary (if Z == 0, i.e.
  *   p == q, from p[s]); if all n are accepted the token is drawn from p[n].
- *   Uniforms: Philox as in mtpc_*_sample with s = 0 and slots 0..n-1 = alpha,
- *   slot n = the final draw; pass an `offset` (or seed) different from the one
- *   that drew the draft.
+ *   Uniforms: Philox as in mtpc_*_sample with slots 0..n-1 = alpha, slot n = the
+ *   final draw, and the draft index s fixed at 2^32 - 1, which no drafting call
+ *   uses: the same (seed, offset) as the call that drew the draft is safe.
  * MTPC_VERIFY_GREEDY: token s+1 is accepted iff it is argmax p[s] (ties: the
  *   smallest id); the emitted token is argmax p[accepted]; seed, offset, logphi
  *   and prefix_logq are unused and may be 0 / NULL.

@@ -143,8 +143,8 @@ def make_inputs(family: str, *, B: int, d: int, n: int, r: int, v: int,
     elif family == "btree":
         L = (n - 2) if layer_count is None else layer_count
         layers, _ = _gauss(seed, 4, (L, r, r), 1.0, False)
-    if targets == "uniform":
-        tg = rng.integers(0, min(v, 256), size=(B, n), dtype=np.int32)
+    if targets == "uniform":                  # every id of the vocabulary, also those beyond the bytes
+        tg = rng.integers(0, v, size=(B, n), dtype=np.int32)
     elif targets == "biased":
         tg = biased_byte_targets(rng, B, n)
     else:
@@ -165,17 +165,17 @@ def config1(seed: int = 1001) -> HeadInputs:
                        h_scale=1.0, targets="uniform")
 
 
-def config2(r: int, B: int = 8192, seed: int = 1002) -> HeadInputs:
+def config2(r: int, B: int = 8192, seed: int = 1002, targets: str = "biased") -> HeadInputs:
     """FF (r=1) or CP (r=16), bf16, d=4096, n=8, v=320, biased byte targets."""
     fam = "ff" if r == 1 else "cp"
     return make_inputs(fam, B=B, d=4096, n=8, r=r, v=320, dtype="bf16", seed=seed,
-                       targets="biased")
+                       targets=targets)
 
 
-def config3(B: int = 8192, seed: int = 1003) -> HeadInputs:
+def config3(B: int = 8192, seed: int = 1003, targets: str = "biased") -> HeadInputs:
     """HMM, bf16, d=4096, n=8, r=32, v=320, one shared static 32x32 transition."""
     return make_inputs("hmm", B=B, d=4096, n=8, r=32, v=320, dtype="bf16", seed=seed,
-                       targets="biased", layer_count=1)
+                       targets=targets, layer_count=1)
 
 
 def config3_contextual(B: int = 8192, seed: int = 1013) -> HeadInputs:
@@ -192,16 +192,16 @@ def config_llama_byte(family: str = "cp", n: int = 8, B: int = 2048, seed: int =
                        h_scale=1.0 / np.sqrt(3072), targets="biased")
 
 
-def config4(B: int = 4096, seed: int = 1004) -> HeadInputs:
+def config4(B: int = 4096, seed: int = 1004, targets: str = "biased") -> HeadInputs:
     """Binary tree, bf16, d=3072, n=16, r=64, v=320, 14 static 64x64 sum layers."""
     return make_inputs("btree", B=B, d=3072, n=16, r=64, v=320, dtype="bf16", seed=seed,
-                       targets="biased")
+                       targets=targets)
 
 
-def config5(B: int = 64, seed: int = 1005) -> HeadInputs:
+def config5(B: int = 64, seed: int = 1005, targets: str = "biased") -> HeadInputs:
     """Decode-shaped CP, bf16, r=32, d=4096, n=16, v=320, B in {1, 8, 64}."""
     return make_inputs("cp", B=B, d=4096, n=16, r=32, v=320, dtype="bf16", seed=seed,
-                       targets="biased")
+                       targets=targets)
 
 
 def verifier_noise(B: int, n: int, v: int, seed: int, peak: float = 3.0) -> np.ndarray:

@@ -6,7 +6,8 @@ own implementation of the same published algorithm.
 Slot map: for position b, draft s and slot t, the 128-bit counter is
 (t // 4, b, s, offset) and the 64-bit key is (seed low word, seed high word);
 slot t takes output word t % 4 and maps it to u = (word >> 8) * 2^-24, which is
-exact in fp32 and lies in [0, 1).
+exact in fp32 and lies in [0, 1).  Drafting uses s = 0 .. S-1; the verification step
+(its acceptance tests in slots 0..n-1, its final draw in slot n) uses s = 2^32 - 1.
 """
 from __future__ import annotations
 
@@ -38,10 +39,21 @@ def philox4x32_10(counter, key):
     return c
 
 
-def uniforms(B: int, S: int, slots: int, seed: int, offset: int = 0) -> np.ndarray:
-    """u[b,s,t] for t < slots, float64 holding values exact in fp32."""
+VERIFY_DRAFT_INDEX = 0xFFFFFFFF
+
+
+def verify_uniforms(B: int, slots: int, seed: int, offset: int = 0) -> np.ndarray:
+    """u[b,t] of the verification step: the same generator and slot map with the draft index
+    fixed at 2^32 - 1, a value no drafting call reaches (its S is a 32-bit signed count), so that
+    equal (seed, offset) never hand a test the uniform that drew the token it tests."""
+    return uniforms(B, 1, slots, seed, offset, first_draft=VERIFY_DRAFT_INDEX)[:, 0]
+
+
+def uniforms(B: int, S: int, slots: int, seed: int, offset: int = 0, first_draft: int = 0) -> np.ndarray:
+    """u[b,s,t] for t < slots, float64 holding values exact in fp32 (draft indices
+    first_draft .. first_draft + S - 1)."""
     b = np.arange(B, dtype=np.uint64)[:, None, None]
-    s = np.arange(S, dtype=np.uint64)[None, :, None]
+    s = (np.arange(S, dtype=np.uint64) + np.uint64(first_draft))[None, :, None]
     t = np.arange(slots, dtype=np.uint64)[None, None, :]
     b, s, t = np.broadcast_arrays(b, s, t)
     key = (np.uint64(seed & 0xFFFFFFFF), np.uint64((seed >> 32) & 0xFFFFFFFF))

@@ -1,9 +1,9 @@
 """CPU oracle for the verification half of a speculative-decoding cycle:
 TEST INFRASTRUCTURE, not a product path (same rules as mtpc_oracle.py).
 
-Follows the accept / reject part of Alg. 2 (speculative sampling with a circuit
-as the draft model) step by step in float64, and the greedy variant the paper
-evaluates next to it (Sec. 3.4: a draft token survives iff it is the verifier's
+States the outcome of the accept / reject part of Alg. 2 (speculative sampling with a
+circuit as the draft model) in float64 - all acceptance tests of a row at once, the
+first failed one decides - and the greedy variant the paper evaluates next to it (Sec. 3.4: a draft token survives iff it is the verifier's
 argmax).  The conditional of the draft model is taken from its definition, a
 ratio of two prefix marginals, for every candidate token: no message passing,
 no reuse of anything the HIP library does.
@@ -64,35 +64,43 @@ def residual(p_next: np.ndarray, q_next: np.ndarray):
 
 
 def speculative_verify(family, logphi, logw, loglayers, drafts, p, u, mode="sampling"):
-    """One verification per position b (Alg. 2 from the acceptance loop on).
+    """One verification per position b (the accept / reject half of Alg. 2).
 
     drafts [B,n] int; p [B,n+1,v] verifier probabilities p(X_{t+i} | x_{<=t+i-1})
     evaluated along the draft; u [B,n+1] uniforms.
-    Returns accepted [B] (s in 0..n), token [B] (the token emitted after the s
-    accepted ones), and margin [B]: the smallest distance of any decision taken
-    for that row from its boundary (|alpha - p/q| of the tests, |u - cdf| of the
-    final draw; inf in greedy mode)."""
+
+    What the procedure defines, stated without its loop: test s passes iff
+    u[b,s] <= p[b,s,x_s] / q(x_s | x_<s) (greedy: iff x_s is the argmax of p[b,s]); the number
+    of accepted tokens is the length of the leading run of passed tests; the token emitted
+    after them is drawn with u[b,n] from the adjusted distribution at the first failed test,
+    or from p[b,n] when none failed (greedy: the argmax there).
+
+    Returns accepted [B] (0..n), token [B], and margin [B]: the smallest distance of any
+    decision that mattered for that row from its boundary (|u - p/q| of the tests up to and
+    including the first failed one, |u - cdf| of the final draw; inf in greedy mode)."""
     B, n, r, v = logphi.shape
     assert drafts.shape == (B, n) and p.shape == (B, n + 1, v) and u.shape == (B, n + 1)
-    accepted = np.zeros(B, dtype=np.int32)
+    rows = np.arange(B)
+    p_draft = p[rows[:, None], np.arange(n)[None, :], drafts]              # p[b,s,x_s]
+    if mode == "greedy":
+        passed = drafts == np.argmax(p[:, :n], axis=-1)
+    else:
+        P = oc.prefix_marginals_from(family, logphi, logw, loglayers, drafts)
+        logq = np.diff(P, axis=1, prepend=0.0)                              # log q(x_s | x_<s)
+        ratio = p_draft / np.exp(logq)
+        passed = u[:, :n] <= ratio
+    # length of the leading run of passed tests = index of the first failed one (n if none)
+    accepted = np.where(passed.all(axis=1), n, np.argmin(passed, axis=1)).astype(np.int32)
     token = np.zeros(B, dtype=np.int32)
     margin = np.full(B, np.inf)
-    P = oc.prefix_marginals_from(family, logphi, logw, loglayers, drafts)
+    if mode == "greedy":
+        token[:] = np.argmax(p[rows, accepted], axis=-1)
+        return accepted, token, margin
+    taken = np.arange(n)[None, :] <= accepted[:, None]                      # tests that were decisive
+    margin = np.min(np.where(taken, np.abs(u[:, :n] - ratio), np.inf), axis=1)
     for b in range(B):
-        s = 0
-        if mode == "greedy":
-            while s < n and drafts[b, s] == int(np.argmax(p[b, s])):
-                s += 1
-            accepted[b], token[b] = s, int(np.argmax(p[b, s]))
-            continue
-        while s < n:
-            alpha = u[b, s]
-            logq = P[b, s] - (P[b, s - 1] if s > 0 else 0.0)      # conditional of the drafted token
-            ratio = p[b, s, drafts[b, s]] / np.exp(logq)
-            margin[b] = min(margin[b], abs(alpha - ratio))
-            if alpha > ratio:
-                break
-            s += 1
+        s = int(accepted[b])
+        dist = p[b, n]
         if s < n:
             lay = None
             if loglayers is not None:
@@ -100,11 +108,8 @@ def speculative_verify(family, logphi, logw, loglayers, drafts, p, u, mode="samp
             q_next = np.exp(conditional_next(family, logphi[b], None if logw is None else logw[b],
                                              lay, drafts[b], s))
             dist = residual(p[b, s], q_next)
-        else:
-            dist = p[b, n]
-        tok, mg = draw_linear(dist, u[b, n])
+        token[b], mg = draw_linear(dist, u[b, n])
         margin[b] = min(margin[b], mg)
-        accepted[b], token[b] = s, tok
     return accepted, token, margin
 
 

@@ -38,21 +38,5 @@ def build(verbose: bool = False) -> str:
     return OUT
 
 
-PROBE_SRC = os.path.join(HERE, "csrc", "probes", "mfma_ceiling.hip")
-PROBE_OUT = os.path.join(HERE, "probes", "mfma_ceiling")
-
-
-def build_probes() -> str:
-    """Stand-alone measurement programs (not part of the library)."""
-    os.makedirs(os.path.dirname(PROBE_OUT), exist_ok=True)
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", PROBE_SRC, "-o", PROBE_OUT],
-                         capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stderr)
-    return PROBE_OUT
-
-
 if __name__ == "__main__":
-    print(build_probes())
     print(build(verbose=True))

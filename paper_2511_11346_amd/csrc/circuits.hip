@@ -644,14 +644,9 @@ __global__ __launch_bounds__(256) void k_btree_static(const CircuitArgs a, int G
   }
 }
 
-#ifndef MTPC_BTREE_RB
-#define MTPC_BTREE_RB 0           // 0: chosen from the row count
-#endif
-
 // rows per group of the program-driven tree kernel: 4 when that still gives every CU
 // two workgroups, else 2 (twice the workgroups, half the LDS each)
 static int btree_static_rb(const CircuitArgs& a) {
-  if (MTPC_BTREE_RB) return MTPC_BTREE_RB;
   int G = 1;
   while (G < a.r && G < 64) G <<= 1;
   return a.rows >= 4ll * (256 / G) * 512 ? 4 : 2;
@@ -673,15 +668,9 @@ static hipError_t launch_btree_static(const CircuitArgs& a, hipStream_t st) {
   const int groups = 256 / G;
   const int RB = btree_static_rb(a);
   const size_t smem = btree_static_smem(a);
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_btree_static<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            160 * 1024 - 64) != hipSuccess ||
-        hipFuncSetAttribute((const void*)k_btree_static<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            160 * 1024 - 64) != hipSuccess)
-      return hipErrorInvalidValue;
-    attr_done = true;
-  }
+  if (hipError_t e = RB == 4 ? allow_lds<k_btree_static<4>>(160 * 1024 - 64) : allow_lds<k_btree_static<2>>(160 * 1024 - 64);
+      e != hipSuccess)
+    return e;
   const long long ngroups = ((long long)a.rows + RB - 1) / RB;
   const dim3 grid((unsigned)((ngroups + groups - 1) / groups));
   if (RB == 4) hipLaunchKernelGGL(k_btree_static<4>, grid, dim3(256), smem, st, a, G);

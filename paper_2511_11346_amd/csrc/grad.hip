@@ -88,13 +88,8 @@ void k_unembed_grad(const GradLogitsArgs a) {
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
 static hipError_t launch_grad_cfg(const GradLogitsArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
-  auto kern = k_unembed_grad<WV, WB, VB, PB, SB, NS, BF16>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr auto kern = k_unembed_grad<WV, WB, VB, PB, SB, NS, BF16>;
+  if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nbt = (int)((a.ldb + TL::TP - 1) / TL::TP);
   hipLaunchKernelGGL(kern, dim3(nbt * a.n * a.r), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();
@@ -187,13 +182,8 @@ void k_gemm_tn(const GemmArgs a) {
 template <int WV, int WB, int VB, int PB, bool BF16>
 static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, 64, 4>;
-  auto kern = k_gemm_tn<WV, WB, VB, PB, 64, 4, BF16>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr auto kern = k_gemm_tn<WV, WB, VB, PB, 64, 4, BF16>;
+  if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nslab = (a.M + TL::TV - 1) / TL::TV, nbt = (a.N + TL::TP - 1) / TL::TP;
   hipLaunchKernelGGL(kern, dim3(nslab * nbt * max(a.ksplit, 1)), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "mtpc.h"
 
 namespace mtpc {
@@ -185,10 +187,7 @@ struct DrawGatherArgs {
   int greedy;
 };
 hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t st);
-#ifndef MTPC_GATHER_TILE
-#define MTPC_GATHER_TILE 128
-#endif
-constexpr int DRAW_GATHER_TILE = MTPC_GATHER_TILE;   // rows per tile of the gathered draw kernel
+constexpr int DRAW_GATHER_TILE = 128;   // rows per tile of the gathered draw kernel
 
 // Verification step of a speculative-decoding cycle (Alg. 2, acceptance loop on)
 struct VerifyArgs {
@@ -291,6 +290,22 @@ struct CircuitBwdArgs {
   float* dlayers;        // [L][r][r] gradient w.r.t. the layer logits (accumulated), or nullptr
 };
 hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st);
+
+// Raises a kernel's dynamic-LDS limit the first time the kernel is launched on a device.  This
+// is the library's only process-wide state: one bit per kernel and device, set once the call
+// has succeeded; threads that race here make the same idempotent call.
+template <auto Kern>
+inline hipError_t allow_lds(int bytes) {
+  static std::atomic<unsigned long long> done{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = (dev >= 0 && dev < 64) ? 1ull << dev : 0ull;
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute((const void*)Kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 hipError_t launch_philox_uniforms(int B, int S, int slots, uint32_t seed_lo, uint32_t seed_hi,
                                   uint32_t offset, float* out, hipStream_t st);

@@ -18,6 +18,11 @@
 namespace mtpc {
 namespace {
 
+// Draft index of the verification step's random numbers: drafting calls use 0 .. S-1 with S a
+// signed 32-bit count, so this counter word is never theirs and equal (seed, offset) cannot hand
+// an acceptance test the uniform that drew the token it tests.
+constexpr uint32_t VERIFY_DRAFT_INDEX = 0xffffffffu;
+
 __device__ __forceinline__ float wmax(float x) { return group_max(x, 64); }
 __device__ __forceinline__ float wsum(float x) { return group_sum(x, 64); }
 // block-wide reductions of 256 threads; `red` holds 4 floats
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(256) void k_verify(const VerifyArgs a, int G) {
   if (tid < n) {
     const float lq = a.prefix[(long long)b * n + tid] - (tid > 0 ? a.prefix[(long long)b * n + tid - 1] : 0.f);
     s_ratio[tid] = pv[(long long)tid * v + tok_at(tid)] / __expf(lq);
-    s_alpha[tid] = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, 0u, (uint32_t)tid);
+    s_alpha[tid] = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, VERIFY_DRAFT_INDEX, (uint32_t)tid);
   }
   __syncthreads();
   if (wave == 0) {
@@ -310,7 +315,7 @@ __global__ __launch_bounds__(256) void k_verify(const VerifyArgs a, int G) {
   }
   if (tid == 0) { s_lo = INT_MAX; s_hi = -1; }
   __syncthreads();
-  const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, 0u, (uint32_t)n);
+  const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, VERIFY_DRAFT_INDEX, (uint32_t)n);
   const float tgt = u * total;
   {
     float run = excl;
@@ -340,13 +345,7 @@ hipError_t launch_verify(const VerifyArgs& a, hipStream_t st) {
   int G = 1;
   while (G < a.r) G <<= 1;                                   // r <= 128 -> at least two column groups
   const size_t smem = ((size_t)a.n * a.r + (a.family == MTPC_BTREE ? (size_t)(a.n - 1) * a.r : 0) + a.v) * 4;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_verify, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) !=
-        hipSuccess)
-      return hipErrorInvalidValue;
-    attr_done = true;
-  }
+  if (hipError_t e = allow_lds<k_verify>(96 * 1024); e != hipSuccess) return e;
   hipLaunchKernelGGL(k_verify, dim3(a.B), dim3(256), smem, st, a, G);
   return hipGetLastError();
 }

@@ -16,10 +16,6 @@ typedef __attribute__((ext_vector_type(4))) int i32x4_t;
 
 constexpr int NSLOT = 16;         // positions sampled per pass of the draw loop
 
-#ifndef MTPC_PINGPONG
-#define MTPC_PINGPONG 1
-#endif
-
 template <int WV, int WB, int VB, int PB, int SB, int NS>
 struct Tile {
   static constexpr int NW = WV * WB;
@@ -71,7 +67,7 @@ struct Frag {
 
 // bf16 tiles of 8 waves (two per SIMD, ping-pong schedule) multiply through 16x16x32 MFMAs
 template <int WV, int WB, int SB, int NS, bool BF16>
-constexpr bool use_m16() { return BF16 && MTPC_PINGPONG && WV * WB == 8 && SB == 64 && NS >= 3; }
+constexpr bool use_m16() { return BF16 && WV * WB == 8 && SB == 64 && NS >= 3; }
 
 template <bool BF16>
 __device__ __forceinline__ void mma_step(f32x4_t& acc, const i32x4_t& a, const i32x4_t& b) {
@@ -175,7 +171,7 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
                                           const int* rows = nullptr, int nrows = 0, int rdiv = 1) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
   using FR = Frag<M16>;
-  static_assert(!M16 || (BF16 && MTPC_PINGPONG && NS >= 3 && TL::NW == 8 && SB == 64),
+  static_assert(!M16 || (BF16 && NS >= 3 && TL::NW == 8 && SB == 64),
                 "16x16 blocks: bf16, two waves per SIMD, one MFMA k-step per 64-byte stage");
   constexpr int ESZ = BF16 ? 2 : 4;
   constexpr int CPR = TL::CPR, KS = TL::KS;
@@ -289,7 +285,6 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   for (int s = 0; s < NS - 1; ++s)
     if (s < KI) issue(s);
 
-#if MTPC_PINGPONG
   if constexpr (NS >= 3 && TL::NW == 8) {
     // Ping-pong schedule for two waves per SIMD.  When both waves of a SIMD have an
     // MFMA ready the older one always wins, and a wave that alternates MFMAs with
@@ -367,9 +362,7 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
       barrier();
     }
     if (group == 0) __syncthreads();        // pairs with the late start of the other group
-  } else
-#endif
-  if constexpr (NS >= 3) {
+  } else if constexpr (NS >= 3) {
     // Waves issue LPW or LPW-1 loads per stage; allowing y*PER loads to stay in
     // flight guarantees, for either kind, that all but the y youngest stages have
     // landed (one count for all waves keeps the loop branch-free).  At the barrier

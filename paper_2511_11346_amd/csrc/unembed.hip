@@ -291,15 +291,8 @@ void k_unembed(const UnembedArgs a) {
   }
 }
 
-#ifndef MTPC_GATHER_NSL
-#define MTPC_GATHER_NSL 16
-#endif
-#ifndef MTPC_GATHER_SB
-#define MTPC_GATHER_SB 64
-#endif
-#ifndef MTPC_GATHER_NS
-#define MTPC_GATHER_NS 4
-#endif
+// stage geometry of the gathered draw tiles and the positions drawn per pass of their draw loop
+constexpr int GATHER_SB = 64, GATHER_NS = 4, GATHER_NSL = 16;
 // Token draws of Alg. 1 for training-sized batches: only the input unit a token is drawn
 // from is evaluated.  The (b, s, i) triples were bucketed by (i, z) = (token, selected
 // unit); a workgroup takes up to TP rows of one bucket, gathers their h rows, multiplies
@@ -333,7 +326,7 @@ void k_draw_gather(const DrawGatherArgs a) {
   int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
   for (int p = tid; p < nrows; p += TL::NT) s_list[p] = p;
   __syncthreads();
-  tile_draws<TL, VB, PB, MTPC_GATHER_NSL, M16>(acc, mx, a.v, smem, nrows, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
+  tile_draws<TL, VB, PB, GATHER_NSL, M16>(acc, mx, a.v, smem, nrows, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
                                                         float Z) {
     const int rid = rows[p];                         // b * S + s
     const int b = rid / a.S, s = rid - b * a.S;
@@ -352,15 +345,10 @@ void k_draw_gather(const DrawGatherArgs a) {
 
 template <int WV, int WB, int VB, int PB, bool BF16>
 static hipError_t launch_draw_gather_cfg(const DrawGatherArgs& a, hipStream_t st) {
-  using TL = Tile<WV, WB, VB, PB, MTPC_GATHER_SB, MTPC_GATHER_NS>;
+  using TL = Tile<WV, WB, VB, PB, GATHER_SB, GATHER_NS>;
   static_assert(TL::TP == DRAW_GATHER_TILE, "the bucketing kernels count tiles of this many rows");
-  auto kern = k_draw_gather<WV, WB, VB, PB, MTPC_GATHER_SB, MTPC_GATHER_NS, BF16>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr auto kern = k_draw_gather<WV, WB, VB, PB, GATHER_SB, GATHER_NS, BF16>;
+  if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const long long rows = (long long)a.B * a.S * a.n;
   const int grid = (int)(rows / TL::TP) + a.n * a.r;             // >= sum over buckets of ceil(rows_g / TP)
   hipLaunchKernelGGL(kern, dim3(grid), dim3(TL::NT), TL::SMEM, st, a);
@@ -379,9 +367,6 @@ hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t st
   return dtype == MTPC_BF16 ? launch_draw_gather_dt<true>(a, st) : launch_draw_gather_dt<false>(a, st);
 }
 
-#ifndef MTPC_SUMUNIT_SB
-#define MTPC_SUMUNIT_SB 128
-#endif
 // Sum-unit parameters for many positions (Sec. 3.3): log omega[b,:] =
 // log_softmax(Wsum h[b]).  Same tile machinery with Wsum as the only "slab" (r rows)
 // and narrow position tiles, so that B/32 workgroups share the work.
@@ -417,13 +402,8 @@ template <int SB, bool BF16>
 static hipError_t launch_sumunit_mfma_cfg(const void* h, long long ld_h, const void* Wsum, int B, int d,
                                           int r, float* logw, hipStream_t st) {
   using TL = Tile<2, 1, 2, 1, SB, 4>;      // 128 rows (r <= 128) x 32 positions, 2 waves
-  auto kern = k_sumunit_mfma<2, 1, 2, 1, SB, 4, BF16>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr auto kern = k_sumunit_mfma<2, 1, 2, 1, SB, 4, BF16>;
+  if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((B + TL::TP - 1) / TL::TP), dim3(TL::NT), TL::SMEM, st, h, ld_h, Wsum, B,
                      d, r, logw);
   return hipGetLastError();
@@ -434,8 +414,8 @@ static hipError_t launch_sumunit_mfma_cfg(const void* h, long long ld_h, const v
 template <bool BF16>
 static hipError_t launch_sumunit_mfma_dt(const void* h, long long ld_h, const void* Wsum, int B, int d,
                                          int r, float* logw, hipStream_t st) {
-  if ((d * (BF16 ? 2 : 4)) % MTPC_SUMUNIT_SB == 0)
-    return launch_sumunit_mfma_cfg<MTPC_SUMUNIT_SB, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
+  if ((d * (BF16 ? 2 : 4)) % 128 == 0)
+    return launch_sumunit_mfma_cfg<128, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
   return launch_sumunit_mfma_cfg<64, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
 }
 
@@ -586,13 +566,8 @@ void k_ctx_layers_dense(const CtxLayerArgs a) {
 template <int R, bool BF16>
 static hipError_t launch_ctx_dense(const CtxLayerArgs& a, hipStream_t st) {
   using TL = Tile<2, 4, 4, 2, 64, 4>;
-  auto kern = k_ctx_layers_dense<R, BF16>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr auto kern = k_ctx_layers_dense<R, BF16>;
+  if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int Mr = a.L * a.r * a.r;
   const int nbt = (a.B + TL::TP - 1) / TL::TP, nslab = (Mr + TL::TV - 1) / TL::TV;
   hipLaunchKernelGGL(kern, dim3(nbt * nslab), dim3(TL::NT), TL::SMEM, st, a);
@@ -613,14 +588,8 @@ static hipError_t launch_ctx_dense_dt(const CtxLayerArgs& a, hipStream_t st) {
 template <int WV, int WB, int VB, int PB, bool BF16>
 static hipError_t launch_ctx_cfg(const CtxLayerArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, 64, 4>;
-  auto kern = k_ctx_layers<WV, WB, VB, PB, 64, 4, BF16>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       TL::SMEM);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr auto kern = k_ctx_layers<WV, WB, VB, PB, 64, 4, BF16>;
+  if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nbt = (a.B + TL::TP - 1) / TL::TP;
   hipLaunchKernelGGL(kern, dim3(nbt * a.L * a.r), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();
@@ -707,14 +676,8 @@ void k_univariate(const UnivariateArgs a) {
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
 static hipError_t launch_uni_cfg(const UnivariateArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
-  auto kern = k_univariate<WV, WB, VB, PB, SB, NS, BF16>;
-  static bool attr_done = false;   // raising the dynamic LDS limit is idempotent
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       TL::SMEM);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr auto kern = k_univariate<WV, WB, VB, PB, SB, NS, BF16>;
+  if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nbt = (a.B + TL::TP - 1) / TL::TP;
   hipLaunchKernelGGL(kern, dim3(nbt * a.n), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();
@@ -739,27 +702,13 @@ hipError_t launch_univariate(const UnivariateArgs& a, int dtype, hipStream_t st)
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE>
 static hipError_t launch_cfg(const UnembedArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
-  auto kern = k_unembed<WV, WB, VB, PB, SB, NS, BF16, SAMPLE>;
-  static bool attr_done = false;   // raising the dynamic LDS limit is idempotent
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       TL::SMEM);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr auto kern = k_unembed<WV, WB, VB, PB, SB, NS, BF16, SAMPLE>;
+  if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nbt = (a.B + TL::TP - 1) / TL::TP;
   const int grid = nbt * a.n * a.r;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();
 }
-
-// Stage geometry of the 320 x 256 training tile (overridable for experiments)
-#ifndef MTPC_TRAIN_SB
-#define MTPC_TRAIN_SB 64
-#endif
-#ifndef MTPC_TRAIN_NS
-#define MTPC_TRAIN_NS 4
-#endif
 
 // Decode-shaped tiles (B <= 64: WV waves over the vocabulary, W streamed once) are bound by HBM:
 // 128-byte stages in a 3-stage ring when the rows allow it (whole cache lines per row and stage,
@@ -777,11 +726,7 @@ static hipError_t launch_dt(const UnembedArgs& a, hipStream_t st) {
   // batches, 64- or 32-wide tiles (W streamed once) for decode-sized ones.
   const int row_bytes = a.d * (BF16 ? 2 : 4);
   if (a.B > 64) {
-    if (a.v > 256) {
-      if (row_bytes % MTPC_TRAIN_SB == 0)
-        return launch_cfg<2, 4, 5, 2, MTPC_TRAIN_SB, MTPC_TRAIN_NS, BF16, SAMPLE>(a, st);
-      return launch_cfg<2, 4, 5, 2, 64, 4, BF16, SAMPLE>(a, st);
-    }
+    if (a.v > 256) return launch_cfg<2, 4, 5, 2, 64, 4, BF16, SAMPLE>(a, st);
     if (a.v > 128) return launch_cfg<2, 4, 4, 2, 64, 4, BF16, SAMPLE>(a, st);
     return launch_cfg<2, 4, 2, 2, 64, 4, BF16, SAMPLE>(a, st);
   }

@@ -10,7 +10,7 @@ import mtpc_inputs as mi
 from oracle import mtpc_oracle as oc
 from oracle import philox
 
-from gpu_util import BOUNDARY, compare_drafts, make_head, tol_check
+from gpu_util import BOUNDARY, FP32_ABS, compare_drafts, make_head, tol_check
 
 pytestmark = pytest.mark.gpu
 
@@ -143,8 +143,9 @@ def test_peaked_logits_and_forbidden_transitions():
     want = oc.joint("hmm", oc.evidence(logphi, inp.targets), logw, loglayers)
     got = head.loglik(tg).cpu().numpy()
     assert np.all(np.isfinite(got))
-    # sharp softmaxes amplify fp32 rounding of the logits themselves (|l| ~ 30)
-    assert np.max(np.abs(got - want)) < 5e-4
+    err = float(np.max(np.abs(got - want)))
+    print(f"peaked logits: max abs err {err:.2e}")
+    assert err <= FP32_ABS
     u = philox.uniforms(70, 2, 5 + 5, seed=11)
     od, ol, margin = oc.sample_from("hmm", logphi, logw, loglayers, u, with_margin=True)
     gd, gl, _ = head.sample(2, seed=11)

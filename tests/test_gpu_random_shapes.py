@@ -42,7 +42,6 @@ def draw_cases(count=24, seed=20251127):
 @pytest.mark.parametrize("family,dtype,B,d,n,r,v", draw_cases())
 def test_every_operation_on_a_drawn_shape(family, dtype, B, d, n, r, v):
     inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=n * 1000 + r * 7 + v, h_scale=1.0)
-    inp.targets[:] = np.random.default_rng(1).integers(0, v, size=inp.targets.shape)
     head = make_head(inp)
     layers = inp.layers if inp.layers is not None and inp.layers.size else None
     logphi, logw, loglayers = oc._params(family, inp.h, inp.W, inp.Wsum, layers)
@@ -71,11 +70,28 @@ def test_every_operation_on_a_drawn_shape(family, dtype, B, d, n, r, v):
     tol_check(both[:, 1], oc.prefix_marginals_from(family, logphi, logw, loglayers, gd2[:, 0].cpu().numpy()), dtype,
               "draft scores (two window sets)")
     tol_check(head.table_scores(table, tg).cpu().numpy(), want[:, -1], dtype, "loglik from the table")
+    # univariate marginals, through the table of input units and mixed in registers: a few tokens of
+    # every position of two rows against the definition (that one variable observed, the others summed
+    # out), and every distribution sums to one
+    rows = np.unique([0, B - 1])
+    ids = np.unique(np.concatenate([[0, v - 1], np.random.default_rng(3).integers(0, v, size=6)]))
+    wins = np.full((len(rows), n, len(ids), n), -1, dtype=np.int64)
+    for i in range(n):
+        wins[:, i, :, i] = ids[None, :]
+    for keep in (True, False):
+        M = head.univariate_marginals(keep_table=keep).cpu().numpy()
+        for k, b in enumerate(rows):
+            x = wins[k].reshape(-1, n)
+            rep = lambda t: None if t is None else np.repeat(t[b:b + 1], len(x), axis=0)
+            lay_b = loglayers[b] if (loglayers is not None and loglayers.ndim == 4) else loglayers
+            want_u = oc.joint(family, oc.evidence(rep(logphi), x), rep(logw), lay_b).reshape(n, len(ids))
+            tol_check(M[b][:, ids], want_u, dtype, f"univariate marginals (table kept: {keep})")
+        assert np.abs(np.log(np.exp(M.astype(np.float64)).sum(axis=-1))).max() < 2e-4
     # verification on oracle-built inputs
     drafts = od[:, 0].astype(np.int32)
     P = oc.prefix_marginals_from(family, logphi, logw, loglayers, drafts)
     p = synthetic_verifier(inp, logphi, logw, loglayers, drafts, seed=4)
-    uv = philox.uniforms(B, 1, n + 1, 10, 1)[:, 0]
+    uv = philox.verify_uniforms(B, n + 1, 10, 1)
     w_acc, w_tok, mg = sp.speculative_verify(family, logphi, logw, loglayers, drafts, p, uv)
     acc, tok = head.verify(torch.from_numpy(drafts).cuda(), torch.from_numpy(p.astype(np.float32)).cuda(),
                            prefix_logq=torch.from_numpy(P.astype(np.float32)).cuda(),

@@ -55,7 +55,7 @@ def test_verify_matches_oracle(family, dtype, B, d, n, r, v, ctx):
     drafts = od[:, 0].astype(np.int32)
     P = oc.prefix_marginals_from(family, logphi, logw, loglayers, drafts)
     p = synthetic_verifier(inp, logphi, logw, loglayers, drafts, seed=5)
-    u = philox.uniforms(B, 1, n + 1, 12, 3)[:, 0]
+    u = philox.verify_uniforms(B, n + 1, 12, 3)
     best = p.argmax(axis=-1)
     greedy_drafts = best[:, :n].astype(np.int32)             # argmax chain, broken at position b % (n+1)
     for b in range(B):

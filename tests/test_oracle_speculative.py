@@ -13,6 +13,7 @@ import pytest
 
 from oracle import bruteforce as bf
 from oracle import mtpc_oracle as oc
+from oracle import philox
 from oracle import speculative as sp
 
 from test_oracle_circuits import tables, tiny
@@ -117,6 +118,41 @@ def test_emitted_tokens_follow_the_verifier(family, n):
         expect = cond.sum(axis=0)
         counts = np.bincount(emitted, minlength=v)
         assert np.all(np.abs(counts - expect) <= 4.5 * np.sqrt(0.25 * len(rows)) + 1), (k, counts, expect)
+
+
+def test_verification_has_a_random_stream_of_its_own():
+    """Drafting and verification called with the SAME seed and offset: the acceptance test of
+    token s must not see the uniform that drew token s (it would then accept or reject in step
+    with the draft and the emitted tokens would stop following the verifier).  The slot map
+    gives verification a draft index no drafting call uses; checked on the words themselves and
+    on the property that defines speculative sampling, Philox-driven end to end."""
+    n, r, v, N = 3, 3, 3, 24000
+    ud = philox.uniforms(N, 2, n + 1, seed=6, offset=2)
+    uv = philox.verify_uniforms(N, n + 1, seed=6, offset=2)
+    assert uv.shape == (N, n + 1) and np.all((uv >= 0) & (uv < 1))
+    assert not np.any(np.all(uv == ud[:, 0], axis=1)) and not np.any(np.all(uv == ud[:, 1], axis=1))
+    assert abs(np.corrcoef(uv[:, 0], ud[:, 0, 0])[0, 1]) < 0.03
+    raw, logphi, logw, loglayers = circuit("cp", n, r, v, seed=21)
+    T = ar_tables(n, v, seed=4)
+    phiN = np.broadcast_to(logphi, (N,) + logphi.shape[1:])
+    lwN = np.broadcast_to(logw, (N, logw.shape[1]))
+    drafts = oc.sample_from("cp", phiN, lwN, None, ud[:, :1])[0][:, 0]
+    p = np.empty((N, n + 1, v))
+    for k in range(n + 1):
+        p[:, k] = T[k][tuple(drafts[:, i] for i in range(k))] if k else T[0]
+    acc, tok, _ = sp.speculative_verify("cp", phiN, lwN, None, drafts, p, uv)
+    for k in range(n + 1):
+        rows = np.nonzero(acc >= k)[0]
+        emitted = np.where(acc[rows] > k, drafts[rows, min(k, n - 1)], tok[rows])
+        cond = T[k][tuple(drafts[rows, i] for i in range(k))] if k else np.broadcast_to(T[0], (len(rows), v))
+        counts = np.bincount(emitted, minlength=v)
+        assert np.all(np.abs(counts - cond.sum(axis=0)) <= 4.5 * np.sqrt(0.25 * len(rows)) + 1), (k, counts)
+    # the collision this guards against does break the property: tests fed the drafting uniforms
+    acc2, tok2, _ = sp.speculative_verify("cp", phiN, lwN, None, drafts, p, ud[:, 0])
+    rows = np.arange(N)
+    emitted = np.where(acc2 > 0, drafts[:, 0], tok2)
+    counts = np.bincount(emitted, minlength=v)
+    assert np.any(np.abs(counts - N * T[0]) > 4.5 * np.sqrt(0.25 * N) + 1)
 
 
 @pytest.mark.parametrize("family", FAMS)
