@@ -308,6 +308,9 @@ mtpc_status mtpc_philox_uniforms(int32_t B, int32_t S, int32_t slots, uint64_t s
  * thread records `start` right before and `stop` right after its unembedding
  * kernel launch(es) on the call's stream.  Pass NULLs to switch it off. */
 void mtpc_profile_unembed(void* start_event, void* stop_event);
+/* The same around the circuit kernel of a call (the sum / product layers of Eqs. FF / CP /
+ * HMM / BTree on the evidence, with or without prefix marginals). */
+void mtpc_profile_circuit(void* start_event, void* stop_event);
 
 #ifdef __cplusplus
 }

@@ -50,7 +50,7 @@ EXPORTS = [
     "mtpc_ff_table_scores", "mtpc_cp_table_scores", "mtpc_hmm_table_scores", "mtpc_btree_table_scores",
     "mtpc_ff_greedy_draft", "mtpc_cp_greedy_draft", "mtpc_hmm_greedy_draft", "mtpc_btree_greedy_draft",
     "mtpc_ff_loss_backward", "mtpc_cp_loss_backward", "mtpc_hmm_loss_backward", "mtpc_btree_loss_backward",
-    "mtpc_philox_uniforms", "mtpc_profile_unembed",
+    "mtpc_philox_uniforms", "mtpc_profile_unembed", "mtpc_profile_circuit",
 ]
 
 _lib = None
@@ -92,8 +92,10 @@ def lib() -> C.CDLL:
                                            fp, C.c_void_p]
         L.mtpc_profile_unembed.argtypes = [C.c_void_p, C.c_void_p]
         L.mtpc_profile_unembed.restype = None
+        L.mtpc_profile_circuit.argtypes = [C.c_void_p, C.c_void_p]
+        L.mtpc_profile_circuit.restype = None
         for name in EXPORTS:
-            if name not in ("mtpc_status_string", "mtpc_workspace_bytes", "mtpc_profile_unembed"):
+            if name not in ("mtpc_status_string", "mtpc_workspace_bytes", "mtpc_profile_unembed", "mtpc_profile_circuit"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -355,3 +357,7 @@ def philox_uniforms(B: int, S: int, slots: int, seed: int, offset: int = 0, devi
 
 def profile_unembed(start_event: Optional[int], stop_event: Optional[int]) -> None:
     lib().mtpc_profile_unembed(start_event, stop_event)
+
+
+def profile_circuit(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    lib().mtpc_profile_circuit(start_event, stop_event)

@@ -11,7 +11,8 @@ constexpr size_t ALIGN = 256;
 inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Events { void* start; void* stop; };
-thread_local Events g_prof = {nullptr, nullptr};
+enum { PROF_UNEMBED = 0, PROF_CIRCUIT = 1 };
+thread_local Events g_prof[2] = {{nullptr, nullptr}, {nullptr, nullptr}};
 
 int n_latents(int family, int n) {
   switch (family) {
@@ -158,13 +159,20 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
 
 struct ProfScope {
   hipStream_t st;
-  explicit ProfScope(hipStream_t s) : st(s) {
-    if (g_prof.start && g_prof.stop) (void)hipEventRecord((hipEvent_t)g_prof.start, st);
+  const Events& ev;
+  explicit ProfScope(hipStream_t s, int which = PROF_UNEMBED) : st(s), ev(g_prof[which]) {
+    if (ev.start && ev.stop) (void)hipEventRecord((hipEvent_t)ev.start, st);
   }
   ~ProfScope() {
-    if (g_prof.start && g_prof.stop) (void)hipEventRecord((hipEvent_t)g_prof.stop, st);
+    if (ev.start && ev.stop) (void)hipEventRecord((hipEvent_t)ev.stop, st);
   }
 };
+
+// the circuit kernel of a call, bracketed by the profiling events when they are set
+hipError_t profiled_circuit(const CircuitArgs& c, hipStream_t st) {
+  ProfScope prof(st, PROF_CIRCUIT);
+  return launch_circuit(c, st);
+}
 
 #define HIP_TRY(x) do { if ((x) != hipSuccess) return MTPC_ERR_HIP; } while (0)
 
@@ -252,7 +260,7 @@ mtpc_status run_evidence_op(int family, const mtpc_head* hd, const mtpc_sumlayer
     ProfScope prof(st);
     HIP_TRY(launch_unembed(u, hd->dtype, st));
   }
-  HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B, 1, out, prefix), st));
+  HIP_TRY(profiled_circuit(circuit_args(family, hd, p, hd->B, 1, out, prefix), st));
   return MTPC_OK;
 }
 
@@ -408,7 +416,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
       g.x = drafts; g.e = (float*)(ws + p.e);
       HIP_TRY(launch_gather_table(g, table, st));
     }
-    HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * S, S, prefix_logq, 1), st));
+    HIP_TRY(profiled_circuit(circuit_args(family, hd, p, hd->B * S, S, prefix_logq, 1), st));
   }
   return MTPC_OK;
 }
@@ -435,7 +443,7 @@ mtpc_status run_window_scores(int family, const mtpc_head* hd, const mtpc_sumlay
     ProfScope prof(st);
     HIP_TRY(launch_unembed(u, hd->dtype, st));
   }
-  HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * (int)TT, (int)TT, out, mode == MTPC_SCORE_PREFIX), st));
+  HIP_TRY(profiled_circuit(circuit_args(family, hd, p, hd->B * (int)TT, (int)TT, out, mode == MTPC_SCORE_PREFIX), st));
   return MTPC_OK;
 }
 
@@ -457,7 +465,7 @@ mtpc_status run_table_scores(int family, const mtpc_head* hd, const mtpc_sumlaye
   g.B = hd->B; g.S = T; g.v = hd->v; g.n = hd->n; g.r = hd->r;
   g.x = x; g.e = (float*)(ws + p.e);
   HIP_TRY(launch_gather_table(g, logphi, st));
-  HIP_TRY(launch_circuit(circuit_args(family, hd, p, hd->B * T, T, out, mode == MTPC_SCORE_PREFIX), st));
+  HIP_TRY(profiled_circuit(circuit_args(family, hd, p, hd->B * T, T, out, mode == MTPC_SCORE_PREFIX), st));
   return MTPC_OK;
 }
 
@@ -910,8 +918,13 @@ mtpc_status mtpc_philox_uniforms(int32_t B, int32_t S, int32_t slots, uint64_t s
 }
 
 void mtpc_profile_unembed(void* start_event, void* stop_event) {
-  g_prof.start = start_event;
-  g_prof.stop = stop_event;
+  g_prof[PROF_UNEMBED].start = start_event;
+  g_prof[PROF_UNEMBED].stop = stop_event;
+}
+
+void mtpc_profile_circuit(void* start_event, void* stop_event) {
+  g_prof[PROF_CIRCUIT].start = start_event;
+  g_prof[PROF_CIRCUIT].stop = stop_event;
 }
 
 }  // extern "C"

@@ -649,7 +649,7 @@ __global__ __launch_bounds__(256) void k_btree_static(const CircuitArgs a, int G
 static int btree_static_rb(const CircuitArgs& a) {
   int G = 1;
   while (G < a.r && G < 64) G <<= 1;
-  return a.rows >= 4ll * (256 / G) * 512 ? 4 : 2;
+  return a.rows >= 8ll * (256 / G) * 512 ? 4 : 2;
 }
 
 // LDS the program-driven tree kernel needs (0: shape not supported by it)

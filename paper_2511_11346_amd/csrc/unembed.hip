@@ -143,13 +143,40 @@ void k_unembed(const UnembedArgs a) {
   const int b0 = bt * TL::TP;
   const int wi = slab / a.r, wj = slab - wi * a.r;
 
+  // Target tokens of the tile's positions, first XW windows of each: fetched now, while nothing
+  // depends on them, parked in LDS after the product (the list / slot area the draws use, idle
+  // in this instantiation).  Read in the epilogue they would be one dependent memory round
+  // trip per position column and window, with the matrix pipe idle.
+  constexpr int XW = 2, XR = (XW * TL::TP + TL::NT - 1) / TL::NT;
+  int* s_x = (int*)(smem + TL::MISC_OFF) + 4;        // [XW][TP]
+  int xpre[XR];
+  int nxw = 0;
+  if constexpr (!SAMPLE) if (a.targets != nullptr) {
+    nxw = min(a.T + a.T2, XW);
+#pragma unroll
+    for (int q = 0; q < XR; ++q) {
+      const int idx = tid + q * TL::NT, t = idx / TL::TP, p = idx - t * TL::TP;
+      const long long b = b0 + p;
+      xpre[q] = -1;
+      if (t < nxw && b < a.B)
+        xpre[q] = t < a.T ? a.targets[(b * a.T + t) * a.n + wi] : a.targets2[(b * a.T2 + (t - a.T)) * a.n + wi];
+    }
+  }
+
   typename FR::blk_t acc[NPB][NVB];
   tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
 
+  if constexpr (!SAMPLE) if (a.targets != nullptr) {
+#pragma unroll
+    for (int q = 0; q < XR; ++q) {
+      const int idx = tid + q * TL::NT;
+      if (idx < nxw * TL::TP) s_x[idx] = xpre[q];
+    }
+  }
   // this lane holds, of position column wb*PB*32 + pb*BR + lcol, rows rbase + vb*BR + roff(i)
   const int rbase = wv * VB * 32 + 4 * lgrp;
   float mx[NPB], lse[NPB];
-  tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
+  tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);   // (one barrier: s_x is visible)
 
   // evidence at the target tokens (the sampling instantiation never has targets)
   if constexpr (!SAMPLE) if (a.targets != nullptr) {
@@ -160,8 +187,9 @@ void k_unembed(const UnembedArgs a) {
         const int TT = a.T + a.T2;
         for (int t = 0; t < TT; ++t) {
           const long long rowid = (long long)b * TT + t;
-          const int x = t < a.T ? a.targets[((long long)b * a.T + t) * a.n + wi]
-                                : a.targets2[((long long)b * a.T2 + (t - a.T)) * a.n + wi];
+          const int x = t < XW ? s_x[t * TL::TP + (b - b0)]
+                        : t < a.T ? a.targets[((long long)b * a.T + t) * a.n + wi]
+                                  : a.targets2[((long long)b * a.T2 + (t - a.T)) * a.n + wi];
           float* dst = a.e + (rowid * a.n + wi) * a.r + wj;
           if (x < 0 || x >= a.v) {
             if (wv == 0 && lgrp == 0) *dst = (x == -1) ? 0.f : __builtin_nanf("");
@@ -306,11 +334,14 @@ void k_draw_gather(const DrawGatherArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   // each XCD owns a contiguous range of logical tiles, so that the tiles of a bucket
   // (which share a W slab) run under one L2
-  const int per = (int)gridDim.x >> 3;
-  const int w = blockIdx.x;
-  const int lid = (w < per * 8) ? (w & 7) * per + (w >> 3) : w;
+  // (the grid is an upper bound; the ranges are cut from the number of tiles there are, so that
+  // every XCD gets its share of them)
   const int ngroups = a.n * a.r;
-  if (lid >= a.tile_off[ngroups]) return;            // the grid is an upper bound
+  const int total = a.tile_off[ngroups];
+  const int w = blockIdx.x;
+  if (w >= total) return;
+  const int per = total >> 3;
+  const int lid = (w < per * 8) ? (w & 7) * per + (w >> 3) : w;
   const int g = a.tile_bucket[lid];                  // tile_off[g] <= lid < tile_off[g+1]
   const int first = a.row_off[g] + (lid - a.tile_off[g]) * TL::TP;
   const int nrows = min(a.row_off[g + 1] - first, TL::TP);     // >= 1 by construction of tile_off
