@@ -164,6 +164,27 @@ mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, in
                               uint64_t seed, uint32_t offset,
                               int32_t* drafts, int32_t* latents, float* prefix_logq, float* logphi);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): mtpc_*_sample with `family` as an argument (`layers` is
+ * ignored for MTPC_FF / MTPC_CP and may be NULL) and with the scratch taken from a static
+ * array of MTPC_STATIC_SCRATCH_BYTES in the library's device image instead of head->workspace
+ * (head->workspace and workspace_bytes are ignored).  Nothing is allocated or freed by the call
+ * or by anything it calls.  Every GPU the library runs on holds its own copy of the array from
+ * load to process end; all calls on one GPU share it, so calls that overlap on one GPU - other
+ * streams, other threads - race: issue them on one stream or order them yourself.  The array's
+ * address on a device is looked up on the first call made with that device current (not a
+ * stream operation; make that call outside a capture).
+ * Sizes: whatever mtpc_*_sample accepts whose scratch fits: the sum-unit weights, the
+ * normalised layers, latents, and - when prefix_logq is asked for - the evidence of the drafts,
+ * about (B r + L r r + B S n (r + 3)) * 4 bytes.  A decode-sized batch (B <= 64) that asks for
+ * prefix_logq must also pass logphi: the table of input units is then the caller's buffer, never
+ * scratch.  Anything larger returns MTPC_ERR_WORKSPACE and launches nothing.
+ * Results are those of mtpc_*_sample for the same arguments, bit for bit. */
+#define MTPC_STATIC_SCRATCH_BYTES (4u << 20)
+mtpc_status mtpc_sample_static(int32_t family, const mtpc_head* head, const mtpc_sumlayers* layers,
+                               int32_t S, uint64_t seed, uint32_t offset, int32_t* drafts,
+                               int32_t* latents, float* prefix_logq, float* logphi);
+
 /* Scores of several windows per position in ONE unembedding pass: the log-likelihood
  * (Eqs. FF / CP / HMM / BTree) or the prefix marginals (Alg. 2) of every window, as
  * mtpc_*_loglik / MTPC_MARG_PREFIX compute them for one.  The windows come as two sets so

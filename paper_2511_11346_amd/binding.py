@@ -50,7 +50,7 @@ EXPORTS = [
     "mtpc_ff_table_scores", "mtpc_cp_table_scores", "mtpc_hmm_table_scores", "mtpc_btree_table_scores",
     "mtpc_ff_greedy_draft", "mtpc_cp_greedy_draft", "mtpc_hmm_greedy_draft", "mtpc_btree_greedy_draft",
     "mtpc_ff_loss_backward", "mtpc_cp_loss_backward", "mtpc_hmm_loss_backward", "mtpc_btree_loss_backward",
-    "mtpc_philox_uniforms", "mtpc_profile_unembed", "mtpc_profile_circuit",
+    "mtpc_philox_uniforms", "mtpc_profile_unembed", "mtpc_profile_circuit", "mtpc_sample_static",
 ]
 
 _lib = None
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
         L.mtpc_btree_loss_backward.argtypes = [hp, lp, ip, fp, fp, fp, fp, fp, fp, fp]
         L.mtpc_philox_uniforms.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
                                            fp, C.c_void_p]
+        L.mtpc_sample_static.argtypes = [C.c_int32, hp, lp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
         L.mtpc_profile_unembed.argtypes = [C.c_void_p, C.c_void_p]
         L.mtpc_profile_unembed.restype = None
         L.mtpc_profile_circuit.argtypes = [C.c_void_p, C.c_void_p]
@@ -233,6 +234,26 @@ class Head:
                           pl.data_ptr() if pl is not None else None,
                           self._phi_ptr(logphi)))
         return drafts, lat, pl
+
+    def sample_static(self, S: int, seed: int, offset: int, drafts: torch.Tensor, latents: Optional[torch.Tensor] = None,
+                      prefix_logq: Optional[torch.Tensor] = None, logphi: Optional[torch.Tensor] = None) -> None:
+        """sample() through the entry point that allocates nothing: every buffer is the caller's, the
+        scratch is the library's static device array (one per GPU; calls on one GPU must not overlap)."""
+        assert drafts.is_cuda and drafts.dtype == torch.int32 and drafts.is_contiguous()
+        assert tuple(drafts.shape) == (self.B, S, self.n)
+        hd = mtpc_head()
+        hd.B, hd.d, hd.n, hd.r, hd.v = self.B, self.d, self.n, self.r, self.v
+        hd.dtype = BF16 if self.h.dtype == torch.bfloat16 else F32
+        hd.h, hd.ld_h = self.h.data_ptr(), self.h.stride(0)
+        hd.W = self.W.data_ptr()
+        hd.Wsum = self.Wsum.data_ptr() if self.Wsum is not None else None
+        hd.workspace, hd.workspace_bytes = None, 0
+        hd.stream = torch.cuda.current_stream(self.h.device).cuda_stream
+        _check(lib().mtpc_sample_static(FAMILY[self.family], C.byref(hd), self._layers_ref(), S, seed, offset,
+                                        drafts.data_ptr(),
+                                        latents.data_ptr() if latents is not None and latents.numel() > 0 else None,
+                                        prefix_logq.data_ptr() if prefix_logq is not None else None,
+                                        self._phi_ptr(logphi)))
 
     def loss_backward(self, targets: torch.Tensor, coef: torch.Tensor, out: Optional[dict] = None,
                       recompute: bool = False) -> dict:

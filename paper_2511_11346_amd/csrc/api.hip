@@ -1,8 +1,15 @@
 // C ABI of libmtpc (include/mtpc.h): argument validation, workspace carve-up and
 // the launch sequence of each operation.  Host code only.
 #include <cstring>
+#include <mutex>
 
 #include "mtpc_internal.h"
+
+// Scratch of mtpc_sample_static: one array per GPU the library is loaded on, held until the
+// process ends.  In host code this name only stands for the symbol; the array's address on a
+// device comes from hipGetSymbolAddress (see static_scratch below) and is what kernels get.
+constexpr size_t STATIC_SCRATCH_BYTES = MTPC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 namespace mtpc {
 namespace {
@@ -107,7 +114,7 @@ mtpc_status check_layers(int family, const mtpc_head* hd, const mtpc_sumlayers* 
 }
 
 Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly, int S, int mode,
-               bool want_prefix) {
+               bool want_prefix, bool caller_table = false) {
   Plan p{};
   const size_t B = hd->B, n = hd->n, r = hd->r;
   const int L = n_layers(family, hd->n);
@@ -134,7 +141,8 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   p.lay_circ = need_tr ? take(lay_bytes) : p.lay_nat;
   const size_t rows = (sample || table_op) ? B * (size_t)S : B;
   p.e = (uni || verify || (sample && !want_prefix)) ? 0 : take(rows * n * r * 4);
-  p.has_table = sample && want_prefix && table_in_workspace(hd, S);
+  // (a sampling call that is handed a table to fill scores its drafts from that one)
+  p.has_table = sample && want_prefix && !caller_table && table_in_workspace(hd, S);
   p.table = p.has_table ? take(B * n * r * (size_t)hd->v * 4) : 0;
   p.rowlogits = (sample && few_drafts(hd, S)) ? take(B * (size_t)S * n * hd->v * 4) : 0;
   if (sample && !decode_sized(hd)) {
@@ -177,13 +185,13 @@ hipError_t profiled_circuit(const CircuitArgs& c, hipStream_t st) {
 #define HIP_TRY(x) do { if ((x) != hipSuccess) return MTPC_ERR_HIP; } while (0)
 
 mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly, int S, int mode,
-                    bool want_prefix, Plan& plan) {
+                    bool want_prefix, Plan& plan, bool caller_table = false) {
   mtpc_status st = check_head(family, hd);
   if (st != MTPC_OK) return st;
   st = check_layers(family, hd, ly);
   if (st != MTPC_OK) return st;
   if ((op == MTPC_OP_SAMPLE || op == MTPC_OP_TABLE || op == MTPC_OP_WINDOWS) && S < 1) return MTPC_ERR_SHAPE;
-  plan = make_plan(family, op, hd, ly, S, mode, want_prefix);
+  plan = make_plan(family, op, hd, ly, S, mode, want_prefix, caller_table);
   if (!hd->workspace) return MTPC_ERR_NULL;
   if ((uintptr_t)hd->workspace & 15) return MTPC_ERR_WORKSPACE;
   if (hd->workspace_bytes < plan.total) {
@@ -320,7 +328,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   if (!drafts) return MTPC_ERR_NULL;
   const bool want_prefix = prefix_logq != nullptr;
   Plan p;
-  mtpc_status s = prepare(family, MTPC_OP_SAMPLE, hd, ly, S, 0, want_prefix, p);
+  mtpc_status s = prepare(family, MTPC_OP_SAMPLE, hd, ly, S, 0, want_prefix, p, logphi != nullptr);
   if (s != MTPC_OK) return s;
   if ((long long)hd->B * S > 0x7fffffffLL / hd->n) return MTPC_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)hd->stream;
@@ -734,6 +742,24 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   return MTPC_OK;
 }
 
+// Address of the static scratch array on the current device, looked up once per device.
+mtpc_status static_scratch(void** out) {
+  constexpr int MAX_DEV = 64;
+  static std::mutex mu;
+  static void* ptrs[MAX_DEV] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return MTPC_ERR_HIP;
+  if (dev < 0 || dev >= MAX_DEV) return MTPC_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptrs[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return MTPC_ERR_HIP;
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return MTPC_OK;
+}
+
 }  // namespace
 }  // namespace mtpc
 
@@ -812,6 +838,20 @@ mtpc_status mtpc_btree_sample(const mtpc_head* head, const mtpc_sumlayers* A, in
                               uint32_t offset, int32_t* drafts, int32_t* latents, float* prefix_logq,
                               float* logphi) {
   return run_sample(MTPC_BTREE, head, A, S, seed, offset, drafts, latents, prefix_logq, logphi);
+}
+
+mtpc_status mtpc_sample_static(int32_t family, const mtpc_head* head, const mtpc_sumlayers* layers, int32_t S,
+                               uint64_t seed, uint32_t offset, int32_t* drafts, int32_t* latents,
+                               float* prefix_logq, float* logphi) {
+  if (family < MTPC_FF || family > MTPC_BTREE) return MTPC_ERR_UNSUPPORTED;
+  if (!head) return MTPC_ERR_NULL;
+  mtpc_head hd = *head;                       // the caller's workspace fields are not used
+  void* ptr = nullptr;
+  const mtpc_status s = static_scratch(&ptr);
+  if (s != MTPC_OK) return s;
+  hd.workspace = ptr;
+  hd.workspace_bytes = STATIC_SCRATCH_BYTES;  // a call that needs more returns MTPC_ERR_WORKSPACE
+  return run_sample(family, &hd, layers, S, seed, offset, drafts, latents, prefix_logq, logphi);
 }
 
 mtpc_status mtpc_ff_greedy_draft(const mtpc_head* head, int32_t* drafts, int32_t* latents, float* prefix_logq,
