@@ -511,7 +511,7 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
 // [M, M + r) sum-unit logits, then - only when the layers are computed from h - a gap up
 // to Mlay (a multiple of 64) and L*r*r layer logits; ldM pads the total to a multiple of 32.
 struct BwdPlan {
-  size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, ct, adj, phi, partial, dlog32, total;
+  size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, Gpart, ct, adj, phi, partial, dlog32, total;
   int ksplit, kchunk;       // split of the dh contraction over K (few output tiles)
   bool keep_phi;            // probabilities kept by the forward pass (else the logits are recomputed)
   bool ctx;                 // layers computed from h, one set per position
@@ -555,6 +555,9 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
       q.pi = take(B * q.steps * r * 4);
       q.gam = take(B * q.steps * r * 4);
       q.G = take((size_t)q.Lst * r * r * 4);
+      q.Gpart = take(((B + LAYER_GRAD_ROWS - 1) / LAYER_GRAD_ROWS) * (size_t)q.steps * r * r * 4);
+    } else if (q.ctx) {                        // bias gradient: column sums per block of rows
+      q.Gpart = take(((B + LAYER_GRAD_ROWS - 1) / LAYER_GRAD_ROWS) * (size_t)q.Lst * r * r * 4);
     }
   }
   if (family == MTPC_BTREE) {
@@ -660,11 +663,13 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
       c.contextual = 1;
       c.dlog = ws + q.dL + (size_t)q.Mlay * esz; c.ld_dlog = q.ldM; c.dlog_cols = (int)(q.ldM - q.Mlay);
       if (q.dlog32) c.dlog32 = (float*)(ws + q.dlog32);
+      c.Gpart = (float*)(ws + q.Gpart);
     } else if (q.perpos) {
       // the caller's [B][Lst][r][r] gradient buffer is the accumulator itself
       c.contextual = 1; c.dlog = nullptr; c.dlog32 = dlayers; c.dlayers = nullptr;
     } else {
       c.pi = (float*)(ws + q.pi); c.gam = (float*)(ws + q.gam); c.G = (float*)(ws + q.G);
+      c.Gpart = (float*)(ws + q.Gpart);
     }
   }
   if (family == MTPC_BTREE) {

@@ -538,24 +538,15 @@ __global__ __launch_bounds__(256) void k_btree_bwd(const CircuitBwdArgs a, int n
   if (lane == 0) a.loss[row] = loss;
 }
 
-// G[l][z][z'] += sum over a block of rows of pi[b][j][z] * gam[b][j][z'], l = j (or 0 for a
-// shared layer).  Thread t owns outputs t, t + 256, ...: NO of them.
-// In tree mode (tree_n > 0) step j applies the layer of node prog[j].m (root steps: none).
+// part[by][j][z][z'] = sum over the rows of block by of pi[b][j][z] * gam[b][j][z'] for step j.
+// Thread t owns outputs t, t + 256, ...: NO of them.  Nothing is accumulated across workgroups
+// here: k_layer_reduce adds the partial tiles in a fixed order, so that the layer gradients are
+// the same bits on every run.
 template <int NO>
 __global__ __launch_bounds__(256) void k_layer_outer(const float* pi, const float* gam, int rows, int steps,
-                                                     int r, int L, int rows_per_block, float* G, int tree_n) {
-  extern __shared__ TreeStep oprog[];
+                                                     int r, int rows_per_block, float* part) {
   __shared__ float sp[16][128], sg[16][128];
   const int j = blockIdx.x, tid = threadIdx.x;
-  int layer = j;
-  if (tree_n > 0) {
-    __shared__ int s_cnt;
-    if (tid == 0) s_cnt = build_tree_program(oprog, tree_n, 1);
-    __syncthreads();
-    if (j >= s_cnt) return;                 // the grid is sized by an upper bound of the program length
-    layer = oprog[j].m - 1;
-    if (layer < 0) return;
-  }
   const long long b0 = (long long)blockIdx.y * rows_per_block;
   const long long b1 = min((long long)rows, b0 + rows_per_block);
   float acc[NO];
@@ -583,12 +574,39 @@ __global__ __launch_bounds__(256) void k_layer_outer(const float* pi, const floa
       }
     }
   }
-  float* dst = G + (L > 1 ? (long long)layer * r * r : 0);
+  float* dst = part + ((long long)blockIdx.y * steps + j) * r * r;
 #pragma unroll
   for (int q = 0; q < NO; ++q) {
     const int o = tid + q * 256;
-    if (o < r * r) atomicAdd(dst + o, acc[q]);
+    if (o < r * r) dst[o] = acc[q];
   }
+}
+
+// G[l][o] = sum over the steps j that apply layer l (ascending), and for each over the row blocks
+// (ascending), of part[by][j][o].  HMM: step j applies layer j (layer 0 when one matrix is shared).
+// Tree mode (tree_n > 0): step j applies the layer of node prog[j].m (root steps: none).
+__global__ __launch_bounds__(256) void k_layer_reduce(const float* part, int steps, int nby, int r, int L,
+                                                      float* G, int tree_n) {
+  extern __shared__ TreeStep oprog[];
+  __shared__ int s_cnt;
+  const int rr = r * r;
+  if (tree_n > 0) {
+    if (threadIdx.x == 0) s_cnt = build_tree_program(oprog, tree_n, 1);
+    __syncthreads();
+  }
+  const int nsteps = tree_n > 0 ? s_cnt : steps;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)L * rr) return;
+  const int l = (int)(idx / rr), o = (int)(idx - (long long)l * rr);
+  float s = 0.f;
+  for (int j = 0; j < nsteps; ++j) {
+    int layer = tree_n > 0 ? oprog[j].m - 1 : j;
+    if (layer < 0) continue;
+    if (L == 1) layer = 0;
+    if (layer != l) continue;
+    for (int by = 0; by < nby; ++by) s += part[((long long)by * steps + j) * rr + o];
+  }
+  G[idx] = s;
 }
 
 // softmax backward of every layer row: dlogit[l][z][:] = T (.) (G - sum_z' T G); one wave per row
@@ -605,10 +623,11 @@ __global__ __launch_bounds__(256) void k_layer_finish(const float* G, const floa
   if (u1) dlayers[row * r + lane + 64] = t1 * (g1 - s);
 }
 
-// out[c] += sum_b src[b][c] over a block of rows (src in the dtype of h, out fp32)
+// part[by][c] = sum_b src[b][c] over the rows of block by (src in the dtype of h, fp32 sums);
+// k_colsum_reduce adds the blocks in ascending order (no atomics: the same bits on every run)
 template <typename T>
-__global__ __launch_bounds__(256) void k_colsum(const T* src, long long ld, int rows, int cols, float* out) {
-  __shared__ float part[4][64];
+__global__ __launch_bounds__(256) void k_colsum(const T* src, long long ld, int rows, int cols, float* part) {
+  __shared__ float red[4][64];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63), ty = threadIdx.x >> 6;
   const int b0 = blockIdx.y * 256;
   float s = 0.f;
@@ -617,10 +636,19 @@ __global__ __launch_bounds__(256) void k_colsum(const T* src, long long ld, int 
       if constexpr (sizeof(T) == 2) s += __uint_as_float(((unsigned)src[(long long)b * ld + c]) << 16);
       else s += src[(long long)b * ld + c];
     }
-  part[ty][threadIdx.x & 63] = s;
+  red[ty][threadIdx.x & 63] = s;
   __syncthreads();
   if (ty == 0 && c < cols)
-    atomicAdd(out + c, (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]));
+    part[(long long)blockIdx.y * cols + c] =
+        (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+__global__ __launch_bounds__(256) void k_colsum_reduce(const float* part, int nby, int cols, float* out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= cols) return;
+  float s = 0.f;
+  for (int by = 0; by < nby; ++by) s += part[(long long)by * cols + c];
+  out[c] = s;
 }
 
 // dst[b][c] (dtype of h, row stride ld) = src[b][c] for c < cols, 0 for cols <= c < cols_pad
@@ -673,29 +701,24 @@ hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
   const size_t prog_bytes = tree ? (size_t)T * sizeof(TreeStep) : 0;
   const bool ctx = a.contextual && a.dlog != nullptr;        // layers computed from h (R): bias gradient = column sums
   const bool layers = !a.contextual && a.dlayers != nullptr && ((a.family == MTPC_HMM && a.n > 1) || (tree && a.n > 2));
-  if (ctx && a.dlayers != nullptr) {               // bias gradient = column sums of the logit gradients
-    const long long cnt = (long long)a.L * r * r;
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.dlayers, cnt);
-  }
   if (a.contextual && a.dlog32 != nullptr) {       // per-position fp32 accumulators
     const long long cnt = (long long)a.rows * a.L * r * r;
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.dlog32, cnt);
   }
-  if (layers) {
-    const long long cnt = (long long)a.L * r * r;
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, a.G, cnt);
-  }
   if (tree) hipLaunchKernelGGL(k_btree_bwd, dim3((unsigned)((rows + 3) / 4)), dim3(256), prog_bytes, st, a, T);
   else hipLaunchKernelGGL(k_circuit_bwd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, a);
   if (layers) {
-    const int steps = T, rpb = 256;
-    const int tn = tree ? a.n : 0;
-    const dim3 grid(steps, (unsigned)((a.rows + rpb - 1) / rpb));
+    const int steps = T, rpb = LAYER_GRAD_ROWS;
+    const int nby = (a.rows + rpb - 1) / rpb;
+    const dim3 grid(steps, (unsigned)nby);
     const int no = (r * r + 255) / 256;
-    if (no <= 1) hipLaunchKernelGGL(k_layer_outer<1>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
-    else if (no <= 4) hipLaunchKernelGGL(k_layer_outer<4>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
-    else if (no <= 16) hipLaunchKernelGGL(k_layer_outer<16>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
-    else hipLaunchKernelGGL(k_layer_outer<64>, grid, dim3(256), prog_bytes, st, a.pi, a.gam, a.rows, steps, r, a.L, rpb, a.G, tn);
+    if (no <= 1) hipLaunchKernelGGL(k_layer_outer<1>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, rpb, a.Gpart);
+    else if (no <= 4) hipLaunchKernelGGL(k_layer_outer<4>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, rpb, a.Gpart);
+    else if (no <= 16) hipLaunchKernelGGL(k_layer_outer<16>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, rpb, a.Gpart);
+    else hipLaunchKernelGGL(k_layer_outer<64>, grid, dim3(256), 0, st, a.pi, a.gam, a.rows, steps, r, rpb, a.Gpart);
+    const long long cnt = (long long)a.L * r * r;
+    hipLaunchKernelGGL(k_layer_reduce, dim3((unsigned)((cnt + 255) / 256)), dim3(256), prog_bytes, st, a.Gpart, steps, nby,
+                       r, a.L, a.G, tree ? a.n : 0);
     const int nrows = a.L * r;
     hipLaunchKernelGGL(k_layer_finish, dim3((nrows + 3) / 4), dim3(256), 0, st, a.G, a.lay_nat, nrows, r, a.dlayers);
   }
@@ -708,13 +731,15 @@ hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st) {
     else hipLaunchKernelGGL(k_convert_block<float>, g, dim3(256), 0, st, a.dlog32, a.rows, cols, a.dlog_cols,
                             (float*)a.dlog, a.ld_dlog);
   }
-  if (ctx && a.dlayers != nullptr) {
+  if (ctx && a.dlayers != nullptr) {               // bias gradient = column sums of the logit gradients
     const int cols = a.L * r * r;
-    const dim3 grid((cols + 63) / 64, (a.rows + 255) / 256);
+    const int nby = (a.rows + LAYER_GRAD_ROWS - 1) / LAYER_GRAD_ROWS;
+    const dim3 grid((cols + 63) / 64, nby);
     if (a.bf16) hipLaunchKernelGGL(k_colsum<unsigned short>, grid, dim3(256), 0, st, (const unsigned short*)a.dlog,
-                                   a.ld_dlog, a.rows, cols, a.dlayers);
+                                   a.ld_dlog, a.rows, cols, a.Gpart);
     else hipLaunchKernelGGL(k_colsum<float>, grid, dim3(256), 0, st, (const float*)a.dlog, a.ld_dlog, a.rows, cols,
-                            a.dlayers);
+                            a.Gpart);
+    hipLaunchKernelGGL(k_colsum_reduce, dim3((cols + 255) / 256), dim3(256), 0, st, a.Gpart, nby, cols, a.dlayers);
   }
   return hipGetLastError();
 }

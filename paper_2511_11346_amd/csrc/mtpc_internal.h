@@ -273,6 +273,8 @@ struct CircuitBwdArgs {
   float* pi;             // scratch [rows][steps][r] (layer gradients only; steps = n-1 for the HMM)
   float* gam;            // scratch [rows][steps][r]
   float* G;              // scratch [L][r][r]
+  float* Gpart;          // scratch: per block of LAYER_GRAD_ROWS rows, [steps][r][r] outer-product partials
+                         // (shared layers) or [L*r*r] column sums (bias gradient of layers computed from h)
   // layers of every position (computed from h): lay_nat / lay_tr hold [rows][L][r][r] and the
   // gradient w.r.t. the logits of position b goes to dlog[b*ld_dlog + (l*r + z)*r + z'] in the
   // dtype of h (dlog_cols columns, zero beyond L*r*r); dlayers then receives the column sums
@@ -290,6 +292,7 @@ struct CircuitBwdArgs {
   float* dlayers;        // [L][r][r] gradient w.r.t. the layer logits (accumulated), or nullptr
 };
 hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t st);
+constexpr int LAYER_GRAD_ROWS = 256;   // rows whose contribution to a layer gradient one workgroup sums
 
 // Raises a kernel's dynamic-LDS limit the first time the kernel is launched on a device.  This
 // is the library's only process-wide state: one bit per kernel and device, set once the call

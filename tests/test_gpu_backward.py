@@ -134,3 +134,27 @@ def test_strided_hidden_states_and_preallocated_outputs():
     again = head.loss_backward(tg, cf, out=out)
     assert torch.equal(again["dW"], ref["dW"])
 
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r,v", [
+    ("hmm-shared", "bf16", 1500, 128, 8, 32, 320),     # one matrix applied by 7 steps, 6 blocks of rows
+    ("hmm", "f32", 700, 64, 5, 16, 100),
+    ("hmm-ctx", "bf16", 700, 128, 4, 16, 130),         # layers R h + bias: bias gradient = column sums
+    ("btree", "bf16", 900, 64, 8, 32, 200),            # a node's layer is applied by several program steps
+    ("btree-ctx", "f32", 300, 64, 4, 8, 64),
+    ("cp", "bf16", 600, 128, 4, 16, 320),
+])
+def test_training_step_is_bit_reproducible(family, dtype, B, d, n, r, v):
+    """The same inputs twice give the same bits in every output: sums over positions (layer and
+    bias gradients, split-K partials) are taken in a fixed order, no float atomics."""
+    inp, targets, coef = make_case(family, dtype, B, d, n, r, v, seed=77)
+    head = make_head(inp)
+    tg = torch.from_numpy(targets).cuda()
+    cf = torch.from_numpy(coef.astype(np.float32)).cuda()
+    for recompute in (False, True):
+        first = {k: (None if t is None else t.clone()) for k, t in head.loss_backward(tg, cf, recompute=recompute).items()}
+        for _ in range(3):
+            again = head.loss_backward(tg, cf, recompute=recompute)
+            for k, t in first.items():
+                if t is not None:
+                    assert torch.equal(t, again[k]), (k, recompute)
