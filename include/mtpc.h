@@ -307,7 +307,9 @@ mtpc_status mtpc_btree_verify(const mtpc_head* head, const mtpc_sumlayers* A, co
  * step / inner node, contiguous, or both shared by all of them): dR [L or 1][r][r][d]
  * receives the gradient w.r.t. R, dlayers the one w.r.t. the bias (may be NULL when
  * there is no bias), and dh includes the path through the layers; otherwise dR is
- * ignored and may be NULL.  Other stride combinations: MTPC_ERR_UNSUPPORTED. */
+ * ignored and may be NULL.  Other stride combinations: MTPC_ERR_UNSUPPORTED.
+ * Size limit of this call alone: a row of the logit gradient, n r v + r (+ L r r with R)
+ * entries, and B, each at most 1,677,696 (beyond: MTPC_ERR_UNSUPPORTED). */
 mtpc_status mtpc_ff_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,
                                   float* loss, float* dh, float* dW);
 mtpc_status mtpc_cp_loss_backward(const mtpc_head* head, const int32_t* targets, const float* coef,

@@ -201,21 +201,6 @@ __global__ __launch_bounds__(256) void k_reduce_splits(const float* partial, lon
   *(f32x4_t*)(C + i) = s;
 }
 
-int gemm_ksplit(int M, int N, int K) {
-  const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-  if (tiles >= 384) return 1;
-  const int cand[] = {1, 2, 3, 4, 6, 8, 12, 16};
-  int best = 1;
-  double best_cost = 1e30;
-  for (int ks : cand) {
-    if (ks > 1 && K / ks < 2048) break;
-    // rounds over the CUs, each 1/ks long, plus a little for writing and adding the partials
-    const double cost = (double)((tiles * ks + 255) / 256) / ks + 0.02 * ks;
-    if (cost < best_cost - 1e-9) { best_cost = cost; best = ks; }
-  }
-  return best;
-}
-
 template <bool BF16>
 static hipError_t launch_gemm_dt(const GemmArgs& a, hipStream_t st) {
   // 320 x 256 workgroup tiles (the forward kernel's shape; measured 7 % faster per output

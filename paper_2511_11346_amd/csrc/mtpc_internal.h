@@ -250,7 +250,20 @@ struct GemmArgs {
 };
 hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t st);
 // number of K splits that fills the 256 CUs best for an M x N output (1: none)
-int gemm_ksplit(int M, int N, int K);
+inline int gemm_ksplit(int M, int N, int K) {
+  const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+  if (tiles >= 384) return 1;
+  const int cand[] = {1, 2, 3, 4, 6, 8, 12, 16};
+  int best = 1;
+  double best_cost = 1e30;
+  for (int ks : cand) {
+    if (ks > 1 && K / ks < 2048) break;
+    // rounds over the CUs, each 1/ks long, plus a little for writing and adding the partials
+    const double cost = (double)((tiles * ks + 255) / 256) / ks + 0.02 * ks;
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = ks; }
+  }
+  return best;
+}
 
 // dst[c][col0 + r] = src[r][c] for r < R, c < C; dst[c][col0 + r] = 0 for R <= r < Rpad.
 struct TransposeArgs {
