@@ -72,6 +72,7 @@ struct Plan {           // byte offsets into the workspace
   size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_tilebucket, bk_list;
   size_t rowlogits;     // compact table of the few-drafts path   // buckets of the token draws (large batches)
   int nb, Lst;          // position blocks and stored layers of the normalised copies
+  bool has_nat;         // the natural-layout copy of the layers has a place of its own
   bool has_table;       // room for the table of input units (sampling with scores, see decode_sized;
                         // univariate marginals of a head with sum units whose table is at most 8 GiB)
 };
@@ -135,8 +136,10 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   const bool uni = op == MTPC_OP_MARGINALS && mode == MTPC_MARG_UNIVARIATE;
   const bool verify = op == MTPC_OP_VERIFY;
   const bool table_op = op == MTPC_OP_TABLE || op == MTPC_OP_WINDOWS;   // S windows per position
-  const bool need_nat = L > 0 && (family == MTPC_HMM || sample || uni || verify);
+  // (the tree's matrix-pipe circuit kernel reads shared layers in natural layout)
+  const bool need_nat = L > 0 && (family == MTPC_HMM || sample || uni || verify || (family == MTPC_BTREE && !ctx && p.nb == 1));
   const bool need_tr = L > 0 && family == MTPC_BTREE && (!sample || want_prefix) && !uni;
+  p.has_nat = need_nat;
   p.lay_nat = need_nat ? take(lay_bytes) : 0;
   p.lay_circ = need_tr ? take(lay_bytes) : p.lay_nat;
   const size_t rows = (sample || table_op) ? B * (size_t)S : B;
@@ -216,6 +219,7 @@ UnembedArgs unembed_args(const mtpc_head* hd) {
 mtpc_status launch_params(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const Plan& p,
                           bool nat, bool circ, hipStream_t st) {
   char* ws = (char*)hd->workspace;
+  nat = nat && p.has_nat;
   if (family != MTPC_FF)
     HIP_TRY(launch_sumunit(hd->h, hd->ld_h, hd->Wsum, hd->B, hd->d, hd->r, hd->dtype,
                            (float*)(ws + p.logw), st));
@@ -246,6 +250,7 @@ CircuitArgs circuit_args(int family, const mtpc_head* hd, const Plan& p, int row
   c.e = (const float*)(ws + p.e);
   c.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
   c.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_circ) : nullptr;
+  c.layers_nat = (c.layers && family == MTPC_BTREE && p.nb == 1 && p.has_nat) ? (const float*)(ws + p.lay_nat) : nullptr;
   c.L = p.Lst; c.contextual = p.nb > 1; c.out = out; c.prefix = prefix;
   return c;
 }
@@ -260,7 +265,7 @@ mtpc_status run_evidence_op(int family, const mtpc_head* hd, const mtpc_sumlayer
   if (s != MTPC_OK) return s;
   hipStream_t st = (hipStream_t)hd->stream;
   char* ws = (char*)hd->workspace;
-  s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
+  s = launch_params(family, hd, ly, p, family != MTPC_FF && family != MTPC_CP, true, st);
   if (s != MTPC_OK) return s;
   UnembedArgs u = unembed_args(hd);
   u.targets = targets; u.T = 1; u.e = (float*)(ws + p.e);
@@ -443,7 +448,7 @@ mtpc_status run_window_scores(int family, const mtpc_head* hd, const mtpc_sumlay
   if (s != MTPC_OK) return s;
   hipStream_t st = (hipStream_t)hd->stream;
   char* ws = (char*)hd->workspace;
-  s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
+  s = launch_params(family, hd, ly, p, family != MTPC_FF && family != MTPC_CP, true, st);
   if (s != MTPC_OK) return s;
   UnembedArgs u = unembed_args(hd);
   u.targets = x; u.T = T; u.targets2 = x2; u.T2 = T2; u.e = (float*)(ws + p.e);
@@ -467,7 +472,7 @@ mtpc_status run_table_scores(int family, const mtpc_head* hd, const mtpc_sumlaye
   if ((long long)hd->B * T > 0x7fffffffLL / hd->n) return MTPC_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)hd->stream;
   char* ws = (char*)hd->workspace;
-  s = launch_params(family, hd, ly, p, family == MTPC_HMM, true, st);
+  s = launch_params(family, hd, ly, p, family != MTPC_FF && family != MTPC_CP, true, st);
   if (s != MTPC_OK) return s;
   GatherArgs g{};
   g.B = hd->B; g.S = T; g.v = hd->v; g.n = hd->n; g.r = hd->r;

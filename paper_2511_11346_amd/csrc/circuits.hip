@@ -7,6 +7,7 @@
 namespace mtpc {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 __device__ __forceinline__ float wave_sum(float x) { return group_sum(x, 64); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
@@ -644,6 +645,172 @@ __global__ __launch_bounds__(256) void k_btree_static(const CircuitArgs a, int G
   }
 }
 
+// ---------------------------------------------------------------------------
+// Binary tree with layers shared by all rows and r = 16, 32 or 64 units: the sum layers on the
+// matrix pipe.  A sum layer applied to many rows is the product  S[k][row] = sum_j A[k][j] X[j][row]
+// with X = exp(children's values - their row maximum) (Eq. BTree in the linear domain after a max
+// shift); one wave owns 16 rows and walks the same step program as k_btree_static with
+// v_mfma_f32_16x16x4_f32 (fp32 operands and accumulation).  Lane (row = l % 16, g = l / 16) holds,
+// of its row, the units j = 16 b + 4 g + i (b < R / 16, i < 4): that is at once the B-operand
+// layout of the product (k-index g), the layout its result comes back in (rows 4 g + i of output
+// block b) and four contiguous floats per block in memory - so a value is written to LDS and read
+// back by the same lane, the path value of a prefix walk never leaves registers, and the wave needs
+// no barrier.  The layer of the next step (natural layout A[k][j], 16-byte loads) and the next
+// step's leaf evidence are fetched while the current step multiplies.
+// LDS: (n-1) node values x 16 rows x (R + 4) floats, and the program.
+// ---------------------------------------------------------------------------
+template <int R>
+__global__ __launch_bounds__(64) void k_btree_mfma(const CircuitArgs a) {
+  constexpr int NB = R / 16;        // blocks of 16 units
+  constexpr int RS = R + 4;         // row stride of a stored node value (floats; 16-byte aligned rows)
+  extern __shared__ __align__(16) float msm[];
+  const int n = a.n;
+  const int lane = threadIdx.x, rl = lane & 15, g = lane >> 4;
+  float* nodes = msm;                                   // [n-1][16][RS]
+  TreeStep* prog = (TreeStep*)(msm + (size_t)(n - 1) * 16 * RS);
+  __shared__ int s_nsteps;
+  if (lane == 0) s_nsteps = build_tree_program(prog, n, a.prefix);
+  __syncthreads();
+  const int nsteps = s_nsteps;
+  const long long row = (long long)blockIdx.x * 16 + rl;
+  const long long rc = row < a.rows ? row : (long long)a.rows - 1;       // clamped: loads stay in bounds
+  const float* e = a.e + rc * n * R + 4 * g;
+  const float* lay = a.layers_nat + (size_t)rl * R + 4 * g;
+  const size_t lstep = a.L > 1 ? (size_t)R * R : 0;
+  float* mine = nodes + (size_t)rl * RS + 4 * g;
+  const float ninf = neg_inf();
+
+  f32x4_t lw[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) lw[b] = *(const f32x4_t*)(a.logw + (rc / a.T) * R + 16 * b + 4 * g);
+
+  // operands and layer of the step after the current one
+  f32x4_t nxl[NB], nxr[NB], An[NB][NB];
+  auto prefetch = [&](int t) {
+    if (t >= nsteps) return;
+    const TreeStep s = prog[t];
+    if (s.lsrc >= n - 1) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) nxl[b] = *(const f32x4_t*)(e + (size_t)(s.lsrc - (n - 1)) * R + 16 * b);
+    }
+    if (s.rsrc >= n - 1) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) nxr[b] = *(const f32x4_t*)(e + (size_t)(s.rsrc - (n - 1)) * R + 16 * b);
+    }
+    if (s.m > 0) {
+      const float* A = lay + (size_t)(s.m - 1) * lstep;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int b2 = 0; b2 < NB; ++b2) An[b][b2] = *(const f32x4_t*)(A + (size_t)16 * b * R + 16 * b2);
+    }
+  };
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    nxl[b] = nxr[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int b2 = 0; b2 < NB; ++b2) An[b][b2] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+  prefetch(0);
+
+  f32x4_t pv[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) pv[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  // the values the lanes that share a row hold are combined over g (lanes l, l ^ 16, l ^ 32, l ^ 48)
+  auto row_max = [](float x) { x = fmaxf(x, __shfl_xor(x, 16)); return fmaxf(x, __shfl_xor(x, 32)); };
+  auto row_sum = [](float x) { x += __shfl_xor(x, 16); return x + __shfl_xor(x, 32); };
+
+  for (int t = 0; t < nsteps; ++t) {
+    const TreeStep st = prog[t];
+    f32x4_t c[NB], Ac[NB][NB];
+    {
+      f32x4_t lv[NB], rv[NB];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        if (st.lsrc == -1) lv[b] = pv[b];
+        else if (st.lsrc == -2) lv[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        else if (st.lsrc >= n - 1) lv[b] = nxl[b];
+        else lv[b] = *(const f32x4_t*)(mine + (size_t)st.lsrc * 16 * RS + 16 * b);
+        if (st.rsrc == -1) rv[b] = pv[b];
+        else if (st.rsrc == -2) rv[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        else if (st.rsrc >= n - 1) rv[b] = nxr[b];
+        else rv[b] = *(const f32x4_t*)(mine + (size_t)st.rsrc * 16 * RS + 16 * b);
+        c[b] = lv[b] + rv[b];
+      }
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int b2 = 0; b2 < NB; ++b2) Ac[b][b2] = An[b][b2];
+    }
+    prefetch(t + 1);
+    if (st.m == 0) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) c[b] += lw[b];
+    }
+    float m = ninf;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) m = fmaxf(m, c[b][i]);
+    m = row_max(m);
+    const float ms = (m == ninf) ? 0.f : m;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) c[b][i] = __expf(c[b][i] - ms);        // exp(-inf) = 0; NaN stays NaN
+    if (st.m == 0) {             // root: mixture with log omega
+      float sum = 0.f;
+#pragma unroll
+      for (int b = 0; b < NB; ++b) sum += (c[b][0] + c[b][1]) + (c[b][2] + c[b][3]);
+      sum = row_sum(sum);
+      const float v = ms + __logf(sum);                                  // log 0 = -inf
+      if (g == 0 && row < a.rows) {
+        if (a.prefix) a.out[row * n + (-2 - st.out)] = v; else a.out[row] = v;
+      }
+      continue;
+    }
+    f32x4_t S[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      S[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int b2 = 0; b2 < NB; ++b2)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) S[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(Ac[b][b2][i], c[b2][i], S[b], 0, 0, 0);
+    }
+    f32x4_t res[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) res[b][i] = ms + __logf(S[b][i]);
+    if (st.out >= 0) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) *(f32x4_t*)(mine + (size_t)st.out * 16 * RS + 16 * b) = res[b];
+    } else {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) pv[b] = res[b];
+    }
+  }
+}
+
+static size_t btree_mfma_smem(const CircuitArgs& a) {
+  if (a.layers_nat == nullptr || (a.r != 16 && a.r != 32 && a.r != 64)) return 0;
+  return (size_t)(a.n - 1) * 16 * (a.r + 4) * 4 + (size_t)tree_program_steps(a.n, a.prefix) * sizeof(TreeStep);
+}
+
+template <int R>
+static hipError_t launch_btree_mfma_r(const CircuitArgs& a, size_t smem, hipStream_t st) {
+  if (hipError_t e = allow_lds<k_btree_mfma<R>>(150 * 1024); e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_btree_mfma<R>, dim3((unsigned)((a.rows + 15) / 16)), dim3(64), smem, st, a);
+  return hipGetLastError();
+}
+
+static hipError_t launch_btree_mfma(const CircuitArgs& a, size_t smem, hipStream_t st) {
+  if (a.r == 64) return launch_btree_mfma_r<64>(a, smem, st);
+  if (a.r == 32) return launch_btree_mfma_r<32>(a, smem, st);
+  return launch_btree_mfma_r<16>(a, smem, st);
+}
+
 // rows per group of the program-driven tree kernel: 4 when that still gives every CU
 // two workgroups, else 2 (twice the workgroups, half the LDS each)
 static int btree_static_rb(const CircuitArgs& a) {
@@ -853,6 +1020,8 @@ hipError_t launch_circuit(const CircuitArgs& a, hipStream_t st) {
   // (measured: the tree's many dependent node evaluations gain from sharing weight
   // loads; the HMM chain prefers more, narrower groups)
   if (a.family == MTPC_BTREE && !a.contextual && a.n > 2 && a.rows >= 256) {
+    const size_t mfma = btree_mfma_smem(a);
+    if (mfma != 0 && mfma <= 150 * 1024) return launch_btree_mfma(a, mfma, st);
     const size_t need = btree_static_smem(a);
     if (need != 0 && need <= 150 * 1024) return launch_btree_static(a, st);
   }

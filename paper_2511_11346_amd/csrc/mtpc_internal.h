@@ -93,6 +93,7 @@ struct CircuitArgs {
   const float* e;       // [rows][n][r]
   const float* logw;    // [B][r] (nullptr for FF)
   const float* layers;  // normalised linear probabilities, HMM: [nb][L][j][j'], BTree: [nb][L][j][k] (transposed)
+  const float* layers_nat;  // BTree with shared layers: the same in natural layout [L][k][j], or nullptr
   int L;                // number of stored layers (1 = homogeneous)
   int contextual;       // 1: layers has a leading position axis
   float* out;           // prefix ? [rows][n] : [rows]

@@ -105,6 +105,7 @@ hipError_t launch_circuit(const CircuitArgs& a, hipStream_t) {
   need(a.e, (u64)a.rows * a.n * a.r * 4, "circuit e");
   if (a.family != MTPC_FF) need(a.logw, pos * a.r * 4, "circuit logw");
   if (a.layers) need(a.layers, (a.contextual ? pos : 1) * (u64)a.L * a.r * a.r * 4, "circuit layers");
+  if (a.layers_nat) need(a.layers_nat, (u64)a.L * a.r * a.r * 4, "circuit layers (natural layout)");
   need(a.out, (u64)a.rows * (a.prefix ? a.n : 1) * 4, "circuit out");
   return ok();
 }

@@ -250,3 +250,35 @@ def test_sum_layers_computed_from_the_hidden_state(family, dtype, B, d, n, r):
     _, _, ll2 = oc._params(family, inp.h, inp.W, inp.Wsum, lay2)
     tol_check(head2.loglik(tg).cpu().numpy(), oc.joint(family, oc.evidence(logphi, inp.targets), logw, ll2),
               dtype, "loglik, shared R")
+
+
+@pytest.mark.parametrize("dtype,B,d,n,r,v", [
+    ("f32", 300, 64, 8, 64, 40), ("bf16", 277, 64, 16, 32, 100), ("f32", 513, 32, 4, 16, 33),
+    ("bf16", 1000, 32, 32, 16, 20), ("f32", 256, 32, 16, 64, 7),
+])
+def test_tree_layers_shared_by_all_rows_with_16_32_64_units(dtype, B, d, n, r, v):
+    """Batches of at least 256 rows of a tree whose layers are shared and whose r is 16, 32 or 64
+    evaluate their sum layers as matrix products (16 rows per wave): ragged row counts, layers
+    with forbidden and deterministic transitions, summed-out and invalid targets, one and two
+    windows per position."""
+    inp = mi.make_inputs("btree", B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=90 + n + r, h_scale=1.0)
+    lay = np.array(inp.layers, copy=True)
+    lay[:, :, 2] = -np.inf                      # unit 2 of every inner node can never be entered
+    lay[1, 3, :] = -np.inf
+    lay[1, 3, 5] = 0.0                          # a deterministic row
+    tg = np.array(inp.targets, copy=True)
+    rng = np.random.default_rng(5)
+    tg[rng.random(tg.shape) < 0.1] = -1
+    tg[7, n // 2] = v + 3                       # an id outside the vocabulary: NaN from there on
+    tg[B - 1, 0] = -5
+    head = make_head(inp, layers=lay)
+    logphi, logw, loglayers = oracle_all(inp, layers=lay)
+    want = oc.prefix_marginals_from("btree", logphi, logw, loglayers, tg)
+    assert np.isnan(want[7, n // 2:]).all() and not np.isnan(want[7, :n // 2]).any()
+    tgd = torch.from_numpy(tg).cuda()
+    tol_check(head.prefix_marginals(tgd).cpu().numpy(), want, dtype, "prefix marginals")
+    tol_check(head.loglik(tgd).cpu().numpy(), want[:, -1], dtype, "loglik")
+    other = np.array(inp.targets[::-1], copy=True)
+    both = head.window_scores(tgd.view(B, 1, n), torch.from_numpy(other).cuda().view(B, 1, n), prefix=True).cpu().numpy()
+    tol_check(both[:, 0], want, dtype, "first window of two")
+    tol_check(both[:, 1], oc.prefix_marginals_from("btree", logphi, logw, loglayers, other), dtype, "second window of two")
