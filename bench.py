@@ -158,16 +158,21 @@ def main():
         return Head(inp.family, h, W, Ws, lay)
 
     def time_op(fn, reps=10):
-        fn(); torch.cuda.synchronize()
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
         t = time.perf_counter()
         for _ in range(reps):
             fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / reps
 
-    def kernel_ms(fn, hook, reps=10):
-        """Mean duration of the kernel `hook` brackets inside `fn`, by HIP events."""
-        fn(); torch.cuda.synchronize()
+    def kernel_ms(fn, hook, reps=10, warm=10):
+        """Mean duration of the kernel `hook` brackets inside `fn`, by HIP events (after enough
+        calls for the clocks to settle: the first launches after an idle spell run slower)."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
         prs = ev.pairs(reps)
         for a, b in prs:
             hook(a, b)
