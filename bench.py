@@ -393,6 +393,21 @@ def main():
             hd.sample(1, seed=0, offset=k, out=o)
             profile_unembed(None, None)
         torch.cuda.synchronize()
+        call_ms_rows = (time.perf_counter() - t) * 1e3 / reps
+        kms_rows = ev.mean_ms(prs)
+        # serving keeps W fixed: from here on the pass streams the stage-major copy of W
+        # (mtpc_pack_weights; same results bit for bit), the figures above are for W's own rows
+        hd.pack_W()
+        for k in range(3):
+            hd.sample(1, seed=0, offset=k, out=o)
+        torch.cuda.synchronize()
+        prs = ev.pairs(reps)
+        t = time.perf_counter()
+        for k in range(reps):
+            profile_unembed(prs[k][0], prs[k][1])
+            hd.sample(1, seed=0, offset=k, out=o)
+            profile_unembed(None, None)
+        torch.cuda.synchronize()
         call_ms = (time.perf_counter() - t) * 1e3 / reps
         kms = ev.mean_ms(prs)
         # W streamed once, h, and the table of input units the sampling pass writes
@@ -467,6 +482,9 @@ def main():
         dec.append({"B": Bd, "call_ms": call_ms, "drafts_per_s": Bd / (call_ms * 1e-3),
                     "k_unembed_ms": kms, "algorithmic_bytes": byts, "achieved_GBps": byts / (kms * 1e-3) / 1e9,
                     "frac_of_hbm_peak": byts / (kms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                    "W_layout": "stage-major copy (mtpc_pack_weights)",
+                    "row_major_W": {"call_ms": call_ms_rows, "k_unembed_ms": kms_rows,
+                                    "frac_of_hbm_peak": byts / (kms_rows * 1e-3) / 1e9 / PEAK_HBM_GBPS},
                     "call_ms_keeping_table": ms_table, "verify_call_ms": ms_verify,
                     "cycle_ms_from_graph": ms_graph, "score_16_prefixes_per_draft_ms": ms_16,
                     "mean_accepted": float(acc.float().mean()),

@@ -72,6 +72,12 @@ typedef struct {
   void* workspace;        /* device scratch, >= mtpc_workspace_bytes(...)                 */
   size_t workspace_bytes;
   void* stream;           /* hipStream_t                                                  */
+  const void* W_stage_major; /* optional (NULL: none): the copy of W that mtpc_pack_weights makes.   */
+                          /* Decode-sized calls (B <= 64) of mtpc_*_sample / *_greedy_draft /  */
+                          /* *_loglik / *_marginals / *_window_scores whose rows of W are a     */
+                          /* multiple of 128 bytes stream it instead of W (same results, bit    */
+                          /* for bit; 3-5 % less time on the HBM-bound pass).  W must be valid  */
+                          /* as well: every other path reads W.                                 */
 } mtpc_head;
 
 /* r x r sum layers, normalised over the LAST axis (softmax), given either as
@@ -320,6 +326,16 @@ mtpc_status mtpc_hmm_loss_backward(const mtpc_head* head, const mtpc_sumlayers* 
 mtpc_status mtpc_btree_loss_backward(const mtpc_head* head, const mtpc_sumlayers* A,
                                      const int32_t* targets, const float* coef, float* loss, float* dh,
                                      float* dW, float* dWsum, float* dlayers, float* dR);
+
+/* Stage-major copy of W for serving (W fixed between calls): per (i, j) slab, the 128 bytes
+ * that each of the v rows contributes to a step along d lie back to back,
+ *   W_stage_major [n*r][d * esz / 128][v][128 bytes]      (esz = 2 or 4 by head->dtype),
+ * so the pass that streams W once (Sec. 3.3: all input units of a handful of positions, bound
+ * by the bytes of W) reads long contiguous runs instead of 128 bytes from each of v rows d
+ * elements apart.  Needs d * esz to be a multiple of 128 (else MTPC_ERR_UNSUPPORTED); uses
+ * head's B, d, n, r, v, dtype, W and stream only; W_stage_major is a device buffer of the size
+ * of W, 16-byte aligned.  Hand it to later calls in mtpc_head.W_stage_major. */
+mtpc_status mtpc_pack_weights(const mtpc_head* head, void* W_stage_major);
 
 /* The uniforms the sampler consumes, out [B][S][slots] fp32 (device), for tests
  * of the generator and its slot map. */

@@ -32,7 +32,8 @@ class mtpc_head(C.Structure):
     _fields_ = [("B", C.c_int32), ("d", C.c_int32), ("n", C.c_int32), ("r", C.c_int32),
                 ("v", C.c_int32), ("dtype", C.c_int32),
                 ("h", C.c_void_p), ("ld_h", C.c_int64), ("W", C.c_void_p), ("Wsum", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
+                ("W_stage_major", C.c_void_p)]
 
 
 class mtpc_sumlayers(C.Structure):
@@ -50,7 +51,7 @@ EXPORTS = [
     "mtpc_ff_table_scores", "mtpc_cp_table_scores", "mtpc_hmm_table_scores", "mtpc_btree_table_scores",
     "mtpc_ff_greedy_draft", "mtpc_cp_greedy_draft", "mtpc_hmm_greedy_draft", "mtpc_btree_greedy_draft",
     "mtpc_ff_loss_backward", "mtpc_cp_loss_backward", "mtpc_hmm_loss_backward", "mtpc_btree_loss_backward",
-    "mtpc_philox_uniforms", "mtpc_profile_unembed", "mtpc_profile_circuit", "mtpc_sample_static",
+    "mtpc_philox_uniforms", "mtpc_profile_unembed", "mtpc_profile_circuit", "mtpc_sample_static", "mtpc_pack_weights",
 ]
 
 _lib = None
@@ -91,6 +92,7 @@ def lib() -> C.CDLL:
         L.mtpc_philox_uniforms.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
                                            fp, C.c_void_p]
         L.mtpc_sample_static.argtypes = [C.c_int32, hp, lp, C.c_int32, C.c_uint64, C.c_uint32, ip, ip, fp, fp]
+        L.mtpc_pack_weights.argtypes = [hp, C.c_void_p]
         L.mtpc_profile_unembed.argtypes = [C.c_void_p, C.c_void_p]
         L.mtpc_profile_unembed.restype = None
         L.mtpc_profile_circuit.argtypes = [C.c_void_p, C.c_void_p]
@@ -156,6 +158,15 @@ class Head:
             else:
                 self._sl.R, self._sl.R_layer_stride = R.data_ptr(), rls
         self._ws = None
+        self.W_stage_major = None
+
+    def pack_W(self) -> None:
+        """Make the stage-major copy of W (for serving, W fixed) and use it from now on: decode-sized
+        calls stream it instead of W's rows.  Costs one more buffer of the size of W."""
+        buf = torch.empty_like(self.W)
+        hd = self._head(256)
+        _check(lib().mtpc_pack_weights(C.byref(hd), buf.data_ptr()))
+        self.W_stage_major = buf
 
     # ---- plumbing --------------------------------------------------------
     def _head(self, ws_bytes: int) -> mtpc_head:
@@ -169,6 +180,7 @@ class Head:
         hd.Wsum = self.Wsum.data_ptr() if self.Wsum is not None else None
         hd.workspace, hd.workspace_bytes = self._ws.data_ptr(), self._ws.numel()
         hd.stream = torch.cuda.current_stream(self.h.device).cuda_stream
+        hd.W_stage_major = self.W_stage_major.data_ptr() if self.W_stage_major is not None else None
         return hd
 
     def _layers_ref(self):
@@ -249,6 +261,7 @@ class Head:
         hd.Wsum = self.Wsum.data_ptr() if self.Wsum is not None else None
         hd.workspace, hd.workspace_bytes = None, 0
         hd.stream = torch.cuda.current_stream(self.h.device).cuda_stream
+        hd.W_stage_major = self.W_stage_major.data_ptr() if self.W_stage_major is not None else None
         _check(lib().mtpc_sample_static(FAMILY[self.family], C.byref(hd), self._layers_ref(), S, seed, offset,
                                         drafts.data_ptr(),
                                         latents.data_ptr() if latents is not None and latents.numel() > 0 else None,

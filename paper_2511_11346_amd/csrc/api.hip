@@ -88,7 +88,7 @@ mtpc_status check_head(int family, const mtpc_head* hd) {
   if (hd->d % 32 != 0 || hd->n > 64 || hd->r > 128 || hd->v > 320) return MTPC_ERR_UNSUPPORTED;
   if (family == MTPC_BTREE && (hd->n < 2 || (hd->n & (hd->n - 1)) != 0)) return MTPC_ERR_UNSUPPORTED;
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
-  if (((uintptr_t)hd->h | (uintptr_t)hd->W | (uintptr_t)hd->Wsum) & 15) return MTPC_ERR_UNSUPPORTED;
+  if (((uintptr_t)hd->h | (uintptr_t)hd->W | (uintptr_t)hd->Wsum | (uintptr_t)hd->W_stage_major) & 15) return MTPC_ERR_UNSUPPORTED;
   if (((size_t)hd->ld_h * esz) & 15) return MTPC_ERR_UNSUPPORTED;
   if ((long long)hd->n * hd->r * hd->v > 0x7fffffffLL) return MTPC_ERR_UNSUPPORTED;
   // a tile (up to 256 rows of h, 320 of W) is addressed through one 32-bit buffer resource
@@ -210,7 +210,7 @@ mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayer
 // the operands every launch of the fused kernel shares
 UnembedArgs unembed_args(const mtpc_head* hd) {
   UnembedArgs u{};
-  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W;
+  u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W; u.Wp = hd->W_stage_major;
   u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
   return u;
 }
@@ -955,6 +955,22 @@ mtpc_status mtpc_btree_loss_backward(const mtpc_head* head, const mtpc_sumlayers
                                      const float* coef, float* loss, float* dh, float* dW, float* dWsum,
                                      float* dlayers, float* dR) {
   return run_backward(MTPC_BTREE, head, A, targets, coef, loss, dh, dW, dWsum, dlayers, dR);
+}
+
+mtpc_status mtpc_pack_weights(const mtpc_head* head, void* W_stage_major) {
+  if (!head || !W_stage_major) return MTPC_ERR_NULL;
+  mtpc_head probe = *head;
+  probe.W_stage_major = nullptr;
+  if (!probe.Wsum) probe.Wsum = probe.W;                 // (not read here; a head without sum units has none)
+  mtpc_status s = check_head(MTPC_CP, &probe);
+  if (s != MTPC_OK) return s;
+  if ((uintptr_t)W_stage_major & 15) return MTPC_ERR_UNSUPPORTED;
+  const long long row_bytes = (long long)head->d * (head->dtype == MTPC_BF16 ? 2 : 4);
+  if (row_bytes % PACK_STAGE_BYTES != 0) return MTPC_ERR_UNSUPPORTED;
+  if (launch_pack_W(head->W, W_stage_major, (long long)head->n * head->r, head->v, (int)row_bytes, PACK_STAGE_BYTES,
+                    (hipStream_t)head->stream) != hipSuccess)
+    return MTPC_ERR_HIP;
+  return MTPC_OK;
 }
 
 mtpc_status mtpc_philox_uniforms(int32_t B, int32_t S, int32_t slots, uint64_t seed, uint32_t offset,

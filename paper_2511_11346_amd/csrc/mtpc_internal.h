@@ -19,6 +19,8 @@ struct UnembedArgs {
   const void* h;        // [B][ld_h]
   long long ld_h;       // elements
   const void* W;        // [n*r][v][d]
+  const void* Wp;       // stage-major copy of W in 128-byte stages (mtpc_pack_weights) or nullptr; read instead
+                        // of W by the decode tiles (B <= 64) when a row is a multiple of 128 bytes
   int B, d, v, n, r;
   // evidence: e[(b*T+t)][i][j] = l[x] - LSE for target window t of position b
   const int* targets;   // [B][T][n] or nullptr
@@ -70,6 +72,9 @@ struct CtxLayerArgs {
 hipError_t launch_ctx_layers(const CtxLayerArgs& a, int dtype, hipStream_t st);
 
 hipError_t launch_unembed(const UnembedArgs& a, int dtype, hipStream_t st);
+// dst[slab][stage][row][stage_bytes] = the stage_bytes of row `row` of slab `slab` of W that K stage `stage` covers
+hipError_t launch_pack_W(const void* W, void* dst, long long slabs, int v, int row_bytes, int stage_bytes, hipStream_t st);
+constexpr int PACK_STAGE_BYTES = 128;
 hipError_t launch_univariate(const UnivariateArgs& a, int dtype, hipStream_t st);
 
 // ---- small kernels (circuits.hip) -----------------------------------------

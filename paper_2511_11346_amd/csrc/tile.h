@@ -164,7 +164,11 @@ __device__ __forceinline__ int swz16(int row) { return (0 - (row >> 2)) & 3; }
 // rows[p] / rdiv of h (p < nrows <= TP, nrows >= 1; b0 is ignored and the whole of h,
 // which must span less than 4 GiB, is one resource).  32-row position blocks past nrows
 // are not multiplied (their accumulators stay zero), so a nearly empty tile is cheap.
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false>
+// WPACK: Wp is the stage-major copy of W (mtpc_pack_weights): per slab, the SB bytes that a K stage takes
+// from each of the v rows lie back to back ([stage][row][SB], ld_w is ignored), so a stage of a
+// slab is one contiguous run of v * SB bytes instead of SB bytes from each of v rows d elements apart.
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false,
+          bool WPACK = false>
 __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const void* hp, long long ld_h,
                                           int B, int d, int v, int slab, int b0, char* smem,
                                           typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
@@ -186,8 +190,9 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   const int hrows = GATHER ? nrows : min(B - b0, TL::TP);
   const int hbase = GATHER ? 0 : b0;
   const int hspan = GATHER ? B : hrows;
-  const i32x4_t srdW = make_srd((const char*)Wp + (long long)slab * v * ld_w * ESZ,
-                                (unsigned)((long long)(v - 1) * ld_w * ESZ + (long long)d * ESZ));
+  const i32x4_t srdW = WPACK ? make_srd((const char*)Wp + (long long)slab * v * d * ESZ, (unsigned)((long long)v * d * ESZ))
+                             : make_srd((const char*)Wp + (long long)slab * v * ld_w * ESZ,
+                                        (unsigned)((long long)(v - 1) * ld_w * ESZ + (long long)d * ESZ));
   const i32x4_t srdH = make_srd((const char*)hp + (long long)hbase * ld_h * ESZ,
                                 (unsigned)((long long)(hspan - 1) * ld_h * ESZ + (long long)d * ESZ));
   // wave-load q of this wave covers LDS rows RPL*wl .. RPL*wl+RPL-1 of every stage
@@ -197,7 +202,7 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     const int wl = min(wave + q * TL::NW, TL::NWL - 1);
     const int row = wl * TL::RPL + lane / CPR;
     const int ch = (lane % CPR) ^ (M16 ? swz16(row) : swz<CPR>(row));
-    if (row < TL::TV) voff[q] = (unsigned)min(row, v - 1) * (unsigned)(ld_w * ESZ) + ch * 16;
+    if (row < TL::TV) voff[q] = (unsigned)min(row, v - 1) * (WPACK ? (unsigned)SB : (unsigned)(ld_w * ESZ)) + ch * 16;
     else {
       int hr = min(row - TL::TV, hrows - 1);
       if constexpr (GATHER) hr = min(max(rows[hr] / rdiv, 0), B - 1);
@@ -206,16 +211,18 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   }
   const unsigned lds0 = (unsigned)(size_t)smem;
   unsigned kofs = 0;                                 // byte offset along K of the next stage to issue
+  unsigned kofsW = 0;                                // the same for the stage-major W (WPACK)
   auto issue_one = [&](int q, int buf) {   // q-th wave-load of this wave for one stage
     const int wl = wave + q * TL::NW;
     if (q < TL::PER || wl < TL::NWL) {
       // a wave-load never straddles the W / h boundary (TV is a multiple of RPL)
       const bool isW = wl * TL::RPL < TL::TV;
-      load_to_lds(voff[q], isW ? srdW : srdH, kofs, lds0 + buf * TL::STAGE + wl * 1024);
+      load_to_lds(voff[q], isW ? srdW : srdH, (WPACK && isW) ? kofsW : kofs, lds0 + buf * TL::STAGE + wl * 1024);
     }
   };
   auto advance = [&]() {
     kofs += SB;
+    if constexpr (WPACK) kofsW += (unsigned)v * SB;
   };
   auto issue = [&](int buf) {
 #pragma unroll

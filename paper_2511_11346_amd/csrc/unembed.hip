@@ -125,7 +125,7 @@ __device__ __forceinline__ void tile_draws(const typename Frag<M16>::blk_t (&acc
   }
 }
 
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE>
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE, bool WPACK = false>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_unembed(const UnembedArgs a) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
@@ -164,7 +164,8 @@ void k_unembed(const UnembedArgs a) {
   }
 
   typename FR::blk_t acc[NPB][NVB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0, smem, acc);
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16, WPACK>(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0,
+                                                             smem, acc);
 
   if constexpr (!SAMPLE) if (a.targets != nullptr) {
 #pragma unroll
@@ -730,10 +731,10 @@ hipError_t launch_univariate(const UnivariateArgs& a, int dtype, hipStream_t st)
   return dtype == MTPC_BF16 ? launch_uni_dt<true>(a, st) : launch_uni_dt<false>(a, st);
 }
 
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE>
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE, bool WPACK = false>
 static hipError_t launch_cfg(const UnembedArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
-  constexpr auto kern = k_unembed<WV, WB, VB, PB, SB, NS, BF16, SAMPLE>;
+  constexpr auto kern = k_unembed<WV, WB, VB, PB, SB, NS, BF16, SAMPLE, WPACK>;
   if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nbt = (a.B + TL::TP - 1) / TL::TP;
   const int grid = nbt * a.n * a.r;
@@ -746,7 +747,11 @@ static hipError_t launch_cfg(const UnembedArgs& a, hipStream_t st) {
 // 90 KB in flight per CU; 1.5-2.5 % faster than 64-byte stages in a 4-stage ring).
 template <int WV, int PB, bool BF16, bool SAMPLE>
 static hipError_t launch_dec(const UnembedArgs& a, int row_bytes, hipStream_t st) {
-  if (row_bytes % 128 == 0) return launch_cfg<WV, 1, 2, PB, 128, 3, BF16, SAMPLE>(a, st);
+  static_assert(PACK_STAGE_BYTES == 128, "the stage-major copy of W is cut for the 128-byte stages");
+  if (row_bytes % 128 == 0) {
+    if (a.Wp != nullptr) return launch_cfg<WV, 1, 2, PB, 128, 3, BF16, SAMPLE, true>(a, st);
+    return launch_cfg<WV, 1, 2, PB, 128, 3, BF16, SAMPLE>(a, st);
+  }
   return launch_cfg<WV, 1, 2, PB, 64, 4, BF16, SAMPLE>(a, st);
 }
 
@@ -769,6 +774,29 @@ static hipError_t launch_dt(const UnembedArgs& a, hipStream_t st) {
   if (a.v > 256) return launch_dec<5, 1, BF16, SAMPLE>(a, row_bytes, st);
   if (a.v > 128) return launch_dec<4, 1, BF16, SAMPLE>(a, row_bytes, st);
   return launch_dec<2, 1, BF16, SAMPLE>(a, row_bytes, st);
+}
+
+// Stage-major copy of W: one thread moves 16 bytes; a workgroup's reads cover 256 / (SB / 16) rows of
+// one stage (SB contiguous bytes each), its writes one contiguous run.
+__global__ __launch_bounds__(256) void k_pack_W(const char* __restrict__ W, char* __restrict__ dst, long long slabs, int v,
+                                                int row_bytes, int stage_bytes) {
+  const int cps = stage_bytes / 16, stages = row_bytes / stage_bytes;
+  const long long per_slab = (long long)v * row_bytes / 16;            // 16-byte chunks of a slab
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;       // chunk index in the packed order
+  if (t >= slabs * per_slab) return;
+  const long long slab = t / per_slab, u = t - slab * per_slab;
+  const int stage = (int)(u / ((long long)v * cps)), w = (int)(u - (long long)stage * v * cps);
+  const int row = w / cps, ch = w - row * cps;
+  (void)stages;
+  const i32x4_t x = *(const i32x4_t*)(W + (slab * v + row) * row_bytes + (long long)stage * stage_bytes + ch * 16);
+  *(i32x4_t*)(dst + t * 16) = x;
+}
+
+hipError_t launch_pack_W(const void* W, void* dst, long long slabs, int v, int row_bytes, int stage_bytes, hipStream_t st) {
+  const long long chunks = slabs * v * (row_bytes / 16);
+  hipLaunchKernelGGL(k_pack_W, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, (const char*)W, (char*)dst, slabs, v,
+                     row_bytes, stage_bytes);
+  return hipGetLastError();
 }
 
 hipError_t launch_unembed(const UnembedArgs& a, int dtype, hipStream_t st) {

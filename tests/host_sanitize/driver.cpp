@@ -97,6 +97,16 @@ void run_case(const Case& c, bool with_backward) {
     }
     lyp = &ly;
   }
+  if ((d * es) % 128 == 0) {            // the stage-major copy of W, handed to every later call of the case
+    void* packed = fake(n * r * v * d * es, "stage-major W");
+    begin(T + " pack W", hd);
+    expect(mtpc_pack_weights(&hd, packed), MTPC_OK, T + " pack W");
+    hd.W_stage_major = packed;
+  } else {
+    void* packed = fake(n * r * v * d * es, "stage-major W");
+    begin(T + " pack W, ragged rows", hd);
+    expect(mtpc_pack_weights(&hd, packed), MTPC_ERR_UNSUPPORTED, T + " pack W, ragged rows");
+  }
   int32_t* targets = (int32_t*)fake(B * n * 4, "targets");
   float* out1 = (float*)fake(B * 4, "loglik");
   float* outP = (float*)fake(B * n * 4, "prefix marginals");

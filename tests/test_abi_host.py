@@ -21,7 +21,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported():
     from paper_2511_11346_amd import binding
     names = declared_symbols()
-    assert len(names) == 38 and sorted(binding.EXPORTS) == names
+    assert len(names) == 39 and sorted(binding.EXPORTS) == names
     L = C.CDLL(LIB)
     for n in names:
         assert hasattr(L, n), n

@@ -230,3 +230,30 @@ def test_a_handful_of_drafts_without_scores(family, dtype, B, S, d, n, r, v, ctx
         assert np.array_equal(g2.cpu().numpy()[safe], want_d[safe])
         if l2 is not None and want_l.shape[1]:
             assert np.array_equal(l2.cpu().numpy()[safe], want_l[safe])
+
+
+@pytest.mark.parametrize("family,dtype,B,d,n,r,v", [
+    ("cp", "bf16", 64, 4096, 16, 32, 320), ("cp", "bf16", 1, 256, 4, 8, 320), ("hmm", "f32", 33, 64, 5, 6, 130),
+    ("btree", "bf16", 8, 128, 8, 16, 268), ("ff", "f32", 20, 96, 3, 1, 100),
+])
+def test_stage_major_copy_of_W_gives_the_same_bits(family, dtype, B, d, n, r, v):
+    """Decode-sized calls that stream the stage-major copy of W (mtpc_pack_weights) instead of its rows:
+    same products in the same order, so every output is bit-identical - drafts, scores, the table of
+    input units, likelihoods, univariate marginals; batches above 64 positions ignore the copy."""
+    inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=60 + n + r, h_scale=1.0)
+    plain, packed = make_head(inp), make_head(inp)
+    packed.pack_W()
+    # the copy itself: [slab][stage][row][128 bytes]
+    es = 2 if dtype == "bf16" else 4
+    stages = d * es // 128
+    want = plain.W.view(torch.uint8).view(n * r, v, stages, 128).permute(0, 2, 1, 3).contiguous()
+    assert torch.equal(packed.W_stage_major.view(torch.uint8).view(n * r, stages, v, 128), want)
+    tg = torch.from_numpy(inp.targets).cuda()
+    assert torch.equal(plain.loglik(tg), packed.loglik(tg))
+    assert torch.equal(plain.prefix_marginals(tg), packed.prefix_marginals(tg))
+    assert torch.equal(plain.univariate_marginals(), packed.univariate_marginals())
+    ta, tb = (torch.empty(B, n, r, v, dtype=torch.float32, device="cuda") for _ in range(2))
+    a = plain.sample(2, seed=3, offset=1, want_prefix=True, logphi=ta)
+    b = packed.sample(2, seed=3, offset=1, want_prefix=True, logphi=tb)
+    assert all(torch.equal(x, y) for x, y in zip(a, b)) and torch.equal(ta, tb)
+    assert torch.equal(plain.greedy_draft()[0], packed.greedy_draft()[0])
