@@ -216,11 +216,17 @@ UnembedArgs unembed_args(const mtpc_head* hd) {
 }
 
 // sum-unit parameters shared by all ops
+// `draws` (sampling calls of a few positions): the launch that computes the sum units goes on to
+// draw the latents, after the layers those draws read; returns with *draws_done set then.
+// `own_sumunit`: the consumer computes its sum units itself (verification of a few positions).
 mtpc_status launch_params(int family, const mtpc_head* hd, const mtpc_sumlayers* ly, const Plan& p,
-                          bool nat, bool circ, hipStream_t st) {
+                          bool nat, bool circ, hipStream_t st, const LatentArgs* draws = nullptr,
+                          bool* draws_done = nullptr, bool own_sumunit = false) {
   char* ws = (char*)hd->workspace;
   nat = nat && p.has_nat;
-  if (family != MTPC_FF)
+  const bool fuse = draws != nullptr && family != MTPC_FF && hd->B <= SUMUNIT_SMALL_B;
+  if (draws_done) *draws_done = fuse;
+  if (family != MTPC_FF && !fuse && !own_sumunit)
     HIP_TRY(launch_sumunit(hd->h, hd->ld_h, hd->Wsum, hd->B, hd->d, hd->r, hd->dtype,
                            (float*)(ws + p.logw), st));
   const int L = n_layers(family, hd->n);
@@ -239,6 +245,8 @@ mtpc_status launch_params(int family, const mtpc_head* hd, const mtpc_sumlayers*
     HIP_TRY(launch_normalise_layers(ly->logits, ly->layer_stride, ly->batch_stride, p.nb, p.Lst, hd->r,
                                     out_nat, out_tr, st));
   }
+  if (fuse)
+    HIP_TRY(launch_sumunit_latents(hd->h, hd->ld_h, hd->Wsum, hd->d, hd->dtype, (float*)(ws + p.logw), *draws, st));
   return MTPC_OK;
 }
 
@@ -338,8 +346,6 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   if ((long long)hd->B * S > 0x7fffffffLL / hd->n) return MTPC_ERR_UNSUPPORTED;
   hipStream_t st = (hipStream_t)hd->stream;
   char* ws = (char*)hd->workspace;
-  s = launch_params(family, hd, ly, p, true, want_prefix, st);
-  if (s != MTPC_OK) return s;
   const uint32_t seed_lo = (uint32_t)(seed & 0xffffffffu), seed_hi = (uint32_t)(seed >> 32);
 
   LatentArgs la{};
@@ -350,7 +356,10 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   la.seed_lo = seed_lo; la.seed_hi = seed_hi; la.offset = offset; la.greedy = greedy;
   la.zleaf = (int*)(ws + p.zleaf);
   la.latents = latents ? latents : (int*)(ws + p.lat);
-  HIP_TRY(launch_latents(la, st));
+  bool drawn = false;
+  s = launch_params(family, hd, ly, p, true, want_prefix, st, &la, &drawn);
+  if (s != MTPC_OK) return s;
+  if (!drawn) HIP_TRY(launch_latents(la, st));
 
   // Where the tokens are drawn (see decode_sized):
   //   InKernel  - in the epilogue of the fused kernel, which evaluates every slab
@@ -494,14 +503,17 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   hipStream_t st = (hipStream_t)hd->stream;
   char* ws = (char*)hd->workspace;
   const int L = n_layers(family, hd->n);
+  // a few positions: each position's workgroup computes its own sum units
+  const bool own = family != MTPC_FF && hd->B <= SUMUNIT_SMALL_B;
   if (mode == MTPC_VERIFY_SAMPLING) {
-    s = launch_params(family, hd, ly, p, true, family == MTPC_BTREE, st);
+    s = launch_params(family, hd, ly, p, true, family == MTPC_BTREE, st, nullptr, nullptr, own);
     if (s != MTPC_OK) return s;
   }
   VerifyArgs a{};
   a.family = family; a.B = hd->B; a.n = hd->n; a.r = hd->r; a.v = hd->v; a.mode = mode;
   a.logphi = logphi; a.drafts = drafts; a.prefix = prefix_logq; a.p = pver;
-  a.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
+  a.logw = (family == MTPC_FF || own) ? nullptr : (const float*)(ws + p.logw);
+  if (own) { a.h = hd->h; a.ld_h = hd->ld_h; a.Wsum = hd->Wsum; a.d = hd->d; a.bf16 = hd->dtype == MTPC_BF16; }
   a.lay_nat = L > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
   a.lay_tr = (L > 0 && family == MTPC_BTREE) ? (const float*)(ws + p.lay_circ) : nullptr;
   a.L = p.Lst; a.contextual = p.nb > 1;

@@ -3,10 +3,10 @@
 // latent marginals, and the table lookup that scores drafts.
 // All of them touch O(B n r) or O(L r^2) data; none is a roofline concern.
 #include "mtpc_internal.h"
+#include "sumunit.h"
 
 namespace mtpc {
 
-typedef __attribute__((ext_vector_type(4))) int i32x4_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 __device__ __forceinline__ float wave_sum(float x) { return group_sum(x, 64); }
@@ -28,95 +28,48 @@ __device__ __forceinline__ int first_nan_position(const float* e, int n, int r, 
   return group_min(fb, G);
 }
 
-// dot of two rows of 8-element (bf16) or 4-element (fp32) 16-byte chunks
-template <bool BF16>
-__device__ __forceinline__ float dot_chunk(const i32x4_t& a, const i32x4_t& b) {
-  float s = 0.f;
-  if constexpr (BF16) {
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const uint32_t ua = (uint32_t)a[t], ub = (uint32_t)b[t];
-      s = fmaf(__uint_as_float(ua << 16), __uint_as_float(ub << 16), s);
-      s = fmaf(__uint_as_float(ua & 0xFFFF0000u), __uint_as_float(ub & 0xFFFF0000u), s);
-    }
-  } else {
-#pragma unroll
-    for (int t = 0; t < 4; ++t) s = fmaf(__int_as_float(a[t]), __int_as_float(b[t]), s);
-  }
-  return s;
-}
+__device__ void draft_latents(const LatentArgs& a, int b, int s, const float* lw, int lane);
 
 // ---------------------------------------------------------------------------
 // log omega[b,:] = log_softmax(Wsum h[b])   (Sec. 3.3, sum unit parameters)
-// Few positions: one workgroup per position, its 4 waves split the r rows, the
-// scores meet in LDS.  Many positions go through the MFMA tile kernel instead.
+// Few positions: one workgroup per position (sumunit_position).  With la.zleaf set the
+// workgroup goes on to draw the latents of the position's drafts from the weights it has just
+// computed (Alg. 1, top-down; one wave per draft) - one launch and one dependent round trip less
+// on the decode path.  Many positions go through the MFMA tile kernel instead.
 // ---------------------------------------------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(256) void k_sumunit(const void* h, long long ld_h, const void* Wsum,
-                                                 int B, int d, int r, float* logw) {
-  constexpr int ESZ = BF16 ? 2 : 4;
-  constexpr int EPC = 16 / ESZ;
+                                                 int B, int d, int r, float* logw, const LatentArgs la) {
   __shared__ float sc[128];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.x;
-  const char* hb = (const char*)h + (long long)b * ld_h * ESZ;
-  const int nch = d / EPC;
-  // the position's hidden vector stays in registers: up to 8 chunks of 16 bytes per
-  // lane per pass (d <= 4096 bf16 / 2048 fp32 in one pass), rows four at a time so
-  // that many loads are in flight
-  for (int c0 = 0; c0 < nch; c0 += 512) {
-    i32x4_t hv[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const int c = c0 + t * 64 + lane;
-      const i32x4_t x = *(const i32x4_t*)(hb + (long long)min(c, nch - 1) * 16);
-      hv[t] = c < nch ? x : i32x4_t{0, 0, 0, 0};
-    }
-    for (int j0 = wave * 4; j0 < r; j0 += 16) {
-      float acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int j = min(j0 + q, r - 1);
-        const char* wr = (const char*)Wsum + (long long)j * d * ESZ;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          // unconditional (clamped) loads so that all of them are in flight together;
-          // chunks beyond d meet a zero hv
-          const int c = min(c0 + t * 64 + lane, nch - 1);
-          acc[q] += dot_chunk<BF16>(*(const i32x4_t*)(wr + (long long)c * 16), hv[t]);
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float v = wave_sum(acc[q]);
-        if (lane == 0 && j0 + q < r) { if (c0 == 0) sc[j0 + q] = v; else sc[j0 + q] += v; }
-      }
-    }
-  }
-  __syncthreads();
-  if (wave == 0) {
-    const float s0 = lane < r ? sc[lane] : neg_inf();
-    const float s1 = lane + 64 < r ? sc[lane + 64] : neg_inf();
-    const float m = group_max(fmaxf(s0, s1), 64);
-    float e = 0.f;
-    if (s0 > neg_inf()) e += __expf(s0 - m);
-    if (s1 > neg_inf()) e += __expf(s1 - m);
-    e = group_sum(e, 64);
-    const float lse = m + __logf(e);
-    if (lane < r) logw[(long long)b * r + lane] = s0 - lse;
-    if (lane + 64 < r) logw[(long long)b * r + lane + 64] = s1 - lse;
-  }
+  sumunit_position<BF16>(h, ld_h, Wsum, b, d, r, sc);
+  if ((int)threadIdx.x < r) logw[(long long)b * r + threadIdx.x] = sc[threadIdx.x];
+  if (la.zleaf != nullptr)
+    for (int s = threadIdx.x >> 6; s < la.S; s += 4) draft_latents(la, b, s, sc, threadIdx.x & 63);
+}
+
+static hipError_t launch_sumunit_small(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
+                                       int dtype, float* logw, const LatentArgs& la, hipStream_t st) {
+  dim3 grid(B), block(256);
+  if (dtype == MTPC_BF16)
+    hipLaunchKernelGGL(k_sumunit<true>, grid, block, 0, st, h, ld_h, Wsum, B, d, r, logw, la);
+  else
+    hipLaunchKernelGGL(k_sumunit<false>, grid, block, 0, st, h, ld_h, Wsum, B, d, r, logw, la);
+  return hipGetLastError();
 }
 
 hipError_t launch_sumunit(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
                           int dtype, float* logw, hipStream_t st) {
-  if (B > 128) return launch_sumunit_mfma(h, ld_h, Wsum, B, d, r, dtype, logw, st);
-  dim3 grid(B), block(256);
-  if (dtype == MTPC_BF16)
-    hipLaunchKernelGGL(k_sumunit<true>, grid, block, 0, st, h, ld_h, Wsum, B, d, r, logw);
-  else
-    hipLaunchKernelGGL(k_sumunit<false>, grid, block, 0, st, h, ld_h, Wsum, B, d, r, logw);
-  return hipGetLastError();
+  if (B > SUMUNIT_SMALL_B) return launch_sumunit_mfma(h, ld_h, Wsum, B, d, r, dtype, logw, st);
+  LatentArgs none{};
+  return launch_sumunit_small(h, ld_h, Wsum, B, d, r, dtype, logw, none, st);
+}
+
+// sum units and latent draws in one launch (B <= SUMUNIT_SMALL_B, a family with sum units; the
+// normalised layers the draws of the HMM / binary tree read must be complete before it)
+hipError_t launch_sumunit_latents(const void* h, long long ld_h, const void* Wsum, int d, int dtype, float* logw,
+                                  const LatentArgs& la, hipStream_t st) {
+  return launch_sumunit_small(h, ld_h, Wsum, la.B, d, la.r, dtype, logw, la, st);
 }
 
 // ---------------------------------------------------------------------------
@@ -1091,17 +1044,11 @@ __device__ __forceinline__ int wave_argmax(float p0, float p1, int r, int lane) 
   return arg;
 }
 
-__global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
-  const int lane = threadIdx.x & 63;
-  const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);     // draft index
-  if (t >= (long long)a.B * a.S) return;
-  const int b = (int)(t / a.S), s = (int)(t % a.S);
+// the latents of draft (b, s) by one wave; lw: the position's log omega (global or LDS)
+__device__ void draft_latents(const LatentArgs& a, int b, int s, const float* lw, int lane) {
+  const long long t = (long long)b * a.S + s;
   const int n = a.n, r = a.r;
   int* zl = a.zleaf + t * n;
-  if (a.family == MTPC_FF) {
-    for (int i = lane; i < n; i += 64) zl[i] = 0;
-    return;
-  }
   const float* lay = a.layers;
   if (a.contextual && lay) lay += (long long)b * a.L * r * r;
   const long long lstep = (a.L > 1) ? (long long)r * r : 0;
@@ -1113,7 +1060,6 @@ __global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
     const float p1 = lane + 64 < r ? row[lane + 64] : 0.f;
     return a.greedy ? wave_argmax(p0, p1, r, lane) : wave_draw(p0, p1, r, U(lat), lane);
   };
-  const float* lw = a.logw + (long long)b * r;
   const float q0 = lane < r ? expf(lw[lane]) : 0.f, q1 = lane + 64 < r ? expf(lw[lane + 64]) : 0.f;
   const int z0 = a.greedy ? wave_argmax(q0, q1, r, lane) : wave_draw(q0, q1, r, U(0), lane);
   if (a.family == MTPC_CP) {
@@ -1140,6 +1086,19 @@ __global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
     if (lane < n - 1) L[lane] = mine;
     for (int i = lane; i < n; i += 64) zl[i] = __shfl(mine, (n - 2 + i) >> 1);
   }
+}
+
+__global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);     // draft index
+  if (t >= (long long)a.B * a.S) return;
+  const int b = (int)(t / a.S), s = (int)(t % a.S);
+  if (a.family == MTPC_FF) {
+    int* zl = a.zleaf + t * a.n;
+    for (int i = lane; i < a.n; i += 64) zl[i] = 0;
+    return;
+  }
+  draft_latents(a, b, s, a.logw + (long long)b * a.r, lane);
 }
 
 hipError_t launch_latents(const LatentArgs& a, hipStream_t st) {

@@ -118,6 +118,12 @@ struct LatentArgs {
   int* latents;         // [B][S][n_lat] or nullptr
 };
 hipError_t launch_latents(const LatentArgs& a, hipStream_t st);
+// batches up to this many positions compute their sum units one workgroup per position
+constexpr int SUMUNIT_SMALL_B = 128;
+// the same draws in the launch that computes log omega (B <= SUMUNIT_SMALL_B, families with sum
+// units): writes logw [B][r] and the latents; the normalised layers must be complete before it
+hipError_t launch_sumunit_latents(const void* h, long long ld_h, const void* Wsum, int d, int dtype, float* logw,
+                                  const LatentArgs& a, hipStream_t st);
 
 // log marginal of the latent that indexes each leaf: logm[b][i][j]
 struct LatentMarginalArgs {
@@ -202,7 +208,11 @@ struct VerifyArgs {
   const int* drafts;    // [B][n]
   const float* prefix;  // [B][n]
   const float* p;       // [B][n+1][v]
-  const float* logw;    // [B][r] (nullptr for FF)
+  const float* logw;    // [B][r] (nullptr for FF, or when the kernel computes it itself, see h)
+  const void* h;        // with h set (B <= SUMUNIT_SMALL_B): log omega = log_softmax(Wsum h[b]) is computed
+  long long ld_h;       // by the position's own workgroup
+  const void* Wsum;
+  int d, bf16;
   const float* lay_nat; // normalised linear layers [nb][L][k][j]
   const float* lay_tr;  // the same transposed [nb][L][j][k] (BTree only)
   int L, contextual;

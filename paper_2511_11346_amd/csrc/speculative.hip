@@ -14,6 +14,7 @@
 #include <climits>
 
 #include "mtpc_internal.h"
+#include "sumunit.h"
 
 namespace mtpc {
 namespace {
@@ -111,6 +112,7 @@ __global__ __launch_bounds__(256) void k_verify(const VerifyArgs a, int G) {
   extern __shared__ float vsm[];
   __shared__ float s_red[4], s_x[128], s_c[128], s_part[256], s_ratio[64], s_alpha[64];
   __shared__ int s_arg[65], s_j, s_lo, s_hi;
+  __shared__ float s_lw[128];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = a.n, r = a.r, v = a.v;
   float* s_e = vsm;                                          // [n][r] evidence of the drafted tokens
@@ -180,6 +182,11 @@ __global__ __launch_bounds__(256) void k_verify(const VerifyArgs a, int G) {
     }
     __syncthreads();
     const float* lw = a.logw ? a.logw + (long long)b * r : nullptr;
+    if (a.h != nullptr && a.family != MTPC_FF) {             // sum units of this position, computed here
+      if (a.bf16) sumunit_position<true>(a.h, a.ld_h, a.Wsum, b, a.d, r, s_lw);
+      else sumunit_position<false>(a.h, a.ld_h, a.Wsum, b, a.d, r, s_lw);
+      lw = s_lw;
+    }
     const long long lstep = a.L > 1 ? (long long)r * r : 0;
     const long long lbase = a.contextual ? (long long)b * a.L * r * r : 0;
     const bool ahead = (r + 256 / G - 1) / (256 / G) <= 16;     // a thread's share of a layer fits mv_load

@@ -117,6 +117,13 @@ hipError_t launch_latents(const LatentArgs& a, hipStream_t) {
   if (nlat(a.family, a.n) > 0) need(a.latents, (u64)a.B * a.S * nlat(a.family, a.n) * 4, "latents out");
   return ok();
 }
+hipError_t launch_sumunit_latents(const void* h, long long ld_h, const void* Wsum, int d, int dtype, float* logw,
+                                  const LatentArgs& a, hipStream_t st) {
+  if (a.B > SUMUNIT_SMALL_B || a.family == MTPC_FF) { std::fprintf(stderr, "fused sum units + latents outside their range\n"); std::abort(); }
+  launch_sumunit(h, ld_h, Wsum, a.B, d, a.r, dtype, logw, st);
+  --host_check::g_launches;
+  return launch_latents(a, st);
+}
 hipError_t launch_latent_marginals(const LatentMarginalArgs& a, hipStream_t) {
   need(a.logw, (u64)a.B * a.r * 4, "latent marginals logw");
   if (a.layers) need(a.layers, (a.contextual ? (u64)a.B : 1) * a.L * a.r * a.r * 4, "latent marginals layers");
@@ -169,7 +176,14 @@ hipError_t launch_verify(const VerifyArgs& a, hipStream_t) {
   if (a.mode == MTPC_VERIFY_SAMPLING) {
     need(a.logphi, (u64)a.B * a.n * a.r * a.v * 4, "verify logphi");
     need(a.prefix, (u64)a.B * a.n * 4, "verify prefix");
-    if (a.family != MTPC_FF) need(a.logw, (u64)a.B * a.r * 4, "verify logw");
+    if (a.family != MTPC_FF) {
+      if (a.h) {
+        need(a.h, strided(a.B, a.ld_h, a.d, a.bf16 ? 2 : 4), "verify h");
+        need(a.Wsum, (u64)a.r * a.d * (a.bf16 ? 2 : 4), "verify Wsum");
+      } else {
+        need(a.logw, (u64)a.B * a.r * 4, "verify logw");
+      }
+    }
     const u64 lay = (a.contextual ? (u64)a.B : 1) * a.L * a.r * a.r * 4;
     if (a.lay_nat) need(a.lay_nat, lay, "verify lay_nat");
     if (a.lay_tr) need(a.lay_tr, lay, "verify lay_tr");
