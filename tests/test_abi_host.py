@@ -156,3 +156,21 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path):
                     str(src), "-o", str(exe), LIB, "-Wl,-rpath," + os.path.dirname(LIB)], check=True)
     res = subprocess.run([str(exe)], capture_output=True, text=True)
     assert res.returncode == 0 and res.stdout.strip() != ""
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU fallback: without the built shared library every call raises."""
+    from paper_2511_11346_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libmtpc.so"))
+    with pytest.raises(binding.MtpcError, match="not found"):
+        binding.lib()
+    with pytest.raises(binding.MtpcError):
+        binding.profile_unembed(None, None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2 and "ONE GPU" in res.stderr and res.stdout.strip() == ""
