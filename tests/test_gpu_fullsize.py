@@ -217,6 +217,78 @@ def test_config2_training_step_full_size():
     assert float(out2["dh"][torch.from_numpy(others).cuda()].abs().max()) == 0.0
 
 
+def test_config4_training_step_full_size():
+    """Training step of configs[3] (binary tree, r = 64, n = 16, B = 4096) in the launch
+    configuration the bench times.  One oracle call differentiates a dozen positions: the dense
+    run's loss and dh are compared on those positions; a second run whose coefficients vanish
+    elsewhere (and are 100 times larger there: the gradients are linear in them) gives dW, dWsum
+    and the gradient of the 14 shared layers entry by entry.  The dense run also has to satisfy
+    sum_a dW[i,j,a,:] = 0 and <dh,h> = <dW,W> + <dWsum,Wsum> (static layers do not depend on h)."""
+    inp = mi.config4()
+    B, n = inp.B, inp.n
+    head = make_head(inp)
+    rng = np.random.default_rng(14)
+    valid = rng.random((B, n)) > 0.1
+    coef = bw.loss_coefficients(0.8, valid, sequence=np.arange(B) // 1024).astype(np.float32)
+    tg = torch.from_numpy(inp.targets).cuda()
+    out = head.loss_backward(tg, torch.from_numpy(coef).cuda())
+    few = np.unique(np.concatenate([sample_rows(B, k=8, seed=4), [2047, 2048, B - 1]]))
+    want = bw.loss_and_gradients("btree", inp.h[few], inp.W, inp.Wsum, inp.layers, inp.targets[few], coef[few])
+    dh = out["dh"].cpu().numpy()[few].astype(np.float64)
+    fro = np.linalg.norm(dh - want["dh"]) / np.linalg.norm(want["dh"])
+    assert fro <= 3e-3 and np.abs(dh - want["dh"]).max() <= 2e-2 * np.abs(want["dh"]).max(), fro
+    loss = out["loss"].cpu().numpy()[few]
+    assert np.all(np.abs(loss - want["loss"]) <= 2e-3 * np.maximum(np.abs(want["loss"]), 1e-6))
+    dW = out["dW"]
+    scale = float(dW.abs().max())
+    assert float(dW.sum(dim=2, dtype=torch.float64).abs().max()) <= 0.1 * scale
+    Wg, hg = torch.from_numpy(inp.W).cuda(), torch.from_numpy(inp.h).cuda()
+    lhs = float((out["dh"].double() * hg.double()).sum())
+    dWW = [float((dW[i].double() * Wg[i].double()).sum()) for i in range(n)]
+    absW = sum(float((dW[i].double() * Wg[i].double()).abs().sum()) for i in range(n))
+    rhs = sum(dWW) + float((out["dWsum"].double() * torch.from_numpy(inp.Wsum).cuda().double()).sum())
+    assert abs(lhs - rhs) <= 3e-3 * max(abs(lhs), absW * 1e-3), (lhs, rhs)
+    print(f"dense run: dh rows rel. Frobenius error {fro:.1e}; <dh,h> = {lhs:.6e}, <dW,W>+<dWsum,Wsum> = {rhs:.6e}")
+    del Wg, hg, dW
+
+    sparse = np.zeros_like(coef)
+    sparse[few] = coef[few] * 100.0
+    out2 = head.loss_backward(tg, torch.from_numpy(sparse).cuda(), out=out)
+    got = out2["dlayers"].cpu().numpy().astype(np.float64)
+    ref = 100.0 * want["dlayers"]
+    f2 = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    assert f2 <= 3e-3 and np.abs(got - ref).max() <= 2e-2 * np.abs(ref).max(), f2
+    print(f"sparse run ({len(few)} positions): dlayers rel. Frobenius error {f2:.1e}")
+    # The gradient of a sum-unit logit is c * (posterior_z - omega_z) summed over the prefixes.  Behind
+    # fourteen random 64 x 64 layers the root's latent hardly depends on the tokens: the posterior is
+    # omega to four or five digits, and the difference of two fp32 numbers of size c * omega keeps
+    # an absolute error of a few units of THEIR last place, not of its own.  So the bound is the
+    # relative one plus 8 fp32 units (2^-23) of the terms that cancel, sum_b |c_b| omega_bz |h_bd|.
+    hs = inp.h[few].astype(np.float64)
+    z = hs @ inp.Wsum.astype(np.float64).T
+    omega = np.exp(z - z.max(axis=1, keepdims=True))
+    omega /= omega.sum(axis=1, keepdims=True)
+    cancel = np.einsum("b,bz,bd->zd", np.abs(sparse[few]).astype(np.float64).sum(axis=1), omega, np.abs(hs))
+    got = out2["dWsum"].cpu().numpy().astype(np.float64)
+    ref = 100.0 * want["dWsum"]
+    err = np.abs(got - ref).max()
+    assert err <= 3e-3 * np.abs(ref).max() + 8 * 2.0 ** -23 * cancel.max(), (err, np.abs(ref).max(), cancel.max())
+    print(f"sparse run: dWsum max error {err:.1e}, largest entry {np.abs(ref).max():.1e}, "
+          f"cancelling terms {cancel.max():.1e}")
+    num = den = 0.0
+    top = 100.0 * np.abs(want["dW"]).max()
+    for i in range(n):                       # token by token: the full array is 8 GB in float64
+        got = out2["dW"][i].cpu().numpy().astype(np.float64)
+        ref = 100.0 * want["dW"][i]
+        assert np.abs(got - ref).max() <= 2e-2 * top, i
+        num += float(((got - ref) ** 2).sum())
+        den += float((ref ** 2).sum())
+    assert np.sqrt(num / den) <= 3e-3, np.sqrt(num / den)
+    print(f"sparse run: dW rel. Frobenius error {np.sqrt(num / den):.1e}")
+    others = np.setdiff1d(np.arange(B), few)
+    assert float(out2["dh"][torch.from_numpy(others).cuda()].abs().max()) == 0.0
+
+
 def test_config3_contextual_training_step_full_size():
     """The HMM the paper trains (transition logits R h + bias), B = 8192: loss and dh on
     sampled positions against the oracle; dW, dWsum, dR and the bias gradient exactly in a
