@@ -251,14 +251,17 @@ def main():
     L = n - 2
     k2_bytes = rows2 * n * r * 4 + B * r * 4 + L * r * r * 4 + rows2 * n * 4
     steps_tree = (n - 2) + n * (n.bit_length() - 1)      # every inner node once, then at most log2 n path steps per prefix
-    circuit = {"kernel": "k_btree_static (prefix marginals of 2 windows per position, 14 shared 64x64 layers)",
+    circuit = {"kernel": "k_btree_mfma<64> (prefix marginals of 2 windows per position, 14 shared 64x64 layers, "
+                         "fp32 MFMA products)",
                "avg_launch_ms": k2_ms,
                "algorithmic_bytes": k2_bytes,          # evidence rows + root weights + layers in, prefix marginals out
                "achieved_GBps": k2_bytes / (k2_ms * 1e-3) / 1e9,
                "frac_of_hbm_peak": k2_bytes / (k2_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
                "note": "34 MB of evidence against a chain of dependent r x r layer products per window: "
                        "bound by that arithmetic and its latency, not by HBM",
-               "layer_products_GFLOPs_upper_bound": 2.0 * r * r * steps_tree * rows2 / (k2_ms * 1e-3) / 1e9}
+               "layer_products_GFLOPs_upper_bound": 2.0 * r * r * steps_tree * rows2 / (k2_ms * 1e-3) / 1e9,
+               "layer_products_frac_of_fp32_mfma_peak_upper_bound":
+                   2.0 * r * r * steps_tree * rows2 / (k2_ms * 1e-3) / 1e12 / PEAK_F32_TFLOPS}
 
     out = {
         "metric": "MtPC head windows/sec (loglik + draft sample)",

@@ -2,6 +2,8 @@
 // layers on the evidence e[rows][n][r], latent draws of the ancestral sampler,
 // latent marginals, and the table lookup that scores drafts.
 // All of them touch O(B n r) or O(L r^2) data; none is a roofline concern.
+#include <type_traits>
+
 #include "mtpc_internal.h"
 #include "sumunit.h"
 
@@ -32,25 +34,25 @@ __device__ void draft_latents(const LatentArgs& a, int b, int s, const float* lw
 
 // ---------------------------------------------------------------------------
 // log omega[b,:] = log_softmax(Wsum h[b])   (Sec. 3.3, sum unit parameters)
-// Few positions: one workgroup per position (sumunit_position).  With la.zleaf set the
+// Few positions: one workgroup of 16 waves per position (sumunit_position).  With la.zleaf set the
 // workgroup goes on to draw the latents of the position's drafts from the weights it has just
 // computed (Alg. 1, top-down; one wave per draft) - one launch and one dependent round trip less
 // on the decode path.  Many positions go through the MFMA tile kernel instead.
 // ---------------------------------------------------------------------------
 template <bool BF16>
-__global__ __launch_bounds__(256) void k_sumunit(const void* h, long long ld_h, const void* Wsum,
-                                                 int B, int d, int r, float* logw, const LatentArgs la) {
+__global__ __launch_bounds__(1024) void k_sumunit(const void* h, long long ld_h, const void* Wsum,
+                                                  int B, int d, int r, float* logw, const LatentArgs la) {
   __shared__ float sc[128];
   const int b = blockIdx.x;
-  sumunit_position<BF16>(h, ld_h, Wsum, b, d, r, sc);
+  sumunit_position<BF16, 16>(h, ld_h, Wsum, b, d, r, sc);
   if ((int)threadIdx.x < r) logw[(long long)b * r + threadIdx.x] = sc[threadIdx.x];
   if (la.zleaf != nullptr)
-    for (int s = threadIdx.x >> 6; s < la.S; s += 4) draft_latents(la, b, s, sc, threadIdx.x & 63);
+    for (int s = threadIdx.x >> 6; s < la.S; s += 16) draft_latents(la, b, s, sc, threadIdx.x & 63);
 }
 
 static hipError_t launch_sumunit_small(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
                                        int dtype, float* logw, const LatentArgs& la, hipStream_t st) {
-  dim3 grid(B), block(256);
+  dim3 grid(B), block(1024);
   if (dtype == MTPC_BF16)
     hipLaunchKernelGGL(k_sumunit<true>, grid, block, 0, st, h, ld_h, Wsum, B, d, r, logw, la);
   else
@@ -602,33 +604,39 @@ __global__ __launch_bounds__(256) void k_btree_static(const CircuitArgs a, int G
 // Binary tree with layers shared by all rows and r = 16, 32 or 64 units: the sum layers on the
 // matrix pipe.  A sum layer applied to many rows is the product  S[k][row] = sum_j A[k][j] X[j][row]
 // with X = exp(children's values - their row maximum) (Eq. BTree in the linear domain after a max
-// shift); one wave owns 16 rows and walks the same step program as k_btree_static with
+// shift); a workgroup owns 16 rows and walks the same step program as k_btree_static with
 // v_mfma_f32_16x16x4_f32 (fp32 operands and accumulation).  Lane (row = l % 16, g = l / 16) holds,
 // of its row, the units j = 16 b + 4 g + i (b < R / 16, i < 4): that is at once the B-operand
 // layout of the product (k-index g), the layout its result comes back in (rows 4 g + i of output
-// block b) and four contiguous floats per block in memory - so a value is written to LDS and read
-// back by the same lane, the path value of a prefix walk never leaves registers, and the wave needs
-// no barrier.  The layer of the next step (natural layout A[k][j], 16-byte loads) and the next
-// step's leaf evidence are fetched while the current step multiplies.
-// LDS: (n-1) node values x 16 rows x (R + 4) floats, and the program.
+// block b) and four contiguous floats per block in memory.
+// The workgroup has one wave per block of 16 output units (R / 16 waves, each on a SIMD of its own):
+// every wave forms the whole operand vector X (the exponentials are repeated, the products are
+// not), multiplies it with its own 16 rows of the layer, and stores its 16 results; one barrier
+// per step makes them visible.  The path value of a prefix walk alternates between two slots, so
+// that a wave may store the new one while another still reads the old one.  The wave's rows of
+// a step's layer (natural layout A[k][j], 16-byte loads) and the step's leaf evidence are fetched
+// two steps ahead, into two register sets used alternately; the steps themselves sit in scalar
+// registers, and the lanes of a row combine their maxima and sums with the vector unit's lane swaps.
+// LDS: (n-1) node values and 2 path values x 16 rows x (R + 4) floats, and the program.
 // ---------------------------------------------------------------------------
 template <int R>
-__global__ __launch_bounds__(64) void k_btree_mfma(const CircuitArgs a) {
-  constexpr int NB = R / 16;        // blocks of 16 units
-  constexpr int RS = R + 4;         // row stride of a stored node value (floats; 16-byte aligned rows)
+__global__ __launch_bounds__(4 * R) void k_btree_mfma(const CircuitArgs a) {
+  constexpr int NB = R / 16;        // blocks of 16 units = waves
+  constexpr int RS = R + 4;         // row stride of a stored value (floats; 16-byte aligned rows)
   extern __shared__ __align__(16) float msm[];
   const int n = a.n;
-  const int lane = threadIdx.x, rl = lane & 15, g = lane >> 4;
-  float* nodes = msm;                                   // [n-1][16][RS]
-  TreeStep* prog = (TreeStep*)(msm + (size_t)(n - 1) * 16 * RS);
+  const int lane = threadIdx.x & 63, rl = lane & 15, g = lane >> 4;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* nodes = msm;                                   // [n+1][16][RS]: nodes 0..n-2, path values n-1 and n
+  TreeStep* prog = (TreeStep*)(msm + (size_t)(n + 1) * 16 * RS);
   __shared__ int s_nsteps;
-  if (lane == 0) s_nsteps = build_tree_program(prog, n, a.prefix);
+  if (threadIdx.x == 0) s_nsteps = build_tree_program(prog, n, a.prefix);
   __syncthreads();
-  const int nsteps = s_nsteps;
+  const int nsteps = __builtin_amdgcn_readfirstlane(s_nsteps);
   const long long row = (long long)blockIdx.x * 16 + rl;
   const long long rc = row < a.rows ? row : (long long)a.rows - 1;       // clamped: loads stay in bounds
   const float* e = a.e + rc * n * R + 4 * g;
-  const float* lay = a.layers_nat + (size_t)rl * R + 4 * g;
+  const float* lay = a.layers_nat + (size_t)(16 * wv + rl) * R + 4 * g;   // this wave's 16 rows of a layer
   const size_t lstep = a.L > 1 ? (size_t)R * R : 0;
   float* mine = nodes + (size_t)rl * RS + 4 * g;
   const float ninf = neg_inf();
@@ -637,65 +645,83 @@ __global__ __launch_bounds__(64) void k_btree_mfma(const CircuitArgs a) {
 #pragma unroll
   for (int b = 0; b < NB; ++b) lw[b] = *(const f32x4_t*)(a.logw + (rc / a.T) * R + 16 * b + 4 * g);
 
-  // operands and layer of the step after the current one
-  f32x4_t nxl[NB], nxr[NB], An[NB][NB];
-  auto prefetch = [&](int t) {
+  // A step of the program, the same for every lane: kept in scalar registers.
+  struct Step { int m, lsrc, rsrc, out; };
+  auto read_step = [&](int t) {
+    const int2 raw = *(const int2*)(prog + min(t, nsteps - 1));          // four shorts
+    const int w0 = __builtin_amdgcn_readfirstlane(raw.x), w1 = __builtin_amdgcn_readfirstlane(raw.y);
+    return Step{(short)(w0 & 0xffff), w0 >> 16, (short)(w1 & 0xffff), w1 >> 16};
+  };
+  // Operands of the two steps after the current one, in two register sets used alternately: leaf
+  // evidence (from HBM: a full step of look-ahead is not enough to cover that) and this wave's
+  // rows of the step's layer.
+  f32x4_t nxl[2][NB], nxr[2][NB], An[2][NB];
+  auto prefetch = [&](auto set, int t, const Step& s) {
+    constexpr int P = decltype(set)::value;
     if (t >= nsteps) return;
-    const TreeStep s = prog[t];
     if (s.lsrc >= n - 1) {
 #pragma unroll
-      for (int b = 0; b < NB; ++b) nxl[b] = *(const f32x4_t*)(e + (size_t)(s.lsrc - (n - 1)) * R + 16 * b);
+      for (int b = 0; b < NB; ++b) nxl[P][b] = *(const f32x4_t*)(e + (size_t)(s.lsrc - (n - 1)) * R + 16 * b);
     }
     if (s.rsrc >= n - 1) {
 #pragma unroll
-      for (int b = 0; b < NB; ++b) nxr[b] = *(const f32x4_t*)(e + (size_t)(s.rsrc - (n - 1)) * R + 16 * b);
+      for (int b = 0; b < NB; ++b) nxr[P][b] = *(const f32x4_t*)(e + (size_t)(s.rsrc - (n - 1)) * R + 16 * b);
     }
     if (s.m > 0) {
       const float* A = lay + (size_t)(s.m - 1) * lstep;
 #pragma unroll
-      for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int b2 = 0; b2 < NB; ++b2) An[b][b2] = *(const f32x4_t*)(A + (size_t)16 * b * R + 16 * b2);
+      for (int b2 = 0; b2 < NB; ++b2) An[P][b2] = *(const f32x4_t*)(A + 16 * b2);
     }
   };
 #pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    nxl[b] = nxr[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < 2; ++q)
 #pragma unroll
-    for (int b2 = 0; b2 < NB; ++b2) An[b][b2] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  }
-  prefetch(0);
+    for (int b = 0; b < NB; ++b) nxl[q][b] = nxr[q][b] = An[q][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  f32x4_t pv[NB];
-#pragma unroll
-  for (int b = 0; b < NB; ++b) pv[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  // the values the lanes that share a row hold are combined over g (lanes l, l ^ 16, l ^ 32, l ^ 48)
-  auto row_max = [](float x) { x = fmaxf(x, __shfl_xor(x, 16)); return fmaxf(x, __shfl_xor(x, 32)); };
-  auto row_sum = [](float x) { x += __shfl_xor(x, 16); return x + __shfl_xor(x, 32); };
+  // The lanes that share a row (l, l ^ 16, l ^ 32, l ^ 48) combine their values with the two lane
+  // swaps of the vector unit: after swapping the odd 16-lane rows of one copy with the even rows of
+  // another, the two copies hold both members of every pair; then the same for the 32-lane halves.
+  auto both16 = [](float x, float& p, float& q) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    p = __uint_as_float(r[0]); q = __uint_as_float(r[1]);
+  };
+  auto both32 = [](float x, float& p, float& q) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    p = __uint_as_float(r[0]); q = __uint_as_float(r[1]);
+  };
+  auto row_max = [&](float x) { float p, q; both16(x, p, q); x = fmaxf(p, q); both32(x, p, q); return fmaxf(p, q); };
+  auto row_sum = [&](float x) { float p, q; both16(x, p, q); x = p + q; both32(x, p, q); return p + q; };
 
-  for (int t = 0; t < nsteps; ++t) {
-    const TreeStep st = prog[t];
-    f32x4_t c[NB], Ac[NB][NB];
+  int pcur = 0;                      // slot (n - 1 + pcur) holds the current path value
+  Step cur = read_step(0), nx1 = read_step(1);
+  prefetch(std::integral_constant<int, 0>{}, 0, cur);
+  prefetch(std::integral_constant<int, 1>{}, 1, nx1);
+
+  // one step with the register set `set`; refills that set for step t + 2
+  auto step = [&](auto set, int t) {
+    constexpr int P = decltype(set)::value;
+    const Step st = cur;
+    const Step nx2 = read_step(t + 2);
+    f32x4_t c[NB], Ac[NB];
     {
+      const int lslot = st.lsrc == -1 ? n - 1 + pcur : st.lsrc;
+      const int rslot = st.rsrc == -1 ? n - 1 + pcur : st.rsrc;
       f32x4_t lv[NB], rv[NB];
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
-        if (st.lsrc == -1) lv[b] = pv[b];
-        else if (st.lsrc == -2) lv[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        else if (st.lsrc >= n - 1) lv[b] = nxl[b];
-        else lv[b] = *(const f32x4_t*)(mine + (size_t)st.lsrc * 16 * RS + 16 * b);
-        if (st.rsrc == -1) rv[b] = pv[b];
-        else if (st.rsrc == -2) rv[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        else if (st.rsrc >= n - 1) rv[b] = nxr[b];
-        else rv[b] = *(const f32x4_t*)(mine + (size_t)st.rsrc * 16 * RS + 16 * b);
+        if (st.lsrc == -2) lv[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        else if (st.lsrc >= n - 1) lv[b] = nxl[P][b];
+        else lv[b] = *(const f32x4_t*)(mine + (size_t)lslot * 16 * RS + 16 * b);
+        if (st.rsrc == -2) rv[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        else if (st.rsrc >= n - 1) rv[b] = nxr[P][b];
+        else rv[b] = *(const f32x4_t*)(mine + (size_t)rslot * 16 * RS + 16 * b);
         c[b] = lv[b] + rv[b];
+        Ac[b] = An[P][b];
       }
-#pragma unroll
-      for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int b2 = 0; b2 < NB; ++b2) Ac[b][b2] = An[b][b2];
     }
-    prefetch(t + 1);
+    prefetch(set, t + 2, nx2);
+    cur = nx1;
+    nx1 = nx2;
     if (st.m == 0) {
 #pragma unroll
       for (int b = 0; b < NB; ++b) c[b] += lw[b];
@@ -711,50 +737,47 @@ __global__ __launch_bounds__(64) void k_btree_mfma(const CircuitArgs a) {
     for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int i = 0; i < 4; ++i) c[b][i] = __expf(c[b][i] - ms);        // exp(-inf) = 0; NaN stays NaN
-    if (st.m == 0) {             // root: mixture with log omega
+    if (st.m == 0) {             // root: mixture with log omega (every wave computes it, the first one stores)
       float sum = 0.f;
 #pragma unroll
       for (int b = 0; b < NB; ++b) sum += (c[b][0] + c[b][1]) + (c[b][2] + c[b][3]);
       sum = row_sum(sum);
       const float v = ms + __logf(sum);                                  // log 0 = -inf
-      if (g == 0 && row < a.rows) {
+      if (wv == 0 && g == 0 && row < a.rows) {
         if (a.prefix) a.out[row * n + (-2 - st.out)] = v; else a.out[row] = v;
       }
-      continue;
+      return;                    // nothing stored in LDS: no barrier needed
     }
-    f32x4_t S[NB];
+    f32x4_t S = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      S[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int b2 = 0; b2 < NB; ++b2)
 #pragma unroll
-      for (int b2 = 0; b2 < NB; ++b2)
+      for (int i = 0; i < 4; ++i) S = __builtin_amdgcn_mfma_f32_16x16x4f32(Ac[b2][i], c[b2][i], S, 0, 0, 0);
+    f32x4_t res;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) S[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(Ac[b][b2][i], c[b2][i], S[b], 0, 0, 0);
-    }
-    f32x4_t res[NB];
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) res[b][i] = ms + __logf(S[b][i]);
-    if (st.out >= 0) {
-#pragma unroll
-      for (int b = 0; b < NB; ++b) *(f32x4_t*)(mine + (size_t)st.out * 16 * RS + 16 * b) = res[b];
-    } else {
-#pragma unroll
-      for (int b = 0; b < NB; ++b) pv[b] = res[b];
-    }
+    for (int i = 0; i < 4; ++i) res[i] = ms + __logf(S[i]);
+    // a node's slot is written once, before any step reads it; the path value goes to the slot
+    // that no wave reads during this step
+    const int oslot = st.out >= 0 ? st.out : n - 1 + (pcur ^ 1);
+    *(f32x4_t*)(mine + (size_t)oslot * 16 * RS + 16 * wv) = res;
+    if (st.out < 0) pcur ^= 1;
+    if constexpr (NB > 1) __syncthreads();
+  };
+  for (int t = 0; t < nsteps; t += 2) {
+    step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < nsteps) step(std::integral_constant<int, 1>{}, t + 1);
   }
 }
 
 static size_t btree_mfma_smem(const CircuitArgs& a) {
   if (a.layers_nat == nullptr || (a.r != 16 && a.r != 32 && a.r != 64)) return 0;
-  return (size_t)(a.n - 1) * 16 * (a.r + 4) * 4 + (size_t)tree_program_steps(a.n, a.prefix) * sizeof(TreeStep);
+  return (size_t)(a.n + 1) * 16 * (a.r + 4) * 4 + (size_t)tree_program_steps(a.n, a.prefix) * sizeof(TreeStep);
 }
 
 template <int R>
 static hipError_t launch_btree_mfma_r(const CircuitArgs& a, size_t smem, hipStream_t st) {
   if (hipError_t e = allow_lds<k_btree_mfma<R>>(150 * 1024); e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_btree_mfma<R>, dim3((unsigned)((a.rows + 15) / 16)), dim3(64), smem, st, a);
+  hipLaunchKernelGGL(k_btree_mfma<R>, dim3((unsigned)((a.rows + 15) / 16)), dim3(4 * R), smem, st, a);
   return hipGetLastError();
 }
 

@@ -27,15 +27,18 @@ __device__ __forceinline__ float dot_chunk(const i32x4_t& a, const i32x4_t& b) {
   return s;
 }
 
-// log omega[b][:] into sc[0..r) (LDS, 128 floats) by a workgroup of 256 threads: its 4 waves split
-// the r rows of Wsum, the position's hidden vector stays in registers (up to 8 chunks of 16 bytes
-// per lane per pass: d <= 4096 bf16 / 2048 fp32 in one pass), rows four at a time so that many
-// loads are in flight.  Ends with a barrier: every thread may read sc afterwards.
-template <bool BF16>
+// log omega[b][:] into sc[0..r) (LDS, 128 floats) by a workgroup of NW waves: they split the r rows
+// of Wsum, the position's hidden vector stays in registers (up to 8 chunks of 16 bytes per lane per
+// pass: d <= 4096 bf16 / 2048 fp32 in one pass), Q rows at a time so that many loads are in flight
+// (a workgroup that does nothing else takes 16 waves: one compute unit then has all of a 32 x 4096
+// Wsum in flight at once instead of in two rounds).  Ends with a barrier: every thread may read sc
+// afterwards.
+template <bool BF16, int NW = 4>
 __device__ __forceinline__ void sumunit_position(const void* h, long long ld_h, const void* Wsum, int b, int d, int r,
                                                  float* sc) {
   constexpr int ESZ = BF16 ? 2 : 4;
   constexpr int EPC = 16 / ESZ;
+  constexpr int Q = NW > 4 ? 2 : 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const char* hb = (const char*)h + (long long)b * ld_h * ESZ;
   const int nch = d / EPC;
@@ -47,10 +50,12 @@ __device__ __forceinline__ void sumunit_position(const void* h, long long ld_h, 
       const i32x4_t x = *(const i32x4_t*)(hb + (long long)min(c, nch - 1) * 16);
       hv[t] = c < nch ? x : i32x4_t{0, 0, 0, 0};
     }
-    for (int j0 = wave * 4; j0 < r; j0 += 16) {
-      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int j0 = wave * Q; j0 < r; j0 += NW * Q) {
+      float acc[Q];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < Q; ++q) acc[q] = 0.f;
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
         const int j = min(j0 + q, r - 1);
         const char* wr = (const char*)Wsum + (long long)j * d * ESZ;
 #pragma unroll
@@ -62,7 +67,7 @@ __device__ __forceinline__ void sumunit_position(const void* h, long long ld_h, 
         }
       }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < Q; ++q) {
         const float v = group_sum(acc[q], 64);
         if (lane == 0 && j0 + q < r) { if (c0 == 0) sc[j0 + q] = v; else sc[j0 + q] += v; }
       }
