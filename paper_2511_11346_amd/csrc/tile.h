@@ -119,9 +119,17 @@ __device__ __forceinline__ void tile_of_block(int w, int nbt, int nslab, int& sl
 // compiler's wait-count insertion does not serialise the ring (it cannot tell
 // which stage a later LDS read touches); completion is tracked by hand with
 // vmcnt + barrier.  Nothing else in these kernels uses M0.
+// NT: the non-temporal hint, for bytes that are read once (a weight matrix streamed through a
+// decode-sized call): they then do not push the small operands of the neighbouring kernels (sum-unit
+// weights, the table, the verifier's rows) out of the caches.
+template <bool NT = false>
 __device__ __forceinline__ void load_to_lds(unsigned voff, i32x4_t srd, unsigned soff, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
-               :: "v"(voff), "s"(srd), "s"(soff), "s"(lds_base) : "memory");
+  if constexpr (NT)
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen nt lds"
+                 :: "v"(voff), "s"(srd), "s"(soff), "s"(lds_base) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
+                 :: "v"(voff), "s"(srd), "s"(soff), "s"(lds_base) : "memory");
 }
 
 // Raw buffer resource over [base, base + bytes): reads beyond it return zero.
@@ -167,8 +175,10 @@ __device__ __forceinline__ int swz16(int row) { return (0 - (row >> 2)) & 3; }
 // WPACK: Wp is the stage-major copy of W (mtpc_pack_weights): per slab, the SB bytes that a K stage takes
 // from each of the v rows lie back to back ([stage][row][SB], ld_w is ignored), so a stage of a
 // slab is one contiguous run of v * SB bytes instead of SB bytes from each of v rows d elements apart.
+// STREAMW: every byte of W is read once by the whole launch (one tile of positions): loaded with the
+// non-temporal hint.
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false,
-          bool WPACK = false>
+          bool WPACK = false, bool STREAMW = false>
 __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const void* hp, long long ld_h,
                                           int B, int d, int v, int slab, int b0, char* smem,
                                           typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
@@ -217,7 +227,10 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     if (q < TL::PER || wl < TL::NWL) {
       // a wave-load never straddles the W / h boundary (TV is a multiple of RPL)
       const bool isW = wl * TL::RPL < TL::TV;
-      load_to_lds(voff[q], isW ? srdW : srdH, (WPACK && isW) ? kofsW : kofs, lds0 + buf * TL::STAGE + wl * 1024);
+      if (STREAMW && isW)
+        load_to_lds<true>(voff[q], srdW, WPACK ? kofsW : kofs, lds0 + buf * TL::STAGE + wl * 1024);
+      else
+        load_to_lds(voff[q], isW ? srdW : srdH, (WPACK && isW) ? kofsW : kofs, lds0 + buf * TL::STAGE + wl * 1024);
     }
   };
   auto advance = [&]() {

@@ -164,7 +164,8 @@ void k_unembed(const UnembedArgs a) {
   }
 
   typename FR::blk_t acc[NPB][NVB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16, WPACK>(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0,
+  // the decode-sized tiles (one wave column) are launched with one tile of positions: W is a stream
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16, WPACK, WB == 1>(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0,
                                                              smem, acc);
 
   if constexpr (!SAMPLE) if (a.targets != nullptr) {
