@@ -255,6 +255,8 @@ def test_sum_layers_computed_from_the_hidden_state(family, dtype, B, d, n, r):
 @pytest.mark.parametrize("dtype,B,d,n,r,v", [
     ("f32", 300, 64, 8, 64, 40), ("bf16", 277, 64, 16, 32, 100), ("f32", 513, 32, 4, 16, 33),
     ("bf16", 1000, 32, 32, 16, 20), ("f32", 256, 32, 16, 64, 7),
+    # the longest windows whose node values still fit the LDS of a CU (146 and 150 KB), and 64 tokens
+    ("f32", 270, 32, 32, 64, 5), ("bf16", 260, 32, 64, 32, 3), ("f32", 257, 32, 64, 16, 9),
 ])
 def test_tree_layers_shared_by_all_rows_with_16_32_64_units(dtype, B, d, n, r, v):
     """Batches of at least 256 rows of a tree whose layers are shared and whose r is 16, 32 or 64
