@@ -60,6 +60,13 @@ bool table_in_workspace(const mtpc_head* hd, int S) {      // for a sampling cal
   return table_fits(hd);                                   // else a second pass
 }
 
+// The 256-position tiles of the fused kernel read h from a stage-major copy when one can be made: whole
+// 64-byte stages per row, and all of it behind one 32-bit buffer resource.
+bool stage_major_h_pays(const mtpc_head* hd) {
+  const unsigned long long row = (unsigned long long)hd->d * (hd->dtype == MTPC_BF16 ? 2 : 4);
+  return hd->B > 64 && row % H_STAGE_BYTES == 0 && row * (unsigned long long)hd->B < (1ull << 32);
+}
+
 // most windows per position whose rows B*T*n still index with an int
 long long hd_rows_limit(const mtpc_head* hd) {
   if (!hd || hd->B < 1 || hd->n < 1) return 0x7fffffffLL;      // rejected later by check_head
@@ -68,6 +75,8 @@ long long hd_rows_limit(const mtpc_head* hd) {
 
 struct Plan {           // byte offsets into the workspace
   size_t logw, lay_nat, lay_circ, e, zleaf, lat, logm, table, total;
+  size_t hs;            // stage-major copy of h for the 256-position tiles of the fused kernel
+  bool has_hs;
   size_t lean_total;    // univariate marginals: the plan without the table
   size_t bk_count, bk_slot, bk_rowoff, bk_tileoff, bk_tilebucket, bk_list;
   size_t rowlogits;     // compact table of the few-drafts path   // buckets of the token draws (large batches)
@@ -132,6 +141,8 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
   p.logw = take(B * r * 4);
+  p.has_hs = (op == MTPC_OP_LOGLIK || op == MTPC_OP_MARGINALS || op == MTPC_OP_WINDOWS) && stage_major_h_pays(hd);
+  p.hs = p.has_hs ? take(B * (size_t)hd->d * (hd->dtype == MTPC_BF16 ? 2 : 4)) : 0;
   const bool sample = op == MTPC_OP_SAMPLE;
   const bool uni = op == MTPC_OP_MARGINALS && mode == MTPC_MARG_UNIVARIATE;
   const bool verify = op == MTPC_OP_VERIFY;
@@ -215,6 +226,15 @@ UnembedArgs unembed_args(const mtpc_head* hd) {
   return u;
 }
 
+// the stage-major copy of h into the workspace (when the plan has room for it) and into the arguments
+hipError_t stage_major_h(const mtpc_head* hd, bool have, size_t off, UnembedArgs& u, hipStream_t st) {
+  if (!have) return hipSuccess;
+  const int esz = hd->dtype == MTPC_BF16 ? 2 : 4;
+  void* dst = (char*)hd->workspace + off;
+  u.hs = dst;
+  return launch_pack_rows(hd->h, dst, 1, hd->B, hd->d * esz, (long long)hd->ld_h * esz, H_STAGE_BYTES, st);
+}
+
 // sum-unit parameters shared by all ops
 // `draws` (sampling calls of a few positions): the launch that computes the sum units goes on to
 // draw the latents, after the layers those draws read; returns with *draws_done set then.
@@ -277,6 +297,7 @@ mtpc_status run_evidence_op(int family, const mtpc_head* hd, const mtpc_sumlayer
   if (s != MTPC_OK) return s;
   UnembedArgs u = unembed_args(hd);
   u.targets = targets; u.T = 1; u.e = (float*)(ws + p.e);
+  HIP_TRY(stage_major_h(hd, p.has_hs, p.hs, u, st));
   {
     ProfScope prof(st);
     HIP_TRY(launch_unembed(u, hd->dtype, st));
@@ -314,6 +335,7 @@ mtpc_status run_univariate(int family, const mtpc_head* hd, const mtpc_sumlayers
   if (family == MTPC_FF || p.has_table) {
     UnembedArgs t = unembed_args(hd);
     t.logphi = family == MTPC_FF ? out : (float*)(ws + p.table);
+    HIP_TRY(stage_major_h(hd, p.has_hs, p.hs, t, st));
     {
       ProfScope prof(st);
       HIP_TRY(launch_unembed(t, hd->dtype, st));
@@ -461,6 +483,7 @@ mtpc_status run_window_scores(int family, const mtpc_head* hd, const mtpc_sumlay
   if (s != MTPC_OK) return s;
   UnembedArgs u = unembed_args(hd);
   u.targets = x; u.T = T; u.targets2 = x2; u.T2 = T2; u.e = (float*)(ws + p.e);
+  HIP_TRY(stage_major_h(hd, p.has_hs, p.hs, u, st));
   {
     ProfScope prof(st);
     HIP_TRY(launch_unembed(u, hd->dtype, st));
@@ -529,6 +552,8 @@ mtpc_status run_verify(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
 // to Mlay (a multiple of 64) and L*r*r layer logits; ldM pads the total to a multiple of 32.
 struct BwdPlan {
   size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, Gpart, ct, adj, phi, partial, dlog32, total;
+  size_t hs;                // stage-major copy of h for the forward pass
+  bool has_hs;
   int ksplit, kchunk;       // split of the dh contraction over K (few output tiles)
   bool keep_phi;            // probabilities kept by the forward pass (else the logits are recomputed)
   bool ctx;                 // layers computed from h, one set per position
@@ -563,6 +588,8 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
   q.dL = take(B * q.ldM * esz);
   q.WT = take((size_t)hd->d * q.ldM * esz);
   q.hT = take((size_t)hd->d * q.ldb * esz);
+  q.has_hs = stage_major_h_pays(hd);
+  q.hs = q.has_hs ? take(B * (size_t)hd->d * esz) : 0;
   q.steps = family == MTPC_BTREE ? tree_program_steps(hd->n, 1) : L;
   if (L > 0) {
     const size_t lay = ((q.ctx || q.perpos) ? B : 1) * (size_t)q.Lst * r * r * 4;
@@ -661,6 +688,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   UnembedArgs u = unembed_args(hd);
   u.targets = targets; u.T = 1; u.e = (float*)(ws + q.e);
   if (q.keep_phi) { u.phiT = (float*)(ws + q.phi); u.ld_phi = q.ldb; }
+  HIP_TRY(stage_major_h(hd, q.has_hs, q.hs, u, st));
   HIP_TRY(launch_unembed(u, hd->dtype, st));
 
   // ---- reverse pass through the circuit
@@ -979,8 +1007,8 @@ mtpc_status mtpc_pack_weights(const mtpc_head* head, void* W_stage_major) {
   if ((uintptr_t)W_stage_major & 15) return MTPC_ERR_UNSUPPORTED;
   const long long row_bytes = (long long)head->d * (head->dtype == MTPC_BF16 ? 2 : 4);
   if (row_bytes % PACK_STAGE_BYTES != 0) return MTPC_ERR_UNSUPPORTED;
-  if (launch_pack_W(head->W, W_stage_major, (long long)head->n * head->r, head->v, (int)row_bytes, PACK_STAGE_BYTES,
-                    (hipStream_t)head->stream) != hipSuccess)
+  if (launch_pack_rows(head->W, W_stage_major, (long long)head->n * head->r, head->v, (int)row_bytes, row_bytes,
+                       PACK_STAGE_BYTES, (hipStream_t)head->stream) != hipSuccess)
     return MTPC_ERR_HIP;
   return MTPC_OK;
 }

@@ -21,6 +21,9 @@ struct UnembedArgs {
   const void* W;        // [n*r][v][d]
   const void* Wp;       // stage-major copy of W in 128-byte stages (mtpc_pack_weights) or nullptr; read instead
                         // of W by the decode tiles (B <= 64) when a row is a multiple of 128 bytes
+  const void* hs;       // stage-major copy of h in 64-byte stages, [d*esz/64][B][64 bytes] (launch_pack_rows), or
+                        // nullptr; read instead of h by the 256-position tiles (B > 64): a stage of a tile is then
+                        // one run of 16 KB and the L2 is asked for whole 128-byte lines
   int B, d, v, n, r;
   // evidence: e[(b*T+t)][i][j] = l[x] - LSE for target window t of position b
   const int* targets;   // [B][T][n] or nullptr
@@ -73,7 +76,12 @@ hipError_t launch_ctx_layers(const CtxLayerArgs& a, int dtype, hipStream_t st);
 
 hipError_t launch_unembed(const UnembedArgs& a, int dtype, hipStream_t st);
 // dst[slab][stage][row][stage_bytes] = the stage_bytes of row `row` of slab `slab` of W that K stage `stage` covers
-hipError_t launch_pack_W(const void* W, void* dst, long long slabs, int v, int row_bytes, int stage_bytes, hipStream_t st);
+// Stage-major copy of `slabs` matrices of v rows (row_bytes used bytes, row_stride bytes apart): per matrix
+// [row_bytes / stage_bytes][v][stage_bytes].  W for the decode tiles (128-byte stages), h for the
+// 256-position tiles (one matrix, 64-byte stages).
+hipError_t launch_pack_rows(const void* src, void* dst, long long slabs, int v, int row_bytes, long long row_stride,
+                            int stage_bytes, hipStream_t st);
+constexpr int H_STAGE_BYTES = 64;
 constexpr int PACK_STAGE_BYTES = 128;
 hipError_t launch_univariate(const UnivariateArgs& a, int dtype, hipStream_t st);
 

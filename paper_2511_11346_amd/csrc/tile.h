@@ -175,6 +175,8 @@ __device__ __forceinline__ int swz16(int row) { return (0 - (row >> 2)) & 3; }
 // WPACK: Wp is the stage-major copy of W (mtpc_pack_weights): per slab, the SB bytes that a K stage takes
 // from each of the v rows lie back to back ([stage][row][SB], ld_w is ignored), so a stage of a
 // slab is one contiguous run of v * SB bytes instead of SB bytes from each of v rows d elements apart.
+// hs (not with GATHER): the stage-major copy of all of h in stages of SB bytes, [d*esz/SB][B][SB]; the tile's
+// rows of a stage are then one contiguous run, read instead of hp.
 // STREAMW: every byte of W is read once by the whole launch (one tile of positions): loaded with the
 // non-temporal hint.
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false,
@@ -182,7 +184,8 @@ template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER
 __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const void* hp, long long ld_h,
                                           int B, int d, int v, int slab, int b0, char* smem,
                                           typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
-                                          const int* rows = nullptr, int nrows = 0, int rdiv = 1) {
+                                          const int* rows = nullptr, int nrows = 0, int rdiv = 1,
+                                          const void* hs = nullptr) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
   using FR = Frag<M16>;
   static_assert(!M16 || (BF16 && NS >= 3 && TL::NW == 8 && SB == 64),
@@ -203,8 +206,10 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   const i32x4_t srdW = WPACK ? make_srd((const char*)Wp + (long long)slab * v * d * ESZ, (unsigned)((long long)v * d * ESZ))
                              : make_srd((const char*)Wp + (long long)slab * v * ld_w * ESZ,
                                         (unsigned)((long long)(v - 1) * ld_w * ESZ + (long long)d * ESZ));
-  const i32x4_t srdH = make_srd((const char*)hp + (long long)hbase * ld_h * ESZ,
-                                (unsigned)((long long)(hspan - 1) * ld_h * ESZ + (long long)d * ESZ));
+  const bool hpk = !GATHER && hs != nullptr;         // workgroup-uniform
+  const i32x4_t srdH = hpk ? make_srd(hs, (unsigned)((long long)B * d * ESZ))
+                           : make_srd((const char*)hp + (long long)hbase * ld_h * ESZ,
+                                      (unsigned)((long long)(hspan - 1) * ld_h * ESZ + (long long)d * ESZ));
   // wave-load q of this wave covers LDS rows RPL*wl .. RPL*wl+RPL-1 of every stage
   unsigned voff[TL::LPW];
 #pragma unroll
@@ -216,12 +221,14 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     else {
       int hr = min(row - TL::TV, hrows - 1);
       if constexpr (GATHER) hr = min(max(rows[hr] / rdiv, 0), B - 1);
-      voff[q] = (unsigned)hr * (unsigned)(ld_h * ESZ) + ch * 16;
+      voff[q] = hpk ? (unsigned)(b0 + hr) * SB + ch * 16 : (unsigned)hr * (unsigned)(ld_h * ESZ) + ch * 16;
     }
   }
   const unsigned lds0 = (unsigned)(size_t)smem;
   unsigned kofs = 0;                                 // byte offset along K of the next stage to issue
   unsigned kofsW = 0;                                // the same for the stage-major W (WPACK)
+  unsigned kofsH = 0;                                // ... and for h, stage-major or not
+  const unsigned hstep = hpk ? (unsigned)B * SB : (unsigned)SB;
   auto issue_one = [&](int q, int buf) {   // q-th wave-load of this wave for one stage
     const int wl = wave + q * TL::NW;
     if (q < TL::PER || wl < TL::NWL) {
@@ -230,12 +237,13 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
       if (STREAMW && isW)
         load_to_lds<true>(voff[q], srdW, WPACK ? kofsW : kofs, lds0 + buf * TL::STAGE + wl * 1024);
       else
-        load_to_lds(voff[q], isW ? srdW : srdH, (WPACK && isW) ? kofsW : kofs, lds0 + buf * TL::STAGE + wl * 1024);
+        load_to_lds(voff[q], isW ? srdW : srdH, isW ? (WPACK ? kofsW : kofs) : kofsH, lds0 + buf * TL::STAGE + wl * 1024);
     }
   };
   auto advance = [&]() {
     kofs += SB;
     if constexpr (WPACK) kofsW += (unsigned)v * SB;
+    kofsH += hstep;
   };
   auto issue = [&](int buf) {
 #pragma unroll

@@ -166,7 +166,8 @@ void k_unembed(const UnembedArgs a) {
   typename FR::blk_t acc[NPB][NVB];
   // the decode-sized tiles (one wave column) are launched with one tile of positions: W is a stream
   tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16, WPACK, WB == 1>(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0,
-                                                             smem, acc);
+                                                             smem, acc, nullptr, 0, 1,
+                                                             (WB != 1 && SB == H_STAGE_BYTES) ? a.hs : nullptr);
 
   if constexpr (!SAMPLE) if (a.targets != nullptr) {
 #pragma unroll
@@ -777,26 +778,26 @@ static hipError_t launch_dt(const UnembedArgs& a, hipStream_t st) {
   return launch_dec<2, 1, BF16, SAMPLE>(a, row_bytes, st);
 }
 
-// Stage-major copy of W: one thread moves 16 bytes; a workgroup's reads cover 256 / (SB / 16) rows of
+// Stage-major copy of a matrix: one thread moves 16 bytes; a workgroup's reads cover 256 / (SB / 16) rows of
 // one stage (SB contiguous bytes each), its writes one contiguous run.
-__global__ __launch_bounds__(256) void k_pack_W(const char* __restrict__ W, char* __restrict__ dst, long long slabs, int v,
-                                                int row_bytes, int stage_bytes) {
-  const int cps = stage_bytes / 16, stages = row_bytes / stage_bytes;
+__global__ __launch_bounds__(256) void k_pack_rows(const char* __restrict__ src, char* __restrict__ dst, long long slabs, int v,
+                                                   int row_bytes, long long row_stride, int stage_bytes) {
+  const int cps = stage_bytes / 16;
   const long long per_slab = (long long)v * row_bytes / 16;            // 16-byte chunks of a slab
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;       // chunk index in the packed order
   if (t >= slabs * per_slab) return;
   const long long slab = t / per_slab, u = t - slab * per_slab;
   const int stage = (int)(u / ((long long)v * cps)), w = (int)(u - (long long)stage * v * cps);
   const int row = w / cps, ch = w - row * cps;
-  (void)stages;
-  const i32x4_t x = *(const i32x4_t*)(W + (slab * v + row) * row_bytes + (long long)stage * stage_bytes + ch * 16);
+  const i32x4_t x = *(const i32x4_t*)(src + (slab * v + row) * row_stride + (long long)stage * stage_bytes + ch * 16);
   *(i32x4_t*)(dst + t * 16) = x;
 }
 
-hipError_t launch_pack_W(const void* W, void* dst, long long slabs, int v, int row_bytes, int stage_bytes, hipStream_t st) {
+hipError_t launch_pack_rows(const void* src, void* dst, long long slabs, int v, int row_bytes, long long row_stride,
+                            int stage_bytes, hipStream_t st) {
   const long long chunks = slabs * v * (row_bytes / 16);
-  hipLaunchKernelGGL(k_pack_W, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, (const char*)W, (char*)dst, slabs, v,
-                     row_bytes, stage_bytes);
+  hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, (const char*)src, (char*)dst,
+                     slabs, v, row_bytes, row_stride, stage_bytes);
   return hipGetLastError();
 }
 

@@ -75,6 +75,7 @@ hipError_t launch_unembed(const UnembedArgs& a, int dtype, hipStream_t) {
   need(a.h, strided(a.B, a.ld_h, a.d, esz(dtype)), "unembed h");
   need(a.W, (u64)a.n * a.r * a.v * a.d * esz(dtype), "unembed W");
   opt(a.Wp, (u64)a.n * a.r * a.v * a.d * esz(dtype), "unembed stage-major W");
+  opt(a.hs, (u64)a.B * a.d * esz(dtype), "unembed stage-major h");
   if (a.targets) {
     need(a.targets, (u64)a.B * a.T * a.n * 4, "unembed targets");
     opt(a.targets2, (u64)a.B * a.T2 * a.n * 4, "unembed targets2");
@@ -266,10 +267,11 @@ hipError_t launch_dwsum(const void* gT, const void* hT, long long ldb, int r, in
   need(out, (u64)r * d * 4, "dwsum out");
   return ok();
 }
-hipError_t launch_pack_W(const void* W, void* dst, long long slabs, int v, int row_bytes, int stage_bytes, hipStream_t) {
-  if (row_bytes % stage_bytes != 0) { std::fprintf(stderr, "pack: ragged stages\n"); std::abort(); }
-  need(W, (u64)slabs * v * row_bytes, "pack W");
-  need(dst, (u64)slabs * v * row_bytes, "pack dst");
+hipError_t launch_pack_rows(const void* src, void* dst, long long slabs, int v, int row_bytes, long long row_stride,
+                            int stage_bytes, hipStream_t) {
+  if (row_bytes % stage_bytes != 0 || row_stride < row_bytes) { std::fprintf(stderr, "pack: ragged stages\n"); std::abort(); }
+  need(src, (u64)(slabs * v - 1) * row_stride + row_bytes, "pack source");
+  need(dst, (u64)slabs * v * row_bytes, "pack destination");
   return ok();
 }
 hipError_t launch_philox_uniforms(int B, int S, int slots, uint32_t, uint32_t, uint32_t, float* out, hipStream_t) {
