@@ -221,21 +221,34 @@ def main():
             profile_unembed(None, None)
             profile_circuit(None, None)
 
-    for k in range(args.warmup):
-        step(k)
-    torch.cuda.synchronize()
-    k1_pairs, k2_pairs = ev.pairs(args.steps), ev.pairs(args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(k, k1_pairs, k2_pairs)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_step = dt * 1e3 / args.steps
-    k1_ms = ev.mean_ms(k1_pairs)
-    k2_ms = ev.mean_ms(k2_pairs)
+    def timed_steps():
+        for k in range(args.warmup):
+            step(k)
+        torch.cuda.synchronize()
+        k1_pairs, k2_pairs = ev.pairs(args.steps), ev.pairs(args.steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(k, k1_pairs, k2_pairs)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        return dt * 1e3 / args.steps, ev.mean_ms(k1_pairs), ev.mean_ms(k2_pairs)
 
     flops = 2.0 * B * n * r * v * d
+    # First the same steps on W's own rows (the layout a training loop has, whose W changes every
+    # step), for the record; then the figures of the line: this workload drafts and scores with fixed
+    # weights, so - like the decode workload below - it reads the stage-major copy of W that serving
+    # makes once (mtpc_pack_weights, 64-byte stages for batches above 64 positions; same results bit
+    # for bit).
+    ms_rows, k1_rows, _ = timed_steps()
+    row_major = {"ms_per_step": ms_rows, "windows_per_s": B / (ms_rows * 1e-3), "k_unembed_ms": k1_rows,
+                 "frac_of_mfma_peak": flops / (k1_rows * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    head.pack_W()
+    torch.cuda.synchronize()
+    ms_pack = (time.perf_counter() - t0) * 1e3
+    ms_step, k1_ms, k2_ms = timed_steps()
     achieved = flops / (k1_ms * 1e-3) / 1e12
     esz = 2
     roofline = {"bound": "mfma",
@@ -273,8 +286,11 @@ def main():
                                "(8.246 TFLOP per pass over W); step = sum units + 1 draft per position (tokens drawn "
                                "through buckets of their input unit) + prefix marginals (last = loglik) of the targets "
                                "and of the draft in one fused unembedding pass + circuit layers",
-                   **WORKLOAD, "S": S},
+                   **WORKLOAD, "S": S,
+                   "W_layout": "stage-major copy in 64-byte stages (mtpc_pack_weights, once per set of weights: "
+                               f"{ms_pack:.2f} ms including its allocation); `row_major_W` = the same steps on W's own rows"},
         "roofline": roofline,
+        "row_major_W": row_major,
         "circuit_kernel": circuit,
         "input_generation_s": t_gen,
     }
@@ -299,8 +315,11 @@ def main():
                      "univariate_marginals_call": ms_uni,
                      "k_unembed_of_loglik_call": k1_lik, "circuit_kernel_of_loglik_call": k2_lik,
                      "circuit_kernel_of_prefix_marginals_call": k2_marg}
+    out["ops_ms"]["W_layout"] = "stage-major copy, as in the timed steps"
     out["loglik_windows_per_s"] = B / (ms_lik * 1e-3)
     out["loglik_k_unembed_frac_of_mfma_peak"] = flops / (k1_lik * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+    # (a training loop changes W every step: it reads W's own rows)
+    head.W_stage_major, head.W_stage_bytes = None, 0
     # training step of the same workload (Sec. 4.1 loss + gradients w.r.t. h, W, Wsum, layers): the
     # forward product (its probabilities are kept) and the two contractions = 3 passes of `flops`
     coef = (torch.full((B, n), 1.0 / B, device=dev) * 0.8 ** torch.arange(n, device=dev)).contiguous()
@@ -328,10 +347,13 @@ def main():
         Bc, nc = inp_c.B, inp_c.n
         fl = 2.0 * Bc * nc * inp_c.r * inp_c.v * inp_c.d
         Pc = torch.empty(Bc, nc, dtype=torch.float32, device=dev)
+        k1_rows = kernel_ms(lambda: hd.prefix_marginals(tgc, out=Pc), profile_unembed)
+        hd.pack_W()               # fixed weights: the stage-major copy from here on, as in the headline
         k1 = kernel_ms(lambda: hd.prefix_marginals(tgc, out=Pc), profile_unembed)
         k2 = kernel_ms(lambda: hd.prefix_marginals(tgc, out=Pc), profile_circuit)
         e = {"config": name, "flop_per_launch": fl, "k_unembed_ms": k1,
              "achieved_TFLOPs": fl / (k1 * 1e-3) / 1e12, "frac_of_mfma_peak": fl / (k1 * 1e-3) / 1e12 / peak,
+             "row_major_W": {"k_unembed_ms": k1_rows, "frac_of_mfma_peak": fl / (k1_rows * 1e-3) / 1e12 / peak},
              "circuit_kernel_ms": k2,
              "prefix_marginals_call_ms": time_op(lambda: hd.prefix_marginals(tgc, out=Pc)),
              }

@@ -73,11 +73,13 @@ typedef struct {
   size_t workspace_bytes;
   void* stream;           /* hipStream_t                                                  */
   const void* W_stage_major; /* optional (NULL: none): the copy of W that mtpc_pack_weights makes.   */
-                          /* Decode-sized calls (B <= 64) of mtpc_*_sample / *_greedy_draft /  */
-                          /* *_loglik / *_marginals / *_window_scores whose rows of W are a     */
-                          /* multiple of 128 bytes stream it instead of W (same results, bit    */
-                          /* for bit; 3-5 % less time on the HBM-bound pass).  W must be valid  */
-                          /* as well: every other path reads W.                                 */
+                          /* The pass over all of W in mtpc_*_sample / *_greedy_draft /         */
+                          /* *_loglik / *_marginals / *_window_scores / *_loss_backward reads it */
+                          /* instead of W when its stages are the ones that pass uses: 128      */
+                          /* bytes for B <= 64, 64 bytes for larger batches (same results, bit  */
+                          /* for bit; 3-5 % less time).  A copy with the other stage size is    */
+                          /* ignored.  W must be valid as well: every other path reads W.       */
+  int32_t W_stage_bytes;  /* stage size of that copy: 128 (also meant by 0) or 64               */
 } mtpc_head;
 
 /* r x r sum layers, normalised over the LAST axis (softmax), given either as
@@ -327,14 +329,16 @@ mtpc_status mtpc_btree_loss_backward(const mtpc_head* head, const mtpc_sumlayers
                                      const int32_t* targets, const float* coef, float* loss, float* dh,
                                      float* dW, float* dWsum, float* dlayers, float* dR);
 
-/* Stage-major copy of W for serving (W fixed between calls): per (i, j) slab, the 128 bytes
+/* Stage-major copy of W for serving (W fixed between calls): per (i, j) slab, the S bytes
  * that each of the v rows contributes to a step along d lie back to back,
- *   W_stage_major [n*r][d * esz / 128][v][128 bytes]      (esz = 2 or 4 by head->dtype),
- * so the pass that streams W once (Sec. 3.3: all input units of a handful of positions, bound
- * by the bytes of W) reads long contiguous runs instead of 128 bytes from each of v rows d
- * elements apart.  Needs d * esz to be a multiple of 128 (else MTPC_ERR_UNSUPPORTED); uses
- * head's B, d, n, r, v, dtype, W and stream only; W_stage_major is a device buffer of the size
- * of W, 16-byte aligned.  Hand it to later calls in mtpc_head.W_stage_major. */
+ *   W_stage_major [n*r][d * esz / S][v][S bytes]      (esz = 2 or 4 by head->dtype),
+ * with S = head->W_stage_bytes (128, also meant by 0, or 64).  With 128-byte stages the pass that
+ * streams W once (Sec. 3.3: all input units of a handful of positions, B <= 64, bound by the bytes
+ * of W) reads long contiguous runs instead of 128 bytes from each of v rows d elements apart; with
+ * 64-byte stages the pass of a larger batch asks the caches for whole lines instead of half lines.
+ * Needs d * esz to be a multiple of S (else MTPC_ERR_UNSUPPORTED); uses head's d, n, r, v, dtype, W,
+ * W_stage_bytes and stream only; W_stage_major is a device buffer of the size of W, 16-byte
+ * aligned.  Hand it to later calls in mtpc_head.W_stage_major, with the same W_stage_bytes. */
 mtpc_status mtpc_pack_weights(const mtpc_head* head, void* W_stage_major);
 
 /* The uniforms the sampler consumes, out [B][S][slots] fp32 (device), for tests

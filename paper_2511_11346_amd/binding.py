@@ -33,7 +33,7 @@ class mtpc_head(C.Structure):
                 ("v", C.c_int32), ("dtype", C.c_int32),
                 ("h", C.c_void_p), ("ld_h", C.c_int64), ("W", C.c_void_p), ("Wsum", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
-                ("W_stage_major", C.c_void_p)]
+                ("W_stage_major", C.c_void_p), ("W_stage_bytes", C.c_int32)]
 
 
 class mtpc_sumlayers(C.Structure):
@@ -159,14 +159,19 @@ class Head:
                 self._sl.R, self._sl.R_layer_stride = R.data_ptr(), rls
         self._ws = None
         self.W_stage_major = None
+        self.W_stage_bytes = 0
 
-    def pack_W(self) -> None:
-        """Make the stage-major copy of W (for serving, W fixed) and use it from now on: decode-sized
-        calls stream it instead of W's rows.  Costs one more buffer of the size of W."""
+    def pack_W(self, stage_bytes: Optional[int] = None) -> None:
+        """Make the stage-major copy of W (for serving, W fixed) and use it from now on: the pass over
+        all of W reads it instead of W's rows.  The stage size has to be the one that pass uses for this
+        head's batch (the default): 128 bytes up to 64 positions, 64 bytes above.  Costs one more buffer
+        of the size of W."""
         buf = torch.empty_like(self.W)
         hd = self._head(256)
+        hd.W_stage_major = None
+        hd.W_stage_bytes = stage_bytes if stage_bytes is not None else (128 if self.B <= 64 else 64)
         _check(lib().mtpc_pack_weights(C.byref(hd), buf.data_ptr()))
-        self.W_stage_major = buf
+        self.W_stage_major, self.W_stage_bytes = buf, hd.W_stage_bytes
 
     # ---- plumbing --------------------------------------------------------
     def _head(self, ws_bytes: int) -> mtpc_head:
@@ -181,6 +186,7 @@ class Head:
         hd.workspace, hd.workspace_bytes = self._ws.data_ptr(), self._ws.numel()
         hd.stream = torch.cuda.current_stream(self.h.device).cuda_stream
         hd.W_stage_major = self.W_stage_major.data_ptr() if self.W_stage_major is not None else None
+        hd.W_stage_bytes = self.W_stage_bytes
         return hd
 
     def _layers_ref(self):
@@ -262,6 +268,7 @@ class Head:
         hd.workspace, hd.workspace_bytes = None, 0
         hd.stream = torch.cuda.current_stream(self.h.device).cuda_stream
         hd.W_stage_major = self.W_stage_major.data_ptr() if self.W_stage_major is not None else None
+        hd.W_stage_bytes = self.W_stage_bytes
         _check(lib().mtpc_sample_static(FAMILY[self.family], C.byref(hd), self._layers_ref(), S, seed, offset,
                                         drafts.data_ptr(),
                                         latents.data_ptr() if latents is not None and latents.numel() > 0 else None,

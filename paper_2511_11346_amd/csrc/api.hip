@@ -99,6 +99,8 @@ mtpc_status check_head(int family, const mtpc_head* hd) {
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
   if (((uintptr_t)hd->h | (uintptr_t)hd->W | (uintptr_t)hd->Wsum | (uintptr_t)hd->W_stage_major) & 15) return MTPC_ERR_UNSUPPORTED;
   if (((size_t)hd->ld_h * esz) & 15) return MTPC_ERR_UNSUPPORTED;
+  if (hd->W_stage_major && hd->W_stage_bytes != 0 && hd->W_stage_bytes != 64 && hd->W_stage_bytes != 128)
+    return MTPC_ERR_UNSUPPORTED;
   if ((long long)hd->n * hd->r * hd->v > 0x7fffffffLL) return MTPC_ERR_UNSUPPORTED;
   // a tile (up to 256 rows of h, 320 of W) is addressed through one 32-bit buffer resource
   if ((unsigned long long)hd->ld_h * esz > (1ull << 24) || (unsigned long long)hd->d * esz > (1ull << 23))
@@ -222,6 +224,7 @@ mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayer
 UnembedArgs unembed_args(const mtpc_head* hd) {
   UnembedArgs u{};
   u.h = hd->h; u.ld_h = hd->ld_h; u.W = hd->W; u.Wp = hd->W_stage_major;
+  u.Wp_stage = hd->W_stage_bytes == 0 ? PACK_STAGE_BYTES : hd->W_stage_bytes;
   u.B = hd->B; u.d = hd->d; u.v = hd->v; u.n = hd->n; u.r = hd->r;
   return u;
 }
@@ -1006,9 +1009,10 @@ mtpc_status mtpc_pack_weights(const mtpc_head* head, void* W_stage_major) {
   if (s != MTPC_OK) return s;
   if ((uintptr_t)W_stage_major & 15) return MTPC_ERR_UNSUPPORTED;
   const long long row_bytes = (long long)head->d * (head->dtype == MTPC_BF16 ? 2 : 4);
-  if (row_bytes % PACK_STAGE_BYTES != 0) return MTPC_ERR_UNSUPPORTED;
+  const int stage = head->W_stage_bytes == 0 ? PACK_STAGE_BYTES : head->W_stage_bytes;
+  if ((stage != 64 && stage != 128) || row_bytes % stage != 0) return MTPC_ERR_UNSUPPORTED;
   if (launch_pack_rows(head->W, W_stage_major, (long long)head->n * head->r, head->v, (int)row_bytes, row_bytes,
-                       PACK_STAGE_BYTES, (hipStream_t)head->stream) != hipSuccess)
+                       stage, (hipStream_t)head->stream) != hipSuccess)
     return MTPC_ERR_HIP;
   return MTPC_OK;
 }

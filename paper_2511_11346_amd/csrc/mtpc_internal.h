@@ -19,8 +19,8 @@ struct UnembedArgs {
   const void* h;        // [B][ld_h]
   long long ld_h;       // elements
   const void* W;        // [n*r][v][d]
-  const void* Wp;       // stage-major copy of W in 128-byte stages (mtpc_pack_weights) or nullptr; read instead
-                        // of W by the decode tiles (B <= 64) when a row is a multiple of 128 bytes
+  const void* Wp;       // stage-major copy of W (mtpc_pack_weights) or nullptr, in stages of Wp_stage bytes; read
+  int Wp_stage;         // instead of W by the tiles whose stages have that size: 128 bytes for B <= 64, else 64
   const void* hs;       // stage-major copy of h in 64-byte stages, [d*esz/64][B][64 bytes] (launch_pack_rows), or
                         // nullptr; read instead of h by the 256-position tiles (B > 64): a stage of a tile is then
                         // one run of 16 KB and the L2 is asked for whole 128-byte lines

@@ -751,7 +751,7 @@ template <int WV, int PB, bool BF16, bool SAMPLE>
 static hipError_t launch_dec(const UnembedArgs& a, int row_bytes, hipStream_t st) {
   static_assert(PACK_STAGE_BYTES == 128, "the stage-major copy of W is cut for the 128-byte stages");
   if (row_bytes % 128 == 0) {
-    if (a.Wp != nullptr) return launch_cfg<WV, 1, 2, PB, 128, 3, BF16, SAMPLE, true>(a, st);
+    if (a.Wp != nullptr && a.Wp_stage == 128) return launch_cfg<WV, 1, 2, PB, 128, 3, BF16, SAMPLE, true>(a, st);
     return launch_cfg<WV, 1, 2, PB, 128, 3, BF16, SAMPLE>(a, st);
   }
   return launch_cfg<WV, 1, 2, PB, 64, 4, BF16, SAMPLE>(a, st);
@@ -764,6 +764,11 @@ static hipError_t launch_dt(const UnembedArgs& a, hipStream_t st) {
   // batches, 64- or 32-wide tiles (W streamed once) for decode-sized ones.
   const int row_bytes = a.d * (BF16 ? 2 : 4);
   if (a.B > 64) {
+    if (a.Wp != nullptr && a.Wp_stage == 64) {      // the copy of W in the 64-byte stages of these tiles
+      if (a.v > 256) return launch_cfg<2, 4, 5, 2, 64, 4, BF16, SAMPLE, true>(a, st);
+      if (a.v > 128) return launch_cfg<2, 4, 4, 2, 64, 4, BF16, SAMPLE, true>(a, st);
+      return launch_cfg<2, 4, 2, 2, 64, 4, BF16, SAMPLE, true>(a, st);
+    }
     if (a.v > 256) return launch_cfg<2, 4, 5, 2, 64, 4, BF16, SAMPLE>(a, st);
     if (a.v > 128) return launch_cfg<2, 4, 4, 2, 64, 4, BF16, SAMPLE>(a, st);
     return launch_cfg<2, 4, 2, 2, 64, 4, BF16, SAMPLE>(a, st);

@@ -97,11 +97,17 @@ void run_case(const Case& c, bool with_backward) {
     }
     lyp = &ly;
   }
-  if ((d * es) % 128 == 0) {            // the stage-major copy of W, handed to every later call of the case
+  const int stage = B <= 64 ? 128 : 64;  // the stage size the pass over W uses for this batch
+  if ((d * es) % stage == 0) {          // the stage-major copy of W, handed to every later call of the case
     void* packed = fake(n * r * v * d * es, "stage-major W");
+    hd.W_stage_bytes = stage;
     begin(T + " pack W", hd);
     expect(mtpc_pack_weights(&hd, packed), MTPC_OK, T + " pack W");
     hd.W_stage_major = packed;
+    hd.W_stage_bytes = 96;
+    begin(T + " stage size that does not exist", hd);
+    expect(mtpc_pack_weights(&hd, packed), MTPC_ERR_UNSUPPORTED, T + " stage size that does not exist");
+    hd.W_stage_bytes = stage;
   } else {
     void* packed = fake(n * r * v * d * es, "stage-major W");
     begin(T + " pack W, ragged rows", hd);

@@ -235,20 +235,32 @@ def test_a_handful_of_drafts_without_scores(family, dtype, B, S, d, n, r, v, ctx
 @pytest.mark.parametrize("family,dtype,B,d,n,r,v", [
     ("cp", "bf16", 64, 4096, 16, 32, 320), ("cp", "bf16", 1, 256, 4, 8, 320), ("hmm", "f32", 33, 64, 5, 6, 130),
     ("btree", "bf16", 8, 128, 8, 16, 268), ("ff", "f32", 20, 96, 3, 1, 100),
+    # more than 64 positions: the 256-position tiles, 64-byte stages
+    ("cp", "bf16", 300, 128, 4, 5, 320), ("btree", "f32", 130, 64, 8, 16, 100), ("hmm", "bf16", 513, 96, 3, 4, 200),
 ])
 def test_stage_major_copy_of_W_gives_the_same_bits(family, dtype, B, d, n, r, v):
-    """Decode-sized calls that stream the stage-major copy of W (mtpc_pack_weights) instead of its rows:
-    same products in the same order, so every output is bit-identical - drafts, scores, the table of
-    input units, likelihoods, univariate marginals; batches above 64 positions ignore the copy."""
+    """Calls that read the stage-major copy of W (mtpc_pack_weights) instead of its rows: same products
+    in the same order, so every output is bit-identical - drafts, scores, the table of input units,
+    likelihoods, univariate marginals, the training step.  Up to 64 positions the copy has 128-byte
+    stages, above 64-byte ones; a copy with the other stage size is ignored."""
     inp = mi.make_inputs(family, B=B, d=d, n=n, r=r, v=v, dtype=dtype, seed=60 + n + r, h_scale=1.0)
-    plain, packed = make_head(inp), make_head(inp)
+    plain, packed, other = make_head(inp), make_head(inp), make_head(inp)
     packed.pack_W()
-    # the copy itself: [slab][stage][row][128 bytes]
+    sb = 128 if B <= 64 else 64
+    assert packed.W_stage_bytes == sb
+    # the copy itself: [slab][stage][row][sb bytes]
     es = 2 if dtype == "bf16" else 4
-    stages = d * es // 128
-    want = plain.W.view(torch.uint8).view(n * r, v, stages, 128).permute(0, 2, 1, 3).contiguous()
-    assert torch.equal(packed.W_stage_major.view(torch.uint8).view(n * r, stages, v, 128), want)
+    stages = d * es // sb
+    want = plain.W.view(torch.uint8).view(n * r, v, stages, sb).permute(0, 2, 1, 3).contiguous()
+    assert torch.equal(packed.W_stage_major.view(torch.uint8).view(n * r, stages, v, sb), want)
     tg = torch.from_numpy(inp.targets).cuda()
+    if (d * es) % 128 == 0 or sb == 128:
+        other.pack_W(stage_bytes=192 - sb)      # the other size: made, handed over, not read
+        assert torch.equal(plain.loglik(tg), other.loglik(tg))
+    if B > 64:
+        coef = torch.full((B, n), 1.0 / B, device="cuda")
+        ga, gb = plain.loss_backward(tg, coef), packed.loss_backward(tg, coef)
+        assert all(torch.equal(ga[k], gb[k]) for k in ga if ga[k] is not None)
     assert torch.equal(plain.loglik(tg), packed.loglik(tg))
     assert torch.equal(plain.prefix_marginals(tg), packed.prefix_marginals(tg))
     assert torch.equal(plain.univariate_marginals(), packed.univariate_marginals())
