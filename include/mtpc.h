@@ -77,8 +77,10 @@ typedef struct {
                           /* *_loglik / *_marginals / *_window_scores / *_loss_backward reads it */
                           /* instead of W when its stages are the ones that pass uses: 128      */
                           /* bytes for B <= 64, 64 bytes for larger batches (same results, bit  */
-                          /* for bit; 3-5 % less time).  A copy with the other stage size is    */
-                          /* ignored.  W must be valid as well: every other path reads W.       */
+                          /* for bit; 3-5 % less time), and so do the token draws of a larger   */
+                          /* batch (each from its one slab; 64-byte stages, 6-8 % less time).   */
+                          /* A copy with the other stage size is ignored.  W must be valid as   */
+                          /* well: every other path reads W.                                    */
   int32_t W_stage_bytes;  /* stage size of that copy: 128 (also meant by 0) or 64               */
 } mtpc_head;
 

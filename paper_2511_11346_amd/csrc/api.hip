@@ -426,6 +426,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     HIP_TRY(launch_buckets(bk, st));
     DrawGatherArgs dg{};
     dg.h = hd->h; dg.ld_h = hd->ld_h; dg.W = hd->W;
+    dg.Wp = (hd->W_stage_major && hd->W_stage_bytes == GATHER_STAGE_BYTES) ? hd->W_stage_major : nullptr;
     dg.B = hd->B; dg.S = S; dg.d = hd->d; dg.v = hd->v; dg.n = hd->n; dg.r = hd->r;
     dg.row_off = bk.row_off; dg.tile_off = bk.tile_off; dg.tile_bucket = bk.tile_bucket; dg.list = bk.list;
     dg.drafts = drafts;

@@ -197,6 +197,7 @@ struct DrawGatherArgs {
   const void* h;
   long long ld_h;
   const void* W;
+  const void* Wp;       // stage-major copy of W in the 64-byte stages of these tiles, or nullptr
   int B, S, d, v, n, r;
   const int* row_off;
   const int* tile_off;
@@ -208,6 +209,7 @@ struct DrawGatherArgs {
 };
 hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t st);
 constexpr int DRAW_GATHER_TILE = 128;   // rows per tile of the gathered draw kernel
+constexpr int GATHER_STAGE_BYTES = 64;  // ... and the bytes of a row it takes per stage
 
 // Verification step of a speculative-decoding cycle (Alg. 2, acceptance loop on)
 struct VerifyArgs {

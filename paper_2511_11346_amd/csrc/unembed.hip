@@ -323,13 +323,13 @@ void k_unembed(const UnembedArgs a) {
 }
 
 // stage geometry of the gathered draw tiles and the positions drawn per pass of their draw loop
-constexpr int GATHER_SB = 64, GATHER_NS = 4, GATHER_NSL = 16;
+constexpr int GATHER_SB = GATHER_STAGE_BYTES, GATHER_NS = 4, GATHER_NSL = 16;
 // Token draws of Alg. 1 for training-sized batches: only the input unit a token is drawn
 // from is evaluated.  The (b, s, i) triples were bucketed by (i, z) = (token, selected
 // unit); a workgroup takes up to TP rows of one bucket, gathers their h rows, multiplies
 // them with the one slab W[i][z] and draws every row's token - 1/r of the products a
 // pass over all slabs needs.
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool WPACK>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_draw_gather(const DrawGatherArgs a) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
@@ -353,7 +353,8 @@ void k_draw_gather(const DrawGatherArgs a) {
 
   constexpr bool M16 = use_m16<WV, WB, SB, NS, BF16>();
   typename Frag<M16>::blk_t acc[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, true, M16>(a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, g, 0, smem, acc, rows, nrows, a.S);
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, true, M16, WPACK>(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, g, 0, smem, acc, rows,
+                                                            nrows, a.S);
   float mx[PB * Frag<M16>::SUB], lse[PB * Frag<M16>::SUB];
   tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 
@@ -377,11 +378,13 @@ void k_draw_gather(const DrawGatherArgs a) {
   });
 }
 
-template <int WV, int WB, int VB, int PB, bool BF16>
+template <int WV, int WB, int VB, int PB, bool BF16, bool WPACK = false>
 static hipError_t launch_draw_gather_cfg(const DrawGatherArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, GATHER_SB, GATHER_NS>;
   static_assert(TL::TP == DRAW_GATHER_TILE, "the bucketing kernels count tiles of this many rows");
-  constexpr auto kern = k_draw_gather<WV, WB, VB, PB, GATHER_SB, GATHER_NS, BF16>;
+  if constexpr (!WPACK)
+    if (a.Wp != nullptr) return launch_draw_gather_cfg<WV, WB, VB, PB, BF16, true>(a, st);
+  constexpr auto kern = k_draw_gather<WV, WB, VB, PB, GATHER_SB, GATHER_NS, BF16, WPACK>;
   if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const long long rows = (long long)a.B * a.S * a.n;
   const int grid = (int)(rows / TL::TP) + a.n * a.r;             // >= sum over buckets of ceil(rows_g / TP)

@@ -167,6 +167,7 @@ hipError_t launch_buckets(const BucketArgs& a, hipStream_t) {
 hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t) {
   need(a.h, strided(a.B, a.ld_h, a.d, esz(dtype)), "draw gather h");
   need(a.W, (u64)a.n * a.r * a.v * a.d * esz(dtype), "draw gather W");
+  opt(a.Wp, (u64)a.n * a.r * a.v * a.d * esz(dtype), "draw gather stage-major W");
   bucket_arrays(a.row_off, a.tile_off, a.tile_bucket, a.list, a.B, a.S, a.n, a.r, DRAW_GATHER_TILE);
   need(a.drafts, (u64)a.B * a.S * a.n * 4, "draw gather drafts");
   return ok();

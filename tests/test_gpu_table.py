@@ -269,3 +269,7 @@ def test_stage_major_copy_of_W_gives_the_same_bits(family, dtype, B, d, n, r, v)
     b = packed.sample(2, seed=3, offset=1, want_prefix=True, logphi=tb)
     assert all(torch.equal(x, y) for x, y in zip(a, b)) and torch.equal(ta, tb)
     assert torch.equal(plain.greedy_draft()[0], packed.greedy_draft()[0])
+    # drafts alone: a large batch draws each token from its one slab, gathered (also from the copy)
+    c = plain.sample(2, seed=4, want_prefix=False)
+    e = packed.sample(2, seed=4, want_prefix=False)
+    assert torch.equal(c[0], e[0]) and (c[1] is None or torch.equal(c[1], e[1]))
