@@ -558,6 +558,8 @@ struct BwdPlan {
   size_t logw, e, Ge, dLT, dL, WT, hT, lay_nat, lay_tr, pi, gam, G, Gpart, ct, adj, phi, partial, dlog32, total;
   size_t hs;                // stage-major copy of h for the forward pass
   bool has_hs;
+  size_t hTs;               // stage-major copy of hT for the dW contraction
+  bool has_hTs;
   int ksplit, kchunk;       // split of the dh contraction over K (few output tiles)
   bool keep_phi;            // probabilities kept by the forward pass (else the logits are recomputed)
   bool ctx;                 // layers computed from h, one set per position
@@ -594,6 +596,8 @@ BwdPlan make_bwd_plan(int family, const mtpc_head* hd, const mtpc_sumlayers* ly,
   q.hT = take((size_t)hd->d * q.ldb * esz);
   q.has_hs = stage_major_h_pays(hd);
   q.hs = q.has_hs ? take(B * (size_t)hd->d * esz) : 0;
+  q.has_hTs = (unsigned long long)hd->d * q.ldb * esz < (1ull << 32);
+  q.hTs = q.has_hTs ? take((size_t)hd->d * q.ldb * esz) : 0;
   q.steps = family == MTPC_BTREE ? tree_program_steps(hd->n, 1) : L;
   if (L > 0) {
     const size_t lay = ((q.ctx || q.perpos) ? B : 1) * (size_t)q.Lst * r * r * 4;
@@ -755,6 +759,10 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     HIP_TRY(launch_transpose(t, hd->dtype, st));
   }
   // ---- WT = [W; Wsum; (gap); R]^T [d][ldM], hT = h^T [d][ldb]
+  // WT is read by the dh contraction only, as its 256-row operand: written stage-major straight away
+  // (64-byte stages, [ldM * esz / 64][d][64 bytes]) when one 32-bit buffer resource spans it
+  const bool wt_staged = (unsigned long long)hd->d * q.ldM * esz < (1ull << 32);
+  t.stage_rows = wt_staged ? hd->d : 0;
   t.src = hd->W; t.ld_src = hd->d; t.R = (int)q.M; t.C = hd->d;
   t.dst = ws + q.WT; t.ld_dst = q.ldM; t.col0 = 0; t.Rpad = (int)(family == MTPC_FF ? q.ldM : q.M);
   HIP_TRY(launch_transpose(t, hd->dtype, st));
@@ -768,14 +776,18 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     t.col0 = q.Mlay; t.Rpad = (int)(q.ldM - q.Mlay);
     HIP_TRY(launch_transpose(t, hd->dtype, st));
   }
+  t.stage_rows = 0;                           // hT also feeds the small dWsum kernel: plain, plus a stage-major copy
   t.src = hd->h; t.ld_src = hd->ld_h; t.R = hd->B; t.C = hd->d;
   t.dst = ws + q.hT; t.ld_dst = q.ldb; t.col0 = 0; t.Rpad = (int)q.ldb;
   HIP_TRY(launch_transpose(t, hd->dtype, st));
+  if (q.has_hTs)
+    HIP_TRY(launch_pack_rows(ws + q.hT, ws + q.hTs, 1, hd->d, (int)(q.ldb * esz), q.ldb * (long long)esz, H_STAGE_BYTES, st));
 
   // ---- the two contractions
   GemmArgs m{};
   m.A = ws + q.dL; m.lda = q.ldM; m.M = hd->B;                   // dh[b][k] = sum_m dL[b][m] WT[k][m]
   m.Bm = ws + q.WT; m.ldb = q.ldM; m.N = hd->d; m.K = (int)q.ldM;
+  m.Bs = wt_staged ? ws + q.WT : nullptr;
   m.C = dh; m.ldc = hd->d; m.split = hd->B; m.n2 = 0; m.C2 = nullptr; m.split3 = 0x7fffffff; m.C3 = nullptr;
   m.ksplit = q.ksplit; m.kchunk = q.kchunk; m.partial = q.ksplit > 1 ? (float*)(ws + q.partial) : nullptr;
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
@@ -787,6 +799,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   const bool own_dwsum = family != MTPC_FF && !ctx;
   m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)(own_dwsum ? q.M : q.Mtot);
   m.Bm = ws + q.hT; m.ldb = q.ldb; m.N = hd->d; m.K = (int)q.ldb;
+  m.Bs = q.has_hTs ? ws + q.hTs : nullptr;
   m.C = dW; m.ldc = hd->d;
   m.split = (int)q.M; m.n2 = (family == MTPC_FF || own_dwsum) ? 0 : hd->r; m.C2 = dWsum;
   m.split3 = ctx ? (int)q.Mlay : 0x7fffffff; m.C3 = dR;

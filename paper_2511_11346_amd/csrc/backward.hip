@@ -33,9 +33,14 @@ __global__ __launch_bounds__(256) void k_transpose(const TransposeArgs a) {
   }
   __syncthreads();
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    const int c = c0 + ty + 4 * k, r = r0 + tx;
-    if (c < a.C && r < a.Rpad) dst[(long long)c * a.ld_dst + a.col0 + r] = tile[tx][ty + 4 * k];
+  for (int k0 = 0; k0 < 16; ++k0) {
+    const int c = c0 + ty + 4 * k0, r = r0 + tx;
+    if (c < a.C && r < a.Rpad) {
+      constexpr int EPS = 64 / (int)sizeof(T);         // elements of a row per stage
+      const long long k = a.col0 + r;
+      if (a.stage_rows) dst[(k / EPS * a.stage_rows + c) * EPS + k % EPS] = tile[tx][ty + 4 * k0];
+      else dst[(long long)c * a.ld_dst + k] = tile[tx][ty + 4 * k0];
+    }
   }
 }
 
@@ -72,7 +77,9 @@ __global__ __launch_bounds__(256) void k_transpose_vec(const TransposeArgs a) {
     Vec x;
 #pragma unroll
     for (int t = 0; t < VE; ++t) x.v[t] = tile[tx * VE + t][cc];
-    T* o = dst + (long long)c * a.ld_dst + a.col0 + r;
+    constexpr int EPS = 64 / (int)sizeof(T);           // elements of a row per stage (a multiple of VE)
+    const long long k = a.col0 + r;
+    T* o = a.stage_rows ? dst + (k / EPS * a.stage_rows + c) * EPS + k % EPS : dst + (long long)c * a.ld_dst + k;
     if (r + VE <= a.Rpad) *(Vec*)o = x;
     else
       for (int t = 0; t < VE; ++t)

@@ -129,9 +129,11 @@ void k_gemm_tn(const GemmArgs a) {
   const int rows = min(TL::TV, a.M - slab * TL::TV);
   const int k0 = ks * a.kchunk, klen = min(a.kchunk, a.K - k0);
   typename FR::blk_t acc[NPB][NVB];
+  // (the chunk [k0, k0 + klen) of the stage-major operand is the run of its stages k0 * ESZ / 64 onwards)
+  const char* bs = (a.Bs != nullptr && SB == 64) ? (const char*)a.Bs + (long long)k0 * ESZ / 64 * a.N * 64 : nullptr;
   tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>((const char*)a.A + ((long long)slab * TL::TV * a.lda + k0) * ESZ, a.lda,
                                                       (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0,
-                                                      b0, smem, acc);
+                                                      b0, smem, acc, nullptr, 0, 1, bs);
   const int rbase = wv * VB * 32 + 4 * lgrp;
   // A full tile that lies inside one destination (the common case): one base pointer per
   // column, rows at constant multiples of ldc.

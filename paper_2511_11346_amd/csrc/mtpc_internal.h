@@ -263,6 +263,7 @@ hipError_t launch_grad_from_phi(const GradPhiArgs& a, int dtype, hipStream_t st)
 struct GemmArgs {
   const void* A; long long lda; int M;
   const void* Bm; long long ldb; int N;
+  const void* Bs;       // Bm stage-major, [K * esz / 64][N][64 bytes] (read instead of Bm), or nullptr
   int K;
   float* C; long long ldc;
   // output rows are dealt to up to three buffers: [0, split) -> C, [split, split + n2) -> C2,
@@ -295,6 +296,9 @@ inline int gemm_ksplit(int M, int N, int K) {
 struct TransposeArgs {
   const void* src; long long ld_src; int R, C;
   void* dst; long long ld_dst; long long col0; int Rpad;
+  // 0: dst[c][col0 + r].  Else the destination is stage-major in 64-byte stages with this many rows,
+  // [columns * esz / 64][stage_rows][64 bytes] (the form the contraction kernels read an operand in)
+  int stage_rows;
 };
 hipError_t launch_transpose(const TransposeArgs& a, int dtype, hipStream_t st);
 

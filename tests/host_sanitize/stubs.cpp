@@ -213,6 +213,7 @@ hipError_t launch_grad_from_phi(const GradPhiArgs& a, int dtype, hipStream_t) {
 hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t) {
   need(a.A, strided(a.M, a.lda, a.K, esz(dtype)), "gemm A");
   need(a.Bm, strided(a.N, a.ldb, a.K, esz(dtype)), "gemm B");
+  opt(a.Bs, (u64)a.N * a.K * esz(dtype), "gemm B, stage-major");
   const int r1 = a.M < a.split ? a.M : a.split;
   need(a.C, strided(r1, a.ldc, a.N, 4), "gemm C");
   if (a.n2 > 0) need(a.C2, strided(a.n2, a.ldc, a.N, 4), "gemm C2");
@@ -223,7 +224,13 @@ hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t) {
 hipError_t launch_transpose(const TransposeArgs& a, int dtype, hipStream_t) {
   if (a.C < 1 || a.Rpad < 1) return hipSuccess;
   need(a.src, strided(a.R, a.ld_src, a.C, esz(dtype)), "transpose src");
-  need((const char*)a.dst + (u64)a.col0 * esz(dtype), strided(a.C, a.ld_dst, a.Rpad, esz(dtype)), "transpose dst");
+  if (a.stage_rows) {                     // stage-major destination: whole 64-byte stages of stage_rows rows
+    const u64 eps = 64 / esz(dtype);
+    if (a.stage_rows < a.C) { std::fprintf(stderr, "transpose: bad stage-major destination\n"); std::abort(); }
+    need(a.dst, ((u64)a.col0 + a.Rpad + eps - 1) / eps * a.stage_rows * 64, "transpose dst, stage-major");
+  } else {
+    need((const char*)a.dst + (u64)a.col0 * esz(dtype), strided(a.C, a.ld_dst, a.Rpad, esz(dtype)), "transpose dst");
+  }
   return ok();
 }
 hipError_t launch_circuit_bwd(const CircuitBwdArgs& a, hipStream_t) {
