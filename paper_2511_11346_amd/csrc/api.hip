@@ -731,6 +731,10 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   HIP_TRY(launch_circuit_bwd(c, st));
 
   // ---- logit gradient in both layouts: dLT [.][ldb] and dL = dLT^T [B][ldM]
+  // (stage-major, as the contractions read their 320-row operands, when this kernel writes every element of
+  // both - no layer-logit columns from elsewhere - and one 32-bit buffer resource spans each)
+  const bool grads_staged = q.keep_phi && !ctx && (unsigned long long)q.M * q.ldb * esz < (1ull << 32) &&
+                            (unsigned long long)hd->B * q.ldM * esz < (1ull << 32);
   TransposeArgs t{};
   if (q.keep_phi) {
     GradPhiArgs g{};
@@ -739,6 +743,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
     g.M = q.M; g.Mx = q.Mx; g.ldM = q.ldM; g.ldb = q.ldb;
     g.dl_end = ctx ? q.Mlay : q.ldM;           // the layer-logit columns are written by the reverse pass
     g.dLT = ws + q.dLT; g.dL = ws + q.dL;
+    g.staged = grads_staged;
     HIP_TRY(launch_grad_from_phi(g, hd->dtype, st));
   } else {
     GradLogitsArgs g{};
@@ -788,6 +793,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   m.A = ws + q.dL; m.lda = q.ldM; m.M = hd->B;                   // dh[b][k] = sum_m dL[b][m] WT[k][m]
   m.Bm = ws + q.WT; m.ldb = q.ldM; m.N = hd->d; m.K = (int)q.ldM;
   m.Bs = wt_staged ? ws + q.WT : nullptr;
+  m.As = grads_staged ? ws + q.dL : nullptr; m.As_rows = hd->B;
   m.C = dh; m.ldc = hd->d; m.split = hd->B; m.n2 = 0; m.C2 = nullptr; m.split3 = 0x7fffffff; m.C3 = nullptr;
   m.ksplit = q.ksplit; m.kchunk = q.kchunk; m.partial = q.ksplit > 1 ? (float*)(ws + q.partial) : nullptr;
   HIP_TRY(launch_gemm_tn(m, hd->dtype, st));
@@ -800,6 +806,7 @@ mtpc_status run_backward(int family, const mtpc_head* hd, const mtpc_sumlayers* 
   m.A = ws + q.dLT; m.lda = q.ldb; m.M = (int)(own_dwsum ? q.M : q.Mtot);
   m.Bm = ws + q.hT; m.ldb = q.ldb; m.N = hd->d; m.K = (int)q.ldb;
   m.Bs = q.has_hTs ? ws + q.hTs : nullptr;
+  m.As = grads_staged ? ws + q.dLT : nullptr; m.As_rows = (int)q.M;
   m.C = dW; m.ldc = hd->d;
   m.split = (int)q.M; m.n2 = (family == MTPC_FF || own_dwsum) ? 0 : hd->r; m.C2 = dWsum;
   m.split3 = ctx ? (int)q.Mlay : 0x7fffffff; m.C3 = dR;

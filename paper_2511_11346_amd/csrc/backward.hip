@@ -131,7 +131,9 @@ __global__ __launch_bounds__(256) void k_grad_from_phi(const GradPhiArgs a) {
 #pragma unroll
       for (int c = 0; c < 4; ++c)
         if (b + c < a.B && x[c] != -1) out.v[c] = conv(g[c] * ((av == x[c] ? 1.f : 0.f) - pv[c]));
-      *(Quad*)(dLT + m * a.ldb + b) = out;
+      constexpr int EPS = 64 / (int)sizeof(T);     // elements of a row per stage (b is a multiple of 4)
+      if (a.staged) *(Quad*)(dLT + ((long long)(b / EPS) * a.M + m) * EPS + b % EPS) = out;
+      else *(Quad*)(dLT + m * a.ldb + b) = out;
     } else if (m < a.Mx && col_ok) {
       out = *(const Quad*)(dLT + m * a.ldb + b);   // sum-unit rows, written by the reverse pass
     }
@@ -148,7 +150,9 @@ __global__ __launch_bounds__(256) void k_grad_from_phi(const GradPhiArgs a) {
       Quad out;
 #pragma unroll
       for (int c = 0; c < 4; ++c) out.v[c] = tile[4 * mq + c][bl];
-      *(Quad*)(dL + (long long)(b0 + bl) * a.ldM + m) = out;
+      constexpr int EPS = 64 / (int)sizeof(T);
+      if (a.staged) *(Quad*)(dL + ((m / EPS) * a.B + (b0 + bl)) * EPS + m % EPS) = out;
+      else *(Quad*)(dL + (long long)(b0 + bl) * a.ldM + m) = out;
     }
   }
 }

@@ -107,7 +107,7 @@ hipError_t launch_unembed_grad(const GradLogitsArgs& a, int dtype, hipStream_t s
 }
 
 // ---------------------------------------------------------------------------
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16>
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool ASTAGED>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_gemm_tn(const GemmArgs a) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
@@ -131,9 +131,14 @@ void k_gemm_tn(const GemmArgs a) {
   typename FR::blk_t acc[NPB][NVB];
   // (the chunk [k0, k0 + klen) of the stage-major operand is the run of its stages k0 * ESZ / 64 onwards)
   const char* bs = (a.Bs != nullptr && SB == 64) ? (const char*)a.Bs + (long long)k0 * ESZ / 64 * a.N * 64 : nullptr;
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>((const char*)a.A + ((long long)slab * TL::TV * a.lda + k0) * ESZ, a.lda,
-                                                      (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0,
-                                                      b0, smem, acc, nullptr, 0, 1, bs);
+  if constexpr (ASTAGED)
+    tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16, true>((const char*)a.As + (long long)k0 * ESZ / 64 * a.As_rows * 64, 0,
+                                                              (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0,
+                                                              b0, smem, acc, nullptr, 0, 1, bs, a.As_rows, slab * TL::TV);
+  else
+    tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>((const char*)a.A + ((long long)slab * TL::TV * a.lda + k0) * ESZ, a.lda,
+                                                        (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0,
+                                                        b0, smem, acc, nullptr, 0, 1, bs);
   const int rbase = wv * VB * 32 + 4 * lgrp;
   // A full tile that lies inside one destination (the common case): one base pointer per
   // column, rows at constant multiples of ldc.
@@ -181,10 +186,12 @@ void k_gemm_tn(const GemmArgs a) {
     }
 }
 
-template <int WV, int WB, int VB, int PB, bool BF16>
+template <int WV, int WB, int VB, int PB, bool BF16, bool ASTAGED = false>
 static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t st) {
   using TL = Tile<WV, WB, VB, PB, 64, 4>;
-  constexpr auto kern = k_gemm_tn<WV, WB, VB, PB, 64, 4, BF16>;
+  if constexpr (!ASTAGED)
+    if (a.As != nullptr) return launch_gemm_cfg<WV, WB, VB, PB, BF16, true>(a, st);
+  constexpr auto kern = k_gemm_tn<WV, WB, VB, PB, 64, 4, BF16, ASTAGED>;
   if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nslab = (a.M + TL::TV - 1) / TL::TV, nbt = (a.N + TL::TP - 1) / TL::TP;
   hipLaunchKernelGGL(kern, dim3(nslab * nbt * max(a.ksplit, 1)), dim3(TL::NT), TL::SMEM, st, a);

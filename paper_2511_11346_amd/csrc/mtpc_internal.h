@@ -255,6 +255,10 @@ struct GradPhiArgs {
   long long M, Mx, ldM, ldb;
   long long dl_end;     // dL is written for m < dl_end (a multiple of 4); columns beyond belong to others
   void* dLT; void* dL;
+  // 1: both are written stage-major in 64-byte stages, as the contractions read their 320-row operands:
+  // rows m < M of dLT as [ldb * esz / 64][M][64 bytes] (the sum-unit rows M..Mx-1 stay where they are, behind
+  // it), dL as [ldM * esz / 64][B][64 bytes] (then dl_end = ldM: every column is written here)
+  int staged;
 };
 hipError_t launch_grad_from_phi(const GradPhiArgs& a, int dtype, hipStream_t st);
 
@@ -264,6 +268,8 @@ struct GemmArgs {
   const void* A; long long lda; int M;
   const void* Bm; long long ldb; int N;
   const void* Bs;       // Bm stage-major, [K * esz / 64][N][64 bytes] (read instead of Bm), or nullptr
+  const void* As;       // A stage-major, [K * esz / 64][As_rows][64 bytes] with As_rows >= M (read instead of A), or nullptr
+  int As_rows;
   int K;
   float* C; long long ldc;
   // output rows are dealt to up to three buffers: [0, split) -> C, [split, split + n2) -> C2,

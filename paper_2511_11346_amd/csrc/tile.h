@@ -175,6 +175,8 @@ __device__ __forceinline__ int swz16(int row) { return (0 - (row >> 2)) & 3; }
 // WPACK: Wp is the stage-major copy of W (mtpc_pack_weights): per slab, the SB bytes that a K stage takes
 // from each of the v rows lie back to back ([stage][row][SB], ld_w is ignored), so a stage of a
 // slab is one contiguous run of v * SB bytes instead of SB bytes from each of v rows d elements apart.
+// WPACK with wrows_total > 0: Wp is ONE stage-major matrix of wrows_total rows, [d*esz/SB][wrows_total][SB], of which
+// this workgroup takes rows wrow0 .. wrow0 + v - 1 (slab is ignored).
 // hs (not with GATHER): the stage-major copy of all of h in stages of SB bytes, [d*esz/SB][B][SB]; the tile's
 // rows of a stage are then one contiguous run, read instead of hp.
 // STREAMW: every byte of W is read once by the whole launch (one tile of positions): loaded with the
@@ -185,7 +187,7 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
                                           int B, int d, int v, int slab, int b0, char* smem,
                                           typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
                                           const int* rows = nullptr, int nrows = 0, int rdiv = 1,
-                                          const void* hs = nullptr) {
+                                          const void* hs = nullptr, int wrows_total = 0, int wrow0 = 0) {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
   using FR = Frag<M16>;
   static_assert(!M16 || (BF16 && NS >= 3 && TL::NW == 8 && SB == 64),
@@ -203,7 +205,9 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   const int hrows = GATHER ? nrows : min(B - b0, TL::TP);
   const int hbase = GATHER ? 0 : b0;
   const int hspan = GATHER ? B : hrows;
-  const i32x4_t srdW = WPACK ? make_srd((const char*)Wp + (long long)slab * v * d * ESZ, (unsigned)((long long)v * d * ESZ))
+  const bool wall = WPACK && wrows_total > 0;        // workgroup-uniform
+  const i32x4_t srdW = wall  ? make_srd(Wp, (unsigned)((long long)wrows_total * d * ESZ))
+                       : WPACK ? make_srd((const char*)Wp + (long long)slab * v * d * ESZ, (unsigned)((long long)v * d * ESZ))
                              : make_srd((const char*)Wp + (long long)slab * v * ld_w * ESZ,
                                         (unsigned)((long long)(v - 1) * ld_w * ESZ + (long long)d * ESZ));
   const bool hpk = !GATHER && hs != nullptr;         // workgroup-uniform
@@ -217,7 +221,7 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     const int wl = min(wave + q * TL::NW, TL::NWL - 1);
     const int row = wl * TL::RPL + lane / CPR;
     const int ch = (lane % CPR) ^ (M16 ? swz16(row) : swz<CPR>(row));
-    if (row < TL::TV) voff[q] = (unsigned)min(row, v - 1) * (WPACK ? (unsigned)SB : (unsigned)(ld_w * ESZ)) + ch * 16;
+    if (row < TL::TV) voff[q] = (unsigned)((wall ? wrow0 : 0) + min(row, v - 1)) * (WPACK ? (unsigned)SB : (unsigned)(ld_w * ESZ)) + ch * 16;
     else {
       int hr = min(row - TL::TV, hrows - 1);
       if constexpr (GATHER) hr = min(max(rows[hr] / rdiv, 0), B - 1);
@@ -228,7 +232,10 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   unsigned kofs = 0;                                 // byte offset along K of the next stage to issue
   unsigned kofsW = 0;                                // the same for the stage-major W (WPACK)
   unsigned kofsH = 0;                                // ... and for h, stage-major or not
-  const unsigned hstep = hpk ? (unsigned)B * SB : (unsigned)SB;
+  // (steps along K of the stage-major operands; uniform over the workgroup, which the register allocator
+  // has to be told where they come out of a select)
+  const unsigned hstep = (unsigned)__builtin_amdgcn_readfirstlane((int)(hpk ? (unsigned)B * SB : (unsigned)SB));
+  const unsigned wstep = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)(wall ? wrows_total : v) * SB));
   auto issue_one = [&](int q, int buf) {   // q-th wave-load of this wave for one stage
     const int wl = wave + q * TL::NW;
     if (q < TL::PER || wl < TL::NWL) {
@@ -242,7 +249,7 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
   };
   auto advance = [&]() {
     kofs += SB;
-    if constexpr (WPACK) kofsW += (unsigned)v * SB;
+    if constexpr (WPACK) kofsW += wstep;
     kofsH += hstep;
   };
   auto issue = [&](int buf) {

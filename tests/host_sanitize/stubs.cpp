@@ -214,6 +214,10 @@ hipError_t launch_gemm_tn(const GemmArgs& a, int dtype, hipStream_t) {
   need(a.A, strided(a.M, a.lda, a.K, esz(dtype)), "gemm A");
   need(a.Bm, strided(a.N, a.ldb, a.K, esz(dtype)), "gemm B");
   opt(a.Bs, (u64)a.N * a.K * esz(dtype), "gemm B, stage-major");
+  if (a.As) {
+    if (a.As_rows < a.M) { std::fprintf(stderr, "gemm: stage-major A with too few rows\n"); std::abort(); }
+    need(a.As, (u64)a.As_rows * a.K * esz(dtype), "gemm A, stage-major");
+  }
   const int r1 = a.M < a.split ? a.M : a.split;
   need(a.C, strided(r1, a.ldc, a.N, 4), "gemm C");
   if (a.n2 > 0) need(a.C2, strided(a.n2, a.ldc, a.N, 4), "gemm C2");
