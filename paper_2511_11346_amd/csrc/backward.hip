@@ -126,8 +126,10 @@ __global__ __launch_bounds__(256) void k_grad_from_phi(const GradPhiArgs a) {
           }
         }
       }
-      const float4 ph = *(const float4*)(a.phiT + m * a.ld_phi + b);
-      const float pv[4] = {ph.x, ph.y, ph.z, ph.w};
+      // (the probabilities are read once, here: as a stream)
+      typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+      const f32x4_t ph = __builtin_nontemporal_load((const f32x4_t*)(a.phiT + m * a.ld_phi + b));
+      const float pv[4] = {ph[0], ph[1], ph[2], ph[3]};
 #pragma unroll
       for (int c = 0; c < 4; ++c)
         if (b + c < a.B && x[c] != -1) out.v[c] = conv(g[c] * ((av == x[c] ? 1.f : 0.f) - pv[c]));
