@@ -177,6 +177,12 @@ Plan make_plan(int family, int op, const mtpc_head* hd, const mtpc_sumlayers* ly
     p.has_table = true;
     p.table = take(B * n * r * (size_t)hd->v * 4);
   }
+  // a sampling call whose fused kernel runs on the 256-position tiles: the stage-major copy of h, last, so
+  // that a caller with a workspace of the older size still runs (see prepare)
+  if (sample && stage_major_h_pays(hd) && (want_prefix || caller_table || !buckets_pay(hd, S, want_prefix))) {
+    p.has_hs = true;
+    p.hs = take(B * (size_t)hd->d * (hd->dtype == MTPC_BF16 ? 2 : 4));
+  }
   p.total = off;
   return p;
 }
@@ -213,6 +219,11 @@ mtpc_status prepare(int family, int op, const mtpc_head* hd, const mtpc_sumlayer
   if (hd->workspace_bytes < plan.total) {
     // univariate marginals run without the table when the workspace has no room for it
     const bool uni = op == MTPC_OP_MARGINALS && mode == MTPC_MARG_UNIVARIATE;
+    if (op == MTPC_OP_SAMPLE && plan.has_hs && hd->workspace_bytes >= plan.hs) {
+      plan.has_hs = false;         // sampling without the stage-major copy of h (the last carve)
+      plan.total = plan.hs;
+      return MTPC_OK;
+    }
     if (!uni || !plan.has_table || hd->workspace_bytes < plan.lean_total) return MTPC_ERR_WORKSPACE;
     plan.has_table = false;
     plan.total = plan.lean_total;
@@ -394,6 +405,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   // fused pass with the drafts as targets.
   //   Rows      - k_rows_logits on the n slabs a draft needs, k_draw_table on the compact result
   enum class Draw { InKernel, Buckets, FromTable, Rows };
+  const void* hs_ready = nullptr;            // the stage-major copy of h, once a launch of this call has made it
   const size_t esz = hd->dtype == MTPC_BF16 ? 2 : 4;
   const bool span_ok = (unsigned long long)hd->B * (unsigned long long)hd->ld_h * esz <= 0xffffffffull;
   const Draw draw = (!want_prefix && !logphi && few_drafts(hd, S)) ? Draw::Rows
@@ -435,6 +447,8 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   } else {
     UnembedArgs u = unembed_args(hd);
     u.logphi = table;
+    HIP_TRY(stage_major_h(hd, p.has_hs, p.hs, u, st));
+    hs_ready = u.hs;
     if (draw == Draw::InKernel) {
       u.zleaf = la.zleaf; u.S = S; u.drafts = drafts;
       u.seed_lo = seed_lo; u.seed_hi = seed_hi; u.offset = offset; u.greedy = greedy;
@@ -454,6 +468,8 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   if (want_prefix && !table_scores) {
     UnembedArgs u2 = unembed_args(hd);
     u2.targets = drafts; u2.T = S; u2.e = (float*)(ws + p.e);
+    if (hs_ready != nullptr) u2.hs = hs_ready;
+    else HIP_TRY(stage_major_h(hd, p.has_hs, p.hs, u2, st));
     ProfScope prof(st);
     HIP_TRY(launch_unembed(u2, hd->dtype, st));
   }
