@@ -342,9 +342,9 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     bool act16[2 * PB];
 #pragma unroll
     for (int pb = 0; pb < 2 * PB; ++pb) act16[pb] = !GATHER || wb * PB * 32 + pb * 16 < hrows;
-    // memory cluster of stage `it`: its fragments, and the loads of stage it+NS-1 into the
+    // memory cluster of stage `it`: its fragments, and (LOAD) the loads of stage it+NS-1 into the
     // buffer of stage it-1 (last read before the previous barrier)
-    auto mem_cluster = [&](int it) {
+    auto mem_cluster = [&](int it, auto load) {
       const char* cur = smem + (it % NS) * TL::STAGE;
       if constexpr (M16) {
 #pragma unroll
@@ -355,19 +355,23 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
         load_frags(cur, 0, 0);
         load_frags(cur, 1, 1);
       }
-      if (it + NS - 1 < KI) issue((it + NS - 1) % NS);
+      if constexpr (decltype(load)::value) issue((it + NS - 1) % NS);
       __builtin_amdgcn_sched_barrier(0);
     };
+    // (a branch between two MFMAs costs about as much as an MFMA: empty position blocks are
+    // skipped a whole row of products at a time)
     auto compute_cluster = [&]() {
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_setprio(1);
       if constexpr (M16) {
 #pragma unroll
         for (int pb = 0; pb < 2 * PB; ++pb)
+          if (!GATHER || act16[pb]) {
 #pragma unroll
-          for (int vb = 0; vb < 2 * VB; ++vb) {
-            if (!GATHER || act16[pb]) mma_step<BF16>(acc[pb][vb], ga[vb], gb[pb]);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int vb = 0; vb < 2 * VB; ++vb) {
+              mma_step<BF16>(acc[pb][vb], ga[vb], gb[pb]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
           }
       } else {
         substep(0, 0, nullptr, 0, 0, -1);
@@ -376,10 +380,6 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
       __builtin_amdgcn_s_setprio(0);
       __builtin_amdgcn_sched_barrier(0);
     };
-    // own loads of stage it+1 have landed (stages up to it+NS-1 are issued)
-    auto wait_next = [&](int it) {
-      if (it + NS - 1 < KI) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-    };
     auto barrier = [&]() {
       __builtin_amdgcn_sched_barrier(0);
       __syncthreads();
@@ -387,14 +387,37 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     };
     if (KI > NS - 2) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
     __syncthreads();                        // stage 0 has landed everywhere
-    if (group == 1) __syncthreads();        // start one cluster late
-    for (int it = 0; it < KI; ++it) {
-      mem_cluster(it);
-      if (group == 1) wait_next(it);        // stage it+1 must be complete before the next barrier
-      barrier();
-      compute_cluster();
-      if (group == 0) wait_next(it);
-      barrier();
+    // One copy of the loop per wave group, and the iterations that still issue loads apart from
+    // the last NS-1: no branch but the loop's own between two barriers.  A wave waits for its own
+    // loads of stage it+1 (stages up to it+NS-1 are issued, so all but the (NS-2) youngest stages'
+    // loads have landed) before the barrier after which the other group reads that stage: group 1
+    // at the end of its memory cluster, group 0 after its compute cluster.
+    auto run = [&](auto grp) {
+      constexpr int G = decltype(grp)::value;
+      const int KM = max(KI - (NS - 1), 0);
+      int it = 0;
+      for (; it < KM; ++it) {
+        mem_cluster(it, std::true_type{});
+        if constexpr (G == 1) MTPC_WAIT_VMCNT((NS - 2) * TL::PER);
+        barrier();
+        compute_cluster();
+        if constexpr (G == 0) MTPC_WAIT_VMCNT((NS - 2) * TL::PER);
+        barrier();
+      }
+      for (; it < KI; ++it) {
+        mem_cluster(it, std::false_type{});
+        if constexpr (G == 1) MTPC_WAIT_VMCNT(0);
+        barrier();
+        compute_cluster();
+        if constexpr (G == 0) MTPC_WAIT_VMCNT(0);
+        barrier();
+      }
+    };
+    if (group == 1) {
+      __syncthreads();                      // start one cluster late
+      run(std::integral_constant<int, 1>{});
+    } else {
+      run(std::integral_constant<int, 0>{});
     }
     if (group == 0) __syncthreads();        // pairs with the late start of the other group
   } else if constexpr (NS >= 3) {
