@@ -359,6 +359,23 @@ inline hipError_t allow_lds(int bytes) {
   return e;
 }
 
+// Compute units of the current device (asked once per device).
+inline hipError_t cu_count(int* n) {
+  static std::atomic<int> known[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool slot = dev >= 0 && dev < 64;
+  int v = slot ? known[dev].load(std::memory_order_acquire) : 0;
+  if (v == 0) {
+    e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    if (slot) known[dev].store(v, std::memory_order_release);
+  }
+  *n = v;
+  return hipSuccess;
+}
+
 hipError_t launch_philox_uniforms(int B, int S, int slots, uint32_t seed_lo, uint32_t seed_hi,
                                   uint32_t offset, float* out, hipStream_t st);
 

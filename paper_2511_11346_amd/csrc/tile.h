@@ -166,77 +166,26 @@ __device__ __forceinline__ int swz(int row) {
 // 1^f(8+k) must differ: f = (0, 3, 2, 1).
 __device__ __forceinline__ int swz16(int row) { return (0 - (row >> 2)) & 3; }
 
-// D = W_slab x h_tile^T for one workgroup; on return every wave holds its VB x PB
-// accumulator blocks and all waves have passed a barrier (the ring is free).
-// GATHER: the tile's position rows are not consecutive: row p of the tile is row
-// rows[p] / rdiv of h (p < nrows <= TP, nrows >= 1; b0 is ignored and the whole of h,
-// which must span less than 4 GiB, is one resource).  32-row position blocks past nrows
-// are not multiplied (their accumulators stay zero), so a nearly empty tile is cheap.
-// WPACK: Wp is the stage-major copy of W (mtpc_pack_weights): per slab, the SB bytes that a K stage takes
-// from each of the v rows lie back to back ([stage][row][SB], ld_w is ignored), so a stage of a
-// slab is one contiguous run of v * SB bytes instead of SB bytes from each of v rows d elements apart.
-// WPACK with wrows_total > 0: Wp is ONE stage-major matrix of wrows_total rows, [d*esz/SB][wrows_total][SB], of which
-// this workgroup takes rows wrow0 .. wrow0 + v - 1 (slab is ignored).
-// hs (not with GATHER): the stage-major copy of all of h in stages of SB bytes, [d*esz/SB][B][SB]; the tile's
-// rows of a stage are then one contiguous run, read instead of hp.
-// STREAMW: every byte of W is read once by the whole launch (one tile of positions): loaded with the
-// non-temporal hint.
+// Where the operands of one tile come from, and the direct-to-LDS loads that bring them in: open()
+// describes the tile and issues the first NS-1 stages of its ring, tile_gemm_run() multiplies.  Apart,
+// so that a workgroup that walks several tiles can open the next one (the ring is free once the run
+// has returned) before it turns to the epilogue of the one it has just multiplied.
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false,
           bool WPACK = false, bool STREAMW = false>
-__device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const void* hp, long long ld_h,
-                                          int B, int d, int v, int slab, int b0, char* smem,
-                                          typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
-                                          const int* rows = nullptr, int nrows = 0, int rdiv = 1,
-                                          const void* hs = nullptr, int wrows_total = 0, int wrow0 = 0) {
+struct TileFeed {
   using TL = Tile<WV, WB, VB, PB, SB, NS>;
-  using FR = Frag<M16>;
-  static_assert(!M16 || (BF16 && NS >= 3 && TL::NW == 8 && SB == 64),
-                "16x16 blocks: bf16, two waves per SIMD, one MFMA k-step per 64-byte stage");
-  constexpr int ESZ = BF16 ? 2 : 4;
-  constexpr int CPR = TL::CPR, KS = TL::KS;
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wv = wave % WV, wb = wave / WV;
-  const int l31 = lane & 31, lhalf = lane >> 5;
+  static constexpr int ESZ = BF16 ? 2 : 4;
+  static constexpr int CPR = TL::CPR;
+  i32x4_t srdW, srdH;
+  unsigned voff[TL::LPW];                            // lane offsets of this wave's loads, constant over K
+  unsigned lds0;
+  unsigned kofs;                                     // byte offset along K of the next stage to issue
+  unsigned kofsW;                                    // the same for the stage-major W (WPACK)
+  unsigned kofsH;                                    // ... and for h, stage-major or not
+  unsigned hstep, wstep;
+  int wave, hrows;
 
-  // Two resources: this slab of W (v rows of d, row stride ld_w) and this tile of h (rows b0..).
-  // Lane offsets are relative to them and constant over K; the K advance is the
-  // instruction's scalar offset.  Rows beyond v / B are clamped (in bounds; their
-  // results are masked or never written).
-  const int hrows = GATHER ? nrows : min(B - b0, TL::TP);
-  const int hbase = GATHER ? 0 : b0;
-  const int hspan = GATHER ? B : hrows;
-  const bool wall = WPACK && wrows_total > 0;        // workgroup-uniform
-  const i32x4_t srdW = wall  ? make_srd(Wp, (unsigned)((long long)wrows_total * d * ESZ))
-                       : WPACK ? make_srd((const char*)Wp + (long long)slab * v * d * ESZ, (unsigned)((long long)v * d * ESZ))
-                             : make_srd((const char*)Wp + (long long)slab * v * ld_w * ESZ,
-                                        (unsigned)((long long)(v - 1) * ld_w * ESZ + (long long)d * ESZ));
-  const bool hpk = !GATHER && hs != nullptr;         // workgroup-uniform
-  const i32x4_t srdH = hpk ? make_srd(hs, (unsigned)((long long)B * d * ESZ))
-                           : make_srd((const char*)hp + (long long)hbase * ld_h * ESZ,
-                                      (unsigned)((long long)(hspan - 1) * ld_h * ESZ + (long long)d * ESZ));
-  // wave-load q of this wave covers LDS rows RPL*wl .. RPL*wl+RPL-1 of every stage
-  unsigned voff[TL::LPW];
-#pragma unroll
-  for (int q = 0; q < TL::LPW; ++q) {
-    const int wl = min(wave + q * TL::NW, TL::NWL - 1);
-    const int row = wl * TL::RPL + lane / CPR;
-    const int ch = (lane % CPR) ^ (M16 ? swz16(row) : swz<CPR>(row));
-    if (row < TL::TV) voff[q] = (unsigned)((wall ? wrow0 : 0) + min(row, v - 1)) * (WPACK ? (unsigned)SB : (unsigned)(ld_w * ESZ)) + ch * 16;
-    else {
-      int hr = min(row - TL::TV, hrows - 1);
-      if constexpr (GATHER) hr = min(max(rows[hr] / rdiv, 0), B - 1);
-      voff[q] = hpk ? (unsigned)(b0 + hr) * SB + ch * 16 : (unsigned)hr * (unsigned)(ld_h * ESZ) + ch * 16;
-    }
-  }
-  const unsigned lds0 = (unsigned)(size_t)smem;
-  unsigned kofs = 0;                                 // byte offset along K of the next stage to issue
-  unsigned kofsW = 0;                                // the same for the stage-major W (WPACK)
-  unsigned kofsH = 0;                                // ... and for h, stage-major or not
-  // (steps along K of the stage-major operands; uniform over the workgroup, which the register allocator
-  // has to be told where they come out of a select)
-  const unsigned hstep = (unsigned)__builtin_amdgcn_readfirstlane((int)(hpk ? (unsigned)B * SB : (unsigned)SB));
-  const unsigned wstep = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)(wall ? wrows_total : v) * SB));
-  auto issue_one = [&](int q, int buf) {   // q-th wave-load of this wave for one stage
+  __device__ __forceinline__ void issue_one(int q, int buf) {   // q-th wave-load of this wave for one stage
     const int wl = wave + q * TL::NW;
     if (q < TL::PER || wl < TL::NWL) {
       // a wave-load never straddles the W / h boundary (TV is a multiple of RPL)
@@ -246,17 +195,87 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
       else
         load_to_lds(voff[q], isW ? srdW : srdH, isW ? (WPACK ? kofsW : kofs) : kofsH, lds0 + buf * TL::STAGE + wl * 1024);
     }
-  };
-  auto advance = [&]() {
+  }
+  __device__ __forceinline__ void advance() {
     kofs += SB;
     if constexpr (WPACK) kofsW += wstep;
     kofsH += hstep;
-  };
-  auto issue = [&](int buf) {
+  }
+  __device__ __forceinline__ void issue(int buf) {
 #pragma unroll
     for (int q = 0; q < TL::LPW; ++q) issue_one(q, buf);
     advance();
-  };
+  }
+
+  // Arguments as for tile_gemm.  The ring must be free (no wave still reads it).
+  __device__ __forceinline__ void open(const void* Wp, long long ld_w, const void* hp, long long ld_h,
+                                       int B, int d, int v, int slab, int b0, char* smem,
+                                       const int* rows = nullptr, int nrows = 0, int rdiv = 1,
+                                       const void* hs = nullptr, int wrows_total = 0, int wrow0 = 0) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Two resources: this slab of W (v rows of d, row stride ld_w) and this tile of h (rows b0..).
+    // Lane offsets are relative to them and constant over K; the K advance is the
+    // instruction's scalar offset.  Rows beyond v / B are clamped (in bounds; their
+    // results are masked or never written).
+    hrows = GATHER ? nrows : min(B - b0, TL::TP);
+    const int hbase = GATHER ? 0 : b0;
+    const int hspan = GATHER ? B : hrows;
+    const bool wall = WPACK && wrows_total > 0;        // workgroup-uniform
+    srdW = wall  ? make_srd(Wp, (unsigned)((long long)wrows_total * d * ESZ))
+           : WPACK ? make_srd((const char*)Wp + (long long)slab * v * d * ESZ, (unsigned)((long long)v * d * ESZ))
+                   : make_srd((const char*)Wp + (long long)slab * v * ld_w * ESZ,
+                              (unsigned)((long long)(v - 1) * ld_w * ESZ + (long long)d * ESZ));
+    const bool hpk = !GATHER && hs != nullptr;         // workgroup-uniform
+    srdH = hpk ? make_srd(hs, (unsigned)((long long)B * d * ESZ))
+               : make_srd((const char*)hp + (long long)hbase * ld_h * ESZ,
+                          (unsigned)((long long)(hspan - 1) * ld_h * ESZ + (long long)d * ESZ));
+    // wave-load q of this wave covers LDS rows RPL*wl .. RPL*wl+RPL-1 of every stage
+#pragma unroll
+    for (int q = 0; q < TL::LPW; ++q) {
+      const int wl = min(wave + q * TL::NW, TL::NWL - 1);
+      const int row = wl * TL::RPL + lane / CPR;
+      const int ch = (lane % CPR) ^ (M16 ? swz16(row) : swz<CPR>(row));
+      if (row < TL::TV) voff[q] = (unsigned)((wall ? wrow0 : 0) + min(row, v - 1)) * (WPACK ? (unsigned)SB : (unsigned)(ld_w * ESZ)) + ch * 16;
+      else {
+        int hr = min(row - TL::TV, hrows - 1);
+        if constexpr (GATHER) hr = min(max(rows[hr] / rdiv, 0), B - 1);
+        voff[q] = hpk ? (unsigned)(b0 + hr) * SB + ch * 16 : (unsigned)hr * (unsigned)(ld_h * ESZ) + ch * 16;
+      }
+    }
+    lds0 = (unsigned)(size_t)smem;
+    kofs = 0;
+    kofsW = 0;
+    kofsH = 0;
+    // (steps along K of the stage-major operands; uniform over the workgroup, which the register allocator
+    // has to be told where they come out of a select)
+    hstep = (unsigned)__builtin_amdgcn_readfirstlane((int)(hpk ? (unsigned)B * SB : (unsigned)SB));
+    wstep = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)(wall ? wrows_total : v) * SB));
+    const int KI = d * ESZ / SB;
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < KI) issue(s);
+  }
+};
+
+// The product of a tile whose feed is open: on return every wave holds its VB x PB accumulator blocks and
+// all waves have passed a barrier (the ring is free).
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER, bool M16, bool WPACK, bool STREAMW>
+__device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, BF16, GATHER, M16, WPACK, STREAMW>& feed,
+                                              int d, char* smem,
+                                              typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB]) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  using FR = Frag<M16>;
+  static_assert(!M16 || (BF16 && NS >= 3 && TL::NW == 8 && SB == 64),
+                "16x16 blocks: bf16, two waves per SIMD, one MFMA k-step per 64-byte stage");
+  constexpr int ESZ = BF16 ? 2 : 4;
+  constexpr int CPR = TL::CPR, KS = TL::KS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = feed.wave;
+  const int wv = wave % WV, wb = wave / WV;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int hrows = feed.hrows;
+  auto issue_one = [&](int q, int buf) { feed.issue_one(q, buf); };
+  auto advance = [&]() { feed.advance(); };
+  auto issue = [&](int buf) { feed.issue(buf); };
 
 #pragma unroll
   for (int pb = 0; pb < PB * FR::SUB; ++pb)
@@ -316,9 +335,6 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < KI) issue(s);
 
   if constexpr (NS >= 3 && TL::NW == 8) {
     // Ping-pong schedule for two waves per SIMD.  When both waves of a SIMD have an
@@ -469,6 +485,33 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
     }
   }
   __syncthreads();     // all waves are done reading the ring
+}
+
+// D = W_slab x h_tile^T for one workgroup; on return every wave holds its VB x PB
+// accumulator blocks and all waves have passed a barrier (the ring is free).
+// GATHER: the tile's position rows are not consecutive: row p of the tile is row
+// rows[p] / rdiv of h (p < nrows <= TP, nrows >= 1; b0 is ignored and the whole of h,
+// which must span less than 4 GiB, is one resource).  32-row position blocks past nrows
+// are not multiplied (their accumulators stay zero), so a nearly empty tile is cheap.
+// WPACK: Wp is the stage-major copy of W (mtpc_pack_weights): per slab, the SB bytes that a K stage takes
+// from each of the v rows lie back to back ([stage][row][SB], ld_w is ignored), so a stage of a
+// slab is one contiguous run of v * SB bytes instead of SB bytes from each of v rows d elements apart.
+// WPACK with wrows_total > 0: Wp is ONE stage-major matrix of wrows_total rows, [d*esz/SB][wrows_total][SB], of which
+// this workgroup takes rows wrow0 .. wrow0 + v - 1 (slab is ignored).
+// hs (not with GATHER): the stage-major copy of all of h in stages of SB bytes, [d*esz/SB][B][SB]; the tile's
+// rows of a stage are then one contiguous run, read instead of hp.
+// STREAMW: every byte of W is read once by the whole launch (one tile of positions): loaded with the
+// non-temporal hint.
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false,
+          bool WPACK = false, bool STREAMW = false>
+__device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const void* hp, long long ld_h,
+                                          int B, int d, int v, int slab, int b0, char* smem,
+                                          typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
+                                          const int* rows = nullptr, int nrows = 0, int rdiv = 1,
+                                          const void* hs = nullptr, int wrows_total = 0, int wrow0 = 0) {
+  TileFeed<WV, WB, VB, PB, SB, NS, BF16, GATHER, M16, WPACK, STREAMW> feed;
+  feed.open(Wp, ld_w, hp, ld_h, B, d, v, slab, b0, smem, rows, nrows, rdiv, hs, wrows_total, wrow0);
+  tile_gemm_run(feed, d, smem, acc);
 }
 
 // Softmax statistics of every position column of the tile: max and log-sum-exp

@@ -125,6 +125,113 @@ __device__ __forceinline__ void tile_draws(const typename Frag<M16>::blk_t (&acc
   }
 }
 
+// Draws for every position column of a tile at once, from the accumulators (16x16 blocks): one token per
+// column p < ncols, by inverse CDF (Alg. 1: the smallest token k with u Z < cdf[k]; the last token with
+// positive mass if rounding leaves u Z >= Z) or, greedy, the most likely token (ties: the smallest id).
+// A column's v values lie in 4 lane groups x VB*2 blocks x WV waves; each lane forms the prefix of its own
+// rows (sums over the lane groups by lane permutes, over the blocks in registers, over the waves through
+// LDS) and looks for the crossing among its rows; the smallest crossing row of a column wins (LDS minimum).
+// Three workgroup barriers per tile, all waves busy, nothing dumped to LDS but one sum per column and wave.
+// The stage buffers must be free.  uni(p) gives the uniform of column p, out(p, token) takes the result.
+template <class TL, int WV, int VB, int PB, class Uni, class Out>
+__device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[PB * 2][VB * 2], const float (&mx)[PB * 2], int v,
+                                                char* smem, int ncols, bool greedy, Uni uni, Out out) {
+  constexpr int NPB = PB * 2, NVB = VB * 2;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wv = wave % WV, wb = wave / WV;
+  const int lcol = lane & 15, lgrp = lane >> 4;
+  const int rbase = wv * VB * 32 + 4 * lgrp;
+  float* wsum = (float*)smem;                                        // [WV][TP] sum of a wave's rows of a column
+  int* cand = (int*)(wsum + WV * TL::TP);                            // [TP] smallest crossing row
+  int* lastp = cand + TL::TP;                                        // [TP] last row with positive mass
+  unsigned long long* best = (unsigned long long*)(lastp + TL::TP);  // [TP] greedy: (value, -row)
+  static_assert((WV + 2) * TL::TP * 4 + TL::TP * 8 <= TL::RED_OFF, "fits in the stage buffers");
+  for (int p = tid; p < TL::TP; p += TL::NT) {
+    cand[p] = 0x7fffffff;
+    lastp[p] = -1;
+    best[p] = 0ull;
+  }
+  float e[NPB][NVB][4], ex[NPB][NVB], tot[NPB][NVB];
+#pragma unroll
+  for (int pb = 0; pb < NPB; ++pb) {
+    float colsum = 0.f;
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) e[pb][vb][t] = (rbase + vb * 16 + t < v) ? expf(acc[pb][vb][t] - mx[pb]) : 0.f;
+      const float s4 = ((e[pb][vb][0] + e[pb][vb][1]) + e[pb][vb][2]) + e[pb][vb][3];
+      // inclusive scan over the four lane groups that hold this column (lanes lcol + 16 g)
+      const float u1 = __shfl_up(s4, 16);
+      const float i1 = lgrp >= 1 ? s4 + u1 : s4;
+      const float u2 = __shfl_up(i1, 32);
+      const float incl = lgrp >= 2 ? i1 + u2 : i1;
+      ex[pb][vb] = incl - s4;
+      tot[pb][vb] = __shfl(incl, 48 + lcol);
+      colsum += tot[pb][vb];
+    }
+    if (lgrp == 0) wsum[wv * TL::TP + wb * PB * 32 + pb * 16 + lcol] = colsum;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pb = 0; pb < NPB; ++pb) {
+    const int col = wb * PB * 32 + pb * 16 + lcol;
+    if (greedy) {
+      float bv = -1.f;
+      int br = 0;
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          if (e[pb][vb][t] > bv) { bv = e[pb][vb][t]; br = rbase + vb * 16 + t; }
+      atomicMax(&best[col], ((unsigned long long)__float_as_uint(bv) << 32) | (unsigned)(0x7fffffff - br));
+    } else {
+      float below = 0.f, Z = 0.f;
+#pragma unroll
+      for (int w = 0; w < WV; ++w) {
+        const float x = wsum[w * TL::TP + col];
+        if (w < wv) below += x;
+        Z += x;
+      }
+      const float tgt = uni(col) * Z;
+      float run = below;
+      int first = 0x7fffffff, last = -1;
+#pragma unroll
+      for (int vb = 0; vb < NVB; ++vb) {
+        float c = run + ex[pb][vb];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          c += e[pb][vb][t];
+          const int row = rbase + vb * 16 + t;
+          if (tgt < c) first = min(first, row);
+          if (e[pb][vb][t] > 0.f) last = row;
+        }
+        run += tot[pb][vb];
+      }
+      if (first != 0x7fffffff) atomicMin(&cand[col], first);
+      atomicMax(&lastp[col], last);
+    }
+  }
+  __syncthreads();
+  if (wv == 0 && lgrp == 0) {
+#pragma unroll
+    for (int pb = 0; pb < NPB; ++pb) {
+      const int col = wb * PB * 32 + pb * 16 + lcol;
+      if (col < ncols) {
+        int tok;
+        if (greedy) tok = 0x7fffffff - (int)(unsigned)(best[col] & 0xffffffffull);
+        else tok = cand[col] != 0x7fffffff ? cand[col] : lastp[col];
+        out(col, tok);
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// Which instantiations of k_unembed walk several tiles per workgroup: the ones whose epilogue leaves the
+// ring alone (no draws) on the tiles of training-sized batches.
+template <int WB, bool SAMPLE>
+constexpr bool unembed_walks_tiles() { return !SAMPLE && WB != 1; }
+
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool SAMPLE, bool WPACK = false>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_unembed(const UnembedArgs a) {
@@ -138,8 +245,22 @@ void k_unembed(const UnembedArgs a) {
   const int lcol = FR::lcol(lane), lgrp = FR::lgrp(lane);
   const int nslab = a.n * a.r;
   const int nbt = (a.B + TL::TP - 1) / TL::TP;
+  // The evidence kernel of a training-sized batch is launched with one workgroup per CU (unembed_walks_tiles):
+  // a workgroup walks the tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the grid is a multiple of the number
+  // of XCDs, so all of them lie in this XCD's range of logical tiles) and opens the feed of the next tile
+  // before the epilogue of the one it has multiplied: the first stages of the next ring arrive while the
+  // softmax statistics are taken, instead of after a workgroup launch with the matrix pipe idle.
+  // Every other instantiation has one tile per workgroup and leaves the loop after it.
+  constexpr bool WALK = unembed_walks_tiles<WB, SAMPLE>();
+  using Feed = TileFeed<WV, WB, VB, PB, SB, NS, BF16, false, M16, WPACK, WB == 1>;
+  const void* const hstaged = (WB != 1 && SB == H_STAGE_BYTES) ? a.hs : nullptr;
+  const int ntiles = nbt * nslab;
   int slab, bt;
   tile_of_block(blockIdx.x, nbt, nslab, slab, bt);
+  Feed feed;
+  // the decode-sized tiles (one wave column) are launched with one tile of positions: W is a stream
+  feed.open(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, bt * TL::TP, smem, nullptr, 0, 1, hstaged);
+  for (int w = blockIdx.x;;) {
   const int b0 = bt * TL::TP;
   const int wi = slab / a.r, wj = slab - wi * a.r;
 
@@ -164,10 +285,14 @@ void k_unembed(const UnembedArgs a) {
   }
 
   typename FR::blk_t acc[NPB][NVB];
-  // the decode-sized tiles (one wave column) are launched with one tile of positions: W is a stream
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16, WPACK, WB == 1>(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab, b0,
-                                                             smem, acc, nullptr, 0, 1,
-                                                             (WB != 1 && SB == H_STAGE_BYTES) ? a.hs : nullptr);
+  tile_gemm_run(feed, a.d, smem, acc);
+  const int wnext = w + (int)gridDim.x;
+  int slab_next = 0, bt_next = 0;
+  if constexpr (WALK)
+    if (wnext < ntiles) {
+      tile_of_block(wnext, nbt, nslab, slab_next, bt_next);
+      feed.open(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, slab_next, bt_next * TL::TP, smem, nullptr, 0, 1, hstaged);
+    }
 
   if constexpr (!SAMPLE) if (a.targets != nullptr) {
 #pragma unroll
@@ -320,6 +445,11 @@ void k_unembed(const UnembedArgs a) {
       }
     });
   }
+  if (!WALK || wnext >= ntiles) break;
+  w = wnext;
+  slab = slab_next;
+  bt = bt_next;
+  }
 }
 
 // stage geometry of the gathered draw tiles and the positions drawn per pass of their draw loop
@@ -358,6 +488,18 @@ void k_draw_gather(const DrawGatherArgs a) {
   float mx[PB * Frag<M16>::SUB], lse[PB * Frag<M16>::SUB];
   tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 
+  if constexpr (M16) {
+    const int S = a.S;
+    tile_draws_cols<TL, WV, VB, PB>(
+        acc, mx, a.v, smem, nrows, a.greedy != 0,
+        [&](int p) {
+          const int rid = rows[min(p, nrows - 1)];       // b * S + s
+          const int b = rid / S, sd = rid - b * S;
+          return philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)sd, (uint32_t)wi);
+        },
+        [&](int p, int tok) { a.drafts[(long long)rows[p] * a.n + wi] = tok; });
+    return;
+  }
   int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
   for (int p = tid; p < nrows; p += TL::NT) s_list[p] = p;
   __syncthreads();
@@ -742,7 +884,14 @@ static hipError_t launch_cfg(const UnembedArgs& a, hipStream_t st) {
   constexpr auto kern = k_unembed<WV, WB, VB, PB, SB, NS, BF16, SAMPLE, WPACK>;
   if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nbt = (a.B + TL::TP - 1) / TL::TP;
-  const int grid = nbt * a.n * a.r;
+  int grid = nbt * a.n * a.r;
+  if constexpr (unembed_walks_tiles<WB, SAMPLE>()) {
+    // one workgroup per CU (the ring takes most of a CU's LDS, so no two share one), a multiple of the
+    // 8 XCDs the workgroup ids are dealt over
+    int cus = 0;
+    if (hipError_t e = cu_count(&cus); e != hipSuccess) return e;
+    if (cus >= 8) grid = std::min(grid, cus / 8 * 8);
+  }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();
 }
