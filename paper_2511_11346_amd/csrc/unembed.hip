@@ -577,11 +577,11 @@ void k_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int 
   }
 }
 
-template <int SB, bool BF16>
+template <int WV, int VB, int SB, int NS, bool BF16>
 static hipError_t launch_sumunit_mfma_cfg(const void* h, long long ld_h, const void* Wsum, int B, int d,
                                           int r, float* logw, hipStream_t st) {
-  using TL = Tile<2, 1, 2, 1, SB, 4>;      // 128 rows (r <= 128) x 32 positions, 2 waves
-  constexpr auto kern = k_sumunit_mfma<2, 1, 2, 1, SB, 4, BF16>;
+  using TL = Tile<WV, 1, VB, 1, SB, NS>;   // WV * VB * 32 rows (>= r) x 32 positions, WV waves
+  constexpr auto kern = k_sumunit_mfma<WV, 1, VB, 1, SB, NS, BF16>;
   if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((B + TL::TP - 1) / TL::TP), dim3(TL::NT), TL::SMEM, st, h, ld_h, Wsum, B,
                      d, r, logw);
@@ -589,13 +589,18 @@ static hipError_t launch_sumunit_mfma_cfg(const void* h, long long ld_h, const v
 }
 
 // The kernel streams h once with one small workgroup per 32 positions, so what limits it is
-// the number of bytes it keeps in flight: 128-byte stages when the rows allow it.
+// the number of bytes of h it keeps in flight: 128-byte stages when the rows allow it, no more
+// rows of Wsum in a stage than r needs (they are loaded beside h), and the LDS that saves spent
+// on a deeper ring.
 template <bool BF16>
 static hipError_t launch_sumunit_mfma_dt(const void* h, long long ld_h, const void* Wsum, int B, int d,
                                          int r, float* logw, hipStream_t st) {
-  if ((d * (BF16 ? 2 : 4)) % 128 == 0)
-    return launch_sumunit_mfma_cfg<128, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
-  return launch_sumunit_mfma_cfg<64, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
+  if ((d * (BF16 ? 2 : 4)) % 128 == 0) {
+    if (r <= 32) return launch_sumunit_mfma_cfg<1, 1, 128, 8, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
+    if (r <= 64) return launch_sumunit_mfma_cfg<2, 1, 128, 6, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
+    return launch_sumunit_mfma_cfg<2, 2, 128, 4, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
+  }
+  return launch_sumunit_mfma_cfg<2, 2, 64, 4, BF16>(h, ld_h, Wsum, B, d, r, logw, st);
 }
 
 hipError_t launch_sumunit_mfma(const void* h, long long ld_h, const void* Wsum, int B, int d, int r,
