@@ -1,5 +1,6 @@
 // C ABI of libmtpc (include/mtpc.h): argument validation, workspace carve-up and
 // the launch sequence of each operation.  Host code only.
+#include <cmath>
 #include <cstring>
 #include <mutex>
 
@@ -48,6 +49,19 @@ bool decode_sized(const mtpc_head* hd) { return hd->B <= 64; }
 bool buckets_pay(const mtpc_head* hd, int S, bool want_scores) {
   if (decode_sized(hd) || hd->r < 2) return false;
   return !want_scores || (long long)hd->B * S >= 64LL * hd->r;
+}
+// Rows per tile of the gathered draws.  A tile takes nearly the same time whatever it holds (its K loop is
+// bound by what every stage costs, not by the products), so what counts is the number of rounds the tiles
+// make over the CUs: buckets of B S / r rows on average (+- a few standard deviations of the multinomial
+// spread) are cut into 128-row tiles or, bf16 only, into 192-row tiles that cost about 1.4 times as much.
+int draw_gather_tile(const mtpc_head* hd, int S) {
+  if (hd->dtype != MTPC_BF16) return DRAW_GATHER_TILE;
+  int cus = 0;
+  if (cu_count(&cus) != hipSuccess || cus < 1) cus = 256;
+  const double m = (double)hd->B * S / hd->r, top = m + 1.5 * std::sqrt(m);
+  const double nb = (double)hd->n * hd->r;
+  auto rounds = [&](int tile) { return std::ceil(nb * std::ceil(top / tile) / cus); };
+  return 1.4 * rounds(DRAW_GATHER_TILE_WIDE) < rounds(DRAW_GATHER_TILE) ? DRAW_GATHER_TILE_WIDE : DRAW_GATHER_TILE;
 }
 // A handful of drafts without scores (2 B S <= r, say batch-1 greedy speculative decoding): only
 // the n slabs a draft's tokens are drawn from are read, as plain dot products.
@@ -384,19 +398,6 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   char* ws = (char*)hd->workspace;
   const uint32_t seed_lo = (uint32_t)(seed & 0xffffffffu), seed_hi = (uint32_t)(seed >> 32);
 
-  LatentArgs la{};
-  la.family = family; la.B = hd->B; la.S = S; la.n = hd->n; la.r = hd->r;
-  la.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
-  la.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
-  la.L = p.Lst; la.contextual = p.nb > 1;
-  la.seed_lo = seed_lo; la.seed_hi = seed_hi; la.offset = offset; la.greedy = greedy;
-  la.zleaf = (int*)(ws + p.zleaf);
-  la.latents = latents ? latents : (int*)(ws + p.lat);
-  bool drawn = false;
-  s = launch_params(family, hd, ly, p, true, want_prefix, st, &la, &drawn);
-  if (s != MTPC_OK) return s;
-  if (!drawn) HIP_TRY(launch_latents(la, st));
-
   // Where the tokens are drawn (see decode_sized):
   //   InKernel  - in the epilogue of the fused kernel, which evaluates every slab
   //   Buckets   - k_draw_gather on the one slab each token needs
@@ -413,6 +414,20 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
                     : logphi         ? Draw::FromTable
                     : span_ok && buckets_pay(hd, S, want_prefix) ? Draw::Buckets   // (h through one 4 GiB resource)
                                      : Draw::InKernel;
+
+  LatentArgs la{};
+  la.family = family; la.B = hd->B; la.S = S; la.n = hd->n; la.r = hd->r;
+  la.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
+  la.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
+  la.L = p.Lst; la.contextual = p.nb > 1;
+  la.seed_lo = seed_lo; la.seed_hi = seed_hi; la.offset = offset; la.greedy = greedy;
+  la.zleaf = (int*)(ws + p.zleaf);
+  la.latents = latents ? latents : (int*)(ws + p.lat);
+  bool drawn = false;
+  s = launch_params(family, hd, ly, p, true, want_prefix, st, &la, &drawn);
+  if (s != MTPC_OK) return s;
+  if (!drawn) HIP_TRY(launch_latents(la, st));
+
   const bool table_scores = want_prefix && draw != Draw::Buckets && (logphi != nullptr || p.has_table);
   float* table = logphi ? logphi : (table_scores ? (float*)(ws + p.table) : nullptr);
 
@@ -429,7 +444,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     HIP_TRY(launch_draw_table(dr, st));
   } else if (draw == Draw::Buckets) {
     BucketArgs bk{};
-    bk.B = hd->B; bk.S = S; bk.n = hd->n; bk.r = hd->r; bk.tile = DRAW_GATHER_TILE;
+    bk.B = hd->B; bk.S = S; bk.n = hd->n; bk.r = hd->r; bk.tile = draw_gather_tile(hd, S);
     bk.zleaf = la.zleaf;
     bk.count = (int*)(ws + p.bk_count); bk.slot = (int*)(ws + p.bk_slot);
     bk.row_off = (int*)(ws + p.bk_rowoff); bk.tile_off = (int*)(ws + p.bk_tileoff);
@@ -443,6 +458,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     dg.row_off = bk.row_off; dg.tile_off = bk.tile_off; dg.tile_bucket = bk.tile_bucket; dg.list = bk.list;
     dg.drafts = drafts;
     dg.seed_lo = seed_lo; dg.seed_hi = seed_hi; dg.offset = offset; dg.greedy = greedy;
+    dg.tile = bk.tile;
     HIP_TRY(launch_draw_gather(dg, hd->dtype, st));
   } else {
     UnembedArgs u = unembed_args(hd);

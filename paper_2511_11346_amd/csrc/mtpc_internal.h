@@ -206,9 +206,13 @@ struct DrawGatherArgs {
   int* drafts;          // [B][S][n]
   uint32_t seed_lo, seed_hi, offset;
   int greedy;
+  int tile;             // rows per tile the buckets were cut into: DRAW_GATHER_TILE or (bf16) DRAW_GATHER_TILE_WIDE
 };
 hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t st);
 constexpr int DRAW_GATHER_TILE = 128;   // rows per tile of the gathered draw kernel
+// ... and of its wider bf16 tile, for buckets that would leave a nearly empty last tile of 128 rows behind
+// (a tile costs nearly the same whatever it holds, so what counts is the number of rounds over the CUs)
+constexpr int DRAW_GATHER_TILE_WIDE = 192;
 constexpr int GATHER_STAGE_BYTES = 64;  // ... and the bytes of a row it takes per stage
 
 // Verification step of a speculative-decoding cycle (Alg. 2, acceptance loop on)

@@ -16,12 +16,15 @@ typedef __attribute__((ext_vector_type(4))) int i32x4_t;
 
 constexpr int NSLOT = 16;         // positions sampled per pass of the draw loop
 
-template <int WV, int WB, int VB, int PB, int SB, int NS>
+// PH: one more block of 16 position columns per wave (kernels on the 16x16 MFMA blocks only), for tiles
+// whose width is not a multiple of 32 columns per wave.
+template <int WV, int WB, int VB, int PB, int SB, int NS, int PH = 0>
 struct Tile {
   static constexpr int NW = WV * WB;
   static constexpr int NT = NW * 64;
   static constexpr int TV = WV * VB * 32;
-  static constexpr int TP = WB * PB * 32;
+  static constexpr int WP = PB * 32 + PH * 16;         // position columns of a wave
+  static constexpr int TP = WB * WP;
   static constexpr int ROWS = TV + TP;
   static constexpr int CPR = SB / 16;                  // 16-byte chunks per row per stage
   static constexpr int RPL = 64 / CPR;                 // rows covered by one 1 KiB wave-load
@@ -171,9 +174,9 @@ __device__ __forceinline__ int swz16(int row) { return (0 - (row >> 2)) & 3; }
 // so that a workgroup that walks several tiles can open the next one (the ring is free once the run
 // has returned) before it turns to the epilogue of the one it has just multiplied.
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false,
-          bool WPACK = false, bool STREAMW = false>
+          bool WPACK = false, bool STREAMW = false, int PH = 0>
 struct TileFeed {
-  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  using TL = Tile<WV, WB, VB, PB, SB, NS, PH>;
   static constexpr int ESZ = BF16 ? 2 : 4;
   static constexpr int CPR = TL::CPR;
   i32x4_t srdW, srdH;
@@ -259,11 +262,12 @@ struct TileFeed {
 
 // The product of a tile whose feed is open: on return every wave holds its VB x PB accumulator blocks and
 // all waves have passed a barrier (the ring is free).
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER, bool M16, bool WPACK, bool STREAMW>
-__device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, BF16, GATHER, M16, WPACK, STREAMW>& feed,
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER, bool M16, bool WPACK, bool STREAMW, int PH>
+__device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, BF16, GATHER, M16, WPACK, STREAMW, PH>& feed,
                                               int d, char* smem,
-                                              typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB]) {
-  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+                                              typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB + PH][VB * Frag<M16>::SUB]) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS, PH>;
+  static_assert(PH == 0 || M16, "half blocks of position columns: 16x16 MFMA blocks only");
   using FR = Frag<M16>;
   static_assert(!M16 || (BF16 && NS >= 3 && TL::NW == 8 && SB == 64),
                 "16x16 blocks: bf16, two waves per SIMD, one MFMA k-step per 64-byte stage");
@@ -278,7 +282,7 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
   auto issue = [&](int buf) { feed.issue(buf); };
 
 #pragma unroll
-  for (int pb = 0; pb < PB * FR::SUB; ++pb)
+  for (int pb = 0; pb < PB * FR::SUB + PH; ++pb)
 #pragma unroll
     for (int vb = 0; vb < VB * FR::SUB; ++vb)
 #pragma unroll
@@ -287,7 +291,7 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
   const int KI = d * ESZ / SB;
   const int sw = swz<CPR>(l31);
   const int a_off = (wv * VB * 32 + l31) * SB + ((lhalf ^ sw) << 4);
-  const int b_off = (TL::TV + wb * PB * 32 + l31) * SB + ((lhalf ^ sw) << 4);
+  const int b_off = (TL::TV + wb * TL::WP + l31) * SB + ((lhalf ^ sw) << 4);
 
   // logical chunk 2*ks + lhalf of a row sits at byte offset base ^ (32*ks)
   // One k-substep: the PB*VB MFMAs on fragment set `cs`, and interleaved with them
@@ -353,18 +357,19 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
     const int l15 = lane & 15, lq = lane >> 4;
     const int sw16 = swz16(l15);
     const int a16 = (wv * VB * 32 + l15) * SB + ((lq ^ sw16) << 4);
-    const int b16 = (TL::TV + wb * PB * 32 + l15) * SB + ((lq ^ sw16) << 4);
-    i32x4_t ga[2 * VB], gb[2 * PB];
-    bool act16[2 * PB];
+    constexpr int NPB16 = 2 * PB + PH;
+    const int b16 = (TL::TV + wb * TL::WP + l15) * SB + ((lq ^ sw16) << 4);
+    i32x4_t ga[2 * VB], gb[NPB16];
+    bool act16[NPB16];
 #pragma unroll
-    for (int pb = 0; pb < 2 * PB; ++pb) act16[pb] = !GATHER || wb * PB * 32 + pb * 16 < hrows;
+    for (int pb = 0; pb < NPB16; ++pb) act16[pb] = !GATHER || wb * TL::WP + pb * 16 < hrows;
     // memory cluster of stage `it`: its fragments, and (LOAD) the loads of stage it+NS-1 into the
     // buffer of stage it-1 (last read before the previous barrier)
     auto mem_cluster = [&](int it, auto load) {
       const char* cur = smem + (it % NS) * TL::STAGE;
       if constexpr (M16) {
 #pragma unroll
-        for (int pb = 0; pb < 2 * PB; ++pb) gb[pb] = *(const i32x4_t*)(cur + b16 + pb * 16 * SB);
+        for (int pb = 0; pb < NPB16; ++pb) gb[pb] = *(const i32x4_t*)(cur + b16 + pb * 16 * SB);
 #pragma unroll
         for (int vb = 0; vb < 2 * VB; ++vb) ga[vb] = *(const i32x4_t*)(cur + a16 + vb * 16 * SB);
       } else {
@@ -381,7 +386,7 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
       __builtin_amdgcn_s_setprio(1);
       if constexpr (M16) {
 #pragma unroll
-        for (int pb = 0; pb < 2 * PB; ++pb)
+        for (int pb = 0; pb < NPB16; ++pb)
           if (!GATHER || act16[pb]) {
 #pragma unroll
             for (int vb = 0; vb < 2 * VB; ++vb) {
@@ -503,13 +508,13 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
 // STREAMW: every byte of W is read once by the whole launch (one tile of positions): loaded with the
 // non-temporal hint.
 template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool GATHER = false, bool M16 = false,
-          bool WPACK = false, bool STREAMW = false>
+          bool WPACK = false, bool STREAMW = false, int PH = 0>
 __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const void* hp, long long ld_h,
                                           int B, int d, int v, int slab, int b0, char* smem,
-                                          typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
+                                          typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB + PH][VB * Frag<M16>::SUB],
                                           const int* rows = nullptr, int nrows = 0, int rdiv = 1,
                                           const void* hs = nullptr, int wrows_total = 0, int wrow0 = 0) {
-  TileFeed<WV, WB, VB, PB, SB, NS, BF16, GATHER, M16, WPACK, STREAMW> feed;
+  TileFeed<WV, WB, VB, PB, SB, NS, BF16, GATHER, M16, WPACK, STREAMW, PH> feed;
   feed.open(Wp, ld_w, hp, ld_h, B, d, v, slab, b0, smem, rows, nrows, rdiv, hs, wrows_total, wrow0);
   tile_gemm_run(feed, d, smem, acc);
 }
@@ -519,13 +524,13 @@ __device__ __forceinline__ void tile_gemm(const void* Wp, long long ld_w, const 
 // position column p = wb*PB*32 + pb*FR::BR + lcol, the vocabulary rows
 //   row(vb, i) = wv*VB*32 + vb*FR::BR + 4*lgrp + FR::roff(i).
 // Contains one workgroup barrier; `red` must not be reused before the next one.
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool M16 = false>
-__device__ __forceinline__ void tile_lse(const typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB],
-                                         int v, float2* red, float (&mx)[PB * Frag<M16>::SUB],
-                                         float (&lse)[PB * Frag<M16>::SUB]) {
-  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool M16 = false, int PH = 0>
+__device__ __forceinline__ void tile_lse(const typename Frag<M16>::blk_t (&acc)[PB * Frag<M16>::SUB + PH][VB * Frag<M16>::SUB],
+                                         int v, float2* red, float (&mx)[PB * Frag<M16>::SUB + PH],
+                                         float (&lse)[PB * Frag<M16>::SUB + PH]) {
+  using TL = Tile<WV, WB, VB, PB, SB, NS, PH>;
   using FR = Frag<M16>;
-  constexpr int NPB = PB * FR::SUB, NVB = VB * FR::SUB;
+  constexpr int NPB = PB * FR::SUB + PH, NVB = VB * FR::SUB;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wv = wave % WV, wb = wave / WV;
   const int lcol = FR::lcol(lane), lgrp = FR::lgrp(lane);
@@ -570,12 +575,12 @@ __device__ __forceinline__ void tile_lse(const typename Frag<M16>::blk_t (&acc)[
         }
     }
     s = FR::across(s, [](float x, float y) { return x + y; });
-    if (lgrp == 0) red[wv * TL::TP + wb * PB * 32 + pb * FR::BR + lcol] = make_float2(m, s);
+    if (lgrp == 0) red[wv * TL::TP + wb * TL::WP + pb * FR::BR + lcol] = make_float2(m, s);
   }
   __syncthreads();
 #pragma unroll
   for (int pb = 0; pb < NPB; ++pb) {
-    const int p = wb * PB * 32 + pb * FR::BR + lcol;
+    const int p = wb * TL::WP + pb * FR::BR + lcol;
     float M = neg_inf();
 #pragma unroll
     for (int w = 0; w < WV; ++w) M = fmaxf(M, red[w * TL::TP + p].x);

@@ -133,10 +133,11 @@ __device__ __forceinline__ void tile_draws(const typename Frag<M16>::blk_t (&acc
 // LDS) and looks for the crossing among its rows; the smallest crossing row of a column wins (LDS minimum).
 // Three workgroup barriers per tile, all waves busy, nothing dumped to LDS but one sum per column and wave.
 // The stage buffers must be free.  uni(p) gives the uniform of column p, out(p, token) takes the result.
-template <class TL, int WV, int VB, int PB, class Uni, class Out>
-__device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[PB * 2][VB * 2], const float (&mx)[PB * 2], int v,
+template <class TL, int WV, int VB, int NPB, class Uni, class Out>
+__device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[NPB][VB * 2], const float (&mx)[NPB], int v,
                                                 char* smem, int ncols, bool greedy, Uni uni, Out out) {
-  constexpr int NPB = PB * 2, NVB = VB * 2;
+  constexpr int NVB = VB * 2;
+  static_assert(NPB * 16 == TL::WP, "the wave's blocks of 16 position columns");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wv = wave % WV, wb = wave / WV;
   const int lcol = lane & 15, lgrp = lane >> 4;
@@ -169,12 +170,12 @@ __device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[PB * 2][VB 
       tot[pb][vb] = __shfl(incl, 48 + lcol);
       colsum += tot[pb][vb];
     }
-    if (lgrp == 0) wsum[wv * TL::TP + wb * PB * 32 + pb * 16 + lcol] = colsum;
+    if (lgrp == 0) wsum[wv * TL::TP + wb * TL::WP + pb * 16 + lcol] = colsum;
   }
   __syncthreads();
 #pragma unroll
   for (int pb = 0; pb < NPB; ++pb) {
-    const int col = wb * PB * 32 + pb * 16 + lcol;
+    const int col = wb * TL::WP + pb * 16 + lcol;
     if (greedy) {
       float bv = -1.f;
       int br = 0;
@@ -215,7 +216,7 @@ __device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[PB * 2][VB 
   if (wv == 0 && lgrp == 0) {
 #pragma unroll
     for (int pb = 0; pb < NPB; ++pb) {
-      const int col = wb * PB * 32 + pb * 16 + lcol;
+      const int col = wb * TL::WP + pb * 16 + lcol;
       if (col < ncols) {
         int tok;
         if (greedy) tok = 0x7fffffff - (int)(unsigned)(best[col] & 0xffffffffull);
@@ -459,10 +460,10 @@ constexpr int GATHER_SB = GATHER_STAGE_BYTES, GATHER_NS = 4, GATHER_NSL = 16;
 // unit); a workgroup takes up to TP rows of one bucket, gathers their h rows, multiplies
 // them with the one slab W[i][z] and draws every row's token - 1/r of the products a
 // pass over all slabs needs.
-template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool WPACK>
+template <int WV, int WB, int VB, int PB, int SB, int NS, bool BF16, bool WPACK, int PH>
 __global__ __launch_bounds__(WV * WB * 64)
 void k_draw_gather(const DrawGatherArgs a) {
-  using TL = Tile<WV, WB, VB, PB, SB, NS>;
+  using TL = Tile<WV, WB, VB, PB, SB, NS, PH>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   // each XCD owns a contiguous range of logical tiles, so that the tiles of a bucket
@@ -482,15 +483,16 @@ void k_draw_gather(const DrawGatherArgs a) {
   const int wi = g / a.r;
 
   constexpr bool M16 = use_m16<WV, WB, SB, NS, BF16>();
-  typename Frag<M16>::blk_t acc[PB * Frag<M16>::SUB][VB * Frag<M16>::SUB];
-  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, true, M16, WPACK>(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, g, 0, smem, acc, rows,
-                                                            nrows, a.S);
-  float mx[PB * Frag<M16>::SUB], lse[PB * Frag<M16>::SUB];
-  tile_lse<WV, WB, VB, PB, SB, NS, M16>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
+  constexpr int NPB = PB * Frag<M16>::SUB + PH;
+  typename Frag<M16>::blk_t acc[NPB][VB * Frag<M16>::SUB];
+  tile_gemm<WV, WB, VB, PB, SB, NS, BF16, true, M16, WPACK, false, PH>(WPACK ? a.Wp : a.W, a.d, a.h, a.ld_h, a.B, a.d, a.v, g, 0, smem,
+                                                                       acc, rows, nrows, a.S);
+  float mx[NPB], lse[NPB];
+  tile_lse<WV, WB, VB, PB, SB, NS, M16, PH>(acc, a.v, (float2*)(smem + TL::RED_OFF), mx, lse);
 
   if constexpr (M16) {
     const int S = a.S;
-    tile_draws_cols<TL, WV, VB, PB>(
+    tile_draws_cols<TL, WV, VB, NPB>(
         acc, mx, a.v, smem, nrows, a.greedy != 0,
         [&](int p) {
           const int rid = rows[min(p, nrows - 1)];       // b * S + s
@@ -498,35 +500,35 @@ void k_draw_gather(const DrawGatherArgs a) {
           return philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)sd, (uint32_t)wi);
         },
         [&](int p, int tok) { a.drafts[(long long)rows[p] * a.n + wi] = tok; });
-    return;
+  } else {
+    int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
+    for (int p = tid; p < nrows; p += TL::NT) s_list[p] = p;
+    __syncthreads();
+    tile_draws<TL, VB, PB, GATHER_NSL, M16>(acc, mx, a.v, smem, nrows, [&](int p, const float (&vals)[TL::VPL], float ls,
+                                                                           float incl, float Z) {
+      const int rid = rows[p];                         // b * S + s
+      const int b = rid / a.S, s = rid - b * a.S;
+      int tok;
+      bool writer;
+      if (a.greedy) {
+        tok = wave_argmax_token<TL::VPL>(vals, lane);
+        writer = lane == 0;
+      } else {
+        const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)s, (uint32_t)wi);
+        tok = wave_draw_token<TL::VPL>(vals, ls, incl, Z, u, lane, writer);
+      }
+      if (writer) a.drafts[(long long)rid * a.n + wi] = tok;
+    });
   }
-  int* s_list = (int*)(smem + TL::MISC_OFF) + 4;
-  for (int p = tid; p < nrows; p += TL::NT) s_list[p] = p;
-  __syncthreads();
-  tile_draws<TL, VB, PB, GATHER_NSL, M16>(acc, mx, a.v, smem, nrows, [&](int p, const float (&vals)[TL::VPL], float ls, float incl,
-                                                        float Z) {
-    const int rid = rows[p];                         // b * S + s
-    const int b = rid / a.S, s = rid - b * a.S;
-    int tok;
-    bool writer;
-    if (a.greedy) {
-      tok = wave_argmax_token<TL::VPL>(vals, lane);
-      writer = lane == 0;
-    } else {
-      const float u = philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)b, (uint32_t)s, (uint32_t)wi);
-      tok = wave_draw_token<TL::VPL>(vals, ls, incl, Z, u, lane, writer);
-    }
-    if (writer) a.drafts[(long long)rid * a.n + wi] = tok;
-  });
 }
 
-template <int WV, int WB, int VB, int PB, bool BF16, bool WPACK = false>
+template <int WV, int WB, int VB, int PB, int PH, bool BF16, bool WPACK = false>
 static hipError_t launch_draw_gather_cfg(const DrawGatherArgs& a, hipStream_t st) {
-  using TL = Tile<WV, WB, VB, PB, GATHER_SB, GATHER_NS>;
-  static_assert(TL::TP == DRAW_GATHER_TILE, "the bucketing kernels count tiles of this many rows");
+  using TL = Tile<WV, WB, VB, PB, GATHER_SB, GATHER_NS, PH>;
+  static_assert(TL::TP == DRAW_GATHER_TILE || TL::TP == DRAW_GATHER_TILE_WIDE, "the tile heights the bucketing is run with");
   if constexpr (!WPACK)
-    if (a.Wp != nullptr) return launch_draw_gather_cfg<WV, WB, VB, PB, BF16, true>(a, st);
-  constexpr auto kern = k_draw_gather<WV, WB, VB, PB, GATHER_SB, GATHER_NS, BF16, WPACK>;
+    if (a.Wp != nullptr) return launch_draw_gather_cfg<WV, WB, VB, PB, PH, BF16, true>(a, st);
+  constexpr auto kern = k_draw_gather<WV, WB, VB, PB, GATHER_SB, GATHER_NS, BF16, WPACK, PH>;
   if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const long long rows = (long long)a.B * a.S * a.n;
   const int grid = (int)(rows / TL::TP) + a.n * a.r;             // >= sum over buckets of ceil(rows_g / TP)
@@ -536,10 +538,16 @@ static hipError_t launch_draw_gather_cfg(const DrawGatherArgs& a, hipStream_t st
 
 template <bool BF16>
 static hipError_t launch_draw_gather_dt(const DrawGatherArgs& a, hipStream_t st) {
-  constexpr int PB = DRAW_GATHER_TILE / 128;
-  if (a.v > 256) return launch_draw_gather_cfg<2, 4, 5, PB, BF16>(a, st);
-  if (a.v > 128) return launch_draw_gather_cfg<2, 4, 4, PB, BF16>(a, st);
-  return launch_draw_gather_cfg<2, 4, 2, PB, BF16>(a, st);
+  if constexpr (BF16)                                // (the wide tile counts its columns in blocks of 16)
+    if (a.tile == DRAW_GATHER_TILE_WIDE) {
+      if (a.v > 256) return launch_draw_gather_cfg<2, 4, 5, 1, 1, BF16>(a, st);
+      if (a.v > 128) return launch_draw_gather_cfg<2, 4, 4, 1, 1, BF16>(a, st);
+      return launch_draw_gather_cfg<2, 4, 2, 1, 1, BF16>(a, st);
+    }
+  if (a.tile != DRAW_GATHER_TILE) return hipErrorInvalidValue;
+  if (a.v > 256) return launch_draw_gather_cfg<2, 4, 5, 1, 0, BF16>(a, st);
+  if (a.v > 128) return launch_draw_gather_cfg<2, 4, 4, 1, 0, BF16>(a, st);
+  return launch_draw_gather_cfg<2, 4, 2, 1, 0, BF16>(a, st);
 }
 
 hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t st) {

@@ -168,7 +168,11 @@ hipError_t launch_draw_gather(const DrawGatherArgs& a, int dtype, hipStream_t) {
   need(a.h, strided(a.B, a.ld_h, a.d, esz(dtype)), "draw gather h");
   need(a.W, (u64)a.n * a.r * a.v * a.d * esz(dtype), "draw gather W");
   opt(a.Wp, (u64)a.n * a.r * a.v * a.d * esz(dtype), "draw gather stage-major W");
-  bucket_arrays(a.row_off, a.tile_off, a.tile_bucket, a.list, a.B, a.S, a.n, a.r, DRAW_GATHER_TILE);
+  if (a.tile != DRAW_GATHER_TILE && !(dtype == MTPC_BF16 && a.tile == DRAW_GATHER_TILE_WIDE)) {
+    std::fprintf(stderr, "[%s] draw gather: tile height %d\n", host_check::g_case, a.tile);
+    std::abort();
+  }
+  bucket_arrays(a.row_off, a.tile_off, a.tile_bucket, a.list, a.B, a.S, a.n, a.r, a.tile);
   need(a.drafts, (u64)a.B * a.S * a.n * 4, "draw gather drafts");
   return ok();
 }
