@@ -126,17 +126,21 @@ __device__ __forceinline__ void tile_draws(const typename Frag<M16>::blk_t (&acc
 }
 
 // Draws for every position column of a tile at once, from the accumulators (16x16 blocks): one token per
-// column p < ncols, by inverse CDF (Alg. 1: the smallest token k with u Z < cdf[k]; the last token with
+// column p with need(p), by inverse CDF (Alg. 1: the smallest token k with u Z < cdf[k]; the last token with
 // positive mass if rounding leaves u Z >= Z) or, greedy, the most likely token (ties: the smallest id).
 // A column's v values lie in 4 lane groups x VB*2 blocks x WV waves; each lane forms the prefix of its own
 // rows (sums over the lane groups by lane permutes, over the blocks in registers, over the waves through
 // LDS) and looks for the crossing among its rows; the smallest crossing row of a column wins (LDS minimum).
-// Three workgroup barriers per tile, all waves busy, nothing dumped to LDS but one sum per column and wave.
+// Three workgroup barriers per call, all waves busy, nothing dumped to LDS but one sum per column and wave.
+// Wide wave tiles (more than three blocks of columns) form the terms of a block a second time after the
+// barrier instead of keeping those of all blocks in registers.
 // The stage buffers must be free.  uni(p) gives the uniform of column p, out(p, token) takes the result.
-template <class TL, int WV, int VB, int NPB, class Uni, class Out>
+template <class TL, int WV, int VB, int NPB, class Need, class Uni, class Out>
 __device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[NPB][VB * 2], const float (&mx)[NPB], int v,
-                                                char* smem, int ncols, bool greedy, Uni uni, Out out) {
+                                                char* smem, bool greedy, Need need, Uni uni, Out out) {
   constexpr int NVB = VB * 2;
+  constexpr bool KEEP = NPB <= 3;
+  constexpr int NK = KEEP ? NPB : 1;
   static_assert(NPB * 16 == TL::WP, "the wave's blocks of 16 position columns");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wv = wave % WV, wb = wave / WV;
@@ -152,30 +156,39 @@ __device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[NPB][VB * 2
     lastp[p] = -1;
     best[p] = 0ull;
   }
-  float e[NPB][NVB][4], ex[NPB][NVB], tot[NPB][NVB];
-#pragma unroll
-  for (int pb = 0; pb < NPB; ++pb) {
+  // the terms of block pb: e = exp(l - max) of this lane's rows, ex = what the lane groups below this one
+  // hold of a block of 16 rows, tot = the block's sum; returns the sum of the wave's rows of the column
+  auto terms = [&](int pb, float (&e)[NVB][4], float (&ex)[NVB], float (&tot)[NVB]) {
     float colsum = 0.f;
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb) {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) e[pb][vb][t] = (rbase + vb * 16 + t < v) ? expf(acc[pb][vb][t] - mx[pb]) : 0.f;
-      const float s4 = ((e[pb][vb][0] + e[pb][vb][1]) + e[pb][vb][2]) + e[pb][vb][3];
+      for (int t = 0; t < 4; ++t) e[vb][t] = (rbase + vb * 16 + t < v) ? expf(acc[pb][vb][t] - mx[pb]) : 0.f;
+      const float s4 = ((e[vb][0] + e[vb][1]) + e[vb][2]) + e[vb][3];
       // inclusive scan over the four lane groups that hold this column (lanes lcol + 16 g)
       const float u1 = __shfl_up(s4, 16);
       const float i1 = lgrp >= 1 ? s4 + u1 : s4;
       const float u2 = __shfl_up(i1, 32);
       const float incl = lgrp >= 2 ? i1 + u2 : i1;
-      ex[pb][vb] = incl - s4;
-      tot[pb][vb] = __shfl(incl, 48 + lcol);
-      colsum += tot[pb][vb];
+      ex[vb] = incl - s4;
+      tot[vb] = __shfl(incl, 48 + lcol);
+      colsum += tot[vb];
     }
+    return colsum;
+  };
+  float e[NK][NVB][4], ex[NK][NVB], tot[NK][NVB];
+#pragma unroll
+  for (int pb = 0; pb < NPB; ++pb) {
+    const float colsum = terms(pb, e[KEEP ? pb : 0], ex[KEEP ? pb : 0], tot[KEEP ? pb : 0]);
     if (lgrp == 0) wsum[wv * TL::TP + wb * TL::WP + pb * 16 + lcol] = colsum;
   }
   __syncthreads();
 #pragma unroll
   for (int pb = 0; pb < NPB; ++pb) {
     const int col = wb * TL::WP + pb * 16 + lcol;
+    constexpr int k0 = 0;
+    const int k = KEEP ? pb : k0;
+    if constexpr (!KEEP) (void)terms(pb, e[0], ex[0], tot[0]);
     if (greedy) {
       float bv = -1.f;
       int br = 0;
@@ -183,7 +196,7 @@ __device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[NPB][VB * 2
       for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
         for (int t = 0; t < 4; ++t)
-          if (e[pb][vb][t] > bv) { bv = e[pb][vb][t]; br = rbase + vb * 16 + t; }
+          if (e[k][vb][t] > bv) { bv = e[k][vb][t]; br = rbase + vb * 16 + t; }
       atomicMax(&best[col], ((unsigned long long)__float_as_uint(bv) << 32) | (unsigned)(0x7fffffff - br));
     } else {
       float below = 0.f, Z = 0.f;
@@ -198,15 +211,15 @@ __device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[NPB][VB * 2
       int first = 0x7fffffff, last = -1;
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb) {
-        float c = run + ex[pb][vb];
+        float c = run + ex[k][vb];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          c += e[pb][vb][t];
+          c += e[k][vb][t];
           const int row = rbase + vb * 16 + t;
           if (tgt < c) first = min(first, row);
-          if (e[pb][vb][t] > 0.f) last = row;
+          if (e[k][vb][t] > 0.f) last = row;
         }
-        run += tot[pb][vb];
+        run += tot[k][vb];
       }
       if (first != 0x7fffffff) atomicMin(&cand[col], first);
       atomicMax(&lastp[col], last);
@@ -217,7 +230,7 @@ __device__ __forceinline__ void tile_draws_cols(const f32x4_t (&acc)[NPB][VB * 2
 #pragma unroll
     for (int pb = 0; pb < NPB; ++pb) {
       const int col = wb * TL::WP + pb * 16 + lcol;
-      if (col < ncols) {
+      if (need(col)) {
         int tok;
         if (greedy) tok = 0x7fffffff - (int)(unsigned)(best[col] & 0xffffffffull);
         else tok = cand[col] != 0x7fffffff ? cand[col] : lastp[col];
@@ -409,7 +422,24 @@ void k_unembed(const UnembedArgs a) {
         }
     }
   }
-  if constexpr (SAMPLE) {
+  if constexpr (SAMPLE && M16 && WB != 1) {
+    // training-sized tiles: the tokens of all columns at once, one pass per draft (only tiles in which some
+    // position draws token wi of that draft from component wj)
+    if (a.zleaf == nullptr) return;
+    for (int s = 0; s < a.S; ++s) {
+      auto need = [&](int p) {
+        const long long b = b0 + p;
+        return b < a.B && a.zleaf[(b * a.S + s) * a.n + wi] == wj;
+      };
+      bool any = false;
+      for (int p = tid; p < TL::TP; p += TL::NT) any |= need(p);
+      if (!__syncthreads_or(any)) continue;
+      tile_draws_cols<TL, WV, VB, NPB>(
+          acc, mx, a.v, smem, a.greedy != 0, need,
+          [&](int p) { return philox_uniform(a.seed_lo, a.seed_hi, a.offset, (uint32_t)(b0 + p), (uint32_t)s, (uint32_t)wi); },
+          [&](int p, int tok) { a.drafts[((long long)(b0 + p) * a.S + s) * a.n + wi] = tok; });
+    }
+  } else if constexpr (SAMPLE) {
     if (a.zleaf == nullptr) return;
     // ---- which positions of this tile draw token wi from component wj?
     int* misc = (int*)(smem + TL::MISC_OFF);
@@ -493,7 +523,7 @@ void k_draw_gather(const DrawGatherArgs a) {
   if constexpr (M16) {
     const int S = a.S;
     tile_draws_cols<TL, WV, VB, NPB>(
-        acc, mx, a.v, smem, nrows, a.greedy != 0,
+        acc, mx, a.v, smem, a.greedy != 0, [&](int p) { return p < nrows; },
         [&](int p) {
           const int rid = rows[min(p, nrows - 1)];       // b * S + s
           const int b = rid / S, sd = rid - b * S;
