@@ -192,6 +192,37 @@ def test_bucket_extremes(family, B, n, r, v, flat):
     assert np.array_equal(g2.cpu().numpy()[safe], want_d[safe])
 
 
+@pytest.mark.parametrize("family,B,n,r,v", [
+    ("cp", 4950, 8, 33, 300),        # 264 buckets whose sizes follow the mixture weights: from a few rows to several tiles
+    ("hmm", 7200, 6, 48, 200),       # 288 buckets of about 150 rows, the 256-row vocabulary tile
+    ("btree", 6000, 8, 40, 100),     # 320 buckets, the 128-row vocabulary tile
+])
+def test_gathered_draws_on_the_wide_tiles(family, B, n, r, v):
+    """Shapes for which the bucketed draws take their 192-row tiles (more than 256 buckets of 112 to 172
+    rows on average: one wide tile per bucket instead of two of 128 rows, a round over the CUs less):
+    drafts and latents of sampled rows against the oracle, the greedy draft too."""
+    inp = mi.make_inputs(family, B=B, d=64, n=n, r=r, v=v, dtype="bf16", seed=40 + r, h_scale=1.0)
+    head = make_head(inp)
+    rng = np.random.default_rng(B)
+    rows = np.unique(np.concatenate([np.arange(8), np.arange(B - 8, B), rng.integers(0, B, 80)]))
+    logphi, logw, loglayers = oc._params(family, inp.h[rows], inp.W, inp.Wsum, inp.layers)
+    S, seed = 1, 7
+    u = philox.uniforms(B, S, n + oc.n_latents(family, n), seed, 0)
+    od, ol, margin = oc.sample_from(family, logphi, logw, loglayers, u[rows], with_margin=True)
+    gd, gl, _ = head.sample(S, seed=seed)
+    near, _ = compare_drafts(gd[rows], gl[rows] if gl is not None else None, od, ol, margin)
+    assert near <= max(4, margin.size // 50)
+    assert int(gd.min()) >= 0 and int(gd.max()) < v
+    want_d, want_l, gap = sp.greedy_draft(family, logphi, logw, loglayers)
+    g2, l2, _ = head.greedy_draft()
+    safe = gap >= 1e-6
+    assert safe.sum() >= len(rows) // 2
+    assert np.array_equal(g2.cpu().numpy()[rows][safe], want_d[safe])
+    # the same draws again: the order of the rows inside a bucket (atomics) changes nothing
+    gd2, _, _ = head.sample(S, seed=seed)
+    assert torch.equal(gd2, gd)
+
+
 @pytest.mark.parametrize("family,dtype,B,S,d,n,r,v,ctx", [
     ("cp", "bf16", 1, 1, 4096, 16, 32, 320, False),     # batch-1 decoding at the full head width
     ("cp", "f32", 2, 2, 96, 4, 8, 33, False),           # exactly 2 B S = r
