@@ -121,69 +121,98 @@ void k_gemm_tn(const GemmArgs a) {
   const int lcol = FR::lcol(lane), lgrp = FR::lgrp(lane);
   const int nslab = (a.M + TL::TV - 1) / TL::TV;
   const int nbt = (a.N + TL::TP - 1) / TL::TP;
-  int slab, bt;
   const int tiles = nbt * nslab;
-  const int ks = blockIdx.x / tiles;                 // K split handled by this workgroup
-  tile_of_block(blockIdx.x - ks * tiles, nbt, nslab, slab, bt);
-  const int b0 = bt * TL::TP;
-  const int rows = min(TL::TV, a.M - slab * TL::TV);
-  const int k0 = ks * a.kchunk, klen = min(a.kchunk, a.K - k0);
-  typename FR::blk_t acc[NPB][NVB];
-  // (the chunk [k0, k0 + klen) of the stage-major operand is the run of its stages k0 * ESZ / 64 onwards)
-  const char* bs = (a.Bs != nullptr && SB == 64) ? (const char*)a.Bs + (long long)k0 * ESZ / 64 * a.N * 64 : nullptr;
-  if constexpr (ASTAGED)
-    tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16, true>((const char*)a.As + (long long)k0 * ESZ / 64 * a.As_rows * 64, 0,
-                                                              (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0,
-                                                              b0, smem, acc, nullptr, 0, 1, bs, a.As_rows, slab * TL::TV);
-  else
-    tile_gemm<WV, WB, VB, PB, SB, NS, BF16, false, M16>((const char*)a.A + ((long long)slab * TL::TV * a.lda + k0) * ESZ, a.lda,
-                                                        (const char*)a.Bm + (long long)k0 * ESZ, a.ldb, a.N, klen, rows, 0,
-                                                        b0, smem, acc, nullptr, 0, 1, bs);
-  const int rbase = wv * VB * 32 + 4 * lgrp;
-  // A full tile that lies inside one destination (the common case): one base pointer per
-  // column, rows at constant multiples of ldc.
-  {
-    const long long gr0 = (long long)slab * TL::TV;
-    float* base = nullptr;
-    if (rows == TL::TV) {
-      if (a.ksplit > 1) base = a.partial + ((long long)ks * a.M + gr0) * a.ldc;
-      else if (gr0 + TL::TV <= a.split) base = a.C + gr0 * a.ldc;
+  const int total = tiles * max(a.ksplit, 1);
+  // One workgroup per CU walks the tiles blockIdx.x, blockIdx.x + gridDim.x, ... and opens the feed of the
+  // next tile before it stores the one it has multiplied (the stores touch no ring memory): the first
+  // stages of the next ring arrive while the 320 x 256 results leave.
+  struct Where { int slab, b0, rows, ks, k0, klen; };
+  auto where = [&](int w) {
+    Where t;
+    int bt;
+    t.ks = w / tiles;                                // K split handled by this tile
+    tile_of_block(w - t.ks * tiles, nbt, nslab, t.slab, bt);
+    t.b0 = bt * TL::TP;
+    t.rows = min(TL::TV, a.M - t.slab * TL::TV);
+    t.k0 = t.ks * a.kchunk;
+    t.klen = min(a.kchunk, a.K - t.k0);
+    return t;
+  };
+  TileFeed<WV, WB, VB, PB, SB, NS, BF16, false, M16, ASTAGED> feed;
+  auto open = [&](const Where& t) {
+    // (the chunk [k0, k0 + klen) of a stage-major operand is the run of its stages k0 * ESZ / 64 onwards)
+    const char* bs = (a.Bs != nullptr && SB == 64) ? (const char*)a.Bs + (long long)t.k0 * ESZ / 64 * a.N * 64 : nullptr;
+    if constexpr (ASTAGED)
+      feed.open((const char*)a.As + (long long)t.k0 * ESZ / 64 * a.As_rows * 64, 0, (const char*)a.Bm + (long long)t.k0 * ESZ,
+                a.ldb, a.N, t.klen, t.rows, 0, t.b0, smem, nullptr, 0, 1, bs, a.As_rows, t.slab * TL::TV);
+    else
+      feed.open((const char*)a.A + ((long long)t.slab * TL::TV * a.lda + t.k0) * ESZ, a.lda,
+                (const char*)a.Bm + (long long)t.k0 * ESZ, a.ldb, a.N, t.klen, t.rows, 0, t.b0, smem, nullptr, 0, 1, bs);
+  };
+  Where cur = where(blockIdx.x);
+  open(cur);
+  for (int w = blockIdx.x;;) {
+    typename FR::blk_t acc[NPB][NVB];
+    tile_gemm_run(feed, cur.klen, smem, acc);
+    const int wnext = w + (int)gridDim.x;
+    Where nxt = cur;
+    if (wnext < total) {
+      nxt = where(wnext);
+      open(nxt);
     }
-    if (base != nullptr) {
-      // the column blocks of a row back to back: together they fill whole lines
-      const int col0 = b0 + wb * PB * 32 + lcol;
-      float* cp = base + (long long)rbase * a.ldc + col0;
+    const int slab = cur.slab, b0 = cur.b0, rows = cur.rows, ks = cur.ks;
+    const int rbase = wv * VB * 32 + 4 * lgrp;
+    // A full tile that lies inside one destination (the common case): one base pointer per
+    // column, rows at constant multiples of ldc.
+    bool stored = false;
+    {
+      const long long gr0 = (long long)slab * TL::TV;
+      float* base = nullptr;
+      if (rows == TL::TV) {
+        if (a.ksplit > 1) base = a.partial + ((long long)ks * a.M + gr0) * a.ldc;
+        else if (gr0 + TL::TV <= a.split) base = a.C + gr0 * a.ldc;
+      }
+      if (base != nullptr) {
+        // the column blocks of a row back to back: together they fill whole lines
+        const int col0 = b0 + wb * PB * 32 + lcol;
+        float* cp = base + (long long)rbase * a.ldc + col0;
+#pragma unroll
+        for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+          for (int i = 0; i < FR::NI; ++i)
+#pragma unroll
+            for (int pb = 0; pb < NPB; ++pb)
+              if (col0 + pb * FR::BR < a.N)
+                cp[(long long)(vb * FR::BR + FR::roff(i)) * a.ldc + pb * FR::BR] = acc[pb][vb][i];
+        stored = true;
+      }
+    }
+    if (!stored) {
+      // one destination row at a time (keeps the address arithmetic out of the 160 live accumulators)
 #pragma unroll
       for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-        for (int i = 0; i < FR::NI; ++i)
+        for (int i = 0; i < FR::NI; ++i) {
+          const int row = rbase + vb * FR::BR + FR::roff(i);
+          if (row >= rows) continue;
+          const long long gr = (long long)slab * TL::TV + row;
+          float* rp = nullptr;
+          if (a.ksplit > 1) rp = a.partial + ((long long)ks * a.M + gr) * a.ldc;
+          else if (gr < a.split) rp = a.C + gr * a.ldc;
+          else if (gr < a.split + a.n2) rp = a.C2 + (gr - a.split) * a.ldc;
+          else if (gr >= a.split3) rp = a.C3 + (gr - a.split3) * a.ldc;
+          if (rp == nullptr) continue;
 #pragma unroll
-          for (int pb = 0; pb < NPB; ++pb)
-            if (col0 + pb * FR::BR < a.N)
-              cp[(long long)(vb * FR::BR + FR::roff(i)) * a.ldc + pb * FR::BR] = acc[pb][vb][i];
-      return;
+          for (int pb = 0; pb < NPB; ++pb) {
+            const int col = b0 + wb * PB * 32 + pb * FR::BR + lcol;
+            if (col < a.N) rp[col] = acc[pb][vb][i];
+          }
+        }
     }
+    if (wnext >= total) break;
+    w = wnext;
+    cur = nxt;
   }
-  // one destination row at a time (keeps the address arithmetic out of the 160 live accumulators)
-#pragma unroll
-  for (int vb = 0; vb < NVB; ++vb)
-#pragma unroll
-    for (int i = 0; i < FR::NI; ++i) {
-      const int row = rbase + vb * FR::BR + FR::roff(i);
-      if (row >= rows) continue;
-      const long long gr = (long long)slab * TL::TV + row;
-      float* rp = nullptr;
-      if (a.ksplit > 1) rp = a.partial + ((long long)ks * a.M + gr) * a.ldc;
-      else if (gr < a.split) rp = a.C + gr * a.ldc;
-      else if (gr < a.split + a.n2) rp = a.C2 + (gr - a.split) * a.ldc;
-      else if (gr >= a.split3) rp = a.C3 + (gr - a.split3) * a.ldc;
-      if (rp == nullptr) continue;
-#pragma unroll
-      for (int pb = 0; pb < NPB; ++pb) {
-        const int col = b0 + wb * PB * 32 + pb * FR::BR + lcol;
-        if (col < a.N) rp[col] = acc[pb][vb][i];
-      }
-    }
 }
 
 template <int WV, int WB, int VB, int PB, bool BF16, bool ASTAGED = false>
@@ -194,7 +223,12 @@ static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t st) {
   constexpr auto kern = k_gemm_tn<WV, WB, VB, PB, 64, 4, BF16, ASTAGED>;
   if (hipError_t e = allow_lds<kern>(TL::SMEM); e != hipSuccess) return e;
   const int nslab = (a.M + TL::TV - 1) / TL::TV, nbt = (a.N + TL::TP - 1) / TL::TP;
-  hipLaunchKernelGGL(kern, dim3(nslab * nbt * max(a.ksplit, 1)), dim3(TL::NT), TL::SMEM, st, a);
+  int grid = nslab * nbt * max(a.ksplit, 1);
+  // one workgroup per CU (the ring takes most of a CU's LDS), a multiple of the 8 XCDs the ids are dealt over
+  int cus = 0;
+  if (hipError_t e = cu_count(&cus); e != hipSuccess) return e;
+  if (cus >= 8) grid = std::min(grid, cus / 8 * 8);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(TL::NT), TL::SMEM, st, a);
   return hipGetLastError();
 }
 
