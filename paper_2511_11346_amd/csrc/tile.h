@@ -189,6 +189,7 @@ struct TileFeed {
   int wave, hrows;
 
   __device__ __forceinline__ void issue_one(int q, int buf) {   // q-th wave-load of this wave for one stage
+    __builtin_assume(wave >= 0 && wave < TL::NW);    // (which loads are W's and which exist is then known per q, mostly)
     const int wl = wave + q * TL::NW;
     if (q < TL::PER || wl < TL::NWL) {
       // a wave-load never straddles the W / h boundary (TV is a multiple of RPL)
@@ -318,7 +319,9 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
 #pragma unroll
     for (int r = 0; r < NR; ++r) read_frag(s, ks, set, r);
   };
-  auto substep = [&](int cs, int ks, const char* nsrc, int nks, int ns, int buf) {
+  // (rd: whether there is a next fragment set to read; a flag of its own, known where the loops are
+  // unrolled: that a pointer into LDS is not null is not)
+  auto substep = [&](int cs, int ks, bool rd, const char* nsrc, int nks, int ns, int buf) {
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
       if constexpr (!M16)
@@ -327,7 +330,7 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
       for (int o = 0; o < NOPS; ++o) {
         if ((o * NM) / NOPS != m) continue;          // op o rides behind MFMA o*NM/NOPS
         if (o < NR) {
-          if (nsrc != nullptr) read_frag(nsrc, nks, ns, o);
+          if (rd) read_frag(nsrc, nks, ns, o);
         } else {
           const int q = ks * LPS + (o - NR);
           if (buf >= 0 && q < TL::LPW) {
@@ -395,8 +398,8 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
             }
           }
       } else {
-        substep(0, 0, nullptr, 0, 0, -1);
-        substep(1, 1, nullptr, 0, 0, -1);
+        substep(0, 0, false, nullptr, 0, 0, -1);
+        substep(1, 1, false, nullptr, 0, 0, -1);
       }
       __builtin_amdgcn_s_setprio(0);
       __builtin_amdgcn_sched_barrier(0);
@@ -442,39 +445,31 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
     }
     if (group == 0) __syncthreads();        // pairs with the late start of the other group
   } else if constexpr (NS >= 3) {
-    // Waves issue LPW or LPW-1 loads per stage; allowing y*PER loads to stay in
-    // flight guarantees, for either kind, that all but the y youngest stages have
-    // landed (one count for all waves keeps the loop branch-free).  At the barrier
-    // of iteration `it` stage it+1 is already complete, so its first fragments are
-    // read during the last substep of stage `it`: no wave starts an iteration by
-    // waiting on LDS.
-    const int KM = max(KI - (NS - 1), 0);   // iterations whose whole look-ahead exists
-    if (KI > NS - 2) MTPC_WAIT_VMCNT((NS - 2) * TL::PER); else MTPC_WAIT_VMCNT(0);
-    __syncthreads();
-    load_frags(smem, 0, 0);
+    // Plain ring (tiles of fewer than 8 waves: the decode-sized tiles and the narrow ones of the sum units,
+    // all bound by the latency of their stream).  At the barrier of iteration `it` stage `it` has landed and
+    // nobody reads stage it-1 any more: its buffer takes all loads of stage it+NS-1 at once, so NS-1 stages
+    // are in flight while stage `it` is multiplied (its first fragments are read behind that barrier; reading
+    // them one stage ahead would need stage it+1 complete here, i.e. one stage less in flight).
+    // Waves issue LPW or LPW-1 loads per stage; allowing y*PER loads to stay in flight guarantees, for either
+    // kind, that all but the y youngest stages have landed (one count for all waves keeps the loop branch-free).
+    const int KM = max(KI - (NS - 1), 0);   // iterations that still issue a stage
     int it = 0;
     for (; it < KM; ++it) {
-      MTPC_WAIT_VMCNT((NS - 3) * TL::PER);   // stage it+1 landed (stages up to it+NS-2 issued)
+      MTPC_WAIT_VMCNT((NS - 2) * TL::PER);   // stage `it` landed (stages up to it+NS-2 issued)
       __syncthreads();                       // ... everywhere; stage it-1 is no longer read
-      const int pbuf = (it + NS - 1) % NS;   // free since the barrier: receives stage it+NS-1
+      issue((it + NS - 1) % NS);
       const char* cur = smem + (it % NS) * TL::STAGE;
-      const char* nxt = smem + ((it + 1) % NS) * TL::STAGE;
+      load_frags(cur, 0, 0);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if (ks + 1 < KS) substep(ks & 1, ks, cur, ks + 1, (ks + 1) & 1, pbuf);
-        else substep(ks & 1, ks, nxt, 0, 0, pbuf);
-      }
+      for (int ks = 0; ks < KS; ++ks) substep(ks & 1, ks, ks + 1 < KS, cur, ks + 1, (ks + 1) & 1, -1);
     }
     for (; it < KI; ++it) {
       MTPC_WAIT_VMCNT(0);
       __syncthreads();
       const char* cur = smem + (it % NS) * TL::STAGE;
-      const char* nxt = (it + 1 < KI) ? smem + ((it + 1) % NS) * TL::STAGE : nullptr;
+      load_frags(cur, 0, 0);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if (ks + 1 < KS) substep(ks & 1, ks, cur, ks + 1, (ks + 1) & 1, -1);
-        else substep(ks & 1, ks, nxt, 0, 0, -1);
-      }
+      for (int ks = 0; ks < KS; ++ks) substep(ks & 1, ks, ks + 1 < KS, cur, ks + 1, (ks + 1) & 1, -1);
     }
   } else {
     // two stages: the other buffer is being filled while this one is multiplied
@@ -486,7 +481,7 @@ __device__ __forceinline__ void tile_gemm_run(TileFeed<WV, WB, VB, PB, SB, NS, B
       load_frags(cur, 0, 0);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        substep(ks & 1, ks, ks + 1 < KS ? cur : nullptr, ks + 1, (ks + 1) & 1, pbuf);
+        substep(ks & 1, ks, ks + 1 < KS, cur, ks + 1, (ks + 1) & 1, pbuf);
     }
   }
   __syncthreads();     // all waves are done reading the ring
