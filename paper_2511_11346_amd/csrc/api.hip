@@ -398,19 +398,6 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
   char* ws = (char*)hd->workspace;
   const uint32_t seed_lo = (uint32_t)(seed & 0xffffffffu), seed_hi = (uint32_t)(seed >> 32);
 
-  LatentArgs la{};
-  la.family = family; la.B = hd->B; la.S = S; la.n = hd->n; la.r = hd->r;
-  la.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
-  la.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
-  la.L = p.Lst; la.contextual = p.nb > 1;
-  la.seed_lo = seed_lo; la.seed_hi = seed_hi; la.offset = offset; la.greedy = greedy;
-  la.zleaf = (int*)(ws + p.zleaf);
-  la.latents = latents ? latents : (int*)(ws + p.lat);
-  bool drawn = false;
-  s = launch_params(family, hd, ly, p, true, want_prefix, st, &la, &drawn);
-  if (s != MTPC_OK) return s;
-  if (!drawn) HIP_TRY(launch_latents(la, st));
-
   // Where the tokens are drawn (see decode_sized):
   //   InKernel  - in the epilogue of the fused kernel, which evaluates every slab
   //   Buckets   - k_draw_gather on the one slab each token needs
@@ -427,6 +414,24 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
                     : logphi         ? Draw::FromTable
                     : span_ok && buckets_pay(hd, S, want_prefix) ? Draw::Buckets   // (h through one 4 GiB resource)
                                      : Draw::InKernel;
+
+  LatentArgs la{};
+  la.family = family; la.B = hd->B; la.S = S; la.n = hd->n; la.r = hd->r;
+  la.logw = family == MTPC_FF ? nullptr : (const float*)(ws + p.logw);
+  la.layers = n_layers(family, hd->n) > 0 ? (const float*)(ws + p.lay_nat) : nullptr;
+  la.L = p.Lst; la.contextual = p.nb > 1;
+  la.seed_lo = seed_lo; la.seed_hi = seed_hi; la.offset = offset; la.greedy = greedy;
+  la.zleaf = (int*)(ws + p.zleaf);
+  la.latents = latents ? latents : (int*)(ws + p.lat);
+  if (draw == Draw::Buckets) {                            // the launch that draws the latents also clears the bucket counters
+    la.zero = (int*)(ws + p.bk_count);
+    la.nzero = hd->n * hd->r;
+  }
+  bool drawn = false;
+  s = launch_params(family, hd, ly, p, true, want_prefix, st, &la, &drawn);
+  if (s != MTPC_OK) return s;
+  if (!drawn) HIP_TRY(launch_latents(la, st));
+
 
   const bool table_scores = want_prefix && draw != Draw::Buckets && (logphi != nullptr || p.has_table);
   float* table = logphi ? logphi : (table_scores ? (float*)(ws + p.table) : nullptr);
@@ -447,6 +452,7 @@ mtpc_status run_sample(int family, const mtpc_head* hd, const mtpc_sumlayers* ly
     bk.B = hd->B; bk.S = S; bk.n = hd->n; bk.r = hd->r; bk.tile = draw_gather_tile(hd, S);
     bk.zleaf = la.zleaf;
     bk.count = (int*)(ws + p.bk_count); bk.slot = (int*)(ws + p.bk_slot);
+    bk.cleared = !drawn;         // (a launch that made the sum units and drew the latents at once did not)
     bk.row_off = (int*)(ws + p.bk_rowoff); bk.tile_off = (int*)(ws + p.bk_tileoff);
     bk.tile_bucket = (int*)(ws + p.bk_tilebucket);
     bk.list = (int*)(ws + p.bk_list);

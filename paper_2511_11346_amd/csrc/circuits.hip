@@ -1113,6 +1113,8 @@ __device__ void draft_latents(const LatentArgs& a, int b, int s, const float* lw
 
 __global__ __launch_bounds__(256) void k_latents(const LatentArgs a) {
   const int lane = threadIdx.x & 63;
+  if (a.zero != nullptr)
+    for (long long g = (long long)blockIdx.x * 256 + threadIdx.x; g < a.nzero; g += (long long)gridDim.x * 256) a.zero[g] = 0;
   const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);     // draft index
   if (t >= (long long)a.B * a.S) return;
   const int b = (int)(t / a.S), s = (int)(t % a.S);
@@ -1544,7 +1546,7 @@ hipError_t launch_buckets(const BucketArgs& a, hipStream_t st) {
   const int ng = a.n * a.r;
   const long long rows = (long long)a.B * a.S * a.n;
   const unsigned gb = (unsigned)((rows + 255) / 256);
-  hipLaunchKernelGGL(k_bucket_clear, dim3((ng + 255) / 256), dim3(256), 0, st, a.count, ng);
+  if (!a.cleared) hipLaunchKernelGGL(k_bucket_clear, dim3((ng + 255) / 256), dim3(256), 0, st, a.count, ng);
   hipLaunchKernelGGL(k_bucket_count, dim3((unsigned)((rows + 1023) / 1024)), dim3(1024), (size_t)ng * 4, st, a);
   hipLaunchKernelGGL(k_bucket_offsets, dim3(1), dim3(256), 0, st, a);
   hipLaunchKernelGGL(k_bucket_fill, dim3(gb), dim3(256), 0, st, a);

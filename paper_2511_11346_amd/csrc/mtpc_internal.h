@@ -124,6 +124,8 @@ struct LatentArgs {
   int greedy;           // 1: every sum unit takes its largest weight
   int* zleaf;           // [B][S][n] state that indexes leaf i
   int* latents;         // [B][S][n_lat] or nullptr
+  int* zero;            // launch_latents only: nzero ints it also sets to zero (the counters of the
+  int nzero;            // bucketing that follows, which saves that a launch of its own), or nullptr
 };
 hipError_t launch_latents(const LatentArgs& a, hipStream_t st);
 // batches up to this many positions compute their sum units one workgroup per position
@@ -184,6 +186,7 @@ struct BucketArgs {
   int B, S, n, r, tile;
   const int* zleaf;     // [B][S][n]
   int* count;           // [n*r] scratch
+  int cleared;          // count is already zero (launch_latents did it)
   int* slot;            // [B*S*n] scratch: rank of a triple inside its bucket
   int* row_off;         // [n*r + 1]
   int* tile_off;        // [n*r + 1]

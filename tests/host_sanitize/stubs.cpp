@@ -116,6 +116,7 @@ hipError_t launch_latents(const LatentArgs& a, hipStream_t) {
   if (a.layers) need(a.layers, (a.contextual ? (u64)a.B : 1) * a.L * a.r * a.r * 4, "latents layers");
   need(a.zleaf, (u64)a.B * a.S * a.n * 4, "latents zleaf");
   if (nlat(a.family, a.n) > 0) need(a.latents, (u64)a.B * a.S * nlat(a.family, a.n) * 4, "latents out");
+  opt(a.zero, (u64)a.nzero * 4, "latents: counters to clear");
   return ok();
 }
 hipError_t launch_sumunit_latents(const void* h, long long ld_h, const void* Wsum, int d, int dtype, float* logw,
